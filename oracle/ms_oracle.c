@@ -1,0 +1,306 @@
+/*
+ * CPU oracle for the dense tensor operators of "Tensor Program Optimization
+ * with Probabilistic Programs" (arXiv 2205.13603).
+ *
+ * TEST INFRASTRUCTURE ONLY.  This file is the reference the GPU kernels are
+ * compared with; nothing in the product library includes, links or calls it.
+ * It shares no code with the HIP path.
+ *
+ * The paper's search space S(e0) contains only programs that are
+ * semantically equal to the initial program e0 (Section 2; Section 3.1:
+ * every transformation step maps e_{i-1} to an equivalent e_i).  So whatever
+ * trace is chosen, the result is the operator's plain definition, and the
+ * oracle is that definition written as nested loops, one loop per index of
+ * the definition, no blocking, no reordering:
+ *
+ *   GEMM / batched matmul (Appendix A.2: GMM, TBG)
+ *       C[b][i][j] = sum_k A[b][i][k] * B[b][k][j]
+ *   conv2d NHWC with bias and ReLU (Appendix A.2: C2D, CBR)
+ *       Y[n][oh][ow][co] = act(bias[co] + sum_{kh,kw,ci}
+ *             Xpad[n][oh*s+kh-p][ow*s+kw-p][ci] * W[kh][kw][ci][co])
+ *   depthwise conv2d NHWC (Appendix A.2: DEP)
+ *       Y[n][oh][ow][c] = sum_{kh,kw} Xpad[n][oh*s+kh-p][ow*s+kw-p][c] * W[kh][kw][c]
+ *
+ * Readings where the paper is silent: cross-correlation (no kernel flip),
+ * zero padding, output size floor((H + 2p - KH)/s) + 1, weights HWIO.
+ *
+ * Floating point inputs (fp32, fp16, bf16 bit patterns) are widened exactly
+ * to double and accumulated in double, in index order.  int8 inputs are
+ * accumulated in int32.  Outputs are dense row-major.
+ *
+ * Operands are addressed through element strides so that transposed layouts
+ * (the TBG workload's fused transpose) need no copy.
+ *
+ * The outermost output loop carries an OpenMP pragma; it changes nothing in
+ * the arithmetic of any output element.
+ */
+#include <stdint.h>
+#include <stddef.h>
+#include <string.h>
+#ifdef _OPENMP
+#include <omp.h>
+#endif
+
+enum { ORA_F32 = 0, ORA_F16 = 1, ORA_BF16 = 2, ORA_I8 = 3 };
+
+/* IEEE binary16 bit pattern -> double, exact. */
+static double half_bits_to_double(uint16_t h)
+{
+    int sign = (h >> 15) & 1;
+    int expo = (h >> 10) & 0x1f;
+    int frac = h & 0x3ff;
+    double v;
+    if (expo == 0) {
+        v = (double)frac * (1.0 / 16777216.0); /* frac * 2^-24 (subnormal) */
+    } else if (expo == 31) {
+        if (frac == 0) {
+            v = 1.0 / 0.0;
+        } else {
+            v = 0.0 / 0.0;
+        }
+    } else {
+        double scale = 1.0;
+        int e = expo - 15;
+        int t;
+        for (t = 0; t < e; ++t) scale *= 2.0;
+        for (t = 0; t > e; --t) scale *= 0.5;
+        v = (1.0 + (double)frac / 1024.0) * scale;
+    }
+    return sign ? -v : v;
+}
+
+/* bfloat16 bit pattern -> double: it is the high half of a binary32. */
+static double bf16_bits_to_double(uint16_t b)
+{
+    uint32_t w = (uint32_t)b << 16;
+    float f;
+    memcpy(&f, &w, sizeof f);
+    return (double)f;
+}
+
+static double load_elem(int dtype, const void *base, int64_t idx)
+{
+    switch (dtype) {
+    case ORA_F32: return (double)((const float *)base)[idx];
+    case ORA_F16: return half_bits_to_double(((const uint16_t *)base)[idx]);
+    case ORA_BF16: return bf16_bits_to_double(((const uint16_t *)base)[idx]);
+    case ORA_I8: return (double)((const int8_t *)base)[idx];
+    default: return 0.0 / 0.0;
+    }
+}
+
+int ms_oracle_threads(void)
+{
+#ifdef _OPENMP
+    return omp_get_max_threads();
+#else
+    return 1;
+#endif
+}
+
+/* Exposed so that tests can pin the widening itself. */
+double ms_oracle_widen(int dtype, const void *base, int64_t idx)
+{
+    return load_elem(dtype, base, idx);
+}
+
+/*
+ * Batched matmul, floating point.  C is dense [nb][M][N] in double.
+ * A element (b,i,k) sits at A[b*sAb + i*sAi + k*sAk]; B element (b,k,j) at
+ * B[b*sBb + k*sBk + j*sBj].  Returns 0, or -1 on a bad dtype.
+ */
+int ms_oracle_bmm(int dtype, int64_t nb, int64_t M, int64_t N, int64_t K,
+                  const void *A, int64_t sAb, int64_t sAi, int64_t sAk,
+                  const void *B, int64_t sBb, int64_t sBk, int64_t sBj,
+                  double *C)
+{
+    if (dtype != ORA_F32 && dtype != ORA_F16 && dtype != ORA_BF16) return -1;
+    int64_t bi;
+#pragma omp parallel for schedule(static)
+    for (bi = 0; bi < nb * M; ++bi) {
+        int64_t b = bi / M, i = bi % M;
+        for (int64_t j = 0; j < N; ++j) {
+            double acc = 0.0;
+            for (int64_t k = 0; k < K; ++k) {
+                double a = load_elem(dtype, A, b * sAb + i * sAi + k * sAk);
+                double w = load_elem(dtype, B, b * sBb + k * sBk + j * sBj);
+                acc += a * w;
+            }
+            C[(b * M + i) * N + j] = acc;
+        }
+    }
+    return 0;
+}
+
+/* Batched matmul, int8 x int8 -> int32, exact. */
+int ms_oracle_bmm_i8(int64_t nb, int64_t M, int64_t N, int64_t K,
+                     const int8_t *A, int64_t sAb, int64_t sAi, int64_t sAk,
+                     const int8_t *B, int64_t sBb, int64_t sBk, int64_t sBj,
+                     int32_t *C)
+{
+    int64_t bi;
+#pragma omp parallel for schedule(static)
+    for (bi = 0; bi < nb * M; ++bi) {
+        int64_t b = bi / M, i = bi % M;
+        for (int64_t j = 0; j < N; ++j) {
+            int32_t acc = 0;
+            for (int64_t k = 0; k < K; ++k) {
+                int32_t a = A[b * sAb + i * sAi + k * sAk];
+                int32_t w = B[b * sBb + k * sBk + j * sBj];
+                acc += a * w;
+            }
+            C[(b * M + i) * N + j] = acc;
+        }
+    }
+    return 0;
+}
+
+static int64_t conv_out_size(int64_t in, int64_t k, int64_t s, int64_t p)
+{
+    int64_t span = in + 2 * p - k;
+    if (span < 0) return 0;
+    return span / s + 1;
+}
+
+int64_t ms_oracle_conv_out_size(int64_t in, int64_t k, int64_t s, int64_t p)
+{
+    return conv_out_size(in, k, s, p);
+}
+
+/*
+ * conv2d, NHWC activations, HWIO weights, optional fp32 bias (NULL = none),
+ * optional ReLU.  Y is dense [N][OH][OW][Cout] in double.
+ */
+int ms_oracle_conv2d_nhwc(int dtype, int64_t N, int64_t H, int64_t W_, int64_t Cin, int64_t Cout,
+                          int64_t KH, int64_t KW, int64_t stride, int64_t pad,
+                          const void *X, const void *Wt, const float *bias, int relu,
+                          double *Y)
+{
+    if (dtype != ORA_F32 && dtype != ORA_F16 && dtype != ORA_BF16) return -1;
+    int64_t OH = conv_out_size(H, KH, stride, pad);
+    int64_t OW = conv_out_size(W_, KW, stride, pad);
+    int64_t row;
+#pragma omp parallel for schedule(static)
+    for (row = 0; row < N * OH; ++row) {
+        int64_t n = row / OH, oh = row % OH;
+        for (int64_t ow = 0; ow < OW; ++ow) {
+            for (int64_t co = 0; co < Cout; ++co) {
+                double acc = 0.0;
+                for (int64_t kh = 0; kh < KH; ++kh) {
+                    int64_t ih = oh * stride + kh - pad;
+                    for (int64_t kw = 0; kw < KW; ++kw) {
+                        int64_t iw = ow * stride + kw - pad;
+                        for (int64_t ci = 0; ci < Cin; ++ci) {
+                            double x = 0.0;
+                            if (ih >= 0 && ih < H && iw >= 0 && iw < W_)
+                                x = load_elem(dtype, X, ((n * H + ih) * W_ + iw) * Cin + ci);
+                            double w = load_elem(dtype, Wt, ((kh * KW + kw) * Cin + ci) * Cout + co);
+                            acc += x * w;
+                        }
+                    }
+                }
+                if (bias) acc += (double)bias[co];
+                if (relu && acc < 0.0) acc = 0.0;
+                Y[((n * OH + oh) * OW + ow) * Cout + co] = acc;
+            }
+        }
+    }
+    return 0;
+}
+
+/* depthwise conv2d, NHWC activations, weights [KH][KW][C], multiplier 1. */
+int ms_oracle_dwconv2d_nhwc(int dtype, int64_t N, int64_t H, int64_t W_, int64_t C,
+                            int64_t KH, int64_t KW, int64_t stride, int64_t pad,
+                            const void *X, const void *Wt, double *Y)
+{
+    if (dtype != ORA_F32 && dtype != ORA_F16 && dtype != ORA_BF16) return -1;
+    int64_t OH = conv_out_size(H, KH, stride, pad);
+    int64_t OW = conv_out_size(W_, KW, stride, pad);
+    int64_t row;
+#pragma omp parallel for schedule(static)
+    for (row = 0; row < N * OH; ++row) {
+        int64_t n = row / OH, oh = row % OH;
+        for (int64_t ow = 0; ow < OW; ++ow) {
+            for (int64_t c = 0; c < C; ++c) {
+                double acc = 0.0;
+                for (int64_t kh = 0; kh < KH; ++kh) {
+                    int64_t ih = oh * stride + kh - pad;
+                    for (int64_t kw = 0; kw < KW; ++kw) {
+                        int64_t iw = ow * stride + kw - pad;
+                        if (ih >= 0 && ih < H && iw >= 0 && iw < W_) {
+                            double x = load_elem(dtype, X, ((n * H + ih) * W_ + iw) * C + c);
+                            double w = load_elem(dtype, Wt, (kh * KW + kw) * C + c);
+                            acc += x * w;
+                        }
+                    }
+                }
+                Y[((n * OH + oh) * OW + ow) * C + c] = acc;
+            }
+        }
+    }
+    return 0;
+}
+
+/*
+ * The split transformation (Section 3.1, the figure that splits loop i into
+ * extents 32, 8, 4; Table 2 "split"): a loop of extent E becomes n nested
+ * loops with extents f[0..n-1], outermost first, product E, and the original
+ * index is recovered as i = ((i0*f1 + i1)*f2 + i2)...  This routine walks
+ * the nest in order and writes the recovered index of each iteration.
+ * Returns the iteration count, or -1 if out is too short.
+ */
+int64_t ms_oracle_split_walk(int n, const int64_t *f, int64_t *out, int64_t out_len)
+{
+    int64_t idx[16];
+    int64_t count = 0;
+    int d;
+    if (n < 1 || n > 16) return -1;
+    for (d = 0; d < n; ++d) {
+        if (f[d] < 1) return -1;
+        idx[d] = 0;
+    }
+    for (;;) {
+        int64_t i = 0;
+        for (d = 0; d < n; ++d) i = i * f[d] + idx[d];
+        if (count >= out_len) return -1;
+        out[count++] = i;
+        d = n - 1;
+        while (d >= 0 && ++idx[d] == f[d]) {
+            idx[d] = 0;
+            --d;
+        }
+        if (d < 0) break;
+    }
+    return count;
+}
+
+/*
+ * Support set of sample-perfect-tile (Table 2): all ordered n-tuples of
+ * positive integers whose product is the extent.  Brute force: try every
+ * divisor at each position.  Writes tuples consecutively into out (n values
+ * each) while room remains and returns the total number of tuples.
+ */
+static int64_t enum_rec(int64_t rest, int pos, int n, int64_t *cur, int64_t *out, int64_t cap, int64_t count)
+{
+    if (pos == n - 1) {
+        cur[pos] = rest;
+        if (out && count < cap) {
+            int d;
+            for (d = 0; d < n; ++d) out[count * n + d] = cur[d];
+        }
+        return count + 1;
+    }
+    for (int64_t f = 1; f <= rest; ++f) {
+        if (rest % f) continue;
+        cur[pos] = f;
+        count = enum_rec(rest / f, pos + 1, n, cur, out, cap, count);
+    }
+    return count;
+}
+
+int64_t ms_oracle_perfect_tiles(int64_t extent, int n, int64_t *out, int64_t cap_tuples)
+{
+    int64_t cur[16];
+    if (n < 1 || n > 16 || extent < 1) return -1;
+    return enum_rec(extent, 0, n, cur, out, cap_tuples, 0);
+}

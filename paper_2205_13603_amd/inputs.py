@@ -1,0 +1,120 @@
+"""Seeded synthetic inputs for the five workload configurations.
+
+This module holds no operator arithmetic: it only draws random tensors with
+numpy and rounds them once to the operator's storage dtype on the host.  The
+same host arrays feed the GPU path and the CPU oracle.
+
+Recipe (numpy.random.default_rng(seed); one draw per tensor, in the order the
+tensors are listed):
+  C1  fp32 GEMM 128^3            A, B ~ U[-1, 1]                 (GMM, Appendix A.2)
+  C2  fp16 GEMM 1024^3           A, B ~ 0.1 * N(0, 1) -> fp16    (fused-dense, Section 5.3)
+  C3  conv2d NHWC fp16 56x56x64 -> 64, 3x3 s1 p1, bias + ReLU
+                                 X ~ U[0, 1], W ~ N(0, 0.05), bias ~ N(0, 0.05) fp32
+  C4a BMM-NT fp16 12 x [128x64].[128x64]^T     Q, K ~ N(0, 1)   (TBG, Appendix A.2)
+  C4b BMM-NN fp16 12 x [128x128].[128x64]      P, V ~ N(0, 1)
+  C4c int8 GEMM 512^3 -> int32   integers U{-128..127}
+  C5a depthwise fp32 112x112x32 3x3 s1 p1      X, W ~ U[-1, 1]  (DEP, Appendix A.2)
+  C5b depthwise fp32 56x56x144 3x3 s2 p1       X, W ~ U[-1, 1]
+"""
+import numpy as np
+
+
+def rng(seed):
+    return np.random.default_rng(seed)
+
+
+def f32_to_bf16_bits(x):
+    """Round-to-nearest-even float32 -> bfloat16 bit patterns (uint16)."""
+    u = np.ascontiguousarray(x, np.float32).view(np.uint32).astype(np.uint64)
+    lsb = (u >> 16) & 1
+    r = (u + 0x7FFF + lsb) >> 16
+    return r.astype(np.uint16)
+
+
+def bf16_bits_to_f32(b):
+    return (np.ascontiguousarray(b, np.uint16).astype(np.uint32) << 16).view(np.float32)
+
+
+def _cast(x, dtype):
+    if dtype == "f32":
+        return x.astype(np.float32)
+    if dtype == "f16":
+        return x.astype(np.float32).astype(np.float16)
+    if dtype == "bf16":
+        return f32_to_bf16_bits(x.astype(np.float32))
+    raise ValueError(dtype)
+
+
+def uniform(g, shape, lo, hi, dtype):
+    return _cast(g.uniform(lo, hi, size=shape), dtype)
+
+
+def normal(g, shape, sigma, dtype):
+    return _cast(g.normal(0.0, sigma, size=shape), dtype)
+
+
+def small_ints(g, shape, lo, hi, dtype):
+    """Integer-valued floats: every partial sum is exact in fp32."""
+    return _cast(g.integers(lo, hi + 1, size=shape).astype(np.float64), dtype)
+
+
+def int8_uniform(g, shape):
+    return g.integers(-128, 128, size=shape, dtype=np.int64).astype(np.int8)
+
+
+def gemm_inputs(M, N, K, dtype, seed=0, dist="uniform", scale=1.0, batch=None):
+    g = rng(seed)
+    sa = (M, K) if batch is None else (batch, M, K)
+    sb = (K, N) if batch is None else (batch, K, N)
+    if dtype == "i8":
+        return int8_uniform(g, sa), int8_uniform(g, sb)
+    if dist == "uniform":
+        return uniform(g, sa, -scale, scale, dtype), uniform(g, sb, -scale, scale, dtype)
+    if dist == "normal":
+        return normal(g, sa, scale, dtype), normal(g, sb, scale, dtype)
+    if dist == "ints":
+        return small_ints(g, sa, -2, 2, dtype), small_ints(g, sb, -2, 2, dtype)
+    raise ValueError(dist)
+
+
+def c1(seed=0):
+    return gemm_inputs(128, 128, 128, "f32", seed, "uniform", 1.0)
+
+
+def c2(seed=0, M=1024, N=1024, K=1024, dtype="f16"):
+    return gemm_inputs(M, N, K, dtype, seed, "normal", 0.1)
+
+
+def c3(seed=0, N=1, H=56, W=56, Cin=64, Cout=64, KH=3, KW=3, dtype="f16"):
+    g = rng(seed)
+    X = uniform(g, (N, H, W, Cin), 0.0, 1.0, dtype)
+    Wt = normal(g, (KH, KW, Cin, Cout), 0.05, dtype)
+    bias = g.normal(0.0, 0.05, size=(Cout,)).astype(np.float32)
+    return X, Wt, bias
+
+
+def c4a(seed=0, heads=12, seq=128, dim=64, dtype="f16"):
+    g = rng(seed)
+    return normal(g, (heads, seq, dim), 1.0, dtype), normal(g, (heads, seq, dim), 1.0, dtype)
+
+
+def c4b(seed=0, heads=12, seq=128, dim=64, dtype="f16"):
+    g = rng(seed)
+    return normal(g, (heads, seq, seq), 1.0, dtype), normal(g, (heads, seq, dim), 1.0, dtype)
+
+
+def c4c(seed=0, M=512, N=512, K=512):
+    return gemm_inputs(M, N, K, "i8", seed)
+
+
+def dw_inputs(N, H, W, C, KH=3, KW=3, seed=0, dtype="f32"):
+    g = rng(seed)
+    return uniform(g, (N, H, W, C), -1.0, 1.0, dtype), uniform(g, (KH, KW, C), -1.0, 1.0, dtype)
+
+
+def c5a(seed=0):
+    return dw_inputs(1, 112, 112, 32, seed=seed)
+
+
+def c5b(seed=0):
+    return dw_inputs(1, 56, 56, 144, seed=seed)

@@ -1,0 +1,336 @@
+"""Pins of the CPU oracle against facts it does not compute itself:
+the paper's worked example, closed forms, invariants, brute force in pure
+Python, and independent library routines (numpy float64 matmul, torch CPU
+conv2d).  All CPU-only.
+"""
+import itertools
+import math
+import os
+
+import numpy as np
+import pytest
+
+from oracle import oracle as O
+from paper_2205_13603_amd import inputs as I
+
+GOLD = os.path.join(os.path.dirname(__file__), "golden")
+
+
+# ---------------------------------------------------------------- widening
+def test_fp16_widening_all_bit_patterns():
+    bits = np.arange(65536, dtype=np.uint32).astype(np.uint16)
+    h = bits.view(np.float16)
+    want = h.astype(np.float64)
+    got = O.widen(h)
+    nan = np.isnan(want)
+    assert np.array_equal(np.isnan(got), nan)
+    assert np.array_equal(got[~nan], want[~nan])
+    assert np.array_equal(np.signbit(got[~nan]), np.signbit(want[~nan]))
+
+
+def test_bf16_widening():
+    g = I.rng(3)
+    x = g.normal(0, 10, size=4096).astype(np.float32)
+    b = I.f32_to_bf16_bits(x)
+    got = O.widen(b, bf16=True)
+    assert np.array_equal(got, I.bf16_bits_to_f32(b).astype(np.float64))
+    # bf16 keeps 8 significand bits: relative rounding error <= 2^-9
+    assert np.all(np.abs(got - x) <= np.abs(x) * 2.0 ** -8)
+
+
+# ---------------------------------------------------------------- split
+def _read_split_example():
+    f, e = None, None
+    for line in open(os.path.join(GOLD, "split_example.txt")):
+        t = line.split("#")[0].split()
+        if not t:
+            continue
+        if t[0] == "factors":
+            f = [int(v) for v in t[1:]]
+        if t[0] == "extent":
+            e = int(t[1])
+    return f, e
+
+
+def test_split_worked_example():
+    f, e = _read_split_example()
+    assert f == [32, 8, 4] and e == 1024
+    walk = O.split_walk(f)
+    assert walk.size == e
+    # every original iteration exactly once, and consecutive loops keep order
+    assert np.array_equal(walk, np.arange(e))
+
+
+def test_split_index_formula_python():
+    f = [3, 5, 2, 7]
+    walk = O.split_walk(f)
+    want = [((a * 5 + b) * 2 + c) * 7 + d for a in range(3) for b in range(5) for c in range(2) for d in range(7)]
+    assert walk.tolist() == want
+
+
+# ---------------------------------------------------------------- perfect tiles
+def _golden_counts():
+    rows = []
+    for line in open(os.path.join(GOLD, "perfect_tile_counts.txt")):
+        t = line.split("#")[0].split()
+        if len(t) == 3:
+            rows.append(tuple(int(v) for v in t))
+    return rows
+
+
+def _closed_form(extent, n):
+    cnt, e, p = 1, extent, 2
+    while e > 1:
+        a = 0
+        while e % p == 0:
+            e //= p
+            a += 1
+        if a:
+            cnt *= math.comb(a + n - 1, n - 1)
+        p += 1
+    return cnt
+
+
+@pytest.mark.parametrize("extent,n,count", _golden_counts())
+def test_perfect_tile_counts(extent, n, count):
+    tiles = O.perfect_tiles(extent, n)
+    assert tiles.shape == (count, n)
+    assert _closed_form(extent, n) == count
+    assert np.all(tiles >= 1)
+    assert np.all(np.prod(tiles, axis=1) == extent)
+    assert len({tuple(t) for t in tiles.tolist()}) == count
+
+
+def test_perfect_tiles_bruteforce_python():
+    for extent, n in [(12, 3), (30, 2), (16, 4), (7, 3)]:
+        want = sorted(t for t in itertools.product(range(1, extent + 1), repeat=n) if math.prod(t) == extent)
+        got = sorted(tuple(t) for t in O.perfect_tiles(extent, n).tolist())
+        assert got == want
+
+
+# ---------------------------------------------------------------- GEMM / BMM
+def _py_matmul(A, B):
+    M, K = len(A), len(A[0])
+    N = len(B[0])
+    return [[sum(A[i][k] * B[k][j] for k in range(K)) for j in range(N)] for i in range(M)]
+
+
+def test_gemm_tiny_pure_python():
+    g = I.rng(1)
+    for (M, N, K) in [(1, 1, 1), (2, 3, 4), (5, 2, 7), (8, 8, 8)]:
+        A = g.integers(-4, 5, size=(M, K)).astype(np.float32)
+        B = g.integers(-4, 5, size=(K, N)).astype(np.float32)
+        want = np.array(_py_matmul(A.astype(int).tolist(), B.astype(int).tolist()), np.float64)
+        assert np.array_equal(O.gemm(A, B), want)
+
+
+def test_gemm_identity_zero_ones():
+    g = I.rng(2)
+    A = g.uniform(-1, 1, size=(17, 9)).astype(np.float32)
+    assert np.array_equal(O.gemm(A, np.eye(9, dtype=np.float32)), A.astype(np.float64))
+    assert np.array_equal(O.gemm(np.eye(17, dtype=np.float32), A), A.astype(np.float64))
+    assert np.all(O.gemm(A, np.zeros((9, 5), np.float32)) == 0)
+    assert np.all(O.gemm(np.ones((6, 128), np.float16), np.ones((128, 4), np.float16)) == 128.0)
+
+
+def test_gemm_linearity_exact_on_small_ints():
+    A1, B = I.gemm_inputs(13, 11, 29, "f32", 5, "ints")
+    A2, _ = I.gemm_inputs(13, 11, 29, "f32", 6, "ints")
+    assert np.array_equal(O.gemm(A1 + A2, B), O.gemm(A1, B) + O.gemm(A2, B))
+    assert np.array_equal(O.gemm(3 * A1, B), 3 * O.gemm(A1, B))
+
+
+@pytest.mark.parametrize("dtype", ["f32", "f16", "bf16"])
+def test_gemm_vs_numpy_float64(dtype):
+    # non-square so that a transposed operand or swapped extent cannot pass
+    A, B = I.gemm_inputs(37, 21, 53, dtype, 7, "normal", 1.0)
+    if dtype == "bf16":
+        Ad, Bd = I.bf16_bits_to_f32(A).astype(np.float64), I.bf16_bits_to_f32(B).astype(np.float64)
+        got = O.gemm(A, B, bf16=True)
+    else:
+        Ad, Bd = A.astype(np.float64), B.astype(np.float64)
+        got = O.gemm(A, B)
+    want = Ad @ Bd
+    # both accumulate in double; only the summation order may differ
+    bound = 53 * 2.0 ** -52 * (np.abs(Ad) @ np.abs(Bd))
+    assert np.all(np.abs(got - want) <= bound)
+
+
+def test_bmm_nt_equals_per_head_gemm_with_materialised_transpose():
+    Q, Kk = I.c4a(seed=4, heads=3, seq=10, dim=6)
+    got = O.bmm(Q, Kk, trans_b=True)
+    for h in range(3):
+        KT = np.ascontiguousarray(Kk[h].T)
+        assert np.array_equal(got[h], O.gemm(Q[h], KT))
+    # strided view of a [seq][head][dim] layout gives the same result (fused transpose)
+    Qs = np.ascontiguousarray(Q.transpose(1, 0, 2))
+    assert np.array_equal(O.bmm(Qs.transpose(1, 0, 2), Kk, trans_b=True), got)
+
+
+def test_bmm_nn_heads_independent():
+    P, V = I.c4b(seed=5, heads=4, seq=8, dim=5)
+    got = O.bmm(P, V)
+    perm = [2, 0, 3, 1]
+    assert np.array_equal(O.bmm(P[perm], V[perm]), got[perm])
+    for h in range(4):
+        assert np.array_equal(got[h], O.gemm(P[h], V[h]))
+
+
+def test_int8_gemm_extremes_and_bigint():
+    A = np.full((4, 512), -128, np.int8)
+    B = np.full((512, 3), -128, np.int8)
+    assert np.all(O.gemm(A, B) == 8388608)
+    B2 = np.full((512, 3), 127, np.int8)
+    assert np.all(O.gemm(A, B2) == -128 * 127 * 512)
+    a, b = I.gemm_inputs(5, 4, 9, "i8", 8)
+    want = np.array(_py_matmul(a.astype(int).tolist(), b.astype(int).tolist()), np.int64)
+    got = O.gemm(a, b)
+    assert got.dtype == np.int32 and np.array_equal(got.astype(np.int64), want)
+
+
+def test_int8_gemm_vs_numpy_int64():
+    a, b = I.gemm_inputs(33, 18, 47, "i8", 9)
+    assert np.array_equal(O.gemm(a, b).astype(np.int64), a.astype(np.int64) @ b.astype(np.int64))
+
+
+# ---------------------------------------------------------------- conv2d
+def test_conv_out_size():
+    assert O.conv_out_size(56, 3, 1, 1) == 56
+    assert O.conv_out_size(56, 3, 2, 1) == 28
+    assert O.conv_out_size(224, 7, 2, 3) == 112
+    assert O.conv_out_size(112, 3, 1, 1) == 112
+
+
+def test_conv_1x1_is_gemm():
+    g = I.rng(10)
+    X = g.integers(-3, 4, size=(2, 5, 4, 7)).astype(np.float32)
+    W = g.integers(-3, 4, size=(1, 1, 7, 6)).astype(np.float32)
+    got = O.conv2d_nhwc(X, W)
+    want = O.gemm(X.reshape(-1, 7), W.reshape(7, 6)).reshape(2, 5, 4, 6)
+    assert np.array_equal(got, want)
+
+
+def test_conv_centre_tap_identity_and_shift():
+    X, _, _ = I.c3(seed=11, H=9, W=7, Cin=5, Cout=5)
+    W = np.zeros((3, 3, 5, 5), np.float16)
+    for c in range(5):
+        W[1, 1, c, c] = 1
+    Y = O.conv2d_nhwc(X, W, bias=np.zeros(5, np.float32), relu=True, stride=1, pad=1)
+    assert np.array_equal(Y, X.astype(np.float64))  # ReLU inactive: X in [0,1]
+    # one-hot tap at (kh,kw) = (0,0): Y[oh][ow] = Xpad[oh-1][ow-1] -> shifted by (+1,+1)
+    W0 = np.zeros((3, 3, 5, 5), np.float16)
+    for c in range(5):
+        W0[0, 0, c, c] = 1
+    Y0 = O.conv2d_nhwc(X, W0, stride=1, pad=1)
+    assert np.all(Y0[:, 0, :, :] == 0) and np.all(Y0[:, :, 0, :] == 0)
+    assert np.array_equal(Y0[:, 1:, 1:, :], X.astype(np.float64)[:, :-1, :-1, :])
+    # tap at (2,1): Y[oh][ow] = Xpad[oh+1][ow]
+    W1 = np.zeros((3, 3, 5, 5), np.float16)
+    for c in range(5):
+        W1[2, 1, c, c] = 1
+    Y1 = O.conv2d_nhwc(X, W1, stride=1, pad=1)
+    assert np.all(Y1[:, -1, :, :] == 0)
+    assert np.array_equal(Y1[:, :-1, :, :], X.astype(np.float64)[:, 1:, :, :])
+
+
+def test_conv_all_ones_border_pattern():
+    Cin = 64
+    X = np.ones((1, 6, 8, Cin), np.float16)
+    W = np.ones((3, 3, Cin, 3), np.float16)
+    Y = O.conv2d_nhwc(X, W, stride=1, pad=1)
+    assert np.all(Y[0, 1:-1, 1:-1] == 9 * Cin)
+    assert np.all(Y[0, 0, 1:-1] == 6 * Cin) and np.all(Y[0, 1:-1, 0] == 6 * Cin)
+    assert np.all(Y[0, -1, 1:-1] == 6 * Cin) and np.all(Y[0, 1:-1, -1] == 6 * Cin)
+    for (a, b) in [(0, 0), (0, -1), (-1, 0), (-1, -1)]:
+        assert np.all(Y[0, a, b] == 4 * Cin)
+
+
+def test_conv_bias_and_relu():
+    X, W, bias = I.c3(seed=12, H=6, W=6, Cin=4, Cout=5)
+    big_neg = np.full(5, -1e4, np.float32)
+    assert np.all(O.conv2d_nhwc(X, W, bias=big_neg, relu=True, stride=1, pad=1) == 0)
+    Y = O.conv2d_nhwc(X, np.zeros_like(W), bias=bias, relu=True, stride=1, pad=1)
+    assert np.array_equal(Y, np.broadcast_to(np.maximum(0, bias.astype(np.float64)), Y.shape))
+    # bias enters before ReLU, once per output element
+    Yn = O.conv2d_nhwc(X, W, bias=None, relu=False, stride=1, pad=1)
+    Yb = O.conv2d_nhwc(X, W, bias=bias, relu=False, stride=1, pad=1)
+    assert np.allclose(Yb - Yn, bias.astype(np.float64), rtol=0, atol=1e-12)
+    Yr = O.conv2d_nhwc(X, W, bias=bias, relu=True, stride=1, pad=1)
+    assert np.array_equal(Yr, np.maximum(Yb, 0))
+
+
+@pytest.mark.parametrize("stride,pad,k", [(1, 1, 3), (2, 1, 3), (2, 3, 7), (1, 0, 2)])
+def test_conv_vs_torch_cpu(stride, pad, k):
+    torch = pytest.importorskip("torch")
+    g = I.rng(13)
+    X = g.normal(size=(2, 11, 9, 5)).astype(np.float32)
+    W = g.normal(size=(k, k, 5, 4)).astype(np.float32)
+    b = g.normal(size=4).astype(np.float32)
+    got = O.conv2d_nhwc(X, W, bias=b, relu=True, stride=stride, pad=pad)
+    xt = torch.from_numpy(X).double().permute(0, 3, 1, 2)
+    wt = torch.from_numpy(W).double().permute(3, 2, 0, 1)
+    want = torch.relu(torch.nn.functional.conv2d(xt, wt, torch.from_numpy(b).double(), stride=stride, padding=pad))
+    want = want.permute(0, 2, 3, 1).numpy()
+    assert got.shape == want.shape
+    assert np.allclose(got, want, rtol=1e-12, atol=1e-12)
+
+
+# ---------------------------------------------------------------- depthwise
+def test_dw_equals_conv_with_block_diagonal_weights():
+    X, W = I.dw_inputs(2, 7, 6, 5, seed=14)
+    Wfull = np.zeros((3, 3, 5, 5), np.float32)
+    for c in range(5):
+        Wfull[:, :, c, c] = W[:, :, c]
+    for s in (1, 2):
+        assert np.array_equal(O.dwconv2d_nhwc(X, W, stride=s, pad=1), O.conv2d_nhwc(X, Wfull, stride=s, pad=1))
+
+
+def test_dw_all_ones_patterns():
+    X = np.ones((1, 10, 10, 3), np.float32)
+    W = np.ones((3, 3, 3), np.float32)
+    Y = O.dwconv2d_nhwc(X, W, stride=1, pad=1)
+    assert np.all(Y[0, 1:-1, 1:-1] == 9) and np.all(Y[0, 0, 1:-1] == 6) and Y[0, 0, 0, 0] == 4 and Y[0, -1, -1, 0] == 4
+    # stride 2, pad 1, even H: only the top/left padding is touched
+    X = np.ones((1, 56, 56, 2), np.float32)
+    W = np.ones((3, 3, 2), np.float32)
+    Y = O.dwconv2d_nhwc(X, W, stride=2, pad=1)
+    assert Y.shape == (1, 28, 28, 2)
+    assert np.all(Y[0, 0, 0] == 4) and np.all(Y[0, 0, 1:] == 6) and np.all(Y[0, 1:, 0] == 6) and np.all(Y[0, 1:, 1:] == 9)
+
+
+def test_dw_channel_permutation():
+    X, W = I.dw_inputs(1, 9, 8, 6, seed=15)
+    perm = np.array([3, 0, 5, 1, 4, 2])
+    Y = O.dwconv2d_nhwc(X, W, stride=1, pad=1)
+    Yp = O.dwconv2d_nhwc(np.ascontiguousarray(X[..., perm]), np.ascontiguousarray(W[..., perm]), stride=1, pad=1)
+    assert np.array_equal(Yp, Y[..., perm])
+
+
+@pytest.mark.parametrize("stride", [1, 2])
+def test_dw_vs_torch_cpu(stride):
+    torch = pytest.importorskip("torch")
+    X, W = I.dw_inputs(2, 12, 10, 7, seed=16)
+    got = O.dwconv2d_nhwc(X, W, stride=stride, pad=1)
+    xt = torch.from_numpy(X).double().permute(0, 3, 1, 2)
+    wt = torch.from_numpy(W).double().permute(2, 0, 1).unsqueeze(1)
+    want = torch.nn.functional.conv2d(xt, wt, None, stride=stride, padding=1, groups=7).permute(0, 2, 3, 1).numpy()
+    assert got.shape == want.shape and np.allclose(got, want, rtol=1e-12, atol=1e-12)
+
+
+def test_full_size_spot_checks():
+    """Config-size runs finish in seconds; spot-check single outputs by the definition."""
+    A, B = I.c1()
+    C = O.gemm(A, B)
+    for (i, j) in [(0, 0), (127, 127), (5, 99)]:
+        assert abs(C[i, j] - float(np.dot(A[i].astype(np.float64), B[:, j].astype(np.float64)))) < 1e-12
+    X, W = I.c5b()
+    Y = O.dwconv2d_nhwc(X, W, stride=2, pad=1)
+    assert Y.shape == (1, 28, 28, 144)
+    oh, ow, c = 27, 27, 143
+    acc = 0.0
+    for kh in range(3):
+        for kw in range(3):
+            ih, iw = oh * 2 + kh - 1, ow * 2 + kw - 1
+            assert 0 <= ih < 56 and 0 <= iw < 56
+            acc += float(X[0, ih, iw, c]) * float(W[kh, kw, c])
+    assert abs(Y[0, oh, ow, c] - acc) < 1e-12
