@@ -1,0 +1,454 @@
+/*
+ * ms.h - C ABI of the schedule-parameterised operator kernel library for
+ * AMD MI355X (gfx950).
+ *
+ * What the library is, in the vocabulary of "Tensor Program Optimization with
+ * Probabilistic Programs" (arXiv 2205.13603):
+ *
+ *   e0        an operator definition (ms_op): a loop nest with spatial and
+ *             reduction loops (Section 2; workloads of Appendix A.2).
+ *   S(e0)     the search space (ms_space): an ordered list of sampling
+ *             instructions, sample-perfect-tile and sample-categorical
+ *             (Table 2), produced by the transformation modules enabled in
+ *             `flags` (Section 3.2: Multi-Level-Tiling, the hardware-specific
+ *             tensorize module, cache-read, unroll/vectorize).
+ *   tau       a trace (ms_trace): one decision per sampling instruction
+ *             (Section 4, "Execution tracing").  A trace is plain data owned
+ *             by the caller.
+ *   g(e0,tau) a variant (ms_variant): the concrete GPU kernel the trace
+ *             selects.  Every valid trace computes the same function as e0.
+ *   validator ms_trace_validate: rejects traces that exceed hardware limits
+ *             (Section 4, "Trace validation").
+ *   f(e)      ms_measure: latency of a variant on the device (Eq. 1).
+ *   search    ms_search: evolutionary search over traces by mutating
+ *             decisions, accept/reject with the annealed weight exp(-f/T)
+ *             (Section 4, "End-to-end search", Eq. 1), on measured latency.
+ *
+ * Conventions
+ *   - Every call returns an ms_status.  On failure ms_last_error() gives a
+ *     NUL-terminated reason, valid until the next failing call on the same
+ *     thread.  No exception crosses this boundary and nothing aborts.
+ *   - "device pointer" = memory of the current HIP device, owned by the
+ *     caller; the library never allocates, frees or retains user tensors.
+ *     "host pointer" = ordinary process memory.  `stream` is a hipStream_t
+ *     passed as void* (NULL = the default stream).
+ *   - Handles (ms_op*, ms_variant*) are created and destroyed by the library;
+ *     destroy accepts NULL.  ms_space and ms_trace are caller-owned PODs.
+ *   - Tensors are row-major with the last index contiguous unless element
+ *     strides in the op descriptor say otherwise.  Outputs are always dense.
+ *   - An "instance" is one independent copy of the operator's whole problem;
+ *     a launch over R instances reads R consecutive dense copies of each
+ *     input and writes R consecutive copies of the output.  Per-instance
+ *     tiling is exactly what the trace says.
+ */
+#ifndef MS_H
+#define MS_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define MS_ABI_VERSION 1
+
+typedef enum ms_status {
+    MS_OK = 0,
+    MS_ERR_BAD_ARG = 1,       /* NULL pointer, bad enum, bad size */
+    MS_ERR_INVALID_TRACE = 2, /* the validator rejected the trace */
+    MS_ERR_UNSUPPORTED = 3,   /* well-formed request outside what is implemented */
+    MS_ERR_COMPILE = 4,       /* run-time compilation of the variant failed */
+    MS_ERR_HIP = 5,           /* a HIP runtime call failed */
+    MS_ERR_NOMEM = 6
+} ms_status;
+
+/* ------------------------------------------------------------------ e0 */
+
+typedef enum ms_op_kind {
+    MS_OP_GEMM = 0,          /* C[i][j]    = sum_k A[i][k]    * B[k][j]     (GMM) */
+    MS_OP_BMM_NT = 1,        /* C[b][i][j] = sum_k A[b][i][k] * B[b][j][k]  (TBG: Q.K^T) */
+    MS_OP_BMM_NN = 2,        /* C[b][i][j] = sum_k A[b][i][k] * B[b][k][j] */
+    MS_OP_CONV2D_NHWC = 3,   /* Y = act(bias + conv(X, W)), X NHWC, W HWIO  (C2D / CBR) */
+    MS_OP_DWCONV2D_NHWC = 4  /* depthwise, X NHWC, W [KH][KW][C]            (DEP) */
+} ms_op_kind;
+
+typedef enum ms_dtype { MS_F32 = 0, MS_F16 = 1, MS_BF16 = 2, MS_I8 = 3, MS_I32 = 4 } ms_dtype;
+
+/*
+ * dims:
+ *   GEMM            M, N, K
+ *   BMM_NT, BMM_NN  B, M, N, K
+ *   CONV2D_NHWC     N, H, W, Cin, Cout, KH, KW
+ *   DWCONV2D_NHWC   N, H, W, C, KH, KW
+ * Convolutions: cross-correlation, zero padding `pad` on all four sides,
+ * output size floor((H + 2*pad - KH)/stride) + 1.  bias is fp32 [Cout], added
+ * to the accumulator before ReLU, before the single rounding to out_dtype.
+ * Accumulation is fp32 for F32/F16/BF16 inputs and exact int32 for I8.
+ * out_dtype: F32 or the input dtype for float inputs; I32 for I8.
+ * a_strides / b_strides (GEMM and BMM only; element units; all zero = the
+ * dense default of the op kind): A element (b,i,k) at b*a[0] + i*a[1] + k*a[2];
+ * B element (b,k,j) at b*b[0] + k*b[1] + j*b[2].
+ * Inputs of a launch: GEMM/BMM {A, B}; CONV {X, W, bias or NULL}; DW {X, W}.
+ */
+typedef struct ms_op_desc {
+    int32_t kind;
+    int32_t in_dtype;
+    int32_t out_dtype;
+    int32_t stride;
+    int32_t pad;
+    int32_t has_bias;
+    int32_t relu;
+    int32_t reserved;
+    int64_t dims[8];
+    int64_t a_strides[3];
+    int64_t b_strides[3];
+} ms_op_desc;
+
+typedef struct ms_op ms_op;
+
+/* Create an operator from a descriptor (host pointer, copied).  Errors:
+ * BAD_ARG for a NULL pointer, non-positive dim or unknown enum; UNSUPPORTED
+ * for a dtype combination outside the list above. */
+int32_t ms_op_create(const ms_op_desc *desc, ms_op **out);
+void ms_op_destroy(ms_op *op);
+/* Copy the descriptor back, with default strides filled in. */
+int32_t ms_op_get_desc(const ms_op *op, ms_op_desc *out);
+
+/* The loop nest of e0 after the fusions fixed per operator (conv: n,oh,ow are
+ * fused into one spatial loop, kh,kw,ci into one reduction loop). */
+#define MS_MAX_LOOPS 8
+typedef struct ms_loop {
+    char name[8];
+    int64_t extent;
+    int32_t is_reduction; /* 0 = spatial (data parallel), 1 = reduction */
+    int32_t reserved;
+} ms_loop;
+int32_t ms_op_loops(const ms_op *op, ms_loop *loops /* [MS_MAX_LOOPS] */, int32_t *n_loops);
+/* Algorithmic work of one instance: flop = 2 * MACs of the definition,
+ * bytes = every input and output tensor moved once. */
+int32_t ms_op_work(const ms_op *op, double *flop, double *bytes);
+/* Byte size of input `idx` / of the output, for one instance. */
+int32_t ms_op_tensor_bytes(const ms_op *op, int32_t idx /* -1 = output */, int64_t *bytes);
+
+/* ------------------------------------------------------------------ S(e0) */
+
+#define MS_MAX_SLOTS 16
+#define MS_MAX_FACTORS 4
+#define MS_MAX_CANDS 8
+
+typedef enum ms_slot_kind { MS_SLOT_PERFECT_TILE = 0, MS_SLOT_CATEGORICAL = 1 } ms_slot_kind;
+
+/* Semantic ids of the sampling instructions. */
+typedef enum ms_slot_id {
+    MS_SLOT_TENSORIZE = 0, /* categorical: matrix-core intrinsic (candidates = codes below) */
+    MS_SLOT_TILE_I = 1,    /* perfect tile of spatial loop 0 (rows / oh) */
+    MS_SLOT_TILE_J = 2,    /* perfect tile of spatial loop 1 (cols / ow) */
+    MS_SLOT_TILE_C = 3,    /* perfect tile of the channel loop (depthwise) */
+    MS_SLOT_TILE_K = 4,    /* perfect tile of the reduction loop */
+    MS_SLOT_UNROLL = 5,    /* categorical: unroll budget, candidates {0,16,64} */
+    MS_SLOT_CACHE_READ = 6,/* categorical: 0 = operands read from global memory,
+                              1 = staged in LDS, 2 = staged in LDS, double buffered */
+    MS_SLOT_VECTORIZE = 7, /* categorical: elements per global load instruction */
+    MS_SLOT_STORAGE_ALIGN = 8, /* categorical: LDS row padding in 16-byte units */
+    MS_SLOT_REORDER = 9    /* categorical: order of the grid loops, 0 = i outer, 1 = j outer,
+                              2 = i outer with workgroups grouped per XCD */
+} ms_slot_id;
+
+/* Tensorize candidates: (m, n, k) of one matrix-core instruction.  The code
+ * is m*10000 + n*100 + k, e.g. 161616, 323208, 161632, 323216, 161664, 323232. */
+#define MS_MFMA_CODE(m, n, k) ((m) * 10000 + (n) * 100 + (k))
+#define MS_MFMA_NONE 0
+
+/*
+ * One sampling instruction.  Perfect tile: draw n_factors positive integers,
+ * outermost first, with product `extent` (Table 2, sample-perfect-tile; the
+ * split of Section 3.1 with extents 32, 8, 4 is the tuple [32,8,4]).  If
+ * depends_on >= 0 the extent is fixed only once the categorical slot at
+ * position depends_on has been decided: extent = extent_by_choice[choice]
+ * (the loop counted in units of the chosen intrinsic's tile); `extent` then
+ * holds the loop's element extent.  Categorical: draw an index into
+ * candidates with probability weight[i] / sum(weight) (Table 2,
+ * sample-categorical).
+ *
+ * Roles of the four factors [f0,f1,f2,f3] of a spatial loop, index
+ * ((x0*f1 + x1)*f2 + x2)*f3 + x3:  x0 -> workgroup (bind blockIdx),
+ * x1 -> register tile, strided; x2 -> thread (ALU kernels) or wavefront
+ * (matrix-core kernels) (bind threadIdx); x3 -> register tile, contiguous.
+ * Reduction loop: x0 -> steps of the LDS tile loop, x1 -> rolled loop inside
+ * a tile, x2 -> loop inside a tile subject to the unroll budget, x3 ->
+ * innermost, always unrolled (vector reads along k / back-to-back intrinsics).
+ */
+typedef struct ms_slot {
+    int32_t slot_id;
+    int32_t kind;
+    char name[16];
+    int64_t extent;
+    int32_t n_factors;
+    int32_t n_candidates;
+    int64_t candidates[MS_MAX_CANDS];
+    int32_t weight[MS_MAX_CANDS];
+    int32_t depends_on;
+    int32_t reserved;
+    int64_t extent_by_choice[MS_MAX_CANDS];
+} ms_slot;
+
+/* Transformation modules that may be composed into the space (Section 3.2). */
+#define MS_SPACE_TENSORIZE 0x1u     /* use the matrix cores (needs F16/BF16/I8 inputs) */
+#define MS_SPACE_CACHE_READ 0x2u    /* sample LDS staging; off = always staged, single buffer */
+#define MS_SPACE_VECTORIZE 0x4u     /* sample global load width; off = scalar loads */
+#define MS_SPACE_UNROLL 0x8u        /* sample the unroll budget; off = 0 */
+#define MS_SPACE_STORAGE_ALIGN 0x10u/* sample LDS padding; off = no padding */
+#define MS_SPACE_REORDER 0x20u      /* sample the grid loop order; off = i outer */
+#define MS_SPACE_DEFAULT 0xffffffffu
+
+typedef enum ms_family { MS_FAM_GEMM_ALU = 0, MS_FAM_GEMM_MFMA = 1, MS_FAM_DWCONV = 2 } ms_family;
+
+typedef struct ms_space {
+    int32_t family;
+    uint32_t flags;
+    int32_t n_slots;
+    int32_t reserved;
+    ms_slot slots[MS_MAX_SLOTS];
+} ms_space;
+
+/* Write the space of `op` under the enabled modules.  MS_SPACE_TENSORIZE is
+ * dropped silently for F32 inputs.  UNSUPPORTED if no kernel family covers the
+ * op with these flags (conv2d needs the tensorize module). */
+int32_t ms_space_describe(const ms_op *op, uint32_t flags, ms_space *out);
+/* log10 of the number of distinct traces of the space (support size). */
+int32_t ms_space_log10_size(const ms_space *space, double *out);
+
+/* ------------------------------------------------------------------ tau */
+
+typedef struct ms_decision {
+    int32_t slot_id;
+    int32_t kind;
+    int32_t n; /* number of values: n_factors, or 1 for a categorical (v[0] = index) */
+    int32_t reserved;
+    int64_t v[MS_MAX_FACTORS];
+} ms_decision;
+
+typedef struct ms_trace {
+    int32_t n;
+    int32_t reserved;
+    ms_decision d[MS_MAX_SLOTS];
+} ms_trace;
+
+/* Draw trace number `index` of the stream `seed`.  Integer-only, reproducible
+ * across runs and machines.  Perfect tiles are uniform over all ordered
+ * factorisations; the result may be rejected by the validator. */
+int32_t ms_trace_sample(const ms_space *space, uint64_t seed, uint64_t index, ms_trace *out);
+/* As above, but redraws (index, attempt) until the validator accepts, at most
+ * max_tries times; INVALID_TRACE if none was accepted. */
+int32_t ms_trace_sample_valid(const ms_op *op, const ms_space *space, uint64_t seed, uint64_t index,
+                              int32_t max_tries, ms_trace *out);
+/* Propose a neighbour: exactly one decision is redrawn or, for a perfect
+ * tile, a prime factor moves between two positions (the product is kept).
+ * A tensorize mutation redraws the tiles that depend on it. */
+int32_t ms_trace_mutate(const ms_space *space, const ms_trace *in, uint64_t seed, ms_trace *out);
+
+/* Linearised program text (Section 4, "Execution tracing"): one instruction
+ * per line, sampling instructions with their decisions followed by the
+ * transformation instructions they parameterise.  from_text reads the
+ * sampling lines only and reproduces the trace exactly.  to_text writes at
+ * most cap bytes including the NUL and reports the needed size in *needed. */
+int32_t ms_trace_to_text(const ms_op *op, const ms_space *space, const ms_trace *trace,
+                         char *buf, size_t cap, size_t *needed);
+int32_t ms_trace_from_text(const ms_space *space, const char *text, ms_trace *out);
+
+/* ------------------------------------------------------------------ g(e0,tau) */
+
+/* What the trace interpreter derives.  Unused fields are zero. */
+typedef struct ms_variant_params {
+    int32_t family;
+    int32_t mfma;           /* MS_MFMA_CODE or MS_MFMA_NONE */
+    int32_t ti[4], tj[4], tc[4], tk[4]; /* the tile decisions (tc: depthwise channels) */
+    int32_t tile_unit[3];   /* elements per unit of ti, tj, tk (intrinsic m, n, k; 1 for ALU) */
+    int32_t block_m, block_n, block_k; /* workgroup tile in elements (depthwise: oh, ow; block_k = channels) */
+    int32_t grid[3];        /* workgroups per instance */
+    int32_t threads;        /* workgroup size */
+    int32_t waves;
+    int32_t acc_per_thread; /* accumulator registers per lane */
+    int32_t lds_bytes;
+    int32_t cache_read;     /* 0, 1, 2 as in MS_SLOT_CACHE_READ */
+    int32_t vec;            /* elements per global load */
+    int32_t unroll;         /* budget */
+    int32_t unroll_k1, unroll_k2; /* unroll factors of the two rolled reduction loops */
+    int32_t lds_pad;        /* padding, in 16-byte units */
+    int32_t reorder;
+    int32_t reserved[8];
+    uint64_t key;           /* hash of everything that selects the kernel */
+} ms_variant_params;
+
+/* Pure host check (no GPU needed).  Rejects with INVALID_TRACE and a reason:
+ * wrong slot order/ids, factor product != extent, non-positive factors,
+ * categorical index out of range, workgroup threads outside [1,1024] (matrix
+ * core kernels: waves outside [1,16]), LDS bytes above the limit,
+ * accumulators per lane above the register budget, vector width that does
+ * not divide the contiguous extent or breaks alignment, grid overflow.
+ * On success fills *out if it is not NULL. */
+int32_t ms_trace_validate(const ms_op *op, const ms_space *space, const ms_trace *trace,
+                          ms_variant_params *out);
+
+/* Hardware limits the validator checks against.  Defaults are those of
+ * MI355X; ms_set_limits replaces them (tests use it to force rejections). */
+typedef struct ms_limits {
+    int32_t max_threads;      /* 1024 */
+    int32_t max_lds_bytes;    /* 65536 (static LDS per workgroup) */
+    int32_t max_acc_per_thread; /* 256 */
+    int32_t wave_size;        /* 64 */
+    int32_t max_waves;        /* 16 */
+    int32_t reserved[3];
+} ms_limits;
+int32_t ms_get_limits(ms_limits *out);
+int32_t ms_set_limits(const ms_limits *in);
+
+typedef struct ms_variant ms_variant;
+
+/* Validate, then materialise the kernel: the family's HIP template is
+ * compiled for gfx950 with the parameters as constants (in memory and on-disk
+ * cache keyed by params.key).  Needs no GPU until the first launch.
+ * Errors: INVALID_TRACE, COMPILE (compiler log in ms_last_error). */
+int32_t ms_variant_build(const ms_op *op, const ms_space *space, const ms_trace *trace, ms_variant **out);
+void ms_variant_destroy(ms_variant *v);
+int32_t ms_variant_info(const ms_variant *v, ms_variant_params *params, size_t *workspace_bytes);
+/* Compile the kernels of n traces ahead of use on `threads` host threads
+ * (invalid traces are skipped).  *n_built = kernels now in the cache. */
+int32_t ms_prebuild(const ms_op *op, const ms_space *space, const ms_trace *traces, int32_t n,
+                    int32_t threads, int32_t *n_built);
+/* Directory of the on-disk kernel cache (NULL or "" = in-memory only). */
+int32_t ms_set_cache_dir(const char *path);
+
+/* Enqueue one execution over `instances` instances on `stream`.  inputs /
+ * outputs: host arrays of device pointers (see ms_op_desc for the order; one
+ * output).  workspace: device pointer of at least workspace_bytes, or NULL
+ * if that is 0.  Asynchronous; returns launch errors only.  BAD_ARG if
+ * instances < 1 or the grid would exceed 2^31-1 workgroups. */
+int32_t ms_variant_launch(ms_variant *v, const void *const *inputs, void *const *outputs,
+                          void *workspace, int32_t instances, void *stream);
+
+/*
+ * Host-side coverage check of the interpreted loop nest (no GPU): walks the
+ * grid / thread / register loops the parameters describe and counts, for
+ * every output element, how often it is produced.  counts: host pointer to
+ * out_elems int32 (one instance).  A correct split/bind visits each exactly
+ * once.  This executes index arithmetic only, never the operator.
+ */
+int32_t ms_variant_coverage(const ms_op *op, const ms_variant_params *params, int32_t *counts, int64_t out_elems);
+
+/* ------------------------------------------------------------------ f(e) */
+
+typedef struct ms_bufset {
+    const void *inputs[4]; /* device pointers */
+    void *output;          /* device pointer */
+    void *workspace;       /* device pointer or NULL */
+} ms_bufset;
+
+/*
+ * One repeat = hipEventRecord, launches_per_repeat launches back to back on
+ * `stream` (launch l uses buffer set l mod n_sets), hipEventRecord, wait.
+ * Per-launch time = elapsed / launches_per_repeat.  `warmup` untimed launches
+ * come first.  Three protocols are built from this:
+ *   single launch      launches_per_repeat = 1, one buffer set
+ *   steady state       launches_per_repeat >= 200 over buffer sets whose
+ *                      footprint exceeds the last-level cache
+ *   device filling     instances = R so that one launch fills the device
+ */
+typedef struct ms_measure_cfg {
+    int32_t warmup;
+    int32_t repeats;
+    int32_t launches_per_repeat;
+    int32_t instances;
+} ms_measure_cfg;
+
+typedef struct ms_measure_result {
+    double min_us, median_us, mean_us; /* per launch */
+    double flop, bytes;                /* algorithmic, per launch (instances included) */
+    int32_t n;                         /* repeats timed */
+    int32_t reserved;
+} ms_measure_result;
+
+/* Synchronises `stream`.  HIP errors are returned as MS_ERR_HIP and leave the
+ * variant destroyable. */
+int32_t ms_measure(ms_variant *v, const ms_bufset *sets, int32_t n_sets, const ms_measure_cfg *cfg,
+                   void *stream, ms_measure_result *out);
+
+/* ------------------------------------------------------------------ search */
+
+typedef struct ms_search_cfg {
+    uint64_t seed;
+    int32_t trials;          /* measured candidates (invalid / failed ones are not counted) */
+    int32_t init_population; /* random valid traces measured first */
+    int32_t population;      /* survivors kept */
+    int32_t children;        /* proposals per generation */
+    int32_t eps_permille;    /* share of fresh random samples among proposals, in 1/1000 */
+    int32_t compile_threads;
+    double temperature0;     /* T anneals geometrically from temperature0 to temperature1 */
+    double temperature1;
+    ms_measure_cfg measure;
+} ms_search_cfg;
+void ms_search_cfg_default(ms_search_cfg *cfg);
+
+typedef struct ms_trial {
+    int32_t index;   /* 1-based among measured candidates */
+    int32_t status;  /* MS_OK or the error that made the candidate fail */
+    double us;       /* measured latency per launch (median) */
+    double best_us;  /* best so far, this trial included */
+    ms_trace trace;
+    uint64_t key;
+} ms_trial;
+/* Called after every measured or failed candidate; return non-zero to stop. */
+typedef int32_t (*ms_trial_cb)(const ms_trial *trial, void *user);
+/* Test hook: if not NULL, latency comes from this function (microseconds,
+ * <= 0 = failed) and neither compiler nor GPU is touched. */
+typedef double (*ms_latency_fn)(const ms_variant_params *params, void *user);
+
+typedef struct ms_search_result {
+    ms_trace best_trace;
+    double best_us;
+    int32_t best_trial;    /* first trial within 1 % of the final best, 1-based */
+    int32_t n_measured;
+    int32_t n_invalid;     /* proposals the validator rejected */
+    int32_t n_failed;      /* compile or launch failures */
+    int32_t n_duplicate;   /* proposals that mapped to an already measured kernel */
+    int32_t reserved;
+    double wall_seconds;
+} ms_search_result;
+
+/* Evolutionary search (Section 4): sample init_population traces; then per
+ * generation propose children by mutating parents drawn with probability
+ * proportional to exp(-f/(T f_best)) (Eq. 1 with measured f), plus a share of
+ * fresh samples; validate; measure; a child enters the population if it
+ * beats the worst member or with probability exp(-(f_child - f_parent)/(T f_best)).
+ * Deterministic in (seed, latency values). */
+int32_t ms_search(const ms_op *op, const ms_space *space, const ms_search_cfg *cfg,
+                  const ms_bufset *sets, int32_t n_sets, void *stream,
+                  ms_latency_fn fake_latency, void *fake_user,
+                  ms_trial_cb cb, void *cb_user, ms_search_result *out);
+
+/* ------------------------------------------------------------------ misc */
+
+typedef struct ms_device_info {
+    char name[64];
+    char arch[32];
+    int32_t compute_units;
+    int32_t wave_size;
+    int32_t lds_bytes_per_block;
+    int32_t max_threads_per_block;
+    int32_t clock_khz;
+    int32_t mem_clock_khz;
+    int32_t mem_bus_bits;
+    int32_t l2_bytes;
+    int64_t global_mem_bytes;
+} ms_device_info;
+/* Properties of the current HIP device.  MS_ERR_HIP if there is none. */
+int32_t ms_device_info_get(ms_device_info *out);
+
+int32_t ms_version(void);
+const char *ms_last_error(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* MS_H */

@@ -1,0 +1,417 @@
+"""ctypes binding of libms.so: same names as include/ms.h, argument marshalling only.
+
+Every step of the hot path (space description, sampling, interpretation,
+validation, kernel materialisation, launch, measurement, search) runs inside
+the library; this module only converts Python values to the C structs.
+There is no CPU fallback: if the library is missing, loading raises.
+"""
+import ctypes as C
+import os
+
+HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(HERE, "libms.so")
+
+MS_OK, MS_ERR_BAD_ARG, MS_ERR_INVALID_TRACE, MS_ERR_UNSUPPORTED, MS_ERR_COMPILE, MS_ERR_HIP, MS_ERR_NOMEM = range(7)
+OP_GEMM, OP_BMM_NT, OP_BMM_NN, OP_CONV2D_NHWC, OP_DWCONV2D_NHWC = range(5)
+F32, F16, BF16, I8, I32 = range(5)
+SLOT_PERFECT_TILE, SLOT_CATEGORICAL = 0, 1
+(SLOT_TENSORIZE, SLOT_TILE_I, SLOT_TILE_J, SLOT_TILE_C, SLOT_TILE_K, SLOT_UNROLL, SLOT_CACHE_READ, SLOT_VECTORIZE,
+ SLOT_STORAGE_ALIGN, SLOT_REORDER) = range(10)
+SPACE_TENSORIZE, SPACE_CACHE_READ, SPACE_VECTORIZE, SPACE_UNROLL, SPACE_STORAGE_ALIGN, SPACE_REORDER = 1, 2, 4, 8, 16, 32
+SPACE_DEFAULT = 0xFFFFFFFF
+FAM_GEMM_ALU, FAM_GEMM_MFMA, FAM_DWCONV = range(3)
+MAX_SLOTS, MAX_FACTORS, MAX_CANDS, MAX_LOOPS = 16, 4, 8, 8
+
+DTYPE_NAMES = {"f32": F32, "f16": F16, "bf16": BF16, "i8": I8, "i32": I32}
+
+
+class MsError(RuntimeError):
+    def __init__(self, code, msg):
+        super().__init__("ms error %d: %s" % (code, msg))
+        self.code = code
+
+
+class ms_op_desc(C.Structure):
+    _fields_ = [("kind", C.c_int32), ("in_dtype", C.c_int32), ("out_dtype", C.c_int32), ("stride", C.c_int32),
+                ("pad", C.c_int32), ("has_bias", C.c_int32), ("relu", C.c_int32), ("reserved", C.c_int32),
+                ("dims", C.c_int64 * 8), ("a_strides", C.c_int64 * 3), ("b_strides", C.c_int64 * 3)]
+
+
+class ms_loop(C.Structure):
+    _fields_ = [("name", C.c_char * 8), ("extent", C.c_int64), ("is_reduction", C.c_int32), ("reserved", C.c_int32)]
+
+
+class ms_slot(C.Structure):
+    _fields_ = [("slot_id", C.c_int32), ("kind", C.c_int32), ("name", C.c_char * 16), ("extent", C.c_int64),
+                ("n_factors", C.c_int32), ("n_candidates", C.c_int32), ("candidates", C.c_int64 * MAX_CANDS),
+                ("weight", C.c_int32 * MAX_CANDS), ("depends_on", C.c_int32), ("reserved", C.c_int32),
+                ("extent_by_choice", C.c_int64 * MAX_CANDS)]
+
+
+class ms_space(C.Structure):
+    _fields_ = [("family", C.c_int32), ("flags", C.c_uint32), ("n_slots", C.c_int32), ("reserved", C.c_int32),
+                ("slots", ms_slot * MAX_SLOTS)]
+
+
+class ms_decision(C.Structure):
+    _fields_ = [("slot_id", C.c_int32), ("kind", C.c_int32), ("n", C.c_int32), ("reserved", C.c_int32),
+                ("v", C.c_int64 * MAX_FACTORS)]
+
+
+class ms_trace(C.Structure):
+    _fields_ = [("n", C.c_int32), ("reserved", C.c_int32), ("d", ms_decision * MAX_SLOTS)]
+
+    def copy(self):
+        t = ms_trace()
+        C.memmove(C.byref(t), C.byref(self), C.sizeof(ms_trace))
+        return t
+
+    def decisions(self):
+        return [(self.d[i].slot_id, [int(self.d[i].v[k]) for k in range(self.d[i].n)]) for i in range(self.n)]
+
+
+class ms_variant_params(C.Structure):
+    _fields_ = [("family", C.c_int32), ("mfma", C.c_int32), ("ti", C.c_int32 * 4), ("tj", C.c_int32 * 4),
+                ("tc", C.c_int32 * 4), ("tk", C.c_int32 * 4), ("tile_unit", C.c_int32 * 3), ("block_m", C.c_int32),
+                ("block_n", C.c_int32), ("block_k", C.c_int32), ("grid", C.c_int32 * 3), ("threads", C.c_int32),
+                ("waves", C.c_int32), ("acc_per_thread", C.c_int32), ("lds_bytes", C.c_int32),
+                ("cache_read", C.c_int32), ("vec", C.c_int32), ("unroll", C.c_int32), ("unroll_k1", C.c_int32),
+                ("unroll_k2", C.c_int32), ("lds_pad", C.c_int32), ("reorder", C.c_int32), ("reserved", C.c_int32 * 8),
+                ("key", C.c_uint64)]
+
+    def as_dict(self):
+        out = {}
+        for name, _ in self._fields_:
+            v = getattr(self, name)
+            out[name] = list(v) if hasattr(v, "__len__") else v
+        return out
+
+
+class ms_limits(C.Structure):
+    _fields_ = [("max_threads", C.c_int32), ("max_lds_bytes", C.c_int32), ("max_acc_per_thread", C.c_int32),
+                ("wave_size", C.c_int32), ("max_waves", C.c_int32), ("reserved", C.c_int32 * 3)]
+
+
+class ms_bufset(C.Structure):
+    _fields_ = [("inputs", C.c_void_p * 4), ("output", C.c_void_p), ("workspace", C.c_void_p)]
+
+
+class ms_measure_cfg(C.Structure):
+    _fields_ = [("warmup", C.c_int32), ("repeats", C.c_int32), ("launches_per_repeat", C.c_int32),
+                ("instances", C.c_int32)]
+
+
+class ms_measure_result(C.Structure):
+    _fields_ = [("min_us", C.c_double), ("median_us", C.c_double), ("mean_us", C.c_double), ("flop", C.c_double),
+                ("bytes", C.c_double), ("n", C.c_int32), ("reserved", C.c_int32)]
+
+
+class ms_search_cfg(C.Structure):
+    _fields_ = [("seed", C.c_uint64), ("trials", C.c_int32), ("init_population", C.c_int32), ("population", C.c_int32),
+                ("children", C.c_int32), ("eps_permille", C.c_int32), ("compile_threads", C.c_int32),
+                ("temperature0", C.c_double), ("temperature1", C.c_double), ("measure", ms_measure_cfg)]
+
+
+class ms_trial(C.Structure):
+    _fields_ = [("index", C.c_int32), ("status", C.c_int32), ("us", C.c_double), ("best_us", C.c_double),
+                ("trace", ms_trace), ("key", C.c_uint64)]
+
+
+class ms_search_result(C.Structure):
+    _fields_ = [("best_trace", ms_trace), ("best_us", C.c_double), ("best_trial", C.c_int32), ("n_measured", C.c_int32),
+                ("n_invalid", C.c_int32), ("n_failed", C.c_int32), ("n_duplicate", C.c_int32), ("reserved", C.c_int32),
+                ("wall_seconds", C.c_double)]
+
+
+class ms_device_info(C.Structure):
+    _fields_ = [("name", C.c_char * 64), ("arch", C.c_char * 32), ("compute_units", C.c_int32), ("wave_size", C.c_int32),
+                ("lds_bytes_per_block", C.c_int32), ("max_threads_per_block", C.c_int32), ("clock_khz", C.c_int32),
+                ("mem_clock_khz", C.c_int32), ("mem_bus_bits", C.c_int32), ("l2_bytes", C.c_int32),
+                ("global_mem_bytes", C.c_int64)]
+
+
+TRIAL_CB = C.CFUNCTYPE(C.c_int32, C.POINTER(ms_trial), C.c_void_p)
+LATENCY_FN = C.CFUNCTYPE(C.c_double, C.POINTER(ms_variant_params), C.c_void_p)
+
+# every symbol include/ms.h declares: name -> (restype, argtypes)
+_P = C.POINTER
+SYMBOLS = {
+    "ms_op_create": (C.c_int32, [_P(ms_op_desc), _P(C.c_void_p)]),
+    "ms_op_destroy": (None, [C.c_void_p]),
+    "ms_op_get_desc": (C.c_int32, [C.c_void_p, _P(ms_op_desc)]),
+    "ms_op_loops": (C.c_int32, [C.c_void_p, _P(ms_loop), _P(C.c_int32)]),
+    "ms_op_work": (C.c_int32, [C.c_void_p, _P(C.c_double), _P(C.c_double)]),
+    "ms_op_tensor_bytes": (C.c_int32, [C.c_void_p, C.c_int32, _P(C.c_int64)]),
+    "ms_space_describe": (C.c_int32, [C.c_void_p, C.c_uint32, _P(ms_space)]),
+    "ms_space_log10_size": (C.c_int32, [_P(ms_space), _P(C.c_double)]),
+    "ms_trace_sample": (C.c_int32, [_P(ms_space), C.c_uint64, C.c_uint64, _P(ms_trace)]),
+    "ms_trace_sample_valid": (C.c_int32, [C.c_void_p, _P(ms_space), C.c_uint64, C.c_uint64, C.c_int32, _P(ms_trace)]),
+    "ms_trace_mutate": (C.c_int32, [_P(ms_space), _P(ms_trace), C.c_uint64, _P(ms_trace)]),
+    "ms_trace_to_text": (C.c_int32, [C.c_void_p, _P(ms_space), _P(ms_trace), C.c_char_p, C.c_size_t, _P(C.c_size_t)]),
+    "ms_trace_from_text": (C.c_int32, [_P(ms_space), C.c_char_p, _P(ms_trace)]),
+    "ms_trace_validate": (C.c_int32, [C.c_void_p, _P(ms_space), _P(ms_trace), _P(ms_variant_params)]),
+    "ms_get_limits": (C.c_int32, [_P(ms_limits)]),
+    "ms_set_limits": (C.c_int32, [_P(ms_limits)]),
+    "ms_variant_build": (C.c_int32, [C.c_void_p, _P(ms_space), _P(ms_trace), _P(C.c_void_p)]),
+    "ms_variant_destroy": (None, [C.c_void_p]),
+    "ms_variant_info": (C.c_int32, [C.c_void_p, _P(ms_variant_params), _P(C.c_size_t)]),
+    "ms_prebuild": (C.c_int32, [C.c_void_p, _P(ms_space), _P(ms_trace), C.c_int32, C.c_int32, _P(C.c_int32)]),
+    "ms_set_cache_dir": (C.c_int32, [C.c_char_p]),
+    "ms_variant_launch": (C.c_int32, [C.c_void_p, _P(C.c_void_p), _P(C.c_void_p), C.c_void_p, C.c_int32, C.c_void_p]),
+    "ms_variant_coverage": (C.c_int32, [C.c_void_p, _P(ms_variant_params), C.c_void_p, C.c_int64]),
+    "ms_measure": (C.c_int32, [C.c_void_p, _P(ms_bufset), C.c_int32, _P(ms_measure_cfg), C.c_void_p, _P(ms_measure_result)]),
+    "ms_search_cfg_default": (None, [_P(ms_search_cfg)]),
+    "ms_search": (C.c_int32, [C.c_void_p, _P(ms_space), _P(ms_search_cfg), _P(ms_bufset), C.c_int32, C.c_void_p,
+                              LATENCY_FN, C.c_void_p, TRIAL_CB, C.c_void_p, _P(ms_search_result)]),
+    "ms_device_info_get": (C.c_int32, [_P(ms_device_info)]),
+    "ms_version": (C.c_int32, []),
+    "ms_last_error": (C.c_char_p, []),
+}
+
+_lib = None
+
+
+def lib():
+    """Load libms.so (built by build_lib.py / __graft_entry__.build()).  Raises if it is missing."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise OSError("%s is missing: run `python -m paper_2205_13603_amd.build_lib` (there is no fallback path)" % LIB_PATH)
+        L = C.CDLL(LIB_PATH)
+        for name, (res, args) in SYMBOLS.items():
+            fn = getattr(L, name)
+            fn.restype = res
+            fn.argtypes = args
+        _lib = L
+    return _lib
+
+
+def last_error():
+    return lib().ms_last_error().decode("utf-8", "replace")
+
+
+def _check(rc):
+    if rc != MS_OK:
+        raise MsError(rc, last_error())
+
+
+# ------------------------------------------------------------------ thin object wrappers
+class Op:
+    def __init__(self, kind, in_dtype, out_dtype, dims, stride=0, pad=0, has_bias=False, relu=False,
+                 a_strides=None, b_strides=None):
+        d = ms_op_desc()
+        d.kind = kind
+        d.in_dtype = DTYPE_NAMES.get(in_dtype, in_dtype)
+        d.out_dtype = DTYPE_NAMES.get(out_dtype, out_dtype)
+        d.stride, d.pad, d.has_bias, d.relu = stride, pad, int(has_bias), int(relu)
+        for i, v in enumerate(dims):
+            d.dims[i] = v
+        for i, v in enumerate(a_strides or ()):
+            d.a_strides[i] = v
+        for i, v in enumerate(b_strides or ()):
+            d.b_strides[i] = v
+        self.handle = C.c_void_p()
+        _check(lib().ms_op_create(C.byref(d), C.byref(self.handle)))
+
+    def __del__(self):
+        if getattr(self, "handle", None) and _lib is not None:
+            _lib.ms_op_destroy(self.handle)
+            self.handle = None
+
+    def desc(self):
+        d = ms_op_desc()
+        _check(lib().ms_op_get_desc(self.handle, C.byref(d)))
+        return d
+
+    def loops(self):
+        arr = (ms_loop * MAX_LOOPS)()
+        n = C.c_int32()
+        _check(lib().ms_op_loops(self.handle, arr, C.byref(n)))
+        return [(arr[i].name.decode(), int(arr[i].extent), bool(arr[i].is_reduction)) for i in range(n.value)]
+
+    def work(self):
+        f, b = C.c_double(), C.c_double()
+        _check(lib().ms_op_work(self.handle, C.byref(f), C.byref(b)))
+        return f.value, b.value
+
+    def tensor_bytes(self, idx):
+        v = C.c_int64()
+        _check(lib().ms_op_tensor_bytes(self.handle, idx, C.byref(v)))
+        return v.value
+
+    def space(self, flags=SPACE_DEFAULT):
+        sp = ms_space()
+        _check(lib().ms_space_describe(self.handle, flags, C.byref(sp)))
+        return sp
+
+
+def gemm_op(M, N, K, in_dtype="f32", out_dtype=None, **kw):
+    return Op(OP_GEMM, in_dtype, out_dtype or ("i32" if in_dtype == "i8" else in_dtype), [M, N, K], **kw)
+
+
+def bmm_op(B, M, N, K, trans_b, in_dtype="f16", out_dtype=None, **kw):
+    return Op(OP_BMM_NT if trans_b else OP_BMM_NN, in_dtype, out_dtype or ("i32" if in_dtype == "i8" else in_dtype),
+              [B, M, N, K], **kw)
+
+
+def conv2d_op(N, H, W, Cin, Cout, KH, KW, stride=1, pad=0, has_bias=True, relu=True, in_dtype="f16", out_dtype=None):
+    return Op(OP_CONV2D_NHWC, in_dtype, out_dtype or in_dtype, [N, H, W, Cin, Cout, KH, KW], stride=stride, pad=pad,
+              has_bias=has_bias, relu=relu)
+
+
+def dwconv2d_op(N, H, W, Cc, KH=3, KW=3, stride=1, pad=1):
+    return Op(OP_DWCONV2D_NHWC, "f32", "f32", [N, H, W, Cc, KH, KW], stride=stride, pad=pad)
+
+
+def space_log10_size(space):
+    v = C.c_double()
+    _check(lib().ms_space_log10_size(C.byref(space), C.byref(v)))
+    return v.value
+
+
+def trace_sample(space, seed, index):
+    t = ms_trace()
+    _check(lib().ms_trace_sample(C.byref(space), seed, index, C.byref(t)))
+    return t
+
+
+def trace_sample_valid(op, space, seed, index, max_tries=1000):
+    t = ms_trace()
+    _check(lib().ms_trace_sample_valid(op.handle, C.byref(space), seed, index, max_tries, C.byref(t)))
+    return t
+
+
+def trace_mutate(space, trace, seed):
+    t = ms_trace()
+    _check(lib().ms_trace_mutate(C.byref(space), C.byref(trace), seed, C.byref(t)))
+    return t
+
+
+def trace_to_text(op, space, trace):
+    need = C.c_size_t()
+    _check(lib().ms_trace_to_text(op.handle, C.byref(space), C.byref(trace), None, 0, C.byref(need)))
+    buf = C.create_string_buffer(need.value)
+    _check(lib().ms_trace_to_text(op.handle, C.byref(space), C.byref(trace), buf, need.value, None))
+    return buf.value.decode()
+
+
+def trace_from_text(space, text):
+    t = ms_trace()
+    _check(lib().ms_trace_from_text(C.byref(space), text.encode(), C.byref(t)))
+    return t
+
+
+def trace_validate(op, space, trace):
+    p = ms_variant_params()
+    _check(lib().ms_trace_validate(op.handle, C.byref(space), C.byref(trace), C.byref(p)))
+    return p
+
+
+def make_trace(space, values):
+    """Build a trace from plain lists: one list per slot (tile factors, or [candidate value])."""
+    t = ms_trace()
+    t.n = space.n_slots
+    assert len(values) == space.n_slots
+    for i, vals in enumerate(values):
+        s = space.slots[i]
+        t.d[i].slot_id, t.d[i].kind = s.slot_id, s.kind
+        if s.kind == SLOT_CATEGORICAL:
+            cands = [s.candidates[c] for c in range(s.n_candidates)]
+            (val,) = vals if isinstance(vals, (list, tuple)) else (vals,)
+            t.d[i].n = 1
+            t.d[i].v[0] = cands.index(val)
+        else:
+            t.d[i].n = len(vals)
+            for k, v in enumerate(vals):
+                t.d[i].v[k] = v
+    return t
+
+
+def get_limits():
+    lim = ms_limits()
+    _check(lib().ms_get_limits(C.byref(lim)))
+    return lim
+
+
+def set_limits(lim):
+    _check(lib().ms_set_limits(C.byref(lim)))
+
+
+def variant_coverage(op, params, out_elems):
+    import numpy as np
+    counts = np.zeros(out_elems, np.int32)
+    _check(lib().ms_variant_coverage(op.handle, C.byref(params), counts.ctypes.data_as(C.c_void_p), out_elems))
+    return counts
+
+
+def prebuild(op, space, traces, threads=8):
+    arr = (ms_trace * len(traces))(*traces)
+    n = C.c_int32()
+    _check(lib().ms_prebuild(op.handle, C.byref(space), arr, len(traces), threads, C.byref(n)))
+    return n.value
+
+
+def set_cache_dir(path):
+    _check(lib().ms_set_cache_dir(path.encode() if path else None))
+
+
+class Variant:
+    def __init__(self, op, space, trace):
+        self.op = op
+        self.handle = C.c_void_p()
+        _check(lib().ms_variant_build(op.handle, C.byref(space), C.byref(trace), C.byref(self.handle)))
+
+    def __del__(self):
+        if getattr(self, "handle", None) and _lib is not None:
+            _lib.ms_variant_destroy(self.handle)
+            self.handle = None
+
+    def params(self):
+        p = ms_variant_params()
+        ws = C.c_size_t()
+        _check(lib().ms_variant_info(self.handle, C.byref(p), C.byref(ws)))
+        return p
+
+    def launch(self, inputs, output, instances=1, stream=None, workspace=None):
+        """inputs / output: device pointers (ints)."""
+        ins = (C.c_void_p * 4)(*[C.c_void_p(p) for p in inputs])
+        outs = (C.c_void_p * 1)(C.c_void_p(output))
+        _check(lib().ms_variant_launch(self.handle, ins, outs, workspace, instances, stream))
+
+    def measure(self, bufsets, warmup=2, repeats=5, launches_per_repeat=20, instances=1, stream=None):
+        """bufsets: list of (inputs, output) device pointer tuples."""
+        arr = (ms_bufset * len(bufsets))()
+        for i, (ins, out) in enumerate(bufsets):
+            for k, p in enumerate(ins):
+                arr[i].inputs[k] = p
+            arr[i].output = out
+        cfg = ms_measure_cfg(warmup, repeats, launches_per_repeat, instances)
+        res = ms_measure_result()
+        _check(lib().ms_measure(self.handle, arr, len(bufsets), C.byref(cfg), stream, C.byref(res)))
+        return res
+
+
+def device_info():
+    info = ms_device_info()
+    _check(lib().ms_device_info_get(C.byref(info)))
+    return info
+
+
+def search_cfg_default():
+    cfg = ms_search_cfg()
+    lib().ms_search_cfg_default(C.byref(cfg))
+    return cfg
+
+
+def search(op, space, cfg, bufsets=(), stream=None, fake_latency=None, on_trial=None):
+    arr = (ms_bufset * max(1, len(bufsets)))()
+    for i, (ins, out) in enumerate(bufsets):
+        for k, p in enumerate(ins):
+            arr[i].inputs[k] = p
+        arr[i].output = out
+    res = ms_search_result()
+    lat = LATENCY_FN(lambda p, u: float(fake_latency(p.contents))) if fake_latency else C.cast(None, LATENCY_FN)
+    cb = TRIAL_CB(lambda t, u: int(on_trial(t.contents) or 0)) if on_trial else C.cast(None, TRIAL_CB)
+    _check(lib().ms_search(op.handle, C.byref(space), C.byref(cfg), arr, len(bufsets), stream, lat, None, cb, None,
+                           C.byref(res)))
+    return res

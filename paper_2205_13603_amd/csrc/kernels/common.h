@@ -1,0 +1,82 @@
+// Shared by every kernel template (spliced in before run-time compilation).
+// Everything that depends on the schedule arrives as a -D constant.
+
+#define DT_F32 0
+#define DT_F16 1
+#define DT_BF16 2
+#define DT_I8 3
+#define DT_I32 4
+
+typedef _Float16 half_t;
+
+template <int DT> struct dt_traits;
+template <> struct dt_traits<DT_F32> { typedef float type; };
+template <> struct dt_traits<DT_F16> { typedef half_t type; };
+template <> struct dt_traits<DT_BF16> { typedef unsigned short type; };
+template <> struct dt_traits<DT_I8> { typedef signed char type; };
+template <> struct dt_traits<DT_I32> { typedef int type; };
+
+typedef dt_traits<IN_DT>::type in_t;
+typedef dt_traits<OUT_DT>::type out_t;
+
+#if IN_DT == DT_I8
+typedef int acc_t;
+#else
+typedef float acc_t;
+#endif
+
+// A naturally aligned group of N elements: loads and stores of it become one
+// memory instruction of N*sizeof(T) bytes.
+template <typename T, int N> struct __attribute__((aligned(sizeof(T) * N))) vec_t {
+    T v[N];
+};
+
+__device__ __forceinline__ float bf16_to_float(unsigned short b) { return __uint_as_float((unsigned)b << 16); }
+
+// round to nearest even; NaN stays NaN
+__device__ __forceinline__ unsigned short float_to_bf16(float f)
+{
+    unsigned u = __float_as_uint(f);
+    if ((u & 0x7fffffffu) > 0x7f800000u) return (unsigned short)((u >> 16) | 0x40u);
+    u += 0x7fffu + ((u >> 16) & 1u);
+    return (unsigned short)(u >> 16);
+}
+
+__device__ __forceinline__ acc_t to_acc(in_t x)
+{
+#if IN_DT == DT_BF16
+    return bf16_to_float(x);
+#else
+    return (acc_t)x;
+#endif
+}
+
+// the single rounding from the accumulator to the output type
+__device__ __forceinline__ out_t from_acc(acc_t x)
+{
+#if OUT_DT == DT_BF16
+    return float_to_bf16(x);
+#else
+    return (out_t)x;
+#endif
+}
+
+// Workgroup id -> (i0, j0) of the two outer spatial loops.
+// REORDER 0: i outer.  1: j outer.  2: i outer, but ids are first permuted so
+// that the workgroups one XCD receives (ids congruent mod 8) are neighbours in
+// tile order and share operand panels in that XCD's L2.
+__device__ __forceinline__ void block_to_tile(int wg, int &i0, int &j0)
+{
+    constexpr int G = I0 * J0;
+#if REORDER == 1
+    j0 = wg / I0;
+    i0 = wg % I0;
+#else
+#if REORDER == 2
+    if (G % 8 == 0) wg = (wg % 8) * (G / 8) + wg / 8;
+#endif
+    i0 = wg / J0;
+    j0 = wg % J0;
+#endif
+    (void)G;
+}

@@ -1,0 +1,60 @@
+// Internal declarations shared by the translation units of libms.
+#pragma once
+#include "../../include/ms.h"
+
+#include <cstdarg>
+#include <cstdint>
+#include <string>
+#include <vector>
+
+struct ms_op {
+    ms_op_desc d;
+    // derived
+    int64_t nb;          // batch (BMM) or 1
+    int64_t M, N, K;     // implicit-GEMM view (conv: M = N*OH*OW, N = Cout, K = KH*KW*Cin)
+    int64_t OH, OW;      // convolutions
+    int in_size, out_size; // bytes per element
+};
+
+namespace ms {
+
+int32_t fail(int32_t code, const char *fmt, ...) __attribute__((format(printf, 2, 3)));
+void set_error(const char *fmt, ...) __attribute__((format(printf, 1, 2)));
+
+// 64-bit counter-based generator: integer only, platform independent.
+struct Rng {
+    uint64_t s;
+    explicit Rng(uint64_t seed) : s(seed) {}
+    uint64_t next();
+    // uniform in [0, n) by rejection, n >= 1
+    uint64_t below(uint64_t n);
+};
+uint64_t mix64(uint64_t x);
+
+const ms_slot *find_slot(const ms_space *sp, int32_t slot_id, int *pos);
+const ms_decision *find_decision(const ms_trace *t, int32_t slot_id);
+int64_t slot_extent(const ms_space *sp, const ms_trace *t, int pos); // resolves depends_on, -1 if unresolved
+
+int dtype_size(int32_t dt);
+const char *dtype_name(int32_t dt);
+const char *op_kind_name(int32_t kind);
+
+extern ms_limits g_limits;
+
+// Kernel source generation: template file + "-D" defines for a variant.
+struct KernelSpec {
+    std::string template_name; // file in kernels/
+    std::vector<std::string> defines;
+    std::string entry;         // kernel symbol
+    unsigned block[3];
+    unsigned grid[3];          // per instance; instances multiply grid[2]
+    unsigned lds_dynamic;
+};
+int32_t make_kernel_spec(const ms_op *op, const ms_variant_params *p, KernelSpec *out);
+
+// JIT (ms_jit.cpp)
+struct CodeObject;
+int32_t jit_get_code(const KernelSpec &spec, uint64_t key, std::vector<char> **code_out);
+std::string kernels_dir();
+
+} // namespace ms

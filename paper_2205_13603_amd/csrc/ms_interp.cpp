@@ -1,0 +1,463 @@
+// Trace interpreter and validator: decisions -> kernel template parameters
+// (the split / reorder / bind / cache-read / unroll / vectorize / tensorize
+// schedule of Table 2, applied in a fixed order per kernel family), plus the
+// hardware-limit checks of the paper's "Trace validation" paragraph.
+// Host only.
+#include "ms_internal.h"
+
+#include <algorithm>
+#include <cinttypes>
+#include <cstdio>
+#include <cstring>
+
+using namespace ms;
+
+namespace {
+
+struct Reject {
+    int32_t code;
+};
+
+int32_t reject(const char *fmt, ...) __attribute__((format(printf, 1, 2)));
+int32_t reject(const char *fmt, ...)
+{
+    char buf[1024];
+    va_list ap;
+    va_start(ap, fmt);
+    vsnprintf(buf, sizeof buf, fmt, ap);
+    va_end(ap);
+    return fail(MS_ERR_INVALID_TRACE, "invalid trace: %s", buf);
+}
+
+int64_t cat_value(const ms_space *sp, const ms_trace *t, int32_t slot_id, int64_t dflt)
+{
+    int pos;
+    const ms_slot *s = find_slot(sp, slot_id, &pos);
+    if (!s) return dflt;
+    return s->candidates[t->d[pos].v[0]];
+}
+
+bool get_tile(const ms_space *sp, const ms_trace *t, int32_t slot_id, int32_t *f)
+{
+    int pos;
+    const ms_slot *s = find_slot(sp, slot_id, &pos);
+    if (!s) return false;
+    for (int i = 0; i < 4; ++i) f[i] = (int32_t)t->d[pos].v[i];
+    return true;
+}
+
+uint64_t hash_params(const ms_op *op, const ms_variant_params *p)
+{
+    uint64_t h = 0x243F6A8885A308D3ull;
+    auto add = [&](uint64_t v) { h = mix64(h ^ mix64(v)); };
+    const ms_op_desc &d = op->d;
+    add((uint64_t)d.kind);
+    add((uint64_t)d.in_dtype);
+    add((uint64_t)d.out_dtype);
+    add((uint64_t)d.stride);
+    add((uint64_t)d.pad);
+    add((uint64_t)d.has_bias);
+    add((uint64_t)d.relu);
+    for (int i = 0; i < 8; ++i) add((uint64_t)d.dims[i]);
+    for (int i = 0; i < 3; ++i) {
+        add((uint64_t)d.a_strides[i]);
+        add((uint64_t)d.b_strides[i]);
+    }
+    add((uint64_t)p->family);
+    add((uint64_t)p->mfma);
+    for (int i = 0; i < 4; ++i) {
+        add((uint64_t)p->ti[i]);
+        add((uint64_t)p->tj[i]);
+        add((uint64_t)p->tc[i]);
+        add((uint64_t)p->tk[i]);
+    }
+    add((uint64_t)p->cache_read);
+    add((uint64_t)p->vec);
+    add((uint64_t)p->unroll_k1);
+    add((uint64_t)p->unroll_k2);
+    add((uint64_t)p->unroll);
+    add((uint64_t)p->lds_pad);
+    add((uint64_t)p->reorder);
+    return h;
+}
+
+void unroll_factors(ms_variant_params *p)
+{
+    // budget = number of innermost iterations that may be unrolled; k3 is always unrolled
+    int32_t u = p->unroll;
+    int32_t k1 = p->tk[1], k2 = p->tk[2], k3 = p->tk[3];
+    if (u <= 0) {
+        p->unroll_k1 = 1;
+        p->unroll_k2 = 1;
+        return;
+    }
+    p->unroll_k2 = std::min(k2, std::max(1, u / k3));
+    if (p->unroll_k2 == k2 && (int64_t)k2 * k3 <= u)
+        p->unroll_k1 = std::min(k1, std::max(1, u / (k2 * k3)));
+    else
+        p->unroll_k1 = 1;
+    // keep the unrolled body within the instruction cache: at most 4096
+    // multiply-accumulate (or matrix-core) instructions per lane
+    int64_t per_iter = (int64_t)std::max(1, p->acc_per_thread) * k3;
+    if (p->mfma) per_iter = (int64_t)p->ti[1] * p->ti[3] * p->tj[1] * p->tj[3] * k3 * 16;
+    while (p->unroll_k1 > 1 && per_iter * p->unroll_k2 * p->unroll_k1 > 4096) p->unroll_k1 = (p->unroll_k1 + 1) / 2;
+    while (p->unroll_k2 > 1 && per_iter * p->unroll_k2 > 4096) p->unroll_k2 = (p->unroll_k2 + 1) / 2;
+}
+
+} // namespace
+
+extern "C" int32_t ms_trace_validate(const ms_op *op, const ms_space *space, const ms_trace *trace, ms_variant_params *out)
+{
+    if (!op || !space || !trace) return fail(MS_ERR_BAD_ARG, "ms_trace_validate: NULL argument");
+    if (space->n_slots < 1 || space->n_slots > MS_MAX_SLOTS) return fail(MS_ERR_BAD_ARG, "ms_trace_validate: bad space");
+    if (trace->n != space->n_slots)
+        return reject("trace has %d decisions, the space has %d sampling instructions (truncated?)", trace->n, space->n_slots);
+    // well-formedness of every decision, read or not
+    for (int i = 0; i < space->n_slots; ++i) {
+        const ms_slot &s = space->slots[i];
+        const ms_decision &d = trace->d[i];
+        if (d.slot_id != s.slot_id) return reject("decision %d is for slot id %d, expected %d (%s)", i, d.slot_id, s.slot_id, s.name);
+        if (d.kind != s.kind) return reject("decision %d (%s) has the wrong kind", i, s.name);
+        if (s.kind == MS_SLOT_CATEGORICAL) {
+            if (d.n != 1) return reject("categorical %s carries %d values", s.name, d.n);
+            if (d.v[0] < 0 || d.v[0] >= s.n_candidates)
+                return reject("categorical %s: index %" PRId64 " outside [0,%d)", s.name, d.v[0], s.n_candidates);
+            if (s.weight[d.v[0]] <= 0) return reject("categorical %s: candidate %" PRId64 " has zero probability", s.name, d.v[0]);
+        } else {
+            if (d.n != s.n_factors) return reject("tile %s carries %d factors, expected %d", s.name, d.n, s.n_factors);
+            int64_t e = slot_extent(space, trace, i);
+            if (e < 1) return reject("tile %s: extent undefined", s.name);
+            int64_t prod = 1;
+            for (int f = 0; f < d.n; ++f) {
+                if (d.v[f] < 1) return reject("tile %s: factor %d is %" PRId64, s.name, f, d.v[f]);
+                if (d.v[f] > e) return reject("tile %s: factor %d = %" PRId64 " exceeds the extent %" PRId64, s.name, f, d.v[f], e);
+                prod *= d.v[f];
+                if (prod > e) break;
+            }
+            if (prod != e) return reject("tile %s: factors multiply to %" PRId64 ", loop extent is %" PRId64, s.name, prod, e);
+        }
+    }
+
+    ms_variant_params p;
+    memset(&p, 0, sizeof p);
+    p.family = space->family;
+    const ms_op_desc &d = op->d;
+    const ms_limits &L = g_limits;
+    p.unroll = (int32_t)cat_value(space, trace, MS_SLOT_UNROLL, 0);
+    p.vec = (int32_t)cat_value(space, trace, MS_SLOT_VECTORIZE, 1);
+    p.lds_pad = (int32_t)cat_value(space, trace, MS_SLOT_STORAGE_ALIGN, 0);
+    p.reorder = (int32_t)cat_value(space, trace, MS_SLOT_REORDER, 0);
+
+    if (space->family == MS_FAM_GEMM_ALU || space->family == MS_FAM_GEMM_MFMA) {
+        if (!get_tile(space, trace, MS_SLOT_TILE_I, p.ti) || !get_tile(space, trace, MS_SLOT_TILE_J, p.tj) ||
+            !get_tile(space, trace, MS_SLOT_TILE_K, p.tk))
+            return fail(MS_ERR_BAD_ARG, "ms_trace_validate: the space lacks a tile slot");
+        p.cache_read = (int32_t)cat_value(space, trace, MS_SLOT_CACHE_READ, 1);
+        int es = op->in_size;
+        if (space->family == MS_FAM_GEMM_ALU) {
+            p.mfma = MS_MFMA_NONE;
+            p.tile_unit[0] = p.tile_unit[1] = p.tile_unit[2] = 1;
+        } else {
+            p.mfma = (int32_t)cat_value(space, trace, MS_SLOT_TENSORIZE, 0);
+            p.tile_unit[0] = p.mfma / 10000;
+            p.tile_unit[1] = p.mfma / 100 % 100;
+            p.tile_unit[2] = p.mfma % 100;
+            if (p.tile_unit[0] != p.tile_unit[1] || (p.tile_unit[0] != 16 && p.tile_unit[0] != 32))
+                return reject("tensorize: unknown intrinsic %d", p.mfma);
+        }
+        int64_t bm = (int64_t)p.ti[1] * p.ti[2] * p.ti[3] * p.tile_unit[0];
+        int64_t bn = (int64_t)p.tj[1] * p.tj[2] * p.tj[3] * p.tile_unit[1];
+        int64_t bk = (int64_t)p.tk[1] * p.tk[2] * p.tk[3] * p.tile_unit[2];
+        if (bm > 4096 || bn > 4096 || bk > 4096) return reject("workgroup tile %" PRId64 "x%" PRId64 "x%" PRId64 " is beyond any register/LDS budget", bm, bn, bk);
+        p.block_m = (int32_t)bm;
+        p.block_n = (int32_t)bn;
+        p.block_k = (int32_t)bk;
+        int64_t g = (int64_t)p.ti[0] * p.tj[0];
+        if (g > 0x7fffffff / std::max<int64_t>(1, op->nb)) return reject("grid of %" PRId64 " workgroups overflows", g);
+        p.grid[0] = (int32_t)g;
+        p.grid[1] = 1;
+        p.grid[2] = (int32_t)op->nb;
+        int64_t units = (int64_t)p.ti[2] * p.tj[2];
+        int64_t acc;
+        if (p.mfma) {
+            if (units > L.max_waves) return reject("%" PRId64 " wavefronts per workgroup, the limit is %d", units, L.max_waves);
+            p.waves = (int32_t)units;
+            p.threads = p.waves * L.wave_size;
+            acc = (int64_t)p.ti[1] * p.ti[3] * p.tj[1] * p.tj[3] * (p.tile_unit[0] * p.tile_unit[1] / L.wave_size);
+        } else {
+            if (units > L.max_threads) return reject("%" PRId64 " threads per workgroup, the limit is %d", units, L.max_threads);
+            p.threads = (int32_t)units;
+            p.waves = (p.threads + L.wave_size - 1) / L.wave_size;
+            acc = (int64_t)p.ti[1] * p.ti[3] * p.tj[1] * p.tj[3];
+        }
+        if (p.threads > L.max_threads) return reject("%d threads per workgroup, the limit is %d", p.threads, L.max_threads);
+        if (acc > L.max_acc_per_thread) return reject("%" PRId64 " accumulators per lane, the register budget is %d", acc, L.max_acc_per_thread);
+        p.acc_per_thread = (int32_t)acc;
+        // cache-read: LDS footprint
+        int64_t lds = 0;
+        if (p.mfma) {
+            int kp = p.tile_unit[2] / (L.wave_size / p.tile_unit[0]); // k elements one lane feeds per intrinsic
+            int64_t rowsA = bm * kp * es + p.lds_pad * 16, rowsB = bn * kp * es + p.lds_pad * 16;
+            lds = (int64_t)p.cache_read * (bk / kp) * (rowsA + rowsB);
+            // fragment operands of one k step for the whole wave tile live in registers too
+            int64_t frag = ((int64_t)p.ti[1] * p.ti[3] + (int64_t)p.tj[1] * p.tj[3]) * p.tk[3] * (kp * es / 4 > 0 ? kp * es / 4 : 1);
+            if (frag + acc > 448) return reject("%" PRId64 " fragment + %" PRId64 " accumulator registers per lane exceed the register file", frag, acc);
+        } else if (p.cache_read) {
+            int stages = p.cache_read;
+            lds = (int64_t)stages * 4 * (bm * (bk + p.lds_pad * 4) + bk * (bn + p.lds_pad * 4));
+            int64_t frag = ((int64_t)p.ti[1] * p.ti[3] + (int64_t)p.tj[1] * p.tj[3]) * p.tk[3];
+            if (frag + acc > 448) return reject("%" PRId64 " operand + %" PRId64 " accumulator registers per lane exceed the register file", frag, acc);
+        } else {
+            if (p.lds_pad) return reject("storage_align without cache_read has nothing to pad");
+            int64_t frag = ((int64_t)p.ti[1] * p.ti[3] + (int64_t)p.tj[1] * p.tj[3]) * p.tk[3];
+            if (frag + acc > 448) return reject("%" PRId64 " operand + %" PRId64 " accumulator registers per lane exceed the register file", frag, acc);
+        }
+        if (lds > L.max_lds_bytes) return reject("LDS tile needs %" PRId64 " bytes, the limit is %d", lds, L.max_lds_bytes);
+        p.lds_bytes = (int32_t)lds;
+        // vectorize: alignment and divisibility of the global loads
+        if (p.vec > 1) {
+            int v = p.vec;
+            if (v * es > 16) return reject("vector of %d x %d bytes is wider than a 16-byte load", v, es);
+            if (d.kind == MS_OP_CONV2D_NHWC) {
+                if (d.dims[3] % v) return reject("vector width %d does not divide Cin = %" PRId64, v, d.dims[3]);
+                if (d.dims[4] % v) return reject("vector width %d does not divide Cout = %" PRId64, v, d.dims[4]);
+                if (bk % v) return reject("vector width %d does not divide the k tile %" PRId64, v, bk);
+            } else {
+                // A: vector along k
+                if (d.a_strides[2] != 1) return reject("vector loads of A need k contiguous");
+                if (bk % v || d.a_strides[1] % v || (op->nb > 1 && d.a_strides[0] % v))
+                    return reject("vector width %d breaks alignment of A (k tile %" PRId64 ", row stride %" PRId64 ")", v, bk, d.a_strides[1]);
+                if (d.b_strides[2] == 1) { // vector along j
+                    if (bn % v || d.b_strides[1] % v || (op->nb > 1 && d.b_strides[0] % v))
+                        return reject("vector width %d breaks alignment of B (j tile %" PRId64 ", row stride %" PRId64 ")", v, bn, d.b_strides[1]);
+                } else if (d.b_strides[1] == 1) { // vector along k
+                    if (bk % v || d.b_strides[2] % v || (op->nb > 1 && d.b_strides[0] % v))
+                        return reject("vector width %d breaks alignment of B (k tile %" PRId64 ", column stride %" PRId64 ")", v, bk, d.b_strides[2]);
+                } else {
+                    return reject("vector loads of B need j or k contiguous");
+                }
+            }
+        }
+        unroll_factors(&p);
+    } else if (space->family == MS_FAM_DWCONV) {
+        if (!get_tile(space, trace, MS_SLOT_TILE_I, p.ti) || !get_tile(space, trace, MS_SLOT_TILE_J, p.tj) ||
+            !get_tile(space, trace, MS_SLOT_TILE_C, p.tc))
+            return fail(MS_ERR_BAD_ARG, "ms_trace_validate: the space lacks a tile slot");
+        p.cache_read = (int32_t)cat_value(space, trace, MS_SLOT_CACHE_READ, 0);
+        p.tile_unit[0] = p.tile_unit[1] = p.tile_unit[2] = 1;
+        int64_t boh = (int64_t)p.ti[1] * p.ti[2] * p.ti[3], bow = (int64_t)p.tj[1] * p.tj[2] * p.tj[3],
+                bc = (int64_t)p.tc[1] * p.tc[2] * p.tc[3];
+        p.block_m = (int32_t)boh;
+        p.block_n = (int32_t)bow;
+        p.block_k = (int32_t)bc;
+        int64_t threads = (int64_t)p.ti[2] * p.tj[2] * p.tc[2];
+        if (threads > L.max_threads) return reject("%" PRId64 " threads per workgroup, the limit is %d", threads, L.max_threads);
+        p.threads = (int32_t)threads;
+        p.waves = (p.threads + L.wave_size - 1) / L.wave_size;
+        int64_t acc = (int64_t)p.ti[1] * p.ti[3] * p.tj[1] * p.tj[3] * p.tc[1] * p.tc[3];
+        if (acc > std::min(L.max_acc_per_thread, 128)) return reject("%" PRId64 " outputs per thread exceed the register budget", acc);
+        p.acc_per_thread = (int32_t)acc;
+        int64_t g = (int64_t)p.ti[0] * p.tj[0] * p.tc[0];
+        if (g > 0x7fffffff / std::max<int64_t>(1, d.dims[0])) return reject("grid of %" PRId64 " workgroups overflows", g);
+        p.grid[0] = (int32_t)g;
+        p.grid[1] = 1;
+        p.grid[2] = (int32_t)d.dims[0];
+        p.vec = p.tc[3];
+        if (p.cache_read) {
+            int64_t ih = (boh - 1) * d.stride + d.dims[4], iw = (bow - 1) * d.stride + d.dims[5];
+            int64_t lds = ih * iw * bc * 4;
+            if (lds > L.max_lds_bytes) return reject("LDS halo tile needs %" PRId64 " bytes, the limit is %d", lds, L.max_lds_bytes);
+            p.lds_bytes = (int32_t)lds;
+        }
+        p.tk[0] = 1;
+        p.tk[1] = (int32_t)d.dims[4];
+        p.tk[2] = (int32_t)d.dims[5];
+        p.tk[3] = 1;
+        p.unroll_k1 = p.unroll_k2 = p.unroll > 0 ? 0 : 1; // 0 = full unroll of the tap loops
+    } else {
+        return fail(MS_ERR_BAD_ARG, "ms_trace_validate: unknown family %d", space->family);
+    }
+    p.key = hash_params(op, &p);
+    if (out) *out = p;
+    return MS_OK;
+}
+
+namespace ms {
+
+static std::string def(const char *name, int64_t v)
+{
+    char buf[96];
+    snprintf(buf, sizeof buf, "-D%s=%" PRId64, name, v);
+    return buf;
+}
+
+static int dt_code(int32_t dt) { return dt; }
+
+int32_t make_kernel_spec(const ms_op *op, const ms_variant_params *p, KernelSpec *out)
+{
+    const ms_op_desc &d = op->d;
+    KernelSpec k;
+    k.entry = "ms_kernel";
+    k.block[0] = (unsigned)p->threads;
+    k.block[1] = k.block[2] = 1;
+    k.grid[0] = (unsigned)p->grid[0];
+    k.grid[1] = (unsigned)p->grid[1];
+    k.grid[2] = (unsigned)p->grid[2];
+    k.lds_dynamic = 0;
+    auto &D = k.defines;
+    D.push_back(def("IN_DT", dt_code(d.in_dtype)));
+    D.push_back(def("OUT_DT", dt_code(d.out_dtype)));
+    const char *tn[4] = {"I", "J", "C", "K"};
+    const int32_t *tl[4] = {p->ti, p->tj, p->tc, p->tk};
+    for (int l = 0; l < 4; ++l)
+        for (int f = 0; f < 4; ++f) {
+            char nm[8];
+            snprintf(nm, sizeof nm, "%s%d", tn[l], f);
+            D.push_back(def(nm, tl[l][f] ? tl[l][f] : 1));
+        }
+    D.push_back(def("NTHREADS", p->threads));
+    D.push_back(def("CACHE_READ", p->cache_read));
+    D.push_back(def("VEC", p->vec));
+    D.push_back(def("UNROLL_K1", p->unroll_k1));
+    D.push_back(def("UNROLL_K2", p->unroll_k2));
+    D.push_back(def("LDS_PAD", p->lds_pad));
+    D.push_back(def("REORDER", p->reorder));
+    if (p->family == MS_FAM_GEMM_ALU || p->family == MS_FAM_GEMM_MFMA) {
+        D.push_back(def("DIM_B", op->nb));
+        D.push_back(def("DIM_M", op->M));
+        D.push_back(def("DIM_N", op->N));
+        D.push_back(def("DIM_K", op->K));
+        bool conv = d.kind == MS_OP_CONV2D_NHWC;
+        D.push_back(def("IS_CONV", conv ? 1 : 0));
+        if (conv) {
+            D.push_back(def("CV_N", d.dims[0]));
+            D.push_back(def("CV_H", d.dims[1]));
+            D.push_back(def("CV_W", d.dims[2]));
+            D.push_back(def("CV_CIN", d.dims[3]));
+            D.push_back(def("CV_COUT", d.dims[4]));
+            D.push_back(def("CV_KH", d.dims[5]));
+            D.push_back(def("CV_KW", d.dims[6]));
+            D.push_back(def("CV_OH", op->OH));
+            D.push_back(def("CV_OW", op->OW));
+            D.push_back(def("CV_STRIDE", d.stride));
+            D.push_back(def("CV_PAD", d.pad));
+            D.push_back(def("HAS_BIAS", d.has_bias ? 1 : 0));
+            D.push_back(def("RELU", d.relu ? 1 : 0));
+            // implicit GEMM view: A rows are output pixels, B = W as [K][N]
+            D.push_back(def("SA_B", 0));
+            D.push_back(def("SA_I", 0));
+            D.push_back(def("SA_K", 1));
+            D.push_back(def("SB_B", 0));
+            D.push_back(def("SB_K", d.dims[4]));
+            D.push_back(def("SB_J", 1));
+            D.push_back(def("A_INST", d.dims[0] * d.dims[1] * d.dims[2] * d.dims[3]));
+            D.push_back(def("B_INST", op->K * op->N));
+        } else {
+            D.push_back(def("HAS_BIAS", 0));
+            D.push_back(def("RELU", 0));
+            D.push_back(def("SA_B", d.a_strides[0]));
+            D.push_back(def("SA_I", d.a_strides[1]));
+            D.push_back(def("SA_K", d.a_strides[2]));
+            D.push_back(def("SB_B", d.b_strides[0]));
+            D.push_back(def("SB_K", d.b_strides[1]));
+            D.push_back(def("SB_J", d.b_strides[2]));
+            int64_t ab, bb;
+            ms_op_tensor_bytes(op, 0, &ab);
+            ms_op_tensor_bytes(op, 1, &bb);
+            D.push_back(def("A_INST", ab / op->in_size));
+            D.push_back(def("B_INST", bb / op->in_size));
+        }
+        if (p->family == MS_FAM_GEMM_MFMA) {
+            k.template_name = "gemm_mfma.hip";
+            D.push_back(def("MI_M", p->tile_unit[0]));
+            D.push_back(def("MI_N", p->tile_unit[1]));
+            D.push_back(def("MI_K", p->tile_unit[2]));
+        } else {
+            k.template_name = "gemm_alu.hip";
+        }
+    } else {
+        k.template_name = "dwconv.hip";
+        D.push_back(def("CV_N", d.dims[0]));
+        D.push_back(def("CV_H", d.dims[1]));
+        D.push_back(def("CV_W", d.dims[2]));
+        D.push_back(def("CV_C", d.dims[3]));
+        D.push_back(def("CV_KH", d.dims[4]));
+        D.push_back(def("CV_KW", d.dims[5]));
+        D.push_back(def("CV_OH", op->OH));
+        D.push_back(def("CV_OW", op->OW));
+        D.push_back(def("CV_STRIDE", d.stride));
+        D.push_back(def("CV_PAD", d.pad));
+    }
+    *out = k;
+    return MS_OK;
+}
+
+} // namespace ms
+
+// Index of the four-level split: ((x0*f1 + x1)*f2 + x2)*f3 + x3.
+static inline int64_t split_index(const int32_t *f, int64_t x0, int64_t x1, int64_t x2, int64_t x3)
+{
+    return ((x0 * f[1] + x1) * f[2] + x2) * f[3] + x3;
+}
+
+extern "C" int32_t ms_variant_coverage(const ms_op *op, const ms_variant_params *p, int32_t *counts, int64_t out_elems)
+{
+    if (!op || !p || !counts) return fail(MS_ERR_BAD_ARG, "ms_variant_coverage: NULL argument");
+    int64_t ob;
+    ms_op_tensor_bytes(op, -1, &ob);
+    if (out_elems != ob / op->out_size) return fail(MS_ERR_BAD_ARG, "ms_variant_coverage: out_elems %" PRId64 " != %" PRId64, out_elems, ob / op->out_size);
+    memset(counts, 0, sizeof(int32_t) * (size_t)out_elems);
+    if (p->family == MS_FAM_GEMM_ALU || p->family == MS_FAM_GEMM_MFMA) {
+        int um = p->tile_unit[0], un = p->tile_unit[1];
+        for (int64_t b = 0; b < op->nb; ++b)
+            for (int64_t wg = 0; wg < p->grid[0]; ++wg) {
+                int64_t i0, j0;
+                if (p->reorder == 1) {
+                    j0 = wg / p->ti[0];
+                    i0 = wg % p->ti[0];
+                } else {
+                    i0 = wg / p->tj[0];
+                    j0 = wg % p->tj[0];
+                }
+                for (int64_t t = 0; t < (int64_t)p->ti[2] * p->tj[2]; ++t) { // thread or wavefront
+                    int64_t ti = t / p->tj[2], tj = t % p->tj[2];
+                    for (int64_t r1 = 0; r1 < p->ti[1]; ++r1)
+                        for (int64_t r3 = 0; r3 < p->ti[3]; ++r3)
+                            for (int64_t c1 = 0; c1 < p->tj[1]; ++c1)
+                                for (int64_t c3 = 0; c3 < p->tj[3]; ++c3) {
+                                    int64_t iu = split_index(p->ti, i0, r1, ti, r3);
+                                    int64_t ju = split_index(p->tj, j0, c1, tj, c3);
+                                    for (int a = 0; a < um; ++a)
+                                        for (int c = 0; c < un; ++c) {
+                                            int64_t i = iu * um + a, j = ju * un + c;
+                                            if (i >= op->M || j >= op->N) return fail(MS_ERR_INVALID_TRACE, "coverage: index out of range");
+                                            ++counts[(b * op->M + i) * op->N + j];
+                                        }
+                                }
+                }
+            }
+    } else {
+        const ms_op_desc &d = op->d;
+        int64_t C = d.dims[3];
+        for (int64_t n = 0; n < d.dims[0]; ++n)
+            for (int64_t wg = 0; wg < p->grid[0]; ++wg) {
+                int64_t c0 = wg % p->tc[0], j0 = wg / p->tc[0] % p->tj[0], i0 = wg / ((int64_t)p->tc[0] * p->tj[0]);
+                for (int64_t t = 0; t < p->threads; ++t) {
+                    int64_t tc = t % p->tc[2], tj = t / p->tc[2] % p->tj[2], ti = t / ((int64_t)p->tc[2] * p->tj[2]);
+                    for (int64_t r1 = 0; r1 < p->ti[1]; ++r1)
+                        for (int64_t r3 = 0; r3 < p->ti[3]; ++r3)
+                            for (int64_t q1 = 0; q1 < p->tj[1]; ++q1)
+                                for (int64_t q3 = 0; q3 < p->tj[3]; ++q3)
+                                    for (int64_t s1 = 0; s1 < p->tc[1]; ++s1)
+                                        for (int64_t s3 = 0; s3 < p->tc[3]; ++s3) {
+                                            int64_t oh = split_index(p->ti, i0, r1, ti, r3);
+                                            int64_t ow = split_index(p->tj, j0, q1, tj, q3);
+                                            int64_t c = split_index(p->tc, c0, s1, tc, s3);
+                                            if (oh >= op->OH || ow >= op->OW || c >= C) return fail(MS_ERR_INVALID_TRACE, "coverage: index out of range");
+                                            ++counts[((n * op->OH + oh) * op->OW + ow) * C + c];
+                                        }
+                }
+            }
+    }
+    return MS_OK;
+}

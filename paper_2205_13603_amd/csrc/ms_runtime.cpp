@@ -1,0 +1,229 @@
+// Variant handles, launch and measurement (the only part of libms that talks
+// to the GPU).
+#include "ms_internal.h"
+
+#include <hip/hip_runtime.h>
+
+#include <algorithm>
+#include <atomic>
+#include <cstring>
+#include <new>
+#include <thread>
+#include <vector>
+
+using namespace ms;
+
+struct ms_variant {
+    ms_op op;
+    ms_variant_params p;
+    KernelSpec spec;
+    std::vector<char> *code; // owned by the cache
+    hipModule_t mod;
+    hipFunction_t fn;
+    int device;              // device the module is loaded on, -1 = not loaded
+};
+
+#define HIP_TRY(call)                                                                               \
+    do {                                                                                            \
+        hipError_t e_ = (call);                                                                     \
+        if (e_ != hipSuccess) return fail(MS_ERR_HIP, "%s: %s", #call, hipGetErrorString(e_));      \
+    } while (0)
+
+extern "C" int32_t ms_variant_build(const ms_op *op, const ms_space *space, const ms_trace *trace, ms_variant **out)
+{
+    if (!op || !space || !trace || !out) return fail(MS_ERR_BAD_ARG, "ms_variant_build: NULL argument");
+    *out = nullptr;
+    ms_variant_params p;
+    int32_t rc = ms_trace_validate(op, space, trace, &p);
+    if (rc != MS_OK) return rc;
+    ms_variant *v = new (std::nothrow) ms_variant();
+    if (!v) return fail(MS_ERR_NOMEM, "ms_variant_build: out of memory");
+    v->op = *op;
+    v->p = p;
+    v->mod = nullptr;
+    v->fn = nullptr;
+    v->device = -1;
+    rc = make_kernel_spec(op, &p, &v->spec);
+    if (rc == MS_OK) rc = jit_get_code(v->spec, p.key, &v->code);
+    if (rc != MS_OK) {
+        delete v;
+        return rc;
+    }
+    *out = v;
+    return MS_OK;
+}
+
+extern "C" void ms_variant_destroy(ms_variant *v)
+{
+    if (!v) return;
+    if (v->mod) (void)hipModuleUnload(v->mod);
+    delete v;
+}
+
+extern "C" int32_t ms_variant_info(const ms_variant *v, ms_variant_params *params, size_t *workspace_bytes)
+{
+    if (!v) return fail(MS_ERR_BAD_ARG, "ms_variant_info: NULL variant");
+    if (params) *params = v->p;
+    if (workspace_bytes) *workspace_bytes = 0;
+    return MS_OK;
+}
+
+extern "C" int32_t ms_prebuild(const ms_op *op, const ms_space *space, const ms_trace *traces, int32_t n, int32_t threads,
+                               int32_t *n_built)
+{
+    if (!op || !space || (!traces && n > 0) || n < 0) return fail(MS_ERR_BAD_ARG, "ms_prebuild: bad argument");
+    threads = std::max(1, std::min(threads, 64));
+    std::atomic<int> next(0), built(0);
+    auto work = [&]() {
+        for (;;) {
+            int i = next.fetch_add(1);
+            if (i >= n) break;
+            ms_variant_params p;
+            if (ms_trace_validate(op, space, &traces[i], &p) != MS_OK) continue;
+            KernelSpec spec;
+            std::vector<char> *code;
+            if (make_kernel_spec(op, &p, &spec) == MS_OK && jit_get_code(spec, p.key, &code) == MS_OK) built.fetch_add(1);
+        }
+    };
+    std::vector<std::thread> pool;
+    for (int t = 1; t < threads; ++t) pool.emplace_back(work);
+    work();
+    for (auto &t : pool) t.join();
+    if (n_built) *n_built = built.load();
+    return MS_OK;
+}
+
+static int32_t ensure_loaded(ms_variant *v)
+{
+    int dev = 0;
+    HIP_TRY(hipGetDevice(&dev));
+    if (v->device == dev) return MS_OK;
+    if (v->mod) {
+        (void)hipModuleUnload(v->mod);
+        v->mod = nullptr;
+        v->device = -1;
+    }
+    hipDeviceProp_t prop;
+    HIP_TRY(hipGetDeviceProperties(&prop, dev));
+    if (strncmp(prop.gcnArchName, "gfx950", 6) != 0)
+        return fail(MS_ERR_UNSUPPORTED, "device %d is %s; kernels are built for gfx950 only", dev, prop.gcnArchName);
+    if ((size_t)v->p.lds_bytes > prop.sharedMemPerBlock)
+        return fail(MS_ERR_HIP, "variant needs %d bytes of LDS, the device offers %zu per workgroup", v->p.lds_bytes, (size_t)prop.sharedMemPerBlock);
+    HIP_TRY(hipModuleLoadData(&v->mod, v->code->data()));
+    HIP_TRY(hipModuleGetFunction(&v->fn, v->mod, v->spec.entry.c_str()));
+    v->device = dev;
+    return MS_OK;
+}
+
+extern "C" int32_t ms_variant_launch(ms_variant *v, const void *const *inputs, void *const *outputs, void *workspace,
+                                     int32_t instances, void *stream)
+{
+    (void)workspace;
+    if (!v || !inputs || !outputs) return fail(MS_ERR_BAD_ARG, "ms_variant_launch: NULL argument");
+    if (instances < 1) return fail(MS_ERR_BAD_ARG, "ms_variant_launch: instances = %d", instances);
+    if (!inputs[0] || !inputs[1] || !outputs[0]) return fail(MS_ERR_BAD_ARG, "ms_variant_launch: NULL tensor pointer");
+    uint64_t gz = (uint64_t)v->spec.grid[2] * (uint64_t)instances;
+    if (gz > 65535ull * 32768ull || (uint64_t)v->spec.grid[0] * gz > 0x7fffffffull)
+        return fail(MS_ERR_BAD_ARG, "ms_variant_launch: %d instances overflow the grid", instances);
+    int32_t rc = ensure_loaded(v);
+    if (rc != MS_OK) return rc;
+    const void *in0 = inputs[0], *in1 = inputs[1];
+    const void *in2 = nullptr;
+    if (v->op.d.kind == MS_OP_CONV2D_NHWC && v->op.d.has_bias) {
+        in2 = inputs[2];
+        if (!in2) return fail(MS_ERR_BAD_ARG, "ms_variant_launch: the op has a bias but inputs[2] is NULL");
+    }
+    void *o = outputs[0];
+    int32_t inst = instances;
+    void *args[] = {&in0, &in1, &in2, &o, &inst};
+    // grid z carries batch x instances; fold overflow beyond 65535 into y
+    unsigned gy = 1, gzz = (unsigned)gz;
+    if (gz > 65535) {
+        // kernels recover z = blockIdx.z * gridDim.y + blockIdx.y
+        gy = 32768;
+        while (gy > 1 && gz % gy) gy >>= 1;
+        gzz = (unsigned)(gz / gy);
+        if (gzz > 65535) return fail(MS_ERR_BAD_ARG, "ms_variant_launch: %d instances overflow the grid", instances);
+    }
+    HIP_TRY(hipModuleLaunchKernel(v->fn, v->spec.grid[0], gy, gzz, v->spec.block[0], 1, 1, v->spec.lds_dynamic,
+                                  (hipStream_t)stream, args, nullptr));
+    return MS_OK;
+}
+
+extern "C" int32_t ms_measure(ms_variant *v, const ms_bufset *sets, int32_t n_sets, const ms_measure_cfg *cfg, void *stream,
+                              ms_measure_result *out)
+{
+    if (!v || !sets || !cfg || !out || n_sets < 1) return fail(MS_ERR_BAD_ARG, "ms_measure: bad argument");
+    if (cfg->repeats < 1 || cfg->launches_per_repeat < 1 || cfg->warmup < 0 || cfg->instances < 1)
+        return fail(MS_ERR_BAD_ARG, "ms_measure: bad configuration");
+    memset(out, 0, sizeof *out);
+    hipStream_t s = (hipStream_t)stream;
+    hipEvent_t e0 = nullptr, e1 = nullptr;
+    HIP_TRY(hipEventCreate(&e0));
+    if (hipEventCreate(&e1) != hipSuccess) {
+        (void)hipEventDestroy(e0);
+        return fail(MS_ERR_HIP, "hipEventCreate failed");
+    }
+    int32_t rc = MS_OK;
+    std::vector<double> us;
+    int set = 0;
+    auto launch = [&]() -> int32_t {
+        const ms_bufset &b = sets[set];
+        set = (set + 1) % n_sets;
+        void *outs[1] = {b.output};
+        return ms_variant_launch(v, b.inputs, outs, b.workspace, cfg->instances, stream);
+    };
+    for (int i = 0; i < cfg->warmup && rc == MS_OK; ++i) rc = launch();
+    if (rc == MS_OK && hipStreamSynchronize(s) != hipSuccess) rc = fail(MS_ERR_HIP, "ms_measure: warm-up failed: %s", hipGetErrorString(hipGetLastError()));
+    for (int r = 0; r < cfg->repeats && rc == MS_OK; ++r) {
+        hipError_t e = hipEventRecord(e0, s);
+        for (int l = 0; l < cfg->launches_per_repeat && rc == MS_OK; ++l) rc = launch();
+        if (rc != MS_OK) break;
+        if (e == hipSuccess) e = hipEventRecord(e1, s);
+        if (e == hipSuccess) e = hipEventSynchronize(e1);
+        float ms_elapsed = 0;
+        if (e == hipSuccess) e = hipEventElapsedTime(&ms_elapsed, e0, e1);
+        if (e != hipSuccess) {
+            rc = fail(MS_ERR_HIP, "ms_measure: %s", hipGetErrorString(e));
+            break;
+        }
+        us.push_back((double)ms_elapsed * 1000.0 / cfg->launches_per_repeat);
+    }
+    (void)hipEventDestroy(e0);
+    (void)hipEventDestroy(e1);
+    if (rc != MS_OK) return rc;
+    std::sort(us.begin(), us.end());
+    out->n = (int32_t)us.size();
+    out->min_us = us.front();
+    out->median_us = us.size() % 2 ? us[us.size() / 2] : 0.5 * (us[us.size() / 2 - 1] + us[us.size() / 2]);
+    double sum = 0;
+    for (double x : us) sum += x;
+    out->mean_us = sum / us.size();
+    double f, b;
+    ms_op_work(&v->op, &f, &b);
+    out->flop = f * cfg->instances;
+    out->bytes = b * cfg->instances;
+    return MS_OK;
+}
+
+extern "C" int32_t ms_device_info_get(ms_device_info *out)
+{
+    if (!out) return fail(MS_ERR_BAD_ARG, "ms_device_info_get: NULL argument");
+    memset(out, 0, sizeof *out);
+    int dev = 0;
+    HIP_TRY(hipGetDevice(&dev));
+    hipDeviceProp_t prop;
+    HIP_TRY(hipGetDeviceProperties(&prop, dev));
+    snprintf(out->name, sizeof out->name, "%s", prop.name);
+    snprintf(out->arch, sizeof out->arch, "%s", prop.gcnArchName);
+    out->compute_units = prop.multiProcessorCount;
+    out->wave_size = prop.warpSize;
+    out->lds_bytes_per_block = (int32_t)prop.sharedMemPerBlock;
+    out->max_threads_per_block = prop.maxThreadsPerBlock;
+    out->clock_khz = prop.clockRate;
+    out->mem_clock_khz = prop.memoryClockRate;
+    out->mem_bus_bits = prop.memoryBusWidth;
+    out->l2_bytes = prop.l2CacheSize;
+    out->global_mem_bytes = (int64_t)prop.totalGlobalMem;
+    return MS_OK;
+}

@@ -1,0 +1,319 @@
+"""Host logic of libms (no GPU): symbols, op descriptors, space, sampler, mutation, text form,
+validator, interpreter coverage."""
+import ctypes as C
+import collections
+import math
+import os
+import re
+
+import numpy as np
+import pytest
+
+from oracle import oracle as O
+from paper_2205_13603_amd import binding as B
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def test_library_exports_every_declared_symbol():
+    hdr = open(os.path.join(ROOT, "include", "ms.h")).read()
+    hdr = re.sub(r"/\*.*?\*/", "", hdr, flags=re.S)
+    declared = set(re.findall(r"\b(ms_[a-z0-9_]+)\s*\(", hdr))
+    declared -= {n for n in declared if re.search(r"typedef[^;]*\(\s*\*\s*%s\s*\)" % n, hdr)}
+    assert declared, "no declarations found"
+    L = B.lib()
+    for name in sorted(declared):
+        assert hasattr(L, name), "libms.so does not export %s" % name
+    assert declared == set(B.SYMBOLS), (declared ^ set(B.SYMBOLS))
+    assert L.ms_version() == 1
+
+
+def test_struct_sizes_match_header():
+    # computed from the header's field lists (natural alignment)
+    assert C.sizeof(B.ms_decision) == 16 + 8 * B.MAX_FACTORS
+    assert C.sizeof(B.ms_trace) == 8 + B.MAX_SLOTS * C.sizeof(B.ms_decision)
+    assert C.sizeof(B.ms_op_desc) == 8 * 4 + 8 * 8 + 3 * 8 + 3 * 8
+    assert C.sizeof(B.ms_slot) == 8 + 16 + 8 + 8 + 8 * B.MAX_CANDS + 4 * B.MAX_CANDS + 8 + 8 * B.MAX_CANDS
+
+
+def test_op_loops_and_work():
+    op = B.gemm_op(128, 128, 128, "f32")
+    assert op.loops() == [("i", 128, False), ("j", 128, False), ("k", 128, True)]
+    assert op.work() == (4194304.0, 196608.0)
+    op = B.gemm_op(1024, 1024, 1024, "f16")
+    assert op.work() == (2147483648.0, 6291456.0)
+    op = B.conv2d_op(1, 56, 56, 64, 64, 3, 3, stride=1, pad=1)
+    assert op.loops() == [("i", 3136, False), ("j", 64, False), ("k", 576, True)]
+    f, b = op.work()
+    assert f == 231211008.0 and b == 401408 + 73728 + 256 + 401408
+    op = B.bmm_op(12, 128, 128, 64, True, "f16")
+    assert op.work() == (25165824.0, 786432.0)
+    d = op.desc()
+    assert list(d.a_strides) == [128 * 64, 64, 1] and list(d.b_strides) == [128 * 64, 1, 64]
+    op = B.bmm_op(12, 128, 64, 128, False, "f16")
+    assert op.work() == (25165824.0, 786432.0)
+    op = B.gemm_op(512, 512, 512, "i8")
+    assert op.work() == (268435456.0, 1572864.0)
+    op = B.dwconv2d_op(1, 112, 112, 32)
+    assert op.work() == (7225344.0, 3212416.0)
+    assert [l[0] for l in op.loops()] == ["n", "i", "j", "c", "kh", "kw"]
+    op = B.dwconv2d_op(1, 56, 56, 144, stride=2)
+    assert op.work() == (2032128.0, 2263104.0)
+    assert op.tensor_bytes(-1) == 28 * 28 * 144 * 4
+
+
+def test_op_errors_do_not_abort():
+    with pytest.raises(B.MsError) as e:
+        B.gemm_op(0, 4, 4)
+    assert e.value.code == B.MS_ERR_BAD_ARG
+    with pytest.raises(B.MsError) as e:
+        B.gemm_op(4, 4, 4, "i8", "f16")
+    assert e.value.code == B.MS_ERR_UNSUPPORTED
+    with pytest.raises(B.MsError) as e:
+        B.Op(17, "f32", "f32", [1, 1, 1])
+    assert e.value.code == B.MS_ERR_BAD_ARG
+    assert B.lib().ms_op_create(None, None) == B.MS_ERR_BAD_ARG
+    B.lib().ms_op_destroy(None)
+    B.lib().ms_variant_destroy(None)
+    with pytest.raises(B.MsError) as e:
+        B.conv2d_op(1, 8, 8, 4, 4, 3, 3, in_dtype="f32", out_dtype="f32").space()
+    assert e.value.code == B.MS_ERR_UNSUPPORTED
+
+
+def slot_names(sp):
+    return [sp.slots[i].name.decode() for i in range(sp.n_slots)]
+
+
+def test_space_composition_by_flags():
+    op = B.gemm_op(128, 128, 128, "f32")
+    assert slot_names(op.space(B.SPACE_UNROLL)) == ["i", "j", "k", "unroll"]
+    assert op.space(B.SPACE_UNROLL).family == B.FAM_GEMM_ALU
+    assert slot_names(op.space(0)) == ["i", "j", "k"]
+    sp = op.space()
+    assert slot_names(sp) == ["i", "j", "k", "unroll", "cache_read", "vectorize", "storage_align", "reorder"]
+    un = sp.slots[3]
+    assert [un.candidates[i] for i in range(un.n_candidates)] == [0, 16, 64]
+    op = B.gemm_op(1024, 1024, 1024, "f16")
+    sp = op.space()
+    assert sp.family == B.FAM_GEMM_MFMA and slot_names(sp)[0] == "tensorize"
+    t = sp.slots[0]
+    assert [t.candidates[i] for i in range(t.n_candidates)] == [161616, 323208, 161632, 323216]
+    assert sp.slots[1].depends_on == 0 and [sp.slots[1].extent_by_choice[c] for c in range(4)] == [64, 32, 64, 32]
+    assert [sp.slots[3].extent_by_choice[c] for c in range(4)] == [64, 128, 32, 64]
+    assert op.space(B.SPACE_DEFAULT & ~B.SPACE_TENSORIZE).family == B.FAM_GEMM_ALU
+    op = B.dwconv2d_op(1, 112, 112, 32)
+    assert slot_names(op.space()) == ["i", "j", "c", "unroll", "cache_read"]
+
+
+def test_space_size_matches_closed_form():
+    op = B.gemm_op(128, 128, 128, "f32")
+    assert abs(B.space_log10_size(op.space(B.SPACE_UNROLL)) - math.log10(120 ** 3 * 3)) < 1e-9
+
+
+@pytest.mark.parametrize("extent", [128, 56, 144, 3136, 12])
+def test_sampler_support_and_uniformity(extent):
+    """sample-perfect-tile: only members of the brute-force support, all of them reached, uniform."""
+    op = B.gemm_op(extent, 4, 4, "f32")
+    sp = op.space(0)
+    support = {tuple(t) for t in O.perfect_tiles(extent, 4).tolist()}
+    n = len(support)
+    draws = 60 * n
+    cnt = collections.Counter()
+    for idx in range(draws):
+        t = B.trace_sample(sp, 11, idx)
+        f = tuple(t.d[0].v[k] for k in range(4))
+        assert f in support
+        cnt[f] += 1
+    assert set(cnt) == support
+    exp = draws / n
+    chi2 = sum((c - exp) ** 2 / exp for c in cnt.values())
+    # chi-square with n-1 dof: mean n-1, sd sqrt(2(n-1)); 6 sigma
+    assert chi2 < (n - 1) + 6 * math.sqrt(2 * (n - 1)), (chi2, n)
+
+
+def test_sampler_is_deterministic_and_seed_dependent():
+    op = B.gemm_op(1024, 1024, 1024, "f16")
+    sp = op.space()
+    a = [B.trace_sample(sp, 5, i).decisions() for i in range(20)]
+    b = [B.trace_sample(sp, 5, i).decisions() for i in range(20)]
+    c = [B.trace_sample(sp, 6, i).decisions() for i in range(20)]
+    assert a == b and a != c and len({str(x) for x in a}) > 15
+
+
+def test_categorical_frequencies():
+    op = B.gemm_op(128, 128, 128, "f32")
+    sp = op.space(B.SPACE_UNROLL)
+    cnt = collections.Counter(B.trace_sample(sp, 3, i).d[3].v[0] for i in range(3000))
+    assert set(cnt) == {0, 1, 2} and all(abs(c - 1000) < 150 for c in cnt.values())
+
+
+def test_dependent_tile_extents_follow_the_tensorize_decision():
+    op = B.gemm_op(1024, 1024, 1024, "f16")
+    sp = op.space()
+    seen = set()
+    for i in range(200):
+        t = B.trace_sample(sp, 9, i)
+        code = sp.slots[0].candidates[t.d[0].v[0]]
+        m, n, k = code // 10000, code // 100 % 100, code % 100
+        seen.add(code)
+        assert math.prod(t.d[1].v[q] for q in range(4)) == 1024 // m
+        assert math.prod(t.d[2].v[q] for q in range(4)) == 1024 // n
+        assert math.prod(t.d[3].v[q] for q in range(4)) == 1024 // k
+    assert len(seen) == 4
+
+
+def test_mutation_changes_one_decision_and_keeps_products():
+    op = B.gemm_op(1024, 1024, 1024, "f16")
+    sp = op.space()
+    t = B.trace_sample(sp, 1, 0)
+    changed_slots = collections.Counter()
+    for s in range(400):
+        m = B.trace_mutate(sp, t, s)
+        a, b = t.decisions(), m.decisions()
+        diff = [i for i in range(len(a)) if a[i] != b[i]]
+        assert diff, "mutation returned the same trace"
+        if diff[0] == 0:  # tensorize changed: dependent tiles are redrawn for the new unit
+            assert set(diff) <= {0, 1, 2, 3}
+        else:
+            assert len(diff) == 1
+            i = diff[0]
+            if sp.slots[i].kind == B.SLOT_PERFECT_TILE:
+                assert math.prod(a[i][1]) == math.prod(b[i][1])
+                assert sum(1 for x, y in zip(a[i][1], b[i][1]) if x != y) == 2
+        changed_slots[diff[0]] += 1
+        code = sp.slots[0].candidates[m.d[0].v[0]]
+        for l, u in zip((1, 2, 3), (code // 10000, code // 100 % 100, code % 100)):
+            assert math.prod(m.d[l].v[q] for q in range(4)) * u == 1024
+    assert len(changed_slots) == sp.n_slots
+
+
+def test_text_round_trip():
+    for op in [B.gemm_op(128, 128, 128, "f32"), B.gemm_op(1024, 1024, 1024, "f16"), B.dwconv2d_op(1, 112, 112, 32)]:
+        sp = op.space()
+        for i in range(10):
+            t = B.trace_sample(sp, 2, i)
+            text = B.trace_to_text(op, sp, t)
+            assert text.count("sample-") == sp.n_slots
+            back = B.trace_from_text(sp, text)
+            assert back.decisions() == t.decisions()
+            assert bytes(back) == bytes(t)
+
+
+def test_text_worked_example_split():
+    """The split of Section 3.1's figure: loop of 1024 into extents 32, 8, 4 (here with a leading 1)."""
+    op = B.gemm_op(1024, 4, 4, "f32")
+    sp = op.space(0)
+    t = B.make_trace(sp, [[1, 32, 8, 4], [1, 1, 4, 1], [1, 1, 4, 1]])
+    p = B.trace_validate(op, sp, t)
+    assert list(p.ti) == [1, 32, 8, 4] and p.block_m == 1024 and p.threads == 8 * 4
+    text = B.trace_to_text(op, sp, t)
+    assert "split(loop=i, factors=[1, 32, 8, 4])" in text
+    cov = B.variant_coverage(op, p, 1024 * 4)
+    assert np.all(cov == 1)
+
+
+def test_text_errors():
+    op = B.gemm_op(128, 128, 128, "f32")
+    sp = op.space(B.SPACE_UNROLL)
+    t = B.trace_sample(sp, 0, 0)
+    text = B.trace_to_text(op, sp, t)
+    lines = text.splitlines()
+    trunc = "\n".join(l for l in lines if "slot=unroll" not in l)
+    with pytest.raises(B.MsError) as e:
+        B.trace_from_text(sp, trunc)
+    assert e.value.code == B.MS_ERR_INVALID_TRACE and "truncated" in str(e.value)
+    swapped = text.replace("slot=i,", "slot=q,")
+    with pytest.raises(B.MsError):
+        B.trace_from_text(sp, swapped)
+
+
+def test_validator_rejections():
+    op = B.gemm_op(128, 128, 128, "f32")
+    sp = op.space()
+
+    def mk(i, j, k, unroll=0, cache=1, vec=1, pad=0, reorder=0):
+        return B.make_trace(sp, [i, j, k, [unroll], [cache], [vec], [pad], [reorder]])
+
+    ok = mk([4, 2, 8, 2], [4, 2, 16, 1], [4, 4, 4, 2])
+    p = B.trace_validate(op, sp, ok)
+    assert p.threads == 128 and p.block_m == 32 and p.block_n == 32 and p.block_k == 32 and p.grid[0] == 16
+    assert p.lds_bytes == 4 * (32 * 32 + 32 * 32) and p.acc_per_thread == 8
+
+    def rejected(t, word):
+        with pytest.raises(B.MsError) as e:
+            B.trace_validate(op, sp, t)
+        assert e.value.code == B.MS_ERR_INVALID_TRACE and word in str(e.value), str(e.value)
+
+    rejected(mk([4, 2, 8, 4], [4, 2, 16, 1], [4, 4, 4, 2]), "multiply to")          # product != extent
+    rejected(mk([1, 1, 128, 1], [1, 1, 128, 1], [4, 4, 4, 2]), "threads per workgroup")  # 16384 threads
+    rejected(mk([1, 16, 1, 8], [1, 16, 1, 8], [128, 1, 1, 1]), "accumulators per lane")
+    rejected(mk([1, 2, 32, 2], [1, 2, 32, 2], [1, 1, 128, 1], cache=2), "LDS tile needs")  # 2*(128*128*2)*4 = 256 KiB
+    rejected(mk([4, 2, 8, 2], [4, 2, 16, 1], [4, 4, 4, 2], cache=0, pad=1), "nothing to pad")
+    bad = ok.copy()
+    bad.d[0].v[0] = 0
+    rejected(bad, "factor 0 is 0")
+    bad = ok.copy()
+    bad.d[3].v[0] = 7
+    rejected(bad, "outside")
+    bad = ok.copy()
+    bad.n = 5
+    rejected(bad, "truncated")
+    bad = ok.copy()
+    bad.d[1].slot_id = 99
+    rejected(bad, "slot id")
+    # vector width must divide the contiguous tile extent: BK = 2 with 4-wide loads
+    rejected(mk([4, 2, 8, 2], [4, 2, 16, 1], [64, 1, 1, 2], vec=4), "vector width")
+    # forced smaller hardware limits reject what passed before, and are restorable
+    lim = B.get_limits()
+    small = B.ms_limits(64, 4096, 16, 64, 2)
+    B.set_limits(small)
+    try:
+        rejected(ok, "threads per workgroup")
+    finally:
+        B.set_limits(lim)
+    B.trace_validate(op, sp, ok)
+
+
+def test_validator_mfma_rules():
+    op = B.gemm_op(1024, 1024, 1024, "f16")
+    sp = op.space()
+
+    def mk(mfma, i, j, k, unroll=0, cache=2, vec=8, pad=0, reorder=0):
+        return B.make_trace(sp, [[mfma], i, j, k, [unroll], [cache], [vec], [pad], [reorder]])
+
+    p = B.trace_validate(op, sp, mk(323216, [4, 2, 2, 2], [4, 2, 2, 2], [16, 1, 2, 2]))
+    assert (p.block_m, p.block_n, p.block_k) == (256, 256, 64) and p.waves == 4 and p.threads == 256
+    assert p.acc_per_thread == 256 and p.lds_bytes == 2 * (64 // 8) * (256 * 16 + 256 * 16)
+    with pytest.raises(B.MsError) as e:
+        B.trace_validate(op, sp, mk(323216, [1, 1, 32, 1], [32, 1, 1, 1], [16, 1, 2, 2]))
+    assert "wavefronts" in str(e.value)
+    with pytest.raises(B.MsError) as e:
+        B.trace_validate(op, sp, mk(323216, [2, 4, 1, 4], [2, 4, 1, 4], [16, 1, 2, 2]))
+    assert "accumulators" in str(e.value)
+    with pytest.raises(B.MsError) as e:  # i tile counted for 16-wide intrinsic but 32-wide chosen
+        B.trace_validate(op, sp, mk(323216, [4, 2, 2, 4], [4, 2, 2, 2], [16, 1, 2, 2]))
+    assert "multiply to" in str(e.value)
+
+
+CONFIG_OPS = [
+    lambda: B.gemm_op(128, 128, 128, "f32"),
+    lambda: B.gemm_op(256, 128, 64, "f16"),
+    lambda: B.bmm_op(3, 128, 128, 64, True, "f16"),
+    lambda: B.gemm_op(128, 64, 128, "i8"),
+    lambda: B.conv2d_op(1, 28, 28, 16, 32, 3, 3, stride=1, pad=1),
+    lambda: B.dwconv2d_op(1, 28, 28, 12),
+    lambda: B.dwconv2d_op(2, 14, 14, 18, stride=2),
+]
+
+
+@pytest.mark.parametrize("mk", CONFIG_OPS)
+def test_interpreter_covers_every_output_once(mk):
+    """The split/bind structure derived from any valid trace tiles the output exactly once."""
+    op = mk()
+    sp = op.space()
+    elems = op.tensor_bytes(-1) // {B.F32: 4, B.F16: 2, B.BF16: 2, B.I32: 4}[op.desc().out_dtype]
+    for idx in range(25):
+        t = B.trace_sample_valid(op, sp, 21, idx)
+        p = B.trace_validate(op, sp, t)
+        cov = B.variant_coverage(op, p, elems)
+        assert cov.min() == 1 and cov.max() == 1, t.decisions()
