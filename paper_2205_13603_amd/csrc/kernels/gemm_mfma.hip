@@ -1,0 +1,379 @@
+// GEMM / batched matmul / implicit-GEMM conv2d (+bias +ReLU) on the CDNA4
+// matrix cores, one kernel per decision trace.
+//
+// Schedule (Table 2 primitives of arXiv 2205.13603, applied in this order):
+//   tensorize the inner MI_M x MI_N x MI_K block of C += A.B onto one MFMA
+//           instruction; the loops i, j, k are from here on counted in tiles
+//   split   i -> I0,I1,I2,I3   j -> J0,J1,J2,J3   k -> K0,K1,K2,K3
+//   reorder i0 j0 | k0 | i2 j2 | k1 k2 k3 | i1 j1 i3 j3
+//   bind    fuse(i0,j0) -> blockIdx.x, fuse(i2,j2) -> wavefront of the workgroup
+//   cache-read A,B tiles of one k0 step into LDS (CACHE_READ 1: one buffer;
+//           2: two buffers, the next tile is fetched into registers while the
+//           current one is multiplied)
+//   storage-align: each LDS plane padded by LDS_PAD*16 bytes
+//   vectorize: global loads of VEC elements
+//   unroll  k1 by UNROLL_K1, k2 by UNROLL_K2; k3 and the wave's tile loops fully
+//
+// LDS layout of both operands: [k group][row][KP], KP = the k elements one
+// lane feeds to one MFMA.  A lane's fragment is then one 8- or 16-byte LDS
+// read, and the 16 or 32 lanes of a row group read consecutive addresses
+// (no bank conflict).  Operands whose contiguous dimension is not k (B of
+// C = A.B, the conv weights) are transposed in registers on the way in.
+#include "common.h"
+
+#define NWAVES (I2 * J2)
+#define LANE_GROUPS (64 / MI_M)
+#define KP (MI_K / LANE_GROUPS)
+
+constexpr int TM = I1 * I3;
+constexpr int TN = J1 * J3;
+constexpr int BM = I1 * I2 * I3 * MI_M;
+constexpr int BN = J1 * J2 * J3 * MI_N;
+constexpr int BK = K1 * K2 * K3 * MI_K;
+constexpr int KG = BK / KP;                       // k groups per tile
+constexpr int ES = sizeof(in_t);
+constexpr int FRAG_BYTES = KP * ES;               // 8 or 16
+constexpr int PLANE_A = BM * FRAG_BYTES + LDS_PAD * 16; // bytes of one k-group plane
+constexpr int PLANE_B = BN * FRAG_BYTES + LDS_PAD * 16;
+constexpr int STAGE_BYTES = KG * (PLANE_A + PLANE_B);
+constexpr int STAGES = CACHE_READ == 2 ? 2 : 1;
+constexpr int KSTEPS = K1 * K2 * K3;              // MFMA k steps per tile
+
+static_assert(MI_M == MI_N, "square intrinsics only");
+static_assert(FRAG_BYTES == 8 || FRAG_BYTES == 16, "fragment is 8 or 16 bytes");
+
+// ---- fragment and accumulator types, one MFMA
+typedef vec_t<in_t, KP> frag_t;
+#if MI_M == 16
+typedef acc_t accv_t __attribute__((ext_vector_type(4)));
+constexpr int ACC_N = 4;
+#else
+typedef acc_t accv_t __attribute__((ext_vector_type(16)));
+constexpr int ACC_N = 16;
+#endif
+
+typedef _Float16 h4_t __attribute__((ext_vector_type(4)));
+typedef _Float16 h8_t __attribute__((ext_vector_type(8)));
+typedef short s4_t __attribute__((ext_vector_type(4)));
+typedef __bf16 b8_t __attribute__((ext_vector_type(8)));
+typedef int i4_t __attribute__((ext_vector_type(4)));
+
+__device__ __forceinline__ accv_t mfma(const frag_t &a, const frag_t &b, accv_t c)
+{
+#if IN_DT == DT_F16
+#if MI_M == 16 && MI_K == 16
+    return __builtin_amdgcn_mfma_f32_16x16x16f16(*(const h4_t *)&a, *(const h4_t *)&b, c, 0, 0, 0);
+#elif MI_M == 32 && MI_K == 8
+    return __builtin_amdgcn_mfma_f32_32x32x8f16(*(const h4_t *)&a, *(const h4_t *)&b, c, 0, 0, 0);
+#elif MI_M == 16 && MI_K == 32
+    return __builtin_amdgcn_mfma_f32_16x16x32_f16(*(const h8_t *)&a, *(const h8_t *)&b, c, 0, 0, 0);
+#elif MI_M == 32 && MI_K == 16
+    return __builtin_amdgcn_mfma_f32_32x32x16_f16(*(const h8_t *)&a, *(const h8_t *)&b, c, 0, 0, 0);
+#else
+#error "no such fp16 intrinsic"
+#endif
+#elif IN_DT == DT_BF16
+#if MI_M == 16 && MI_K == 16
+    return __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(*(const s4_t *)&a, *(const s4_t *)&b, c, 0, 0, 0);
+#elif MI_M == 32 && MI_K == 8
+    return __builtin_amdgcn_mfma_f32_32x32x8bf16_1k(*(const s4_t *)&a, *(const s4_t *)&b, c, 0, 0, 0);
+#elif MI_M == 16 && MI_K == 32
+    return __builtin_amdgcn_mfma_f32_16x16x32_bf16(*(const b8_t *)&a, *(const b8_t *)&b, c, 0, 0, 0);
+#elif MI_M == 32 && MI_K == 16
+    return __builtin_amdgcn_mfma_f32_32x32x16_bf16(*(const b8_t *)&a, *(const b8_t *)&b, c, 0, 0, 0);
+#else
+#error "no such bf16 intrinsic"
+#endif
+#elif IN_DT == DT_I8
+#if MI_M == 16 && MI_K == 32
+    return __builtin_amdgcn_mfma_i32_16x16x32_i8(*(const long *)&a, *(const long *)&b, c, 0, 0, 0);
+#elif MI_M == 32 && MI_K == 16
+    return __builtin_amdgcn_mfma_i32_32x32x16_i8(*(const long *)&a, *(const long *)&b, c, 0, 0, 0);
+#elif MI_M == 16 && MI_K == 64
+    return __builtin_amdgcn_mfma_i32_16x16x64_i8(*(const i4_t *)&a, *(const i4_t *)&b, c, 0, 0, 0);
+#elif MI_M == 32 && MI_K == 32
+    return __builtin_amdgcn_mfma_i32_32x32x32_i8(*(const i4_t *)&a, *(const i4_t *)&b, c, 0, 0, 0);
+#else
+#error "no such int8 intrinsic"
+#endif
+#else
+#error "matrix-core kernels take fp16, bf16 or int8 inputs"
+#endif
+}
+
+// ---- global -> registers -> LDS staging of one operand tile
+//
+// K-contiguous operand (A; B of the NT form; conv activations): a thread
+// moves vectors of VEC elements along k; vector idx -> (row, kv), kv fastest.
+constexpr int VK = VEC;                 // elements per vector along k
+constexpr int KV = BK / VK;             // vectors per tile row
+constexpr int PARTS = VK > KP ? VK / KP : 1; // LDS writes per vector
+constexpr int PART_E = VK > KP ? KP : VK;    // elements per LDS write
+
+template <int ROWS> struct kmajor_stage {
+    static constexpr int TOTAL = ROWS * KV;
+    static constexpr int ITERS = (TOTAL + NTHREADS - 1) / NTHREADS;
+    vec_t<in_t, VK> r[ITERS];
+};
+
+#if IS_CONV
+// im2col on the fly: row = output pixel, k = (kh, kw, ci)
+__device__ __forceinline__ vec_t<in_t, VK> load_conv_a(const in_t *__restrict__ X, int row, int k)
+{
+    const int ow = row % CV_OW, oh = (row / CV_OW) % CV_OH, n = row / (CV_OW * CV_OH);
+    const int ci = k % CV_CIN, kw = (k / CV_CIN) % CV_KW, kh = k / (CV_CIN * CV_KW);
+    const int ih = oh * CV_STRIDE + kh - CV_PAD, iw = ow * CV_STRIDE + kw - CV_PAD;
+    vec_t<in_t, VK> x;
+    if (ih >= 0 && ih < CV_H && iw >= 0 && iw < CV_W) {
+        x = *reinterpret_cast<const vec_t<in_t, VK> *>(X + (((long)n * CV_H + ih) * CV_W + iw) * CV_CIN + ci);
+    } else {
+#pragma unroll
+        for (int q = 0; q < VK; ++q) x.v[q] = 0;
+    }
+    return x;
+}
+#endif
+
+template <int ROWS, bool CONV_A>
+__device__ __forceinline__ void kmajor_load(kmajor_stage<ROWS> &st, const in_t *__restrict__ src, long row0, long k0e, long row_stride,
+                                            int tid)
+{
+    typedef kmajor_stage<ROWS> S;
+#pragma unroll
+    for (int it = 0; it < S::ITERS; ++it) {
+        const int idx = it * NTHREADS + tid;
+        if (S::TOTAL % NTHREADS == 0 || idx < S::TOTAL) {
+            const int row = idx / KV, kv = idx % KV;
+#if IS_CONV
+            if (CONV_A) {
+                st.r[it] = load_conv_a(src, (int)row0 + row, (int)k0e + kv * VK);
+                continue;
+            }
+#endif
+            st.r[it] = *reinterpret_cast<const vec_t<in_t, VK> *>(src + (row0 + row) * row_stride + k0e + kv * VK);
+        }
+    }
+}
+
+template <int ROWS, int PLANE>
+__device__ __forceinline__ void kmajor_store(const kmajor_stage<ROWS> &st, char *__restrict__ lds, int tid)
+{
+    typedef kmajor_stage<ROWS> S;
+#pragma unroll
+    for (int it = 0; it < S::ITERS; ++it) {
+        const int idx = it * NTHREADS + tid;
+        if (S::TOTAL % NTHREADS == 0 || idx < S::TOTAL) {
+            const int row = idx / KV, kv = idx % KV;
+            const int k = kv * VK;
+#pragma unroll
+            for (int p = 0; p < PARTS; ++p) {
+                const int kk = k + p * PART_E;
+                char *dst = lds + (kk / KP) * PLANE + row * FRAG_BYTES + (kk % KP) * ES;
+                vec_t<in_t, PART_E> part;
+#pragma unroll
+                for (int q = 0; q < PART_E; ++q) part.v[q] = st.r[it].v[p * PART_E + q];
+                *reinterpret_cast<vec_t<in_t, PART_E> *>(dst) = part;
+            }
+        }
+    }
+}
+
+// J-contiguous operand (B of the NN form, conv weights): a thread moves a
+// block of KP k-rows x VEC columns and transposes it in registers, so that it
+// lands in LDS as VEC consecutive fragments.
+constexpr int VJ = VEC;
+constexpr int JV = BN / VJ;
+
+struct jmajor_stage {
+    static constexpr int TOTAL = KG * JV;
+    static constexpr int ITERS = (TOTAL + NTHREADS - 1) / NTHREADS;
+    vec_t<in_t, VJ> r[ITERS][KP];
+};
+
+__device__ __forceinline__ void jmajor_load(jmajor_stage &st, const in_t *__restrict__ src, long col0, long k0e, long k_stride, int tid)
+{
+    typedef jmajor_stage S;
+#pragma unroll
+    for (int it = 0; it < S::ITERS; ++it) {
+        const int idx = it * NTHREADS + tid;
+        if (S::TOTAL % NTHREADS == 0 || idx < S::TOTAL) {
+            const int kg = idx / JV, jv = idx % JV;
+#pragma unroll
+            for (int q = 0; q < KP; ++q)
+                st.r[it][q] = *reinterpret_cast<const vec_t<in_t, VJ> *>(src + (k0e + kg * KP + q) * k_stride + col0 + jv * VJ);
+        }
+    }
+}
+
+__device__ __forceinline__ void jmajor_store(const jmajor_stage &st, char *__restrict__ lds, int tid)
+{
+    typedef jmajor_stage S;
+#pragma unroll
+    for (int it = 0; it < S::ITERS; ++it) {
+        const int idx = it * NTHREADS + tid;
+        if (S::TOTAL % NTHREADS == 0 || idx < S::TOTAL) {
+            const int kg = idx / JV, jv = idx % JV;
+            char *dst = lds + kg * PLANE_B + jv * VJ * FRAG_BYTES;
+#pragma unroll
+            for (int c = 0; c < VJ; ++c) {
+                frag_t f;
+#pragma unroll
+                for (int q = 0; q < KP; ++q) f.v[q] = st.r[it][q].v[c];
+                *reinterpret_cast<frag_t *>(dst + c * FRAG_BYTES) = f;
+            }
+        }
+    }
+}
+
+#define B_KMAJOR (!IS_CONV && SB_K == 1 && SB_J != 1)
+
+struct tile_stage {
+    kmajor_stage<BM> a;
+#if B_KMAJOR
+    kmajor_stage<BN> b;
+#else
+    jmajor_stage b;
+#endif
+};
+
+__device__ __forceinline__ void stage_load(tile_stage &st, const in_t *__restrict__ A, const in_t *__restrict__ B, int i0, int j0, int k0,
+                                           int tid)
+{
+    const long k0e = (long)k0 * BK;
+    kmajor_load<BM, true>(st.a, A, (long)i0 * BM, k0e, SA_I, tid);
+#if B_KMAJOR
+    kmajor_load<BN, false>(st.b, B, (long)j0 * BN, k0e, SB_J, tid);
+#else
+    jmajor_load(st.b, B, (long)j0 * BN, k0e, SB_K, tid);
+#endif
+}
+
+__device__ __forceinline__ void stage_store(const tile_stage &st, char *__restrict__ lds, int tid)
+{
+    kmajor_store<BM, PLANE_A>(st.a, lds, tid);
+#if B_KMAJOR
+    kmajor_store<BN, PLANE_B>(st.b, lds + KG * PLANE_A, tid);
+#else
+    jmajor_store(st.b, lds + KG * PLANE_A, tid);
+#endif
+}
+
+extern "C" __global__ void __launch_bounds__(NTHREADS)
+ms_kernel(const void *__restrict__ a_, const void *__restrict__ b_, const void *__restrict__ bias_, void *__restrict__ c_, int instances)
+{
+    const int z = blockIdx.z * gridDim.y + blockIdx.y;
+    const int inst = z / DIM_B, bb = z % DIM_B;
+    if (inst >= instances) return;
+    const in_t *__restrict__ A = (const in_t *)a_ + (long)inst * A_INST + (long)bb * SA_B;
+    const in_t *__restrict__ B = (const in_t *)b_ + (long)inst * B_INST + (long)bb * SB_B;
+    out_t *__restrict__ C = (out_t *)c_ + ((long)inst * DIM_B + bb) * ((long)DIM_M * DIM_N);
+
+    int i0, j0;
+    block_to_tile(blockIdx.x, i0, j0);
+    const int tid = threadIdx.x;
+    const int lane = tid % 64, wave = tid / 64;
+    const int wi = wave / J2, wj = wave % J2;
+    const int lrow = lane % MI_M, lgrp = lane / MI_M;
+
+    __shared__ __attribute__((aligned(16))) char lds[STAGES * STAGE_BYTES];
+
+    accv_t acc[TM][TN];
+#pragma unroll
+    for (int tm = 0; tm < TM; ++tm)
+#pragma unroll
+        for (int tn = 0; tn < TN; ++tn)
+#pragma unroll
+            for (int e = 0; e < ACC_N; ++e) acc[tm][tn][e] = 0;
+
+    tile_stage st;
+    int stage = 0;
+#if CACHE_READ == 2
+    stage_load(st, A, B, i0, j0, 0, tid);
+    stage_store(st, lds, tid);
+    __syncthreads();
+#endif
+
+#pragma unroll 1
+    for (int k0 = 0; k0 < K0; ++k0) {
+#if CACHE_READ == 1
+        stage_load(st, A, B, i0, j0, k0, tid);
+        stage_store(st, lds, tid);
+        __syncthreads();
+#else
+        if (k0 + 1 < K0) stage_load(st, A, B, i0, j0, k0 + 1, tid);
+#endif
+        const char *la = lds + stage * STAGE_BYTES + lgrp * PLANE_A + lrow * FRAG_BYTES;
+        const char *lb = lds + stage * STAGE_BYTES + KG * PLANE_A + lgrp * PLANE_B + lrow * FRAG_BYTES;
+#pragma unroll UNROLL_K1
+        for (int k1 = 0; k1 < K1; ++k1) {
+#pragma unroll UNROLL_K2
+            for (int k2 = 0; k2 < K2; ++k2) {
+                const int s0 = (k1 * K2 + k2) * K3;
+                frag_t fa[K3][TM], fb[K3][TN];
+#pragma unroll
+                for (int q = 0; q < K3; ++q) {
+#pragma unroll
+                    for (int r1 = 0; r1 < I1; ++r1)
+#pragma unroll
+                        for (int r3 = 0; r3 < I3; ++r3) {
+                            const int trow = (r1 * I2 + wi) * I3 + r3;
+                            fa[q][r1 * I3 + r3] =
+                                *reinterpret_cast<const frag_t *>(la + (s0 + q) * LANE_GROUPS * PLANE_A + trow * MI_M * FRAG_BYTES);
+                        }
+#pragma unroll
+                    for (int c1 = 0; c1 < J1; ++c1)
+#pragma unroll
+                        for (int c3 = 0; c3 < J3; ++c3) {
+                            const int tcol = (c1 * J2 + wj) * J3 + c3;
+                            fb[q][c1 * J3 + c3] =
+                                *reinterpret_cast<const frag_t *>(lb + (s0 + q) * LANE_GROUPS * PLANE_B + tcol * MI_N * FRAG_BYTES);
+                        }
+                }
+#pragma unroll
+                for (int q = 0; q < K3; ++q)
+#pragma unroll
+                    for (int tm = 0; tm < TM; ++tm)
+#pragma unroll
+                        for (int tn = 0; tn < TN; ++tn) acc[tm][tn] = mfma(fa[q][tm], fb[q][tn], acc[tm][tn]);
+            }
+        }
+#if CACHE_READ == 1
+        __syncthreads();
+#else
+        if (k0 + 1 < K0) stage_store(st, lds + (stage ^ 1) * STAGE_BYTES, tid);
+        __syncthreads();
+        stage ^= 1;
+#endif
+    }
+
+    // epilogue: (+bias, ReLU,) one rounding to the output type.
+    // accumulator element e of a lane: 16x16 -> row 4*lgrp + e; 32x32 -> row 8*(e/4) + 4*lgrp + e%4; column = lrow
+#pragma unroll
+    for (int r1 = 0; r1 < I1; ++r1)
+#pragma unroll
+        for (int r3 = 0; r3 < I3; ++r3)
+#pragma unroll
+            for (int c1 = 0; c1 < J1; ++c1)
+#pragma unroll
+                for (int c3 = 0; c3 < J3; ++c3) {
+                    const int trow = (r1 * I2 + wi) * I3 + r3, tcol = (c1 * J2 + wj) * J3 + c3;
+                    const long col = (long)j0 * BN + tcol * MI_N + lrow;
+#if HAS_BIAS
+                    const float bias = ((const float *)bias_)[col];
+#endif
+#pragma unroll
+                    for (int e = 0; e < ACC_N; ++e) {
+                        const int rr = MI_M == 16 ? 4 * lgrp + e : 8 * (e / 4) + 4 * lgrp + e % 4;
+                        const long row = (long)i0 * BM + trow * MI_M + rr;
+                        acc_t x = acc[r1 * I3 + r3][c1 * J3 + c3][e];
+#if HAS_BIAS
+                        x += bias;
+#endif
+#if RELU
+                        x = x > 0 ? x : 0;
+#endif
+                        C[row * DIM_N + col] = from_acc(x);
+                    }
+                }
+    (void)bias_;
+}

@@ -201,7 +201,11 @@ extern "C" int32_t ms_trace_validate(const ms_op *op, const ms_space *space, con
             lds = (int64_t)p.cache_read * (bk / kp) * (rowsA + rowsB);
             // fragment operands of one k step for the whole wave tile live in registers too
             int64_t frag = ((int64_t)p.ti[1] * p.ti[3] + (int64_t)p.tj[1] * p.tj[3]) * p.tk[3] * (kp * es / 4 > 0 ? kp * es / 4 : 1);
-            if (frag + acc > 448) return reject("%" PRId64 " fragment + %" PRId64 " accumulator registers per lane exceed the register file", frag, acc);
+            // registers that carry a tile from global memory to LDS; with two buffers they are live across the k step
+            int64_t stage = (bm * bk * es / 4 + p.threads - 1) / p.threads + (bn * bk * es / 4 + p.threads - 1) / p.threads;
+            int64_t live = p.cache_read == 2 ? frag + stage : std::max(frag, stage);
+            if (live + acc > 480)
+                return reject("%" PRId64 " fragment + %" PRId64 " staging + %" PRId64 " accumulator registers per lane exceed the register file", frag, stage, acc);
         } else if (p.cache_read) {
             int stages = p.cache_read;
             lds = (int64_t)stages * 4 * (bm * (bk + p.lds_pad * 4) + bk * (bn + p.lds_pad * 4));

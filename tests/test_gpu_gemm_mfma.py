@@ -1,0 +1,142 @@
+"""GPU parity of the matrix-core GEMM/BMM kernel family against the CPU oracle (configs C2, C4a, C4b, C4c)."""
+import numpy as np
+import pytest
+
+from oracle import compare, oracle as O
+from paper_2205_13603_amd import binding as B, inputs as I
+from gpu_util import run_variant
+
+pytestmark = pytest.mark.gpu
+
+F16_INTRINS = [161616, 323208, 161632, 323216]
+I8_INTRINS = [161632, 323216, 161664, 323232]
+
+
+def traces_covering_intrinsics(op, space, seed, per_intrin, intrins):
+    """Valid traces from the seeded sampler, `per_intrin` for each tensorize candidate."""
+    want = {c: per_intrin for c in intrins}
+    out, idx = [], 0
+    while any(want.values()) and idx < 5000:
+        t = B.trace_sample_valid(op, space, seed, idx)
+        idx += 1
+        code = space.slots[0].candidates[t.d[0].v[0]]
+        if want.get(code, 0) > 0:
+            want[code] -= 1
+            out.append(t)
+    assert not any(want.values()), want
+    return out
+
+
+@pytest.mark.parametrize("dtype", ["f16", "bf16"])
+def test_small_gemm_all_intrinsics(dtype):
+    M, N, K = 192, 160, 224  # several tiles, factors of 3, 5, 7 in the tile counts
+    A, Bm = I.gemm_inputs(M, N, K, dtype, 1, "normal", 1.0)
+    ref = O.gemm(A, Bm, bf16=(dtype == "bf16"))
+    op = B.gemm_op(M, N, K, dtype)
+    space = op.space()
+    assert space.family == B.FAM_GEMM_MFMA
+    for n, t in enumerate(traces_covering_intrinsics(op, space, 3, 4, F16_INTRINS)):
+        print("trace", n, t.decisions(), flush=True)
+        got = run_variant(op, space, t, [A, Bm], dtype, (M, N))
+        if got is None:
+            continue
+        compare.assert_float_close(got, ref, compare.RTOL_HALF, "%s trace %d" % (dtype, n))
+
+
+def test_small_gemm_exact_on_small_ints_fp32_out_instances():
+    """Integer-valued fp16 inputs: every partial sum is exact in fp32, so any trace must equal the oracle
+    bit for bit; 2 instances; fp32 output."""
+    M, N, K = 128, 96, 160
+    A, Bm = I.gemm_inputs(M, N, K, "f16", 2, "ints")
+    ref = O.gemm(A, Bm)
+    op = B.gemm_op(M, N, K, "f16", "f32")
+    space = op.space()
+    for n, t in enumerate(traces_covering_intrinsics(op, space, 4, 3, F16_INTRINS)):
+        print("trace", n, t.decisions(), flush=True)
+        got = run_variant(op, space, t, [A, Bm], "f32", (M, N), instances=2)
+        if got is None:
+            continue
+        assert np.array_equal(got[0], ref) and np.array_equal(got[1], ref), "trace %d" % n
+
+
+def test_c2_fp16_gemm_1024():
+    """Config C2: fp16 GEMM 1024^3, fp32 accumulate, inputs 0.1*N(0,1)."""
+    A, Bm = I.c2(seed=0)
+    op = B.gemm_op(1024, 1024, 1024, "f16")
+    space = op.space()
+    traces = traces_covering_intrinsics(op, space, 0, 3, F16_INTRINS)
+
+    def mk(mfma, i, j, k, unroll=0, cache=2, vec=8, pad=0, reorder=0):
+        return B.make_trace(space, [[mfma], i, j, k, [unroll], [cache], [vec], [pad], [reorder]])
+
+    traces.append(mk(323216, [4, 2, 2, 2], [4, 2, 2, 2], [16, 1, 2, 2], unroll=16, pad=1, reorder=2))
+    traces.append(mk(161632, [8, 2, 2, 2], [8, 1, 2, 4], [8, 2, 2, 1], unroll=64, cache=1, vec=4))
+    ref = None
+    for n, t in enumerate(traces):
+        print("trace", n, t.decisions(), flush=True)
+        got = run_variant(op, space, t, [A, Bm], "f16", (1024, 1024))
+        if got is None:
+            continue
+        if ref is None:
+            ref = O.gemm(A, Bm)
+        compare.assert_float_close(got, ref, compare.RTOL_HALF, "C2 trace %d" % n)
+
+
+def test_c4a_c4b_attention_bmm():
+    """Config C4a/b: 12 heads, S = Q.K^T (reduction index contiguous in both) and O = P.V."""
+    Q, Kk = I.c4a(seed=0)
+    P, V = I.c4b(seed=0)
+    for name, trans_b, X, Y, shape in [("c4a", True, Q, Kk, (12, 128, 128)), ("c4b", False, P, V, (12, 128, 64))]:
+        ref = O.bmm(X, Y, trans_b=trans_b)
+        op = B.bmm_op(12, shape[1], shape[2], X.shape[2], trans_b, "f16")
+        space = op.space()
+        for n, t in enumerate(traces_covering_intrinsics(op, space, 5, 3, F16_INTRINS)):
+            print(name, "trace", n, t.decisions(), flush=True)
+            got = run_variant(op, space, t, [X, Y], "f16", shape)
+            if got is None:
+                continue
+            compare.assert_float_close(got, ref, compare.RTOL_HALF, "%s trace %d" % (name, n))
+
+
+def test_c4a_fused_transpose_layout():
+    """TBG (Appendix A.2): Q stored [seq][head][dim]; the transpose is folded into the strides of A."""
+    heads, seq, dim = 12, 128, 64
+    Q, Kk = I.c4a(seed=1)
+    Qs = np.ascontiguousarray(Q.transpose(1, 0, 2))  # [seq][head][dim]
+    ref = O.bmm(Qs.transpose(1, 0, 2), Kk, trans_b=True)
+    op = B.bmm_op(heads, seq, seq, dim, True, "f16", a_strides=[dim, heads * dim, 1])
+    space = op.space()
+    for n in range(4):
+        t = B.trace_sample_valid(op, space, 6, n)
+        print("trace", n, t.decisions(), flush=True)
+        got = run_variant(op, space, t, [Qs, Kk], "f16", (heads, seq, seq))
+        if got is None:
+            continue
+        compare.assert_float_close(got, ref, compare.RTOL_HALF, "TBG layout trace %d" % n)
+
+
+def test_c4c_int8_gemm_512_bit_exact():
+    """Config C4c: int8 x int8 -> int32, 512^3, values uniform in [-128,127]; bit exact."""
+    A, Bm = I.c4c(seed=0)
+    ref = O.gemm(A, Bm)
+    op = B.gemm_op(512, 512, 512, "i8")
+    space = op.space()
+    for n, t in enumerate(traces_covering_intrinsics(op, space, 7, 3, I8_INTRINS)):
+        print("trace", n, t.decisions(), flush=True)
+        got = run_variant(op, space, t, [A, Bm], "i32", (512, 512))
+        if got is None:
+            continue
+        compare.assert_int_equal(got, ref, "C4c trace %d" % n)
+
+
+def test_int8_extremes():
+    A = np.full((64, 512), -128, np.int8)
+    Bm = np.full((512, 64), -128, np.int8)
+    op = B.gemm_op(64, 64, 512, "i8")
+    space = op.space()
+    for n in range(4):
+        t = B.trace_sample_valid(op, space, 8, n)
+        got = run_variant(op, space, t, [A, Bm], "i32", (64, 64))
+        if got is None:
+            continue
+        assert np.all(got == 8388608)
