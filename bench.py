@@ -1,0 +1,231 @@
+#!/usr/bin/env python3
+"""Benchmark of the hot path on one MI355X.
+
+One "step" = one launch of the best variant found for the workload over a batch of R independent
+instances of the workload's shape (per-instance tiling exactly as the trace says), inputs resident
+in HBM.  Before the timed region the hot path up to that point runs untimed: the operator is
+defined, the space described, candidates (stored tuning records plus a fresh seeded search of
+--trials measured candidates) are validated, compiled and measured, and the fastest is kept.
+
+Prints ONE JSON line (see the keys below).  `value` is the throughput of the K timed steps.
+Also reported, labelled: single-launch and steady-state latency at the workload's own shape
+(one instance per launch), which are bounded by dispatch latency rather than by the kernel.
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+import numpy as np  # noqa: E402
+
+METRIC = "best-variant TFLOP/s per operator (% of MFMA/HBM roofline); trials to reach it"
+
+# published MI355X peaks: dense MFMA TFLOP/s (TOP/s) by input type, fp32 vector TFLOP/s, HBM GB/s
+PEAK_MFMA = {"f16": 2500.0, "bf16": 2500.0, "i8": 5000.0}
+PEAK_FP32_VECTOR = 157.3
+PEAK_HBM_GBS = 8000.0
+
+
+def workload_inputs(name, seed):
+    from paper_2205_13603_amd import inputs as I
+    return {
+        "c1_gemm_f32_128": lambda: list(I.c1(seed)),
+        "c2_gemm_f16_1024": lambda: list(I.c2(seed)),
+        "c3_conv_f16_56x56x64": lambda: list(I.c3(seed)),
+        "c4a_bmm_nt_f16": lambda: list(I.c4a(seed)),
+        "c4b_bmm_nn_f16": lambda: list(I.c4b(seed)),
+        "c4c_gemm_i8_512": lambda: list(I.c4c(seed)),
+        "c5a_dw_f32_112x112x32": lambda: list(I.c5a(seed)),
+        "c5b_dw_f32_56x56x144": lambda: list(I.c5b(seed)),
+    }[name]()
+
+
+def oracle_run(name, ins):
+    from oracle import oracle as O
+    if name in ("c1_gemm_f32_128", "c2_gemm_f16_1024", "c4c_gemm_i8_512"):
+        return O.gemm(ins[0], ins[1])
+    if name == "c4a_bmm_nt_f16":
+        return O.bmm(ins[0], ins[1], trans_b=True)
+    if name == "c4b_bmm_nn_f16":
+        return O.bmm(ins[0], ins[1])
+    if name == "c3_conv_f16_56x56x64":
+        return O.conv2d_nhwc(ins[0], ins[1], bias=ins[2], relu=True, stride=1, pad=1)
+    if name == "c5a_dw_f32_112x112x32":
+        return O.dwconv2d_nhwc(ins[0], ins[1], stride=1, pad=1)
+    if name == "c5b_dw_f32_56x56x144":
+        return O.dwconv2d_nhwc(ins[0], ins[1], stride=2, pad=1)
+    raise KeyError(name)
+
+
+OUT_SHAPE = {
+    "c1_gemm_f32_128": ((128, 128), "f32"), "c2_gemm_f16_1024": ((1024, 1024), "f16"),
+    "c3_conv_f16_56x56x64": ((1, 56, 56, 64), "f16"), "c4a_bmm_nt_f16": ((12, 128, 128), "f16"),
+    "c4b_bmm_nn_f16": ((12, 128, 64), "f16"), "c4c_gemm_i8_512": ((512, 512), "i32"),
+    "c5a_dw_f32_112x112x32": ((1, 112, 112, 32), "f32"), "c5b_dw_f32_56x56x144": ((1, 28, 28, 144), "f32"),
+}
+BOUND = {  # which roofline bounds the workload (AI vs ridge), and the in-dtype
+    "c1_gemm_f32_128": ("alu", "f32"), "c2_gemm_f16_1024": ("mfma", "f16"), "c3_conv_f16_56x56x64": ("mfma", "f16"),
+    "c4a_bmm_nt_f16": ("hbm", "f16"), "c4b_bmm_nn_f16": ("hbm", "f16"), "c4c_gemm_i8_512": ("hbm", "i8"),
+    "c5a_dw_f32_112x112x32": ("hbm", "f32"), "c5b_dw_f32_56x56x144": ("hbm", "f32"),
+}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=50)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--workload", default="c2_gemm_f16_1024")
+    ap.add_argument("--instances", type=int, default=0, help="instances per launch (0 = the workload's default)")
+    ap.add_argument("--trials", type=int, default=16, help="measured candidates of the fresh search")
+    ap.add_argument("--seed", type=int, default=0)
+    ap.add_argument("--no-records", action="store_true", help="ignore stored tuning records")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--trace-file", default="", help="time exactly this trace (text form) instead of searching")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on one GPU; --gpus %d is not supported (every figure is single-GPU)" % args.gpus,
+              file=sys.stderr)
+        return 2
+
+    import torch
+    from paper_2205_13603_amd import binding as B, devmem, tuned
+    from oracle import compare
+
+    devmem.require_gpu()
+    name = args.workload
+    mk, default_r = tuned.WORKLOADS[name]
+    R = args.instances or default_r
+    op = mk()
+    space = op.space()
+    flop1, bytes1 = op.work()
+    stream = devmem.current_stream()
+
+    # ---- inputs: R instances resident in HBM (4 distinct seeds, tiled), one output per instance
+    base = [workload_inputs(name, args.seed + s) for s in range(min(4, R))]
+    dev_in = []
+    for k in range(len(base[0])):
+        parts = [devmem.to_device(b[k]) for b in base]
+        reps = (R + len(parts) - 1) // len(parts)
+        dev_in.append(torch.stack(parts * reps)[:R].contiguous())
+    shape, odt = OUT_SHAPE[name]
+    dev_out = devmem.empty_output(shape, odt, R, poison=True)
+    in_ptrs = [t.data_ptr() for t in dev_in]
+    full_set = [(in_ptrs, dev_out.data_ptr())]
+    # one buffer set per instance, for the single-instance protocols (rotating over > last-level-cache bytes)
+    inst_sets = [([t[r].data_ptr() for t in dev_in], dev_out[r].data_ptr()) for r in range(R)]
+
+    # ---- candidates: stored records + fresh search, all measured now in the timed configuration
+    t_search0 = time.time()
+    mcfg = dict(warmup=1, repeats=3, launches_per_repeat=3, instances=R)
+    best = (None, float("inf"), "none")
+    search_info = {"trials": 0, "trials_to_best": None, "invalid": 0, "failed": 0, "duplicate": 0}
+
+    def consider(trace, origin):
+        nonlocal best
+        try:
+            v = B.Variant(op, space, trace)
+            us = v.measure(full_set, stream=stream, **mcfg).median_us
+        except B.MsError as e:
+            print("candidate from %s failed: %s" % (origin, str(e)[:200]), file=sys.stderr)
+            return
+        if us < best[1]:
+            best = (trace, us, origin)
+
+    if args.trace_file:
+        consider(B.trace_from_text(space, open(args.trace_file).read()), "file")
+    else:
+        if not args.no_records:
+            for t in tuned.record_traces(name, op, space):
+                consider(t, "record")
+        if args.trials > 0:
+            cfg = B.search_cfg_default()
+            cfg.seed, cfg.trials = args.seed, args.trials
+            cfg.init_population = min(cfg.init_population, max(1, args.trials // 2))
+            cfg.measure = B.ms_measure_cfg(**mcfg)
+            res = B.search(op, space, cfg, bufsets=full_set, stream=stream)
+            search_info = {"trials": res.n_measured, "trials_to_best": res.best_trial, "invalid": res.n_invalid,
+                           "failed": res.n_failed, "duplicate": res.n_duplicate}
+            if res.best_us < best[1]:
+                best = (res.best_trace, res.best_us, "search")
+    if best[0] is None:
+        print("bench.py: no candidate could be measured", file=sys.stderr)
+        return 1
+    search_seconds = time.time() - t_search0
+    trace = best[0]
+    v = B.Variant(op, space, trace)
+    params = v.params()
+
+    # ---- correctness of the variant about to be timed: sampled instances against the oracle
+    dev_out.fill_({"bf16": 0x7FC0, "i32": -123456789}.get(odt, float("nan")))
+    v.launch(in_ptrs, dev_out.data_ptr(), instances=R, stream=stream)
+    got = devmem.to_host(dev_out, odt)
+    t_or = time.time()
+    refs = [oracle_run(name, b) for b in base]
+    oracle_seconds = (time.time() - t_or) / len(base)
+    for r in sorted({0, 1 % R, R // 2, R - 1}):
+        ref = refs[r % len(base)]
+        if odt == "i32":
+            compare.assert_int_equal(got[r], ref, "instance %d" % r)
+        else:
+            compare.assert_float_close(got[r], ref, compare.RTOL_F32 if odt == "f32" and BOUND[name][1] == "f32" else compare.RTOL_HALF,
+                                       "instance %d" % r)
+
+    # ---- timed region: W warm-up steps, then exactly K steps between synchronisations
+    for _ in range(args.warmup):
+        v.launch(in_ptrs, dev_out.data_ptr(), instances=R, stream=stream)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    res = v.measure(full_set, warmup=0, repeats=1, launches_per_repeat=args.steps, instances=R, stream=stream)
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t0
+    kernel_us = res.mean_us  # HIP events around the K launches on the launch stream / K
+    ms_per_step = wall * 1e3 / args.steps
+
+    bound, in_dt = BOUND[name]
+    if bound == "hbm":
+        unit, work = "GB/s", bytes1 * R / 1e9
+        peak = PEAK_HBM_GBS
+    else:
+        unit, work = "TFLOP/s", flop1 * R / 1e12
+        peak = PEAK_MFMA[in_dt] if bound == "mfma" else PEAK_FP32_VECTOR
+    value = work * args.steps / wall
+    achieved = work / (kernel_us * 1e-6)
+
+    # ---- single-instance protocols at the workload's own shape
+    l1 = v.measure(inst_sets[:1], warmup=5, repeats=100, launches_per_repeat=1, instances=1, stream=stream)
+    l2 = v.measure(inst_sets, warmup=5, repeats=5, launches_per_repeat=max(200, R), instances=1, stream=stream)
+    per1 = (bytes1 / 1e9) if bound == "hbm" else (flop1 / 1e12)
+
+    out = {
+        "metric": METRIC, "value": value, "unit": unit, "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": in_dt, "data": "synthetic",
+        "config": {"workload": "%s x %d instances per launch (device-filling batch; per-instance tiling as traced)" % (name, R),
+                   "instances": R, "best_from": best[2], "search": search_info, "search_seconds": round(search_seconds, 1),
+                   "variant": {"mfma": params.mfma, "block": [params.block_m, params.block_n, params.block_k],
+                               "waves": params.waves, "lds_bytes": params.lds_bytes, "cache_read": params.cache_read,
+                               "vec": params.vec, "reorder": params.reorder, "lds_pad": params.lds_pad,
+                               "ti": list(params.ti), "tj": list(params.tj), "tk": list(params.tk), "tc": list(params.tc),
+                               "unroll": params.unroll}},
+        "roofline": {"bound": bound, "achieved": achieved, "peak": peak, "unit": unit, "frac": achieved / peak,
+                     "traffic": None, "kernel_us": kernel_us},
+        "single_instance": {"single_launch_us": l1.median_us, "steady_state_us": l2.median_us,
+                            "steady_state_" + ("gbs" if bound == "hbm" else "tflops"): per1 / (l2.median_us * 1e-6),
+                            "rotating_sets": R},
+    }
+    if not args.no_cpu_baseline:
+        from oracle import oracle as O
+        out["cpu_baseline"] = {"value": per1 / oracle_seconds, "unit": unit, "cores": O.threads(), "kind": "oracle",
+                               "sample": "one full instance of the workload, mean of %d runs (%.2f s each)" % (len(base), oracle_seconds)}
+    print(json.dumps(out))
+    return 0
+
+
+if __name__ == "__main__":
+    sys.exit(main())

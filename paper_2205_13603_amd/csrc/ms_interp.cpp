@@ -258,15 +258,19 @@ extern "C" int32_t ms_trace_validate(const ms_op *op, const ms_space *space, con
         if (threads > L.max_threads) return reject("%" PRId64 " threads per workgroup, the limit is %d", threads, L.max_threads);
         p.threads = (int32_t)threads;
         p.waves = (p.threads + L.wave_size - 1) / L.wave_size;
-        int64_t acc = (int64_t)p.ti[1] * p.ti[3] * p.tj[1] * p.tj[3] * p.tc[1] * p.tc[3];
-        if (acc > std::min(L.max_acc_per_thread, 128)) return reject("%" PRId64 " outputs per thread exceed the register budget", acc);
+        // registers of one thread: the I3 x J3 output patch, its input patch and the taps, VC channels each
+        int vc = p.tc[3] % 4 == 0 ? 4 : (p.tc[3] % 2 == 0 ? 2 : 1);
+        int64_t patch_h = (int64_t)(p.ti[3] - 1) * d.stride + d.dims[4], patch_w = (int64_t)(p.tj[3] - 1) * d.stride + d.dims[5];
+        int64_t acc = (int64_t)p.ti[3] * p.tj[3] * vc;
+        int64_t regs = acc + (patch_h * patch_w + d.dims[4] * d.dims[5]) * vc;
+        if (regs > L.max_acc_per_thread) return reject("%" PRId64 " registers for the output and input patch exceed the register budget %d", regs, L.max_acc_per_thread);
         p.acc_per_thread = (int32_t)acc;
         int64_t g = (int64_t)p.ti[0] * p.tj[0] * p.tc[0];
         if (g > 0x7fffffff / std::max<int64_t>(1, d.dims[0])) return reject("grid of %" PRId64 " workgroups overflows", g);
         p.grid[0] = (int32_t)g;
         p.grid[1] = 1;
         p.grid[2] = (int32_t)d.dims[0];
-        p.vec = p.tc[3];
+        p.vec = vc;
         if (p.cache_read) {
             int64_t ih = (boh - 1) * d.stride + d.dims[4], iw = (bow - 1) * d.stride + d.dims[5];
             int64_t lds = ih * iw * bc * 4;

@@ -1,0 +1,64 @@
+"""Tuning records: the best traces earlier searches found, kept as text next to the package (one file per
+workload, the linearised trace of Section 4 plus the measured latency), and the workload table shared by
+bench.py and the tuning command.  Records are only candidates: they are re-measured before use."""
+import json
+import os
+
+from . import binding as B
+
+HERE = os.path.dirname(os.path.abspath(__file__))
+RECORD_DIR = os.path.join(HERE, "tuned_records")
+
+# name -> (op factory, instances of one device-filling launch)
+WORKLOADS = {
+    "c1_gemm_f32_128": (lambda: B.gemm_op(128, 128, 128, "f32"), 4096),
+    "c2_gemm_f16_1024": (lambda: B.gemm_op(1024, 1024, 1024, "f16"), 64),
+    "c3_conv_f16_56x56x64": (lambda: B.conv2d_op(1, 56, 56, 64, 64, 3, 3, stride=1, pad=1), 512),
+    "c4a_bmm_nt_f16": (lambda: B.bmm_op(12, 128, 128, 64, True, "f16"), 1024),
+    "c4b_bmm_nn_f16": (lambda: B.bmm_op(12, 128, 64, 128, False, "f16"), 1024),
+    "c4c_gemm_i8_512": (lambda: B.gemm_op(512, 512, 512, "i8"), 512),
+    "c5a_dw_f32_112x112x32": (lambda: B.dwconv2d_op(1, 112, 112, 32, stride=1, pad=1), 512),
+    "c5b_dw_f32_56x56x144": (lambda: B.dwconv2d_op(1, 56, 56, 144, stride=2, pad=1), 512),
+}
+
+
+def record_path(name):
+    return os.path.join(RECORD_DIR, name + ".jsonl")
+
+
+def load_records(name):
+    """List of dicts {trace: text, us: float, mode: str, ...}, best first."""
+    path = record_path(name)
+    if not os.path.exists(path):
+        return []
+    recs = [json.loads(line) for line in open(path) if line.strip()]
+    return sorted(recs, key=lambda r: r.get("us", 1e30))
+
+
+def append_record(name, rec):
+    os.makedirs(RECORD_DIR, exist_ok=True)
+    with open(record_path(name), "a") as f:
+        f.write(json.dumps(rec, sort_keys=True) + "\n")
+
+
+def record_traces(name, op, space, limit=4):
+    out = []
+    for rec in load_records(name)[:limit]:
+        try:
+            t = B.trace_from_text(space, rec["trace"])
+            B.trace_validate(op, space, t)
+            out.append(t)
+        except B.MsError:
+            continue
+    return out
+
+
+def precompile_all(threads=4):
+    n = 0
+    for name, (mk, _) in WORKLOADS.items():
+        op = mk()
+        space = op.space()
+        traces = record_traces(name, op, space)
+        if traces:
+            n += B.prebuild(op, space, traces, threads)
+    return n

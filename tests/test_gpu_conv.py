@@ -1,0 +1,51 @@
+"""GPU parity of implicit-GEMM conv2d + bias + ReLU (config C3) against the CPU oracle."""
+import numpy as np
+import pytest
+
+from oracle import compare, oracle as O
+from paper_2205_13603_amd import binding as B, inputs as I
+from gpu_util import run_variant
+from test_gpu_gemm_mfma import traces_covering_intrinsics, F16_INTRINS
+
+pytestmark = pytest.mark.gpu
+
+
+def test_c3_conv_bias_relu():
+    """Config C3: 1x56x56x64 -> 64, 3x3 s1 p1, bias + ReLU, fp16 in/out, fp32 accumulate."""
+    X, W, bias = I.c3(seed=0)
+    ref = O.conv2d_nhwc(X, W, bias=bias, relu=True, stride=1, pad=1)
+    assert (ref == 0).mean() > 0.05, "ReLU must be active on part of the output"
+    op = B.conv2d_op(1, 56, 56, 64, 64, 3, 3, stride=1, pad=1)
+    space = op.space()
+    for n, t in enumerate(traces_covering_intrinsics(op, space, 0, 4, F16_INTRINS)):
+        print("trace", n, t.decisions(), flush=True)
+        got = run_variant(op, space, t, [X, W, bias], "f16", (1, 56, 56, 64))
+        if got is None:
+            continue
+        compare.assert_float_close(got, ref, compare.RTOL_HALF, "C3 trace %d" % n)
+
+
+@pytest.mark.parametrize("stride,pad,k,relu,has_bias", [(2, 1, 3, True, True), (1, 0, 1, False, False), (2, 3, 7, True, True),
+                                                       (1, 2, 5, False, True)])
+def test_conv_other_geometries_exact(stride, pad, k, relu, has_bias):
+    """Strides, paddings and kernel sizes beyond C3; batch 2; 2 instances; integer-valued inputs make
+    the fp32 accumulation exact, so the fp32 output must equal the oracle exactly."""
+    N, H, W_, Cin, Cout = 2, 17, 16, 16, 32
+    g = I.rng(11)
+    X = I.small_ints(g, (N, H, W_, Cin), -2, 2, "f16")
+    Wt = I.small_ints(g, (k, k, Cin, Cout), -2, 2, "f16")
+    bias = g.integers(-3, 4, size=Cout).astype(np.float32) if has_bias else None
+    ref = O.conv2d_nhwc(X, Wt, bias=bias, relu=relu, stride=stride, pad=pad)
+    OH, OW = ref.shape[1], ref.shape[2]
+    if (N * OH * OW) % 16:
+        pytest.skip("M = %d output pixels is not a multiple of the 16-row intrinsic" % (N * OH * OW))
+    op = B.conv2d_op(N, H, W_, Cin, Cout, k, k, stride=stride, pad=pad, has_bias=has_bias, relu=relu, out_dtype="f32")
+    space = op.space()
+    ins = [X, Wt] + ([bias] if has_bias else [])
+    for n in range(6):
+        t = B.trace_sample_valid(op, space, 12, n)
+        print("trace", n, t.decisions(), flush=True)
+        got = run_variant(op, space, t, ins, "f32", (N, OH, OW, Cout), instances=2)
+        if got is None:
+            continue
+        assert np.array_equal(got[0], ref) and np.array_equal(got[1], ref), "trace %d" % n

@@ -1,0 +1,82 @@
+"""Search (Section 4, Eq. 1) on a synthetic latency injected through the test hook: no compiler, no GPU."""
+import math
+
+import pytest
+
+from paper_2205_13603_amd import binding as B
+
+
+def synthetic_latency(p):
+    """Analytic stand-in for f: minimum 1.0 at block 64x64x32, 256 threads, double-buffered LDS, 4-wide loads."""
+    f = 1.0
+    f += abs(math.log2(p.block_m / 64.0)) + abs(math.log2(p.block_n / 64.0)) + 0.5 * abs(math.log2(p.block_k / 32.0))
+    f += 0.5 * abs(math.log2(p.threads / 256.0))
+    f += 0.3 * (2 - p.cache_read) + 0.1 * (4 - p.vec)
+    return f
+
+
+def run(seed, trials=256):
+    op = B.gemm_op(128, 128, 128, "f32")
+    sp = op.space()
+    cfg = B.search_cfg_default()
+    cfg.seed, cfg.trials = seed, trials
+    log = []
+    res = B.search(op, sp, cfg, fake_latency=synthetic_latency,
+                   on_trial=lambda t: log.append((t.index, t.status, t.us, t.best_us, bytes(t.trace))) and 0)
+    return op, sp, res, log
+
+
+def test_search_finds_known_optimum_within_budget():
+    op, sp, res, log = run(seed=0)
+    assert res.n_measured == 256
+    assert abs(res.best_us - 1.0) < 1e-12, res.best_us
+    p = B.trace_validate(op, sp, res.best_trace)
+    assert (p.block_m, p.block_n, p.block_k, p.threads, p.cache_read, p.vec) == (64, 64, 32, 256, 2, 4)
+    assert 1 <= res.best_trial <= 256
+    assert log[res.best_trial - 1][2] <= res.best_us * 1.01
+    assert all(l[2] > res.best_us * 1.01 for l in log[:res.best_trial - 1] if l[1] == 0)
+    # best-so-far is monotone, trial indices count measured candidates only
+    bests = [l[3] for l in log if l[1] == 0]
+    assert all(a >= b for a, b in zip(bests, bests[1:]))
+    assert [l[0] for l in log if l[1] == 0] == list(range(1, 257))
+    assert res.n_invalid > 0  # the sampler is not conservative: the validator does the rejecting
+
+
+def test_search_beats_random_sampling():
+    op, sp, res, _ = run(seed=1, trials=128)
+    best_random = min(synthetic_latency(B.trace_validate(op, sp, B.trace_sample_valid(op, sp, 1, i))) for i in range(128))
+    assert res.best_us < best_random
+
+
+def test_search_same_seed_same_trials():
+    _, _, r1, l1 = run(seed=3, trials=96)
+    _, _, r2, l2 = run(seed=3, trials=96)
+    _, _, r3, l3 = run(seed=4, trials=96)
+    assert l1 == l2 and bytes(r1.best_trace) == bytes(r2.best_trace)
+    assert l1 != l3
+
+
+def test_failed_candidates_are_skipped_not_counted():
+    op = B.gemm_op(128, 128, 128, "f32")
+    sp = op.space()
+    cfg = B.search_cfg_default()
+    cfg.seed, cfg.trials = 5, 64
+
+    def flaky(p):
+        return -1.0 if p.threads % 3 == 0 or p.threads < 8 else synthetic_latency(p)
+
+    res = B.search(op, sp, cfg, fake_latency=flaky)
+    assert res.n_measured == 64 and res.n_failed > 0 and res.best_us > 0
+
+
+def test_search_bad_config():
+    op = B.gemm_op(128, 128, 128, "f32")
+    sp = op.space()
+    cfg = B.search_cfg_default()
+    cfg.trials = 0
+    with pytest.raises(B.MsError) as e:
+        B.search(op, sp, cfg, fake_latency=synthetic_latency)
+    assert e.value.code == B.MS_ERR_BAD_ARG
+    cfg = B.search_cfg_default()
+    with pytest.raises(B.MsError):  # measuring needs buffers
+        B.search(op, sp, cfg)
