@@ -445,6 +445,25 @@ typedef struct ms_device_info {
 /* Properties of the current HIP device.  MS_ERR_HIP if there is none. */
 int32_t ms_device_info_get(ms_device_info *out);
 
+/*
+ * Attainable peaks of the current device, measured: they ground the roofline
+ * fractions next to the published ones (Section 5 reports measured latency
+ * only; the roofline is this build's yardstick).
+ * ms_calibrate_mfma: register-resident issue loop of one matrix-core
+ * intrinsic (in_dtype F16/BF16/I8, MS_MFMA_CODE) on every SIMD; *tflops =
+ * 2*m*n*k operations per instruction times instructions per second / 1e12.
+ * operands: NULL (small-integer operands), or a device pointer to 8 KiB of
+ * values of in_dtype from which every lane takes its two fragments (the
+ * attainable rate depends on the operand values through power management).
+ * scratch: device pointer to at least 4 KiB (never written in practice).
+ * ms_calibrate_stream: mode 1 copies `bytes` from src to dst, mode 2 only
+ * reads src; bytes must be a multiple of 4096; device pointers, 16-byte
+ * aligned; *gbs = bytes moved (copy: read + written) per second / 1e9.
+ * Both synchronise `stream`.
+ */
+int32_t ms_calibrate_mfma(int32_t in_dtype, int32_t mfma_code, const void *operands, void *scratch, void *stream, double *tflops);
+int32_t ms_calibrate_stream(int32_t mode, const void *src, void *dst, size_t bytes, void *stream, double *gbs);
+
 int32_t ms_version(void);
 const char *ms_last_error(void);
 

@@ -164,6 +164,8 @@ SYMBOLS = {
     "ms_search": (C.c_int32, [C.c_void_p, _P(ms_space), _P(ms_search_cfg), _P(ms_bufset), C.c_int32, C.c_void_p,
                               LATENCY_FN, C.c_void_p, TRIAL_CB, C.c_void_p, _P(ms_search_result)]),
     "ms_device_info_get": (C.c_int32, [_P(ms_device_info)]),
+    "ms_calibrate_mfma": (C.c_int32, [C.c_int32, C.c_int32, C.c_void_p, C.c_void_p, C.c_void_p, _P(C.c_double)]),
+    "ms_calibrate_stream": (C.c_int32, [C.c_int32, C.c_void_p, C.c_void_p, C.c_size_t, C.c_void_p, _P(C.c_double)]),
     "ms_version": (C.c_int32, []),
     "ms_last_error": (C.c_char_p, []),
 }
@@ -395,6 +397,18 @@ def device_info():
     info = ms_device_info()
     _check(lib().ms_device_info_get(C.byref(info)))
     return info
+
+
+def calibrate_mfma(in_dtype, mfma_code, scratch_ptr, operands_ptr=None, stream=None):
+    v = C.c_double()
+    _check(lib().ms_calibrate_mfma(DTYPE_NAMES.get(in_dtype, in_dtype), mfma_code, operands_ptr, scratch_ptr, stream, C.byref(v)))
+    return v.value
+
+
+def calibrate_stream(mode, src_ptr, dst_ptr, nbytes, stream=None):
+    v = C.c_double()
+    _check(lib().ms_calibrate_stream(mode, src_ptr, dst_ptr, nbytes, stream, C.byref(v)))
+    return v.value
 
 
 def search_cfg_default():

@@ -1,0 +1,112 @@
+// Calibration kernels: what the device attains on a register-resident MFMA issue loop and on a
+// streaming copy.  These ground the roofline percentages; they are not part of any operator.
+//   MODE 0: each wave issues ITERS x 8 independent MFMAs on register operands
+//   MODE 1: copy `n16` 16-byte words src -> dst, grid-stride
+//   MODE 2: read `n16` 16-byte words (sum folded into a value that is stored only if it hits a sentinel)
+#define IN_DT CAL_DT
+#define OUT_DT 0
+#define I0 1
+#define J0 1
+#define REORDER 0
+#include "common.h"
+
+#if MODE == 0
+#define LANE_GROUPS (64 / MI_M)
+#define KP (MI_K / LANE_GROUPS)
+typedef vec_t<in_t, KP> frag_t;
+#if MI_M == 16
+typedef acc_t accv_t __attribute__((ext_vector_type(4)));
+#else
+typedef acc_t accv_t __attribute__((ext_vector_type(16)));
+#endif
+typedef _Float16 h4_t __attribute__((ext_vector_type(4)));
+typedef _Float16 h8_t __attribute__((ext_vector_type(8)));
+typedef short s4_t __attribute__((ext_vector_type(4)));
+typedef __bf16 b8_t __attribute__((ext_vector_type(8)));
+typedef int i4_t __attribute__((ext_vector_type(4)));
+
+__device__ __forceinline__ accv_t mfma(const frag_t &a, const frag_t &b, accv_t c)
+{
+#if IN_DT == DT_F16
+#if MI_M == 16 && MI_K == 16
+    return __builtin_amdgcn_mfma_f32_16x16x16f16(*(const h4_t *)&a, *(const h4_t *)&b, c, 0, 0, 0);
+#elif MI_M == 32 && MI_K == 8
+    return __builtin_amdgcn_mfma_f32_32x32x8f16(*(const h4_t *)&a, *(const h4_t *)&b, c, 0, 0, 0);
+#elif MI_M == 16 && MI_K == 32
+    return __builtin_amdgcn_mfma_f32_16x16x32_f16(*(const h8_t *)&a, *(const h8_t *)&b, c, 0, 0, 0);
+#else
+    return __builtin_amdgcn_mfma_f32_32x32x16_f16(*(const h8_t *)&a, *(const h8_t *)&b, c, 0, 0, 0);
+#endif
+#elif IN_DT == DT_BF16
+#if MI_M == 16 && MI_K == 16
+    return __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(*(const s4_t *)&a, *(const s4_t *)&b, c, 0, 0, 0);
+#elif MI_M == 32 && MI_K == 8
+    return __builtin_amdgcn_mfma_f32_32x32x8bf16_1k(*(const s4_t *)&a, *(const s4_t *)&b, c, 0, 0, 0);
+#elif MI_M == 16 && MI_K == 32
+    return __builtin_amdgcn_mfma_f32_16x16x32_bf16(*(const b8_t *)&a, *(const b8_t *)&b, c, 0, 0, 0);
+#else
+    return __builtin_amdgcn_mfma_f32_32x32x16_bf16(*(const b8_t *)&a, *(const b8_t *)&b, c, 0, 0, 0);
+#endif
+#else
+#if MI_M == 16 && MI_K == 32
+    return __builtin_amdgcn_mfma_i32_16x16x32_i8(*(const long *)&a, *(const long *)&b, c, 0, 0, 0);
+#elif MI_M == 32 && MI_K == 16
+    return __builtin_amdgcn_mfma_i32_32x32x16_i8(*(const long *)&a, *(const long *)&b, c, 0, 0, 0);
+#elif MI_M == 16 && MI_K == 64
+    return __builtin_amdgcn_mfma_i32_16x16x64_i8(*(const i4_t *)&a, *(const i4_t *)&b, c, 0, 0, 0);
+#else
+    return __builtin_amdgcn_mfma_i32_32x32x32_i8(*(const i4_t *)&a, *(const i4_t *)&b, c, 0, 0, 0);
+#endif
+#endif
+}
+
+extern "C" __global__ void __launch_bounds__(256) ms_kernel(const void *src, const void *, const void *, void *dst, int iters)
+{
+    // operands: taken from `src` when given (2 fragments per lane; realistic values make the matrix
+    // cores draw realistic power, which the clock governor reacts to), else small integers
+    frag_t a, b;
+    if (src != nullptr) {
+        a = ((const frag_t *)src)[threadIdx.x];
+        b = ((const frag_t *)src)[256 + threadIdx.x];
+    } else {
+#pragma unroll
+        for (int q = 0; q < KP; ++q) {
+            a.v[q] = (in_t)((threadIdx.x + q) & 3);
+            b.v[q] = (in_t)((threadIdx.x * 3 + q) & 1);
+        }
+    }
+    accv_t acc[8];
+#pragma unroll
+    for (int t = 0; t < 8; ++t)
+#pragma unroll
+        for (int e = 0; e < (MI_M == 16 ? 4 : 16); ++e) acc[t][e] = 0;
+#pragma unroll 1
+    for (int it = 0; it < iters; ++it) {
+#pragma unroll
+        for (int t = 0; t < 8; ++t) acc[t] = mfma(a, b, acc[t]);
+    }
+    acc_t s = 0;
+#pragma unroll
+    for (int t = 0; t < 8; ++t) s += acc[t][0];
+    if (s == (acc_t)-12345) ((acc_t *)dst)[threadIdx.x] = s; // never true: keeps the loop alive
+}
+#else
+typedef vec_t<float, 4> w16_t;
+extern "C" __global__ void __launch_bounds__(256) ms_kernel(const void *src, const void *, const void *, void *dst, int n16_lo)
+{
+    const long n16 = (long)(unsigned)n16_lo * 256; // the host passes the word count / 256
+    const long stride = (long)gridDim.x * blockDim.x;
+    const w16_t *s = (const w16_t *)src;
+    w16_t *d = (w16_t *)dst;
+#if MODE == 1
+    for (long i = (long)blockIdx.x * blockDim.x + threadIdx.x; i < n16; i += stride) d[i] = s[i];
+#else
+    float acc = 0.f;
+    for (long i = (long)blockIdx.x * blockDim.x + threadIdx.x; i < n16; i += stride) {
+        w16_t x = s[i];
+        acc += x.v[0] + x.v[1] + x.v[2] + x.v[3];
+    }
+    if (acc == -12345.678f) d[threadIdx.x].v[0] = acc;
+#endif
+}
+#endif

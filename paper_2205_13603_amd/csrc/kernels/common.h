@@ -61,22 +61,32 @@ __device__ __forceinline__ out_t from_acc(acc_t x)
 #endif
 }
 
-// Workgroup id -> (i0, j0) of the two outer spatial loops.
-// REORDER 0: i outer.  1: j outer.  2: i outer, but ids are first permuted so
-// that the workgroups one XCD receives (ids congruent mod 8) are neighbours in
-// tile order and share operand panels in that XCD's L2.
-__device__ __forceinline__ void block_to_tile(int wg, int &i0, int &j0)
+// Workgroup -> (z, i0, j0): z = instance * batch + batch index, (i0, j0) = the two outer spatial loops.
+// REORDER 0: i outer.  1: j outer.  2: i outer, after a permutation of the launch-wide workgroup
+// id that undoes the round-robin of workgroups over the 8 XCDs: the hardware sends workgroup f
+// (x fastest, then y, z) to XCD f mod 8, so id (f mod 8) * (total / 8) + f / 8 makes the workgroups
+// one XCD receives consecutive in (z, i0, j0) order; tiles that share operand panels, and whole
+// instances, then sit behind one L2.
+__device__ __forceinline__ void block_to_tile(int &z, int &i0, int &j0)
 {
     constexpr int G = I0 * J0;
+    int wg = blockIdx.x;
+    z = blockIdx.z * gridDim.y + blockIdx.y;
+#if REORDER == 2
+    const int nz = gridDim.y * gridDim.z;
+    const long total = (long)G * nz;
+    if (total % 8 == 0) {
+        const long f = wg + (long)G * z;
+        const long g = (f % 8) * (total / 8) + f / 8;
+        wg = (int)(g % G);
+        z = (int)(g / G);
+    }
+#endif
 #if REORDER == 1
     j0 = wg / I0;
     i0 = wg % I0;
 #else
-#if REORDER == 2
-    if (G % 8 == 0) wg = (wg % 8) * (G / 8) + wg / 8;
-#endif
     i0 = wg / J0;
     j0 = wg % J0;
 #endif
-    (void)G;
 }

@@ -71,15 +71,14 @@ extern "C" __global__ void __launch_bounds__(NTHREADS)
 ms_kernel(const void *__restrict__ a_, const void *__restrict__ b_, const void *__restrict__ unused_, void *__restrict__ c_, int instances)
 {
     (void)unused_;
-    const int z = blockIdx.z * gridDim.y + blockIdx.y;
+    int z, i0, j0;
+    block_to_tile(z, i0, j0);
     const int inst = z / DIM_B, bb = z % DIM_B;
     if (inst >= instances) return;
     const in_t *__restrict__ A = (const in_t *)a_ + (long)inst * A_INST + (long)bb * SA_B;
     const in_t *__restrict__ B = (const in_t *)b_ + (long)inst * B_INST + (long)bb * SB_B;
     out_t *__restrict__ C = (out_t *)c_ + ((long)inst * DIM_B + bb) * ((long)DIM_M * DIM_N);
 
-    int i0, j0;
-    block_to_tile(blockIdx.x, i0, j0);
     const int tid = threadIdx.x;
     const int ti = tid / J2, tj = tid % J2;
 

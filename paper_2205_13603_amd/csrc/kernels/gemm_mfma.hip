@@ -12,7 +12,10 @@
 //           current one is multiplied)
 //   storage-align: each LDS plane padded by LDS_PAD*16 bytes
 //   vectorize: global loads of VEC elements
-//   unroll  k1 by UNROLL_K1, k2 by UNROLL_K2; k3 and the wave's tile loops fully
+//   unroll  k1 by UNROLL_K1, k2 by UNROLL_K2; k3 and the wave's tile loops fully.  When the
+//           budget unrolls k1 and k2 completely the k step becomes a software pipeline: each of
+//           its K1*K2 slots issues the next slot's LDS reads and a share of the next tile's global
+//           loads ahead of its own MFMAs
 //
 // LDS layout of both operands: [k group][row][KP], KP = the k elements one
 // lane feeds to one MFMA.  A lane's fragment is then one 8- or 16-byte LDS
@@ -134,13 +137,16 @@ __device__ __forceinline__ vec_t<in_t, VK> load_conv_a(const in_t *__restrict__ 
 }
 #endif
 
+// Loads are numbered ("units") so that a caller can issue any sub-range [u0, u1) of a tile's loads:
+// the software-pipelined main loop spreads them between the MFMAs of a k step.
 template <int ROWS, bool CONV_A>
 __device__ __forceinline__ void kmajor_load(kmajor_stage<ROWS> &st, const in_t *__restrict__ src, long row0, long k0e, long row_stride,
-                                            int tid)
+                                            int tid, int u0, int u1)
 {
     typedef kmajor_stage<ROWS> S;
 #pragma unroll
     for (int it = 0; it < S::ITERS; ++it) {
+        if (it < u0 || it >= u1) continue;
         const int idx = it * NTHREADS + tid;
         if (S::TOTAL % NTHREADS == 0 || idx < S::TOTAL) {
             const int row = idx / KV, kv = idx % KV;
@@ -150,7 +156,14 @@ __device__ __forceinline__ void kmajor_load(kmajor_stage<ROWS> &st, const in_t *
                 continue;
             }
 #endif
-            st.r[it] = *reinterpret_cast<const vec_t<in_t, VK> *>(src + (row0 + row) * row_stride + k0e + kv * VK);
+            if (NTHREADS % KV == 0) {
+                // address = uniform base (scalar registers) + one 32-bit per-lane offset shared by all iterations
+                const char *ub = (const char *)(src + (row0 + it * (NTHREADS / KV)) * row_stride + k0e);
+                const unsigned voff = (unsigned)(((tid / KV) * row_stride + (tid % KV) * VK) * ES);
+                st.r[it] = *reinterpret_cast<const vec_t<in_t, VK> *>(ub + voff);
+            } else {
+                st.r[it] = *reinterpret_cast<const vec_t<in_t, VK> *>(src + (row0 + row) * row_stride + k0e + kv * VK);
+            }
         }
     }
 }
@@ -159,11 +172,16 @@ template <int ROWS, int PLANE>
 __device__ __forceinline__ void kmajor_store(const kmajor_stage<ROWS> &st, char *__restrict__ lds, int tid)
 {
     typedef kmajor_stage<ROWS> S;
+    // when the thread count is a multiple of the vectors per row, every iteration of a thread differs
+    // from the first by a constant number of rows: one address register, constant offsets
+    constexpr bool AFFINE = NTHREADS % KV == 0;
+    const int row_t = tid / KV, kv_t = tid % KV;
 #pragma unroll
     for (int it = 0; it < S::ITERS; ++it) {
         const int idx = it * NTHREADS + tid;
         if (S::TOTAL % NTHREADS == 0 || idx < S::TOTAL) {
-            const int row = idx / KV, kv = idx % KV;
+            const int row = AFFINE ? row_t + it * (NTHREADS / KV) : idx / KV;
+            const int kv = AFFINE ? kv_t : idx % KV;
             const int k = kv * VK;
 #pragma unroll
             for (int p = 0; p < PARTS; ++p) {
@@ -190,7 +208,8 @@ struct jmajor_stage {
     vec_t<in_t, VJ> r[ITERS][KP];
 };
 
-__device__ __forceinline__ void jmajor_load(jmajor_stage &st, const in_t *__restrict__ src, long col0, long k0e, long k_stride, int tid)
+__device__ __forceinline__ void jmajor_load(jmajor_stage &st, const in_t *__restrict__ src, long col0, long k0e, long k_stride, int tid,
+                                            int u0, int u1)
 {
     typedef jmajor_stage S;
 #pragma unroll
@@ -199,8 +218,17 @@ __device__ __forceinline__ void jmajor_load(jmajor_stage &st, const in_t *__rest
         if (S::TOTAL % NTHREADS == 0 || idx < S::TOTAL) {
             const int kg = idx / JV, jv = idx % JV;
 #pragma unroll
-            for (int q = 0; q < KP; ++q)
-                st.r[it][q] = *reinterpret_cast<const vec_t<in_t, VJ> *>(src + (k0e + kg * KP + q) * k_stride + col0 + jv * VJ);
+            for (int q = 0; q < KP; ++q) {
+                const int u = it * KP + q;
+                if (u < u0 || u >= u1) continue;
+                if (NTHREADS % JV == 0) {
+                    const char *ub = (const char *)(src + (k0e + (it * (NTHREADS / JV)) * KP + q) * k_stride + col0);
+                    const unsigned voff = (unsigned)(((tid / JV) * KP * k_stride + (tid % JV) * VJ) * ES);
+                    st.r[it][q] = *reinterpret_cast<const vec_t<in_t, VJ> *>(ub + voff);
+                } else {
+                    st.r[it][q] = *reinterpret_cast<const vec_t<in_t, VJ> *>(src + (k0e + kg * KP + q) * k_stride + col0 + jv * VJ);
+                }
+            }
         }
     }
 }
@@ -208,11 +236,14 @@ __device__ __forceinline__ void jmajor_load(jmajor_stage &st, const in_t *__rest
 __device__ __forceinline__ void jmajor_store(const jmajor_stage &st, char *__restrict__ lds, int tid)
 {
     typedef jmajor_stage S;
+    constexpr bool AFFINE = NTHREADS % JV == 0;
+    const int kg_t = tid / JV, jv_t = tid % JV;
 #pragma unroll
     for (int it = 0; it < S::ITERS; ++it) {
         const int idx = it * NTHREADS + tid;
         if (S::TOTAL % NTHREADS == 0 || idx < S::TOTAL) {
-            const int kg = idx / JV, jv = idx % JV;
+            const int kg = AFFINE ? kg_t + it * (NTHREADS / JV) : idx / JV;
+            const int jv = AFFINE ? jv_t : idx % JV;
             char *dst = lds + kg * PLANE_B + jv * VJ * FRAG_BYTES;
 #pragma unroll
             for (int c = 0; c < VJ; ++c) {
@@ -231,20 +262,25 @@ struct tile_stage {
     kmajor_stage<BM> a;
 #if B_KMAJOR
     kmajor_stage<BN> b;
+    static constexpr int UNITS_B = kmajor_stage<BN>::ITERS;
 #else
     jmajor_stage b;
+    static constexpr int UNITS_B = jmajor_stage::ITERS * KP;
 #endif
+    static constexpr int UNITS_A = kmajor_stage<BM>::ITERS;
+    static constexpr int UNITS = UNITS_A + UNITS_B; // global load instructions per thread and tile
 };
 
+// issue load units [u0, u1) of the tile of step k0
 __device__ __forceinline__ void stage_load(tile_stage &st, const in_t *__restrict__ A, const in_t *__restrict__ B, int i0, int j0, int k0,
-                                           int tid)
+                                           int tid, int u0 = 0, int u1 = tile_stage::UNITS)
 {
     const long k0e = (long)k0 * BK;
-    kmajor_load<BM, true>(st.a, A, (long)i0 * BM, k0e, SA_I, tid);
+    kmajor_load<BM, true>(st.a, A, (long)i0 * BM, k0e, SA_I, tid, u0, u1);
 #if B_KMAJOR
-    kmajor_load<BN, false>(st.b, B, (long)j0 * BN, k0e, SB_J, tid);
+    kmajor_load<BN, false>(st.b, B, (long)j0 * BN, k0e, SB_J, tid, u0 - tile_stage::UNITS_A, u1 - tile_stage::UNITS_A);
 #else
-    jmajor_load(st.b, B, (long)j0 * BN, k0e, SB_K, tid);
+    jmajor_load(st.b, B, (long)j0 * BN, k0e, SB_K, tid, u0 - tile_stage::UNITS_A, u1 - tile_stage::UNITS_A);
 #endif
 }
 
@@ -258,18 +294,56 @@ __device__ __forceinline__ void stage_store(const tile_stage &st, char *__restri
 #endif
 }
 
+// fragments of slot `slot` (K3 consecutive MFMA k steps) for the wave's TM x TN tiles
+__device__ __forceinline__ void read_frags(frag_t (&fa)[K3][TM], frag_t (&fb)[K3][TN], const char *__restrict__ la,
+                                           const char *__restrict__ lb, int slot, int wi, int wj)
+{
+#pragma unroll
+    for (int q = 0; q < K3; ++q) {
+        const int step = slot * K3 + q;
+#pragma unroll
+        for (int r1 = 0; r1 < I1; ++r1)
+#pragma unroll
+            for (int r3 = 0; r3 < I3; ++r3) {
+                const int trow = (r1 * I2 + wi) * I3 + r3;
+                fa[q][r1 * I3 + r3] = *reinterpret_cast<const frag_t *>(la + step * LANE_GROUPS * PLANE_A + trow * MI_M * FRAG_BYTES);
+            }
+#pragma unroll
+        for (int c1 = 0; c1 < J1; ++c1)
+#pragma unroll
+            for (int c3 = 0; c3 < J3; ++c3) {
+                const int tcol = (c1 * J2 + wj) * J3 + c3;
+                fb[q][c1 * J3 + c3] = *reinterpret_cast<const frag_t *>(lb + step * LANE_GROUPS * PLANE_B + tcol * MI_N * FRAG_BYTES);
+            }
+    }
+}
+
+// operands swapped: the instruction produces the transposed tile, so that a lane ends up with 4
+// consecutive columns of one row of C (one vector store in the epilogue)
+__device__ __forceinline__ void mfma_slot(accv_t (&acc)[TM][TN], const frag_t (&fa)[K3][TM], const frag_t (&fb)[K3][TN])
+{
+#pragma unroll
+    for (int q = 0; q < K3; ++q)
+#pragma unroll
+        for (int tm = 0; tm < TM; ++tm)
+#pragma unroll
+            for (int tn = 0; tn < TN; ++tn) acc[tm][tn] = mfma(fb[q][tn], fa[q][tm], acc[tm][tn]);
+}
+
+constexpr int NS = K1 * K2;
+#define PIPELINED (UNROLL_K1 == K1 && UNROLL_K2 == K2 && K1 * K2 > 1)
+
 extern "C" __global__ void __launch_bounds__(NTHREADS)
 ms_kernel(const void *__restrict__ a_, const void *__restrict__ b_, const void *__restrict__ bias_, void *__restrict__ c_, int instances)
 {
-    const int z = blockIdx.z * gridDim.y + blockIdx.y;
+    int z, i0, j0;
+    block_to_tile(z, i0, j0);
     const int inst = z / DIM_B, bb = z % DIM_B;
     if (inst >= instances) return;
     const in_t *__restrict__ A = (const in_t *)a_ + (long)inst * A_INST + (long)bb * SA_B;
     const in_t *__restrict__ B = (const in_t *)b_ + (long)inst * B_INST + (long)bb * SB_B;
     out_t *__restrict__ C = (out_t *)c_ + ((long)inst * DIM_B + bb) * ((long)DIM_M * DIM_N);
 
-    int i0, j0;
-    block_to_tile(blockIdx.x, i0, j0);
     const int tid = threadIdx.x;
     const int lane = tid % 64, wave = tid / 64;
     const int wi = wave / J2, wj = wave % J2;
@@ -299,55 +373,59 @@ ms_kernel(const void *__restrict__ a_, const void *__restrict__ b_, const void *
         stage_load(st, A, B, i0, j0, k0, tid);
         stage_store(st, lds, tid);
         __syncthreads();
-#else
-        if (k0 + 1 < K0) stage_load(st, A, B, i0, j0, k0 + 1, tid);
 #endif
         const char *la = lds + stage * STAGE_BYTES + lgrp * PLANE_A + lrow * FRAG_BYTES;
         const char *lb = lds + stage * STAGE_BYTES + KG * PLANE_A + lgrp * PLANE_B + lrow * FRAG_BYTES;
+#if PIPELINED
+        // k1, k2 fully unrolled: software pipeline over the NS = K1*K2 slots of this tile.  Slot s
+        // first issues the LDS reads of slot s+1 and its share of the next tile's global loads, then
+        // its own MFMAs; nothing is moved across a slot boundary.
+        {
+            frag_t fa[2][K3][TM], fb[2][K3][TN];
+            read_frags(fa[0], fb[0], la, lb, 0, wi, wj);
+#pragma unroll
+            for (int s = 0; s < NS; ++s) {
+                if (s + 1 < NS) read_frags(fa[(s + 1) & 1], fb[(s + 1) & 1], la, lb, s + 1, wi, wj);
+#if CACHE_READ == 2
+                // the last step fetches its own tile again instead of branching: the loop body stays one block
+                stage_load(st, A, B, i0, j0, k0 + 1 < K0 ? k0 + 1 : k0, tid, s * tile_stage::UNITS / NS, (s + 1) * tile_stage::UNITS / NS);
+#endif
+                mfma_slot(acc, fa[s & 1], fb[s & 1]);
+                __builtin_amdgcn_sched_barrier(0);
+            }
+        }
+#else
+#if CACHE_READ == 2
+        if (k0 + 1 < K0) stage_load(st, A, B, i0, j0, k0 + 1, tid);
+#endif
 #pragma unroll UNROLL_K1
         for (int k1 = 0; k1 < K1; ++k1) {
 #pragma unroll UNROLL_K2
             for (int k2 = 0; k2 < K2; ++k2) {
-                const int s0 = (k1 * K2 + k2) * K3;
                 frag_t fa[K3][TM], fb[K3][TN];
-#pragma unroll
-                for (int q = 0; q < K3; ++q) {
-#pragma unroll
-                    for (int r1 = 0; r1 < I1; ++r1)
-#pragma unroll
-                        for (int r3 = 0; r3 < I3; ++r3) {
-                            const int trow = (r1 * I2 + wi) * I3 + r3;
-                            fa[q][r1 * I3 + r3] =
-                                *reinterpret_cast<const frag_t *>(la + (s0 + q) * LANE_GROUPS * PLANE_A + trow * MI_M * FRAG_BYTES);
-                        }
-#pragma unroll
-                    for (int c1 = 0; c1 < J1; ++c1)
-#pragma unroll
-                        for (int c3 = 0; c3 < J3; ++c3) {
-                            const int tcol = (c1 * J2 + wj) * J3 + c3;
-                            fb[q][c1 * J3 + c3] =
-                                *reinterpret_cast<const frag_t *>(lb + (s0 + q) * LANE_GROUPS * PLANE_B + tcol * MI_N * FRAG_BYTES);
-                        }
-                }
-#pragma unroll
-                for (int q = 0; q < K3; ++q)
-#pragma unroll
-                    for (int tm = 0; tm < TM; ++tm)
-#pragma unroll
-                        for (int tn = 0; tn < TN; ++tn) acc[tm][tn] = mfma(fa[q][tm], fb[q][tn], acc[tm][tn]);
+                read_frags(fa, fb, la, lb, k1 * K2 + k2, wi, wj);
+                mfma_slot(acc, fa, fb);
             }
         }
+#endif
 #if CACHE_READ == 1
         __syncthreads();
 #else
+#if PIPELINED
+        // unconditional (the last step re-stores its own tile into the idle buffer): a conditional store
+        // would let the compiler sink the prefetch loads down here, behind the MFMAs
+        stage_store(st, lds + (stage ^ 1) * STAGE_BYTES, tid);
+#else
         if (k0 + 1 < K0) stage_store(st, lds + (stage ^ 1) * STAGE_BYTES, tid);
+#endif
         __syncthreads();
         stage ^= 1;
 #endif
     }
 
     // epilogue: (+bias, ReLU,) one rounding to the output type.
-    // accumulator element e of a lane: 16x16 -> row 4*lgrp + e; 32x32 -> row 8*(e/4) + 4*lgrp + e%4; column = lrow
+    // With the operands swapped a lane holds row `lrow` of the tile and, per group g of 4 accumulator
+    // elements, the 4 consecutive columns 4*lgrp (16x16) or 8*g + 4*lgrp (32x32) onwards.
 #pragma unroll
     for (int r1 = 0; r1 < I1; ++r1)
 #pragma unroll
@@ -357,22 +435,26 @@ ms_kernel(const void *__restrict__ a_, const void *__restrict__ b_, const void *
 #pragma unroll
                 for (int c3 = 0; c3 < J3; ++c3) {
                     const int trow = (r1 * I2 + wi) * I3 + r3, tcol = (c1 * J2 + wj) * J3 + c3;
-                    const long col = (long)j0 * BN + tcol * MI_N + lrow;
+                    const long row = (long)i0 * BM + trow * MI_M + lrow;
+#pragma unroll
+                    for (int g = 0; g < ACC_N / 4; ++g) {
+                        const long col = (long)j0 * BN + tcol * MI_N + (MI_M == 16 ? 4 * lgrp : 8 * g + 4 * lgrp);
+                        vec_t<out_t, 4> o;
 #if HAS_BIAS
-                    const float bias = ((const float *)bias_)[col];
+                        const vec_t<float, 4> bias = *reinterpret_cast<const vec_t<float, 4> *>((const float *)bias_ + col);
 #endif
 #pragma unroll
-                    for (int e = 0; e < ACC_N; ++e) {
-                        const int rr = MI_M == 16 ? 4 * lgrp + e : 8 * (e / 4) + 4 * lgrp + e % 4;
-                        const long row = (long)i0 * BM + trow * MI_M + rr;
-                        acc_t x = acc[r1 * I3 + r3][c1 * J3 + c3][e];
+                        for (int e = 0; e < 4; ++e) {
+                            acc_t x = acc[r1 * I3 + r3][c1 * J3 + c3][4 * g + e];
 #if HAS_BIAS
-                        x += bias;
+                            x += bias.v[e];
 #endif
 #if RELU
-                        x = x > 0 ? x : 0;
+                            x = x > 0 ? x : 0;
 #endif
-                        C[row * DIM_N + col] = from_acc(x);
+                            o.v[e] = from_acc(x);
+                        }
+                        *reinterpret_cast<vec_t<out_t, 4> *>(C + row * DIM_N + col) = o;
                     }
                 }
     (void)bias_;

@@ -193,6 +193,7 @@ extern "C" int32_t ms_trace_validate(const ms_op *op, const ms_space *space, con
         if (p.threads > L.max_threads) return reject("%d threads per workgroup, the limit is %d", p.threads, L.max_threads);
         if (acc > L.max_acc_per_thread) return reject("%" PRId64 " accumulators per lane, the register budget is %d", acc, L.max_acc_per_thread);
         p.acc_per_thread = (int32_t)acc;
+        unroll_factors(&p);
         // cache-read: LDS footprint
         int64_t lds = 0;
         if (p.mfma) {
@@ -201,6 +202,8 @@ extern "C" int32_t ms_trace_validate(const ms_op *op, const ms_space *space, con
             lds = (int64_t)p.cache_read * (bk / kp) * (rowsA + rowsB);
             // fragment operands of one k step for the whole wave tile live in registers too
             int64_t frag = ((int64_t)p.ti[1] * p.ti[3] + (int64_t)p.tj[1] * p.tj[3]) * p.tk[3] * (kp * es / 4 > 0 ? kp * es / 4 : 1);
+            // with k1 and k2 fully unrolled the kernel is software pipelined: two fragment sets are live
+            if (p.unroll_k1 == p.tk[1] && p.unroll_k2 == p.tk[2] && p.tk[1] * p.tk[2] > 1) frag *= 2;
             // registers that carry a tile from global memory to LDS; with two buffers they are live across the k step
             int64_t stage = (bm * bk * es / 4 + p.threads - 1) / p.threads + (bn * bk * es / 4 + p.threads - 1) / p.threads;
             int64_t live = p.cache_read == 2 ? frag + stage : std::max(frag, stage);
@@ -242,7 +245,6 @@ extern "C" int32_t ms_trace_validate(const ms_op *op, const ms_space *space, con
                 }
             }
         }
-        unroll_factors(&p);
     } else if (space->family == MS_FAM_DWCONV) {
         if (!get_tile(space, trace, MS_SLOT_TILE_I, p.ti) || !get_tile(space, trace, MS_SLOT_TILE_J, p.tj) ||
             !get_tile(space, trace, MS_SLOT_TILE_C, p.tc))

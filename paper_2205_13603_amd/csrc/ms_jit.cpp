@@ -106,6 +106,20 @@ int32_t jit_get_code(const KernelSpec &spec, uint64_t key, std::vector<char> **c
     if (rc != MS_OK) return rc;
     std::string opts_joined;
     for (auto &d : spec.defines) opts_joined += d + " ";
+    // developer knob: extra -D options for experiments with a private copy of the templates
+    std::vector<std::string> extra;
+    if (const char *env = getenv("MS_EXTRA_DEFINES")) {
+        std::string e(env), tok;
+        for (size_t i = 0; i <= e.size(); ++i) {
+            if (i == e.size() || e[i] == ' ') {
+                if (!tok.empty()) extra.push_back(tok);
+                tok.clear();
+            } else {
+                tok += e[i];
+            }
+        }
+        for (auto &x : extra) opts_joined += x + " ";
+    }
     uint64_t k = mix64(key ^ hash_bytes(src) ^ mix64(hash_bytes(opts_joined)));
     {
         std::lock_guard<std::mutex> lk(g_mu);
@@ -128,6 +142,7 @@ int32_t jit_get_code(const KernelSpec &spec, uint64_t key, std::vector<char> **c
         hiprtcResult r = hiprtcCreateProgram(&prog, src.c_str(), spec.template_name.c_str(), 0, nullptr, nullptr);
         if (r != HIPRTC_SUCCESS) return fail(MS_ERR_COMPILE, "hiprtcCreateProgram: %s", hiprtcGetErrorString(r));
         std::vector<std::string> opts = spec.defines;
+        for (auto &x : extra) opts.push_back(x);
         opts.push_back("--offload-arch=gfx950");
         opts.push_back("-O3");
         opts.push_back("-std=c++17");

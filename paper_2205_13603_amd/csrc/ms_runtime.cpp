@@ -227,3 +227,107 @@ extern "C" int32_t ms_device_info_get(ms_device_info *out)
     out->global_mem_bytes = (int64_t)prop.totalGlobalMem;
     return MS_OK;
 }
+
+// ---------------------------------------------------------------- calibration
+
+namespace {
+
+struct CalibKernel {
+    hipModule_t mod = nullptr;
+    hipFunction_t fn = nullptr;
+};
+
+int32_t load_calib(const std::vector<std::string> &defs, uint64_t key, CalibKernel *out)
+{
+    KernelSpec spec;
+    spec.template_name = "calib.hip";
+    spec.defines = defs;
+    spec.entry = "ms_kernel";
+    std::vector<char> *code;
+    int32_t rc = jit_get_code(spec, key, &code);
+    if (rc != MS_OK) return rc;
+    HIP_TRY(hipModuleLoadData(&out->mod, code->data()));
+    HIP_TRY(hipModuleGetFunction(&out->fn, out->mod, "ms_kernel"));
+    return MS_OK;
+}
+
+int32_t time_launches(hipFunction_t fn, unsigned grid, void **args, hipStream_t s, int reps, double *best_ms)
+{
+    hipEvent_t e0, e1;
+    HIP_TRY(hipEventCreate(&e0));
+    HIP_TRY(hipEventCreate(&e1));
+    double best = 1e30;
+    int32_t rc = MS_OK;
+    for (int r = 0; r < reps + 1 && rc == MS_OK; ++r) { // first repeat is the warm-up
+        hipError_t e = hipEventRecord(e0, s);
+        if (e == hipSuccess) e = hipModuleLaunchKernel(fn, grid, 1, 1, 256, 1, 1, 0, s, args, nullptr);
+        if (e == hipSuccess) e = hipEventRecord(e1, s);
+        if (e == hipSuccess) e = hipEventSynchronize(e1);
+        float ms_el = 0;
+        if (e == hipSuccess) e = hipEventElapsedTime(&ms_el, e0, e1);
+        if (e != hipSuccess) rc = fail(MS_ERR_HIP, "calibration launch: %s", hipGetErrorString(e));
+        else if (r > 0 && ms_el < best) best = ms_el;
+    }
+    (void)hipEventDestroy(e0);
+    (void)hipEventDestroy(e1);
+    *best_ms = best;
+    return rc;
+}
+
+} // namespace
+
+extern "C" int32_t ms_calibrate_mfma(int32_t in_dtype, int32_t mfma_code, const void *operands, void *scratch, void *stream, double *tflops)
+{
+    if (!scratch || !tflops) return fail(MS_ERR_BAD_ARG, "ms_calibrate_mfma: NULL argument");
+    static const int f16_codes[] = {161616, 323208, 161632, 323216}, i8_codes[] = {161632, 323216, 161664, 323232};
+    const int *codes = in_dtype == MS_I8 ? i8_codes : f16_codes;
+    if (in_dtype != MS_F16 && in_dtype != MS_BF16 && in_dtype != MS_I8) return fail(MS_ERR_BAD_ARG, "ms_calibrate_mfma: bad dtype");
+    bool ok = false;
+    for (int i = 0; i < 4; ++i) ok = ok || codes[i] == mfma_code;
+    if (!ok) return fail(MS_ERR_BAD_ARG, "ms_calibrate_mfma: no intrinsic %d for %s", mfma_code, dtype_name(in_dtype));
+    int m = mfma_code / 10000, n = mfma_code / 100 % 100, k = mfma_code % 100;
+    std::vector<std::string> defs = {"-DMODE=0", "-DCAL_DT=" + std::to_string(in_dtype), "-DMI_M=" + std::to_string(m),
+                                     "-DMI_N=" + std::to_string(n), "-DMI_K=" + std::to_string(k)};
+    CalibKernel ck;
+    int32_t rc = load_calib(defs, mix64(0xCA11B0ull ^ (uint64_t)mfma_code * 131 ^ (uint64_t)in_dtype), &ck);
+    if (rc != MS_OK) return rc;
+    int dev = 0;
+    hipDeviceProp_t prop;
+    HIP_TRY(hipGetDevice(&dev));
+    HIP_TRY(hipGetDeviceProperties(&prop, dev));
+    unsigned grid = (unsigned)prop.multiProcessorCount * 2; // 2 workgroups x 4 waves per CU = 2 waves per SIMD
+    int iters = 20000;
+    const void *src = operands;
+    void *args[] = {&src, &src, &src, &scratch, &iters};
+    double ms_best = 0;
+    rc = time_launches(ck.fn, grid, args, (hipStream_t)stream, 3, &ms_best);
+    (void)hipModuleUnload(ck.mod);
+    if (rc != MS_OK) return rc;
+    double insts = (double)grid * 4 * iters * 8;
+    *tflops = insts * 2.0 * m * n * k / (ms_best * 1e-3) / 1e12;
+    return MS_OK;
+}
+
+extern "C" int32_t ms_calibrate_stream(int32_t mode, const void *src, void *dst, size_t bytes, void *stream, double *gbs)
+{
+    if (!src || !dst || !gbs) return fail(MS_ERR_BAD_ARG, "ms_calibrate_stream: NULL argument");
+    if ((mode != 1 && mode != 2) || bytes == 0 || bytes % 4096 || bytes / 4096 > 0x7fffffffull)
+        return fail(MS_ERR_BAD_ARG, "ms_calibrate_stream: mode must be 1 or 2 and bytes a multiple of 4096");
+    std::vector<std::string> defs = {"-DMODE=" + std::to_string(mode), "-DCAL_DT=0"};
+    CalibKernel ck;
+    int32_t rc = load_calib(defs, mix64(0xCA11B1ull ^ (uint64_t)mode), &ck);
+    if (rc != MS_OK) return rc;
+    int dev = 0;
+    hipDeviceProp_t prop;
+    HIP_TRY(hipGetDevice(&dev));
+    HIP_TRY(hipGetDeviceProperties(&prop, dev));
+    unsigned grid = (unsigned)prop.multiProcessorCount * 16;
+    int n16_by_256 = (int)(bytes / 4096);
+    void *args[] = {&src, &src, &src, &dst, &n16_by_256};
+    double ms_best = 0;
+    rc = time_launches(ck.fn, grid, args, (hipStream_t)stream, 5, &ms_best);
+    (void)hipModuleUnload(ck.mod);
+    if (rc != MS_OK) return rc;
+    *gbs = (double)bytes * (mode == 1 ? 2.0 : 1.0) / (ms_best * 1e-3) / 1e9;
+    return MS_OK;
+}
