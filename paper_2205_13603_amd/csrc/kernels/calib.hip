@@ -60,7 +60,7 @@ __device__ __forceinline__ accv_t mfma(const frag_t &a, const frag_t &b, accv_t 
 #endif
 }
 
-extern "C" __global__ void __launch_bounds__(256) ms_kernel(const void *src, const void *, const void *, void *dst, int iters)
+extern "C" __global__ void __launch_bounds__(256) ms_calib_kernel(const void *src, const void *, const void *, void *dst, int iters)
 {
     // operands: taken from `src` when given (2 fragments per lane; realistic values make the matrix
     // cores draw realistic power, which the clock governor reacts to), else small integers
@@ -92,7 +92,7 @@ extern "C" __global__ void __launch_bounds__(256) ms_kernel(const void *src, con
 }
 #else
 typedef vec_t<float, 4> w16_t;
-extern "C" __global__ void __launch_bounds__(256) ms_kernel(const void *src, const void *, const void *, void *dst, int n16_lo)
+extern "C" __global__ void __launch_bounds__(256) ms_calib_kernel(const void *src, const void *, const void *, void *dst, int n16_lo)
 {
     const long n16 = (long)(unsigned)n16_lo * 256; // the host passes the word count / 256
     const long stride = (long)gridDim.x * blockDim.x;

@@ -242,12 +242,12 @@ int32_t load_calib(const std::vector<std::string> &defs, uint64_t key, CalibKern
     KernelSpec spec;
     spec.template_name = "calib.hip";
     spec.defines = defs;
-    spec.entry = "ms_kernel";
+    spec.entry = "ms_calib_kernel";
     std::vector<char> *code;
     int32_t rc = jit_get_code(spec, key, &code);
     if (rc != MS_OK) return rc;
     HIP_TRY(hipModuleLoadData(&out->mod, code->data()));
-    HIP_TRY(hipModuleGetFunction(&out->fn, out->mod, "ms_kernel"));
+    HIP_TRY(hipModuleGetFunction(&out->fn, out->mod, "ms_calib_kernel"));
     return MS_OK;
 }
 
