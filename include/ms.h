@@ -149,10 +149,14 @@ typedef enum ms_slot_id {
     MS_SLOT_UNROLL = 5,    /* categorical: unroll budget, candidates {0,16,64} */
     MS_SLOT_CACHE_READ = 6,/* categorical: 0 = operands read from global memory,
                               1 = staged in LDS, 2 = staged in LDS, double buffered */
-    MS_SLOT_VECTORIZE = 7, /* categorical: elements per global load instruction */
-    MS_SLOT_STORAGE_ALIGN = 8, /* categorical: LDS row padding in 16-byte units */
-    MS_SLOT_REORDER = 9    /* categorical: order of the grid loops, 0 = i outer, 1 = j outer,
+    MS_SLOT_VECTORIZE = 7, /* categorical: elements per global load instruction of operand A (conv: X) */
+    MS_SLOT_STORAGE_ALIGN = 8, /* categorical: LDS layout: 0 = dense, 1 = each row / plane padded by 16 bytes,
+                              2 (matrix-core kernels) = padded, and the 16-byte slots of a plane XOR-swizzled */
+    MS_SLOT_REORDER = 9,   /* categorical: order of the grid loops, 0 = i outer, 1 = j outer,
                               2 = i outer with workgroups grouped per XCD */
+    MS_SLOT_VECTORIZE_B = 10, /* categorical: elements per global load instruction of operand B (conv: W) */
+    MS_SLOT_CACHE_WRITE = 11  /* categorical (matrix-core kernels): 0 = results go from registers to global memory,
+                                 1 = the workgroup's output tile is staged in LDS and written as whole rows */
 } ms_slot_id;
 
 /* Tensorize candidates: (m, n, k) of one matrix-core instruction.  The code
@@ -200,6 +204,7 @@ typedef struct ms_slot {
 #define MS_SPACE_UNROLL 0x8u        /* sample the unroll budget; off = 0 */
 #define MS_SPACE_STORAGE_ALIGN 0x10u/* sample LDS padding; off = no padding */
 #define MS_SPACE_REORDER 0x20u      /* sample the grid loop order; off = i outer */
+#define MS_SPACE_CACHE_WRITE 0x40u   /* sample LDS staging of the output tile; off = direct stores */
 #define MS_SPACE_DEFAULT 0xffffffffu
 
 typedef enum ms_family { MS_FAM_GEMM_ALU = 0, MS_FAM_GEMM_MFMA = 1, MS_FAM_DWCONV = 2 } ms_family;
@@ -272,12 +277,14 @@ typedef struct ms_variant_params {
     int32_t acc_per_thread; /* accumulator registers per lane */
     int32_t lds_bytes;
     int32_t cache_read;     /* 0, 1, 2 as in MS_SLOT_CACHE_READ */
-    int32_t vec;            /* elements per global load */
+    int32_t vec;            /* elements per global load of A (depthwise: channels per access) */
     int32_t unroll;         /* budget */
     int32_t unroll_k1, unroll_k2; /* unroll factors of the two rolled reduction loops */
-    int32_t lds_pad;        /* padding, in 16-byte units */
+    int32_t lds_pad;        /* the storage-align decision: 0, 1 or 2 */
     int32_t reorder;
-    int32_t reserved[8];
+    int32_t vec_b;          /* elements per global load of B */
+    int32_t cache_write;    /* 0, 1 as in MS_SLOT_CACHE_WRITE */
+    int32_t reserved[6];
     uint64_t key;           /* hash of everything that selects the kernel */
 } ms_variant_params;
 
@@ -463,6 +470,9 @@ int32_t ms_device_info_get(ms_device_info *out);
  */
 int32_t ms_calibrate_mfma(int32_t in_dtype, int32_t mfma_code, const void *operands, void *scratch, void *stream, double *tflops);
 int32_t ms_calibrate_stream(int32_t mode, const void *src, void *dst, size_t bytes, void *stream, double *gbs);
+/* LDS read rate with 16-byte conflict-free reads on every CU: aggregate GB/s and bytes per clock per CU
+ * at the device's nominal clock. */
+int32_t ms_calibrate_lds(void *scratch, void *stream, double *bytes_per_clk_per_cu, double *gbs);
 
 int32_t ms_version(void);
 const char *ms_last_error(void);

@@ -16,8 +16,8 @@ OP_GEMM, OP_BMM_NT, OP_BMM_NN, OP_CONV2D_NHWC, OP_DWCONV2D_NHWC = range(5)
 F32, F16, BF16, I8, I32 = range(5)
 SLOT_PERFECT_TILE, SLOT_CATEGORICAL = 0, 1
 (SLOT_TENSORIZE, SLOT_TILE_I, SLOT_TILE_J, SLOT_TILE_C, SLOT_TILE_K, SLOT_UNROLL, SLOT_CACHE_READ, SLOT_VECTORIZE,
- SLOT_STORAGE_ALIGN, SLOT_REORDER) = range(10)
-SPACE_TENSORIZE, SPACE_CACHE_READ, SPACE_VECTORIZE, SPACE_UNROLL, SPACE_STORAGE_ALIGN, SPACE_REORDER = 1, 2, 4, 8, 16, 32
+ SLOT_STORAGE_ALIGN, SLOT_REORDER, SLOT_VECTORIZE_B, SLOT_CACHE_WRITE) = range(12)
+SPACE_TENSORIZE, SPACE_CACHE_READ, SPACE_VECTORIZE, SPACE_UNROLL, SPACE_STORAGE_ALIGN, SPACE_REORDER, SPACE_CACHE_WRITE = 1, 2, 4, 8, 16, 32, 64
 SPACE_DEFAULT = 0xFFFFFFFF
 FAM_GEMM_ALU, FAM_GEMM_MFMA, FAM_DWCONV = range(3)
 MAX_SLOTS, MAX_FACTORS, MAX_CANDS, MAX_LOOPS = 16, 4, 8, 8
@@ -76,7 +76,7 @@ class ms_variant_params(C.Structure):
                 ("block_n", C.c_int32), ("block_k", C.c_int32), ("grid", C.c_int32 * 3), ("threads", C.c_int32),
                 ("waves", C.c_int32), ("acc_per_thread", C.c_int32), ("lds_bytes", C.c_int32),
                 ("cache_read", C.c_int32), ("vec", C.c_int32), ("unroll", C.c_int32), ("unroll_k1", C.c_int32),
-                ("unroll_k2", C.c_int32), ("lds_pad", C.c_int32), ("reorder", C.c_int32), ("reserved", C.c_int32 * 8),
+                ("unroll_k2", C.c_int32), ("lds_pad", C.c_int32), ("reorder", C.c_int32), ("vec_b", C.c_int32), ("cache_write", C.c_int32), ("reserved", C.c_int32 * 6),
                 ("key", C.c_uint64)]
 
     def as_dict(self):
@@ -166,6 +166,7 @@ SYMBOLS = {
     "ms_device_info_get": (C.c_int32, [_P(ms_device_info)]),
     "ms_calibrate_mfma": (C.c_int32, [C.c_int32, C.c_int32, C.c_void_p, C.c_void_p, C.c_void_p, _P(C.c_double)]),
     "ms_calibrate_stream": (C.c_int32, [C.c_int32, C.c_void_p, C.c_void_p, C.c_size_t, C.c_void_p, _P(C.c_double)]),
+    "ms_calibrate_lds": (C.c_int32, [C.c_void_p, C.c_void_p, _P(C.c_double), _P(C.c_double)]),
     "ms_version": (C.c_int32, []),
     "ms_last_error": (C.c_char_p, []),
 }
@@ -409,6 +410,12 @@ def calibrate_stream(mode, src_ptr, dst_ptr, nbytes, stream=None):
     v = C.c_double()
     _check(lib().ms_calibrate_stream(mode, src_ptr, dst_ptr, nbytes, stream, C.byref(v)))
     return v.value
+
+
+def calibrate_lds(scratch_ptr, stream=None):
+    a, b = C.c_double(), C.c_double()
+    _check(lib().ms_calibrate_lds(scratch_ptr, stream, C.byref(a), C.byref(b)))
+    return a.value, b.value
 
 
 def search_cfg_default():

@@ -90,6 +90,27 @@ extern "C" __global__ void __launch_bounds__(256) ms_calib_kernel(const void *sr
     for (int t = 0; t < 8; ++t) s += acc[t][0];
     if (s == (acc_t)-12345) ((acc_t *)dst)[threadIdx.x] = s; // never true: keeps the loop alive
 }
+#elif MODE == 3
+// LDS read rate: every wave reads 16 bytes per lane, lanes at consecutive addresses (no bank conflict),
+// 8 independent reads per iteration
+typedef unsigned u4_t __attribute__((ext_vector_type(4)));
+extern "C" __global__ void __launch_bounds__(256) ms_calib_kernel(const void *src, const void *, const void *, void *dst, int iters)
+{
+    __shared__ u4_t buf[4096]; // 64 KiB
+    for (int i = threadIdx.x; i < 4096; i += 256) buf[i] = u4_t{(unsigned)i, 1u, 2u, 3u};
+    __syncthreads();
+    u4_t acc = {0, 0, 0, 0};
+    const int base = threadIdx.x;
+#pragma unroll 1
+    for (int it = 0; it < iters; ++it) {
+#pragma unroll
+        for (int t = 0; t < 8; ++t) {
+            u4_t x = buf[(base + t * 256 + (it & 7) * 64) & 4095];
+            acc ^= x;
+        }
+    }
+    if (acc[0] == 0xdeadbeefu && src != nullptr) ((u4_t *)dst)[threadIdx.x] = acc;
+}
 #else
 typedef vec_t<float, 4> w16_t;
 extern "C" __global__ void __launch_bounds__(256) ms_calib_kernel(const void *src, const void *, const void *, void *dst, int n16_lo)

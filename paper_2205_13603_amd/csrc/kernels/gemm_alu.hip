@@ -6,8 +6,8 @@
 //   bind    fuse(i0,j0) -> blockIdx.x, fuse(i2,j2) -> threadIdx.x
 //   cache-read A,B into LDS at k0 (CACHE_READ 1: one buffer, 2: two buffers,
 //           0: operands come straight from global memory)
-//   storage-align: LDS rows padded by LDS_PAD*16 bytes
-//   vectorize: global loads of VEC elements; stores of J3 elements
+//   storage-align: LDS rows padded by 16 bytes when LDS_PAD != 0
+//   vectorize: global loads of VEC (A) and VEC_B (B) elements; stores of J3 elements
 //   unroll  k1 by UNROLL_K1, k2 by UNROLL_K2; k3 and the register tile fully
 // Index of a split loop: ((x0*F1 + x1)*F2 + x2)*F3 + x3.
 #include "common.h"
@@ -17,7 +17,7 @@ constexpr int BN = J1 * J2 * J3;
 constexpr int BK = K1 * K2 * K3;
 constexpr int RM = I1 * I3;
 constexpr int RN = J1 * J3;
-constexpr int PAD = LDS_PAD * 4; // elements of 4 bytes
+constexpr int PAD = LDS_PAD ? 4 : 0; // elements of 4 bytes
 constexpr int LDA = BK + PAD;
 constexpr int LDB = BN + PAD;
 constexpr int STAGES = CACHE_READ == 2 ? 2 : 1;
@@ -42,7 +42,7 @@ __device__ __forceinline__ void load_tiles(const in_t *__restrict__ A, const in_
     }
     // B tile: BK x BN
     if (SB_K == 1 && SB_J != 1) { // reduction index contiguous ("NT"): vectors along k
-        constexpr int VB = VEC;
+        constexpr int VB = VEC_B;
         constexpr int KV = BK / VB;
         constexpr int TOTAL = BN * KV;
         for (int idx = tid; idx < TOTAL; idx += NTHREADS) {
@@ -53,7 +53,7 @@ __device__ __forceinline__ void load_tiles(const in_t *__restrict__ A, const in_
             for (int q = 0; q < VB; ++q) Bs[(kv * VB + q) * LDB + j] = to_acc(x.v[q]);
         }
     } else {
-        constexpr int VB = (SB_J == 1) ? VEC : 1;
+        constexpr int VB = (SB_J == 1) ? VEC_B : 1;
         constexpr int JV = BN / VB;
         constexpr int TOTAL = BK * JV;
         for (int idx = tid; idx < TOTAL; idx += NTHREADS) {

@@ -10,8 +10,9 @@
 //   cache-read A,B tiles of one k0 step into LDS (CACHE_READ 1: one buffer;
 //           2: two buffers, the next tile is fetched into registers while the
 //           current one is multiplied)
-//   storage-align: each LDS plane padded by LDS_PAD*16 bytes
-//   vectorize: global loads of VEC elements
+//   storage-align: LDS_PAD 1, 2: each LDS plane padded by 16 bytes; 2: slots of a plane XOR-swizzled
+//   vectorize: global loads of VEC (A) and VEC_B (B) elements
+//   cache-write (CACHE_WRITE 1): the output tile is assembled in LDS and stored as whole rows
 //   unroll  k1 by UNROLL_K1, k2 by UNROLL_K2; k3 and the wave's tile loops fully.  When the
 //           budget unrolls k1 and k2 completely the k step becomes a software pipeline: each of
 //           its K1*K2 slots issues the next slot's LDS reads and a share of the next tile's global
@@ -36,8 +37,21 @@ constexpr int BK = K1 * K2 * K3 * MI_K;
 constexpr int KG = BK / KP;                       // k groups per tile
 constexpr int ES = sizeof(in_t);
 constexpr int FRAG_BYTES = KP * ES;               // 8 or 16
-constexpr int PLANE_A = BM * FRAG_BYTES + LDS_PAD * 16; // bytes of one k-group plane
-constexpr int PLANE_B = BN * FRAG_BYTES + LDS_PAD * 16;
+constexpr int PLANE_A = BM * FRAG_BYTES + (LDS_PAD ? 16 : 0); // bytes of one k-group plane
+constexpr int PLANE_B = BN * FRAG_BYTES + (LDS_PAD ? 16 : 0);
+
+// Slot of row `n` inside a plane (a slot = one fragment).  The swizzle XORs the low 3 bits of the slot
+// with bits 3..5: a thread that writes 8 consecutive slots (the transposed j-contiguous operand) then
+// starts in a different bank group than its 7 neighbours, and 8 consecutive lanes that read 8
+// consecutive rows still touch 8 distinct slots of one aligned group.
+__device__ __forceinline__ int lds_slot(int n)
+{
+#if LDS_PAD == 2
+    return n ^ ((n >> 3) & 7);
+#else
+    return n;
+#endif
+}
 constexpr int STAGE_BYTES = KG * (PLANE_A + PLANE_B);
 constexpr int STAGES = CACHE_READ == 2 ? 2 : 1;
 constexpr int KSTEPS = K1 * K2 * K3;              // MFMA k steps per tile
@@ -107,31 +121,30 @@ __device__ __forceinline__ accv_t mfma(const frag_t &a, const frag_t &b, accv_t 
 // ---- global -> registers -> LDS staging of one operand tile
 //
 // K-contiguous operand (A; B of the NT form; conv activations): a thread
-// moves vectors of VEC elements along k; vector idx -> (row, kv), kv fastest.
-constexpr int VK = VEC;                 // elements per vector along k
-constexpr int KV = BK / VK;             // vectors per tile row
-constexpr int PARTS = VK > KP ? VK / KP : 1; // LDS writes per vector
-constexpr int PART_E = VK > KP ? KP : VK;    // elements per LDS write
-
-template <int ROWS> struct kmajor_stage {
+// moves vectors of V elements along k (V = VEC for A, VEC_B for B); vector idx -> (row, kv), kv fastest.
+template <int ROWS, int V> struct kmajor_stage {
+    static constexpr int VK = V;                          // elements per vector along k
+    static constexpr int KV = BK / V;                     // vectors per tile row
+    static constexpr int PARTS = V > KP ? V / KP : 1;     // LDS writes per vector
+    static constexpr int PART_E = V > KP ? KP : V;        // elements per LDS write
     static constexpr int TOTAL = ROWS * KV;
     static constexpr int ITERS = (TOTAL + NTHREADS - 1) / NTHREADS;
-    vec_t<in_t, VK> r[ITERS];
+    vec_t<in_t, V> r[ITERS];
 };
 
 #if IS_CONV
 // im2col on the fly: row = output pixel, k = (kh, kw, ci)
-__device__ __forceinline__ vec_t<in_t, VK> load_conv_a(const in_t *__restrict__ X, int row, int k)
+template <int V> __device__ __forceinline__ vec_t<in_t, V> load_conv_a(const in_t *__restrict__ X, int row, int k)
 {
     const int ow = row % CV_OW, oh = (row / CV_OW) % CV_OH, n = row / (CV_OW * CV_OH);
     const int ci = k % CV_CIN, kw = (k / CV_CIN) % CV_KW, kh = k / (CV_CIN * CV_KW);
     const int ih = oh * CV_STRIDE + kh - CV_PAD, iw = ow * CV_STRIDE + kw - CV_PAD;
-    vec_t<in_t, VK> x;
+    vec_t<in_t, V> x;
     if (ih >= 0 && ih < CV_H && iw >= 0 && iw < CV_W) {
-        x = *reinterpret_cast<const vec_t<in_t, VK> *>(X + (((long)n * CV_H + ih) * CV_W + iw) * CV_CIN + ci);
+        x = *reinterpret_cast<const vec_t<in_t, V> *>(X + (((long)n * CV_H + ih) * CV_W + iw) * CV_CIN + ci);
     } else {
 #pragma unroll
-        for (int q = 0; q < VK; ++q) x.v[q] = 0;
+        for (int q = 0; q < V; ++q) x.v[q] = 0;
     }
     return x;
 }
@@ -139,11 +152,12 @@ __device__ __forceinline__ vec_t<in_t, VK> load_conv_a(const in_t *__restrict__ 
 
 // Loads are numbered ("units") so that a caller can issue any sub-range [u0, u1) of a tile's loads:
 // the software-pipelined main loop spreads them between the MFMAs of a k step.
-template <int ROWS, bool CONV_A>
-__device__ __forceinline__ void kmajor_load(kmajor_stage<ROWS> &st, const in_t *__restrict__ src, long row0, long k0e, long row_stride,
+template <int ROWS, int V, bool CONV_A>
+__device__ __forceinline__ void kmajor_load(kmajor_stage<ROWS, V> &st, const in_t *__restrict__ src, long row0, long k0e, long row_stride,
                                             int tid, int u0, int u1)
 {
-    typedef kmajor_stage<ROWS> S;
+    typedef kmajor_stage<ROWS, V> S;
+    constexpr int KV = S::KV;
 #pragma unroll
     for (int it = 0; it < S::ITERS; ++it) {
         if (it < u0 || it >= u1) continue;
@@ -152,26 +166,27 @@ __device__ __forceinline__ void kmajor_load(kmajor_stage<ROWS> &st, const in_t *
             const int row = idx / KV, kv = idx % KV;
 #if IS_CONV
             if (CONV_A) {
-                st.r[it] = load_conv_a(src, (int)row0 + row, (int)k0e + kv * VK);
+                st.r[it] = load_conv_a<V>(src, (int)row0 + row, (int)k0e + kv * V);
                 continue;
             }
 #endif
             if (NTHREADS % KV == 0) {
                 // address = uniform base (scalar registers) + one 32-bit per-lane offset shared by all iterations
                 const char *ub = (const char *)(src + (row0 + it * (NTHREADS / KV)) * row_stride + k0e);
-                const unsigned voff = (unsigned)(((tid / KV) * row_stride + (tid % KV) * VK) * ES);
-                st.r[it] = *reinterpret_cast<const vec_t<in_t, VK> *>(ub + voff);
+                const unsigned voff = (unsigned)(((tid / KV) * row_stride + (tid % KV) * V) * ES);
+                st.r[it] = *reinterpret_cast<const vec_t<in_t, V> *>(ub + voff);
             } else {
-                st.r[it] = *reinterpret_cast<const vec_t<in_t, VK> *>(src + (row0 + row) * row_stride + k0e + kv * VK);
+                st.r[it] = *reinterpret_cast<const vec_t<in_t, V> *>(src + (row0 + row) * row_stride + k0e + kv * V);
             }
         }
     }
 }
 
-template <int ROWS, int PLANE>
-__device__ __forceinline__ void kmajor_store(const kmajor_stage<ROWS> &st, char *__restrict__ lds, int tid)
+template <int ROWS, int V, int PLANE>
+__device__ __forceinline__ void kmajor_store(const kmajor_stage<ROWS, V> &st, char *__restrict__ lds, int tid)
 {
-    typedef kmajor_stage<ROWS> S;
+    typedef kmajor_stage<ROWS, V> S;
+    constexpr int KV = S::KV, PARTS = S::PARTS, PART_E = S::PART_E;
     // when the thread count is a multiple of the vectors per row, every iteration of a thread differs
     // from the first by a constant number of rows: one address register, constant offsets
     constexpr bool AFFINE = NTHREADS % KV == 0;
@@ -182,11 +197,11 @@ __device__ __forceinline__ void kmajor_store(const kmajor_stage<ROWS> &st, char 
         if (S::TOTAL % NTHREADS == 0 || idx < S::TOTAL) {
             const int row = AFFINE ? row_t + it * (NTHREADS / KV) : idx / KV;
             const int kv = AFFINE ? kv_t : idx % KV;
-            const int k = kv * VK;
+            const int k = kv * V;
 #pragma unroll
             for (int p = 0; p < PARTS; ++p) {
                 const int kk = k + p * PART_E;
-                char *dst = lds + (kk / KP) * PLANE + row * FRAG_BYTES + (kk % KP) * ES;
+                char *dst = lds + (kk / KP) * PLANE + lds_slot(row) * FRAG_BYTES + (kk % KP) * ES;
                 vec_t<in_t, PART_E> part;
 #pragma unroll
                 for (int q = 0; q < PART_E; ++q) part.v[q] = st.r[it].v[p * PART_E + q];
@@ -197,9 +212,9 @@ __device__ __forceinline__ void kmajor_store(const kmajor_stage<ROWS> &st, char 
 }
 
 // J-contiguous operand (B of the NN form, conv weights): a thread moves a
-// block of KP k-rows x VEC columns and transposes it in registers, so that it
-// lands in LDS as VEC consecutive fragments.
-constexpr int VJ = VEC;
+// block of KP k-rows x VEC_B columns and transposes it in registers, so that it
+// lands in LDS as VEC_B consecutive fragments.
+constexpr int VJ = VEC_B;
 constexpr int JV = BN / VJ;
 
 struct jmajor_stage {
@@ -244,13 +259,13 @@ __device__ __forceinline__ void jmajor_store(const jmajor_stage &st, char *__res
         if (S::TOTAL % NTHREADS == 0 || idx < S::TOTAL) {
             const int kg = AFFINE ? kg_t + it * (NTHREADS / JV) : idx / JV;
             const int jv = AFFINE ? jv_t : idx % JV;
-            char *dst = lds + kg * PLANE_B + jv * VJ * FRAG_BYTES;
+            char *dst = lds + kg * PLANE_B;
 #pragma unroll
             for (int c = 0; c < VJ; ++c) {
                 frag_t f;
 #pragma unroll
                 for (int q = 0; q < KP; ++q) f.v[q] = st.r[it][q].v[c];
-                *reinterpret_cast<frag_t *>(dst + c * FRAG_BYTES) = f;
+                *reinterpret_cast<frag_t *>(dst + lds_slot(jv * VJ + c) * FRAG_BYTES) = f;
             }
         }
     }
@@ -259,15 +274,15 @@ __device__ __forceinline__ void jmajor_store(const jmajor_stage &st, char *__res
 #define B_KMAJOR (!IS_CONV && SB_K == 1 && SB_J != 1)
 
 struct tile_stage {
-    kmajor_stage<BM> a;
+    kmajor_stage<BM, VEC> a;
 #if B_KMAJOR
-    kmajor_stage<BN> b;
-    static constexpr int UNITS_B = kmajor_stage<BN>::ITERS;
+    kmajor_stage<BN, VEC_B> b;
+    static constexpr int UNITS_B = kmajor_stage<BN, VEC_B>::ITERS;
 #else
     jmajor_stage b;
     static constexpr int UNITS_B = jmajor_stage::ITERS * KP;
 #endif
-    static constexpr int UNITS_A = kmajor_stage<BM>::ITERS;
+    static constexpr int UNITS_A = kmajor_stage<BM, VEC>::ITERS;
     static constexpr int UNITS = UNITS_A + UNITS_B; // global load instructions per thread and tile
 };
 
@@ -276,9 +291,9 @@ __device__ __forceinline__ void stage_load(tile_stage &st, const in_t *__restric
                                            int tid, int u0 = 0, int u1 = tile_stage::UNITS)
 {
     const long k0e = (long)k0 * BK;
-    kmajor_load<BM, true>(st.a, A, (long)i0 * BM, k0e, SA_I, tid, u0, u1);
+    kmajor_load<BM, VEC, true>(st.a, A, (long)i0 * BM, k0e, SA_I, tid, u0, u1);
 #if B_KMAJOR
-    kmajor_load<BN, false>(st.b, B, (long)j0 * BN, k0e, SB_J, tid, u0 - tile_stage::UNITS_A, u1 - tile_stage::UNITS_A);
+    kmajor_load<BN, VEC_B, false>(st.b, B, (long)j0 * BN, k0e, SB_J, tid, u0 - tile_stage::UNITS_A, u1 - tile_stage::UNITS_A);
 #else
     jmajor_load(st.b, B, (long)j0 * BN, k0e, SB_K, tid, u0 - tile_stage::UNITS_A, u1 - tile_stage::UNITS_A);
 #endif
@@ -286,9 +301,9 @@ __device__ __forceinline__ void stage_load(tile_stage &st, const in_t *__restric
 
 __device__ __forceinline__ void stage_store(const tile_stage &st, char *__restrict__ lds, int tid)
 {
-    kmajor_store<BM, PLANE_A>(st.a, lds, tid);
+    kmajor_store<BM, VEC, PLANE_A>(st.a, lds, tid);
 #if B_KMAJOR
-    kmajor_store<BN, PLANE_B>(st.b, lds + KG * PLANE_A, tid);
+    kmajor_store<BN, VEC_B, PLANE_B>(st.b, lds + KG * PLANE_A, tid);
 #else
     jmajor_store(st.b, lds + KG * PLANE_A, tid);
 #endif
@@ -296,7 +311,7 @@ __device__ __forceinline__ void stage_store(const tile_stage &st, char *__restri
 
 // fragments of slot `slot` (K3 consecutive MFMA k steps) for the wave's TM x TN tiles
 __device__ __forceinline__ void read_frags(frag_t (&fa)[K3][TM], frag_t (&fb)[K3][TN], const char *__restrict__ la,
-                                           const char *__restrict__ lb, int slot, int wi, int wj)
+                                           const char *__restrict__ lb, int slot, int wi, int wj, int lrow)
 {
 #pragma unroll
     for (int q = 0; q < K3; ++q) {
@@ -306,14 +321,16 @@ __device__ __forceinline__ void read_frags(frag_t (&fa)[K3][TM], frag_t (&fb)[K3
 #pragma unroll
             for (int r3 = 0; r3 < I3; ++r3) {
                 const int trow = (r1 * I2 + wi) * I3 + r3;
-                fa[q][r1 * I3 + r3] = *reinterpret_cast<const frag_t *>(la + step * LANE_GROUPS * PLANE_A + trow * MI_M * FRAG_BYTES);
+                fa[q][r1 * I3 + r3] =
+                    *reinterpret_cast<const frag_t *>(la + step * LANE_GROUPS * PLANE_A + lds_slot(trow * MI_M + lrow) * FRAG_BYTES);
             }
 #pragma unroll
         for (int c1 = 0; c1 < J1; ++c1)
 #pragma unroll
             for (int c3 = 0; c3 < J3; ++c3) {
                 const int tcol = (c1 * J2 + wj) * J3 + c3;
-                fb[q][c1 * J3 + c3] = *reinterpret_cast<const frag_t *>(lb + step * LANE_GROUPS * PLANE_B + tcol * MI_N * FRAG_BYTES);
+                fb[q][c1 * J3 + c3] =
+                    *reinterpret_cast<const frag_t *>(lb + step * LANE_GROUPS * PLANE_B + lds_slot(tcol * MI_N + lrow) * FRAG_BYTES);
             }
     }
 }
@@ -349,7 +366,9 @@ ms_kernel(const void *__restrict__ a_, const void *__restrict__ b_, const void *
     const int wi = wave / J2, wj = wave % J2;
     const int lrow = lane % MI_M, lgrp = lane / MI_M;
 
-    __shared__ __attribute__((aligned(16))) char lds[STAGES * STAGE_BYTES];
+    constexpr int CROW = BN * (int)sizeof(out_t) + 16; // bytes of one staged output row (cache-write)
+    constexpr int LDS_BYTES = (CACHE_WRITE && BM * CROW > STAGES * STAGE_BYTES) ? BM * CROW : STAGES * STAGE_BYTES;
+    __shared__ __attribute__((aligned(16))) char lds[LDS_BYTES];
 
     accv_t acc[TM][TN];
 #pragma unroll
@@ -374,18 +393,18 @@ ms_kernel(const void *__restrict__ a_, const void *__restrict__ b_, const void *
         stage_store(st, lds, tid);
         __syncthreads();
 #endif
-        const char *la = lds + stage * STAGE_BYTES + lgrp * PLANE_A + lrow * FRAG_BYTES;
-        const char *lb = lds + stage * STAGE_BYTES + KG * PLANE_A + lgrp * PLANE_B + lrow * FRAG_BYTES;
+        const char *la = lds + stage * STAGE_BYTES + lgrp * PLANE_A;
+        const char *lb = lds + stage * STAGE_BYTES + KG * PLANE_A + lgrp * PLANE_B;
 #if PIPELINED
         // k1, k2 fully unrolled: software pipeline over the NS = K1*K2 slots of this tile.  Slot s
         // first issues the LDS reads of slot s+1 and its share of the next tile's global loads, then
         // its own MFMAs; nothing is moved across a slot boundary.
         {
             frag_t fa[2][K3][TM], fb[2][K3][TN];
-            read_frags(fa[0], fb[0], la, lb, 0, wi, wj);
+            read_frags(fa[0], fb[0], la, lb, 0, wi, wj, lrow);
 #pragma unroll
             for (int s = 0; s < NS; ++s) {
-                if (s + 1 < NS) read_frags(fa[(s + 1) & 1], fb[(s + 1) & 1], la, lb, s + 1, wi, wj);
+                if (s + 1 < NS) read_frags(fa[(s + 1) & 1], fb[(s + 1) & 1], la, lb, s + 1, wi, wj, lrow);
 #if CACHE_READ == 2
                 // the last step fetches its own tile again instead of branching: the loop body stays one block
                 stage_load(st, A, B, i0, j0, k0 + 1 < K0 ? k0 + 1 : k0, tid, s * tile_stage::UNITS / NS, (s + 1) * tile_stage::UNITS / NS);
@@ -403,7 +422,7 @@ ms_kernel(const void *__restrict__ a_, const void *__restrict__ b_, const void *
 #pragma unroll UNROLL_K2
             for (int k2 = 0; k2 < K2; ++k2) {
                 frag_t fa[K3][TM], fb[K3][TN];
-                read_frags(fa, fb, la, lb, k1 * K2 + k2, wi, wj);
+                read_frags(fa, fb, la, lb, k1 * K2 + k2, wi, wj, lrow);
                 mfma_slot(acc, fa, fb);
             }
         }
@@ -426,6 +445,9 @@ ms_kernel(const void *__restrict__ a_, const void *__restrict__ b_, const void *
     // epilogue: (+bias, ReLU,) one rounding to the output type.
     // With the operands swapped a lane holds row `lrow` of the tile and, per group g of 4 accumulator
     // elements, the 4 consecutive columns 4*lgrp (16x16) or 8*g + 4*lgrp (32x32) onwards.
+    // CACHE_WRITE 0: those 4 values go to global memory as one vector.  CACHE_WRITE 1: the workgroup's
+    // tile is first assembled in LDS (the operand buffers are free: the k loop ended with a barrier) and
+    // then written as whole rows, 16 bytes per lane, consecutive lanes at consecutive addresses.
 #pragma unroll
     for (int r1 = 0; r1 < I1; ++r1)
 #pragma unroll
@@ -435,10 +457,11 @@ ms_kernel(const void *__restrict__ a_, const void *__restrict__ b_, const void *
 #pragma unroll
                 for (int c3 = 0; c3 < J3; ++c3) {
                     const int trow = (r1 * I2 + wi) * I3 + r3, tcol = (c1 * J2 + wj) * J3 + c3;
-                    const long row = (long)i0 * BM + trow * MI_M + lrow;
+                    const int lr = trow * MI_M + lrow; // row inside the workgroup tile
 #pragma unroll
                     for (int g = 0; g < ACC_N / 4; ++g) {
-                        const long col = (long)j0 * BN + tcol * MI_N + (MI_M == 16 ? 4 * lgrp : 8 * g + 4 * lgrp);
+                        const int lc = tcol * MI_N + (MI_M == 16 ? 4 * lgrp : 8 * g + 4 * lgrp); // column inside the tile
+                        const long col = (long)j0 * BN + lc;
                         vec_t<out_t, 4> o;
 #if HAS_BIAS
                         const vec_t<float, 4> bias = *reinterpret_cast<const vec_t<float, 4> *>((const float *)bias_ + col);
@@ -454,8 +477,27 @@ ms_kernel(const void *__restrict__ a_, const void *__restrict__ b_, const void *
 #endif
                             o.v[e] = from_acc(x);
                         }
-                        *reinterpret_cast<vec_t<out_t, 4> *>(C + row * DIM_N + col) = o;
+#if CACHE_WRITE
+                        *reinterpret_cast<vec_t<out_t, 4> *>(lds + lr * CROW + lc * (int)sizeof(out_t)) = o;
+#else
+                        *reinterpret_cast<vec_t<out_t, 4> *>(C + ((long)i0 * BM + lr) * DIM_N + col) = o;
+#endif
                     }
                 }
+#if CACHE_WRITE
+    __syncthreads();
+    {
+        constexpr int CHUNKS_PER_ROW = BN * (int)sizeof(out_t) / 16;
+        constexpr int TOTAL = BM * CHUNKS_PER_ROW;
+        typedef vec_t<unsigned, 4> chunk_t;
+#pragma unroll 4
+        for (int idx = tid; idx < TOTAL; idx += NTHREADS) {
+            const int row = idx / CHUNKS_PER_ROW, ch = idx % CHUNKS_PER_ROW;
+            const chunk_t v = *reinterpret_cast<const chunk_t *>(lds + row * CROW + ch * 16);
+            char *dst = (char *)(C + ((long)i0 * BM + row) * DIM_N + (long)j0 * BN) + ch * 16;
+            *reinterpret_cast<chunk_t *>(dst) = v;
+        }
+    }
+#endif
     (void)bias_;
 }

@@ -408,8 +408,8 @@ extern "C" int32_t ms_space_describe(const ms_op *op, uint32_t flags, ms_space *
     memset(out, 0, sizeof *out);
     const ms_op_desc &d = op->d;
     if (d.in_dtype == MS_F32) flags &= ~MS_SPACE_TENSORIZE;
-    if (d.kind == MS_OP_DWCONV2D_NHWC) flags &= ~(MS_SPACE_TENSORIZE | MS_SPACE_VECTORIZE | MS_SPACE_STORAGE_ALIGN | MS_SPACE_REORDER);
-    flags &= 0x3fu;
+    if (d.kind == MS_OP_DWCONV2D_NHWC) flags &= ~(MS_SPACE_TENSORIZE | MS_SPACE_VECTORIZE | MS_SPACE_STORAGE_ALIGN | MS_SPACE_REORDER | MS_SPACE_CACHE_WRITE);
+    flags &= 0x7fu;
     out->flags = flags;
     if (d.kind == MS_OP_DWCONV2D_NHWC) {
         out->family = MS_FAM_DWCONV;
@@ -457,13 +457,21 @@ extern "C" int32_t ms_space_describe(const ms_op *op, uint32_t flags, ms_space *
         if (flags & MS_SPACE_UNROLL) add_cat(out, MS_SLOT_UNROLL, "unroll", {0, 16, 64});
         if (flags & MS_SPACE_CACHE_READ) add_cat(out, MS_SLOT_CACHE_READ, "cache_read", {1, 2});
         if (flags & MS_SPACE_VECTORIZE) {
-            if (d.in_dtype == MS_I8) add_cat(out, MS_SLOT_VECTORIZE, "vectorize", {1, 4, 8, 16});
-            else add_cat(out, MS_SLOT_VECTORIZE, "vectorize", {1, 2, 4, 8});
+            if (d.in_dtype == MS_I8) {
+                add_cat(out, MS_SLOT_VECTORIZE, "vectorize", {1, 4, 8, 16});
+                add_cat(out, MS_SLOT_VECTORIZE_B, "vectorize_b", {1, 4, 8, 16});
+            } else {
+                add_cat(out, MS_SLOT_VECTORIZE, "vectorize", {1, 2, 4, 8});
+                add_cat(out, MS_SLOT_VECTORIZE_B, "vectorize_b", {1, 2, 4, 8});
+            }
         }
-        if (flags & MS_SPACE_STORAGE_ALIGN) add_cat(out, MS_SLOT_STORAGE_ALIGN, "storage_align", {0, 1});
+        if (flags & MS_SPACE_STORAGE_ALIGN) add_cat(out, MS_SLOT_STORAGE_ALIGN, "storage_align", {0, 1, 2});
         if (flags & MS_SPACE_REORDER) add_cat(out, MS_SLOT_REORDER, "reorder", {0, 1, 2});
+        if (flags & MS_SPACE_CACHE_WRITE) add_cat(out, MS_SLOT_CACHE_WRITE, "cache_write", {0, 1});
         return MS_OK;
     }
+    flags &= ~MS_SPACE_CACHE_WRITE;
+    out->flags = flags;
     if (d.kind == MS_OP_CONV2D_NHWC)
         return fail(MS_ERR_UNSUPPORTED, "ms_space_describe: conv2d needs the tensorize module (fp16/bf16 inputs)");
     out->family = MS_FAM_GEMM_ALU;
@@ -472,7 +480,10 @@ extern "C" int32_t ms_space_describe(const ms_op *op, uint32_t flags, ms_space *
     add_tile(out, MS_SLOT_TILE_K, "k", op->K);
     if (flags & MS_SPACE_UNROLL) add_cat(out, MS_SLOT_UNROLL, "unroll", {0, 16, 64});
     if (flags & MS_SPACE_CACHE_READ) add_cat(out, MS_SLOT_CACHE_READ, "cache_read", {0, 1, 2});
-    if (flags & MS_SPACE_VECTORIZE) add_cat(out, MS_SLOT_VECTORIZE, "vectorize", {1, 2, 4});
+    if (flags & MS_SPACE_VECTORIZE) {
+        add_cat(out, MS_SLOT_VECTORIZE, "vectorize", {1, 2, 4});
+        add_cat(out, MS_SLOT_VECTORIZE_B, "vectorize_b", {1, 2, 4});
+    }
     if (flags & MS_SPACE_STORAGE_ALIGN) add_cat(out, MS_SLOT_STORAGE_ALIGN, "storage_align", {0, 1});
     if (flags & MS_SPACE_REORDER) add_cat(out, MS_SLOT_REORDER, "reorder", {0, 1, 2});
     return MS_OK;
@@ -748,9 +759,11 @@ extern "C" int32_t ms_trace_to_text(const ms_op *op, const ms_space *space, cons
         }
         if (p.cache_read) {
             appendf(s, "cache-read(buffers=[A, B], scope=lds, at=k0, stages=%d)\n", p.cache_read);
-            appendf(s, "storage-align(scope=lds, pad_bytes=%d)\n", p.lds_pad * 16);
+            appendf(s, "storage-align(scope=lds, pad_bytes=%d, swizzle=%d)\n", p.lds_pad ? 16 : 0, p.lds_pad == 2);
         }
-        if (p.vec > 1) appendf(s, "vectorize(global loads, width=%d)\n", p.vec);
+        if (p.cache_write) appendf(s, "cache-write(buffer=C, scope=lds)\n");
+        if (p.vec > 1) appendf(s, "vectorize(global loads of A, width=%d)\n", p.vec);
+        if (p.vec_b > 1) appendf(s, "vectorize(global loads of B, width=%d)\n", p.vec_b);
         appendf(s, "unroll(k1, factor=%d)\nunroll(k2, factor=%d)\n", p.unroll_k1, p.unroll_k2);
         appendf(s, "# workgroup=%d threads, grid=%d, lds=%d B, acc/lane=%d\n", p.threads, p.grid[0] * p.grid[1] * p.grid[2], p.lds_bytes,
                 p.acc_per_thread);

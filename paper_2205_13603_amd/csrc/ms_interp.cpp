@@ -73,6 +73,8 @@ uint64_t hash_params(const ms_op *op, const ms_variant_params *p)
     }
     add((uint64_t)p->cache_read);
     add((uint64_t)p->vec);
+    add((uint64_t)p->vec_b);
+    add((uint64_t)p->cache_write);
     add((uint64_t)p->unroll_k1);
     add((uint64_t)p->unroll_k2);
     add((uint64_t)p->unroll);
@@ -145,6 +147,8 @@ extern "C" int32_t ms_trace_validate(const ms_op *op, const ms_space *space, con
     const ms_limits &L = g_limits;
     p.unroll = (int32_t)cat_value(space, trace, MS_SLOT_UNROLL, 0);
     p.vec = (int32_t)cat_value(space, trace, MS_SLOT_VECTORIZE, 1);
+    p.vec_b = (int32_t)cat_value(space, trace, MS_SLOT_VECTORIZE_B, 1);
+    p.cache_write = (int32_t)cat_value(space, trace, MS_SLOT_CACHE_WRITE, 0);
     p.lds_pad = (int32_t)cat_value(space, trace, MS_SLOT_STORAGE_ALIGN, 0);
     p.reorder = (int32_t)cat_value(space, trace, MS_SLOT_REORDER, 0);
 
@@ -198,8 +202,15 @@ extern "C" int32_t ms_trace_validate(const ms_op *op, const ms_space *space, con
         int64_t lds = 0;
         if (p.mfma) {
             int kp = p.tile_unit[2] / (L.wave_size / p.tile_unit[0]); // k elements one lane feeds per intrinsic
-            int64_t rowsA = bm * kp * es + p.lds_pad * 16, rowsB = bn * kp * es + p.lds_pad * 16;
+            int64_t padb = p.lds_pad ? 16 : 0;
+            int64_t rowsA = bm * kp * es + padb, rowsB = bn * kp * es + padb;
             lds = (int64_t)p.cache_read * (bk / kp) * (rowsA + rowsB);
+            if (p.cache_write) {
+                // the output tile reuses the operand buffers: rows of bn outputs padded by 16 bytes
+                int64_t ctile = bm * (bn * op->out_size + 16);
+                if (ctile > lds) lds = ctile;
+                if ((op->N * op->out_size) % 16) return reject("cache_write needs output rows that are multiples of 16 bytes");
+            }
             // fragment operands of one k step for the whole wave tile live in registers too
             int64_t frag = ((int64_t)p.ti[1] * p.ti[3] + (int64_t)p.tj[1] * p.tj[3]) * p.tk[3] * (kp * es / 4 > 0 ? kp * es / 4 : 1);
             // with k1 and k2 fully unrolled the kernel is software pipelined: two fragment sets are live
@@ -211,7 +222,7 @@ extern "C" int32_t ms_trace_validate(const ms_op *op, const ms_space *space, con
                 return reject("%" PRId64 " fragment + %" PRId64 " staging + %" PRId64 " accumulator registers per lane exceed the register file", frag, stage, acc);
         } else if (p.cache_read) {
             int stages = p.cache_read;
-            lds = (int64_t)stages * 4 * (bm * (bk + p.lds_pad * 4) + bk * (bn + p.lds_pad * 4));
+            lds = (int64_t)stages * 4 * (bm * (bk + (p.lds_pad ? 4 : 0)) + bk * (bn + (p.lds_pad ? 4 : 0)));
             int64_t frag = ((int64_t)p.ti[1] * p.ti[3] + (int64_t)p.tj[1] * p.tj[3]) * p.tk[3];
             if (frag + acc > 448) return reject("%" PRId64 " operand + %" PRId64 " accumulator registers per lane exceed the register file", frag, acc);
         } else {
@@ -221,28 +232,33 @@ extern "C" int32_t ms_trace_validate(const ms_op *op, const ms_space *space, con
         }
         if (lds > L.max_lds_bytes) return reject("LDS tile needs %" PRId64 " bytes, the limit is %d", lds, L.max_lds_bytes);
         p.lds_bytes = (int32_t)lds;
-        // vectorize: alignment and divisibility of the global loads
+        // vectorize: alignment and divisibility of the global loads, per operand
         if (p.vec > 1) {
             int v = p.vec;
             if (v * es > 16) return reject("vector of %d x %d bytes is wider than a 16-byte load", v, es);
             if (d.kind == MS_OP_CONV2D_NHWC) {
                 if (d.dims[3] % v) return reject("vector width %d does not divide Cin = %" PRId64, v, d.dims[3]);
-                if (d.dims[4] % v) return reject("vector width %d does not divide Cout = %" PRId64, v, d.dims[4]);
                 if (bk % v) return reject("vector width %d does not divide the k tile %" PRId64, v, bk);
             } else {
-                // A: vector along k
                 if (d.a_strides[2] != 1) return reject("vector loads of A need k contiguous");
                 if (bk % v || d.a_strides[1] % v || (op->nb > 1 && d.a_strides[0] % v))
                     return reject("vector width %d breaks alignment of A (k tile %" PRId64 ", row stride %" PRId64 ")", v, bk, d.a_strides[1]);
-                if (d.b_strides[2] == 1) { // vector along j
-                    if (bn % v || d.b_strides[1] % v || (op->nb > 1 && d.b_strides[0] % v))
-                        return reject("vector width %d breaks alignment of B (j tile %" PRId64 ", row stride %" PRId64 ")", v, bn, d.b_strides[1]);
-                } else if (d.b_strides[1] == 1) { // vector along k
-                    if (bk % v || d.b_strides[2] % v || (op->nb > 1 && d.b_strides[0] % v))
-                        return reject("vector width %d breaks alignment of B (k tile %" PRId64 ", column stride %" PRId64 ")", v, bk, d.b_strides[2]);
-                } else {
-                    return reject("vector loads of B need j or k contiguous");
-                }
+            }
+        }
+        if (p.vec_b > 1) {
+            int v = p.vec_b;
+            if (v * es > 16) return reject("vector of %d x %d bytes is wider than a 16-byte load", v, es);
+            if (d.kind == MS_OP_CONV2D_NHWC) {
+                if (d.dims[4] % v) return reject("vector width %d does not divide Cout = %" PRId64, v, d.dims[4]);
+                if (bn % v) return reject("vector width %d does not divide the j tile %" PRId64, v, bn);
+            } else if (d.b_strides[2] == 1) { // vector along j
+                if (bn % v || d.b_strides[1] % v || (op->nb > 1 && d.b_strides[0] % v))
+                    return reject("vector width %d breaks alignment of B (j tile %" PRId64 ", row stride %" PRId64 ")", v, bn, d.b_strides[1]);
+            } else if (d.b_strides[1] == 1) { // vector along k
+                if (bk % v || d.b_strides[2] % v || (op->nb > 1 && d.b_strides[0] % v))
+                    return reject("vector width %d breaks alignment of B (k tile %" PRId64 ", column stride %" PRId64 ")", v, bk, d.b_strides[2]);
+            } else {
+                return reject("vector loads of B need j or k contiguous");
             }
         }
     } else if (space->family == MS_FAM_DWCONV) {
@@ -328,6 +344,8 @@ int32_t make_kernel_spec(const ms_op *op, const ms_variant_params *p, KernelSpec
     D.push_back(def("NTHREADS", p->threads));
     D.push_back(def("CACHE_READ", p->cache_read));
     D.push_back(def("VEC", p->vec));
+    D.push_back(def("VEC_B", p->vec_b > 0 ? p->vec_b : 1));
+    D.push_back(def("CACHE_WRITE", p->cache_write));
     D.push_back(def("UNROLL_K1", p->unroll_k1));
     D.push_back(def("UNROLL_K2", p->unroll_k2));
     D.push_back(def("LDS_PAD", p->lds_pad));

@@ -331,3 +331,28 @@ extern "C" int32_t ms_calibrate_stream(int32_t mode, const void *src, void *dst,
     *gbs = (double)bytes * (mode == 1 ? 2.0 : 1.0) / (ms_best * 1e-3) / 1e9;
     return MS_OK;
 }
+
+extern "C" int32_t ms_calibrate_lds(void *scratch, void *stream, double *bytes_per_clk_per_cu, double *gbs)
+{
+    if (!scratch || !bytes_per_clk_per_cu || !gbs) return fail(MS_ERR_BAD_ARG, "ms_calibrate_lds: NULL argument");
+    std::vector<std::string> defs = {"-DMODE=3", "-DCAL_DT=0"};
+    CalibKernel ck;
+    int32_t rc = load_calib(defs, mix64(0xCA11B3ull), &ck);
+    if (rc != MS_OK) return rc;
+    int dev = 0;
+    hipDeviceProp_t prop;
+    HIP_TRY(hipGetDevice(&dev));
+    HIP_TRY(hipGetDeviceProperties(&prop, dev));
+    unsigned grid = (unsigned)prop.multiProcessorCount * 2;
+    int iters = 20000;
+    const void *src = nullptr;
+    void *args[] = {&src, &src, &src, &scratch, &iters};
+    double ms_best = 0;
+    rc = time_launches(ck.fn, grid, args, (hipStream_t)stream, 3, &ms_best);
+    (void)hipModuleUnload(ck.mod);
+    if (rc != MS_OK) return rc;
+    double bytes = (double)grid * 256 * 16.0 * 8 * iters;
+    *gbs = bytes / (ms_best * 1e-3) / 1e9;
+    *bytes_per_clk_per_cu = bytes / (ms_best * 1e-3) / ((double)prop.clockRate * 1e3) / prop.multiProcessorCount;
+    return MS_OK;
+}

@@ -66,11 +66,14 @@ def test_c2_fp16_gemm_1024():
     space = op.space()
     traces = traces_covering_intrinsics(op, space, 0, 3, F16_INTRINS)
 
-    def mk(mfma, i, j, k, unroll=0, cache=2, vec=8, pad=0, reorder=0):
-        return B.make_trace(space, [[mfma], i, j, k, [unroll], [cache], [vec], [pad], [reorder]])
+    def mk(mfma, i, j, k, unroll=0, cache=2, vec=8, vec_b=8, pad=0, reorder=0, cw=0):
+        return B.make_trace(space, [[mfma], i, j, k, [unroll], [cache], [vec], [vec_b], [pad], [reorder], [cw]])
 
     traces.append(mk(323216, [4, 2, 2, 2], [4, 2, 2, 2], [16, 1, 2, 2], unroll=16, pad=1, reorder=2))
-    traces.append(mk(161632, [8, 2, 2, 2], [8, 1, 2, 4], [8, 2, 2, 1], unroll=64, cache=1, vec=4))
+    traces.append(mk(323216, [4, 2, 2, 2], [4, 2, 2, 2], [16, 1, 4, 1], unroll=64, pad=2, reorder=2))  # software pipelined, swizzled
+    traces.append(mk(161632, [8, 2, 2, 2], [8, 1, 2, 4], [8, 2, 2, 1], unroll=64, cache=1, vec=4, vec_b=2))
+    traces.append(mk(161632, [4, 4, 4, 1], [8, 4, 2, 1], [16, 2, 1, 1], unroll=16, cache=1, vec=8, vec_b=2, pad=2, reorder=1))
+    traces.append(mk(323216, [4, 1, 2, 4], [4, 1, 8, 1], [16, 1, 1, 4], vec=8, vec_b=1, pad=1, reorder=2, cw=1))
     ref = None
     for n, t in enumerate(traces):
         print("trace", n, t.decisions(), flush=True)

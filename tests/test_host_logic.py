@@ -90,7 +90,7 @@ def test_space_composition_by_flags():
     assert op.space(B.SPACE_UNROLL).family == B.FAM_GEMM_ALU
     assert slot_names(op.space(0)) == ["i", "j", "k"]
     sp = op.space()
-    assert slot_names(sp) == ["i", "j", "k", "unroll", "cache_read", "vectorize", "storage_align", "reorder"]
+    assert slot_names(sp) == ["i", "j", "k", "unroll", "cache_read", "vectorize", "vectorize_b", "storage_align", "reorder"]
     un = sp.slots[3]
     assert [un.candidates[i] for i in range(un.n_candidates)] == [0, 16, 64]
     op = B.gemm_op(1024, 1024, 1024, "f16")
@@ -231,8 +231,8 @@ def test_validator_rejections():
     op = B.gemm_op(128, 128, 128, "f32")
     sp = op.space()
 
-    def mk(i, j, k, unroll=0, cache=1, vec=1, pad=0, reorder=0):
-        return B.make_trace(sp, [i, j, k, [unroll], [cache], [vec], [pad], [reorder]])
+    def mk(i, j, k, unroll=0, cache=1, vec=1, vec_b=1, pad=0, reorder=0):
+        return B.make_trace(sp, [i, j, k, [unroll], [cache], [vec], [vec_b], [pad], [reorder]])
 
     ok = mk([4, 2, 8, 2], [4, 2, 16, 1], [4, 4, 4, 2])
     p = B.trace_validate(op, sp, ok)
@@ -261,8 +261,9 @@ def test_validator_rejections():
     bad = ok.copy()
     bad.d[1].slot_id = 99
     rejected(bad, "slot id")
-    # vector width must divide the contiguous tile extent: BK = 2 with 4-wide loads
+    # vector width must divide the contiguous tile extent: BK = 2 with 4-wide loads of A; BN = 2 for B
     rejected(mk([4, 2, 8, 2], [4, 2, 16, 1], [64, 1, 1, 2], vec=4), "vector width")
+    rejected(mk([4, 2, 8, 2], [64, 1, 2, 1], [4, 4, 4, 2], vec_b=4), "vector width")
     # forced smaller hardware limits reject what passed before, and are restorable
     lim = B.get_limits()
     small = B.ms_limits(64, 4096, 16, 64, 2)
@@ -278,8 +279,8 @@ def test_validator_mfma_rules():
     op = B.gemm_op(1024, 1024, 1024, "f16")
     sp = op.space()
 
-    def mk(mfma, i, j, k, unroll=0, cache=2, vec=8, pad=0, reorder=0):
-        return B.make_trace(sp, [[mfma], i, j, k, [unroll], [cache], [vec], [pad], [reorder]])
+    def mk(mfma, i, j, k, unroll=0, cache=2, vec=8, vec_b=8, pad=0, reorder=0, cw=0):
+        return B.make_trace(sp, [[mfma], i, j, k, [unroll], [cache], [vec], [vec_b], [pad], [reorder], [cw]])
 
     p = B.trace_validate(op, sp, mk(323216, [4, 2, 2, 2], [4, 2, 2, 2], [16, 1, 2, 2]))
     assert (p.block_m, p.block_n, p.block_k) == (256, 256, 64) and p.waves == 4 and p.threads == 256

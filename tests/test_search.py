@@ -43,9 +43,13 @@ def test_search_finds_known_optimum_within_budget():
 
 
 def test_search_beats_random_sampling():
-    op, sp, res, _ = run(seed=1, trials=128)
-    best_random = min(synthetic_latency(B.trace_validate(op, sp, B.trace_sample_valid(op, sp, 1, i))) for i in range(128))
-    assert res.best_us < best_random
+    """Same number of measured candidates, summed over six seeds (a single seed is a coin with a bias)."""
+    tot_search, tot_random = 0.0, 0.0
+    for seed in range(6):
+        op, sp, res, _ = run(seed=seed, trials=128)
+        tot_search += res.best_us
+        tot_random += min(synthetic_latency(B.trace_validate(op, sp, B.trace_sample_valid(op, sp, seed, i))) for i in range(128))
+    assert tot_search < 0.9 * tot_random, (tot_search, tot_random)
 
 
 def test_search_same_seed_same_trials():
