@@ -75,6 +75,9 @@ BOUND = {  # which roofline bounds the workload (AI vs ridge), and the in-dtype
 }
 
 
+PROFILE_NAME = {"c2_gemm_f16_1024": "gemm_mfma_c2_gemm_f16_1024"}
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -202,6 +205,14 @@ def main():
     l2 = v.measure(inst_sets, warmup=5, repeats=5, launches_per_repeat=max(200, R), instances=1, stream=stream)
     per1 = (bytes1 / 1e9) if bound == "hbm" else (flop1 / 1e12)
 
+    # HBM bytes per launch from the committed rocprofv3 counter summary of this very variant (stored record)
+    traffic = None
+    prof = os.path.join(ROOT, "profiles", "ms_kernel_%s.txt" % PROFILE_NAME.get(name, name))
+    if best[2] == "record" and R == default_r and os.path.exists(prof):
+        for line in open(prof):
+            if line.startswith("traffic_bytes_per_launch:"):
+                traffic = float(line.split(":")[1])
+
     out = {
         "metric": METRIC, "value": value, "unit": unit, "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
@@ -214,7 +225,7 @@ def main():
                                "ti": list(params.ti), "tj": list(params.tj), "tk": list(params.tk), "tc": list(params.tc),
                                "unroll": params.unroll}},
         "roofline": {"bound": bound, "achieved": achieved, "peak": peak, "unit": unit, "frac": achieved / peak,
-                     "traffic": None, "kernel_us": kernel_us},
+                     "traffic": traffic, "kernel_us": kernel_us},
         "single_instance": {"single_launch_us": l1.median_us, "steady_state_us": l2.median_us,
                             "steady_state_" + ("gbs" if bound == "hbm" else "tflops"): per1 / (l2.median_us * 1e-6),
                             "rotating_sets": R},

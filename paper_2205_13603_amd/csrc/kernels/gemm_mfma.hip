@@ -9,7 +9,8 @@
 //   bind    fuse(i0,j0) -> blockIdx.x, fuse(i2,j2) -> wavefront of the workgroup
 //   cache-read A,B tiles of one k0 step into LDS (CACHE_READ 1: one buffer;
 //           2: two buffers, the next tile is fetched into registers while the
-//           current one is multiplied)
+//           current one is multiplied; 3: two buffers and two register sets, the
+//           tile two steps ahead is in flight)
 //   storage-align: LDS_PAD 1, 2: each LDS plane padded by 16 bytes; 2: slots of a plane XOR-swizzled
 //   vectorize: global loads of VEC (A) and VEC_B (B) elements
 //   cache-write (CACHE_WRITE 1): the output tile is assembled in LDS and stored as whole rows
@@ -53,7 +54,7 @@ __device__ __forceinline__ int lds_slot(int n)
 #endif
 }
 constexpr int STAGE_BYTES = KG * (PLANE_A + PLANE_B);
-constexpr int STAGES = CACHE_READ == 2 ? 2 : 1;
+constexpr int STAGES = CACHE_READ >= 2 ? 2 : 1;
 constexpr int KSTEPS = K1 * K2 * K3;              // MFMA k steps per tile
 
 static_assert(MI_M == MI_N, "square intrinsics only");
@@ -347,8 +348,24 @@ __device__ __forceinline__ void mfma_slot(accv_t (&acc)[TM][TN], const frag_t (&
             for (int tn = 0; tn < TN; ++tn) acc[tm][tn] = mfma(fb[q][tn], fa[q][tm], acc[tm][tn]);
 }
 
+// multiply the tile staged at `stage_base` (rolled / partly unrolled k1, k2 loops)
+__device__ __forceinline__ void multiply_tile(accv_t (&acc)[TM][TN], const char *__restrict__ stage_base, int lgrp, int wi, int wj, int lrow)
+{
+    const char *la = stage_base + lgrp * PLANE_A;
+    const char *lb = stage_base + KG * PLANE_A + lgrp * PLANE_B;
+#pragma unroll UNROLL_K1
+    for (int k1 = 0; k1 < K1; ++k1) {
+#pragma unroll UNROLL_K2
+        for (int k2 = 0; k2 < K2; ++k2) {
+            frag_t fa[K3][TM], fb[K3][TN];
+            read_frags(fa, fb, la, lb, k1 * K2 + k2, wi, wj, lrow);
+            mfma_slot(acc, fa, fb);
+        }
+    }
+}
+
 constexpr int NS = K1 * K2;
-#define PIPELINED (UNROLL_K1 == K1 && UNROLL_K2 == K2 && K1 * K2 > 1)
+#define PIPELINED (CACHE_READ != 3 && UNROLL_K1 == K1 && UNROLL_K2 == K2 && K1 * K2 > 1)
 
 extern "C" __global__ void __launch_bounds__(NTHREADS)
 ms_kernel(const void *__restrict__ a_, const void *__restrict__ b_, const void *__restrict__ bias_, void *__restrict__ c_, int instances)
@@ -378,6 +395,32 @@ ms_kernel(const void *__restrict__ a_, const void *__restrict__ b_, const void *
 #pragma unroll
             for (int e = 0; e < ACC_N; ++e) acc[tm][tn][e] = 0;
 
+#if CACHE_READ == 3
+    // Two LDS buffers and two register sets: the tile of step k+2 is requested while step k is
+    // multiplied, so a global load has two whole steps to arrive.  The k0 loop advances by two
+    // steps per iteration so that each register set has a fixed name; tile indices beyond the
+    // last are clamped (a harmless re-load) instead of branching.
+    {
+        tile_stage st0, st1;
+        stage_load(st0, A, B, i0, j0, 0, tid);
+        stage_load(st1, A, B, i0, j0, K0 > 1 ? 1 : 0, tid);
+        stage_store(st0, lds, tid);
+        __syncthreads();
+#pragma unroll 1
+        for (int k0 = 0; k0 < K0; k0 += 2) {
+            stage_load(st0, A, B, i0, j0, k0 + 2 < K0 ? k0 + 2 : K0 - 1, tid);
+            multiply_tile(acc, lds, lgrp, wi, wj, lrow);
+            stage_store(st1, lds + STAGE_BYTES, tid);
+            __syncthreads();
+            if (k0 + 1 < K0) {
+                stage_load(st1, A, B, i0, j0, k0 + 3 < K0 ? k0 + 3 : K0 - 1, tid);
+                multiply_tile(acc, lds + STAGE_BYTES, lgrp, wi, wj, lrow);
+                stage_store(st0, lds, tid);
+                __syncthreads();
+            }
+        }
+    }
+#else
     tile_stage st;
     int stage = 0;
 #if CACHE_READ == 2
@@ -441,6 +484,8 @@ ms_kernel(const void *__restrict__ a_, const void *__restrict__ b_, const void *
         stage ^= 1;
 #endif
     }
+
+#endif // CACHE_READ != 3
 
     // epilogue: (+bias, ReLU,) one rounding to the output type.
     // With the operands swapped a lane holds row `lrow` of the tile and, per group g of 4 accumulator

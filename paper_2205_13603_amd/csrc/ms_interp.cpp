@@ -204,7 +204,7 @@ extern "C" int32_t ms_trace_validate(const ms_op *op, const ms_space *space, con
             int kp = p.tile_unit[2] / (L.wave_size / p.tile_unit[0]); // k elements one lane feeds per intrinsic
             int64_t padb = p.lds_pad ? 16 : 0;
             int64_t rowsA = bm * kp * es + padb, rowsB = bn * kp * es + padb;
-            lds = (int64_t)p.cache_read * (bk / kp) * (rowsA + rowsB);
+            lds = (int64_t)(p.cache_read >= 2 ? 2 : 1) * (bk / kp) * (rowsA + rowsB);
             if (p.cache_write) {
                 // the output tile reuses the operand buffers: rows of bn outputs padded by 16 bytes
                 int64_t ctile = bm * (bn * op->out_size + 16);
@@ -217,7 +217,7 @@ extern "C" int32_t ms_trace_validate(const ms_op *op, const ms_space *space, con
             if (p.unroll_k1 == p.tk[1] && p.unroll_k2 == p.tk[2] && p.tk[1] * p.tk[2] > 1) frag *= 2;
             // registers that carry a tile from global memory to LDS; with two buffers they are live across the k step
             int64_t stage = (bm * bk * es / 4 + p.threads - 1) / p.threads + (bn * bk * es / 4 + p.threads - 1) / p.threads;
-            int64_t live = p.cache_read == 2 ? frag + stage : std::max(frag, stage);
+            int64_t live = p.cache_read == 3 ? frag + 2 * stage : (p.cache_read == 2 ? frag + stage : std::max(frag, stage));
             if (live + acc > 480)
                 return reject("%" PRId64 " fragment + %" PRId64 " staging + %" PRId64 " accumulator registers per lane exceed the register file", frag, stage, acc);
         } else if (p.cache_read) {
