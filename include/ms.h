@@ -149,7 +149,8 @@ typedef enum ms_slot_id {
     MS_SLOT_UNROLL = 5,    /* categorical: unroll budget, candidates {0,16,64} */
     MS_SLOT_CACHE_READ = 6,/* categorical: 0 = operands read from global memory,
                               1 = staged in LDS, 2 = staged in LDS, double buffered,
-                              3 (matrix-core kernels) = double buffered, prefetch two tiles ahead */
+                              3 (matrix-core kernels) = double buffered, prefetch two tiles ahead,
+                              4 (matrix-core kernels) = double buffered, two wavefront groups half a step apart */
     MS_SLOT_VECTORIZE = 7, /* categorical: elements per global load instruction of operand A (conv: X) */
     MS_SLOT_STORAGE_ALIGN = 8, /* categorical: LDS layout: 0 = dense, 1 = each row / plane padded by 16 bytes,
                               2 (matrix-core kernels) = padded, and the 16-byte slots of a plane XOR-swizzled */
@@ -277,7 +278,7 @@ typedef struct ms_variant_params {
     int32_t waves;
     int32_t acc_per_thread; /* accumulator registers per lane */
     int32_t lds_bytes;
-    int32_t cache_read;     /* 0, 1, 2, 3 as in MS_SLOT_CACHE_READ */
+    int32_t cache_read;     /* 0 .. 4 as in MS_SLOT_CACHE_READ */
     int32_t vec;            /* elements per global load of A (depthwise: channels per access) */
     int32_t unroll;         /* budget */
     int32_t unroll_k1, unroll_k2; /* unroll factors of the two rolled reduction loops */

@@ -10,7 +10,9 @@
 //   cache-read A,B tiles of one k0 step into LDS (CACHE_READ 1: one buffer;
 //           2: two buffers, the next tile is fetched into registers while the
 //           current one is multiplied; 3: two buffers and two register sets, the
-//           tile two steps ahead is in flight)
+//           tile two steps ahead is in flight; 4: two buffers, the wavefronts split
+//           into two groups half a step apart so that one group's memory phase
+//           runs under the other's MFMA phase)
 //   storage-align: LDS_PAD 1, 2: each LDS plane padded by 16 bytes; 2: slots of a plane XOR-swizzled
 //   vectorize: global loads of VEC (A) and VEC_B (B) elements
 //   cache-write (CACHE_WRITE 1): the output tile is assembled in LDS and stored as whole rows
@@ -365,7 +367,7 @@ __device__ __forceinline__ void multiply_tile(accv_t (&acc)[TM][TN], const char 
 }
 
 constexpr int NS = K1 * K2;
-#define PIPELINED (CACHE_READ != 3 && UNROLL_K1 == K1 && UNROLL_K2 == K2 && K1 * K2 > 1)
+#define PIPELINED (CACHE_READ < 3 && UNROLL_K1 == K1 && UNROLL_K2 == K2 && K1 * K2 > 1)
 
 extern "C" __global__ void __launch_bounds__(NTHREADS)
 ms_kernel(const void *__restrict__ a_, const void *__restrict__ b_, const void *__restrict__ bias_, void *__restrict__ c_, int instances)
@@ -419,6 +421,38 @@ ms_kernel(const void *__restrict__ a_, const void *__restrict__ b_, const void *
                 __syncthreads();
             }
         }
+    }
+#elif CACHE_READ == 4
+    // Ping-pong: the wavefronts form two groups that run the same code half a step apart.  A step is
+    // a memory phase (LDS reads of all fragments of the current tile, LDS writes of the next tile,
+    // global loads of the tile after it), a barrier, an MFMA phase, a barrier.  The second group
+    // passes one extra barrier before the loop, so while one group multiplies the other moves data;
+    // the first group passes the matching extra barrier after the loop.  (K1 = K2 = 1: a tile's
+    // fragments are all in registers when its MFMA phase starts.)
+    {
+        tile_stage st;
+        const bool late = wave >= NWAVES / 2;
+        stage_load(st, A, B, i0, j0, 0, tid);
+        stage_store(st, lds, tid);
+        stage_load(st, A, B, i0, j0, K0 > 1 ? 1 : 0, tid);
+        __syncthreads();
+        if (late) __builtin_amdgcn_s_barrier();
+        int stage = 0;
+#pragma unroll 1
+        for (int k0 = 0; k0 < K0; ++k0) {
+            frag_t fa[K3][TM], fb[K3][TN];
+            const char *base = lds + stage * STAGE_BYTES;
+            read_frags(fa, fb, base + lgrp * PLANE_A, base + KG * PLANE_A + lgrp * PLANE_B, 0, wi, wj, lrow);
+            stage_store(st, lds + (stage ^ 1) * STAGE_BYTES, tid);
+            stage_load(st, A, B, i0, j0, k0 + 2 < K0 ? k0 + 2 : K0 - 1, tid);
+            __syncthreads();
+            __builtin_amdgcn_s_setprio(1);
+            mfma_slot(acc, fa, fb);
+            __builtin_amdgcn_s_setprio(0);
+            __syncthreads();
+            stage ^= 1;
+        }
+        if (!late) __builtin_amdgcn_s_barrier();
     }
 #else
     tile_stage st;

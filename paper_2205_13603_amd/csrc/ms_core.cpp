@@ -455,7 +455,7 @@ extern "C" int32_t ms_space_describe(const ms_op *op, uint32_t flags, ms_space *
             }
         }
         if (flags & MS_SPACE_UNROLL) add_cat(out, MS_SLOT_UNROLL, "unroll", {0, 16, 64});
-        if (flags & MS_SPACE_CACHE_READ) add_cat(out, MS_SLOT_CACHE_READ, "cache_read", {1, 2, 3});
+        if (flags & MS_SPACE_CACHE_READ) add_cat(out, MS_SLOT_CACHE_READ, "cache_read", {1, 2, 3, 4});
         if (flags & MS_SPACE_VECTORIZE) {
             if (d.in_dtype == MS_I8) {
                 add_cat(out, MS_SLOT_VECTORIZE, "vectorize", {1, 4, 8, 16});
@@ -758,7 +758,8 @@ extern "C" int32_t ms_trace_to_text(const ms_op *op, const ms_space *space, cons
             appendf(s, "bind(fuse(i2, j2), %s)\n", p.mfma ? "wavefront" : "threadIdx.x");
         }
         if (p.cache_read) {
-            appendf(s, "cache-read(buffers=[A, B], scope=lds, at=k0, stages=%d, prefetch_distance=%d)\n", p.cache_read >= 2 ? 2 : 1, p.cache_read - 1);
+            appendf(s, "cache-read(buffers=[A, B], scope=lds, at=k0, stages=%d, prefetch_distance=%d)\n", p.cache_read >= 2 ? 2 : 1, p.cache_read == 3 ? 2 : (p.cache_read >= 2 ? 1 : 0));
+            if (p.cache_read == 4) appendf(s, "annotate(block=C, key=wave_groups, value=ping_pong)\n");
             appendf(s, "storage-align(scope=lds, pad_bytes=%d, swizzle=%d)\n", p.lds_pad ? 16 : 0, p.lds_pad == 2);
         }
         if (p.cache_write) appendf(s, "cache-write(buffer=C, scope=lds)\n");

@@ -213,13 +213,18 @@ extern "C" int32_t ms_trace_validate(const ms_op *op, const ms_space *space, con
             }
             // fragment operands of one k step for the whole wave tile live in registers too
             int64_t frag = ((int64_t)p.ti[1] * p.ti[3] + (int64_t)p.tj[1] * p.tj[3]) * p.tk[3] * (kp * es / 4 > 0 ? kp * es / 4 : 1);
-            // with k1 and k2 fully unrolled the kernel is software pipelined: two fragment sets are live
-            if (p.unroll_k1 == p.tk[1] && p.unroll_k2 == p.tk[2] && p.tk[1] * p.tk[2] > 1) frag *= 2;
             // registers that carry a tile from global memory to LDS; with two buffers they are live across the k step
             int64_t stage = (bm * bk * es / 4 + p.threads - 1) / p.threads + (bn * bk * es / 4 + p.threads - 1) / p.threads;
-            int64_t live = p.cache_read == 3 ? frag + 2 * stage : (p.cache_read == 2 ? frag + stage : std::max(frag, stage));
-            if (live + acc > 480)
-                return reject("%" PRId64 " fragment + %" PRId64 " staging + %" PRId64 " accumulator registers per lane exceed the register file", frag, stage, acc);
+            int64_t live = p.cache_read == 3 ? frag + 2 * stage : (p.cache_read >= 2 ? frag + stage : std::max(frag, stage));
+            if (p.cache_read == 4) {
+                if (p.waves % 2) return reject("ping-pong wave groups need an even number of wavefronts, not %d", p.waves);
+                if (p.tk[1] != 1 || p.tk[2] != 1) return reject("ping-pong wave groups need k1 = k2 = 1 (a tile's fragments are read in one phase)");
+            }
+            // a SIMD's 512 registers per lane are shared by the workgroup's wavefronts resident on it
+            int64_t budget = 512 / ((p.waves + 3) / 4);
+            if (live + acc > budget)
+                return reject("%" PRId64 " fragment + %" PRId64 " staging + %" PRId64 " accumulator registers per lane exceed the %" PRId64
+                              " a wavefront can have with %d wavefronts per workgroup", frag, stage, acc, budget, p.waves);
         } else if (p.cache_read) {
             int stages = p.cache_read;
             lds = (int64_t)stages * 4 * (bm * (bk + (p.lds_pad ? 4 : 0)) + bk * (bn + (p.lds_pad ? 4 : 0)));

@@ -76,6 +76,8 @@ def test_c2_fp16_gemm_1024():
     traces.append(mk(323216, [4, 1, 2, 4], [4, 1, 8, 1], [16, 1, 1, 4], vec=8, vec_b=1, pad=1, reorder=2, cw=1))
     traces.append(mk(323216, [4, 1, 2, 4], [4, 1, 8, 1], [16, 1, 1, 4], cache=3, vec=8, vec_b=2, pad=1, reorder=2, cw=1))
     traces.append(mk(161632, [8, 2, 2, 2], [8, 1, 2, 4], [32, 1, 1, 1], cache=3, vec=8, vec_b=4, pad=2))
+    traces.append(mk(323216, [4, 1, 4, 2], [4, 2, 2, 2], [16, 1, 1, 4], cache=4, vec=8, vec_b=4, pad=1, reorder=2, cw=1))  # ping-pong
+    traces.append(mk(161632, [8, 2, 2, 2], [8, 1, 2, 4], [16, 1, 1, 2], cache=4, vec=8, vec_b=2, pad=2))
     ref = None
     for n, t in enumerate(traces):
         print("trace", n, t.decisions(), flush=True)
