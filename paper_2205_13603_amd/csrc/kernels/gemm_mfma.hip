@@ -543,7 +543,7 @@ ms_kernel(const void *__restrict__ a_, const void *__restrict__ b_, const void *
                         const long col = (long)j0 * BN + lc;
                         vec_t<out_t, 4> o;
 #if HAS_BIAS
-                        const vec_t<float, 4> bias = *reinterpret_cast<const vec_t<float, 4> *>((const float *)bias_ + col);
+                        const vec_t<float, 4> bias = *reinterpret_cast<const vec_t<float, 4> *>((const float *)bias_ + (long)inst * DIM_N + col);
 #endif
 #pragma unroll
                         for (int e = 0; e < 4; ++e) {

@@ -11,3 +11,16 @@ def run_variant(op, space, trace, inputs, out_dtype, out_shape, instances=1):
     out = devmem.empty_output(out_shape, out_dtype, instances, poison=True)
     v.launch([d.data_ptr() for d in dev], out.data_ptr(), instances=instances, stream=devmem.current_stream())
     return devmem.to_host(out, out_dtype)
+
+
+def run_variant_distinct(op, space, trace, per_instance_inputs, out_dtype, out_shape):
+    """Like run_variant, but every instance has its own inputs: per_instance_inputs[r] = list of arrays."""
+    import numpy as np
+    v = B.Variant(op, space, trace)
+    if not devmem.gpu_available():
+        return None
+    R = len(per_instance_inputs)
+    dev = [devmem.to_device(np.stack([per_instance_inputs[r][k] for r in range(R)])) for k in range(len(per_instance_inputs[0]))]
+    out = devmem.empty_output(out_shape, out_dtype, R, poison=True)
+    v.launch([d.data_ptr() for d in dev], out.data_ptr(), instances=R, stream=devmem.current_stream())
+    return devmem.to_host(out, out_dtype)

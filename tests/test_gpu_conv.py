@@ -4,7 +4,7 @@ import pytest
 
 from oracle import compare, oracle as O
 from paper_2205_13603_amd import binding as B, inputs as I
-from gpu_util import run_variant
+from gpu_util import run_variant, run_variant_distinct
 from test_gpu_gemm_mfma import traces_covering_intrinsics, F16_INTRINS
 
 pytestmark = pytest.mark.gpu
@@ -49,3 +49,19 @@ def test_conv_other_geometries_exact(stride, pad, k, relu, has_bias):
         if got is None:
             continue
         assert np.array_equal(got[0], ref) and np.array_equal(got[1], ref), "trace %d" % n
+
+
+def test_conv_instances_with_distinct_inputs():
+    """Three instances, each with its own activations, weights and bias (every input is per instance)."""
+    ins = [list(I.c3(seed=s, H=14, W=16, Cin=16, Cout=32)) for s in (1, 2, 3)]
+    refs = [O.conv2d_nhwc(x, w, bias=b, relu=True, stride=1, pad=1) for x, w, b in ins]
+    op = B.conv2d_op(1, 14, 16, 16, 32, 3, 3, stride=1, pad=1)
+    space = op.space()
+    for n in range(5):
+        t = B.trace_sample_valid(op, space, 13, n)
+        print("trace", n, t.decisions(), flush=True)
+        got = run_variant_distinct(op, space, t, ins, "f16", (1, 14, 16, 32))
+        if got is None:
+            continue
+        for r in range(3):
+            compare.assert_float_close(got[r], refs[r], compare.RTOL_HALF, "instance %d trace %d" % (r, n))

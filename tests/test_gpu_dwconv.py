@@ -4,7 +4,7 @@ import pytest
 
 from oracle import compare, oracle as O
 from paper_2205_13603_amd import binding as B, inputs as I
-from gpu_util import run_variant
+from gpu_util import run_variant, run_variant_distinct
 
 pytestmark = pytest.mark.gpu
 
@@ -41,3 +41,17 @@ def test_depthwise_other_geometries_exact(stride, pad, k):
         if got is None:
             continue
         assert np.array_equal(got[0], ref) and np.array_equal(got[1], ref), "trace %d" % n
+
+
+def test_depthwise_instances_with_distinct_inputs():
+    ins = [list(I.dw_inputs(1, 12, 10, 8, seed=s)) for s in (5, 6, 7)]
+    refs = [O.dwconv2d_nhwc(x, w, stride=1, pad=1) for x, w in ins]
+    op = B.dwconv2d_op(1, 12, 10, 8)
+    space = op.space()
+    for n in range(5):
+        t = B.trace_sample_valid(op, space, 14, n)
+        got = run_variant_distinct(op, space, t, ins, "f32", (1, 12, 10, 8))
+        if got is None:
+            continue
+        for r in range(3):
+            compare.assert_float_close(got[r], refs[r], compare.RTOL_F32, "instance %d trace %d" % (r, n))

@@ -4,7 +4,7 @@ import pytest
 
 from oracle import compare, oracle as O
 from paper_2205_13603_amd import binding as B, inputs as I
-from gpu_util import run_variant
+from gpu_util import run_variant, run_variant_distinct
 
 pytestmark = pytest.mark.gpu
 
@@ -147,3 +147,17 @@ def test_int8_extremes():
         if got is None:
             continue
         assert np.all(got == 8388608)
+
+
+def test_bmm_instances_with_distinct_inputs():
+    ins = [list(I.c4b(seed=s, heads=2, seq=32, dim=16)) for s in (1, 2, 3)]
+    refs = [O.bmm(p, v) for p, v in ins]
+    op = B.bmm_op(2, 32, 16, 32, False, "f16")
+    space = op.space()
+    for n in range(5):
+        t = B.trace_sample_valid(op, space, 15, n)
+        got = run_variant_distinct(op, space, t, ins, "f16", (2, 32, 16))
+        if got is None:
+            continue
+        for r in range(3):
+            compare.assert_float_close(got[r], refs[r], compare.RTOL_HALF, "instance %d trace %d" % (r, n))
