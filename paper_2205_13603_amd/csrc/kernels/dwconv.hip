@@ -6,6 +6,7 @@
 //   reorder i0 j0 c0 | i2 j2 c2 | i1 j1 c1 | i3 j3 | kh kw | c3
 //   bind    fuse(i0,j0,c0) -> blockIdx.x (c fastest), fuse(i2,j2,c2) -> threadIdx.x (c fastest:
 //           neighbouring lanes touch neighbouring channels of one pixel = coalesced)
+//   reorder (REORDER 2): workgroup order grouped per XCD
 //   vectorize c3 (4 or 2 channels per load/store when 4 or 2 divides C3)
 //   cache-read (CACHE_READ 1): the workgroup's input halo tile is staged in LDS, zero padded
 //   unroll  the kh,kw tap loops (UNROLL_K1 == 0: fully, with the I3 x J3 output patch sharing one
@@ -43,13 +44,27 @@ extern "C" __global__ void __launch_bounds__(NTHREADS)
 ms_kernel(const void *__restrict__ x_, const void *__restrict__ w_, const void *__restrict__ unused_, void *__restrict__ y_, int instances)
 {
     (void)unused_;
-    const int z = blockIdx.z * gridDim.y + blockIdx.y; // instance * N + n
+    int z = blockIdx.z * gridDim.y + blockIdx.y; // instance * N + n
+    int wg = blockIdx.x;
+#if REORDER == 2
+    // undo the round-robin of workgroups over the 8 XCDs (workgroup f of the launch goes to XCD f mod 8):
+    // neighbouring tiles, which share halo rows and columns, then sit behind the same L2
+    {
+        constexpr int G = I0 * J0 * C0;
+        const long total = (long)G * gridDim.y * gridDim.z;
+        if (total % 8 == 0) {
+            const long f = wg + (long)G * z;
+            const long g = (f % 8) * (total / 8) + f / 8;
+            wg = (int)(g % G);
+            z = (int)(g / G);
+        }
+    }
+#endif
     if (z >= instances * CV_N) return;
     const float *__restrict__ X = (const float *)x_ + (long)z * CV_H * CV_W * CV_C;
     const float *__restrict__ Wt = (const float *)w_ + (long)(z / CV_N) * CV_KH * CV_KW * CV_C;
     float *__restrict__ Y = (float *)y_ + (long)z * CV_OH * CV_OW * CV_C;
 
-    const int wg = blockIdx.x;
     const int c0 = wg % C0, j0 = (wg / C0) % J0, i0 = wg / (C0 * J0);
     const int tid = threadIdx.x;
     const int tc = tid % C2, tj = (tid / C2) % J2, ti = tid / (C2 * J2);

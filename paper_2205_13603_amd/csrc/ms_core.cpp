@@ -408,7 +408,7 @@ extern "C" int32_t ms_space_describe(const ms_op *op, uint32_t flags, ms_space *
     memset(out, 0, sizeof *out);
     const ms_op_desc &d = op->d;
     if (d.in_dtype == MS_F32) flags &= ~MS_SPACE_TENSORIZE;
-    if (d.kind == MS_OP_DWCONV2D_NHWC) flags &= ~(MS_SPACE_TENSORIZE | MS_SPACE_VECTORIZE | MS_SPACE_STORAGE_ALIGN | MS_SPACE_REORDER | MS_SPACE_CACHE_WRITE);
+    if (d.kind == MS_OP_DWCONV2D_NHWC) flags &= ~(MS_SPACE_TENSORIZE | MS_SPACE_VECTORIZE | MS_SPACE_STORAGE_ALIGN | MS_SPACE_CACHE_WRITE);
     flags &= 0x7fu;
     out->flags = flags;
     if (d.kind == MS_OP_DWCONV2D_NHWC) {
@@ -418,6 +418,7 @@ extern "C" int32_t ms_space_describe(const ms_op *op, uint32_t flags, ms_space *
         add_tile(out, MS_SLOT_TILE_C, "c", d.dims[3]);
         if (flags & MS_SPACE_UNROLL) add_cat(out, MS_SLOT_UNROLL, "unroll", {0, 16, 64});
         if (flags & MS_SPACE_CACHE_READ) add_cat(out, MS_SLOT_CACHE_READ, "cache_read", {0, 1});
+        if (flags & MS_SPACE_REORDER) add_cat(out, MS_SLOT_REORDER, "reorder", {0, 2});
         return MS_OK;
     }
     if (flags & MS_SPACE_TENSORIZE) {

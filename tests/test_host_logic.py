@@ -102,7 +102,7 @@ def test_space_composition_by_flags():
     assert [sp.slots[3].extent_by_choice[c] for c in range(4)] == [64, 128, 32, 64]
     assert op.space(B.SPACE_DEFAULT & ~B.SPACE_TENSORIZE).family == B.FAM_GEMM_ALU
     op = B.dwconv2d_op(1, 112, 112, 32)
-    assert slot_names(op.space()) == ["i", "j", "c", "unroll", "cache_read"]
+    assert slot_names(op.space()) == ["i", "j", "c", "unroll", "cache_read", "reorder"]
 
 
 def test_space_size_matches_closed_form():
