@@ -150,12 +150,15 @@ typedef enum ms_slot_id {
     MS_SLOT_CACHE_READ = 6,/* categorical: 0 = operands read from global memory,
                               1 = staged in LDS, 2 = staged in LDS, double buffered,
                               3 (matrix-core kernels) = double buffered, prefetch two tiles ahead,
-                              4 (matrix-core kernels) = double buffered, two wavefront groups half a step apart */
+                              4 (matrix-core kernels) = double buffered, two wavefront groups half a step apart,
+                              5, 6, 7 (matrix-core kernels, 2-byte inputs) = global memory -> LDS directly,
+                              a ring of 2, 3, 4 buffers */
     MS_SLOT_VECTORIZE = 7, /* categorical: elements per global load instruction of operand A (conv: X) */
     MS_SLOT_STORAGE_ALIGN = 8, /* categorical: LDS layout: 0 = dense, 1 = each row / plane padded by 16 bytes,
                               2 (matrix-core kernels) = padded, and the 16-byte slots of a plane XOR-swizzled */
     MS_SLOT_REORDER = 9,   /* categorical: order of the grid loops, 0 = i outer, 1 = j outer,
-                              2 = i outer with workgroups grouped per XCD */
+                              2 = i outer with workgroups grouped per XCD, 3 (with cache_read 5..7) = as 2 with
+                              persistent workgroups that loop over tiles */
     MS_SLOT_VECTORIZE_B = 10, /* categorical: elements per global load instruction of operand B (conv: W) */
     MS_SLOT_CACHE_WRITE = 11  /* categorical (matrix-core kernels): 0 = results go from registers to global memory,
                                  1 = the workgroup's output tile is staged in LDS and written as whole rows */
@@ -278,7 +281,7 @@ typedef struct ms_variant_params {
     int32_t waves;
     int32_t acc_per_thread; /* accumulator registers per lane */
     int32_t lds_bytes;
-    int32_t cache_read;     /* 0 .. 4 as in MS_SLOT_CACHE_READ */
+    int32_t cache_read;     /* 0 .. 7 as in MS_SLOT_CACHE_READ */
     int32_t vec;            /* elements per global load of A (depthwise: channels per access) */
     int32_t unroll;         /* budget */
     int32_t unroll_k1, unroll_k2; /* unroll factors of the two rolled reduction loops */
@@ -475,6 +478,9 @@ int32_t ms_calibrate_stream(int32_t mode, const void *src, void *dst, size_t byt
 /* LDS read rate with 16-byte conflict-free reads on every CU: aggregate GB/s and bytes per clock per CU
  * at the device's nominal clock. */
 int32_t ms_calibrate_lds(void *scratch, void *stream, double *bytes_per_clk_per_cu, double *gbs);
+/* Rate at which the L2 caches feed the compute units: every workgroup reads the same 2 MiB window at src
+ * (device pointer, at least 2 MiB) over and over; aggregate GB/s. */
+int32_t ms_calibrate_l2(const void *src, void *scratch, void *stream, double *gbs);
 
 int32_t ms_version(void);
 const char *ms_last_error(void);

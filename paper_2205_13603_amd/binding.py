@@ -167,6 +167,7 @@ SYMBOLS = {
     "ms_calibrate_mfma": (C.c_int32, [C.c_int32, C.c_int32, C.c_void_p, C.c_void_p, C.c_void_p, _P(C.c_double)]),
     "ms_calibrate_stream": (C.c_int32, [C.c_int32, C.c_void_p, C.c_void_p, C.c_size_t, C.c_void_p, _P(C.c_double)]),
     "ms_calibrate_lds": (C.c_int32, [C.c_void_p, C.c_void_p, _P(C.c_double), _P(C.c_double)]),
+    "ms_calibrate_l2": (C.c_int32, [C.c_void_p, C.c_void_p, C.c_void_p, _P(C.c_double)]),
     "ms_version": (C.c_int32, []),
     "ms_last_error": (C.c_char_p, []),
 }
@@ -416,6 +417,12 @@ def calibrate_lds(scratch_ptr, stream=None):
     a, b = C.c_double(), C.c_double()
     _check(lib().ms_calibrate_lds(scratch_ptr, stream, C.byref(a), C.byref(b)))
     return a.value, b.value
+
+
+def calibrate_l2(src_ptr, scratch_ptr, stream=None):
+    v = C.c_double()
+    _check(lib().ms_calibrate_l2(src_ptr, scratch_ptr, stream, C.byref(v)))
+    return v.value
 
 
 def search_cfg_default():

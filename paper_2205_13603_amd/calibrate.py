@@ -31,6 +31,7 @@ def main():
     if not args.quick:
         scratch = torch.zeros(1 << 16, dtype=torch.float32, device="cuda")
         bpc, gbs = B.calibrate_lds(scratch.data_ptr())
+        out["l2_read_gbs"] = B.calibrate_l2(src.data_ptr(), scratch.data_ptr())
         out["lds_read"] = {"bytes_per_clk_per_cu_at_nominal_clock": bpc, "gbs": gbs}
         rnd = (torch.randn(8192, device="cuda") * 0.1)
         ops = {"f16": rnd.half(), "bf16": rnd.bfloat16(), "i8": torch.randint(-128, 128, (8192,), device="cuda", dtype=torch.int8)}

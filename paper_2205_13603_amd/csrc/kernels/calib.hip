@@ -111,6 +111,27 @@ extern "C" __global__ void __launch_bounds__(256) ms_calib_kernel(const void *sr
     }
     if (acc[0] == 0xdeadbeefu && src != nullptr) ((u4_t *)dst)[threadIdx.x] = acc;
 }
+#elif MODE == 4
+// L2 read rate: every workgroup reads the same 2 MiB window `reps` times (16 bytes per lane, coalesced);
+// the window stays resident in each XCD's L2, so this is the rate at which the L2s feed the compute units
+typedef vec_t<float, 4> w16_t;
+extern "C" __global__ void __launch_bounds__(256) ms_calib_kernel(const void *src, const void *, const void *, void *dst, int reps)
+{
+    const w16_t *s = (const w16_t *)src;
+    constexpr int WORDS = (2 << 20) / 16;
+    float acc = 0.f;
+    int i = (blockIdx.x * 256 + threadIdx.x) % WORDS;
+#pragma unroll 1
+    for (int r = 0; r < reps; ++r) {
+#pragma unroll
+        for (int t = 0; t < 8; ++t) {
+            w16_t x = s[i];
+            acc += x.v[0] + x.v[3];
+            i = (i + 256 * 61) % WORDS;
+        }
+    }
+    if (acc == -12345.678f) ((float *)dst)[threadIdx.x] = acc;
+}
 #else
 typedef vec_t<float, 4> w16_t;
 extern "C" __global__ void __launch_bounds__(256) ms_calib_kernel(const void *src, const void *, const void *, void *dst, int n16_lo)

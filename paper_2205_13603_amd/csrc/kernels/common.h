@@ -72,7 +72,7 @@ __device__ __forceinline__ void block_to_tile(int &z, int &i0, int &j0)
     constexpr int G = I0 * J0;
     int wg = blockIdx.x;
     z = blockIdx.z * gridDim.y + blockIdx.y;
-#if REORDER == 2
+#if REORDER >= 2
     const int nz = gridDim.y * gridDim.z;
     const long total = (long)G * nz;
     if (total % 8 == 0) {

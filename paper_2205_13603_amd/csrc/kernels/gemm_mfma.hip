@@ -6,13 +6,15 @@
 //           instruction; the loops i, j, k are from here on counted in tiles
 //   split   i -> I0,I1,I2,I3   j -> J0,J1,J2,J3   k -> K0,K1,K2,K3
 //   reorder i0 j0 | k0 | i2 j2 | k1 k2 k3 | i1 j1 i3 j3
-//   bind    fuse(i0,j0) -> blockIdx.x, fuse(i2,j2) -> wavefront of the workgroup
+//   bind    fuse(i0,j0) -> blockIdx.x (REORDER 3: -> a loop of persistent workgroups), fuse(i2,j2) -> wavefront
 //   cache-read A,B tiles of one k0 step into LDS (CACHE_READ 1: one buffer;
 //           2: two buffers, the next tile is fetched into registers while the
 //           current one is multiplied; 3: two buffers and two register sets, the
-//           tile two steps ahead is in flight; 4: two buffers, the wavefronts split
+//           tile two steps ahead is in flight, and with k1, k2 fully unrolled the LDS
+//           writes of the next tile are spread between the MFMAs as well; 4: two buffers, the wavefronts split
 //           into two groups half a step apart so that one group's memory phase
-//           runs under the other's MFMA phase)
+//           runs under the other's MFMA phase; 5, 6, 7: tiles loaded from global memory
+//           straight into a ring of 2, 3, 4 LDS buffers (see "Direct-to-LDS path" below))
 //   storage-align: LDS_PAD 1, 2: each LDS plane padded by 16 bytes; 2: slots of a plane XOR-swizzled
 //   vectorize: global loads of VEC (A) and VEC_B (B) elements
 //   cache-write (CACHE_WRITE 1): the output tile is assembled in LDS and stored as whole rows
@@ -186,7 +188,7 @@ __device__ __forceinline__ void kmajor_load(kmajor_stage<ROWS, V> &st, const in_
 }
 
 template <int ROWS, int V, int PLANE>
-__device__ __forceinline__ void kmajor_store(const kmajor_stage<ROWS, V> &st, char *__restrict__ lds, int tid)
+__device__ __forceinline__ void kmajor_store(const kmajor_stage<ROWS, V> &st, char *__restrict__ lds, int tid, int u0, int u1)
 {
     typedef kmajor_stage<ROWS, V> S;
     constexpr int KV = S::KV, PARTS = S::PARTS, PART_E = S::PART_E;
@@ -196,6 +198,7 @@ __device__ __forceinline__ void kmajor_store(const kmajor_stage<ROWS, V> &st, ch
     const int row_t = tid / KV, kv_t = tid % KV;
 #pragma unroll
     for (int it = 0; it < S::ITERS; ++it) {
+        if (it < u0 || it >= u1) continue;
         const int idx = it * NTHREADS + tid;
         if (S::TOTAL % NTHREADS == 0 || idx < S::TOTAL) {
             const int row = AFFINE ? row_t + it * (NTHREADS / KV) : idx / KV;
@@ -251,13 +254,14 @@ __device__ __forceinline__ void jmajor_load(jmajor_stage &st, const in_t *__rest
     }
 }
 
-__device__ __forceinline__ void jmajor_store(const jmajor_stage &st, char *__restrict__ lds, int tid)
+__device__ __forceinline__ void jmajor_store(const jmajor_stage &st, char *__restrict__ lds, int tid, int u0, int u1)
 {
     typedef jmajor_stage S;
     constexpr bool AFFINE = NTHREADS % JV == 0;
     const int kg_t = tid / JV, jv_t = tid % JV;
 #pragma unroll
     for (int it = 0; it < S::ITERS; ++it) {
+        if (it < u0 || it >= u1) continue;
         const int idx = it * NTHREADS + tid;
         if (S::TOTAL % NTHREADS == 0 || idx < S::TOTAL) {
             const int kg = AFFINE ? kg_t + it * (NTHREADS / JV) : idx / JV;
@@ -287,6 +291,8 @@ struct tile_stage {
 #endif
     static constexpr int UNITS_A = kmajor_stage<BM, VEC>::ITERS;
     static constexpr int UNITS = UNITS_A + UNITS_B; // global load instructions per thread and tile
+    static constexpr int SUNITS_A = kmajor_stage<BM, VEC>::ITERS;
+    static constexpr int SUNITS = SUNITS_A + (B_KMAJOR ? UNITS_B : UNITS_B / KP); // store units (one per staged vector / block)
 };
 
 // issue load units [u0, u1) of the tile of step k0
@@ -302,13 +308,14 @@ __device__ __forceinline__ void stage_load(tile_stage &st, const in_t *__restric
 #endif
 }
 
-__device__ __forceinline__ void stage_store(const tile_stage &st, char *__restrict__ lds, int tid)
+// write store units [u0, u1) of a staged tile to the LDS stage at `lds`
+__device__ __forceinline__ void stage_store(const tile_stage &st, char *__restrict__ lds, int tid, int u0 = 0, int u1 = tile_stage::SUNITS)
 {
-    kmajor_store<BM, VEC, PLANE_A>(st.a, lds, tid);
+    kmajor_store<BM, VEC, PLANE_A>(st.a, lds, tid, u0, u1);
 #if B_KMAJOR
-    kmajor_store<BN, VEC_B, PLANE_B>(st.b, lds + KG * PLANE_A, tid);
+    kmajor_store<BN, VEC_B, PLANE_B>(st.b, lds + KG * PLANE_A, tid, u0 - tile_stage::SUNITS_A, u1 - tile_stage::SUNITS_A);
 #else
-    jmajor_store(st.b, lds + KG * PLANE_A, tid);
+    jmajor_store(st.b, lds + KG * PLANE_A, tid, u0 - tile_stage::SUNITS_A, u1 - tile_stage::SUNITS_A);
 #endif
 }
 
@@ -350,6 +357,30 @@ __device__ __forceinline__ void mfma_slot(accv_t (&acc)[TM][TN], const frag_t (&
             for (int tn = 0; tn < TN; ++tn) acc[tm][tn] = mfma(fb[q][tn], fa[q][tm], acc[tm][tn]);
 }
 
+// One fully software-pipelined step (k1, k2 unrolled): multiplies the tile staged at `cur` while it
+// writes the already arrived tile `ready` to the other LDS stage `nxt` and requests tile `kload`
+// into `inflight`.  Each of the NS slots issues, ahead of its own MFMAs, the next slot's LDS reads,
+// its share of the LDS writes and its share of the global loads: loads, LDS traffic and matrix
+// cores work at the same time instead of taking turns.
+#define NS_ (K1 * K2)
+__device__ __forceinline__ void pipelined_step(accv_t (&acc)[TM][TN], const char *__restrict__ cur, char *__restrict__ nxt,
+                                               const tile_stage &ready, tile_stage &inflight, const in_t *__restrict__ A,
+                                               const in_t *__restrict__ B, int i0, int j0, int kload, int tid, int lgrp, int wi, int wj, int lrow)
+{
+    const char *la = cur + lgrp * PLANE_A;
+    const char *lb = cur + KG * PLANE_A + lgrp * PLANE_B;
+    frag_t fa[2][K3][TM], fb[2][K3][TN];
+    read_frags(fa[0], fb[0], la, lb, 0, wi, wj, lrow);
+#pragma unroll
+    for (int s = 0; s < NS_; ++s) {
+        if (s + 1 < NS_) read_frags(fa[(s + 1) & 1], fb[(s + 1) & 1], la, lb, s + 1, wi, wj, lrow);
+        stage_store(ready, nxt, tid, s * tile_stage::SUNITS / NS_, (s + 1) * tile_stage::SUNITS / NS_);
+        stage_load(inflight, A, B, i0, j0, kload, tid, s * tile_stage::UNITS / NS_, (s + 1) * tile_stage::UNITS / NS_);
+        mfma_slot(acc, fa[s & 1], fb[s & 1]);
+        __builtin_amdgcn_sched_barrier(0);
+    }
+}
+
 // multiply the tile staged at `stage_base` (rolled / partly unrolled k1, k2 loops)
 __device__ __forceinline__ void multiply_tile(accv_t (&acc)[TM][TN], const char *__restrict__ stage_base, int lgrp, int wi, int wj, int lrow)
 {
@@ -369,6 +400,337 @@ __device__ __forceinline__ void multiply_tile(accv_t (&acc)[TM][TN], const char 
 constexpr int NS = K1 * K2;
 #define PIPELINED (CACHE_READ < 3 && UNROLL_K1 == K1 && UNROLL_K2 == K2 && K1 * K2 > 1)
 
+// ======================================================================================
+// Direct-to-LDS path (CACHE_READ 5, 6, 7 = a ring of 2, 3, 4 LDS stages).
+//
+// Tiles go from global memory straight into LDS (global_load_lds, 16 bytes per lane, the 64
+// lanes of a wavefront fill 1 KiB of consecutive LDS): no staging registers, no LDS write
+// instructions, and up to 3 tiles in flight while one is multiplied.  Because the LDS side of
+// such a load is fixed (lane i -> byte 16*i), the layouts are chosen for the readers and the
+// global address of each lane is derived from them:
+//   k-contiguous operand (A; B of NT): row-major rows of BK elements, the 16-byte chunks of a
+//       row XOR-swizzled with the row number, so that the 8 or 16 lanes that read the same
+//       logical chunk of consecutive rows hit different banks; one load instruction covers
+//       whole 128-byte lines of 64/CPR rows.
+//   j-contiguous operand (B of NN): row-major k-rows of BN elements as in global memory (a load
+//       instruction covers whole 128-byte lines), the 32-byte granules (16 columns) of a row
+//       XOR-swizzled with the row number, read with the LDS
+//       transpose load (ds_read_b64_tr_b16: inside a group of 16 lanes, lane i receives element
+//       i%4 of lanes i/4, 4 + i/4, 8 + i/4, 12 + i/4): four lanes hand in one k-row of the panel,
+//       every lane gets 4 consecutive k of its own column - the MFMA B fragment.
+// 2-byte inputs and 8-element fragments (16x16x32, 32x32x16) only.
+#if CACHE_READ >= 5
+constexpr int DL_STAGES = CACHE_READ - 3;
+constexpr int CPR = BK / 8;                               // 16-byte chunks per k-contiguous row
+constexpr int ROW_BYTES = BK * 2;
+constexpr int SWZ_DIV = CPR >= 8 ? 1 : 8 / CPR;           // rows that share one 128-byte line
+constexpr int RPI = 64 / CPR;                             // rows per load instruction
+constexpr int DL_A_BYTES = BM * ROW_BYTES;
+#if B_KMAJOR
+constexpr int DL_B_BYTES = BN * ROW_BYTES;
+#else
+constexpr int DL_B_BYTES = ((BK * (BN / 8) + 63) / 64) * 1024;
+#endif
+constexpr int DL_STAGE_BYTES = DL_A_BYTES + DL_B_BYTES;
+constexpr int DL_IA = BM / RPI;                           // load instructions per A tile
+#if B_KMAJOR
+constexpr int DL_IB = BN / RPI;
+#else
+constexpr int CB = BN / 8;                                // 16-byte chunks per k-row of the j-contiguous B tile
+constexpr int BROW_BYTES = BN * 2;
+constexpr int DL_IB = (BK * CB + 63) / 64;
+// swizzle of the 32-byte granules (16 columns) of a row with the row number; needs a power-of-two granule count
+constexpr int NGRAN = BN / 16;
+constexpr int GRAN_MASK = (NGRAN & (NGRAN - 1)) ? 0 : (NGRAN > 16 ? 15 : NGRAN - 1);
+#endif
+constexpr int DL_INSTR = DL_IA + DL_IB;
+constexpr int DL_LPW_MIN = DL_INSTR / NWAVES;             // loads every wavefront issues per tile, at least
+static_assert(ES == 2 && KP == 8, "direct-to-LDS path: 2-byte inputs, 8-element fragments");
+static_assert(CPR == 4 || CPR == 8 || CPR == 16, "direct-to-LDS path: k tile of 32, 64 or 128");
+
+#define AS1(p) ((const __attribute__((address_space(1))) void *)(p))
+#define AS3(p) ((__attribute__((address_space(3))) void *)(p))
+
+__device__ __forceinline__ int dl_swz(int row) { return (row / SWZ_DIV) % CPR; }
+#if !B_KMAJOR
+// chunk-index XOR for k-row `k` of the j-contiguous operand: moves whole 32-byte granules
+__device__ __forceinline__ int dl_swz_b(int k) { return (k & GRAN_MASK) << 1; }
+#endif
+
+// issue this wavefront's share of the loads of tile `k0` into the stage at `stage`
+__device__ __forceinline__ void dl_issue(const in_t *__restrict__ A, const in_t *__restrict__ B, char *stage, int i0, int j0, int k0, int wave,
+                                         int lane)
+{
+    const long k0e = (long)k0 * BK;
+#pragma unroll
+    for (int n = 0; n < (DL_INSTR + NWAVES - 1) / NWAVES; ++n) {
+        const int inst = n * NWAVES + wave; // wave-uniform
+        // every address = wave-uniform base (scalar registers) + a 32-bit per-lane byte offset
+        if (inst < DL_IA) {
+            const int row = inst * RPI + lane / CPR;
+            const int c = (lane % CPR) ^ dl_swz(row);
+            const char *ub = (const char *)(A + ((long)i0 * BM + inst * RPI) * SA_I + k0e);
+            const unsigned voff = (unsigned)(((lane / CPR) * SA_I + c * 8) * 2);
+            __builtin_amdgcn_global_load_lds(AS1(ub + voff), AS3(stage + inst * 1024), 16, 0, 0);
+        } else if (inst < DL_INSTR) {
+            const int ib = inst - DL_IA;
+#if B_KMAJOR
+            const int row = ib * RPI + lane / CPR;
+            const int c = (lane % CPR) ^ dl_swz(row);
+            const char *ub = (const char *)(B + ((long)j0 * BN + ib * RPI) * SB_J + k0e);
+            const unsigned voff = (unsigned)(((lane / CPR) * SB_J + c * 8) * 2);
+#else
+            // lane-linear over the tile's chunks: whole 128-byte lines of consecutive k-rows per instruction
+            const int idx = ib * 64 + lane;
+            const int k = (BK * CB) % 64 == 0 ? idx / CB : (idx / CB < BK ? idx / CB : BK - 1);
+            const int c = (idx % CB) ^ dl_swz_b(k);
+            const char *ub = (const char *)(B + k0e * SB_K + (long)j0 * BN);
+            const unsigned voff = (unsigned)((k * SB_K + c * 8) * 2);
+#endif
+            __builtin_amdgcn_global_load_lds(AS1(ub + voff), AS3(stage + DL_A_BYTES + ib * 1024), 16, 0, 0);
+        }
+    }
+}
+
+typedef short tr4_t __attribute__((ext_vector_type(4)));
+
+__device__ __forceinline__ void dl_read_frags(frag_t (&fa)[K3][TM], frag_t (&fb)[K3][TN], const char *__restrict__ stage, int slot, int wi, int wj,
+                                              int lane)
+{
+    const int lrow = lane % MI_M, lgrp = lane / MI_M;
+#pragma unroll
+    for (int q = 0; q < K3; ++q) {
+        const int step = slot * K3 + q;
+        const int chunk = step * LANE_GROUPS + lgrp;
+#pragma unroll
+        for (int r1 = 0; r1 < I1; ++r1)
+#pragma unroll
+            for (int r3 = 0; r3 < I3; ++r3) {
+                const int row = ((r1 * I2 + wi) * I3 + r3) * MI_M + lrow;
+                fa[q][r1 * I3 + r3] = *reinterpret_cast<const frag_t *>(stage + row * ROW_BYTES + ((chunk ^ dl_swz(row)) * 16));
+            }
+#pragma unroll
+        for (int c1 = 0; c1 < J1; ++c1)
+#pragma unroll
+            for (int c3 = 0; c3 < J3; ++c3) {
+                const int tcol = (c1 * J2 + wj) * J3 + c3;
+#if B_KMAJOR
+                const int row = tcol * MI_N + lrow;
+                fb[q][c1 * J3 + c3] = *reinterpret_cast<const frag_t *>(stage + DL_A_BYTES + row * ROW_BYTES + ((chunk ^ dl_swz(row)) * 16));
+#else
+                const int pn = (tcol * MI_N + lrow) / 16; // 16-column granule of this lane's column
+                const int li = lane % 16;
+                const int krow = step * MI_K + lgrp * 8 + li / 4;
+                const char *b0 = stage + DL_A_BYTES + krow * BROW_BYTES + (((pn << 1) ^ dl_swz_b(krow)) * 16) + (li % 4) * 8;
+                const char *b1 = stage + DL_A_BYTES + (krow + 4) * BROW_BYTES + (((pn << 1) ^ dl_swz_b(krow + 4)) * 16) + (li % 4) * 8;
+                const tr4_t lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) tr4_t *)(b0));
+                const tr4_t hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) tr4_t *)(b1));
+                frag_t f;
+                *reinterpret_cast<tr4_t *>(&f.v[0]) = lo;
+                *reinterpret_cast<tr4_t *>(&f.v[4]) = hi;
+                fb[q][c1 * J3 + c3] = f;
+#endif
+            }
+    }
+}
+
+// wait until at most `n` of this wavefront's vector-memory operations are outstanding
+#define DL_WAIT_VM(n) __builtin_amdgcn_s_waitcnt((((n) & 15) | (((n) >> 4) << 14) | (7 << 4) | (15 << 8)))
+#endif // CACHE_READ >= 5
+
+
+constexpr int CROW = BN * (int)sizeof(out_t) + 16; // bytes of one staged output row (cache-write)
+
+// Epilogue of one workgroup tile.  `cstage`: LDS region of BM * CROW bytes for CACHE_WRITE 1 (must not be
+// read or written by anything else between the caller's preceding barrier and the end of this call).
+__device__ __forceinline__ void write_tile(accv_t (&acc)[TM][TN], out_t *__restrict__ C, const void *__restrict__ bias_, int inst, int i0, int j0,
+                                           char *__restrict__ cstage, int tid, int wi, int wj, int lrow, int lgrp)
+{
+    // epilogue: (+bias, ReLU,) one rounding to the output type.
+    // With the operands swapped a lane holds row `lrow` of the tile and, per group g of 4 accumulator
+    // elements, the 4 consecutive columns 4*lgrp (16x16) or 8*g + 4*lgrp (32x32) onwards.
+    // CACHE_WRITE 0: those 4 values go to global memory as one vector.  CACHE_WRITE 1: the workgroup's
+    // tile is first assembled in LDS (the operand buffers are free: the k loop ended with a barrier) and
+    // then written as whole rows, 16 bytes per lane, consecutive lanes at consecutive addresses.
+#pragma unroll
+    for (int r1 = 0; r1 < I1; ++r1)
+#pragma unroll
+        for (int r3 = 0; r3 < I3; ++r3)
+#pragma unroll
+            for (int c1 = 0; c1 < J1; ++c1)
+#pragma unroll
+                for (int c3 = 0; c3 < J3; ++c3) {
+                    const int trow = (r1 * I2 + wi) * I3 + r3, tcol = (c1 * J2 + wj) * J3 + c3;
+                    const int lr = trow * MI_M + lrow; // row inside the workgroup tile
+#pragma unroll
+                    for (int g = 0; g < ACC_N / 4; ++g) {
+                        const int lc = tcol * MI_N + (MI_M == 16 ? 4 * lgrp : 8 * g + 4 * lgrp); // column inside the tile
+                        const long col = (long)j0 * BN + lc;
+                        vec_t<out_t, 4> o;
+#if HAS_BIAS
+                        const vec_t<float, 4> bias = *reinterpret_cast<const vec_t<float, 4> *>((const float *)bias_ + (long)inst * DIM_N + col);
+#endif
+#pragma unroll
+                        for (int e = 0; e < 4; ++e) {
+                            acc_t x = acc[r1 * I3 + r3][c1 * J3 + c3][4 * g + e];
+#if HAS_BIAS
+                            x += bias.v[e];
+#endif
+#if RELU
+                            x = x > 0 ? x : 0;
+#endif
+                            o.v[e] = from_acc(x);
+                        }
+#if CACHE_WRITE
+                        *reinterpret_cast<vec_t<out_t, 4> *>(cstage + lr * CROW + lc * (int)sizeof(out_t)) = o;
+#else
+                        *reinterpret_cast<vec_t<out_t, 4> *>(C + ((long)i0 * BM + lr) * DIM_N + col) = o;
+#endif
+                    }
+                }
+#if CACHE_WRITE
+    __syncthreads();
+    {
+        constexpr int CHUNKS_PER_ROW = BN * (int)sizeof(out_t) / 16;
+        constexpr int TOTAL = BM * CHUNKS_PER_ROW;
+        typedef vec_t<unsigned, 4> chunk_t;
+#pragma unroll 4
+        for (int idx = tid; idx < TOTAL; idx += NTHREADS) {
+            const int row = idx / CHUNKS_PER_ROW, ch = idx % CHUNKS_PER_ROW;
+            const chunk_t v = *reinterpret_cast<const chunk_t *>(cstage + row * CROW + ch * 16);
+            char *dst = (char *)(C + ((long)i0 * BM + row) * DIM_N + (long)j0 * BN) + ch * 16;
+            *reinterpret_cast<chunk_t *>(dst) = v;
+        }
+    }
+#endif
+    (void)bias_;
+    (void)inst;
+    (void)cstage;
+    (void)tid;
+}
+
+#if REORDER == 3
+// --------------------------------------------------------------------------------------
+// Persistent workgroups (REORDER 3, direct-to-LDS staging only): the launch has about one workgroup
+// per compute unit, and workgroup w multiplies the tiles w, w + gridDim.x, ... of the launch-wide
+// tile list (XCD-grouped order as in REORDER 2).  The LDS ring runs across tile boundaries: while
+// a tile's result is written out the first k steps of the next tile are already in flight, so there
+// is neither a fill bubble per tile nor a new workgroup to start.
+struct tile_id {
+    int inst, bb, i0, j0;
+};
+
+__device__ __forceinline__ tile_id decode_tile(long f, long total)
+{
+    constexpr int G = I0 * J0;
+    if (total % 8 == 0) f = (f % 8) * (total / 8) + f / 8;
+    const int wg = (int)(f % G), z = (int)(f / G);
+    tile_id t;
+    t.inst = z / DIM_B;
+    t.bb = z % DIM_B;
+    t.i0 = wg / J0;
+    t.j0 = wg % J0;
+    return t;
+}
+
+extern "C" __global__ void __launch_bounds__(NTHREADS)
+ms_kernel(const void *__restrict__ a_, const void *__restrict__ b_, const void *__restrict__ bias_, void *__restrict__ c_, int instances)
+{
+    const int tid = threadIdx.x;
+    const int lane = tid % 64, wave = tid / 64;
+    const int wi = wave / J2, wj = wave % J2;
+    const int lrow = lane % MI_M, lgrp = lane / MI_M;
+    const int wave_u = __builtin_amdgcn_readfirstlane(wave);
+
+    constexpr int OPND_BYTES = DL_STAGES * DL_STAGE_BYTES;
+    constexpr int LDS_BYTES = OPND_BYTES + (CACHE_WRITE ? BM * CROW : 0); // the output staging area sits behind the ring
+    __shared__ __attribute__((aligned(16))) char lds[LDS_BYTES];
+
+    const long total = (long)I0 * J0 * DIM_B * instances;
+    const long first = blockIdx.x, stride = gridDim.x;
+    if (first >= total) return;
+    const long my_tiles = (total - first + stride - 1) / stride;
+    const long my_steps = my_tiles * K0;
+
+    // load cursor: step `ls` of this workgroup's step list = k step lk of tile lt
+    long ls = 0;
+    int lk = 0;
+    tile_id lt = decode_tile(first, total);
+    long lf = first;
+    int wr = 0;
+    auto issue_next = [&]() {
+        // past the end the last step is loaded again (never read): every wavefront keeps issuing the same number of loads
+        const in_t *A = (const in_t *)a_ + (long)lt.inst * A_INST + (long)lt.bb * SA_B;
+        const in_t *B = (const in_t *)b_ + (long)lt.inst * B_INST + (long)lt.bb * SB_B;
+        dl_issue(A, B, lds + wr * DL_STAGE_BYTES, lt.i0, lt.j0, lk, wave_u, lane);
+        wr = wr + 1 == DL_STAGES ? 0 : wr + 1;
+        if (ls + 1 < my_steps) {
+            ++ls;
+            if (++lk == K0) {
+                lk = 0;
+                lf += stride;
+                lt = decode_tile(lf, total);
+            }
+        }
+    };
+#pragma unroll
+    for (int t = 0; t < DL_STAGES - 1; ++t) issue_next();
+
+    int rd = 0;
+#pragma unroll 1
+    for (long ti = 0; ti < my_tiles; ++ti) {
+        const tile_id ct = decode_tile(first + ti * stride, total);
+        accv_t acc[TM][TN];
+#pragma unroll
+        for (int tm = 0; tm < TM; ++tm)
+#pragma unroll
+            for (int tn = 0; tn < TN; ++tn)
+#pragma unroll
+                for (int e = 0; e < ACC_N; ++e) acc[tm][tn][e] = 0;
+#pragma unroll 1
+        for (int k0 = 0; k0 < K0; ++k0) {
+            // right after an epilogue the counter also holds that tile's stores, which need not retire in
+            // order with the loads: drain it once, then count loads again
+            if (k0 == 0 && ti > 0) DL_WAIT_VM(0);
+            else DL_WAIT_VM((DL_STAGES - 2) * DL_LPW_MIN);
+            __builtin_amdgcn_s_barrier();
+            issue_next();
+            const char *stage = lds + rd * DL_STAGE_BYTES;
+#if UNROLL_K1 == K1 && UNROLL_K2 == K2 && K1 * K2 > 1
+            {
+                frag_t fa[2][K3][TM], fb[2][K3][TN];
+                dl_read_frags(fa[0], fb[0], stage, 0, wi, wj, lane);
+#pragma unroll
+                for (int sl = 0; sl < K1 * K2; ++sl) {
+                    if (sl + 1 < K1 * K2) dl_read_frags(fa[(sl + 1) & 1], fb[(sl + 1) & 1], stage, sl + 1, wi, wj, lane);
+                    mfma_slot(acc, fa[sl & 1], fb[sl & 1]);
+                    __builtin_amdgcn_sched_barrier(0);
+                }
+            }
+#else
+#pragma unroll UNROLL_K1
+            for (int k1 = 0; k1 < K1; ++k1) {
+#pragma unroll UNROLL_K2
+                for (int k2 = 0; k2 < K2; ++k2) {
+                    frag_t fa[K3][TM], fb[K3][TN];
+                    dl_read_frags(fa, fb, stage, k1 * K2 + k2, wi, wj, lane);
+                    mfma_slot(acc, fa, fb);
+                }
+            }
+#endif
+            rd = rd + 1 == DL_STAGES ? 0 : rd + 1;
+        }
+        out_t *C = (out_t *)c_ + ((long)ct.inst * DIM_B + ct.bb) * ((long)DIM_M * DIM_N);
+#if CACHE_WRITE
+        // the staging area was last read by the previous tile's row stores, K0 barriers ago
+        write_tile(acc, C, bias_, ct.inst, ct.i0, ct.j0, lds + OPND_BYTES, tid, wi, wj, lrow, lgrp);
+#else
+        write_tile(acc, C, bias_, ct.inst, ct.i0, ct.j0, lds, tid, wi, wj, lrow, lgrp);
+#endif
+    }
+    DL_WAIT_VM(0); // the re-loads past the end must land before the workgroup's LDS is released
+}
+#else // REORDER != 3
 extern "C" __global__ void __launch_bounds__(NTHREADS)
 ms_kernel(const void *__restrict__ a_, const void *__restrict__ b_, const void *__restrict__ bias_, void *__restrict__ c_, int instances)
 {
@@ -385,8 +747,12 @@ ms_kernel(const void *__restrict__ a_, const void *__restrict__ b_, const void *
     const int wi = wave / J2, wj = wave % J2;
     const int lrow = lane % MI_M, lgrp = lane / MI_M;
 
-    constexpr int CROW = BN * (int)sizeof(out_t) + 16; // bytes of one staged output row (cache-write)
-    constexpr int LDS_BYTES = (CACHE_WRITE && BM * CROW > STAGES * STAGE_BYTES) ? BM * CROW : STAGES * STAGE_BYTES;
+#if CACHE_READ >= 5
+    constexpr int OPND_BYTES = DL_STAGES * DL_STAGE_BYTES;
+#else
+    constexpr int OPND_BYTES = STAGES * STAGE_BYTES;
+#endif
+    constexpr int LDS_BYTES = (CACHE_WRITE && BM * CROW > OPND_BYTES) ? BM * CROW : OPND_BYTES;
     __shared__ __attribute__((aligned(16))) char lds[LDS_BYTES];
 
     accv_t acc[TM][TN];
@@ -397,7 +763,52 @@ ms_kernel(const void *__restrict__ a_, const void *__restrict__ b_, const void *
 #pragma unroll
             for (int e = 0; e < ACC_N; ++e) acc[tm][tn][e] = 0;
 
-#if CACHE_READ == 3
+#if CACHE_READ >= 5
+    {
+        const int wave_u = __builtin_amdgcn_readfirstlane(wave); // scalar register: load addresses and LDS targets become wave-uniform
+        // prologue: DL_STAGES - 1 tiles in flight
+#pragma unroll
+        for (int t = 0; t < DL_STAGES - 1; ++t) dl_issue(A, B, lds + t * DL_STAGE_BYTES, i0, j0, t < K0 ? t : K0 - 1, wave_u, lane);
+        int rd = 0, wr = DL_STAGES - 1; // stage multiplied in this step / stage refilled in this step
+#pragma unroll 1
+        for (int k0 = 0; k0 < K0; ++k0) {
+            // this wavefront's loads of tile k0 have landed once at most the loads of the DL_STAGES - 2
+            // younger tiles are outstanding; the barrier then covers every wavefront's share, and also
+            // tells that all of them are done reading the stage that is refilled next
+            DL_WAIT_VM((DL_STAGES - 2) * DL_LPW_MIN);
+            __builtin_amdgcn_s_barrier();
+            dl_issue(A, B, lds + wr * DL_STAGE_BYTES, i0, j0, k0 + DL_STAGES - 1 < K0 ? k0 + DL_STAGES - 1 : K0 - 1, wave_u, lane);
+            const char *stage = lds + rd * DL_STAGE_BYTES;
+#if UNROLL_K1 == K1 && UNROLL_K2 == K2 && K1 * K2 > 1
+            {
+                frag_t fa[2][K3][TM], fb[2][K3][TN];
+                dl_read_frags(fa[0], fb[0], stage, 0, wi, wj, lane);
+#pragma unroll
+                for (int sl = 0; sl < K1 * K2; ++sl) {
+                    if (sl + 1 < K1 * K2) dl_read_frags(fa[(sl + 1) & 1], fb[(sl + 1) & 1], stage, sl + 1, wi, wj, lane);
+                    mfma_slot(acc, fa[sl & 1], fb[sl & 1]);
+                    __builtin_amdgcn_sched_barrier(0);
+                }
+            }
+#else
+#pragma unroll UNROLL_K1
+            for (int k1 = 0; k1 < K1; ++k1) {
+#pragma unroll UNROLL_K2
+                for (int k2 = 0; k2 < K2; ++k2) {
+                    frag_t fa[K3][TM], fb[K3][TN];
+                    dl_read_frags(fa, fb, stage, k1 * K2 + k2, wi, wj, lane);
+                    mfma_slot(acc, fa, fb);
+                }
+            }
+#endif
+            rd = rd + 1 == DL_STAGES ? 0 : rd + 1;
+            wr = wr + 1 == DL_STAGES ? 0 : wr + 1;
+        }
+        // the clamped re-loads of the last steps are still in flight and the epilogue may reuse LDS
+        DL_WAIT_VM(0);
+        __syncthreads();
+    }
+#elif CACHE_READ == 3
     // Two LDS buffers and two register sets: the tile of step k+2 is requested while step k is
     // multiplied, so a global load has two whole steps to arrive.  The k0 loop advances by two
     // steps per iteration so that each register set has a fixed name; tile indices beyond the
@@ -410,6 +821,14 @@ ms_kernel(const void *__restrict__ a_, const void *__restrict__ b_, const void *
         __syncthreads();
 #pragma unroll 1
         for (int k0 = 0; k0 < K0; k0 += 2) {
+#if UNROLL_K1 == K1 && UNROLL_K2 == K2
+            pipelined_step(acc, lds, lds + STAGE_BYTES, st1, st0, A, B, i0, j0, k0 + 2 < K0 ? k0 + 2 : K0 - 1, tid, lgrp, wi, wj, lrow);
+            __syncthreads();
+            if (k0 + 1 < K0) {
+                pipelined_step(acc, lds + STAGE_BYTES, lds, st0, st1, A, B, i0, j0, k0 + 3 < K0 ? k0 + 3 : K0 - 1, tid, lgrp, wi, wj, lrow);
+                __syncthreads();
+            }
+#else
             stage_load(st0, A, B, i0, j0, k0 + 2 < K0 ? k0 + 2 : K0 - 1, tid);
             multiply_tile(acc, lds, lgrp, wi, wj, lrow);
             stage_store(st1, lds + STAGE_BYTES, tid);
@@ -420,6 +839,7 @@ ms_kernel(const void *__restrict__ a_, const void *__restrict__ b_, const void *
                 stage_store(st0, lds, tid);
                 __syncthreads();
             }
+#endif
         }
     }
 #elif CACHE_READ == 4
@@ -521,62 +941,6 @@ ms_kernel(const void *__restrict__ a_, const void *__restrict__ b_, const void *
 
 #endif // CACHE_READ != 3
 
-    // epilogue: (+bias, ReLU,) one rounding to the output type.
-    // With the operands swapped a lane holds row `lrow` of the tile and, per group g of 4 accumulator
-    // elements, the 4 consecutive columns 4*lgrp (16x16) or 8*g + 4*lgrp (32x32) onwards.
-    // CACHE_WRITE 0: those 4 values go to global memory as one vector.  CACHE_WRITE 1: the workgroup's
-    // tile is first assembled in LDS (the operand buffers are free: the k loop ended with a barrier) and
-    // then written as whole rows, 16 bytes per lane, consecutive lanes at consecutive addresses.
-#pragma unroll
-    for (int r1 = 0; r1 < I1; ++r1)
-#pragma unroll
-        for (int r3 = 0; r3 < I3; ++r3)
-#pragma unroll
-            for (int c1 = 0; c1 < J1; ++c1)
-#pragma unroll
-                for (int c3 = 0; c3 < J3; ++c3) {
-                    const int trow = (r1 * I2 + wi) * I3 + r3, tcol = (c1 * J2 + wj) * J3 + c3;
-                    const int lr = trow * MI_M + lrow; // row inside the workgroup tile
-#pragma unroll
-                    for (int g = 0; g < ACC_N / 4; ++g) {
-                        const int lc = tcol * MI_N + (MI_M == 16 ? 4 * lgrp : 8 * g + 4 * lgrp); // column inside the tile
-                        const long col = (long)j0 * BN + lc;
-                        vec_t<out_t, 4> o;
-#if HAS_BIAS
-                        const vec_t<float, 4> bias = *reinterpret_cast<const vec_t<float, 4> *>((const float *)bias_ + (long)inst * DIM_N + col);
-#endif
-#pragma unroll
-                        for (int e = 0; e < 4; ++e) {
-                            acc_t x = acc[r1 * I3 + r3][c1 * J3 + c3][4 * g + e];
-#if HAS_BIAS
-                            x += bias.v[e];
-#endif
-#if RELU
-                            x = x > 0 ? x : 0;
-#endif
-                            o.v[e] = from_acc(x);
-                        }
-#if CACHE_WRITE
-                        *reinterpret_cast<vec_t<out_t, 4> *>(lds + lr * CROW + lc * (int)sizeof(out_t)) = o;
-#else
-                        *reinterpret_cast<vec_t<out_t, 4> *>(C + ((long)i0 * BM + lr) * DIM_N + col) = o;
-#endif
-                    }
-                }
-#if CACHE_WRITE
-    __syncthreads();
-    {
-        constexpr int CHUNKS_PER_ROW = BN * (int)sizeof(out_t) / 16;
-        constexpr int TOTAL = BM * CHUNKS_PER_ROW;
-        typedef vec_t<unsigned, 4> chunk_t;
-#pragma unroll 4
-        for (int idx = tid; idx < TOTAL; idx += NTHREADS) {
-            const int row = idx / CHUNKS_PER_ROW, ch = idx % CHUNKS_PER_ROW;
-            const chunk_t v = *reinterpret_cast<const chunk_t *>(lds + row * CROW + ch * 16);
-            char *dst = (char *)(C + ((long)i0 * BM + row) * DIM_N + (long)j0 * BN) + ch * 16;
-            *reinterpret_cast<chunk_t *>(dst) = v;
-        }
-    }
-#endif
-    (void)bias_;
+    write_tile(acc, C, bias_, inst, i0, j0, lds, tid, wi, wj, lrow, lgrp);
 }
+#endif // REORDER != 3

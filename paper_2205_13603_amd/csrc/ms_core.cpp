@@ -456,7 +456,11 @@ extern "C" int32_t ms_space_describe(const ms_op *op, uint32_t flags, ms_space *
             }
         }
         if (flags & MS_SPACE_UNROLL) add_cat(out, MS_SLOT_UNROLL, "unroll", {0, 16, 64});
-        if (flags & MS_SPACE_CACHE_READ) add_cat(out, MS_SLOT_CACHE_READ, "cache_read", {1, 2, 3, 4});
+        if (flags & MS_SPACE_CACHE_READ) {
+            // direct-to-LDS staging (5, 6, 7) exists for 2-byte inputs of plain matrix products
+            if (d.in_dtype != MS_I8 && d.kind != MS_OP_CONV2D_NHWC) add_cat(out, MS_SLOT_CACHE_READ, "cache_read", {1, 2, 3, 4, 5, 6, 7});
+            else add_cat(out, MS_SLOT_CACHE_READ, "cache_read", {1, 2, 3, 4});
+        }
         if (flags & MS_SPACE_VECTORIZE) {
             if (d.in_dtype == MS_I8) {
                 add_cat(out, MS_SLOT_VECTORIZE, "vectorize", {1, 4, 8, 16});
@@ -467,7 +471,10 @@ extern "C" int32_t ms_space_describe(const ms_op *op, uint32_t flags, ms_space *
             }
         }
         if (flags & MS_SPACE_STORAGE_ALIGN) add_cat(out, MS_SLOT_STORAGE_ALIGN, "storage_align", {0, 1, 2});
-        if (flags & MS_SPACE_REORDER) add_cat(out, MS_SLOT_REORDER, "reorder", {0, 1, 2});
+        if (flags & MS_SPACE_REORDER) {
+            if (d.in_dtype != MS_I8 && d.kind != MS_OP_CONV2D_NHWC) add_cat(out, MS_SLOT_REORDER, "reorder", {0, 1, 2, 3});
+            else add_cat(out, MS_SLOT_REORDER, "reorder", {0, 1, 2});
+        }
         if (flags & MS_SPACE_CACHE_WRITE) add_cat(out, MS_SLOT_CACHE_WRITE, "cache_write", {0, 1});
         return MS_OK;
     }
@@ -755,11 +762,15 @@ extern "C" int32_t ms_trace_to_text(const ms_op *op, const ms_space *space, cons
             s += "bind(fuse(i0, j0, c0), blockIdx.x)\nbind(fuse(i2, j2, c2), threadIdx.x)\nvectorize(c3)\n";
         } else {
             s += "reorder(i0, j0, k0, i2, j2, k1, k2, k3, i1, j1, i3, j3)\n";
-            appendf(s, "bind(fuse(%s), blockIdx.x)\n", p.reorder == 1 ? "j0, i0" : "i0, j0");
+            if (p.reorder == 3) appendf(s, "bind(fuse(i0, j0), persistent workgroup loop, one workgroup per compute unit)\n");
+            else appendf(s, "bind(fuse(%s), blockIdx.x)\n", p.reorder == 1 ? "j0, i0" : "i0, j0");
             appendf(s, "bind(fuse(i2, j2), %s)\n", p.mfma ? "wavefront" : "threadIdx.x");
         }
         if (p.cache_read) {
-            appendf(s, "cache-read(buffers=[A, B], scope=lds, at=k0, stages=%d, prefetch_distance=%d)\n", p.cache_read >= 2 ? 2 : 1, p.cache_read == 3 ? 2 : (p.cache_read >= 2 ? 1 : 0));
+            if (p.cache_read >= 5)
+                appendf(s, "cache-read(buffers=[A, B], scope=lds, at=k0, stages=%d, prefetch_distance=%d, direct_to_lds=1)\n", p.cache_read - 3, p.cache_read - 4);
+            else
+                appendf(s, "cache-read(buffers=[A, B], scope=lds, at=k0, stages=%d, prefetch_distance=%d)\n", p.cache_read >= 2 ? 2 : 1, p.cache_read == 3 ? 2 : (p.cache_read >= 2 ? 1 : 0));
             if (p.cache_read == 4) appendf(s, "annotate(block=C, key=wave_groups, value=ping_pong)\n");
             appendf(s, "storage-align(scope=lds, pad_bytes=%d, swizzle=%d)\n", p.lds_pad ? 16 : 0, p.lds_pad == 2);
         }

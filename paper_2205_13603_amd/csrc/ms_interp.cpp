@@ -205,16 +205,36 @@ extern "C" int32_t ms_trace_validate(const ms_op *op, const ms_space *space, con
             int64_t padb = p.lds_pad ? 16 : 0;
             int64_t rowsA = bm * kp * es + padb, rowsB = bn * kp * es + padb;
             lds = (int64_t)(p.cache_read >= 2 ? 2 : 1) * (bk / kp) * (rowsA + rowsB);
+            if (p.cache_read >= 5) {
+                // direct-to-LDS ring: dense tiles, no padding (the swizzle replaces it)
+                if (es != 2 || kp != 8) return reject("direct-to-LDS staging needs 2-byte inputs and an intrinsic with 8 k per lane");
+                if (bk != 32 && bk != 64 && bk != 128) return reject("direct-to-LDS staging needs a k tile of 32, 64 or 128, not %" PRId64, bk);
+                if (d.a_strides[2] != 1 || d.a_strides[1] % 8 || d.a_strides[0] % 8) return reject("direct-to-LDS staging needs 16-byte aligned rows of A");
+                if (d.b_strides[1] == 1 && d.b_strides[2] != 1) {
+                    if (d.b_strides[2] % 8 || d.b_strides[0] % 8) return reject("direct-to-LDS staging needs 16-byte aligned rows of B");
+                } else if (d.b_strides[2] == 1) {
+                    if (d.b_strides[1] % 8 || d.b_strides[0] % 8) return reject("direct-to-LDS staging needs 16-byte aligned rows of B");
+                } else {
+                    return reject("direct-to-LDS staging needs B contiguous along k or j");
+                }
+                if (p.lds_pad) return reject("direct-to-LDS staging has its own swizzle: storage_align must be 0");
+                // the j-contiguous B tile is rounded up to whole 1 KiB load instructions
+                int64_t btile = d.b_strides[2] == 1 ? ((bk * (bn / 8) + 63) / 64) * 1024 : bn * bk * es;
+                lds = (int64_t)(p.cache_read - 3) * (bm * bk * es + btile);
+            }
+            if (p.reorder == 3 && p.cache_read < 5) return reject("persistent workgroups (reorder 3) are built on direct-to-LDS staging (cache_read 5, 6, 7)");
             if (p.cache_write) {
                 // the output tile reuses the operand buffers: rows of bn outputs padded by 16 bytes
                 int64_t ctile = bm * (bn * op->out_size + 16);
-                if (ctile > lds) lds = ctile;
+                if (p.reorder == 3) lds += ctile; // persistent workgroups keep the operand ring alive during the epilogue
+                else if (ctile > lds) lds = ctile;
                 if ((op->N * op->out_size) % 16) return reject("cache_write needs output rows that are multiples of 16 bytes");
             }
             // fragment operands of one k step for the whole wave tile live in registers too
             int64_t frag = ((int64_t)p.ti[1] * p.ti[3] + (int64_t)p.tj[1] * p.tj[3]) * p.tk[3] * (kp * es / 4 > 0 ? kp * es / 4 : 1);
             // registers that carry a tile from global memory to LDS; with two buffers they are live across the k step
             int64_t stage = (bm * bk * es / 4 + p.threads - 1) / p.threads + (bn * bk * es / 4 + p.threads - 1) / p.threads;
+            if (p.cache_read >= 5) stage = 0;
             int64_t live = p.cache_read == 3 ? frag + 2 * stage : (p.cache_read >= 2 ? frag + stage : std::max(frag, stage));
             if (p.cache_read == 4) {
                 if (p.waves % 2) return reject("ping-pong wave groups need an even number of wavefronts, not %d", p.waves);

@@ -21,6 +21,7 @@ struct ms_variant {
     hipModule_t mod;
     hipFunction_t fn;
     int device;              // device the module is loaded on, -1 = not loaded
+    int compute_units;       // of that device
 };
 
 #define HIP_TRY(call)                                                                               \
@@ -112,6 +113,7 @@ static int32_t ensure_loaded(ms_variant *v)
     HIP_TRY(hipModuleLoadData(&v->mod, v->code->data()));
     HIP_TRY(hipModuleGetFunction(&v->fn, v->mod, v->spec.entry.c_str()));
     v->device = dev;
+    v->compute_units = prop.multiProcessorCount;
     return MS_OK;
 }
 
@@ -145,8 +147,15 @@ extern "C" int32_t ms_variant_launch(ms_variant *v, const void *const *inputs, v
         gzz = (unsigned)(gz / gy);
         if (gzz > 65535) return fail(MS_ERR_BAD_ARG, "ms_variant_launch: %d instances overflow the grid", instances);
     }
-    HIP_TRY(hipModuleLaunchKernel(v->fn, v->spec.grid[0], gy, gzz, v->spec.block[0], 1, 1, v->spec.lds_dynamic,
-                                  (hipStream_t)stream, args, nullptr));
+    unsigned gx = v->spec.grid[0];
+    if (v->p.family == MS_FAM_GEMM_MFMA && v->p.reorder == 3) {
+        // persistent workgroups: one per compute unit (fewer if there are fewer tiles), each loops over its tiles
+        uint64_t total = (uint64_t)v->spec.grid[0] * gz;
+        gx = (unsigned)std::min<uint64_t>(total, (uint64_t)std::max(1, v->compute_units));
+        gy = 1;
+        gzz = 1;
+    }
+    HIP_TRY(hipModuleLaunchKernel(v->fn, gx, gy, gzz, v->spec.block[0], 1, 1, v->spec.lds_dynamic, (hipStream_t)stream, args, nullptr));
     return MS_OK;
 }
 
@@ -354,5 +363,27 @@ extern "C" int32_t ms_calibrate_lds(void *scratch, void *stream, double *bytes_p
     double bytes = (double)grid * 256 * 16.0 * 8 * iters;
     *gbs = bytes / (ms_best * 1e-3) / 1e9;
     *bytes_per_clk_per_cu = bytes / (ms_best * 1e-3) / ((double)prop.clockRate * 1e3) / prop.multiProcessorCount;
+    return MS_OK;
+}
+
+extern "C" int32_t ms_calibrate_l2(const void *src, void *scratch, void *stream, double *gbs)
+{
+    if (!src || !scratch || !gbs) return fail(MS_ERR_BAD_ARG, "ms_calibrate_l2: NULL argument");
+    std::vector<std::string> defs = {"-DMODE=4", "-DCAL_DT=0"};
+    CalibKernel ck;
+    int32_t rc = load_calib(defs, mix64(0xCA11B4ull), &ck);
+    if (rc != MS_OK) return rc;
+    int dev = 0;
+    hipDeviceProp_t prop;
+    HIP_TRY(hipGetDevice(&dev));
+    HIP_TRY(hipGetDeviceProperties(&prop, dev));
+    unsigned grid = (unsigned)prop.multiProcessorCount * 8;
+    int reps = 2000;
+    void *args[] = {&src, &src, &src, &scratch, &reps};
+    double ms_best = 0;
+    rc = time_launches(ck.fn, grid, args, (hipStream_t)stream, 3, &ms_best);
+    (void)hipModuleUnload(ck.mod);
+    if (rc != MS_OK) return rc;
+    *gbs = (double)grid * 256 * 16.0 * 8 * reps / (ms_best * 1e-3) / 1e9;
     return MS_OK;
 }

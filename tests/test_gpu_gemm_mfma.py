@@ -78,6 +78,14 @@ def test_c2_fp16_gemm_1024():
     traces.append(mk(161632, [8, 2, 2, 2], [8, 1, 2, 4], [32, 1, 1, 1], cache=3, vec=8, vec_b=4, pad=2))
     traces.append(mk(323216, [4, 1, 4, 2], [4, 2, 2, 2], [16, 1, 1, 4], cache=4, vec=8, vec_b=4, pad=1, reorder=2, cw=1))  # ping-pong
     traces.append(mk(161632, [8, 2, 2, 2], [8, 1, 2, 4], [16, 1, 1, 2], cache=4, vec=8, vec_b=2, pad=2))
+    # direct-to-LDS ring, 2 / 3 / 4 stages, both intrinsics with 8-element fragments
+    traces.append(mk(323216, [4, 2, 2, 2], [4, 2, 2, 2], [16, 1, 4, 1], unroll=64, cache=5, pad=0, reorder=2, cw=1))
+    traces.append(mk(161632, [8, 2, 2, 2], [8, 2, 2, 2], [16, 1, 2, 1], unroll=0, cache=6, pad=0, reorder=0))
+    traces.append(mk(323216, [8, 1, 4, 1], [4, 2, 2, 2], [32, 1, 1, 2], unroll=16, cache=7, pad=0, reorder=1, cw=1))
+    traces.append(mk(161632, [8, 2, 4, 1], [8, 4, 2, 1], [8, 2, 2, 1], unroll=64, cache=5, pad=0, reorder=2))  # BK = 128
+    # persistent workgroups on the direct-to-LDS ring
+    traces.append(mk(323216, [4, 1, 4, 2], [4, 2, 2, 2], [16, 1, 4, 1], unroll=64, cache=5, pad=0, reorder=3, cw=0))
+    traces.append(mk(161632, [8, 2, 4, 1], [8, 4, 2, 1], [16, 1, 2, 1], unroll=64, cache=6, pad=0, reorder=3, cw=1))
     ref = None
     for n, t in enumerate(traces):
         print("trace", n, t.decisions(), flush=True)
@@ -161,3 +169,28 @@ def test_bmm_instances_with_distinct_inputs():
             continue
         for r in range(3):
             compare.assert_float_close(got[r], refs[r], compare.RTOL_HALF, "instance %d trace %d" % (r, n))
+
+
+def test_persistent_workgroups_many_tiles_per_workgroup():
+    """reorder = 3: 3 instances x 256 tiles = 768 tiles for at most 256 workgroups, so every workgroup walks
+    through several tiles, crossing instance boundaries; distinct inputs per instance; fp32 output."""
+    M, N, K = 256, 256, 192
+    ins = [list(I.gemm_inputs(M, N, K, "f16", s, "normal", 1.0)) for s in (1, 2, 3)]
+    refs = [O.gemm(a, b) for a, b in ins]
+    op = B.gemm_op(M, N, K, "f16", "f32")
+    space = op.space()
+
+    def mk(mfma, i, j, k, unroll=0, cache=5, pad=0, reorder=3, cw=0):
+        return B.make_trace(space, [[mfma], i, j, k, [unroll], [cache], [8], [8], [pad], [reorder], [cw]])
+
+    traces = [mk(161632, [16, 1, 1, 1], [16, 1, 1, 1], [3, 1, 1, 2]),           # 16x16 tiles, 1 wave, K0 = 3
+              mk(161632, [16, 1, 1, 1], [8, 1, 2, 1], [6, 1, 1, 1], cache=7),   # 4-stage ring, BK = 32, K0 = 6
+              mk(323216, [8, 1, 1, 1], [8, 1, 1, 1], [3, 1, 2, 2], unroll=64, cache=6, cw=1),
+              mk(161632, [8, 1, 2, 1], [16, 1, 1, 1], [3, 2, 1, 1], unroll=16, cache=5, cw=1)]
+    for n, t in enumerate(traces):
+        print("trace", n, t.decisions(), flush=True)
+        got = run_variant_distinct(op, space, t, ins, "f32", (M, N))
+        if got is None:
+            continue
+        for r in range(3):
+            compare.assert_float_close(got[r], refs[r], 1e-4, "instance %d trace %d" % (r, n))
