@@ -160,8 +160,17 @@ typedef enum ms_slot_id {
                               2 = i outer with workgroups grouped per XCD, 3 (with cache_read 5..7) = as 2 with
                               persistent workgroups that loop over tiles */
     MS_SLOT_VECTORIZE_B = 10, /* categorical: elements per global load instruction of operand B (conv: W) */
-    MS_SLOT_CACHE_WRITE = 11  /* categorical (matrix-core kernels): 0 = results go from registers to global memory,
+    MS_SLOT_CACHE_WRITE = 11, /* categorical (matrix-core kernels): 0 = results go from registers to global memory,
                                  1 = the workgroup's output tile is staged in LDS and written as whole rows */
+    MS_SLOT_COMPUTE_AT = 12   /* categorical (conv2d; Table 2, sample-compute-location): loop under which the
+                                 cache-read of the activations X is computed.  0 = under k0: every k step stages its
+                                 im2col tile; 1 = under fuse(i0, j0): the input rows the workgroup's output tile needs
+                                 are staged once (zero halo included) and every k step reads its operands from that
+                                 patch; the cache_read decision then governs the weights only (1, 2 or 3);
+                                 2 = as 1, and the cache-read of the weights W moves above the tile loop: persistent
+                                 workgroups own runs of consecutive tiles, the weights of the current instance stay in
+                                 LDS, the k loop has no barrier and no global load; cache_read 1 = the next patch is
+                                 loaded between tiles, 2 = it is prefetched into registers during the k loop */
 } ms_slot_id;
 
 /* Tensorize candidates: (m, n, k) of one matrix-core instruction.  The code
@@ -210,6 +219,7 @@ typedef struct ms_slot {
 #define MS_SPACE_STORAGE_ALIGN 0x10u/* sample LDS padding; off = no padding */
 #define MS_SPACE_REORDER 0x20u      /* sample the grid loop order; off = i outer */
 #define MS_SPACE_CACHE_WRITE 0x40u   /* sample LDS staging of the output tile; off = direct stores */
+#define MS_SPACE_COMPUTE_AT 0x80u    /* conv2d: sample the loop that holds the cache-read of X; off = under k0 */
 #define MS_SPACE_DEFAULT 0xffffffffu
 
 typedef enum ms_family { MS_FAM_GEMM_ALU = 0, MS_FAM_GEMM_MFMA = 1, MS_FAM_DWCONV = 2 } ms_family;
@@ -289,7 +299,8 @@ typedef struct ms_variant_params {
     int32_t reorder;
     int32_t vec_b;          /* elements per global load of B */
     int32_t cache_write;    /* 0, 1 as in MS_SLOT_CACHE_WRITE */
-    int32_t reserved[6];
+    int32_t compute_at;     /* 0, 1 as in MS_SLOT_COMPUTE_AT */
+    int32_t reserved[5];
     uint64_t key;           /* hash of everything that selects the kernel */
 } ms_variant_params;
 

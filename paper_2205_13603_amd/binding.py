@@ -16,8 +16,9 @@ OP_GEMM, OP_BMM_NT, OP_BMM_NN, OP_CONV2D_NHWC, OP_DWCONV2D_NHWC = range(5)
 F32, F16, BF16, I8, I32 = range(5)
 SLOT_PERFECT_TILE, SLOT_CATEGORICAL = 0, 1
 (SLOT_TENSORIZE, SLOT_TILE_I, SLOT_TILE_J, SLOT_TILE_C, SLOT_TILE_K, SLOT_UNROLL, SLOT_CACHE_READ, SLOT_VECTORIZE,
- SLOT_STORAGE_ALIGN, SLOT_REORDER, SLOT_VECTORIZE_B, SLOT_CACHE_WRITE) = range(12)
+ SLOT_STORAGE_ALIGN, SLOT_REORDER, SLOT_VECTORIZE_B, SLOT_CACHE_WRITE, SLOT_COMPUTE_AT) = range(13)
 SPACE_TENSORIZE, SPACE_CACHE_READ, SPACE_VECTORIZE, SPACE_UNROLL, SPACE_STORAGE_ALIGN, SPACE_REORDER, SPACE_CACHE_WRITE = 1, 2, 4, 8, 16, 32, 64
+SPACE_COMPUTE_AT = 128
 SPACE_DEFAULT = 0xFFFFFFFF
 FAM_GEMM_ALU, FAM_GEMM_MFMA, FAM_DWCONV = range(3)
 MAX_SLOTS, MAX_FACTORS, MAX_CANDS, MAX_LOOPS = 16, 4, 8, 8
@@ -76,7 +77,7 @@ class ms_variant_params(C.Structure):
                 ("block_n", C.c_int32), ("block_k", C.c_int32), ("grid", C.c_int32 * 3), ("threads", C.c_int32),
                 ("waves", C.c_int32), ("acc_per_thread", C.c_int32), ("lds_bytes", C.c_int32),
                 ("cache_read", C.c_int32), ("vec", C.c_int32), ("unroll", C.c_int32), ("unroll_k1", C.c_int32),
-                ("unroll_k2", C.c_int32), ("lds_pad", C.c_int32), ("reorder", C.c_int32), ("vec_b", C.c_int32), ("cache_write", C.c_int32), ("reserved", C.c_int32 * 6),
+                ("unroll_k2", C.c_int32), ("lds_pad", C.c_int32), ("reorder", C.c_int32), ("vec_b", C.c_int32), ("cache_write", C.c_int32), ("compute_at", C.c_int32), ("reserved", C.c_int32 * 5),
                 ("key", C.c_uint64)]
 
     def as_dict(self):

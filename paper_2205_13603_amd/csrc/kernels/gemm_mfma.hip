@@ -28,7 +28,25 @@
 // read, and the 16 or 32 lanes of a row group read consecutive addresses
 // (no bank conflict).  Operands whose contiguous dimension is not k (B of
 // C = A.B, the conv weights) are transposed in registers on the way in.
+//
+// conv2d with COMPUTE_AT 1 (the cache-read of X computed under the workgroup tile loop instead of
+// under k0): the input rows that the tile's BM output pixels need, zero halo included, are staged
+// once as [patch row][patch column][Cin] and the A fragments of every k step are read straight
+// from that patch (pixel of the lane + tap offset + channel offset); the k0 loop then stages the
+// weights only.  No im2col copy exists anywhere, and X is fetched once per tile instead of KH*KW times.
+//
+// conv2d with COMPUTE_AT 2: additionally the cache-read of W sits above the tile loop.  Workgroups are
+// persistent (about one per compute unit) and own a run of consecutive tiles; the weights of the current
+// instance stay in LDS in fragment layout (reloaded only when the run crosses into the next instance), the
+// k loop is free of barriers and global loads, and with CACHE_READ 2 the next tile's input patch is
+// fetched into registers while the current tile is multiplied.
 #include "common.h"
+
+#ifndef COMPUTE_AT
+#define COMPUTE_AT 0
+#endif
+#define CONV_PATCH (IS_CONV && COMPUTE_AT >= 1)
+#define CONV_RESIDENT (IS_CONV && COMPUTE_AT == 2)
 
 #define NWAVES (I2 * J2)
 #define LANE_GROUPS (64 / MI_M)
@@ -57,7 +75,8 @@ __device__ __forceinline__ int lds_slot(int n)
     return n;
 #endif
 }
-constexpr int STAGE_BYTES = KG * (PLANE_A + PLANE_B);
+constexpr int A_STAGE_BYTES = CONV_PATCH ? 0 : KG * PLANE_A; // the per-k-step stage holds A unless X is resident as a patch
+constexpr int STAGE_BYTES = A_STAGE_BYTES + KG * PLANE_B;
 constexpr int STAGES = CACHE_READ >= 2 ? 2 : 1;
 constexpr int KSTEPS = K1 * K2 * K3;              // MFMA k steps per tile
 
@@ -280,8 +299,130 @@ __device__ __forceinline__ void jmajor_store(const jmajor_stage &st, char *__res
 
 #define B_KMAJOR (!IS_CONV && SB_K == 1 && SB_J != 1)
 
+#if CONV_PATCH
+// ---- resident input patch (COMPUTE_AT 1)
+constexpr int P_ROWS_OUT = BM % CV_OW == 0 ? BM / CV_OW : (CV_OW + BM - 2) / CV_OW + 1; // output rows a tile can touch
+constexpr int P_R = (P_ROWS_OUT - 1) * CV_STRIDE + CV_KH;   // patch rows
+constexpr int P_W = (CV_OW - 1) * CV_STRIDE + CV_KW;        // patch columns (column pc = input column pc - pad)
+constexpr int P_PS = CV_CIN * ES + (LDS_PAD ? 16 : 0);      // bytes per patch pixel; the pad staggers neighbouring pixels over the banks
+constexpr int P_RS = P_W * P_PS;                            // bytes per patch row
+constexpr int PATCH_BYTES = ((P_R * P_RS + 15) / 16) * 16;
+static_assert(CV_CIN % MI_K == 0, "resident input patch: an MFMA k step must stay inside one filter tap");
+static_assert((CV_OH * CV_OW) % BM == 0, "resident input patch: tiles must not straddle images");
+
+struct conv_ctx {
+    const char *patch; // + this lane's k-group offset
+    int pix[TM];       // byte offset of the lane's output pixel (tap 0, 0) per MFMA tile row
+};
+
+// The patch goes global memory -> registers -> LDS in two calls (fetch, commit), so that a persistent
+// workgroup can fetch the next tile's patch while it multiplies the current one.  A patch row is
+// P_CR vectors of VEC channels; threads are laid over rows so that a thread's column, its channel
+// vector and the in-image test of the column do not depend on the tile.
+constexpr int P_CPP = CV_CIN / VEC;                              // vectors per pixel
+constexpr int P_CR = P_W * P_CPP;                                // vectors per patch row
+constexpr int P_PPR = (P_CR + NTHREADS - 1) / NTHREADS;          // passes of the workgroup over one row
+constexpr int P_RPP = NTHREADS >= P_CR ? NTHREADS / P_CR : 1;    // rows per pass
+constexpr int P_PASSES = (P_R + P_RPP - 1) / P_RPP;
+constexpr int P_ITERS = P_PASSES * P_PPR;
+
+struct patch_regs {
+    vec_t<in_t, VEC> r[P_ITERS];
+};
+
+struct patch_map {   // per thread, the same for every tile
+    int row_t;       // row inside a pass (0 when a row takes the whole workgroup)
+    int goff[P_PPR]; // element offset of the thread's vector from the start of an input row (may be negative: left halo)
+    int loff[P_PPR]; // byte offset inside a patch row
+    bool ok[P_PPR];  // the vector exists and its column is inside the image
+};
+
+__device__ __forceinline__ void patch_map_init(patch_map &pm, int tid)
+{
+    pm.row_t = NTHREADS >= P_CR ? tid / P_CR : 0;
+#pragma unroll
+    for (int s = 0; s < P_PPR; ++s) {
+        const int q = NTHREADS >= P_CR ? tid % P_CR : s * NTHREADS + tid;
+        const int pc = q / P_CPP, c = q % P_CPP;
+        const int iw = pc - CV_PAD;
+        pm.goff[s] = iw * CV_CIN + c * VEC;
+        pm.loff[s] = pc * P_PS + c * (VEC * ES);
+        pm.ok[s] = q < P_CR && pm.row_t < P_RPP && (unsigned)iw < (unsigned)CV_W;
+    }
+}
+
+// request input rows [ih_lo, ih_lo + P_R) of the image that holds output tile i0 (X: the instance's activations)
+__device__ __forceinline__ void patch_fetch(patch_regs &pr, const patch_map &pm, const in_t *__restrict__ X, int i0)
+{
+    const int m0 = i0 * BM;
+    const int n = m0 / (CV_OH * CV_OW);
+    const int ih_lo = ((m0 % (CV_OH * CV_OW)) / CV_OW) * CV_STRIDE - CV_PAD;
+    const in_t *img = X + (long)n * (CV_H * CV_W * CV_CIN);
+#pragma unroll
+    for (int p = 0; p < P_PASSES; ++p)
+#pragma unroll
+        for (int s = 0; s < P_PPR; ++s) {
+            const int row = p * P_RPP + pm.row_t;
+            const int ih = ih_lo + row;
+            const bool ok = pm.ok[s] && (unsigned)ih < (unsigned)CV_H && (P_R % P_RPP == 0 || row < P_R);
+            // elements outside the image read element 0 (always mapped) and become zero: no divergent loads
+            const int off = ok ? ih * (CV_W * CV_CIN) + pm.goff[s] : 0;
+            vec_t<in_t, VEC> x = *reinterpret_cast<const vec_t<in_t, VEC> *>(img + off);
+            if (!ok) {
+#pragma unroll
+                for (int q = 0; q < VEC; ++q) x.v[q] = 0;
+            }
+            pr.r[p * P_PPR + s] = x;
+        }
+}
+
+// write the fetched patch to LDS (halo elements as zeros)
+__device__ __forceinline__ void patch_commit(const patch_regs &pr, const patch_map &pm, char *__restrict__ patch, int tid)
+{
+#pragma unroll
+    for (int p = 0; p < P_PASSES; ++p)
+#pragma unroll
+        for (int s = 0; s < P_PPR; ++s) {
+            const int row = p * P_RPP + pm.row_t;
+            const int q = NTHREADS >= P_CR ? tid % P_CR : s * NTHREADS + tid;
+            const bool live = (NTHREADS >= P_CR ? pm.row_t < P_RPP : q < P_CR) && (P_R % P_RPP == 0 || row < P_R);
+            if (live) *reinterpret_cast<vec_t<in_t, VEC> *>(patch + row * P_RS + pm.loff[s]) = pr.r[p * P_PPR + s];
+        }
+}
+
+__device__ __forceinline__ void conv_ctx_init(conv_ctx &cx, const char *patch, int i0, int wi, int lrow, int lgrp)
+{
+    const int m0 = i0 * BM;
+    const int oh_lo = (m0 % (CV_OH * CV_OW)) / CV_OW;
+    cx.patch = patch + lgrp * FRAG_BYTES;
+#pragma unroll
+    for (int r1 = 0; r1 < I1; ++r1)
+#pragma unroll
+        for (int r3 = 0; r3 < I3; ++r3) {
+            const int trow = (r1 * I2 + wi) * I3 + r3;
+            const int mm = (m0 + trow * MI_M + lrow) % (CV_OH * CV_OW);
+            const int oh = mm / CV_OW, ow = mm % CV_OW;
+            cx.pix[r1 * I3 + r3] = (oh - oh_lo) * CV_STRIDE * P_RS + ow * CV_STRIDE * P_PS;
+        }
+}
+
+// byte offset inside the patch of MFMA k step `step` of tile k0, relative to a pixel's (tap 0, 0, channel 0)
+__device__ __forceinline__ int conv_koff(int k0, int step)
+{
+    const int kg = k0 * BK + step * MI_K; // wave-uniform
+    const int tap = kg / CV_CIN, ci = kg % CV_CIN;
+    const int kh = tap / CV_KW, kw = tap % CV_KW;
+    return kh * P_RS + kw * P_PS + ci * ES;
+}
+#else
+struct conv_ctx {
+};
+#endif
+
 struct tile_stage {
+#if !CONV_PATCH
     kmajor_stage<BM, VEC> a;
+#endif
 #if B_KMAJOR
     kmajor_stage<BN, VEC_B> b;
     static constexpr int UNITS_B = kmajor_stage<BN, VEC_B>::ITERS;
@@ -289,9 +430,9 @@ struct tile_stage {
     jmajor_stage b;
     static constexpr int UNITS_B = jmajor_stage::ITERS * KP;
 #endif
-    static constexpr int UNITS_A = kmajor_stage<BM, VEC>::ITERS;
+    static constexpr int UNITS_A = CONV_PATCH ? 0 : kmajor_stage<BM, VEC>::ITERS;
     static constexpr int UNITS = UNITS_A + UNITS_B; // global load instructions per thread and tile
-    static constexpr int SUNITS_A = kmajor_stage<BM, VEC>::ITERS;
+    static constexpr int SUNITS_A = UNITS_A;
     static constexpr int SUNITS = SUNITS_A + (B_KMAJOR ? UNITS_B : UNITS_B / KP); // store units (one per staged vector / block)
 };
 
@@ -300,7 +441,9 @@ __device__ __forceinline__ void stage_load(tile_stage &st, const in_t *__restric
                                            int tid, int u0 = 0, int u1 = tile_stage::UNITS)
 {
     const long k0e = (long)k0 * BK;
+#if !CONV_PATCH
     kmajor_load<BM, VEC, true>(st.a, A, (long)i0 * BM, k0e, SA_I, tid, u0, u1);
+#endif
 #if B_KMAJOR
     kmajor_load<BN, VEC_B, false>(st.b, B, (long)j0 * BN, k0e, SB_J, tid, u0 - tile_stage::UNITS_A, u1 - tile_stage::UNITS_A);
 #else
@@ -311,21 +454,29 @@ __device__ __forceinline__ void stage_load(tile_stage &st, const in_t *__restric
 // write store units [u0, u1) of a staged tile to the LDS stage at `lds`
 __device__ __forceinline__ void stage_store(const tile_stage &st, char *__restrict__ lds, int tid, int u0 = 0, int u1 = tile_stage::SUNITS)
 {
+#if !CONV_PATCH
     kmajor_store<BM, VEC, PLANE_A>(st.a, lds, tid, u0, u1);
+#endif
 #if B_KMAJOR
-    kmajor_store<BN, VEC_B, PLANE_B>(st.b, lds + KG * PLANE_A, tid, u0 - tile_stage::SUNITS_A, u1 - tile_stage::SUNITS_A);
+    kmajor_store<BN, VEC_B, PLANE_B>(st.b, lds + A_STAGE_BYTES, tid, u0 - tile_stage::SUNITS_A, u1 - tile_stage::SUNITS_A);
 #else
-    jmajor_store(st.b, lds + KG * PLANE_A, tid, u0 - tile_stage::SUNITS_A, u1 - tile_stage::SUNITS_A);
+    jmajor_store(st.b, lds + A_STAGE_BYTES, tid, u0 - tile_stage::SUNITS_A, u1 - tile_stage::SUNITS_A);
 #endif
 }
 
 // fragments of slot `slot` (K3 consecutive MFMA k steps) for the wave's TM x TN tiles
+// (COMPUTE_AT 1: the A fragments come from the resident input patch; `la` is unused, `kcur` is the tile's k0)
 __device__ __forceinline__ void read_frags(frag_t (&fa)[K3][TM], frag_t (&fb)[K3][TN], const char *__restrict__ la,
-                                           const char *__restrict__ lb, int slot, int wi, int wj, int lrow)
+                                           const char *__restrict__ lb, int slot, int wi, int wj, int lrow, const conv_ctx &cx, int kcur)
 {
 #pragma unroll
     for (int q = 0; q < K3; ++q) {
         const int step = slot * K3 + q;
+#if CONV_PATCH
+        const int koff = conv_koff(kcur, step);
+#pragma unroll
+        for (int tm = 0; tm < TM; ++tm) fa[q][tm] = *reinterpret_cast<const frag_t *>(cx.patch + (cx.pix[tm] + koff));
+#else
 #pragma unroll
         for (int r1 = 0; r1 < I1; ++r1)
 #pragma unroll
@@ -334,6 +485,7 @@ __device__ __forceinline__ void read_frags(frag_t (&fa)[K3][TM], frag_t (&fb)[K3
                 fa[q][r1 * I3 + r3] =
                     *reinterpret_cast<const frag_t *>(la + step * LANE_GROUPS * PLANE_A + lds_slot(trow * MI_M + lrow) * FRAG_BYTES);
             }
+#endif
 #pragma unroll
         for (int c1 = 0; c1 < J1; ++c1)
 #pragma unroll
@@ -365,15 +517,16 @@ __device__ __forceinline__ void mfma_slot(accv_t (&acc)[TM][TN], const frag_t (&
 #define NS_ (K1 * K2)
 __device__ __forceinline__ void pipelined_step(accv_t (&acc)[TM][TN], const char *__restrict__ cur, char *__restrict__ nxt,
                                                const tile_stage &ready, tile_stage &inflight, const in_t *__restrict__ A,
-                                               const in_t *__restrict__ B, int i0, int j0, int kload, int tid, int lgrp, int wi, int wj, int lrow)
+                                               const in_t *__restrict__ B, int i0, int j0, int kload, int tid, int lgrp, int wi, int wj, int lrow,
+                                               const conv_ctx &cx, int kcur)
 {
     const char *la = cur + lgrp * PLANE_A;
-    const char *lb = cur + KG * PLANE_A + lgrp * PLANE_B;
+    const char *lb = cur + A_STAGE_BYTES + lgrp * PLANE_B;
     frag_t fa[2][K3][TM], fb[2][K3][TN];
-    read_frags(fa[0], fb[0], la, lb, 0, wi, wj, lrow);
+    read_frags(fa[0], fb[0], la, lb, 0, wi, wj, lrow, cx, kcur);
 #pragma unroll
     for (int s = 0; s < NS_; ++s) {
-        if (s + 1 < NS_) read_frags(fa[(s + 1) & 1], fb[(s + 1) & 1], la, lb, s + 1, wi, wj, lrow);
+        if (s + 1 < NS_) read_frags(fa[(s + 1) & 1], fb[(s + 1) & 1], la, lb, s + 1, wi, wj, lrow, cx, kcur);
         stage_store(ready, nxt, tid, s * tile_stage::SUNITS / NS_, (s + 1) * tile_stage::SUNITS / NS_);
         stage_load(inflight, A, B, i0, j0, kload, tid, s * tile_stage::UNITS / NS_, (s + 1) * tile_stage::UNITS / NS_);
         mfma_slot(acc, fa[s & 1], fb[s & 1]);
@@ -382,18 +535,35 @@ __device__ __forceinline__ void pipelined_step(accv_t (&acc)[TM][TN], const char
 }
 
 // multiply the tile staged at `stage_base` (rolled / partly unrolled k1, k2 loops)
-__device__ __forceinline__ void multiply_tile(accv_t (&acc)[TM][TN], const char *__restrict__ stage_base, int lgrp, int wi, int wj, int lrow)
+__device__ __forceinline__ void multiply_tile(accv_t (&acc)[TM][TN], const char *__restrict__ stage_base, int lgrp, int wi, int wj, int lrow,
+                                              const conv_ctx &cx, int kcur)
 {
     const char *la = stage_base + lgrp * PLANE_A;
-    const char *lb = stage_base + KG * PLANE_A + lgrp * PLANE_B;
+    const char *lb = stage_base + A_STAGE_BYTES + lgrp * PLANE_B;
 #pragma unroll UNROLL_K1
     for (int k1 = 0; k1 < K1; ++k1) {
 #pragma unroll UNROLL_K2
         for (int k2 = 0; k2 < K2; ++k2) {
             frag_t fa[K3][TM], fb[K3][TN];
-            read_frags(fa, fb, la, lb, k1 * K2 + k2, wi, wj, lrow);
+            read_frags(fa, fb, la, lb, k1 * K2 + k2, wi, wj, lrow, cx, kcur);
             mfma_slot(acc, fa, fb);
         }
+    }
+}
+
+// the same with k1, k2 fully unrolled: slot s issues the LDS reads of slot s+1 ahead of its own MFMAs
+__device__ __forceinline__ void multiply_tile_unrolled(accv_t (&acc)[TM][TN], const char *__restrict__ stage_base, int lgrp, int wi, int wj,
+                                                       int lrow, const conv_ctx &cx, int kcur)
+{
+    const char *la = stage_base + lgrp * PLANE_A;
+    const char *lb = stage_base + A_STAGE_BYTES + lgrp * PLANE_B;
+    frag_t fa[2][K3][TM], fb[2][K3][TN];
+    read_frags(fa[0], fb[0], la, lb, 0, wi, wj, lrow, cx, kcur);
+#pragma unroll
+    for (int s = 0; s < K1 * K2; ++s) {
+        if (s + 1 < K1 * K2) read_frags(fa[(s + 1) & 1], fb[(s + 1) & 1], la, lb, s + 1, wi, wj, lrow, cx, kcur);
+        mfma_slot(acc, fa[s & 1], fb[s & 1]);
+        __builtin_amdgcn_sched_barrier(0);
     }
 }
 
@@ -730,6 +900,90 @@ ms_kernel(const void *__restrict__ a_, const void *__restrict__ b_, const void *
     }
     DL_WAIT_VM(0); // the re-loads past the end must land before the workgroup's LDS is released
 }
+#elif CONV_RESIDENT
+// --------------------------------------------------------------------------------------
+// conv2d, COMPUTE_AT 2: persistent workgroups, resident weights, input patch per tile.
+// Tile list of the launch: index f = (inst * J0 + j0) * I0 + i0; workgroup w owns the run
+// [w * run, (w + 1) * run): consecutive tiles share their weights and neighbouring patches.
+extern "C" __global__ void __launch_bounds__(NTHREADS)
+ms_kernel(const void *__restrict__ a_, const void *__restrict__ b_, const void *__restrict__ bias_, void *__restrict__ c_, int instances)
+{
+    const int tid = threadIdx.x;
+    const int lane = tid % 64, wave = tid / 64;
+    const int wi = wave / J2, wj = wave % J2;
+    const int lrow = lane % MI_M, lgrp = lane / MI_M;
+
+    constexpr int W_BYTES = K0 * STAGE_BYTES;                      // all k steps of the weights, fragment layout
+    constexpr int LDS_BYTES = W_BYTES + PATCH_BYTES + (CACHE_WRITE ? BM * CROW : 0);
+    __shared__ __attribute__((aligned(16))) char lds[LDS_BYTES];
+    char *const patch = lds + W_BYTES;
+    char *const cstage = lds + W_BYTES + PATCH_BYTES;
+
+    const long total = (long)I0 * J0 * instances;
+    const long run = (total + gridDim.x - 1) / gridDim.x;
+    const long first = (long)blockIdx.x * run;
+    const long last = first + run < total ? first + run : total;
+    if (first >= last) return;
+
+    patch_map pm;
+    patch_regs pr;
+    patch_map_init(pm, tid);
+    {
+        const int inst = (int)(first / (I0 * J0)), i0 = (int)(first % I0);
+        patch_fetch(pr, pm, (const in_t *)a_ + (long)inst * A_INST, i0);
+        patch_commit(pr, pm, patch, tid);
+    }
+    long have_w = -1; // (inst, j0) of the weights in LDS
+#pragma unroll 1
+    for (long f = first; f < last; ++f) {
+        const int i0 = (int)(f % I0), j0 = (int)((f / I0) % J0), inst = (int)(f / (I0 * J0));
+        if (f / I0 != have_w) {
+            // every wavefront has passed the barrier that ended the previous tile's k loop: the old weights are dead
+            have_w = f / I0;
+            const in_t *Wt = (const in_t *)b_ + (long)inst * B_INST;
+            tile_stage st;
+#pragma unroll 1
+            for (int k0 = 0; k0 < K0; ++k0) {
+                stage_load(st, nullptr, Wt, 0, j0, k0, tid);
+                stage_store(st, lds + k0 * STAGE_BYTES, tid);
+            }
+        }
+        __syncthreads(); // patch and weights are in place
+#if CACHE_READ >= 2
+        if (f + 1 < last) {
+            const long g = f + 1;
+            patch_fetch(pr, pm, (const in_t *)a_ + (g / (I0 * J0)) * A_INST, (int)(g % I0));
+        }
+#endif
+        conv_ctx cx;
+        conv_ctx_init(cx, patch, i0, wi, lrow, lgrp);
+        accv_t acc[TM][TN];
+#pragma unroll
+        for (int tm = 0; tm < TM; ++tm)
+#pragma unroll
+            for (int tn = 0; tn < TN; ++tn)
+#pragma unroll
+                for (int e = 0; e < ACC_N; ++e) acc[tm][tn][e] = 0;
+#pragma unroll 1
+        for (int k0 = 0; k0 < K0; ++k0) {
+#if UNROLL_K1 == K1 && UNROLL_K2 == K2 && K1 * K2 > 1
+            multiply_tile_unrolled(acc, lds + k0 * STAGE_BYTES, lgrp, wi, wj, lrow, cx, k0);
+#else
+            multiply_tile(acc, lds + k0 * STAGE_BYTES, lgrp, wi, wj, lrow, cx, k0);
+#endif
+        }
+        __syncthreads(); // the patch has been read by everyone
+        if (f + 1 < last) {
+#if CACHE_READ < 2
+            const long g = f + 1;
+            patch_fetch(pr, pm, (const in_t *)a_ + (g / (I0 * J0)) * A_INST, (int)(g % I0));
+#endif
+            patch_commit(pr, pm, patch, tid);
+        }
+        out_t *C = (out_t *)c_ + (long)inst * ((long)DIM_M * DIM_N);
+        write_tile(acc, C, bias_, inst, i0, j0, cstage, tid, wi, wj, lrow, lgrp);
+    }
+}
 #else // REORDER != 3
 extern "C" __global__ void __launch_bounds__(NTHREADS)
 ms_kernel(const void *__restrict__ a_, const void *__restrict__ b_, const void *__restrict__ bias_, void *__restrict__ c_, int instances)
@@ -752,8 +1006,26 @@ ms_kernel(const void *__restrict__ a_, const void *__restrict__ b_, const void *
 #else
     constexpr int OPND_BYTES = STAGES * STAGE_BYTES;
 #endif
-    constexpr int LDS_BYTES = (CACHE_WRITE && BM * CROW > OPND_BYTES) ? BM * CROW : OPND_BYTES;
+#if CONV_PATCH
+    constexpr int RES_BYTES = OPND_BYTES + PATCH_BYTES; // weight stages, then the resident input patch
+#else
+    constexpr int RES_BYTES = OPND_BYTES;
+#endif
+    constexpr int LDS_BYTES = (CACHE_WRITE && BM * CROW > RES_BYTES) ? BM * CROW : RES_BYTES;
     __shared__ __attribute__((aligned(16))) char lds[LDS_BYTES];
+
+    conv_ctx cx;
+#if CONV_PATCH
+    // every staging mode below passes a barrier between its first LDS writes and its first fragment reads
+    {
+        patch_map pm;
+        patch_regs pr;
+        patch_map_init(pm, tid);
+        patch_fetch(pr, pm, A, i0);
+        patch_commit(pr, pm, lds + OPND_BYTES, tid);
+    }
+    conv_ctx_init(cx, lds + OPND_BYTES, i0, wi, lrow, lgrp);
+#endif
 
     accv_t acc[TM][TN];
 #pragma unroll
@@ -822,20 +1094,20 @@ ms_kernel(const void *__restrict__ a_, const void *__restrict__ b_, const void *
 #pragma unroll 1
         for (int k0 = 0; k0 < K0; k0 += 2) {
 #if UNROLL_K1 == K1 && UNROLL_K2 == K2
-            pipelined_step(acc, lds, lds + STAGE_BYTES, st1, st0, A, B, i0, j0, k0 + 2 < K0 ? k0 + 2 : K0 - 1, tid, lgrp, wi, wj, lrow);
+            pipelined_step(acc, lds, lds + STAGE_BYTES, st1, st0, A, B, i0, j0, k0 + 2 < K0 ? k0 + 2 : K0 - 1, tid, lgrp, wi, wj, lrow, cx, k0);
             __syncthreads();
             if (k0 + 1 < K0) {
-                pipelined_step(acc, lds + STAGE_BYTES, lds, st0, st1, A, B, i0, j0, k0 + 3 < K0 ? k0 + 3 : K0 - 1, tid, lgrp, wi, wj, lrow);
+                pipelined_step(acc, lds + STAGE_BYTES, lds, st0, st1, A, B, i0, j0, k0 + 3 < K0 ? k0 + 3 : K0 - 1, tid, lgrp, wi, wj, lrow, cx, k0 + 1);
                 __syncthreads();
             }
 #else
             stage_load(st0, A, B, i0, j0, k0 + 2 < K0 ? k0 + 2 : K0 - 1, tid);
-            multiply_tile(acc, lds, lgrp, wi, wj, lrow);
+            multiply_tile(acc, lds, lgrp, wi, wj, lrow, cx, k0);
             stage_store(st1, lds + STAGE_BYTES, tid);
             __syncthreads();
             if (k0 + 1 < K0) {
                 stage_load(st1, A, B, i0, j0, k0 + 3 < K0 ? k0 + 3 : K0 - 1, tid);
-                multiply_tile(acc, lds + STAGE_BYTES, lgrp, wi, wj, lrow);
+                multiply_tile(acc, lds + STAGE_BYTES, lgrp, wi, wj, lrow, cx, k0 + 1);
                 stage_store(st0, lds, tid);
                 __syncthreads();
             }
@@ -862,7 +1134,7 @@ ms_kernel(const void *__restrict__ a_, const void *__restrict__ b_, const void *
         for (int k0 = 0; k0 < K0; ++k0) {
             frag_t fa[K3][TM], fb[K3][TN];
             const char *base = lds + stage * STAGE_BYTES;
-            read_frags(fa, fb, base + lgrp * PLANE_A, base + KG * PLANE_A + lgrp * PLANE_B, 0, wi, wj, lrow);
+            read_frags(fa, fb, base + lgrp * PLANE_A, base + A_STAGE_BYTES + lgrp * PLANE_B, 0, wi, wj, lrow, cx, k0);
             stage_store(st, lds + (stage ^ 1) * STAGE_BYTES, tid);
             stage_load(st, A, B, i0, j0, k0 + 2 < K0 ? k0 + 2 : K0 - 1, tid);
             __syncthreads();
@@ -891,17 +1163,17 @@ ms_kernel(const void *__restrict__ a_, const void *__restrict__ b_, const void *
         __syncthreads();
 #endif
         const char *la = lds + stage * STAGE_BYTES + lgrp * PLANE_A;
-        const char *lb = lds + stage * STAGE_BYTES + KG * PLANE_A + lgrp * PLANE_B;
+        const char *lb = lds + stage * STAGE_BYTES + A_STAGE_BYTES + lgrp * PLANE_B;
 #if PIPELINED
         // k1, k2 fully unrolled: software pipeline over the NS = K1*K2 slots of this tile.  Slot s
         // first issues the LDS reads of slot s+1 and its share of the next tile's global loads, then
         // its own MFMAs; nothing is moved across a slot boundary.
         {
             frag_t fa[2][K3][TM], fb[2][K3][TN];
-            read_frags(fa[0], fb[0], la, lb, 0, wi, wj, lrow);
+            read_frags(fa[0], fb[0], la, lb, 0, wi, wj, lrow, cx, k0);
 #pragma unroll
             for (int s = 0; s < NS; ++s) {
-                if (s + 1 < NS) read_frags(fa[(s + 1) & 1], fb[(s + 1) & 1], la, lb, s + 1, wi, wj, lrow);
+                if (s + 1 < NS) read_frags(fa[(s + 1) & 1], fb[(s + 1) & 1], la, lb, s + 1, wi, wj, lrow, cx, k0);
 #if CACHE_READ == 2
                 // the last step fetches its own tile again instead of branching: the loop body stays one block
                 stage_load(st, A, B, i0, j0, k0 + 1 < K0 ? k0 + 1 : k0, tid, s * tile_stage::UNITS / NS, (s + 1) * tile_stage::UNITS / NS);
@@ -919,7 +1191,7 @@ ms_kernel(const void *__restrict__ a_, const void *__restrict__ b_, const void *
 #pragma unroll UNROLL_K2
             for (int k2 = 0; k2 < K2; ++k2) {
                 frag_t fa[K3][TM], fb[K3][TN];
-                read_frags(fa, fb, la, lb, k1 * K2 + k2, wi, wj, lrow);
+                read_frags(fa, fb, la, lb, k1 * K2 + k2, wi, wj, lrow, cx, k0);
                 mfma_slot(acc, fa, fb);
             }
         }

@@ -409,7 +409,8 @@ extern "C" int32_t ms_space_describe(const ms_op *op, uint32_t flags, ms_space *
     const ms_op_desc &d = op->d;
     if (d.in_dtype == MS_F32) flags &= ~MS_SPACE_TENSORIZE;
     if (d.kind == MS_OP_DWCONV2D_NHWC) flags &= ~(MS_SPACE_TENSORIZE | MS_SPACE_VECTORIZE | MS_SPACE_STORAGE_ALIGN | MS_SPACE_CACHE_WRITE);
-    flags &= 0x7fu;
+    if (d.kind != MS_OP_CONV2D_NHWC) flags &= ~MS_SPACE_COMPUTE_AT;
+    flags &= 0xffu;
     out->flags = flags;
     if (d.kind == MS_OP_DWCONV2D_NHWC) {
         out->family = MS_FAM_DWCONV;
@@ -476,9 +477,10 @@ extern "C" int32_t ms_space_describe(const ms_op *op, uint32_t flags, ms_space *
             else add_cat(out, MS_SLOT_REORDER, "reorder", {0, 1, 2});
         }
         if (flags & MS_SPACE_CACHE_WRITE) add_cat(out, MS_SLOT_CACHE_WRITE, "cache_write", {0, 1});
+        if (flags & MS_SPACE_COMPUTE_AT) add_cat(out, MS_SLOT_COMPUTE_AT, "compute_at", {0, 1, 2});
         return MS_OK;
     }
-    flags &= ~MS_SPACE_CACHE_WRITE;
+    flags &= ~(MS_SPACE_CACHE_WRITE | MS_SPACE_COMPUTE_AT);
     out->flags = flags;
     if (d.kind == MS_OP_CONV2D_NHWC)
         return fail(MS_ERR_UNSUPPORTED, "ms_space_describe: conv2d needs the tensorize module (fp16/bf16 inputs)");
@@ -769,8 +771,17 @@ extern "C" int32_t ms_trace_to_text(const ms_op *op, const ms_space *space, cons
         if (p.cache_read) {
             if (p.cache_read >= 5)
                 appendf(s, "cache-read(buffers=[A, B], scope=lds, at=k0, stages=%d, prefetch_distance=%d, direct_to_lds=1)\n", p.cache_read - 3, p.cache_read - 4);
+            else if (p.compute_at == 2)
+                appendf(s, "bind(fuse(i0, j0), persistent workgroup loop over runs of consecutive tiles)\n"
+                           "cache-read(buffer=W, scope=lds, compute-at=root of the tile loop, all k steps resident)\n"
+                           "cache-read(buffer=X, scope=lds, compute-at=fuse(i0, j0), input rows of the tile with zero halo, prefetch_distance=%d)\n",
+                        p.cache_read >= 2 ? 1 : 0);
+            else if (p.compute_at)
+                appendf(s, "cache-read(buffer=X, scope=lds, compute-at=fuse(i0, j0), input rows of the tile with zero halo)\n"
+                           "cache-read(buffer=W, scope=lds, compute-at=k0, stages=%d, prefetch_distance=%d)\n",
+                        p.cache_read >= 2 ? 2 : 1, p.cache_read == 3 ? 2 : (p.cache_read >= 2 ? 1 : 0));
             else
-                appendf(s, "cache-read(buffers=[A, B], scope=lds, at=k0, stages=%d, prefetch_distance=%d)\n", p.cache_read >= 2 ? 2 : 1, p.cache_read == 3 ? 2 : (p.cache_read >= 2 ? 1 : 0));
+                appendf(s, "cache-read(buffers=[A, B], scope=lds, compute-at=k0, stages=%d, prefetch_distance=%d)\n", p.cache_read >= 2 ? 2 : 1, p.cache_read == 3 ? 2 : (p.cache_read >= 2 ? 1 : 0));
             if (p.cache_read == 4) appendf(s, "annotate(block=C, key=wave_groups, value=ping_pong)\n");
             appendf(s, "storage-align(scope=lds, pad_bytes=%d, swizzle=%d)\n", p.lds_pad ? 16 : 0, p.lds_pad == 2);
         }

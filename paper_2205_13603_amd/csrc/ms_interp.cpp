@@ -80,6 +80,7 @@ uint64_t hash_params(const ms_op *op, const ms_variant_params *p)
     add((uint64_t)p->unroll);
     add((uint64_t)p->lds_pad);
     add((uint64_t)p->reorder);
+    add((uint64_t)p->compute_at);
     return h;
 }
 
@@ -151,6 +152,7 @@ extern "C" int32_t ms_trace_validate(const ms_op *op, const ms_space *space, con
     p.cache_write = (int32_t)cat_value(space, trace, MS_SLOT_CACHE_WRITE, 0);
     p.lds_pad = (int32_t)cat_value(space, trace, MS_SLOT_STORAGE_ALIGN, 0);
     p.reorder = (int32_t)cat_value(space, trace, MS_SLOT_REORDER, 0);
+    p.compute_at = (int32_t)cat_value(space, trace, MS_SLOT_COMPUTE_AT, 0);
 
     if (space->family == MS_FAM_GEMM_ALU || space->family == MS_FAM_GEMM_MFMA) {
         if (!get_tile(space, trace, MS_SLOT_TILE_I, p.ti) || !get_tile(space, trace, MS_SLOT_TILE_J, p.tj) ||
@@ -222,11 +224,30 @@ extern "C" int32_t ms_trace_validate(const ms_op *op, const ms_space *space, con
                 int64_t btile = d.b_strides[2] == 1 ? ((bk * (bn / 8) + 63) / 64) * 1024 : bn * bk * es;
                 lds = (int64_t)(p.cache_read - 3) * (bm * bk * es + btile);
             }
+            if (p.compute_at) {
+                // conv2d with the activations' cache-read under the workgroup tile loop: the input rows of
+                // the tile (zero halo included) are resident, only the weights are staged per k step
+                if (d.kind != MS_OP_CONV2D_NHWC) return reject("compute_location applies to conv2d only");
+                if (p.compute_at == 1 && p.cache_read > 3) return reject("with the input patch resident only the weights are staged per k step: cache_read 1, 2 or 3");
+                if (p.compute_at == 2 && p.cache_read > 2) return reject("with resident weights cache_read is 1 (patch loaded between tiles) or 2 (next patch prefetched)");
+                if (p.compute_at == 2 && p.reorder != 0) return reject("persistent workgroups with resident weights walk the tile list in order: reorder must be 0");
+                int64_t cin = d.dims[3], ohw = op->OH * op->OW;
+                if (cin % p.tile_unit[2]) return reject("resident input patch: Cin = %" PRId64 " is not a multiple of the intrinsic's k = %d", cin, p.tile_unit[2]);
+                if (ohw % bm) return reject("resident input patch: the %" PRId64 "-pixel tile straddles images of %" PRId64 " output pixels", bm, ohw);
+                int64_t rows = bm % op->OW == 0 ? bm / op->OW : (op->OW + bm - 2) / op->OW + 1;
+                int64_t pr = (rows - 1) * d.stride + d.dims[5], pw = (op->OW - 1) * d.stride + d.dims[6];
+                int64_t ps = cin * es + (p.lds_pad ? 16 : 0);
+                int64_t patch = pr * pw * ps;
+                lds = (int64_t)(p.cache_read >= 2 ? 2 : 1) * (bk / kp) * rowsB + patch;
+                if (p.compute_at == 2) lds = (int64_t)p.tk[0] * (bk / kp) * rowsB + patch; // all k steps of the weights
+                if ((cin * es) % 16 && p.lds_pad) return reject("resident input patch: padded pixels need Cin * element size to be a multiple of 16 bytes");
+                if (d.dims[0] * d.dims[1] * d.dims[2] * cin > 0x7fffffff / es) return reject("resident input patch: one instance of X exceeds 32-bit byte offsets");
+            }
             if (p.reorder == 3 && p.cache_read < 5) return reject("persistent workgroups (reorder 3) are built on direct-to-LDS staging (cache_read 5, 6, 7)");
             if (p.cache_write) {
                 // the output tile reuses the operand buffers: rows of bn outputs padded by 16 bytes
                 int64_t ctile = bm * (bn * op->out_size + 16);
-                if (p.reorder == 3) lds += ctile; // persistent workgroups keep the operand ring alive during the epilogue
+                if (p.reorder == 3 || p.compute_at == 2) lds += ctile; // persistent workgroups keep their operands alive during the epilogue
                 else if (ctile > lds) lds = ctile;
                 if ((op->N * op->out_size) % 16) return reject("cache_write needs output rows that are multiples of 16 bytes");
             }
@@ -235,6 +256,13 @@ extern "C" int32_t ms_trace_validate(const ms_op *op, const ms_space *space, con
             // registers that carry a tile from global memory to LDS; with two buffers they are live across the k step
             int64_t stage = (bm * bk * es / 4 + p.threads - 1) / p.threads + (bn * bk * es / 4 + p.threads - 1) / p.threads;
             if (p.cache_read >= 5) stage = 0;
+            if (p.compute_at) stage = (bn * bk * es / 4 + p.threads - 1) / p.threads;
+            if (p.compute_at == 2 && p.cache_read == 2) {
+                // the next tile's patch waits in registers during the k loop
+                int64_t rows = bm % op->OW == 0 ? bm / op->OW : (op->OW + bm - 2) / op->OW + 1;
+                int64_t pr = (rows - 1) * d.stride + d.dims[5], pw = (op->OW - 1) * d.stride + d.dims[6];
+                stage = std::max(stage, (pr * pw * d.dims[3] * es / 4 + p.threads - 1) / p.threads);
+            }
             int64_t live = p.cache_read == 3 ? frag + 2 * stage : (p.cache_read >= 2 ? frag + stage : std::max(frag, stage));
             if (p.cache_read == 4) {
                 if (p.waves % 2) return reject("ping-pong wave groups need an even number of wavefronts, not %d", p.waves);
@@ -378,6 +406,7 @@ int32_t make_kernel_spec(const ms_op *op, const ms_variant_params *p, KernelSpec
     D.push_back(def("UNROLL_K2", p->unroll_k2));
     D.push_back(def("LDS_PAD", p->lds_pad));
     D.push_back(def("REORDER", p->reorder));
+    D.push_back(def("COMPUTE_AT", p->compute_at));
     if (p->family == MS_FAM_GEMM_ALU || p->family == MS_FAM_GEMM_MFMA) {
         D.push_back(def("DIM_B", op->nb));
         D.push_back(def("DIM_M", op->M));

@@ -41,16 +41,21 @@ def append_record(name, rec):
         f.write(json.dumps(rec, sort_keys=True) + "\n")
 
 
-def record_traces(name, op, space, limit=4):
+def records_with_traces(name, op, space, limit=4):
+    """[(record dict, parsed trace)] of the stored records that still parse and validate, best first."""
     out = []
     for rec in load_records(name)[:limit]:
         try:
             t = B.trace_from_text(space, rec["trace"])
             B.trace_validate(op, space, t)
-            out.append(t)
+            out.append((rec, t))
         except B.MsError:
             continue
     return out
+
+
+def record_traces(name, op, space, limit=4):
+    return [t for _, t in records_with_traces(name, op, space, limit)]
 
 
 def precompile_all(threads=4):

@@ -65,3 +65,96 @@ def test_conv_instances_with_distinct_inputs():
             continue
         for r in range(3):
             compare.assert_float_close(got[r], refs[r], compare.RTOL_HALF, "instance %d trace %d" % (r, n))
+
+
+def _traces_with_resident_patch(op, space, seed, count, compute_at=1, max_index=1500):
+    """Sampled valid traces with the given compute-location decision: 1 = the input patch of a tile is resident
+    in LDS, 2 = also the weights, under persistent workgroups."""
+    out = []
+    for idx in range(max_index):
+        if len(out) == count:
+            break
+        t = B.trace_sample_valid(op, space, seed, idx)
+        if B.trace_validate(op, space, t).compute_at == compute_at:
+            out.append(t)
+    return out
+
+
+@pytest.mark.parametrize("compute_at", [1, 2])
+def test_c3_conv_resident_patch(compute_at):
+    """C3 with the cache-read of X under the workgroup tile loop (sample-compute-location = tile), and with the
+    weights resident as well: row-aligned tiles and tiles that start in the middle of an output row."""
+    X, W, bias = I.c3(seed=3)
+    ref = O.conv2d_nhwc(X, W, bias=bias, relu=True, stride=1, pad=1)
+    op = B.conv2d_op(1, 56, 56, 64, 64, 3, 3, stride=1, pad=1)
+    space = op.space()
+    traces = _traces_with_resident_patch(op, space, 21, 6, compute_at)
+    assert len(traces) == 6
+    aligned = [B.trace_validate(op, space, t).block_m % 56 == 0 for t in traces]
+    print("row-aligned tiles:", aligned, flush=True)
+    for n, t in enumerate(traces):
+        print("trace", n, t.decisions(), flush=True)
+        got = run_variant(op, space, t, [X, W, bias], "f16", (1, 56, 56, 64))
+        if got is None:
+            continue
+        compare.assert_float_close(got, ref, compare.RTOL_HALF, "C3 compute_at %d, trace %d" % (compute_at, n))
+
+
+@pytest.mark.parametrize("compute_at", [1, 2])
+@pytest.mark.parametrize("stride,pad,k,H,W_", [(1, 1, 3, 16, 16), (2, 1, 3, 16, 32), (1, 0, 1, 8, 16), (2, 3, 7, 32, 16), (1, 2, 5, 12, 16)])
+def test_conv_resident_patch_geometries_exact(stride, pad, k, H, W_, compute_at):
+    """Resident input patch with other strides, paddings and filter sizes, batch 2, 2 instances with distinct
+    data; integer-valued inputs make fp32 accumulation exact: the fp32 output must equal the oracle."""
+    N, Cin, Cout = 2, 32, 32
+    g = I.rng(17)
+    ins, refs = [], []
+    for r in range(2):
+        X = I.small_ints(g, (N, H, W_, Cin), -2, 2, "f16")
+        Wt = I.small_ints(g, (k, k, Cin, Cout), -2, 2, "f16")
+        bias = g.integers(-3, 4, size=Cout).astype(np.float32)
+        ins.append([X, Wt, bias])
+        refs.append(O.conv2d_nhwc(X, Wt, bias=bias, relu=True, stride=stride, pad=pad))
+    OH, OW = refs[0].shape[1], refs[0].shape[2]
+    assert (OH * OW) % 16 == 0
+    op = B.conv2d_op(N, H, W_, Cin, Cout, k, k, stride=stride, pad=pad, out_dtype="f32")
+    space = op.space()
+    traces = _traces_with_resident_patch(op, space, 5, 4, compute_at)
+    assert traces, "no valid trace with compute_at %d" % compute_at
+    for n, t in enumerate(traces):
+        print("trace", n, t.decisions(), flush=True)
+        got = run_variant_distinct(op, space, t, ins, "f32", (N, OH, OW, Cout))
+        if got is None:
+            continue
+        for r in range(2):
+            assert np.array_equal(got[r], refs[r]), "instance %d trace %d" % (r, n)
+
+
+def test_conv_persistent_runs_cross_instances():
+    """Resident weights under persistent workgroups, with more tiles than workgroups: every workgroup walks a
+    run of consecutive tiles that crosses image and instance boundaries (weights reloaded, patch prefetched).
+    600 instances of 5 distinct data sets in rotation; integer-valued inputs, fp32 output: exact equality."""
+    N, H, W_, Cin, Cout, R = 2, 16, 16, 32, 32, 600
+    g = I.rng(23)
+    sets, refs = [], []
+    for r in range(5):
+        X = I.small_ints(g, (N, H, W_, Cin), -2, 2, "f16")
+        Wt = I.small_ints(g, (3, 3, Cin, Cout), -2, 2, "f16")
+        bias = g.integers(-3, 4, size=Cout).astype(np.float32)
+        sets.append([X, Wt, bias])
+        refs.append(O.conv2d_nhwc(X, Wt, bias=bias, relu=True, stride=1, pad=1))
+    ins = [sets[r % 5] for r in range(R)]
+    op = B.conv2d_op(N, H, W_, Cin, Cout, 3, 3, stride=1, pad=1, out_dtype="f32")
+    space = op.space()
+    for cache_read in (1, 2):
+        traces = [t for t in _traces_with_resident_patch(op, space, 9, 40, 2) if B.trace_validate(op, space, t).cache_read == cache_read][:2]
+        assert traces, "no valid trace with compute_at 2 and cache_read %d" % cache_read
+        for n, t in enumerate(traces):
+            p = B.trace_validate(op, space, t)
+            tiles = p.grid[0] * R
+            print("cache_read", cache_read, "trace", n, t.decisions(), "tiles", tiles, flush=True)
+            assert tiles > 4 * 256, "the launch must have several tiles per workgroup"
+            got = run_variant_distinct(op, space, t, ins, "f32", (N, H, W_, Cout))
+            if got is None:
+                continue
+            for r in range(R):
+                assert np.array_equal(got[r], refs[r % 5]), "instance %d trace %d" % (r, n)
