@@ -170,7 +170,13 @@ typedef enum ms_slot_id {
                                  2 = as 1, and the cache-read of the weights W moves above the tile loop: persistent
                                  workgroups own runs of consecutive tiles, the weights of the current instance stay in
                                  LDS, the k loop has no barrier and no global load; cache_read 1 = the next patch is
-                                 loaded between tiles, 2 = it is prefetched into registers during the k loop */
+                                 loaded between tiles, 2 = it is prefetched into registers during the k loop;
+                                 3 = as 2 with cache_read 2 and cache_write 1, plus four helper wavefronts that do all
+                                 global loads and stores of the tile loop while the others multiply;
+                                 4 = as 2 (cache_read 1 or 2), but the weights end in registers: each wavefront keeps
+                                 the fragments of its own output columns for all k steps, the k loop is fully
+                                 unrolled whatever the unroll budget (the k split only sets the size of the staging
+                                 steps) and reads only activations from LDS */
 } ms_slot_id;
 
 /* Tensorize candidates: (m, n, k) of one matrix-core instruction.  The code

@@ -40,13 +40,28 @@
 // instance stay in LDS in fragment layout (reloaded only when the run crosses into the next instance), the
 // k loop is free of barriers and global loads, and with CACHE_READ 2 the next tile's input patch is
 // fetched into registers while the current tile is multiplied.
+//
+// conv2d with COMPUTE_AT 3: as 2, with HELPER_WAVES extra wavefronts that do all global memory traffic of
+// the tile loop.  While the I2*J2 matrix-core wavefronts multiply tile t, the helpers write tile t-1 from
+// its LDS staging area to global memory and fetch the patch of tile t+1; between two k loops only LDS is
+// touched (accumulators -> staging area, patch registers -> patch).
+//
+// conv2d with COMPUTE_AT 4: as 2, but the cache-read of W ends in registers: every wavefront keeps the
+// weight fragments of its own output columns for all k steps (loaded through a one-step LDS staging
+// buffer when the run enters a new instance), the k loop is fully unrolled and reads only the A
+// fragments from LDS - a third to two thirds less LDS traffic, which is what bounds modes 2 and 3.
 #include "common.h"
 
 #ifndef COMPUTE_AT
 #define COMPUTE_AT 0
 #endif
 #define CONV_PATCH (IS_CONV && COMPUTE_AT >= 1)
-#define CONV_RESIDENT (IS_CONV && COMPUTE_AT == 2)
+#define CONV_RESIDENT (IS_CONV && COMPUTE_AT >= 2)
+#define CONV_HELPERS (IS_CONV && COMPUTE_AT == 3)
+#define CONV_BREG (IS_CONV && COMPUTE_AT == 4)
+#ifndef HELPER_WAVES
+#define HELPER_WAVES 0
+#endif
 
 #define NWAVES (I2 * J2)
 #define LANE_GROUPS (64 / MI_M)
@@ -319,10 +334,11 @@ struct conv_ctx {
 // workgroup can fetch the next tile's patch while it multiplies the current one.  A patch row is
 // P_CR vectors of VEC channels; threads are laid over rows so that a thread's column, its channel
 // vector and the in-image test of the column do not depend on the tile.
+constexpr int P_NT = CONV_HELPERS ? HELPER_WAVES * 64 : NTHREADS; // threads that move the patch
 constexpr int P_CPP = CV_CIN / VEC;                              // vectors per pixel
 constexpr int P_CR = P_W * P_CPP;                                // vectors per patch row
-constexpr int P_PPR = (P_CR + NTHREADS - 1) / NTHREADS;          // passes of the workgroup over one row
-constexpr int P_RPP = NTHREADS >= P_CR ? NTHREADS / P_CR : 1;    // rows per pass
+constexpr int P_PPR = (P_CR + P_NT - 1) / P_NT;                  // passes of the movers over one row
+constexpr int P_RPP = P_NT >= P_CR ? P_NT / P_CR : 1;            // rows per pass
 constexpr int P_PASSES = (P_R + P_RPP - 1) / P_RPP;
 constexpr int P_ITERS = P_PASSES * P_PPR;
 
@@ -339,10 +355,10 @@ struct patch_map {   // per thread, the same for every tile
 
 __device__ __forceinline__ void patch_map_init(patch_map &pm, int tid)
 {
-    pm.row_t = NTHREADS >= P_CR ? tid / P_CR : 0;
+    pm.row_t = P_NT >= P_CR ? tid / P_CR : 0;
 #pragma unroll
     for (int s = 0; s < P_PPR; ++s) {
-        const int q = NTHREADS >= P_CR ? tid % P_CR : s * NTHREADS + tid;
+        const int q = P_NT >= P_CR ? tid % P_CR : s * P_NT + tid;
         const int pc = q / P_CPP, c = q % P_CPP;
         const int iw = pc - CV_PAD;
         pm.goff[s] = iw * CV_CIN + c * VEC;
@@ -384,8 +400,8 @@ __device__ __forceinline__ void patch_commit(const patch_regs &pr, const patch_m
 #pragma unroll
         for (int s = 0; s < P_PPR; ++s) {
             const int row = p * P_RPP + pm.row_t;
-            const int q = NTHREADS >= P_CR ? tid % P_CR : s * NTHREADS + tid;
-            const bool live = (NTHREADS >= P_CR ? pm.row_t < P_RPP : q < P_CR) && (P_R % P_RPP == 0 || row < P_R);
+            const int q = P_NT >= P_CR ? tid % P_CR : s * P_NT + tid;
+            const bool live = (P_NT >= P_CR ? pm.row_t < P_RPP : q < P_CR) && (P_R % P_RPP == 0 || row < P_R);
             if (live) *reinterpret_cast<vec_t<in_t, VEC> *>(patch + row * P_RS + pm.loff[s]) = pr.r[p * P_PPR + s];
         }
 }
@@ -567,6 +583,56 @@ __device__ __forceinline__ void multiply_tile_unrolled(accv_t (&acc)[TM][TN], co
     }
 }
 
+#if CONV_BREG
+constexpr int NSTEP = K0 * KSTEPS; // all MFMA k steps of the reduction
+
+// weights of output columns j0*BN .. of one instance -> registers of the wavefronts that own the columns
+__device__ __forceinline__ void weights_to_regs(frag_t (&bw)[NSTEP][TN], const in_t *__restrict__ Wt, int j0, char *__restrict__ wstage, int tid,
+                                                int lgrp, int wj, int lrow)
+{
+    tile_stage st;
+#pragma unroll
+    for (int k0 = 0; k0 < K0; ++k0) {
+        stage_load(st, nullptr, Wt, 0, j0, k0, tid);
+        if (k0 > 0) __syncthreads(); // the previous step's fragments have been read
+        stage_store(st, wstage, tid);
+        __syncthreads();
+        const char *lb = wstage + lgrp * PLANE_B;
+#pragma unroll
+        for (int q = 0; q < KSTEPS; ++q)
+#pragma unroll
+            for (int c1 = 0; c1 < J1; ++c1)
+#pragma unroll
+                for (int c3 = 0; c3 < J3; ++c3) {
+                    const int tcol = (c1 * J2 + wj) * J3 + c3;
+                    bw[k0 * KSTEPS + q][c1 * J3 + c3] =
+                        *reinterpret_cast<const frag_t *>(lb + q * LANE_GROUPS * PLANE_B + lds_slot(tcol * MI_N + lrow) * FRAG_BYTES);
+                }
+    }
+}
+
+// the whole reduction of one tile: A fragments from the patch (read one step ahead), B from registers
+__device__ __forceinline__ void multiply_all_k(accv_t (&acc)[TM][TN], const frag_t (&bw)[NSTEP][TN], const conv_ctx &cx)
+{
+    frag_t fa[2][TM];
+#pragma unroll
+    for (int tm = 0; tm < TM; ++tm) fa[0][tm] = *reinterpret_cast<const frag_t *>(cx.patch + (cx.pix[tm] + conv_koff(0, 0)));
+#pragma unroll
+    for (int s = 0; s < NSTEP; ++s) {
+        if (s + 1 < NSTEP) {
+#pragma unroll
+            for (int tm = 0; tm < TM; ++tm)
+                fa[(s + 1) & 1][tm] = *reinterpret_cast<const frag_t *>(cx.patch + (cx.pix[tm] + conv_koff(0, s + 1)));
+        }
+#pragma unroll
+        for (int tm = 0; tm < TM; ++tm)
+#pragma unroll
+            for (int tn = 0; tn < TN; ++tn) acc[tm][tn] = mfma(bw[s][tn], fa[s & 1][tm], acc[tm][tn]);
+        __builtin_amdgcn_sched_barrier(0);
+    }
+}
+#endif
+
 constexpr int NS = K1 * K2;
 #define PIPELINED (CACHE_READ < 3 && UNROLL_K1 == K1 && UNROLL_K2 == K2 && K1 * K2 > 1)
 
@@ -711,6 +777,22 @@ __device__ __forceinline__ void dl_read_frags(frag_t (&fa)[K3][TM], frag_t (&fb)
 
 constexpr int CROW = BN * (int)sizeof(out_t) + 16; // bytes of one staged output row (cache-write)
 
+// second half of the CACHE_WRITE epilogue: NT threads (t = 0 .. NT-1) write the staged tile as whole rows
+template <int NT>
+__device__ __forceinline__ void flush_cstage(out_t *__restrict__ C, int i0, int j0, const char *__restrict__ cstage, int t)
+{
+    constexpr int CHUNKS_PER_ROW = BN * (int)sizeof(out_t) / 16;
+    constexpr int TOTAL = BM * CHUNKS_PER_ROW;
+    typedef vec_t<unsigned, 4> chunk_t;
+#pragma unroll 4
+    for (int idx = t; idx < TOTAL; idx += NT) {
+        const int row = idx / CHUNKS_PER_ROW, ch = idx % CHUNKS_PER_ROW;
+        const chunk_t v = *reinterpret_cast<const chunk_t *>(cstage + row * CROW + ch * 16);
+        char *dst = (char *)(C + ((long)i0 * BM + row) * DIM_N + (long)j0 * BN) + ch * 16;
+        *reinterpret_cast<chunk_t *>(dst) = v;
+    }
+}
+
 // Epilogue of one workgroup tile.  `cstage`: LDS region of BM * CROW bytes for CACHE_WRITE 1 (must not be
 // read or written by anything else between the caller's preceding barrier and the end of this call).
 __device__ __forceinline__ void write_tile(accv_t (&acc)[TM][TN], out_t *__restrict__ C, const void *__restrict__ bias_, int inst, int i0, int j0,
@@ -758,20 +840,9 @@ __device__ __forceinline__ void write_tile(accv_t (&acc)[TM][TN], out_t *__restr
 #endif
                     }
                 }
-#if CACHE_WRITE
+#if CACHE_WRITE && !CONV_HELPERS
     __syncthreads();
-    {
-        constexpr int CHUNKS_PER_ROW = BN * (int)sizeof(out_t) / 16;
-        constexpr int TOTAL = BM * CHUNKS_PER_ROW;
-        typedef vec_t<unsigned, 4> chunk_t;
-#pragma unroll 4
-        for (int idx = tid; idx < TOTAL; idx += NTHREADS) {
-            const int row = idx / CHUNKS_PER_ROW, ch = idx % CHUNKS_PER_ROW;
-            const chunk_t v = *reinterpret_cast<const chunk_t *>(cstage + row * CROW + ch * 16);
-            char *dst = (char *)(C + ((long)i0 * BM + row) * DIM_N + (long)j0 * BN) + ch * 16;
-            *reinterpret_cast<chunk_t *>(dst) = v;
-        }
-    }
+    flush_cstage<NTHREADS>(C, i0, j0, cstage, tid);
 #endif
     (void)bias_;
     (void)inst;
@@ -913,7 +984,8 @@ ms_kernel(const void *__restrict__ a_, const void *__restrict__ b_, const void *
     const int wi = wave / J2, wj = wave % J2;
     const int lrow = lane % MI_M, lgrp = lane / MI_M;
 
-    constexpr int W_BYTES = K0 * STAGE_BYTES;                      // all k steps of the weights, fragment layout
+    // all k steps of the weights in fragment layout; with the weights in registers, one step as a staging buffer
+    constexpr int W_BYTES = (CONV_BREG ? 1 : K0) * STAGE_BYTES;
     constexpr int LDS_BYTES = W_BYTES + PATCH_BYTES + (CACHE_WRITE ? BM * CROW : 0);
     __shared__ __attribute__((aligned(16))) char lds[LDS_BYTES];
     char *const patch = lds + W_BYTES;
@@ -925,20 +997,25 @@ ms_kernel(const void *__restrict__ a_, const void *__restrict__ b_, const void *
     const long last = first + run < total ? first + run : total;
     if (first >= last) return;
 
+#if CONV_HELPERS
+    static_assert(CACHE_WRITE == 1, "helper wavefronts write the tile from its LDS staging area");
+    // wave-uniform role: matrix-core wavefronts 0 .. NWAVES-1, then the helpers
+    const bool helper = __builtin_amdgcn_readfirstlane(wave) >= NWAVES;
+    const int htid = tid - NWAVES * 64;
     patch_map pm;
     patch_regs pr;
-    patch_map_init(pm, tid);
-    {
+    if (helper) {
+        patch_map_init(pm, htid);
         const int inst = (int)(first / (I0 * J0)), i0 = (int)(first % I0);
         patch_fetch(pr, pm, (const in_t *)a_ + (long)inst * A_INST, i0);
-        patch_commit(pr, pm, patch, tid);
+        patch_commit(pr, pm, patch, htid);
     }
-    long have_w = -1; // (inst, j0) of the weights in LDS
+    long have_w = -1;
 #pragma unroll 1
     for (long f = first; f < last; ++f) {
         const int i0 = (int)(f % I0), j0 = (int)((f / I0) % J0), inst = (int)(f / (I0 * J0));
         if (f / I0 != have_w) {
-            // every wavefront has passed the barrier that ended the previous tile's k loop: the old weights are dead
+            // all wavefronts load the weights; the previous tile's k loop ended with barrier B
             have_w = f / I0;
             const in_t *Wt = (const in_t *)b_ + (long)inst * B_INST;
             tile_stage st;
@@ -947,6 +1024,80 @@ ms_kernel(const void *__restrict__ a_, const void *__restrict__ b_, const void *
                 stage_load(st, nullptr, Wt, 0, j0, k0, tid);
                 stage_store(st, lds + k0 * STAGE_BYTES, tid);
             }
+        }
+        __syncthreads(); // barrier A: patch f, weights and the staged result of tile f-1 are in place
+        if (helper) {
+            // loads before stores: the wait for the patch then does not include the younger stores
+            if (f + 1 < last) {
+                const long g = f + 1;
+                patch_fetch(pr, pm, (const in_t *)a_ + (g / (I0 * J0)) * A_INST, (int)(g % I0));
+            }
+            if (f > first) {
+                const long g = f - 1;
+                out_t *Cp = (out_t *)c_ + (g / (I0 * J0)) * ((long)DIM_M * DIM_N);
+                flush_cstage<P_NT>(Cp, (int)(g % I0), (int)((g / I0) % J0), cstage, htid);
+            }
+            __syncthreads(); // barrier B: the matrix-core wavefronts are done with patch f, the helpers with the staging area
+            if (f + 1 < last) patch_commit(pr, pm, patch, htid);
+        } else {
+            conv_ctx cx;
+            conv_ctx_init(cx, patch, i0, wi, lrow, lgrp);
+            accv_t acc[TM][TN];
+#pragma unroll
+            for (int tm = 0; tm < TM; ++tm)
+#pragma unroll
+                for (int tn = 0; tn < TN; ++tn)
+#pragma unroll
+                    for (int e = 0; e < ACC_N; ++e) acc[tm][tn][e] = 0;
+#pragma unroll 1
+            for (int k0 = 0; k0 < K0; ++k0) {
+#if UNROLL_K1 == K1 && UNROLL_K2 == K2 && K1 * K2 > 1
+                multiply_tile_unrolled(acc, lds + k0 * STAGE_BYTES, lgrp, wi, wj, lrow, cx, k0);
+#else
+                multiply_tile(acc, lds + k0 * STAGE_BYTES, lgrp, wi, wj, lrow, cx, k0);
+#endif
+            }
+            __syncthreads(); // barrier B
+            write_tile(acc, nullptr, bias_, inst, i0, j0, cstage, tid, wi, wj, lrow, lgrp); // accumulators -> staging area only
+        }
+    }
+    __syncthreads();
+    if (helper) {
+        const long g = last - 1;
+        out_t *Cp = (out_t *)c_ + (g / (I0 * J0)) * ((long)DIM_M * DIM_N);
+        flush_cstage<P_NT>(Cp, (int)(g % I0), (int)((g / I0) % J0), cstage, htid);
+    }
+}
+#else
+    patch_map pm;
+    patch_regs pr;
+    patch_map_init(pm, tid);
+    {
+        const int inst = (int)(first / (I0 * J0)), i0 = (int)(first % I0);
+        patch_fetch(pr, pm, (const in_t *)a_ + (long)inst * A_INST, i0);
+        patch_commit(pr, pm, patch, tid);
+    }
+    long have_w = -1; // (inst, j0) of the weights in LDS (or registers)
+#if CONV_BREG
+    frag_t bw[NSTEP][TN];
+#endif
+#pragma unroll 1
+    for (long f = first; f < last; ++f) {
+        const int i0 = (int)(f % I0), j0 = (int)((f / I0) % J0), inst = (int)(f / (I0 * J0));
+        if (f / I0 != have_w) {
+            // every wavefront has passed the barrier that ended the previous tile's k loop: the old weights are dead
+            have_w = f / I0;
+            const in_t *Wt = (const in_t *)b_ + (long)inst * B_INST;
+#if CONV_BREG
+            weights_to_regs(bw, Wt, j0, lds, tid, lgrp, wj, lrow);
+#else
+            tile_stage st;
+#pragma unroll 1
+            for (int k0 = 0; k0 < K0; ++k0) {
+                stage_load(st, nullptr, Wt, 0, j0, k0, tid);
+                stage_store(st, lds + k0 * STAGE_BYTES, tid);
+            }
+#endif
         }
         __syncthreads(); // patch and weights are in place
 #if CACHE_READ >= 2
@@ -964,6 +1115,9 @@ ms_kernel(const void *__restrict__ a_, const void *__restrict__ b_, const void *
             for (int tn = 0; tn < TN; ++tn)
 #pragma unroll
                 for (int e = 0; e < ACC_N; ++e) acc[tm][tn][e] = 0;
+#if CONV_BREG
+        multiply_all_k(acc, bw, cx);
+#else
 #pragma unroll 1
         for (int k0 = 0; k0 < K0; ++k0) {
 #if UNROLL_K1 == K1 && UNROLL_K2 == K2 && K1 * K2 > 1
@@ -972,6 +1126,7 @@ ms_kernel(const void *__restrict__ a_, const void *__restrict__ b_, const void *
             multiply_tile(acc, lds + k0 * STAGE_BYTES, lgrp, wi, wj, lrow, cx, k0);
 #endif
         }
+#endif
         __syncthreads(); // the patch has been read by everyone
         if (f + 1 < last) {
 #if CACHE_READ < 2
@@ -984,6 +1139,7 @@ ms_kernel(const void *__restrict__ a_, const void *__restrict__ b_, const void *
         write_tile(acc, C, bias_, inst, i0, j0, cstage, tid, wi, wj, lrow, lgrp);
     }
 }
+#endif // CONV_HELPERS
 #else // REORDER != 3
 extern "C" __global__ void __launch_bounds__(NTHREADS)
 ms_kernel(const void *__restrict__ a_, const void *__restrict__ b_, const void *__restrict__ bias_, void *__restrict__ c_, int instances)

@@ -477,7 +477,7 @@ extern "C" int32_t ms_space_describe(const ms_op *op, uint32_t flags, ms_space *
             else add_cat(out, MS_SLOT_REORDER, "reorder", {0, 1, 2});
         }
         if (flags & MS_SPACE_CACHE_WRITE) add_cat(out, MS_SLOT_CACHE_WRITE, "cache_write", {0, 1});
-        if (flags & MS_SPACE_COMPUTE_AT) add_cat(out, MS_SLOT_COMPUTE_AT, "compute_at", {0, 1, 2});
+        if (flags & MS_SPACE_COMPUTE_AT) add_cat(out, MS_SLOT_COMPUTE_AT, "compute_at", {0, 1, 2, 3, 4});
         return MS_OK;
     }
     flags &= ~(MS_SPACE_CACHE_WRITE | MS_SPACE_COMPUTE_AT);
@@ -771,11 +771,12 @@ extern "C" int32_t ms_trace_to_text(const ms_op *op, const ms_space *space, cons
         if (p.cache_read) {
             if (p.cache_read >= 5)
                 appendf(s, "cache-read(buffers=[A, B], scope=lds, at=k0, stages=%d, prefetch_distance=%d, direct_to_lds=1)\n", p.cache_read - 3, p.cache_read - 4);
-            else if (p.compute_at == 2)
-                appendf(s, "bind(fuse(i0, j0), persistent workgroup loop over runs of consecutive tiles)\n"
-                           "cache-read(buffer=W, scope=lds, compute-at=root of the tile loop, all k steps resident)\n"
+            else if (p.compute_at >= 2)
+                appendf(s, "%sbind(fuse(i0, j0), persistent workgroup loop over runs of consecutive tiles)\n"
+                           "cache-read(buffer=W, scope=%s, compute-at=root of the tile loop, all k steps resident)\n"
                            "cache-read(buffer=X, scope=lds, compute-at=fuse(i0, j0), input rows of the tile with zero halo, prefetch_distance=%d)\n",
-                        p.cache_read >= 2 ? 1 : 0);
+                        p.compute_at == 3 ? "annotate(block=C, key=helper_wavefronts, value=4)  # global loads and stores of the tile loop\n" : "",
+                        p.compute_at == 4 ? "registers (through an LDS staging buffer)" : "lds", p.cache_read >= 2 ? 1 : 0);
             else if (p.compute_at)
                 appendf(s, "cache-read(buffer=X, scope=lds, compute-at=fuse(i0, j0), input rows of the tile with zero halo)\n"
                            "cache-read(buffer=W, scope=lds, compute-at=k0, stages=%d, prefetch_distance=%d)\n",

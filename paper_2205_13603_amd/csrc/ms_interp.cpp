@@ -186,6 +186,8 @@ extern "C" int32_t ms_trace_validate(const ms_op *op, const ms_space *space, con
         int64_t units = (int64_t)p.ti[2] * p.tj[2];
         int64_t acc;
         if (p.mfma) {
+            // conv2d with helper wavefronts (compute_at 3): four more, one per SIMD, that only move data
+            if (p.compute_at == 3) units += 4;
             if (units > L.max_waves) return reject("%" PRId64 " wavefronts per workgroup, the limit is %d", units, L.max_waves);
             p.waves = (int32_t)units;
             p.threads = p.waves * L.wave_size;
@@ -230,7 +232,9 @@ extern "C" int32_t ms_trace_validate(const ms_op *op, const ms_space *space, con
                 if (d.kind != MS_OP_CONV2D_NHWC) return reject("compute_location applies to conv2d only");
                 if (p.compute_at == 1 && p.cache_read > 3) return reject("with the input patch resident only the weights are staged per k step: cache_read 1, 2 or 3");
                 if (p.compute_at == 2 && p.cache_read > 2) return reject("with resident weights cache_read is 1 (patch loaded between tiles) or 2 (next patch prefetched)");
-                if (p.compute_at == 2 && p.reorder != 0) return reject("persistent workgroups with resident weights walk the tile list in order: reorder must be 0");
+                if (p.compute_at == 3 && (p.cache_read != 2 || !p.cache_write))
+                    return reject("helper wavefronts prefetch the patch and write the staged tile: cache_read 2 and cache_write 1");
+                if (p.compute_at >= 2 && p.reorder != 0) return reject("persistent workgroups with resident weights walk the tile list in order: reorder must be 0");
                 int64_t cin = d.dims[3], ohw = op->OH * op->OW;
                 if (cin % p.tile_unit[2]) return reject("resident input patch: Cin = %" PRId64 " is not a multiple of the intrinsic's k = %d", cin, p.tile_unit[2]);
                 if (ohw % bm) return reject("resident input patch: the %" PRId64 "-pixel tile straddles images of %" PRId64 " output pixels", bm, ohw);
@@ -239,7 +243,12 @@ extern "C" int32_t ms_trace_validate(const ms_op *op, const ms_space *space, con
                 int64_t ps = cin * es + (p.lds_pad ? 16 : 0);
                 int64_t patch = pr * pw * ps;
                 lds = (int64_t)(p.cache_read >= 2 ? 2 : 1) * (bk / kp) * rowsB + patch;
-                if (p.compute_at == 2) lds = (int64_t)p.tk[0] * (bk / kp) * rowsB + patch; // all k steps of the weights
+                if (p.compute_at >= 2) lds = (int64_t)p.tk[0] * (bk / kp) * rowsB + patch; // all k steps of the weights
+                if (p.compute_at == 4) {
+                    // weights in registers: LDS holds one k step of them as a staging buffer
+                    lds = (bk / kp) * rowsB + patch;
+                    if (p.cache_read > 2) return reject("with the weights in registers cache_read is 1 (patch loaded between tiles) or 2 (next patch prefetched)");
+                }
                 if ((cin * es) % 16 && p.lds_pad) return reject("resident input patch: padded pixels need Cin * element size to be a multiple of 16 bytes");
                 if (d.dims[0] * d.dims[1] * d.dims[2] * cin > 0x7fffffff / es) return reject("resident input patch: one instance of X exceeds 32-bit byte offsets");
             }
@@ -247,7 +256,7 @@ extern "C" int32_t ms_trace_validate(const ms_op *op, const ms_space *space, con
             if (p.cache_write) {
                 // the output tile reuses the operand buffers: rows of bn outputs padded by 16 bytes
                 int64_t ctile = bm * (bn * op->out_size + 16);
-                if (p.reorder == 3 || p.compute_at == 2) lds += ctile; // persistent workgroups keep their operands alive during the epilogue
+                if (p.reorder == 3 || p.compute_at >= 2) lds += ctile; // persistent workgroups keep their operands alive during the epilogue
                 else if (ctile > lds) lds = ctile;
                 if ((op->N * op->out_size) % 16) return reject("cache_write needs output rows that are multiples of 16 bytes");
             }
@@ -257,6 +266,12 @@ extern "C" int32_t ms_trace_validate(const ms_op *op, const ms_space *space, con
             int64_t stage = (bm * bk * es / 4 + p.threads - 1) / p.threads + (bn * bk * es / 4 + p.threads - 1) / p.threads;
             if (p.cache_read >= 5) stage = 0;
             if (p.compute_at) stage = (bn * bk * es / 4 + p.threads - 1) / p.threads;
+            if (p.compute_at == 3) {
+                // only the helpers carry the patch, over 256 lanes
+                int64_t rows = bm % op->OW == 0 ? bm / op->OW : (op->OW + bm - 2) / op->OW + 1;
+                int64_t pr = (rows - 1) * d.stride + d.dims[5], pw = (op->OW - 1) * d.stride + d.dims[6];
+                stage = std::max(stage, (pr * pw * d.dims[3] * es / 4 + 255) / 256);
+            }
             if (p.compute_at == 2 && p.cache_read == 2) {
                 // the next tile's patch waits in registers during the k loop
                 int64_t rows = bm % op->OW == 0 ? bm / op->OW : (op->OW + bm - 2) / op->OW + 1;
@@ -264,6 +279,25 @@ extern "C" int32_t ms_trace_validate(const ms_op *op, const ms_space *space, con
                 stage = std::max(stage, (pr * pw * d.dims[3] * es / 4 + p.threads - 1) / p.threads);
             }
             int64_t live = p.cache_read == 3 ? frag + 2 * stage : (p.cache_read >= 2 ? frag + stage : std::max(frag, stage));
+            if (p.compute_at == 4) {
+                // weight fragments of the wavefront's columns for every k step, A fragments of two steps
+                int64_t fr = kp * es / 4 > 0 ? kp * es / 4 : 1;
+                int64_t breg = (int64_t)p.tj[1] * p.tj[3] * (op->K / p.tile_unit[2]) * fr;
+                int64_t areg = 2 * (int64_t)p.ti[1] * p.ti[3] * fr;
+                int64_t pre = 0;
+                if (p.cache_read == 2) {
+                    int64_t rows = bm % op->OW == 0 ? bm / op->OW : (op->OW + bm - 2) / op->OW + 1;
+                    int64_t pr = (rows - 1) * d.stride + d.dims[5], pw = (op->OW - 1) * d.stride + d.dims[6];
+                    pre = (pr * pw * d.dims[3] * es / 4 + p.threads - 1) / p.threads;
+                }
+                int64_t have = 512 / ((p.waves + 3) / 4);
+                if (breg + areg + pre + acc + 24 > have)
+                    return reject("weights in registers: %" PRId64 " weight + %" PRId64 " operand + %" PRId64 " prefetch + %" PRId64
+                                  " accumulator registers per lane exceed the %" PRId64 " a wavefront can have", breg, areg, pre, acc, have);
+                frag = 0; // accounted for above
+                stage = 0;
+                live = 0;
+            }
             if (p.cache_read == 4) {
                 if (p.waves % 2) return reject("ping-pong wave groups need an even number of wavefronts, not %d", p.waves);
                 if (p.tk[1] != 1 || p.tk[2] != 1) return reject("ping-pong wave groups need k1 = k2 = 1 (a tile's fragments are read in one phase)");
@@ -407,6 +441,7 @@ int32_t make_kernel_spec(const ms_op *op, const ms_variant_params *p, KernelSpec
     D.push_back(def("LDS_PAD", p->lds_pad));
     D.push_back(def("REORDER", p->reorder));
     D.push_back(def("COMPUTE_AT", p->compute_at));
+    D.push_back(def("HELPER_WAVES", p->compute_at == 3 ? 4 : 0));
     if (p->family == MS_FAM_GEMM_ALU || p->family == MS_FAM_GEMM_MFMA) {
         D.push_back(def("DIM_B", op->nb));
         D.push_back(def("DIM_M", op->M));

@@ -155,7 +155,7 @@ extern "C" int32_t ms_variant_launch(ms_variant *v, const void *const *inputs, v
         gy = 1;
         gzz = 1;
     }
-    if (v->p.family == MS_FAM_GEMM_MFMA && v->p.compute_at == 2) {
+    if (v->p.family == MS_FAM_GEMM_MFMA && v->p.compute_at >= 2) {
         // persistent workgroups with resident weights: as many as fit the compute units' LDS, each owns a run of tiles
         uint64_t total = (uint64_t)v->spec.grid[0] * gz;
         uint64_t per_cu = std::max<uint64_t>(1, std::min<uint64_t>(4, (160u * 1024u) / (uint64_t)std::max(1, v->p.lds_bytes)));

@@ -80,10 +80,11 @@ def _traces_with_resident_patch(op, space, seed, count, compute_at=1, max_index=
     return out
 
 
-@pytest.mark.parametrize("compute_at", [1, 2])
+@pytest.mark.parametrize("compute_at", [1, 2, 3, 4])
 def test_c3_conv_resident_patch(compute_at):
-    """C3 with the cache-read of X under the workgroup tile loop (sample-compute-location = tile), and with the
-    weights resident as well: row-aligned tiles and tiles that start in the middle of an output row."""
+    """C3 with the cache-read of X under the workgroup tile loop (sample-compute-location = tile), with the
+    weights resident as well (2), with helper wavefronts (3), and with the weights in registers (4): row-aligned tiles and tiles that start in the
+    middle of an output row."""
     X, W, bias = I.c3(seed=3)
     ref = O.conv2d_nhwc(X, W, bias=bias, relu=True, stride=1, pad=1)
     op = B.conv2d_op(1, 56, 56, 64, 64, 3, 3, stride=1, pad=1)
@@ -100,7 +101,7 @@ def test_c3_conv_resident_patch(compute_at):
         compare.assert_float_close(got, ref, compare.RTOL_HALF, "C3 compute_at %d, trace %d" % (compute_at, n))
 
 
-@pytest.mark.parametrize("compute_at", [1, 2])
+@pytest.mark.parametrize("compute_at", [1, 2, 3, 4])
 @pytest.mark.parametrize("stride,pad,k,H,W_", [(1, 1, 3, 16, 16), (2, 1, 3, 16, 32), (1, 0, 1, 8, 16), (2, 3, 7, 32, 16), (1, 2, 5, 12, 16)])
 def test_conv_resident_patch_geometries_exact(stride, pad, k, H, W_, compute_at):
     """Resident input patch with other strides, paddings and filter sizes, batch 2, 2 instances with distinct
@@ -145,13 +146,14 @@ def test_conv_persistent_runs_cross_instances():
     ins = [sets[r % 5] for r in range(R)]
     op = B.conv2d_op(N, H, W_, Cin, Cout, 3, 3, stride=1, pad=1, out_dtype="f32")
     space = op.space()
-    for cache_read in (1, 2):
-        traces = [t for t in _traces_with_resident_patch(op, space, 9, 40, 2) if B.trace_validate(op, space, t).cache_read == cache_read][:2]
-        assert traces, "no valid trace with compute_at 2 and cache_read %d" % cache_read
+    for compute_at, cache_read in ((2, 1), (2, 2), (3, 2), (4, 1), (4, 2)):
+        traces = [t for t in _traces_with_resident_patch(op, space, 9, 40, compute_at)
+                  if B.trace_validate(op, space, t).cache_read == cache_read][:2]
+        assert traces, "no valid trace with compute_at %d and cache_read %d" % (compute_at, cache_read)
         for n, t in enumerate(traces):
             p = B.trace_validate(op, space, t)
             tiles = p.grid[0] * R
-            print("cache_read", cache_read, "trace", n, t.decisions(), "tiles", tiles, flush=True)
+            print("compute_at", compute_at, "cache_read", cache_read, "trace", n, t.decisions(), "tiles", tiles, flush=True)
             assert tiles > 4 * 256, "the launch must have several tiles per workgroup"
             got = run_variant_distinct(op, space, t, ins, "f32", (N, H, W_, Cout))
             if got is None:
