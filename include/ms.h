@@ -180,7 +180,7 @@ typedef enum ms_slot_id {
 } ms_slot_id;
 
 /* Tensorize candidates: (m, n, k) of one matrix-core instruction.  The code
- * is m*10000 + n*100 + k, e.g. 161616, 323208, 161632, 323216, 161664, 323232. */
+ * is m*10000 + n*100 + k, e.g. 161616, 323208, 161632, 323216, 161664, 323232; fp32: 161604, 323202. */
 #define MS_MFMA_CODE(m, n, k) ((m) * 10000 + (n) * 100 + (k))
 #define MS_MFMA_NONE 0
 
@@ -226,7 +226,11 @@ typedef struct ms_slot {
 #define MS_SPACE_REORDER 0x20u      /* sample the grid loop order; off = i outer */
 #define MS_SPACE_CACHE_WRITE 0x40u   /* sample LDS staging of the output tile; off = direct stores */
 #define MS_SPACE_COMPUTE_AT 0x80u    /* conv2d: sample the loop that holds the cache-read of X; off = under k0 */
-#define MS_SPACE_DEFAULT 0xffffffffu
+#define MS_SPACE_TENSORIZE_F32 0x100u /* opt-in, not part of the default: fp32 operators on the fp32 matrix-core
+                                         intrinsics (16x16x4, 32x32x2) instead of the vector ALUs; the products are
+                                         summed in another order than in the vector kernels, within the fp32 tolerance */
+#define MS_SPACE_DEFAULT 0xffu       /* every module above except the opt-in one; masks with bit 31 set (the
+                                         all-ones default of earlier tuning records) mean the same */
 
 typedef enum ms_family { MS_FAM_GEMM_ALU = 0, MS_FAM_GEMM_MFMA = 1, MS_FAM_DWCONV = 2 } ms_family;
 

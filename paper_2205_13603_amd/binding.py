@@ -19,7 +19,8 @@ SLOT_PERFECT_TILE, SLOT_CATEGORICAL = 0, 1
  SLOT_STORAGE_ALIGN, SLOT_REORDER, SLOT_VECTORIZE_B, SLOT_CACHE_WRITE, SLOT_COMPUTE_AT) = range(13)
 SPACE_TENSORIZE, SPACE_CACHE_READ, SPACE_VECTORIZE, SPACE_UNROLL, SPACE_STORAGE_ALIGN, SPACE_REORDER, SPACE_CACHE_WRITE = 1, 2, 4, 8, 16, 32, 64
 SPACE_COMPUTE_AT = 128
-SPACE_DEFAULT = 0xFFFFFFFF
+SPACE_TENSORIZE_F32 = 0x100  # opt-in: fp32 operators on the fp32 matrix-core intrinsics
+SPACE_DEFAULT = 0xFF
 FAM_GEMM_ALU, FAM_GEMM_MFMA, FAM_DWCONV = range(3)
 MAX_SLOTS, MAX_FACTORS, MAX_CANDS, MAX_LOOPS = 16, 4, 8, 8
 

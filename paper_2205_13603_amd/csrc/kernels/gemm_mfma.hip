@@ -96,7 +96,7 @@ constexpr int STAGES = CACHE_READ >= 2 ? 2 : 1;
 constexpr int KSTEPS = K1 * K2 * K3;              // MFMA k steps per tile
 
 static_assert(MI_M == MI_N, "square intrinsics only");
-static_assert(FRAG_BYTES == 8 || FRAG_BYTES == 16, "fragment is 8 or 16 bytes");
+static_assert(FRAG_BYTES == 4 || FRAG_BYTES == 8 || FRAG_BYTES == 16, "fragment is 4 (fp32), 8 or 16 bytes");
 
 // ---- fragment and accumulator types, one MFMA
 typedef vec_t<in_t, KP> frag_t;
@@ -152,8 +152,16 @@ __device__ __forceinline__ accv_t mfma(const frag_t &a, const frag_t &b, accv_t 
 #else
 #error "no such int8 intrinsic"
 #endif
+#elif IN_DT == DT_F32
+#if MI_M == 16 && MI_K == 4
+    return __builtin_amdgcn_mfma_f32_16x16x4f32(a.v[0], b.v[0], c, 0, 0, 0);
+#elif MI_M == 32 && MI_K == 2
+    return __builtin_amdgcn_mfma_f32_32x32x2f32(a.v[0], b.v[0], c, 0, 0, 0);
 #else
-#error "matrix-core kernels take fp16, bf16 or int8 inputs"
+#error "no such fp32 intrinsic"
+#endif
+#else
+#error "matrix-core kernels take fp16, bf16, int8 or fp32 inputs"
 #endif
 }
 

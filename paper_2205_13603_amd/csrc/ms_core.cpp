@@ -407,10 +407,14 @@ extern "C" int32_t ms_space_describe(const ms_op *op, uint32_t flags, ms_space *
     if (!op || !out) return fail(MS_ERR_BAD_ARG, "ms_space_describe: NULL argument");
     memset(out, 0, sizeof *out);
     const ms_op_desc &d = op->d;
-    if (d.in_dtype == MS_F32) flags &= ~MS_SPACE_TENSORIZE;
+    if (flags & 0x80000000u) flags &= 0xffu; // all-ones masks of earlier records: the default set, opt-in modules off
+    if (d.in_dtype == MS_F32 && !((flags & MS_SPACE_TENSORIZE_F32) && d.kind != MS_OP_DWCONV2D_NHWC && d.kind != MS_OP_CONV2D_NHWC))
+        flags &= ~(MS_SPACE_TENSORIZE | MS_SPACE_TENSORIZE_F32);
+    if (d.in_dtype != MS_F32) flags &= ~MS_SPACE_TENSORIZE_F32;
+    if (flags & MS_SPACE_TENSORIZE_F32) flags |= MS_SPACE_TENSORIZE;
     if (d.kind == MS_OP_DWCONV2D_NHWC) flags &= ~(MS_SPACE_TENSORIZE | MS_SPACE_VECTORIZE | MS_SPACE_STORAGE_ALIGN | MS_SPACE_CACHE_WRITE);
     if (d.kind != MS_OP_CONV2D_NHWC) flags &= ~MS_SPACE_COMPUTE_AT;
-    flags &= 0xffu;
+    flags &= 0x1ffu;
     out->flags = flags;
     if (d.kind == MS_OP_DWCONV2D_NHWC) {
         out->family = MS_FAM_DWCONV;
@@ -431,8 +435,9 @@ extern "C" int32_t ms_space_describe(const ms_op *op, uint32_t flags, ms_space *
         ms_slot *t = add_slot(out, MS_SLOT_TENSORIZE, MS_SLOT_CATEGORICAL, "tensorize");
         static const int64_t f16_list[] = {161616, 323208, 161632, 323216};
         static const int64_t i8_list[] = {161632, 323216, 161664, 323232};
-        const int64_t *list = d.in_dtype == MS_I8 ? i8_list : f16_list;
-        for (int c = 0; c < 4; ++c) {
+        static const int64_t f32_list[] = {161604, 323202};
+        const int64_t *list = d.in_dtype == MS_I8 ? i8_list : (d.in_dtype == MS_F32 ? f32_list : f16_list);
+        for (int c = 0; c < (d.in_dtype == MS_F32 ? 2 : 4); ++c) {
             int m, n, k;
             mfma_dims(list[c], &m, &n, &k);
             if (op->M % m || op->N % n || op->K % k) continue;
@@ -459,13 +464,17 @@ extern "C" int32_t ms_space_describe(const ms_op *op, uint32_t flags, ms_space *
         if (flags & MS_SPACE_UNROLL) add_cat(out, MS_SLOT_UNROLL, "unroll", {0, 16, 64});
         if (flags & MS_SPACE_CACHE_READ) {
             // direct-to-LDS staging (5, 6, 7) exists for 2-byte inputs of plain matrix products
-            if (d.in_dtype != MS_I8 && d.kind != MS_OP_CONV2D_NHWC) add_cat(out, MS_SLOT_CACHE_READ, "cache_read", {1, 2, 3, 4, 5, 6, 7});
+            if (d.in_dtype != MS_I8 && d.in_dtype != MS_F32 && d.kind != MS_OP_CONV2D_NHWC)
+                add_cat(out, MS_SLOT_CACHE_READ, "cache_read", {1, 2, 3, 4, 5, 6, 7});
             else add_cat(out, MS_SLOT_CACHE_READ, "cache_read", {1, 2, 3, 4});
         }
         if (flags & MS_SPACE_VECTORIZE) {
             if (d.in_dtype == MS_I8) {
                 add_cat(out, MS_SLOT_VECTORIZE, "vectorize", {1, 4, 8, 16});
                 add_cat(out, MS_SLOT_VECTORIZE_B, "vectorize_b", {1, 4, 8, 16});
+            } else if (d.in_dtype == MS_F32) {
+                add_cat(out, MS_SLOT_VECTORIZE, "vectorize", {1, 2, 4});
+                add_cat(out, MS_SLOT_VECTORIZE_B, "vectorize_b", {1, 2, 4});
             } else {
                 add_cat(out, MS_SLOT_VECTORIZE, "vectorize", {1, 2, 4, 8});
                 add_cat(out, MS_SLOT_VECTORIZE_B, "vectorize_b", {1, 2, 4, 8});
@@ -473,7 +482,7 @@ extern "C" int32_t ms_space_describe(const ms_op *op, uint32_t flags, ms_space *
         }
         if (flags & MS_SPACE_STORAGE_ALIGN) add_cat(out, MS_SLOT_STORAGE_ALIGN, "storage_align", {0, 1, 2});
         if (flags & MS_SPACE_REORDER) {
-            if (d.in_dtype != MS_I8 && d.kind != MS_OP_CONV2D_NHWC) add_cat(out, MS_SLOT_REORDER, "reorder", {0, 1, 2, 3});
+            if (d.in_dtype != MS_I8 && d.in_dtype != MS_F32 && d.kind != MS_OP_CONV2D_NHWC) add_cat(out, MS_SLOT_REORDER, "reorder", {0, 1, 2, 3});
             else add_cat(out, MS_SLOT_REORDER, "reorder", {0, 1, 2});
         }
         if (flags & MS_SPACE_CACHE_WRITE) add_cat(out, MS_SLOT_CACHE_WRITE, "cache_write", {0, 1});

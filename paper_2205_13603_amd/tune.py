@@ -18,7 +18,7 @@ def main():
     ap.add_argument("--trials", type=int, default=256)
     ap.add_argument("--seed", type=int, default=0)
     ap.add_argument("--instances", type=int, default=0)
-    ap.add_argument("--flags", type=lambda s: int(s, 0), default=0xFFFFFFFF, help="search-space module mask")
+    ap.add_argument("--flags", type=lambda s: int(s, 0), default=0xFF, help="search-space module mask (0xff = default, 0x1ff = with fp32 tensorize)")
     ap.add_argument("--out", default="gpurun_out/tuned")
     ap.add_argument("--seed-records", action="store_true", help="measure stored records first (reported, not part of the search)")
     args = ap.parse_args()

@@ -41,29 +41,29 @@ def append_record(name, rec):
         f.write(json.dumps(rec, sort_keys=True) + "\n")
 
 
-def records_with_traces(name, op, space, limit=4):
-    """[(record dict, parsed trace)] of the stored records that still parse and validate, best first."""
+def records_with_traces(name, op, limit=4):
+    """[(record dict, space, parsed trace)] of the stored records that still parse and validate, best first.
+    Every record names the module mask of the space it was found in (`flags`), so each gets its own space."""
     out = []
+    spaces = {}
     for rec in load_records(name)[:limit]:
+        flags = int(rec.get("flags", B.SPACE_DEFAULT))
         try:
+            if flags not in spaces:
+                spaces[flags] = op.space(flags)
+            space = spaces[flags]
             t = B.trace_from_text(space, rec["trace"])
             B.trace_validate(op, space, t)
-            out.append((rec, t))
+            out.append((rec, space, t))
         except B.MsError:
             continue
     return out
-
-
-def record_traces(name, op, space, limit=4):
-    return [t for _, t in records_with_traces(name, op, space, limit)]
 
 
 def precompile_all(threads=4):
     n = 0
     for name, (mk, _) in WORKLOADS.items():
         op = mk()
-        space = op.space()
-        traces = record_traces(name, op, space)
-        if traces:
-            n += B.prebuild(op, space, traces, threads)
+        for _, space, t in records_with_traces(name, op):
+            n += B.prebuild(op, space, [t], threads)
     return n

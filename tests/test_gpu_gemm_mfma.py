@@ -194,3 +194,40 @@ def test_persistent_workgroups_many_tiles_per_workgroup():
             continue
         for r in range(3):
             compare.assert_float_close(got[r], refs[r], 1e-4, "instance %d trace %d" % (r, n))
+
+
+F32_INTRINS = [161604, 323202]
+
+
+def test_c1_fp32_on_matrix_cores():
+    """Config C1 (fp32 GEMM 128^3) with the opt-in fp32 tensorize module: both fp32 intrinsics, the fp32
+    tolerance, 3 instances with distinct inputs."""
+    ins = [list(I.c1(seed=s)) for s in (0, 1, 2)]
+    refs = [O.gemm(a, b) for a, b in ins]
+    op = B.gemm_op(128, 128, 128, "f32")
+    space = op.space(B.SPACE_DEFAULT | B.SPACE_TENSORIZE_F32)
+    assert space.family == B.FAM_GEMM_MFMA
+    for n, t in enumerate(traces_covering_intrinsics(op, space, 6, 4, F32_INTRINS)):
+        print("trace", n, t.decisions(), flush=True)
+        got = run_variant_distinct(op, space, t, ins, "f32", (128, 128))
+        if got is None:
+            continue
+        for r in range(3):
+            compare.assert_float_close(got[r], refs[r], compare.RTOL_F32, "C1 on MFMA, instance %d trace %d" % (r, n))
+
+
+def test_fp32_matrix_cores_exact_on_small_ints_odd_tiles():
+    """fp32 intrinsics on a shape with factors 3, 5, 7 in the tile counts and a batch; integer-valued inputs:
+    every product and partial sum is exact, so the result must equal the oracle bit for bit."""
+    Bn, M, N, K = 2, 96, 160, 56
+    A, Bm = I.gemm_inputs(M, N, K, "f32", 5, "ints", batch=Bn)
+    ref = O.bmm(A, Bm, trans_b=False)
+    op = B.bmm_op(Bn, M, N, K, False, "f32")
+    space = op.space(B.SPACE_DEFAULT | B.SPACE_TENSORIZE_F32)
+    assert space.family == B.FAM_GEMM_MFMA
+    for n, t in enumerate(traces_covering_intrinsics(op, space, 8, 3, F32_INTRINS)):
+        print("trace", n, t.decisions(), flush=True)
+        got = run_variant(op, space, t, [A, Bm], "f32", (Bn, M, N), instances=2)
+        if got is None:
+            continue
+        assert np.array_equal(got[0], ref) and np.array_equal(got[1], ref), "trace %d" % n

@@ -103,6 +103,15 @@ def test_space_composition_by_flags():
     assert op.space(B.SPACE_DEFAULT & ~B.SPACE_TENSORIZE).family == B.FAM_GEMM_ALU
     op = B.dwconv2d_op(1, 112, 112, 32)
     assert slot_names(op.space()) == ["i", "j", "c", "unroll", "cache_read", "reorder"]
+    # fp32 on the matrix cores is opt-in; all-ones masks (earlier tuning records) mean the default set
+    op = B.gemm_op(128, 128, 128, "f32")
+    assert op.space().family == B.FAM_GEMM_ALU and op.space(0xFFFFFFFF).family == B.FAM_GEMM_ALU
+    sp = op.space(B.SPACE_DEFAULT | B.SPACE_TENSORIZE_F32)
+    assert sp.family == B.FAM_GEMM_MFMA
+    assert [sp.slots[0].candidates[i] for i in range(sp.slots[0].n_candidates)] == [161604, 323202]
+    assert [sp.slots[1].extent_by_choice[c] for c in range(2)] == [8, 4] and [sp.slots[3].extent_by_choice[c] for c in range(2)] == [32, 64]
+    assert B.dwconv2d_op(1, 8, 8, 4).space(B.SPACE_DEFAULT | B.SPACE_TENSORIZE_F32).family == B.FAM_DWCONV
+    assert B.gemm_op(64, 64, 64, "f16").space(B.SPACE_DEFAULT | B.SPACE_TENSORIZE_F32).flags == B.SPACE_DEFAULT & ~B.SPACE_COMPUTE_AT
 
 
 def test_space_size_matches_closed_form():
