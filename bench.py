@@ -75,7 +75,8 @@ BOUND = {  # which roofline bounds the workload (AI vs ridge), and the in-dtype
 }
 
 
-PROFILE_NAME = {"c2_gemm_f16_1024": "gemm_mfma_c2_gemm_f16_1024"}
+PROFILE_NAME = {"c1_gemm_f32_128": "gemm_mfma_c1_gemm_f32_128", "c2_gemm_f16_1024": "gemm_mfma_c2_gemm_f16_1024",
+                "c3_conv_f16_56x56x64": "gemm_mfma_c3_conv_f16_56x56x64", "c5a_dw_f32_112x112x32": "dwconv_c5a_dw_f32_112x112x32"}
 
 
 def main():
@@ -230,13 +231,13 @@ def main():
     l2 = v.measure(inst_sets, warmup=5, repeats=5, launches_per_repeat=max(200, R), instances=1, stream=stream)
     per1 = (bytes1 / 1e9) if bound == "hbm" else (flop1 / 1e12)
 
-    # HBM bytes per launch from the committed rocprofv3 counter summary of this very variant (stored record)
+    # HBM bytes per launch from the committed rocprofv3 counter summary, if it is of this very variant
     traffic = None
     prof = os.path.join(ROOT, "profiles", "ms_kernel_%s.txt" % PROFILE_NAME.get(name, name))
-    if best[2] == "record" and R == default_r and os.path.exists(prof):
-        for line in open(prof):
-            if line.startswith("traffic_bytes_per_launch:"):
-                traffic = float(line.split(":")[1])
+    if R == default_r and os.path.exists(prof):
+        fields = dict(line.split(":", 1) for line in open(prof) if line.startswith(("traffic_bytes_per_launch:", "variant_key:")))
+        if fields.get("variant_key", "").strip() == "%016x" % params.key and "traffic_bytes_per_launch" in fields:
+            traffic = float(fields["traffic_bytes_per_launch"])
 
     out = {
         "metric": METRIC, "value": value, "unit": unit, "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
