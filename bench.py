@@ -226,6 +226,22 @@ def main():
     value = work * args.steps / wall
     achieved = work / (kernel_us * 1e-6)
 
+    # ---- what the device attains on the bounding resource, measured now with the same clocks: the register-resident
+    # issue loop of the variant's intrinsic fed with operands of this workload, or the plain copy kernel
+    attainable = None
+    try:
+        if bound == "mfma" and params.mfma:
+            scratch = torch.zeros(1 << 16, dtype=torch.float32, device="cuda")
+            attainable = B.calibrate_mfma(in_dt, params.mfma, scratch.data_ptr(), dev_in[0].data_ptr(), stream=stream)
+        elif bound == "hbm":
+            nb = 1 << 30
+            src = torch.ones(nb, dtype=torch.uint8, device="cuda")
+            dst = torch.empty(nb, dtype=torch.uint8, device="cuda")
+            attainable = B.calibrate_stream(1, src.data_ptr(), dst.data_ptr(), nb, stream=stream)
+            del src, dst
+    except B.MsError as e:
+        print("calibration failed: %s" % str(e)[:200], file=sys.stderr)
+
     # ---- single-instance protocols at the workload's own shape
     l1 = v.measure(inst_sets[:1], warmup=5, repeats=100, launches_per_repeat=1, instances=1, stream=stream)
     l2 = v.measure(inst_sets, warmup=5, repeats=5, launches_per_repeat=max(200, R), instances=1, stream=stream)
@@ -253,7 +269,10 @@ def main():
                                "ti": list(params.ti), "tj": list(params.tj), "tk": list(params.tk), "tc": list(params.tc),
                                "unroll": params.unroll}},
         "roofline": {"bound": bound, "achieved": achieved, "peak": peak, "unit": unit, "frac": achieved / peak,
-                     "traffic": traffic, "kernel_us": kernel_us},
+                     "traffic": traffic, "kernel_us": kernel_us,
+                     "attainable": attainable, "frac_of_attainable": (achieved / attainable) if attainable else None,
+                     "attainable_kind": {"mfma": "register-resident loop of the variant's intrinsic on this workload's operand values",
+                                         "hbm": "1 GiB copy kernel, bytes read + written"}.get(bound) if attainable else None},
         "single_instance": {"single_launch_us": l1.median_us, "steady_state_us": l2.median_us,
                             "steady_state_" + ("gbs" if bound == "hbm" else "tflops"): per1 / (l2.median_us * 1e-6),
                             "rotating_sets": R},

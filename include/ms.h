@@ -503,6 +503,12 @@ int32_t ms_calibrate_lds(void *scratch, void *stream, double *bytes_per_clk_per_
  * (device pointer, at least 2 MiB) over and over; aggregate GB/s. */
 int32_t ms_calibrate_l2(const void *src, void *scratch, void *stream, double *gbs);
 
+/* Times a kernel of known duration with the event timing that ms_measure uses: one wavefront waits until the
+ * device's constant-rate wall clock has advanced by target_us (1 .. 20000).  `cfg->instances` is ignored;
+ * `scratch`: at least 512 bytes of device memory (never written).  On return out->min_us / median_us / mean_us are the
+ * measured durations per launch: they exceed target_us by the launch overhead only.  Synchronises `stream`. */
+int32_t ms_calibrate_timer(double target_us, const ms_measure_cfg *cfg, void *scratch, void *stream, ms_measure_result *out);
+
 int32_t ms_version(void);
 const char *ms_last_error(void);
 

@@ -170,6 +170,7 @@ SYMBOLS = {
     "ms_calibrate_stream": (C.c_int32, [C.c_int32, C.c_void_p, C.c_void_p, C.c_size_t, C.c_void_p, _P(C.c_double)]),
     "ms_calibrate_lds": (C.c_int32, [C.c_void_p, C.c_void_p, _P(C.c_double), _P(C.c_double)]),
     "ms_calibrate_l2": (C.c_int32, [C.c_void_p, C.c_void_p, C.c_void_p, _P(C.c_double)]),
+    "ms_calibrate_timer": (C.c_int32, [C.c_double, _P(ms_measure_cfg), C.c_void_p, C.c_void_p, _P(ms_measure_result)]),
     "ms_version": (C.c_int32, []),
     "ms_last_error": (C.c_char_p, []),
 }
@@ -425,6 +426,13 @@ def calibrate_l2(src_ptr, scratch_ptr, stream=None):
     v = C.c_double()
     _check(lib().ms_calibrate_l2(src_ptr, scratch_ptr, stream, C.byref(v)))
     return v.value
+
+
+def calibrate_timer(target_us, scratch_ptr, warmup=2, repeats=5, launches_per_repeat=1, stream=None):
+    cfg = ms_measure_cfg(warmup, repeats, launches_per_repeat, 1)
+    res = ms_measure_result()
+    _check(lib().ms_calibrate_timer(target_us, C.byref(cfg), scratch_ptr, stream, C.byref(res)))
+    return res
 
 
 def search_cfg_default():

@@ -167,14 +167,13 @@ extern "C" int32_t ms_variant_launch(ms_variant *v, const void *const *inputs, v
     return MS_OK;
 }
 
-extern "C" int32_t ms_measure(ms_variant *v, const ms_bufset *sets, int32_t n_sets, const ms_measure_cfg *cfg, void *stream,
-                              ms_measure_result *out)
+namespace {
+
+// The one timing routine: `launch` is called warm-up + repeats x launches_per_repeat times on `stream`;
+// each repeat is bracketed by two HIP events on that stream.  Fills min / median / mean per launch.
+template <class Launch>
+int32_t timed_repeats(Launch &&launch, const ms_measure_cfg *cfg, hipStream_t s, ms_measure_result *out, const char *who)
 {
-    if (!v || !sets || !cfg || !out || n_sets < 1) return fail(MS_ERR_BAD_ARG, "ms_measure: bad argument");
-    if (cfg->repeats < 1 || cfg->launches_per_repeat < 1 || cfg->warmup < 0 || cfg->instances < 1)
-        return fail(MS_ERR_BAD_ARG, "ms_measure: bad configuration");
-    memset(out, 0, sizeof *out);
-    hipStream_t s = (hipStream_t)stream;
     hipEvent_t e0 = nullptr, e1 = nullptr;
     HIP_TRY(hipEventCreate(&e0));
     if (hipEventCreate(&e1) != hipSuccess) {
@@ -183,15 +182,8 @@ extern "C" int32_t ms_measure(ms_variant *v, const ms_bufset *sets, int32_t n_se
     }
     int32_t rc = MS_OK;
     std::vector<double> us;
-    int set = 0;
-    auto launch = [&]() -> int32_t {
-        const ms_bufset &b = sets[set];
-        set = (set + 1) % n_sets;
-        void *outs[1] = {b.output};
-        return ms_variant_launch(v, b.inputs, outs, b.workspace, cfg->instances, stream);
-    };
     for (int i = 0; i < cfg->warmup && rc == MS_OK; ++i) rc = launch();
-    if (rc == MS_OK && hipStreamSynchronize(s) != hipSuccess) rc = fail(MS_ERR_HIP, "ms_measure: warm-up failed: %s", hipGetErrorString(hipGetLastError()));
+    if (rc == MS_OK && hipStreamSynchronize(s) != hipSuccess) rc = fail(MS_ERR_HIP, "%s: warm-up failed: %s", who, hipGetErrorString(hipGetLastError()));
     for (int r = 0; r < cfg->repeats && rc == MS_OK; ++r) {
         hipError_t e = hipEventRecord(e0, s);
         for (int l = 0; l < cfg->launches_per_repeat && rc == MS_OK; ++l) rc = launch();
@@ -201,7 +193,7 @@ extern "C" int32_t ms_measure(ms_variant *v, const ms_bufset *sets, int32_t n_se
         float ms_elapsed = 0;
         if (e == hipSuccess) e = hipEventElapsedTime(&ms_elapsed, e0, e1);
         if (e != hipSuccess) {
-            rc = fail(MS_ERR_HIP, "ms_measure: %s", hipGetErrorString(e));
+            rc = fail(MS_ERR_HIP, "%s: %s", who, hipGetErrorString(e));
             break;
         }
         us.push_back((double)ms_elapsed * 1000.0 / cfg->launches_per_repeat);
@@ -216,6 +208,27 @@ extern "C" int32_t ms_measure(ms_variant *v, const ms_bufset *sets, int32_t n_se
     double sum = 0;
     for (double x : us) sum += x;
     out->mean_us = sum / us.size();
+    return MS_OK;
+}
+
+} // namespace
+
+extern "C" int32_t ms_measure(ms_variant *v, const ms_bufset *sets, int32_t n_sets, const ms_measure_cfg *cfg, void *stream,
+                              ms_measure_result *out)
+{
+    if (!v || !sets || !cfg || !out || n_sets < 1) return fail(MS_ERR_BAD_ARG, "ms_measure: bad argument");
+    if (cfg->repeats < 1 || cfg->launches_per_repeat < 1 || cfg->warmup < 0 || cfg->instances < 1)
+        return fail(MS_ERR_BAD_ARG, "ms_measure: bad configuration");
+    memset(out, 0, sizeof *out);
+    int set = 0;
+    auto launch = [&]() -> int32_t {
+        const ms_bufset &b = sets[set];
+        set = (set + 1) % n_sets;
+        void *outs[1] = {b.output};
+        return ms_variant_launch(v, b.inputs, outs, b.workspace, cfg->instances, stream);
+    };
+    int32_t rc = timed_repeats(launch, cfg, (hipStream_t)stream, out, "ms_measure");
+    if (rc != MS_OK) return rc;
     double f, b;
     ms_op_work(&v->op, &f, &b);
     out->flop = f * cfg->instances;
@@ -296,9 +309,11 @@ int32_t time_launches(hipFunction_t fn, unsigned grid, void **args, hipStream_t 
 extern "C" int32_t ms_calibrate_mfma(int32_t in_dtype, int32_t mfma_code, const void *operands, void *scratch, void *stream, double *tflops)
 {
     if (!scratch || !tflops) return fail(MS_ERR_BAD_ARG, "ms_calibrate_mfma: NULL argument");
-    static const int f16_codes[] = {161616, 323208, 161632, 323216}, i8_codes[] = {161632, 323216, 161664, 323232};
-    const int *codes = in_dtype == MS_I8 ? i8_codes : f16_codes;
-    if (in_dtype != MS_F16 && in_dtype != MS_BF16 && in_dtype != MS_I8) return fail(MS_ERR_BAD_ARG, "ms_calibrate_mfma: bad dtype");
+    static const int f16_codes[] = {161616, 323208, 161632, 323216}, i8_codes[] = {161632, 323216, 161664, 323232},
+                     f32_codes[] = {161604, 323202, 161604, 323202};
+    const int *codes = in_dtype == MS_I8 ? i8_codes : (in_dtype == MS_F32 ? f32_codes : f16_codes);
+    if (in_dtype != MS_F16 && in_dtype != MS_BF16 && in_dtype != MS_I8 && in_dtype != MS_F32)
+        return fail(MS_ERR_BAD_ARG, "ms_calibrate_mfma: bad dtype");
     bool ok = false;
     for (int i = 0; i < 4; ++i) ok = ok || codes[i] == mfma_code;
     if (!ok) return fail(MS_ERR_BAD_ARG, "ms_calibrate_mfma: no intrinsic %d for %s", mfma_code, dtype_name(in_dtype));
@@ -394,4 +409,31 @@ extern "C" int32_t ms_calibrate_l2(const void *src, void *scratch, void *stream,
     if (rc != MS_OK) return rc;
     *gbs = (double)grid * 256 * 16.0 * 8 * reps / (ms_best * 1e-3) / 1e9;
     return MS_OK;
+}
+
+extern "C" int32_t ms_calibrate_timer(double target_us, const ms_measure_cfg *cfg, void *scratch, void *stream, ms_measure_result *out)
+{
+    if (!cfg || !out || !scratch) return fail(MS_ERR_BAD_ARG, "ms_calibrate_timer: NULL argument");
+    if (!(target_us >= 1.0) || target_us > 20000.0) return fail(MS_ERR_BAD_ARG, "ms_calibrate_timer: target of %g us outside [1, 20000]", target_us);
+    if (cfg->repeats < 1 || cfg->launches_per_repeat < 1 || cfg->warmup < 0) return fail(MS_ERR_BAD_ARG, "ms_calibrate_timer: bad configuration");
+    memset(out, 0, sizeof *out);
+    int dev = 0, khz = 0;
+    HIP_TRY(hipGetDevice(&dev));
+    HIP_TRY(hipDeviceGetAttribute(&khz, hipDeviceAttributeWallClockRate, dev));
+    if (khz <= 0) return fail(MS_ERR_UNSUPPORTED, "ms_calibrate_timer: the device reports no wall clock rate");
+    std::vector<std::string> defs = {"-DMODE=5", "-DCAL_DT=0"};
+    CalibKernel ck;
+    int32_t rc = load_calib(defs, mix64(0xCA11B5ull), &ck);
+    if (rc != MS_OK) return rc;
+    int ticks = (int)(target_us * (double)khz / 1000.0 + 0.5);
+    const void *none = nullptr;
+    void *args[] = {&none, &none, &none, &scratch, &ticks};
+    hipStream_t s = (hipStream_t)stream;
+    auto launch = [&]() -> int32_t {
+        HIP_TRY(hipModuleLaunchKernel(ck.fn, 1, 1, 1, 64, 1, 1, 0, s, args, nullptr));
+        return MS_OK;
+    };
+    rc = timed_repeats(launch, cfg, s, out, "ms_calibrate_timer");
+    (void)hipModuleUnload(ck.mod);
+    return rc;
 }

@@ -104,3 +104,22 @@ def test_bmm_nt_and_nn_alu_fp32():
             if got is None:
                 continue
             compare.assert_float_close(got, ref, compare.RTOL_F32, "bmm trans_b=%s trace %d" % (trans_b, idx))
+
+
+@pytest.mark.parametrize("target_us", [100.0, 1000.0, 5000.0])
+def test_event_timing_recovers_a_known_duration(target_us):
+    """A kernel that waits for `target_us` of the device's constant-rate wall clock, timed with the routine
+    that ms_measure uses: every repeat must report the target plus at most the launch overhead."""
+    from paper_2205_13603_amd import devmem
+    if not devmem.gpu_available():
+        return
+    import torch
+    scratch = torch.zeros(1024, dtype=torch.uint8, device="cuda")
+    res = B.calibrate_timer(target_us, scratch.data_ptr(), warmup=2, repeats=7, launches_per_repeat=1, stream=devmem.current_stream())
+    print("target", target_us, "min", res.min_us, "median", res.median_us, "mean", res.mean_us, flush=True)
+    assert res.n == 7
+    assert target_us - 1.0 <= res.min_us <= res.median_us
+    assert res.median_us <= target_us * 1.01 + 40.0
+    # several launches per repeat: the per-launch figure is the total divided by the count
+    res4 = B.calibrate_timer(target_us, scratch.data_ptr(), warmup=1, repeats=3, launches_per_repeat=4, stream=devmem.current_stream())
+    assert target_us - 1.0 <= res4.min_us <= target_us * 1.01 + 40.0

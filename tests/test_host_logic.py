@@ -305,6 +305,56 @@ def test_validator_mfma_rules():
     assert "multiply to" in str(e.value)
 
 
+def test_validator_conv_compute_location_rules():
+    """sample-compute-location for conv2d: LDS footprints of the resident patch / weights and the constraints
+    each location puts on the other decisions (all checked on the host)."""
+    op = B.conv2d_op(1, 56, 56, 64, 64, 3, 3, stride=1, pad=1)
+    sp = op.space()
+    assert slot_names(sp)[-1] == "compute_at"
+
+    def mk(ca, mfma=161632, i=(14, 7, 2, 1), j=(1, 2, 2, 1), k=(9, 1, 2, 1), unroll=64, cache=2, vec=8, vec_b=8, pad=1, reorder=0, cw=1):
+        return B.make_trace(sp, [[mfma], list(i), list(j), list(k), [unroll], [cache], [vec], [vec_b], [pad], [reorder], [cw], [ca]])
+
+    planes_b = (64 // 8) * (64 * 16 + 16)             # one k step of the weights: 8 k-group planes of 64 fragments + pad
+    patch = 6 * 58 * (64 * 2 + 16)                    # 4 output rows -> 6 input rows x (56 + 2) columns x padded pixel
+    ctile = 224 * (64 * 2 + 16)
+    p0 = B.trace_validate(op, sp, mk(0))
+    assert p0.compute_at == 0 and p0.threads == 256
+    p1 = B.trace_validate(op, sp, mk(1))
+    assert p1.lds_bytes == 2 * planes_b + patch and p1.grid[0] == 14
+    p2 = B.trace_validate(op, sp, mk(2))
+    assert p2.lds_bytes == 9 * planes_b + patch + ctile and p2.threads == 256
+    p3 = B.trace_validate(op, sp, mk(3))
+    assert p3.waves == 8 and p3.threads == 512 and p3.lds_bytes == p2.lds_bytes  # four helper wavefronts
+    p4 = B.trace_validate(op, sp, mk(4))
+    assert p4.lds_bytes == planes_b + patch + ctile
+    assert len({p.key for p in (p0, p1, p2, p3, p4)}) == 5
+    for ca, kw, needle in [(1, dict(cache=4), "cache_read"), (2, dict(cache=3), "cache_read"), (2, dict(reorder=2), "reorder"),
+                           (3, dict(cw=0), "cache_write"), (3, dict(cache=1), "cache_read"),
+                           (4, dict(i=(7, 14, 2, 1), j=(1, 4, 1, 1)), "weights in registers"),
+                           (2, dict(i=(7, 14, 2, 1), k=(1, 9, 2, 1)), "LDS")]:
+        with pytest.raises(B.MsError) as e:
+            B.trace_validate(op, sp, mk(ca, **kw))
+        assert needle in str(e.value), (ca, kw, str(e.value))
+    # a 16-pixel tile of a 12-wide image starts in the middle of a row: 3 output rows, 5 patch rows; Cin = 24 is not
+    # a multiple of the 32-deep intrinsic
+    op2 = B.conv2d_op(1, 12, 12, 32, 32, 3, 3, stride=1, pad=1)
+    sp2 = op2.space()
+    t = B.make_trace(sp2, [[161632], [9, 1, 1, 1], [1, 2, 1, 1], [9, 1, 1, 1], [0], [1], [8], [8], [0], [0], [0], [1]])
+    assert B.trace_validate(op2, sp2, t).lds_bytes == 1 * (32 // 8) * (32 * 16) + 5 * 14 * 64
+    op3 = B.conv2d_op(1, 12, 12, 16, 32, 3, 3, stride=1, pad=1)
+    sp3 = op3.space()
+    cands = [sp3.slots[0].candidates[i] for i in range(sp3.slots[0].n_candidates)]
+    assert 161616 in cands
+    t = B.make_trace(sp3, [[161616], [9, 1, 1, 1], [1, 2, 1, 1], [9, 1, 1, 1], [0], [1], [8], [8], [0], [0], [0], [1]])
+    assert B.trace_validate(op3, sp3, t).compute_at == 1
+    if 161632 in cands:
+        t = B.make_trace(sp3, [[161632], [9, 1, 1, 1], [1, 2, 1, 1], [9, 1, 1, 1], [0], [1], [8], [8], [0], [0], [0], [1]])
+        with pytest.raises(B.MsError) as e:
+            B.trace_validate(op3, sp3, t)
+        assert "Cin" in str(e.value)
+
+
 CONFIG_OPS = [
     lambda: B.gemm_op(128, 128, 128, "f32"),
     lambda: B.gemm_op(256, 128, 64, "f16"),
