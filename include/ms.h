@@ -420,6 +420,10 @@ typedef struct ms_search_cfg {
     double temperature0;     /* T anneals geometrically from temperature0 to temperature1 */
     double temperature1;
     ms_measure_cfg measure;
+    int32_t cost_model;       /* 0 = every proposal is measured; 1 = a learned cost model picks which proposals to measure */
+    int32_t model_candidates; /* with the cost model: proposals scored per measured candidate (e.g. 8) */
+    int32_t model_min_trials; /* measurements needed before the model is used (earlier generations run as without it) */
+    int32_t reserved;
 } ms_search_cfg;
 void ms_search_cfg_default(ms_search_cfg *cfg);
 
@@ -448,6 +452,23 @@ typedef struct ms_search_result {
     int32_t reserved;
     double wall_seconds;
 } ms_search_result;
+
+/* ------------------------------------------------------------ cost model */
+
+/* The learned cost model of Section 4 ("End-to-end search"): least-squares gradient boosting of regression trees
+ * with exact greedy splits, deterministic, host only.  Rows of X are feature vectors (row-major, n x d doubles),
+ * y the targets (the search uses log2 of the measured microseconds).  fit() replaces whatever was fitted before;
+ * predict() needs the same d.  A tree splits a node on the (feature, midpoint between two consecutive distinct
+ * values) that lowers the squared error most, both sides keeping at least min_leaf rows; depth = number of split
+ * levels; every tree's prediction is added with weight learning_rate.  n_trees = 0 predicts the mean of y. */
+typedef struct ms_cost_model ms_cost_model;
+int32_t ms_cost_model_create(int32_t n_trees, int32_t depth, double learning_rate, int32_t min_leaf, ms_cost_model **out);
+void ms_cost_model_destroy(ms_cost_model *m);
+int32_t ms_cost_model_fit(ms_cost_model *m, const double *X, const double *y, int32_t n, int32_t d);
+int32_t ms_cost_model_predict(const ms_cost_model *m, const double *X, int32_t n, int32_t d, double *out);
+/* Feature vector of a variant as the search feeds it to the model (tile factors, workgroup shape, LDS and
+ * register footprints, staging decisions, mostly log2).  out may be NULL to query the count (*n). */
+int32_t ms_variant_features(const ms_op *op, const ms_variant_params *params, double *out, int32_t cap, int32_t *n);
 
 /* Evolutionary search (Section 4): sample init_population traces; then per
  * generation propose children by mutating parents drawn with probability

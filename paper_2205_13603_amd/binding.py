@@ -111,7 +111,8 @@ class ms_measure_result(C.Structure):
 class ms_search_cfg(C.Structure):
     _fields_ = [("seed", C.c_uint64), ("trials", C.c_int32), ("init_population", C.c_int32), ("population", C.c_int32),
                 ("children", C.c_int32), ("eps_permille", C.c_int32), ("compile_threads", C.c_int32),
-                ("temperature0", C.c_double), ("temperature1", C.c_double), ("measure", ms_measure_cfg)]
+                ("temperature0", C.c_double), ("temperature1", C.c_double), ("measure", ms_measure_cfg),
+                ("cost_model", C.c_int32), ("model_candidates", C.c_int32), ("model_min_trials", C.c_int32), ("reserved", C.c_int32)]
 
 
 class ms_trial(C.Structure):
@@ -170,6 +171,11 @@ SYMBOLS = {
     "ms_calibrate_stream": (C.c_int32, [C.c_int32, C.c_void_p, C.c_void_p, C.c_size_t, C.c_void_p, _P(C.c_double)]),
     "ms_calibrate_lds": (C.c_int32, [C.c_void_p, C.c_void_p, _P(C.c_double), _P(C.c_double)]),
     "ms_calibrate_l2": (C.c_int32, [C.c_void_p, C.c_void_p, C.c_void_p, _P(C.c_double)]),
+    "ms_cost_model_create": (C.c_int32, [C.c_int32, C.c_int32, C.c_double, C.c_int32, _P(C.c_void_p)]),
+    "ms_cost_model_destroy": (None, [C.c_void_p]),
+    "ms_cost_model_fit": (C.c_int32, [C.c_void_p, _P(C.c_double), _P(C.c_double), C.c_int32, C.c_int32]),
+    "ms_cost_model_predict": (C.c_int32, [C.c_void_p, _P(C.c_double), C.c_int32, C.c_int32, _P(C.c_double)]),
+    "ms_variant_features": (C.c_int32, [C.c_void_p, _P(ms_variant_params), _P(C.c_double), C.c_int32, _P(C.c_int32)]),
     "ms_calibrate_timer": (C.c_int32, [C.c_double, _P(ms_measure_cfg), C.c_void_p, C.c_void_p, _P(ms_measure_result)]),
     "ms_version": (C.c_int32, []),
     "ms_last_error": (C.c_char_p, []),
@@ -433,6 +439,44 @@ def calibrate_timer(target_us, scratch_ptr, warmup=2, repeats=5, launches_per_re
     res = ms_measure_result()
     _check(lib().ms_calibrate_timer(target_us, C.byref(cfg), scratch_ptr, stream, C.byref(res)))
     return res
+
+
+class CostModel:
+    """Gradient-boosted regression trees of the library (fit / predict on numpy float64 arrays)."""
+
+    def __init__(self, n_trees=50, depth=3, learning_rate=0.3, min_leaf=2):
+        self.handle = C.c_void_p()
+        _check(lib().ms_cost_model_create(n_trees, depth, learning_rate, min_leaf, C.byref(self.handle)))
+
+    def __del__(self):
+        if getattr(self, "handle", None):
+            lib().ms_cost_model_destroy(self.handle)
+            self.handle = None
+
+    def fit(self, X, y):
+        import numpy as np
+        X = np.ascontiguousarray(X, dtype=np.float64)
+        y = np.ascontiguousarray(y, dtype=np.float64)
+        n, d = X.shape
+        assert y.shape == (n,)
+        _check(lib().ms_cost_model_fit(self.handle, X.ctypes.data_as(_P(C.c_double)), y.ctypes.data_as(_P(C.c_double)), n, d))
+
+    def predict(self, X):
+        import numpy as np
+        X = np.ascontiguousarray(X, dtype=np.float64)
+        n, d = X.shape
+        out = np.empty(n, dtype=np.float64)
+        _check(lib().ms_cost_model_predict(self.handle, X.ctypes.data_as(_P(C.c_double)), n, d, out.ctypes.data_as(_P(C.c_double))))
+        return out
+
+
+def variant_features(op, params):
+    import numpy as np
+    n = C.c_int32()
+    _check(lib().ms_variant_features(op.handle, C.byref(params), None, 0, C.byref(n)))
+    out = np.empty(n.value, dtype=np.float64)
+    _check(lib().ms_variant_features(op.handle, C.byref(params), out.ctypes.data_as(_P(C.c_double)), n.value, C.byref(n)))
+    return out
 
 
 def search_cfg_default():

@@ -5,7 +5,7 @@ import subprocess
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libms.so")
-SOURCES = ["ms_core.cpp", "ms_interp.cpp", "ms_jit.cpp", "ms_runtime.cpp", "ms_search.cpp"]
+SOURCES = ["ms_core.cpp", "ms_interp.cpp", "ms_jit.cpp", "ms_runtime.cpp", "ms_search.cpp", "ms_model.cpp"]
 
 
 def build(verbose=False):

@@ -3,7 +3,12 @@
 // mutating sampling decisions; the validator rejects proposals outside the
 // hardware limits; every surviving candidate is measured on the device, and
 // selection / acceptance follow the posterior of Eq. 1, exp(-f) up to an
-// annealed temperature, with the measured latency f (no learned cost model).
+// annealed temperature, with the measured latency f.  With cfg->cost_model the
+// generation proposes model_candidates times as many children, a cost model
+// fitted to all measurements so far (log2 of the latency as a function of the
+// variant's features) predicts each, an annealed Metropolis-Hastings step on
+// the predictions decides which children stay, and only the best predicted
+// ones are measured: the paper's search, with boosted trees of this library.
 #include "ms_internal.h"
 
 #include <algorithm>
@@ -32,6 +37,9 @@ extern "C" void ms_search_cfg_default(ms_search_cfg *cfg)
     cfg->measure.repeats = 5;
     cfg->measure.launches_per_repeat = 20;
     cfg->measure.instances = 1;
+    cfg->cost_model = 0;
+    cfg->model_candidates = 8;
+    cfg->model_min_trials = 48;
 }
 
 namespace {
@@ -56,6 +64,9 @@ struct Search {
     ms_search_result *res;
     std::map<uint64_t, double> seen;
     std::vector<double> curve; // latency of each measured trial
+    std::vector<double> feat;  // features of each measured trial, row-major
+    std::vector<double> target; // log2 of its latency
+    int32_t n_feat = 0;
     bool stop = false;
 
     // returns latency in us, or < 0 when the candidate produced no measurement
@@ -102,6 +113,15 @@ struct Search {
         }
         ++res->n_measured;
         curve.push_back(us);
+        if (cfg->cost_model) {
+            double fv[128];
+            int32_t nf = 0;
+            if (ms_variant_features(op, &p, fv, 128, &nf) == MS_OK) {
+                n_feat = nf;
+                feat.insert(feat.end(), fv, fv + nf);
+                target.push_back(log2(us));
+            }
+        }
         if (res->best_us <= 0 || us < res->best_us) {
             res->best_us = us;
             res->best_trace = t;
@@ -127,6 +147,17 @@ extern "C" int32_t ms_search(const ms_op *op, const ms_space *space, const ms_se
     if (cfg->trials < 1 || cfg->init_population < 1 || cfg->population < 1 || cfg->children < 1 || cfg->eps_permille < 0 ||
         cfg->eps_permille > 1000 || !(cfg->temperature0 > 0) || !(cfg->temperature1 > 0))
         return fail(MS_ERR_BAD_ARG, "ms_search: bad configuration");
+    if (cfg->cost_model && (cfg->model_candidates < 1 || cfg->model_candidates > 1024 || cfg->model_min_trials < 4))
+        return fail(MS_ERR_BAD_ARG, "ms_search: bad cost-model configuration");
+    ms_cost_model *model = nullptr;
+    if (cfg->cost_model) {
+        int32_t rc = ms_cost_model_create(60, 4, 0.3, 2, &model);
+        if (rc != MS_OK) return rc;
+    }
+    struct ModelGuard {
+        ms_cost_model *m;
+        ~ModelGuard() { ms_cost_model_destroy(m); }
+    } model_guard{model};
     auto t_start = std::chrono::steady_clock::now();
     memset(out, 0, sizeof *out);
     Search S;
@@ -201,20 +232,104 @@ extern "C" int32_t ms_search(const ms_op *op, const ms_space *space, const ms_se
             int parent; // -1 = fresh sample
         };
         std::vector<Child> kids;
-        for (int c = 0; c < cfg->children && proposals < max_proposals; ++c) {
-            Child k;
+        auto propose = [&](Child *k) -> bool {
             ++proposals;
             if ((int)rng.below(1000) < cfg->eps_permille) {
-                if (ms_trace_sample(space, cfg->seed, sample_index++, &k.t) != MS_OK) continue;
-                k.parent = -1;
+                if (ms_trace_sample(space, cfg->seed, sample_index++, &k->t) != MS_OK) return false;
+                k->parent = -1;
             } else {
                 double u = unit_uniform(rng) * tot;
                 size_t pi = (size_t)(std::lower_bound(cum.begin(), cum.end(), u) - cum.begin());
                 if (pi >= pop.size()) pi = pop.size() - 1;
-                if (ms_trace_mutate(space, &pop[pi].trace, rng.next(), &k.t) != MS_OK) continue;
-                k.parent = (int)pi;
+                if (ms_trace_mutate(space, &pop[pi].trace, rng.next(), &k->t) != MS_OK) return false;
+                k->parent = (int)pi;
             }
-            kids.push_back(k);
+            return true;
+        };
+        const bool use_model = model && (int32_t)S.target.size() >= cfg->model_min_trials && S.n_feat > 0;
+        if (!use_model) {
+            for (int c = 0; c < cfg->children && proposals < max_proposals; ++c) {
+                Child k;
+                if (propose(&k)) kids.push_back(k);
+            }
+        } else {
+            // the model sees every measurement so far; targets are log2(latency)
+            if (ms_cost_model_fit(model, S.feat.data(), S.target.data(), (int32_t)S.target.size(), S.n_feat) != MS_OK) return MS_ERR_BAD_ARG;
+            struct Scored {
+                Child k;
+                double pred;
+                uint64_t key;
+            };
+            std::vector<Scored> cand;
+            std::map<uint64_t, bool> in_batch;
+            // Candidates come from several rounds of mutation: in the first round the parents are measured
+            // members of the population, in later rounds also candidates accepted so far (their cost is the
+            // predicted one), so that the model can lead the search more than one decision away.
+            const int want = cfg->children * cfg->model_candidates;
+            const int rounds = 3;
+            for (int round = 0; round < rounds; ++round) {
+                const int goal = want * (round + 1) / rounds;
+                const size_t n_prev = cand.size();
+                for (int c = 0; c < want * 4 && (int)cand.size() < goal && proposals < max_proposals; ++c) {
+                    Scored sc;
+                    double parent_cost = -1;
+                    if (round > 0 && n_prev > 0 && rng.below(2) == 0) {
+                        ++proposals;
+                        const Scored &src = cand[(size_t)rng.below(n_prev)];
+                        if (ms_trace_mutate(space, &src.k.t, rng.next(), &sc.k.t) != MS_OK) continue;
+                        sc.k.parent = src.k.parent; // the measured ancestor (-1: a fresh sample)
+                        parent_cost = exp2(src.pred);
+                    } else {
+                        if (!propose(&sc.k)) continue;
+                        if (sc.k.parent >= 0) parent_cost = pop[(size_t)sc.k.parent].us;
+                    }
+                    ms_variant_params p;
+                    if (ms_trace_validate(op, space, &sc.k.t, &p) != MS_OK) {
+                        ++out->n_invalid;
+                        continue;
+                    }
+                    if (S.seen.count(p.key) || in_batch.count(p.key)) {
+                        ++out->n_duplicate;
+                        continue;
+                    }
+                    double fv[128];
+                    int32_t nf = 0;
+                    if (ms_variant_features(op, &p, fv, 128, &nf) != MS_OK || nf != S.n_feat) continue;
+                    if (ms_cost_model_predict(model, fv, 1, nf, &sc.pred) != MS_OK) continue;
+                    // annealed Metropolis-Hastings on the predicted cost: a child predicted slower than its parent
+                    // survives with probability exp(-(f^_child - f_parent) / (T f_best)), latencies in microseconds
+                    if (parent_cost > 0) {
+                        const double fc = exp2(sc.pred);
+                        if (fc > parent_cost && !(unit_uniform(rng) < exp(-(fc - parent_cost) / (T * fbest)))) continue;
+                    }
+                    sc.key = p.key;
+                    in_batch[p.key] = true;
+                    cand.push_back(sc);
+                }
+            }
+            // Half of the generation's measurements go to the best predicted candidates, the other half to
+            // candidates in the order they were proposed (the plain search's own distribution): a model that
+            // is wrong about a region it has not seen must not be able to keep the search out of it.
+            // Fresh samples keep their share of the slots.
+            std::vector<size_t> by_pred(cand.size());
+            for (size_t i = 0; i < cand.size(); ++i) by_pred[i] = i;
+            std::stable_sort(by_pred.begin(), by_pred.end(), [&](size_t a, size_t b) { return cand[a].pred < cand[b].pred; });
+            int fresh_quota = (cfg->children * cfg->eps_permille + 999) / 1000;
+            std::vector<bool> taken(cand.size(), false);
+            auto take = [&](size_t i) {
+                kids.push_back(cand[i].k);
+                taken[i] = true;
+            };
+            for (size_t i = 0; i < cand.size() && fresh_quota > 0 && (int)kids.size() < cfg->children; ++i)
+                if (cand[i].k.parent < 0) {
+                    take(i);
+                    --fresh_quota;
+                }
+            const int by_model = ((int)cfg->children - (int)kids.size() + 1) / 2 + (int)kids.size();
+            for (size_t r = 0; r < by_pred.size() && (int)kids.size() < by_model; ++r)
+                if (!taken[by_pred[r]]) take(by_pred[r]);
+            for (size_t i = 0; i < cand.size() && (int)kids.size() < cfg->children; ++i)
+                if (!taken[i]) take(i);
         }
         if (!fake_latency) {
             std::vector<ms_trace> batch;

@@ -20,6 +20,8 @@ def main():
     ap.add_argument("--instances", type=int, default=0)
     ap.add_argument("--flags", type=lambda s: int(s, 0), default=0xFF, help="search-space module mask (0xff = default, 0x1ff = with fp32 tensorize)")
     ap.add_argument("--out", default="gpurun_out/tuned")
+    ap.add_argument("--cost-model", action="store_true", help="let the learned cost model pick which proposals are measured")
+    ap.add_argument("--model-candidates", type=int, default=8, help="proposals scored per measured candidate")
     ap.add_argument("--seed-records", action="store_true", help="measure stored records first (reported, not part of the search)")
     args = ap.parse_args()
 
@@ -57,6 +59,7 @@ def main():
 
     cfg = B.search_cfg_default()
     cfg.seed, cfg.trials = args.seed, args.trials
+    cfg.cost_model, cfg.model_candidates = int(args.cost_model), args.model_candidates
     cfg.measure = B.ms_measure_cfg(1, 3, 3, R)
     res = B.search(op, space, cfg, bufsets=sets, stream=devmem.current_stream(), on_trial=on_trial)
     flop, byts = op.work()
