@@ -3,6 +3,7 @@
 //   MODE 0: each wave issues ITERS x 8 independent MFMAs on register operands
 //   MODE 1: copy `n16` 16-byte words src -> dst, one contiguous range per workgroup
 //   MODE 2: read `n16` 16-byte words (sum folded into a value that is stored only if it hits a sentinel)
+//   MODE 6: write `n16` 16-byte words to dst
 //   MODE 5: one wavefront waits until the constant-rate wall clock has advanced by `ticks` (a kernel of known
 //           duration: checks the event timing that every measurement here relies on)
 #define IN_DT CAL_DT
@@ -168,6 +169,15 @@ extern "C" __global__ void __launch_bounds__(256) ms_calib_kernel(const void *sr
     const long lo = (long)blockIdx.x * per, hi = lo + per < n16 ? lo + per : n16;
     for (long i = lo + threadIdx.x; i < hi; i += 256) d[i] = s[i];
     (void)stride;
+#elif MODE == 6
+    // write only: one contiguous range per workgroup
+    const long per = (n16 + gridDim.x - 1) / gridDim.x;
+    const long lo = (long)blockIdx.x * per, hi = lo + per < n16 ? lo + per : n16;
+    w16_t x;
+    x.v[0] = x.v[1] = x.v[2] = x.v[3] = (float)blockIdx.x;
+    for (long i = lo + threadIdx.x; i < hi; i += 256) d[i] = x;
+    (void)stride;
+    (void)s;
 #else
     float acc = 0.f;
     for (long i = (long)blockIdx.x * blockDim.x + threadIdx.x; i < n16; i += stride) {

@@ -662,43 +662,46 @@ constexpr int NS = K1 * K2;
 //       transpose load (ds_read_b64_tr_b16: inside a group of 16 lanes, lane i receives element
 //       i%4 of lanes i/4, 4 + i/4, 8 + i/4, 12 + i/4): four lanes hand in one k-row of the panel,
 //       every lane gets 4 consecutive k of its own column - the MFMA B fragment.
-// 2-byte inputs and 8-element fragments (16x16x32, 32x32x16) only.
+// 16-byte fragments only: 2-byte inputs with 16x16x32 / 32x32x16, 1-byte inputs with 16x16x64 / 32x32x32 (their B of NN
+// is read with the 8-bit transpose load, 8 k-rows x 16 columns per group of 16 lanes).
 #if CACHE_READ >= 5
 constexpr int DL_STAGES = CACHE_READ - 3;
-constexpr int CPR = BK / 8;                               // 16-byte chunks per k-contiguous row
-constexpr int ROW_BYTES = BK * 2;
+constexpr int CE = 16 / ES;                               // elements per 16-byte chunk
+constexpr int CPR = BK / CE;                              // 16-byte chunks per k-contiguous row
+constexpr int ROW_BYTES = BK * ES;
 constexpr int SWZ_DIV = CPR >= 8 ? 1 : 8 / CPR;           // rows that share one 128-byte line
 constexpr int RPI = 64 / CPR;                             // rows per load instruction
 constexpr int DL_A_BYTES = BM * ROW_BYTES;
 #if B_KMAJOR
 constexpr int DL_B_BYTES = BN * ROW_BYTES;
 #else
-constexpr int DL_B_BYTES = ((BK * (BN / 8) + 63) / 64) * 1024;
+constexpr int DL_B_BYTES = ((BK * (BN / CE) + 63) / 64) * 1024;
 #endif
 constexpr int DL_STAGE_BYTES = DL_A_BYTES + DL_B_BYTES;
 constexpr int DL_IA = BM / RPI;                           // load instructions per A tile
 #if B_KMAJOR
 constexpr int DL_IB = BN / RPI;
 #else
-constexpr int CB = BN / 8;                                // 16-byte chunks per k-row of the j-contiguous B tile
-constexpr int BROW_BYTES = BN * 2;
+constexpr int CB = BN / CE;                               // 16-byte chunks per k-row of the j-contiguous B tile
+constexpr int BROW_BYTES = BN * ES;
 constexpr int DL_IB = (BK * CB + 63) / 64;
-// swizzle of the 32-byte granules (16 columns) of a row with the row number; needs a power-of-two granule count
+// swizzle of the 16-column granules (what one transpose load covers: 32 bytes of 2-byte, 16 bytes of 1-byte
+// elements) of a row with the row number; needs a power-of-two granule count
 constexpr int NGRAN = BN / 16;
 constexpr int GRAN_MASK = (NGRAN & (NGRAN - 1)) ? 0 : (NGRAN > 16 ? 15 : NGRAN - 1);
 #endif
 constexpr int DL_INSTR = DL_IA + DL_IB;
 constexpr int DL_LPW_MIN = DL_INSTR / NWAVES;             // loads every wavefront issues per tile, at least
-static_assert(ES == 2 && KP == 8, "direct-to-LDS path: 2-byte inputs, 8-element fragments");
-static_assert(CPR == 4 || CPR == 8 || CPR == 16, "direct-to-LDS path: k tile of 32, 64 or 128");
+static_assert((ES == 2 && KP == 8) || (ES == 1 && KP == 16), "direct-to-LDS path: 16-byte fragments of 2-byte or 1-byte inputs");
+static_assert(CPR == 4 || CPR == 8 || CPR == 16, "direct-to-LDS path: k tile of 64, 128 or 256 bytes");
 
 #define AS1(p) ((const __attribute__((address_space(1))) void *)(p))
 #define AS3(p) ((__attribute__((address_space(3))) void *)(p))
 
 __device__ __forceinline__ int dl_swz(int row) { return (row / SWZ_DIV) % CPR; }
 #if !B_KMAJOR
-// chunk-index XOR for k-row `k` of the j-contiguous operand: moves whole 32-byte granules
-__device__ __forceinline__ int dl_swz_b(int k) { return (k & GRAN_MASK) << 1; }
+// chunk-index XOR for k-row `k` of the j-contiguous operand: moves whole 16-column granules (ES chunks each)
+__device__ __forceinline__ int dl_swz_b(int k) { return (k & GRAN_MASK) * ES; }
 #endif
 
 // issue this wavefront's share of the loads of tile `k0` into the stage at `stage`
@@ -714,7 +717,7 @@ __device__ __forceinline__ void dl_issue(const in_t *__restrict__ A, const in_t 
             const int row = inst * RPI + lane / CPR;
             const int c = (lane % CPR) ^ dl_swz(row);
             const char *ub = (const char *)(A + ((long)i0 * BM + inst * RPI) * SA_I + k0e);
-            const unsigned voff = (unsigned)(((lane / CPR) * SA_I + c * 8) * 2);
+            const unsigned voff = (unsigned)(((lane / CPR) * SA_I + c * CE) * ES);
             __builtin_amdgcn_global_load_lds(AS1(ub + voff), AS3(stage + inst * 1024), 16, 0, 0);
         } else if (inst < DL_INSTR) {
             const int ib = inst - DL_IA;
@@ -722,14 +725,14 @@ __device__ __forceinline__ void dl_issue(const in_t *__restrict__ A, const in_t 
             const int row = ib * RPI + lane / CPR;
             const int c = (lane % CPR) ^ dl_swz(row);
             const char *ub = (const char *)(B + ((long)j0 * BN + ib * RPI) * SB_J + k0e);
-            const unsigned voff = (unsigned)(((lane / CPR) * SB_J + c * 8) * 2);
+            const unsigned voff = (unsigned)(((lane / CPR) * SB_J + c * CE) * ES);
 #else
             // lane-linear over the tile's chunks: whole 128-byte lines of consecutive k-rows per instruction
             const int idx = ib * 64 + lane;
             const int k = (BK * CB) % 64 == 0 ? idx / CB : (idx / CB < BK ? idx / CB : BK - 1);
             const int c = (idx % CB) ^ dl_swz_b(k);
             const char *ub = (const char *)(B + k0e * SB_K + (long)j0 * BN);
-            const unsigned voff = (unsigned)((k * SB_K + c * 8) * 2);
+            const unsigned voff = (unsigned)((k * SB_K + c * CE) * ES);
 #endif
             __builtin_amdgcn_global_load_lds(AS1(ub + voff), AS3(stage + DL_A_BYTES + ib * 1024), 16, 0, 0);
         }
@@ -737,6 +740,7 @@ __device__ __forceinline__ void dl_issue(const in_t *__restrict__ A, const in_t 
 }
 
 typedef short tr4_t __attribute__((ext_vector_type(4)));
+typedef int tr2_t __attribute__((ext_vector_type(2)));
 
 __device__ __forceinline__ void dl_read_frags(frag_t (&fa)[K3][TM], frag_t (&fb)[K3][TN], const char *__restrict__ stage, int slot, int wi, int wj,
                                               int lane)
@@ -764,14 +768,28 @@ __device__ __forceinline__ void dl_read_frags(frag_t (&fa)[K3][TM], frag_t (&fb)
 #else
                 const int pn = (tcol * MI_N + lrow) / 16; // 16-column granule of this lane's column
                 const int li = lane % 16;
+                frag_t f;
+#if ES == 2
+                // 16 lanes hand in 4 k-rows x 16 columns (lane: k-row li/4, 4 columns from li%4); two loads = 8 k
                 const int krow = step * MI_K + lgrp * 8 + li / 4;
                 const char *b0 = stage + DL_A_BYTES + krow * BROW_BYTES + (((pn << 1) ^ dl_swz_b(krow)) * 16) + (li % 4) * 8;
                 const char *b1 = stage + DL_A_BYTES + (krow + 4) * BROW_BYTES + (((pn << 1) ^ dl_swz_b(krow + 4)) * 16) + (li % 4) * 8;
                 const tr4_t lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) tr4_t *)(b0));
                 const tr4_t hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) tr4_t *)(b1));
-                frag_t f;
                 *reinterpret_cast<tr4_t *>(&f.v[0]) = lo;
                 *reinterpret_cast<tr4_t *>(&f.v[4]) = hi;
+#else
+                // 8-bit transpose load (ds_read_b64_tr_b8: inside a group of 16 lanes, lane i receives byte i%8 of
+                // lanes i/8, 2 + i/8, ..., 14 + i/8): 16 lanes hand in 8 k-rows x 16 columns (lane: k-row li/2,
+                // 8 columns from li%2), every lane gets 8 consecutive k of its own column; two loads = 16 k
+                const int krow = step * MI_K + lgrp * 16 + li / 2;
+                const char *b0 = stage + DL_A_BYTES + krow * BROW_BYTES + ((pn ^ dl_swz_b(krow)) * 16) + (li % 2) * 8;
+                const char *b1 = stage + DL_A_BYTES + (krow + 8) * BROW_BYTES + ((pn ^ dl_swz_b(krow + 8)) * 16) + (li % 2) * 8;
+                const tr2_t lo = __builtin_amdgcn_ds_read_tr8_b64_v2i32((__attribute__((address_space(3))) tr2_t *)(b0));
+                const tr2_t hi = __builtin_amdgcn_ds_read_tr8_b64_v2i32((__attribute__((address_space(3))) tr2_t *)(b1));
+                *reinterpret_cast<tr2_t *>(&f.v[0]) = lo;
+                *reinterpret_cast<tr2_t *>(&f.v[8]) = hi;
+#endif
                 fb[q][c1 * J3 + c3] = f;
 #endif
             }

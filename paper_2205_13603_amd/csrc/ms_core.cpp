@@ -463,8 +463,8 @@ extern "C" int32_t ms_space_describe(const ms_op *op, uint32_t flags, ms_space *
         }
         if (flags & MS_SPACE_UNROLL) add_cat(out, MS_SLOT_UNROLL, "unroll", {0, 16, 64});
         if (flags & MS_SPACE_CACHE_READ) {
-            // direct-to-LDS staging (5, 6, 7) exists for 2-byte inputs of plain matrix products
-            if (d.in_dtype != MS_I8 && d.in_dtype != MS_F32 && d.kind != MS_OP_CONV2D_NHWC)
+            // direct-to-LDS staging (5, 6, 7) exists for 2-byte and 1-byte inputs of plain matrix products
+            if (d.in_dtype != MS_F32 && d.kind != MS_OP_CONV2D_NHWC)
                 add_cat(out, MS_SLOT_CACHE_READ, "cache_read", {1, 2, 3, 4, 5, 6, 7});
             else add_cat(out, MS_SLOT_CACHE_READ, "cache_read", {1, 2, 3, 4});
         }
@@ -482,7 +482,7 @@ extern "C" int32_t ms_space_describe(const ms_op *op, uint32_t flags, ms_space *
         }
         if (flags & MS_SPACE_STORAGE_ALIGN) add_cat(out, MS_SLOT_STORAGE_ALIGN, "storage_align", {0, 1, 2});
         if (flags & MS_SPACE_REORDER) {
-            if (d.in_dtype != MS_I8 && d.in_dtype != MS_F32 && d.kind != MS_OP_CONV2D_NHWC) add_cat(out, MS_SLOT_REORDER, "reorder", {0, 1, 2, 3});
+            if (d.in_dtype != MS_F32 && d.kind != MS_OP_CONV2D_NHWC) add_cat(out, MS_SLOT_REORDER, "reorder", {0, 1, 2, 3});
             else add_cat(out, MS_SLOT_REORDER, "reorder", {0, 1, 2});
         }
         if (flags & MS_SPACE_CACHE_WRITE) add_cat(out, MS_SLOT_CACHE_WRITE, "cache_write", {0, 1});

@@ -211,19 +211,22 @@ extern "C" int32_t ms_trace_validate(const ms_op *op, const ms_space *space, con
             lds = (int64_t)(p.cache_read >= 2 ? 2 : 1) * (bk / kp) * (rowsA + rowsB);
             if (p.cache_read >= 5) {
                 // direct-to-LDS ring: dense tiles, no padding (the swizzle replaces it)
-                if (es != 2 || kp != 8) return reject("direct-to-LDS staging needs 2-byte inputs and an intrinsic with 8 k per lane");
-                if (bk != 32 && bk != 64 && bk != 128) return reject("direct-to-LDS staging needs a k tile of 32, 64 or 128, not %" PRId64, bk);
-                if (d.a_strides[2] != 1 || d.a_strides[1] % 8 || d.a_strides[0] % 8) return reject("direct-to-LDS staging needs 16-byte aligned rows of A");
+                const int ce = 16 / es; // elements per 16-byte chunk
+                if (!((es == 2 && kp == 8) || (es == 1 && kp == 16)))
+                    return reject("direct-to-LDS staging needs 16-byte fragments: 2-byte inputs with 8 k per lane or 1-byte inputs with 16 k per lane");
+                if (bk * es != 64 && bk * es != 128 && bk * es != 256) return reject("direct-to-LDS staging needs a k tile of 64, 128 or 256 bytes, not %" PRId64, bk * es);
+                if (d.a_strides[2] != 1 || d.a_strides[1] % ce || d.a_strides[0] % ce) return reject("direct-to-LDS staging needs 16-byte aligned rows of A");
                 if (d.b_strides[1] == 1 && d.b_strides[2] != 1) {
-                    if (d.b_strides[2] % 8 || d.b_strides[0] % 8) return reject("direct-to-LDS staging needs 16-byte aligned rows of B");
+                    if (d.b_strides[2] % ce || d.b_strides[0] % ce) return reject("direct-to-LDS staging needs 16-byte aligned rows of B");
                 } else if (d.b_strides[2] == 1) {
-                    if (d.b_strides[1] % 8 || d.b_strides[0] % 8) return reject("direct-to-LDS staging needs 16-byte aligned rows of B");
+                    if (d.b_strides[1] % ce || d.b_strides[0] % ce) return reject("direct-to-LDS staging needs 16-byte aligned rows of B");
+                    if (bn % 16) return reject("direct-to-LDS staging reads B in groups of 16 columns");
                 } else {
                     return reject("direct-to-LDS staging needs B contiguous along k or j");
                 }
                 if (p.lds_pad) return reject("direct-to-LDS staging has its own swizzle: storage_align must be 0");
                 // the j-contiguous B tile is rounded up to whole 1 KiB load instructions
-                int64_t btile = d.b_strides[2] == 1 ? ((bk * (bn / 8) + 63) / 64) * 1024 : bn * bk * es;
+                int64_t btile = d.b_strides[2] == 1 ? ((bk * (bn / ce) + 63) / 64) * 1024 : bn * bk * es;
                 lds = (int64_t)(p.cache_read - 3) * (bm * bk * es + btile);
             }
             if (p.compute_at) {

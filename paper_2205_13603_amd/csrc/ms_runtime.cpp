@@ -343,9 +343,10 @@ extern "C" int32_t ms_calibrate_mfma(int32_t in_dtype, int32_t mfma_code, const 
 extern "C" int32_t ms_calibrate_stream(int32_t mode, const void *src, void *dst, size_t bytes, void *stream, double *gbs)
 {
     if (!src || !dst || !gbs) return fail(MS_ERR_BAD_ARG, "ms_calibrate_stream: NULL argument");
-    if ((mode != 1 && mode != 2) || bytes == 0 || bytes % 4096 || bytes / 4096 > 0x7fffffffull)
-        return fail(MS_ERR_BAD_ARG, "ms_calibrate_stream: mode must be 1 or 2 and bytes a multiple of 4096");
-    std::vector<std::string> defs = {"-DMODE=" + std::to_string(mode), "-DCAL_DT=0"};
+    if ((mode != 1 && mode != 2 && mode != 3) || bytes == 0 || bytes % 4096 || bytes / 4096 > 0x7fffffffull)
+        return fail(MS_ERR_BAD_ARG, "ms_calibrate_stream: mode must be 1, 2 or 3 and bytes a multiple of 4096");
+    // kernel modes: 1 copy, 2 read, 6 write (3, 4, 5 are the LDS, L2 and timer kernels)
+    std::vector<std::string> defs = {"-DMODE=" + std::to_string(mode == 3 ? 6 : mode), "-DCAL_DT=0"};
     CalibKernel ck;
     int32_t rc = load_calib(defs, mix64(0xCA11B1ull ^ (uint64_t)mode), &ck);
     if (rc != MS_OK) return rc;

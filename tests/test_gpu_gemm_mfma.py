@@ -144,6 +144,57 @@ def test_c4c_int8_gemm_512_bit_exact():
         compare.assert_int_equal(got, ref, "C4c trace %d" % n)
 
 
+def test_int8_direct_to_lds_bit_exact():
+    """int8 GEMM (NN) and BMM-NT through the direct-to-LDS ring: A row-major with swizzled chunks, B of the NN form
+    read with the 8-bit LDS transpose load; both 16-k-per-lane intrinsics, 2 / 3 / 4 stages, persistent workgroups,
+    odd tile counts, 3 instances with distinct inputs; int32 results must equal the oracle bit for bit."""
+    M, N, K = 192, 160, 384
+    g = I.rng(31)
+    ins = [[I.int8_uniform(g, (M, K)), I.int8_uniform(g, (K, N))] for _ in range(3)]
+    refs = [O.gemm(a, b) for a, b in ins]
+    op = B.gemm_op(M, N, K, "i8")
+    space = op.space()
+
+    def mk(mfma, i, j, k, unroll=0, cache=5, reorder=0, cw=0):
+        return B.make_trace(space, [[mfma], i, j, k, [unroll], [cache], [16], [16], [0], [reorder], [cw]])
+
+    traces = [mk(161664, [12, 1, 1, 1], [10, 1, 1, 1], [6, 1, 1, 1]),                          # 16x16 tile, 1 wave, BK = 64
+              mk(161664, [3, 2, 2, 1], [5, 1, 2, 1], [3, 1, 2, 1], unroll=64, cache=6, cw=1),  # BK = 128
+              mk(323232, [3, 1, 2, 1], [5, 1, 1, 1], [6, 1, 1, 2], cache=7, reorder=2),          # BK = 64, 4 stages
+              mk(323232, [2, 1, 3, 1], [5, 1, 1, 1], [3, 2, 2, 1], unroll=16, cache=5, reorder=1, cw=1),  # BK = 128
+              mk(323232, [3, 2, 1, 1], [5, 1, 1, 1], [6, 1, 1, 2], cache=6, reorder=3),          # persistent workgroups
+              mk(161664, [6, 1, 2, 1], [5, 2, 1, 1], [3, 1, 1, 2], unroll=64, cache=5, reorder=3, cw=1)]
+    ran = 0
+    for n, t in enumerate(traces):
+        try:
+            B.trace_validate(op, space, t)
+        except B.MsError as e:
+            print("trace", n, "rejected:", str(e)[:120], flush=True)
+            continue
+        print("trace", n, t.decisions(), flush=True)
+        ran += 1
+        got = run_variant_distinct(op, space, t, ins, "i32", (M, N))
+        if got is None:
+            continue
+        for r in range(3):
+            compare.assert_int_equal(got[r], refs[r], "int8 direct-to-LDS, instance %d trace %d" % (r, n))
+    assert ran == 6
+    # NT form (both operands k-contiguous): no transpose load involved
+    Bn, Mh, Nh, Kh = 3, 64, 96, 128
+    Q = I.int8_uniform(g, (Bn, Mh, Kh))
+    Kt = I.int8_uniform(g, (Bn, Nh, Kh))
+    ref = O.bmm(Q, Kt, trans_b=True)
+    op2 = B.bmm_op(Bn, Mh, Nh, Kh, True, "i8")
+    sp2 = op2.space()
+    for n, t in enumerate([B.make_trace(sp2, [[323232], [2, 1, 1, 1], [1, 3, 1, 1], [2, 1, 1, 2], [0], [5], [16], [16], [0], [0], [0]]),
+                           B.make_trace(sp2, [[161664], [2, 1, 2, 1], [3, 1, 2, 1], [1, 1, 2, 1], [64], [6], [16], [16], [0], [2], [1]])]):
+        print("NT trace", n, t.decisions(), flush=True)
+        got = run_variant(op2, sp2, t, [Q, Kt], "i32", (Bn, Mh, Nh))
+        if got is None:
+            continue
+        compare.assert_int_equal(got, ref, "int8 NT direct-to-LDS trace %d" % n)
+
+
 def test_int8_extremes():
     A = np.full((64, 512), -128, np.int8)
     Bm = np.full((512, 64), -128, np.int8)
