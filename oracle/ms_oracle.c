@@ -169,16 +169,19 @@ int64_t ms_oracle_conv_out_size(int64_t in, int64_t k, int64_t s, int64_t p)
 
 /*
  * conv2d, NHWC activations, HWIO weights, optional fp32 bias (NULL = none),
- * optional ReLU.  Y is dense [N][OH][OW][Cout] in double.
+ * optional ReLU; tap (kh, kw) reads input element (oh*stride + kh*dilation - pad,
+ * ow*stride + kw*dilation - pad), zero outside the image.  Y is dense [N][OH][OW][Cout] in double.
  */
 int ms_oracle_conv2d_nhwc(int dtype, int64_t N, int64_t H, int64_t W_, int64_t Cin, int64_t Cout,
-                          int64_t KH, int64_t KW, int64_t stride, int64_t pad,
+                          int64_t KH, int64_t KW, int64_t stride, int64_t pad, int64_t dilation,
                           const void *X, const void *Wt, const float *bias, int relu,
                           double *Y)
 {
     if (dtype != ORA_F32 && dtype != ORA_F16 && dtype != ORA_BF16) return -1;
-    int64_t OH = conv_out_size(H, KH, stride, pad);
-    int64_t OW = conv_out_size(W_, KW, stride, pad);
+    if (dilation < 1) return -1;
+    /* a filter with taps `dilation` apart spans dilation*(K-1)+1 input elements */
+    int64_t OH = conv_out_size(H, dilation * (KH - 1) + 1, stride, pad);
+    int64_t OW = conv_out_size(W_, dilation * (KW - 1) + 1, stride, pad);
     int64_t row;
 #pragma omp parallel for schedule(static)
     for (row = 0; row < N * OH; ++row) {
@@ -187,9 +190,9 @@ int ms_oracle_conv2d_nhwc(int dtype, int64_t N, int64_t H, int64_t W_, int64_t C
             for (int64_t co = 0; co < Cout; ++co) {
                 double acc = 0.0;
                 for (int64_t kh = 0; kh < KH; ++kh) {
-                    int64_t ih = oh * stride + kh - pad;
+                    int64_t ih = oh * stride + kh * dilation - pad;
                     for (int64_t kw = 0; kw < KW; ++kw) {
-                        int64_t iw = ow * stride + kw - pad;
+                        int64_t iw = ow * stride + kw * dilation - pad;
                         for (int64_t ci = 0; ci < Cin; ++ci) {
                             double x = 0.0;
                             if (ih >= 0 && ih < H && iw >= 0 && iw < W_)

@@ -275,6 +275,39 @@ def test_conv_vs_torch_cpu(stride, pad, k):
     assert np.allclose(got, want, rtol=1e-12, atol=1e-12)
 
 
+@pytest.mark.parametrize("stride,pad,k,dil", [(1, 2, 3, 2), (2, 2, 3, 2), (1, 3, 2, 3), (1, 0, 3, 2)])
+def test_dilated_conv_vs_torch_cpu_and_vs_zero_stuffed_filter(stride, pad, k, dil):
+    """Dilation: (a) an independent library routine; (b) by definition a dilated k x k filter equals the dense
+    (dil*(k-1)+1)-wide filter whose taps sit `dil` apart with zeros between them."""
+    torch = pytest.importorskip("torch")
+    g = I.rng(19)
+    X = g.normal(size=(2, 12, 10, 3)).astype(np.float32)
+    W = g.normal(size=(k, k, 3, 4)).astype(np.float32)
+    b = g.normal(size=4).astype(np.float32)
+    got = O.conv2d_nhwc(X, W, bias=b, relu=True, stride=stride, pad=pad, dilation=dil)
+    xt = torch.from_numpy(X).double().permute(0, 3, 1, 2)
+    wt = torch.from_numpy(W).double().permute(3, 2, 0, 1)
+    want = torch.relu(torch.nn.functional.conv2d(xt, wt, torch.from_numpy(b).double(), stride=stride, padding=pad, dilation=dil))
+    want = want.permute(0, 2, 3, 1).numpy()
+    assert got.shape == want.shape
+    assert np.allclose(got, want, rtol=1e-12, atol=1e-12)
+    ke = dil * (k - 1) + 1
+    Wz = np.zeros((ke, ke, 3, 4), np.float32)
+    Wz[::dil, ::dil] = W
+    assert np.array_equal(got, O.conv2d_nhwc(X, Wz, bias=b, relu=True, stride=stride, pad=pad))
+    # one-hot tap at (k-1, k-1): the image shifted by dil*(k-1) - pad in both directions
+    W1 = np.zeros((k, k, 3, 3), np.float32)
+    for c in range(3):
+        W1[k - 1, k - 1, c, c] = 1
+    Y = O.conv2d_nhwc(X, W1, stride=1, pad=pad, dilation=dil)
+    sh = dil * (k - 1) - pad
+    for oh in range(Y.shape[1]):
+        for ow in range(Y.shape[2]):
+            ih, iw = oh + sh, ow + sh
+            ref = X[:, ih, iw, :] if 0 <= ih < 12 and 0 <= iw < 10 else 0.0
+            assert np.array_equal(Y[:, oh, ow, :], np.broadcast_to(ref, (2, 3)).astype(np.float64))
+
+
 # ---------------------------------------------------------------- depthwise
 def test_dw_equals_conv_with_block_diagonal_weights():
     X, W = I.dw_inputs(2, 7, 6, 5, seed=14)
