@@ -99,7 +99,7 @@ typedef struct ms_op_desc {
     int32_t pad;
     int32_t has_bias;
     int32_t relu;
-    int32_t reserved;
+    int32_t dilation;   /* conv2d: distance between filter taps in input elements; 0 or 1 = dense filter */
     int64_t dims[8];
     int64_t a_strides[3];
     int64_t b_strides[3];

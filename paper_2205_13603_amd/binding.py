@@ -35,7 +35,7 @@ class MsError(RuntimeError):
 
 class ms_op_desc(C.Structure):
     _fields_ = [("kind", C.c_int32), ("in_dtype", C.c_int32), ("out_dtype", C.c_int32), ("stride", C.c_int32),
-                ("pad", C.c_int32), ("has_bias", C.c_int32), ("relu", C.c_int32), ("reserved", C.c_int32),
+                ("pad", C.c_int32), ("has_bias", C.c_int32), ("relu", C.c_int32), ("dilation", C.c_int32),
                 ("dims", C.c_int64 * 8), ("a_strides", C.c_int64 * 3), ("b_strides", C.c_int64 * 3)]
 
 
@@ -211,12 +211,12 @@ def _check(rc):
 # ------------------------------------------------------------------ thin object wrappers
 class Op:
     def __init__(self, kind, in_dtype, out_dtype, dims, stride=0, pad=0, has_bias=False, relu=False,
-                 a_strides=None, b_strides=None):
+                 a_strides=None, b_strides=None, dilation=0):
         d = ms_op_desc()
         d.kind = kind
         d.in_dtype = DTYPE_NAMES.get(in_dtype, in_dtype)
         d.out_dtype = DTYPE_NAMES.get(out_dtype, out_dtype)
-        d.stride, d.pad, d.has_bias, d.relu = stride, pad, int(has_bias), int(relu)
+        d.stride, d.pad, d.has_bias, d.relu, d.dilation = stride, pad, int(has_bias), int(relu), dilation
         for i, v in enumerate(dims):
             d.dims[i] = v
         for i, v in enumerate(a_strides or ()):
@@ -267,9 +267,9 @@ def bmm_op(B, M, N, K, trans_b, in_dtype="f16", out_dtype=None, **kw):
               [B, M, N, K], **kw)
 
 
-def conv2d_op(N, H, W, Cin, Cout, KH, KW, stride=1, pad=0, has_bias=True, relu=True, in_dtype="f16", out_dtype=None):
+def conv2d_op(N, H, W, Cin, Cout, KH, KW, stride=1, pad=0, has_bias=True, relu=True, in_dtype="f16", out_dtype=None, dilation=1):
     return Op(OP_CONV2D_NHWC, in_dtype, out_dtype or in_dtype, [N, H, W, Cin, Cout, KH, KW], stride=stride, pad=pad,
-              has_bias=has_bias, relu=relu)
+              has_bias=has_bias, relu=relu, dilation=dilation)
 
 
 def dwconv2d_op(N, H, W, Cc, KH=3, KW=3, stride=1, pad=1):

@@ -185,7 +185,7 @@ template <int V> __device__ __forceinline__ vec_t<in_t, V> load_conv_a(const in_
 {
     const int ow = row % CV_OW, oh = (row / CV_OW) % CV_OH, n = row / (CV_OW * CV_OH);
     const int ci = k % CV_CIN, kw = (k / CV_CIN) % CV_KW, kh = k / (CV_CIN * CV_KW);
-    const int ih = oh * CV_STRIDE + kh - CV_PAD, iw = ow * CV_STRIDE + kw - CV_PAD;
+    const int ih = oh * CV_STRIDE + kh * CV_DIL - CV_PAD, iw = ow * CV_STRIDE + kw * CV_DIL - CV_PAD;
     vec_t<in_t, V> x;
     if (ih >= 0 && ih < CV_H && iw >= 0 && iw < CV_W) {
         x = *reinterpret_cast<const vec_t<in_t, V> *>(X + (((long)n * CV_H + ih) * CV_W + iw) * CV_CIN + ci);
@@ -325,8 +325,8 @@ __device__ __forceinline__ void jmajor_store(const jmajor_stage &st, char *__res
 #if CONV_PATCH
 // ---- resident input patch (COMPUTE_AT 1)
 constexpr int P_ROWS_OUT = BM % CV_OW == 0 ? BM / CV_OW : (CV_OW + BM - 2) / CV_OW + 1; // output rows a tile can touch
-constexpr int P_R = (P_ROWS_OUT - 1) * CV_STRIDE + CV_KH;   // patch rows
-constexpr int P_W = (CV_OW - 1) * CV_STRIDE + CV_KW;        // patch columns (column pc = input column pc - pad)
+constexpr int P_R = (P_ROWS_OUT - 1) * CV_STRIDE + CV_DIL * (CV_KH - 1) + 1; // patch rows (taps CV_DIL apart)
+constexpr int P_W = (CV_OW - 1) * CV_STRIDE + CV_DIL * (CV_KW - 1) + 1;      // patch columns (column pc = input column pc - pad)
 constexpr int P_PS = CV_CIN * ES + (LDS_PAD ? 16 : 0);      // bytes per patch pixel; the pad staggers neighbouring pixels over the banks
 constexpr int P_RS = P_W * P_PS;                            // bytes per patch row
 constexpr int PATCH_BYTES = ((P_R * P_RS + 15) / 16) * 16;
@@ -436,7 +436,7 @@ __device__ __forceinline__ int conv_koff(int k0, int step)
     const int kg = k0 * BK + step * MI_K; // wave-uniform
     const int tap = kg / CV_CIN, ci = kg % CV_CIN;
     const int kh = tap / CV_KW, kw = tap % CV_KW;
-    return kh * P_RS + kw * P_PS + ci * ES;
+    return kh * CV_DIL * P_RS + kw * CV_DIL * P_PS + ci * ES;
 }
 #else
 struct conv_ctx {
@@ -769,7 +769,7 @@ __device__ __forceinline__ void dl_read_frags(frag_t (&fa)[K3][TM], frag_t (&fb)
                 const int pn = (tcol * MI_N + lrow) / 16; // 16-column granule of this lane's column
                 const int li = lane % 16;
                 frag_t f;
-#if ES == 2
+#if IN_DT != DT_I8 // 2-byte elements
                 // 16 lanes hand in 4 k-rows x 16 columns (lane: k-row li/4, 4 columns from li%4); two loads = 8 k
                 const int krow = step * MI_K + lgrp * 8 + li / 4;
                 const char *b0 = stage + DL_A_BYTES + krow * BROW_BYTES + (((pn << 1) ^ dl_swz_b(krow)) * 16) + (li % 4) * 8;

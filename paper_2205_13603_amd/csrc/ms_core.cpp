@@ -224,15 +224,19 @@ extern "C" int32_t ms_op_create(const ms_op_desc *desc, ms_op **out)
         for (int i = 0; i < 3; ++i)
             if (op.d.a_strides[i] < 0 || op.d.b_strides[i] < 0)
                 return fail(MS_ERR_BAD_ARG, "ms_op_create: negative stride");
-        if (d.stride || d.pad || d.has_bias || d.relu)
-            return fail(MS_ERR_BAD_ARG, "ms_op_create: stride/pad/bias/relu only apply to convolutions");
+        if (d.stride || d.pad || d.has_bias || d.relu || d.dilation)
+            return fail(MS_ERR_BAD_ARG, "ms_op_create: stride/pad/bias/relu/dilation only apply to convolutions");
     } else {
         if (d.stride < 1 || d.pad < 0) return fail(MS_ERR_BAD_ARG, "ms_op_create: bad stride/pad");
         int64_t H = d.dims[1], W = d.dims[2];
         int64_t KH = d.kind == MS_OP_CONV2D_NHWC ? d.dims[5] : d.dims[4];
         int64_t KW = d.kind == MS_OP_CONV2D_NHWC ? d.dims[6] : d.dims[5];
-        op.OH = conv_out(H, KH, d.stride, d.pad);
-        op.OW = conv_out(W, KW, d.stride, d.pad);
+        if (d.dilation < 0 || d.dilation > 64) return fail(MS_ERR_BAD_ARG, "ms_op_create: bad dilation");
+        if (op.d.dilation == 0) op.d.dilation = 1;
+        if (op.d.dilation != 1 && d.kind != MS_OP_CONV2D_NHWC) return fail(MS_ERR_UNSUPPORTED, "ms_op_create: dilation is for conv2d only");
+        // a filter whose taps are `dilation` apart spans dilation * (K - 1) + 1 input elements
+        op.OH = conv_out(H, op.d.dilation * (KH - 1) + 1, d.stride, d.pad);
+        op.OW = conv_out(W, op.d.dilation * (KW - 1) + 1, d.stride, d.pad);
         if (op.OH < 1 || op.OW < 1) return fail(MS_ERR_BAD_ARG, "ms_op_create: empty convolution output");
         if (d.kind == MS_OP_CONV2D_NHWC) {
             if (d.in_dtype == MS_I8) return fail(MS_ERR_UNSUPPORTED, "ms_op_create: int8 conv2d is not supported");

@@ -56,6 +56,7 @@ uint64_t hash_params(const ms_op *op, const ms_variant_params *p)
     add((uint64_t)d.out_dtype);
     add((uint64_t)d.stride);
     add((uint64_t)d.pad);
+    add((uint64_t)d.dilation);
     add((uint64_t)d.has_bias);
     add((uint64_t)d.relu);
     for (int i = 0; i < 8; ++i) add((uint64_t)d.dims[i]);
@@ -242,7 +243,7 @@ extern "C" int32_t ms_trace_validate(const ms_op *op, const ms_space *space, con
                 if (cin % p.tile_unit[2]) return reject("resident input patch: Cin = %" PRId64 " is not a multiple of the intrinsic's k = %d", cin, p.tile_unit[2]);
                 if (ohw % bm) return reject("resident input patch: the %" PRId64 "-pixel tile straddles images of %" PRId64 " output pixels", bm, ohw);
                 int64_t rows = bm % op->OW == 0 ? bm / op->OW : (op->OW + bm - 2) / op->OW + 1;
-                int64_t pr = (rows - 1) * d.stride + d.dims[5], pw = (op->OW - 1) * d.stride + d.dims[6];
+                int64_t pr = (rows - 1) * d.stride + d.dilation * (d.dims[5] - 1) + 1, pw = (op->OW - 1) * d.stride + d.dilation * (d.dims[6] - 1) + 1;
                 int64_t ps = cin * es + (p.lds_pad ? 16 : 0);
                 int64_t patch = pr * pw * ps;
                 lds = (int64_t)(p.cache_read >= 2 ? 2 : 1) * (bk / kp) * rowsB + patch;
@@ -272,13 +273,13 @@ extern "C" int32_t ms_trace_validate(const ms_op *op, const ms_space *space, con
             if (p.compute_at == 3) {
                 // only the helpers carry the patch, over 256 lanes
                 int64_t rows = bm % op->OW == 0 ? bm / op->OW : (op->OW + bm - 2) / op->OW + 1;
-                int64_t pr = (rows - 1) * d.stride + d.dims[5], pw = (op->OW - 1) * d.stride + d.dims[6];
+                int64_t pr = (rows - 1) * d.stride + d.dilation * (d.dims[5] - 1) + 1, pw = (op->OW - 1) * d.stride + d.dilation * (d.dims[6] - 1) + 1;
                 stage = std::max(stage, (pr * pw * d.dims[3] * es / 4 + 255) / 256);
             }
             if (p.compute_at == 2 && p.cache_read == 2) {
                 // the next tile's patch waits in registers during the k loop
                 int64_t rows = bm % op->OW == 0 ? bm / op->OW : (op->OW + bm - 2) / op->OW + 1;
-                int64_t pr = (rows - 1) * d.stride + d.dims[5], pw = (op->OW - 1) * d.stride + d.dims[6];
+                int64_t pr = (rows - 1) * d.stride + d.dilation * (d.dims[5] - 1) + 1, pw = (op->OW - 1) * d.stride + d.dilation * (d.dims[6] - 1) + 1;
                 stage = std::max(stage, (pr * pw * d.dims[3] * es / 4 + p.threads - 1) / p.threads);
             }
             int64_t live = p.cache_read == 3 ? frag + 2 * stage : (p.cache_read >= 2 ? frag + stage : std::max(frag, stage));
@@ -290,7 +291,7 @@ extern "C" int32_t ms_trace_validate(const ms_op *op, const ms_space *space, con
                 int64_t pre = 0;
                 if (p.cache_read == 2) {
                     int64_t rows = bm % op->OW == 0 ? bm / op->OW : (op->OW + bm - 2) / op->OW + 1;
-                    int64_t pr = (rows - 1) * d.stride + d.dims[5], pw = (op->OW - 1) * d.stride + d.dims[6];
+                    int64_t pr = (rows - 1) * d.stride + d.dilation * (d.dims[5] - 1) + 1, pw = (op->OW - 1) * d.stride + d.dilation * (d.dims[6] - 1) + 1;
                     pre = (pr * pw * d.dims[3] * es / 4 + p.threads - 1) / p.threads;
                 }
                 int64_t have = 512 / ((p.waves + 3) / 4);
@@ -464,6 +465,7 @@ int32_t make_kernel_spec(const ms_op *op, const ms_variant_params *p, KernelSpec
             D.push_back(def("CV_OW", op->OW));
             D.push_back(def("CV_STRIDE", d.stride));
             D.push_back(def("CV_PAD", d.pad));
+            D.push_back(def("CV_DIL", d.dilation));
             D.push_back(def("HAS_BIAS", d.has_bias ? 1 : 0));
             D.push_back(def("RELU", d.relu ? 1 : 0));
             // implicit GEMM view: A rows are output pixels, B = W as [K][N]

@@ -160,3 +160,35 @@ def test_conv_persistent_runs_cross_instances():
                 continue
             for r in range(R):
                 assert np.array_equal(got[r], refs[r % 5]), "instance %d trace %d" % (r, n)
+
+
+@pytest.mark.parametrize("stride,pad,k,dil,H,W_", [(1, 2, 3, 2, 16, 16), (2, 2, 3, 2, 16, 32), (1, 3, 2, 3, 13, 16), (1, 4, 3, 4, 16, 16)])
+def test_dilated_conv_exact_for_every_compute_location(stride, pad, k, dil, H, W_):
+    """Dilated conv2d (taps `dil` input elements apart; the paper's DIL workload in small): the im2col loader and
+    all resident-patch modes, batch 2, 2 instances with distinct data, integer-valued inputs, fp32 output: exact."""
+    N, Cin, Cout = 2, 32, 32
+    g = I.rng(29)
+    ins, refs = [], []
+    for r in range(2):
+        X = I.small_ints(g, (N, H, W_, Cin), -2, 2, "f16")
+        Wt = I.small_ints(g, (k, k, Cin, Cout), -2, 2, "f16")
+        bias = g.integers(-3, 4, size=Cout).astype(np.float32)
+        ins.append([X, Wt, bias])
+        refs.append(O.conv2d_nhwc(X, Wt, bias=bias, relu=True, stride=stride, pad=pad, dilation=dil))
+    OH, OW = refs[0].shape[1], refs[0].shape[2]
+    if (N * OH * OW) % 16:
+        pytest.skip("M = %d output pixels is not a multiple of the 16-row intrinsic" % (N * OH * OW))
+    op = B.conv2d_op(N, H, W_, Cin, Cout, k, k, stride=stride, pad=pad, out_dtype="f32", dilation=dil)
+    space = op.space()
+    assert op.loops()[0][1] == N * OH * OW
+    ran = set()
+    for compute_at in (0, 1, 2, 3, 4):
+        for n, t in enumerate(_traces_with_resident_patch(op, space, 4, 2, compute_at)):
+            print("compute_at", compute_at, "trace", n, t.decisions(), flush=True)
+            ran.add(compute_at)
+            got = run_variant_distinct(op, space, t, ins, "f32", (N, OH, OW, Cout))
+            if got is None:
+                continue
+            for r in range(2):
+                assert np.array_equal(got[r], refs[r]), "compute_at %d instance %d trace %d" % (compute_at, r, n)
+    assert {0, 1, 2} <= ran
