@@ -192,3 +192,23 @@ def test_dilated_conv_exact_for_every_compute_location(stride, pad, k, dil, H, W
             for r in range(2):
                 assert np.array_equal(got[r], refs[r]), "compute_at %d instance %d trace %d" % (compute_at, r, n)
     assert {0, 1, 2} <= ran
+
+
+def test_conv_bf16_every_compute_location():
+    """bf16 activations and weights (uint16 bit patterns on the host), fp32 accumulate, bf16 output: the same conv
+    kernels with the bf16 intrinsics; 2 instances."""
+    X, W, bias = I.c3(seed=5, H=28, W=28, Cin=32, Cout=64, dtype="bf16")
+    ref = O.conv2d_nhwc(X, W, bias=bias, relu=True, stride=1, pad=1, bf16=True)
+    op = B.conv2d_op(1, 28, 28, 32, 64, 3, 3, stride=1, pad=1, in_dtype="bf16")
+    space = op.space()
+    ran = set()
+    for compute_at in (0, 1, 2, 3, 4):
+        for n, t in enumerate(_traces_with_resident_patch(op, space, 6, 2, compute_at)):
+            print("compute_at", compute_at, "trace", n, t.decisions(), flush=True)
+            ran.add(compute_at)
+            got = run_variant(op, space, t, [X, W, bias], "bf16", (1, 28, 28, 64), instances=2)
+            if got is None:
+                continue
+            for r in range(2):
+                compare.assert_float_close(got[r], ref, compare.RTOL_HALF, "bf16 conv, compute_at %d trace %d" % (compute_at, n))
+    assert {0, 1, 2} <= ran
