@@ -41,7 +41,7 @@
 #include <omp.h>
 #endif
 
-enum { ORA_F32 = 0, ORA_F16 = 1, ORA_BF16 = 2, ORA_I8 = 3 };
+enum { ORA_F32 = 0, ORA_F16 = 1, ORA_BF16 = 2, ORA_I8 = 3, ORA_F8E4M3 = 5 };
 
 /* IEEE binary16 bit pattern -> double, exact. */
 static double half_bits_to_double(uint16_t h)
@@ -78,6 +78,29 @@ static double bf16_bits_to_double(uint16_t b)
     return (double)f;
 }
 
+/* 8-bit float of the OCP "E4M3" kind (1 sign, 4 exponent bits with bias 7, 3 mantissa bits, no
+ * infinities, the all-ones exponent-and-mantissa pattern is NaN, largest finite value 448) -> double, exact. */
+static double f8e4m3_bits_to_double(uint8_t b)
+{
+    int sign = (b >> 7) & 1;
+    int expo = (b >> 3) & 0xf;
+    int frac = b & 0x7;
+    double v;
+    if (expo == 15 && frac == 7) {
+        v = 0.0 / 0.0;
+    } else if (expo == 0) {
+        v = (double)frac * (1.0 / 512.0); /* frac/8 * 2^-6 (subnormal) */
+    } else {
+        double scale = 1.0;
+        int e = expo - 7;
+        int t;
+        for (t = 0; t < e; ++t) scale *= 2.0;
+        for (t = 0; t > e; --t) scale *= 0.5;
+        v = (1.0 + (double)frac / 8.0) * scale;
+    }
+    return sign ? -v : v;
+}
+
 static double load_elem(int dtype, const void *base, int64_t idx)
 {
     switch (dtype) {
@@ -85,6 +108,7 @@ static double load_elem(int dtype, const void *base, int64_t idx)
     case ORA_F16: return half_bits_to_double(((const uint16_t *)base)[idx]);
     case ORA_BF16: return bf16_bits_to_double(((const uint16_t *)base)[idx]);
     case ORA_I8: return (double)((const int8_t *)base)[idx];
+    case ORA_F8E4M3: return f8e4m3_bits_to_double(((const uint8_t *)base)[idx]);
     default: return 0.0 / 0.0;
     }
 }
@@ -114,7 +138,7 @@ int ms_oracle_bmm(int dtype, int64_t nb, int64_t M, int64_t N, int64_t K,
                   const void *B, int64_t sBb, int64_t sBk, int64_t sBj,
                   double *C)
 {
-    if (dtype != ORA_F32 && dtype != ORA_F16 && dtype != ORA_BF16) return -1;
+    if (dtype != ORA_F32 && dtype != ORA_F16 && dtype != ORA_BF16 && dtype != ORA_F8E4M3) return -1;
     int64_t bi;
 #pragma omp parallel for schedule(static)
     for (bi = 0; bi < nb * M; ++bi) {

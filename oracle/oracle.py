@@ -12,7 +12,7 @@ import numpy as np
 
 from . import build as _build
 
-F32, F16, BF16, I8 = 0, 1, 2, 3
+F32, F16, BF16, I8, F8E4M3 = 0, 1, 2, 3, 5
 
 _lib = None
 
@@ -57,6 +57,8 @@ def _dtype_code(a, bf16=False):
         return BF16
     if a.dtype == np.int8:
         return I8
+    if a.dtype == np.uint8:
+        return F8E4M3  # bit patterns of 8-bit floats (4 exponent bits, 3 mantissa bits)
     raise TypeError("unsupported dtype %s" % a.dtype)
 
 

@@ -367,3 +367,49 @@ def test_full_size_spot_checks():
             assert 0 <= ih < 56 and 0 <= iw < 56
             acc += float(X[0, ih, iw, c]) * float(W[kh, kw, c])
     assert abs(Y[0, oh, ow, c] - acc) < 1e-12
+
+
+# ---------------------------------------------------------------- 8-bit floats
+def test_f8e4m3_decoder_all_256_patterns():
+    """Every bit pattern of the 8-bit float with 4 exponent and 3 mantissa bits (bias 7, no infinities, 0x7f / 0xff NaN):
+    closed forms, and an independent library's decoder."""
+    bits = np.arange(256, dtype=np.uint8)
+    got = O.widen(bits)
+    assert got[0x00] == 0.0 and got[0x80] == 0.0 and np.signbit(got[0x80])
+    assert got[0x38] == 1.0 and got[0x40] == 2.0 and got[0x30] == 0.5 and got[0xB8] == -1.0
+    assert got[0x01] == 2.0 ** -9 and got[0x07] == 7 * 2.0 ** -9 and got[0x08] == 2.0 ** -6   # subnormals, smallest normal
+    assert got[0x7E] == 448.0 and got[0xFE] == -448.0                                          # largest finite
+    assert np.isnan(got[0x7F]) and np.isnan(got[0xFF]) and np.isfinite(np.delete(got, [0x7F, 0xFF])).all()
+    # monotone on the positive half, 8 values per binade
+    pos = got[:0x7F]
+    assert np.all(np.diff(pos) > 0)
+    for e in range(1, 15):
+        assert got[8 * e] == 2.0 ** (e - 7) and got[8 * e + 4] == 1.5 * 2.0 ** (e - 7)
+    torch = pytest.importorskip("torch")
+    if not hasattr(torch, "float8_e4m3fn"):
+        pytest.skip("this torch has no 8-bit float type")
+    want = torch.arange(256, dtype=torch.uint8).view(torch.float8_e4m3fn).double().numpy()
+    assert np.array_equal(np.isnan(got), np.isnan(want))
+    ok = ~np.isnan(got)
+    assert np.array_equal(got[ok], want[ok]) and np.array_equal(np.signbit(got[ok]), np.signbit(want[ok]))
+
+
+def test_f8_gemm_against_decoded_float64_matmul():
+    g = I.rng(21)
+    A = g.integers(0, 256, size=(9, 16), dtype=np.uint8)
+    Bm = g.integers(0, 256, size=(16, 7), dtype=np.uint8)
+    A[(A & 0x7F) == 0x7F] = 0x38                      # no NaN patterns
+    Bm[(Bm & 0x7F) == 0x7F] = 0x38
+    got = O.gemm(A, Bm)
+    want = O.widen(A) @ O.widen(Bm)
+    assert np.allclose(got, want, rtol=1e-13, atol=0)
+    # products and sums of these values are exact in double: brute force in index order agrees bit for bit
+    a, b = O.widen(A), O.widen(Bm)
+    brute = np.zeros((9, 7))
+    for i in range(9):
+        for j in range(7):
+            acc = 0.0
+            for k in range(16):
+                acc += a[i, k] * b[k, j]
+            brute[i, j] = acc
+    assert np.array_equal(got, brute)
