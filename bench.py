@@ -26,7 +26,7 @@ import numpy as np  # noqa: E402
 METRIC = "best-variant TFLOP/s per operator (% of MFMA/HBM roofline); trials to reach it"
 
 # published MI355X peaks: dense MFMA TFLOP/s (TOP/s) by input type, fp32 vector TFLOP/s, HBM GB/s
-PEAK_MFMA = {"f16": 2500.0, "bf16": 2500.0, "i8": 5000.0, "f32": 157.3}
+PEAK_MFMA = {"f16": 2500.0, "bf16": 2500.0, "i8": 5000.0, "f32": 157.3, "f8": 5000.0}
 PEAK_FP32_VECTOR = 157.3
 PEAK_HBM_GBS = 8000.0
 
@@ -36,6 +36,7 @@ def workload_inputs(name, seed):
     return {
         "c1_gemm_f32_128": lambda: list(I.c1(seed)),
         "c2_gemm_f16_1024": lambda: list(I.c2(seed)),
+        "x2_gemm_f8_1024": lambda: list(I.c2(seed, dtype="f8")),
         "c3_conv_f16_56x56x64": lambda: list(I.c3(seed)),
         "c4a_bmm_nt_f16": lambda: list(I.c4a(seed)),
         "c4b_bmm_nn_f16": lambda: list(I.c4b(seed)),
@@ -47,7 +48,7 @@ def workload_inputs(name, seed):
 
 def oracle_run(name, ins):
     from oracle import oracle as O
-    if name in ("c1_gemm_f32_128", "c2_gemm_f16_1024", "c4c_gemm_i8_512"):
+    if name in ("c1_gemm_f32_128", "c2_gemm_f16_1024", "c4c_gemm_i8_512", "x2_gemm_f8_1024"):
         return O.gemm(ins[0], ins[1])
     if name == "c4a_bmm_nt_f16":
         return O.bmm(ins[0], ins[1], trans_b=True)
@@ -63,7 +64,7 @@ def oracle_run(name, ins):
 
 
 OUT_SHAPE = {
-    "c1_gemm_f32_128": ((128, 128), "f32"), "c2_gemm_f16_1024": ((1024, 1024), "f16"),
+    "c1_gemm_f32_128": ((128, 128), "f32"), "c2_gemm_f16_1024": ((1024, 1024), "f16"), "x2_gemm_f8_1024": ((1024, 1024), "f16"),
     "c3_conv_f16_56x56x64": ((1, 56, 56, 64), "f16"), "c4a_bmm_nt_f16": ((12, 128, 128), "f16"),
     "c4b_bmm_nn_f16": ((12, 128, 64), "f16"), "c4c_gemm_i8_512": ((512, 512), "i32"),
     "c5a_dw_f32_112x112x32": ((1, 112, 112, 32), "f32"), "c5b_dw_f32_56x56x144": ((1, 28, 28, 144), "f32"),
@@ -72,6 +73,7 @@ BOUND = {  # which roofline bounds the workload (AI vs ridge), and the in-dtype
     "c1_gemm_f32_128": ("alu", "f32"), "c2_gemm_f16_1024": ("mfma", "f16"), "c3_conv_f16_56x56x64": ("mfma", "f16"),
     "c4a_bmm_nt_f16": ("hbm", "f16"), "c4b_bmm_nn_f16": ("hbm", "f16"), "c4c_gemm_i8_512": ("hbm", "i8"),
     "c5a_dw_f32_112x112x32": ("hbm", "f32"), "c5b_dw_f32_56x56x144": ("hbm", "f32"),
+    "x2_gemm_f8_1024": ("mfma", "f8"),  # beyond the eight configs: config 2 with 8-bit float inputs
 }
 
 

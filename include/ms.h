@@ -73,7 +73,10 @@ typedef enum ms_op_kind {
     MS_OP_DWCONV2D_NHWC = 4  /* depthwise, X NHWC, W [KH][KW][C]            (DEP) */
 } ms_op_kind;
 
-typedef enum ms_dtype { MS_F32 = 0, MS_F16 = 1, MS_BF16 = 2, MS_I8 = 3, MS_I32 = 4 } ms_dtype;
+typedef enum ms_dtype { MS_F32 = 0, MS_F16 = 1, MS_BF16 = 2, MS_I8 = 3, MS_I32 = 4,
+                        MS_F8E4M3 = 5 /* input only, GEMM / BMM on the matrix cores: 8-bit float, 4 exponent bits (bias 7),
+                                         3 mantissa bits, no infinities, 0x7f / 0xff NaN; fp32 accumulate, output F16 or F32 */
+} ms_dtype;
 
 /*
  * dims:

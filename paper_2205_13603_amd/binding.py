@@ -24,7 +24,8 @@ SPACE_DEFAULT = 0xFF
 FAM_GEMM_ALU, FAM_GEMM_MFMA, FAM_DWCONV = range(3)
 MAX_SLOTS, MAX_FACTORS, MAX_CANDS, MAX_LOOPS = 16, 4, 8, 8
 
-DTYPE_NAMES = {"f32": F32, "f16": F16, "bf16": BF16, "i8": I8, "i32": I32}
+F8E4M3 = 5
+DTYPE_NAMES = {"f32": F32, "f16": F16, "bf16": BF16, "i8": I8, "i32": I32, "f8": F8E4M3}
 
 
 class MsError(RuntimeError):

@@ -36,13 +36,14 @@ def main():
         out["lds_read"] = {"bytes_per_clk_per_cu_at_nominal_clock": bpc, "gbs": gbs}
         rnd = (torch.randn(8192, device="cuda") * 0.1)
         ops = {"f16": rnd.half(), "bf16": rnd.bfloat16(), "i8": torch.randint(-128, 128, (8192,), device="cuda", dtype=torch.int8),
-               "f32": torch.rand(8192, device="cuda") * 2 - 1}
+               "f32": torch.rand(8192, device="cuda") * 2 - 1,
+               "f8": rnd.clamp(-448, 448).to(torch.float8_e4m3fn).view(torch.uint8)}
         codes = {"f16": [161616, 323208, 161632, 323216], "bf16": [161616, 323208, 161632, 323216],
-                 "i8": [161632, 323216, 161664, 323232], "f32": [161604, 323202]}
+                 "i8": [161632, 323216, 161664, 323232], "f32": [161604, 323202], "f8": [161632, 323216]}
         t = B.calibrate_timer(1000.0, scratch.data_ptr(), repeats=7)
         out["timer_check"] = {"target_us": 1000.0, "measured_min_us": t.min_us, "measured_median_us": t.median_us}
         out["mfma_tflops"] = {}
-        for dt in ("f16", "bf16", "i8", "f32"):
+        for dt in ("f16", "bf16", "i8", "f32", "f8"):
             for c in codes[dt]:
                 out["mfma_tflops"]["%s_%d" % (dt, c)] = {
                     "small_int_operands": B.calibrate_mfma(dt, c, scratch.data_ptr()),

@@ -50,6 +50,12 @@ __device__ __forceinline__ accv_t mfma(const frag_t &a, const frag_t &b, accv_t 
 #else
     return __builtin_amdgcn_mfma_f32_32x32x16_bf16(*(const b8_t *)&a, *(const b8_t *)&b, c, 0, 0, 0);
 #endif
+#elif IN_DT == DT_F8E4M3
+#if MI_M == 16
+    return __builtin_amdgcn_mfma_f32_16x16x32_fp8_fp8(*(const long *)&a, *(const long *)&b, c, 0, 0, 0);
+#else
+    return __builtin_amdgcn_mfma_f32_32x32x16_fp8_fp8(*(const long *)&a, *(const long *)&b, c, 0, 0, 0);
+#endif
 #elif IN_DT == DT_F32
 #if MI_M == 16
     return __builtin_amdgcn_mfma_f32_16x16x4f32(a.v[0], b.v[0], c, 0, 0, 0);
@@ -80,8 +86,13 @@ extern "C" __global__ void __launch_bounds__(256) ms_calib_kernel(const void *sr
     } else {
 #pragma unroll
         for (int q = 0; q < KP; ++q) {
+#if IN_DT == DT_F8E4M3
+            a.v[q] = (in_t)(((threadIdx.x + q) & 3) ? 0x38 + 8 * ((threadIdx.x + q) & 1) : 0); // 0, 1.0 or 2.0
+            b.v[q] = (in_t)(((threadIdx.x * 3 + q) & 1) ? 0x38 : 0);
+#else
             a.v[q] = (in_t)((threadIdx.x + q) & 3);
             b.v[q] = (in_t)((threadIdx.x * 3 + q) & 1);
+#endif
         }
     }
     accv_t acc[8];

@@ -6,6 +6,7 @@
 #define DT_BF16 2
 #define DT_I8 3
 #define DT_I32 4
+#define DT_F8E4M3 5 // input of the matrix-core kernels only: bit patterns, never converted in software
 
 typedef _Float16 half_t;
 
@@ -15,6 +16,7 @@ template <> struct dt_traits<DT_F16> { typedef half_t type; };
 template <> struct dt_traits<DT_BF16> { typedef unsigned short type; };
 template <> struct dt_traits<DT_I8> { typedef signed char type; };
 template <> struct dt_traits<DT_I32> { typedef int type; };
+template <> struct dt_traits<DT_F8E4M3> { typedef unsigned char type; };
 
 typedef dt_traits<IN_DT>::type in_t;
 typedef dt_traits<OUT_DT>::type out_t;

@@ -152,6 +152,14 @@ __device__ __forceinline__ accv_t mfma(const frag_t &a, const frag_t &b, accv_t 
 #else
 #error "no such int8 intrinsic"
 #endif
+#elif IN_DT == DT_F8E4M3
+#if MI_M == 16 && MI_K == 32
+    return __builtin_amdgcn_mfma_f32_16x16x32_fp8_fp8(*(const long *)&a, *(const long *)&b, c, 0, 0, 0);
+#elif MI_M == 32 && MI_K == 16
+    return __builtin_amdgcn_mfma_f32_32x32x16_fp8_fp8(*(const long *)&a, *(const long *)&b, c, 0, 0, 0);
+#else
+#error "no such 8-bit float intrinsic"
+#endif
 #elif IN_DT == DT_F32
 #if MI_M == 16 && MI_K == 4
     return __builtin_amdgcn_mfma_f32_16x16x4f32(a.v[0], b.v[0], c, 0, 0, 0);
@@ -161,7 +169,7 @@ __device__ __forceinline__ accv_t mfma(const frag_t &a, const frag_t &b, accv_t 
 #error "no such fp32 intrinsic"
 #endif
 #else
-#error "matrix-core kernels take fp16, bf16, int8 or fp32 inputs"
+#error "matrix-core kernels take fp16, bf16, int8, fp8 or fp32 inputs"
 #endif
 }
 

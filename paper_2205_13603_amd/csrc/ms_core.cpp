@@ -73,6 +73,7 @@ int dtype_size(int32_t dt)
     case MS_BF16: return 2;
     case MS_I8: return 1;
     case MS_I32: return 4;
+    case MS_F8E4M3: return 1;
     default: return 0;
     }
 }
@@ -85,6 +86,7 @@ const char *dtype_name(int32_t dt)
     case MS_BF16: return "bf16";
     case MS_I8: return "i8";
     case MS_I32: return "i32";
+    case MS_F8E4M3: return "f8e4m3";
     default: return "?";
     }
 }
@@ -185,11 +187,15 @@ extern "C" int32_t ms_op_create(const ms_op_desc *desc, ms_op **out)
     for (int i = 0; i < ndims; ++i)
         if (d.dims[i] < 1 || d.dims[i] > (int64_t(1) << 30))
             return fail(MS_ERR_BAD_ARG, "ms_op_create: dims[%d] = %" PRId64 " out of range", i, d.dims[i]);
-    if (d.in_dtype < MS_F32 || d.in_dtype > MS_I8)
+    if ((d.in_dtype < MS_F32 || d.in_dtype > MS_I8) && d.in_dtype != MS_F8E4M3)
         return fail(MS_ERR_BAD_ARG, "ms_op_create: bad in_dtype %d", d.in_dtype);
+    if (d.in_dtype == MS_F8E4M3 && d.kind != MS_OP_GEMM && d.kind != MS_OP_BMM_NT && d.kind != MS_OP_BMM_NN)
+        return fail(MS_ERR_UNSUPPORTED, "ms_op_create: 8-bit float inputs are for matrix products only");
     bool out_ok;
     if (d.in_dtype == MS_I8)
         out_ok = d.out_dtype == MS_I32;
+    else if (d.in_dtype == MS_F8E4M3)
+        out_ok = d.out_dtype == MS_F32 || d.out_dtype == MS_F16;
     else
         out_ok = d.out_dtype == MS_F32 || d.out_dtype == d.in_dtype;
     if (!out_ok)
@@ -440,8 +446,9 @@ extern "C" int32_t ms_space_describe(const ms_op *op, uint32_t flags, ms_space *
         static const int64_t f16_list[] = {161616, 323208, 161632, 323216};
         static const int64_t i8_list[] = {161632, 323216, 161664, 323232};
         static const int64_t f32_list[] = {161604, 323202};
-        const int64_t *list = d.in_dtype == MS_I8 ? i8_list : (d.in_dtype == MS_F32 ? f32_list : f16_list);
-        for (int c = 0; c < (d.in_dtype == MS_F32 ? 2 : 4); ++c) {
+        static const int64_t f8_list[] = {161632, 323216};
+        const int64_t *list = d.in_dtype == MS_I8 ? i8_list : (d.in_dtype == MS_F32 ? f32_list : (d.in_dtype == MS_F8E4M3 ? f8_list : f16_list));
+        for (int c = 0; c < (d.in_dtype == MS_F32 || d.in_dtype == MS_F8E4M3 ? 2 : 4); ++c) {
             int m, n, k;
             mfma_dims(list[c], &m, &n, &k);
             if (op->M % m || op->N % n || op->K % k) continue;
@@ -468,12 +475,12 @@ extern "C" int32_t ms_space_describe(const ms_op *op, uint32_t flags, ms_space *
         if (flags & MS_SPACE_UNROLL) add_cat(out, MS_SLOT_UNROLL, "unroll", {0, 16, 64});
         if (flags & MS_SPACE_CACHE_READ) {
             // direct-to-LDS staging (5, 6, 7) exists for 2-byte and 1-byte inputs of plain matrix products
-            if (d.in_dtype != MS_F32 && d.kind != MS_OP_CONV2D_NHWC)
+            if (d.in_dtype != MS_F32 && d.in_dtype != MS_F8E4M3 && d.kind != MS_OP_CONV2D_NHWC)
                 add_cat(out, MS_SLOT_CACHE_READ, "cache_read", {1, 2, 3, 4, 5, 6, 7});
             else add_cat(out, MS_SLOT_CACHE_READ, "cache_read", {1, 2, 3, 4});
         }
         if (flags & MS_SPACE_VECTORIZE) {
-            if (d.in_dtype == MS_I8) {
+            if (d.in_dtype == MS_I8 || d.in_dtype == MS_F8E4M3) {
                 add_cat(out, MS_SLOT_VECTORIZE, "vectorize", {1, 4, 8, 16});
                 add_cat(out, MS_SLOT_VECTORIZE_B, "vectorize_b", {1, 4, 8, 16});
             } else if (d.in_dtype == MS_F32) {
@@ -486,7 +493,7 @@ extern "C" int32_t ms_space_describe(const ms_op *op, uint32_t flags, ms_space *
         }
         if (flags & MS_SPACE_STORAGE_ALIGN) add_cat(out, MS_SLOT_STORAGE_ALIGN, "storage_align", {0, 1, 2});
         if (flags & MS_SPACE_REORDER) {
-            if (d.in_dtype != MS_F32 && d.kind != MS_OP_CONV2D_NHWC) add_cat(out, MS_SLOT_REORDER, "reorder", {0, 1, 2, 3});
+            if (d.in_dtype != MS_F32 && d.in_dtype != MS_F8E4M3 && d.kind != MS_OP_CONV2D_NHWC) add_cat(out, MS_SLOT_REORDER, "reorder", {0, 1, 2, 3});
             else add_cat(out, MS_SLOT_REORDER, "reorder", {0, 1, 2});
         }
         if (flags & MS_SPACE_CACHE_WRITE) add_cat(out, MS_SLOT_CACHE_WRITE, "cache_write", {0, 1});
@@ -497,6 +504,8 @@ extern "C" int32_t ms_space_describe(const ms_op *op, uint32_t flags, ms_space *
     out->flags = flags;
     if (d.kind == MS_OP_CONV2D_NHWC)
         return fail(MS_ERR_UNSUPPORTED, "ms_space_describe: conv2d needs the tensorize module (fp16/bf16 inputs)");
+    if (d.in_dtype == MS_F8E4M3)
+        return fail(MS_ERR_UNSUPPORTED, "ms_space_describe: 8-bit float inputs need the tensorize module");
     out->family = MS_FAM_GEMM_ALU;
     add_tile(out, MS_SLOT_TILE_I, "i", op->M);
     add_tile(out, MS_SLOT_TILE_J, "j", op->N);

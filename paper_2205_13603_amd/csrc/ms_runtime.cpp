@@ -311,8 +311,9 @@ extern "C" int32_t ms_calibrate_mfma(int32_t in_dtype, int32_t mfma_code, const 
     if (!scratch || !tflops) return fail(MS_ERR_BAD_ARG, "ms_calibrate_mfma: NULL argument");
     static const int f16_codes[] = {161616, 323208, 161632, 323216}, i8_codes[] = {161632, 323216, 161664, 323232},
                      f32_codes[] = {161604, 323202, 161604, 323202};
-    const int *codes = in_dtype == MS_I8 ? i8_codes : (in_dtype == MS_F32 ? f32_codes : f16_codes);
-    if (in_dtype != MS_F16 && in_dtype != MS_BF16 && in_dtype != MS_I8 && in_dtype != MS_F32)
+    static const int f8_codes[] = {161632, 323216, 161632, 323216};
+    const int *codes = in_dtype == MS_I8 ? i8_codes : (in_dtype == MS_F32 ? f32_codes : (in_dtype == MS_F8E4M3 ? f8_codes : f16_codes));
+    if (in_dtype != MS_F16 && in_dtype != MS_BF16 && in_dtype != MS_I8 && in_dtype != MS_F32 && in_dtype != MS_F8E4M3)
         return fail(MS_ERR_BAD_ARG, "ms_calibrate_mfma: bad dtype");
     bool ok = false;
     for (int i = 0; i < 4; ++i) ok = ok || codes[i] == mfma_code;

@@ -35,6 +35,14 @@ def bf16_bits_to_f32(b):
     return (np.ascontiguousarray(b, np.uint16).astype(np.uint32) << 16).view(np.float32)
 
 
+def f32_to_f8e4m3_bits(x):
+    """float32 -> bit patterns (uint8) of the 8-bit float with 4 exponent and 3 mantissa bits, round to nearest even,
+    values clipped to the largest finite magnitude 448 first (the conversion routine of torch does the rounding)."""
+    import torch
+    t = torch.from_numpy(np.clip(np.ascontiguousarray(x, np.float32), -448.0, 448.0))
+    return t.to(torch.float8_e4m3fn).view(torch.uint8).numpy().copy()
+
+
 def _cast(x, dtype):
     if dtype == "f32":
         return x.astype(np.float32)
@@ -42,6 +50,8 @@ def _cast(x, dtype):
         return x.astype(np.float32).astype(np.float16)
     if dtype == "bf16":
         return f32_to_bf16_bits(x.astype(np.float32))
+    if dtype == "f8":
+        return f32_to_f8e4m3_bits(x.astype(np.float32))
     raise ValueError(dtype)
 
 

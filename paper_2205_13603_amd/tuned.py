@@ -13,6 +13,7 @@ RECORD_DIR = os.path.join(HERE, "tuned_records")
 WORKLOADS = {
     "c1_gemm_f32_128": (lambda: B.gemm_op(128, 128, 128, "f32"), 4096),
     "c2_gemm_f16_1024": (lambda: B.gemm_op(1024, 1024, 1024, "f16"), 64),
+    "x2_gemm_f8_1024": (lambda: B.gemm_op(1024, 1024, 1024, "f8", "f16"), 64),
     "c3_conv_f16_56x56x64": (lambda: B.conv2d_op(1, 56, 56, 64, 64, 3, 3, stride=1, pad=1), 512),
     "c4a_bmm_nt_f16": (lambda: B.bmm_op(12, 128, 128, 64, True, "f16"), 1024),
     "c4b_bmm_nn_f16": (lambda: B.bmm_op(12, 128, 64, 128, False, "f16"), 1024),

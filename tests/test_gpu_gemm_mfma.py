@@ -282,3 +282,50 @@ def test_fp32_matrix_cores_exact_on_small_ints_odd_tiles():
         if got is None:
             continue
         assert np.array_equal(got[0], ref) and np.array_equal(got[1], ref), "trace %d" % n
+
+
+F8_INTRINS = [161632, 323216]
+
+
+def test_fp8_gemm_exact_on_small_ints_then_random():
+    """8-bit float inputs (4 exponent, 3 mantissa bits) on the fp8 matrix-core intrinsics.  Small integers are exact
+    in this format and all partial sums exact in fp32, so the fp32 output must equal the oracle bit for bit (this also
+    pins the hardware's reading of the bit patterns: exponent bias 7); then normal values with fp16 output within the
+    half-precision tolerance and with fp32 output within the fp8 tolerance (the hardware sums the 32 products of one
+    instruction in less than fp32 precision).  NN and NT forms, 2 instances."""
+    M, N, K = 192, 160, 224
+    A, Bm = I.gemm_inputs(M, N, K, "f8", 3, "ints")
+    ref = O.gemm(A, Bm)
+    op = B.gemm_op(M, N, K, "f8", "f32")
+    space = op.space()
+    assert space.family == B.FAM_GEMM_MFMA
+    for n, t in enumerate(traces_covering_intrinsics(op, space, 12, 3, F8_INTRINS)):
+        print("ints trace", n, t.decisions(), flush=True)
+        got = run_variant(op, space, t, [A, Bm], "f32", (M, N), instances=2)
+        if got is None:
+            continue
+        assert np.array_equal(got[0], ref) and np.array_equal(got[1], ref), "trace %d" % n
+    A, Bm = I.gemm_inputs(M, N, K, "f8", 4, "normal", 1.0)
+    ref = O.gemm(A, Bm)
+    op = B.gemm_op(M, N, K, "f8", "f16")
+    space = op.space()
+    for n, t in enumerate(traces_covering_intrinsics(op, space, 13, 2, F8_INTRINS)):
+        print("normal trace", n, t.decisions(), flush=True)
+        got = run_variant(op, space, t, [A, Bm], "f16", (M, N))
+        if got is None:
+            continue
+        compare.assert_float_close(got, ref, compare.RTOL_HALF, "fp8 trace %d" % n)
+    # NT form with a batch (both operands contiguous along k)
+    Bn, Mh, Nh, Kh = 3, 64, 96, 128
+    g = I.rng(41)
+    Q = I.normal(g, (Bn, Mh, Kh), 1.0, "f8")
+    Kt = I.normal(g, (Bn, Nh, Kh), 1.0, "f8")
+    ref = O.bmm(Q, Kt, trans_b=True)
+    op = B.bmm_op(Bn, Mh, Nh, Kh, True, "f8", "f32")
+    space = op.space()
+    for n, t in enumerate(traces_covering_intrinsics(op, space, 14, 2, F8_INTRINS)):
+        print("NT trace", n, t.decisions(), flush=True)
+        got = run_variant(op, space, t, [Q, Kt], "f32", (Bn, Mh, Nh))
+        if got is None:
+            continue
+        compare.assert_float_close(got, ref, compare.RTOL_F8, "fp8 NT trace %d" % n)
