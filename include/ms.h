@@ -183,8 +183,10 @@ typedef enum ms_slot_id {
 } ms_slot_id;
 
 /* Tensorize candidates: (m, n, k) of one matrix-core instruction.  The code
- * is m*10000 + n*100 + k, e.g. 161616, 323208, 161632, 323216, 161664, 323232; fp32: 161604, 323202. */
-#define MS_MFMA_CODE(m, n, k) ((m) * 10000 + (n) * 100 + (k))
+ * is m*10000 + n*100 + k, e.g. 161616, 323208, 161632, 323216, 161664, 323232; fp32: 161604, 323202.
+ * With k of three digits it is m*100000 + n*1000 + k: 1616128, the 128-deep 8-bit float instruction
+ * (its 32x32 sibling is 323264).  Codes of 1000000 and above are of the second form. */
+#define MS_MFMA_CODE(m, n, k) ((k) >= 100 ? (m) * 100000 + (n) * 1000 + (k) : (m) * 10000 + (n) * 100 + (k))
 #define MS_MFMA_NONE 0
 
 /*
@@ -509,7 +511,7 @@ int32_t ms_device_info_get(ms_device_info *out);
  * ms_calibrate_mfma: register-resident issue loop of one matrix-core
  * intrinsic (in_dtype F16/BF16/I8, MS_MFMA_CODE) on every SIMD; *tflops =
  * 2*m*n*k operations per instruction times instructions per second / 1e12.
- * operands: NULL (small-integer operands), or a device pointer to 8 KiB of
+ * operands: NULL (small-integer operands), or a device pointer to 16 KiB of
  * values of in_dtype from which every lane takes its two fragments (the
  * attainable rate depends on the operand values through power management).
  * scratch: device pointer to at least 4 KiB (never written in practice).

@@ -34,12 +34,12 @@ def main():
         bpc, gbs = B.calibrate_lds(scratch.data_ptr())
         out["l2_read_gbs"] = B.calibrate_l2(src.data_ptr(), scratch.data_ptr())
         out["lds_read"] = {"bytes_per_clk_per_cu_at_nominal_clock": bpc, "gbs": gbs}
-        rnd = (torch.randn(8192, device="cuda") * 0.1)
-        ops = {"f16": rnd.half(), "bf16": rnd.bfloat16(), "i8": torch.randint(-128, 128, (8192,), device="cuda", dtype=torch.int8),
-               "f32": torch.rand(8192, device="cuda") * 2 - 1,
+        rnd = (torch.randn(32768, device="cuda") * 0.1)
+        ops = {"f16": rnd.half(), "bf16": rnd.bfloat16(), "i8": torch.randint(-128, 128, (32768,), device="cuda", dtype=torch.int8),
+               "f32": torch.rand(32768, device="cuda") * 2 - 1,
                "f8": rnd.clamp(-448, 448).to(torch.float8_e4m3fn).view(torch.uint8)}
         codes = {"f16": [161616, 323208, 161632, 323216], "bf16": [161616, 323208, 161632, 323216],
-                 "i8": [161632, 323216, 161664, 323232], "f32": [161604, 323202], "f8": [161632, 323216]}
+                 "i8": [161632, 323216, 161664, 323232], "f32": [161604, 323202], "f8": [161632, 323216, 1616128, 323264]}
         t = B.calibrate_timer(1000.0, scratch.data_ptr(), repeats=7)
         out["timer_check"] = {"target_us": 1000.0, "measured_min_us": t.min_us, "measured_median_us": t.median_us}
         out["mfma_tflops"] = {}

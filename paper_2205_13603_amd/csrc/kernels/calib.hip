@@ -27,6 +27,7 @@ typedef _Float16 h8_t __attribute__((ext_vector_type(8)));
 typedef short s4_t __attribute__((ext_vector_type(4)));
 typedef __bf16 b8_t __attribute__((ext_vector_type(8)));
 typedef int i4_t __attribute__((ext_vector_type(4)));
+typedef int i8_t __attribute__((ext_vector_type(8)));
 
 __device__ __forceinline__ accv_t mfma(const frag_t &a, const frag_t &b, accv_t c)
 {
@@ -51,10 +52,15 @@ __device__ __forceinline__ accv_t mfma(const frag_t &a, const frag_t &b, accv_t 
     return __builtin_amdgcn_mfma_f32_32x32x16_bf16(*(const b8_t *)&a, *(const b8_t *)&b, c, 0, 0, 0);
 #endif
 #elif IN_DT == DT_F8E4M3
-#if MI_M == 16
+#if MI_M == 16 && MI_K == 32
     return __builtin_amdgcn_mfma_f32_16x16x32_fp8_fp8(*(const long *)&a, *(const long *)&b, c, 0, 0, 0);
-#else
+#elif MI_M == 32 && MI_K == 16
     return __builtin_amdgcn_mfma_f32_32x32x16_fp8_fp8(*(const long *)&a, *(const long *)&b, c, 0, 0, 0);
+#elif MI_M == 16 && MI_K == 128
+    // 32 bytes per lane; format selectors 0 = this 8-bit float for both operands, zero scale operands = unscaled form
+    return __builtin_amdgcn_mfma_scale_f32_16x16x128_f8f6f4(*(const i8_t *)&a, *(const i8_t *)&b, c, 0, 0, 0, 0, 0, 0);
+#else
+    return __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(*(const i8_t *)&a, *(const i8_t *)&b, c, 0, 0, 0, 0, 0, 0);
 #endif
 #elif IN_DT == DT_F32
 #if MI_M == 16

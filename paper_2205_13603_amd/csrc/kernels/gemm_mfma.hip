@@ -25,8 +25,9 @@
 //
 // LDS layout of both operands: [k group][row][KP], KP = the k elements one
 // lane feeds to one MFMA.  A lane's fragment is then one 8- or 16-byte LDS
-// read, and the 16 or 32 lanes of a row group read consecutive addresses
-// (no bank conflict).  Operands whose contiguous dimension is not k (B of
+// read (two 16-byte reads from two sub-planes for the 32-byte fragments of
+// the deepest 8-bit float intrinsics), and the 16 or 32 lanes of a row group
+// read consecutive addresses (no bank conflict).  Operands whose contiguous dimension is not k (B of
 // C = A.B, the conv weights) are transposed in registers on the way in.
 //
 // conv2d with COMPUTE_AT 1 (the cache-read of X computed under the workgroup tile loop instead of
@@ -74,9 +75,17 @@ constexpr int BN = J1 * J2 * J3 * MI_N;
 constexpr int BK = K1 * K2 * K3 * MI_K;
 constexpr int KG = BK / KP;                       // k groups per tile
 constexpr int ES = sizeof(in_t);
-constexpr int FRAG_BYTES = KP * ES;               // 8 or 16
-constexpr int PLANE_A = BM * FRAG_BYTES + (LDS_PAD ? 16 : 0); // bytes of one k-group plane
-constexpr int PLANE_B = BN * FRAG_BYTES + (LDS_PAD ? 16 : 0);
+constexpr int FRAG_BYTES = KP * ES;               // a lane's operand of one MFMA: 4, 8, 16 or 32 bytes
+// A 32-byte fragment (the 128-deep and 64-deep 8-bit float intrinsics) lies in LDS as two 16-byte halves in
+// two consecutive sub-planes, so that every LDS access stays one 16-byte instruction with the bank
+// behaviour of the 16-byte layouts.
+constexpr int LSPLIT = FRAG_BYTES > 16 ? FRAG_BYTES / 16 : 1;
+constexpr int KPL = KP / LSPLIT;                  // k elements of one LDS fragment
+constexpr int LFRAG_BYTES = KPL * ES;
+constexpr int SUBPLANE_A = BM * LFRAG_BYTES + (LDS_PAD ? 16 : 0); // bytes of one plane of LDS fragments
+constexpr int SUBPLANE_B = BN * LFRAG_BYTES + (LDS_PAD ? 16 : 0);
+constexpr int PLANE_A = LSPLIT * SUBPLANE_A;      // bytes of one k-group plane (all rows, the KP k elements of one lane group)
+constexpr int PLANE_B = LSPLIT * SUBPLANE_B;
 
 // Slot of row `n` inside a plane (a slot = one fragment).  The swizzle XORs the low 3 bits of the slot
 // with bits 3..5: a thread that writes 8 consecutive slots (the transposed j-contiguous operand) then
@@ -96,10 +105,28 @@ constexpr int STAGES = CACHE_READ >= 2 ? 2 : 1;
 constexpr int KSTEPS = K1 * K2 * K3;              // MFMA k steps per tile
 
 static_assert(MI_M == MI_N, "square intrinsics only");
-static_assert(FRAG_BYTES == 4 || FRAG_BYTES == 8 || FRAG_BYTES == 16, "fragment is 4 (fp32), 8 or 16 bytes");
+static_assert(FRAG_BYTES == 4 || FRAG_BYTES == 8 || FRAG_BYTES == 16 || FRAG_BYTES == 32, "fragment is 4 (fp32), 8, 16 or 32 bytes");
 
 // ---- fragment and accumulator types, one MFMA
 typedef vec_t<in_t, KP> frag_t;
+typedef vec_t<in_t, KPL> lfrag_t;
+
+// a lane's fragment from its LSPLIT LDS fragments, SUB bytes apart
+template <int SUB> __device__ __forceinline__ frag_t lds_frag(const char *__restrict__ p)
+{
+    if constexpr (LSPLIT == 1) {
+        return *reinterpret_cast<const frag_t *>(p);
+    } else {
+        frag_t f;
+#pragma unroll
+        for (int h = 0; h < LSPLIT; ++h) {
+            const lfrag_t part = *reinterpret_cast<const lfrag_t *>(p + h * SUB);
+#pragma unroll
+            for (int q = 0; q < KPL; ++q) f.v[h * KPL + q] = part.v[q];
+        }
+        return f;
+    }
+}
 #if MI_M == 16
 typedef acc_t accv_t __attribute__((ext_vector_type(4)));
 constexpr int ACC_N = 4;
@@ -113,6 +140,7 @@ typedef _Float16 h8_t __attribute__((ext_vector_type(8)));
 typedef short s4_t __attribute__((ext_vector_type(4)));
 typedef __bf16 b8_t __attribute__((ext_vector_type(8)));
 typedef int i4_t __attribute__((ext_vector_type(4)));
+typedef int i8v_t __attribute__((ext_vector_type(8)));
 
 __device__ __forceinline__ accv_t mfma(const frag_t &a, const frag_t &b, accv_t c)
 {
@@ -157,6 +185,12 @@ __device__ __forceinline__ accv_t mfma(const frag_t &a, const frag_t &b, accv_t 
     return __builtin_amdgcn_mfma_f32_16x16x32_fp8_fp8(*(const long *)&a, *(const long *)&b, c, 0, 0, 0);
 #elif MI_M == 32 && MI_K == 16
     return __builtin_amdgcn_mfma_f32_32x32x16_fp8_fp8(*(const long *)&a, *(const long *)&b, c, 0, 0, 0);
+#elif MI_M == 16 && MI_K == 128
+    // the 8/6/4-bit float family: format selectors 0 = this 8-bit float for both operands; zero scale
+    // operands select the unscaled form
+    return __builtin_amdgcn_mfma_scale_f32_16x16x128_f8f6f4(*(const i8v_t *)&a, *(const i8v_t *)&b, c, 0, 0, 0, 0, 0, 0);
+#elif MI_M == 32 && MI_K == 64
+    return __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(*(const i8v_t *)&a, *(const i8v_t *)&b, c, 0, 0, 0, 0, 0, 0);
 #else
 #error "no such 8-bit float intrinsic"
 #endif
@@ -180,8 +214,8 @@ __device__ __forceinline__ accv_t mfma(const frag_t &a, const frag_t &b, accv_t 
 template <int ROWS, int V> struct kmajor_stage {
     static constexpr int VK = V;                          // elements per vector along k
     static constexpr int KV = BK / V;                     // vectors per tile row
-    static constexpr int PARTS = V > KP ? V / KP : 1;     // LDS writes per vector
-    static constexpr int PART_E = V > KP ? KP : V;        // elements per LDS write
+    static constexpr int PARTS = V > KPL ? V / KPL : 1;   // LDS writes per vector
+    static constexpr int PART_E = V > KPL ? KPL : V;      // elements per LDS write
     static constexpr int TOTAL = ROWS * KV;
     static constexpr int ITERS = (TOTAL + NTHREADS - 1) / NTHREADS;
     vec_t<in_t, V> r[ITERS];
@@ -257,7 +291,7 @@ __device__ __forceinline__ void kmajor_store(const kmajor_stage<ROWS, V> &st, ch
 #pragma unroll
             for (int p = 0; p < PARTS; ++p) {
                 const int kk = k + p * PART_E;
-                char *dst = lds + (kk / KP) * PLANE + lds_slot(row) * FRAG_BYTES + (kk % KP) * ES;
+                char *dst = lds + (kk / KPL) * PLANE + lds_slot(row) * LFRAG_BYTES + (kk % KPL) * ES;
                 vec_t<in_t, PART_E> part;
 #pragma unroll
                 for (int q = 0; q < PART_E; ++q) part.v[q] = st.r[it].v[p * PART_E + q];
@@ -268,15 +302,15 @@ __device__ __forceinline__ void kmajor_store(const kmajor_stage<ROWS, V> &st, ch
 }
 
 // J-contiguous operand (B of the NN form, conv weights): a thread moves a
-// block of KP k-rows x VEC_B columns and transposes it in registers, so that it
+// block of KPL k-rows x VEC_B columns and transposes it in registers, so that it
 // lands in LDS as VEC_B consecutive fragments.
 constexpr int VJ = VEC_B;
 constexpr int JV = BN / VJ;
 
 struct jmajor_stage {
-    static constexpr int TOTAL = KG * JV;
+    static constexpr int TOTAL = (BK / KPL) * JV;
     static constexpr int ITERS = (TOTAL + NTHREADS - 1) / NTHREADS;
-    vec_t<in_t, VJ> r[ITERS][KP];
+    vec_t<in_t, VJ> r[ITERS][KPL];
 };
 
 __device__ __forceinline__ void jmajor_load(jmajor_stage &st, const in_t *__restrict__ src, long col0, long k0e, long k_stride, int tid,
@@ -289,15 +323,15 @@ __device__ __forceinline__ void jmajor_load(jmajor_stage &st, const in_t *__rest
         if (S::TOTAL % NTHREADS == 0 || idx < S::TOTAL) {
             const int kg = idx / JV, jv = idx % JV;
 #pragma unroll
-            for (int q = 0; q < KP; ++q) {
-                const int u = it * KP + q;
+            for (int q = 0; q < KPL; ++q) {
+                const int u = it * KPL + q;
                 if (u < u0 || u >= u1) continue;
                 if (NTHREADS % JV == 0) {
-                    const char *ub = (const char *)(src + (k0e + (it * (NTHREADS / JV)) * KP + q) * k_stride + col0);
-                    const unsigned voff = (unsigned)(((tid / JV) * KP * k_stride + (tid % JV) * VJ) * ES);
+                    const char *ub = (const char *)(src + (k0e + (it * (NTHREADS / JV)) * KPL + q) * k_stride + col0);
+                    const unsigned voff = (unsigned)(((tid / JV) * KPL * k_stride + (tid % JV) * VJ) * ES);
                     st.r[it][q] = *reinterpret_cast<const vec_t<in_t, VJ> *>(ub + voff);
                 } else {
-                    st.r[it][q] = *reinterpret_cast<const vec_t<in_t, VJ> *>(src + (k0e + kg * KP + q) * k_stride + col0 + jv * VJ);
+                    st.r[it][q] = *reinterpret_cast<const vec_t<in_t, VJ> *>(src + (k0e + kg * KPL + q) * k_stride + col0 + jv * VJ);
                 }
             }
         }
@@ -316,13 +350,13 @@ __device__ __forceinline__ void jmajor_store(const jmajor_stage &st, char *__res
         if (S::TOTAL % NTHREADS == 0 || idx < S::TOTAL) {
             const int kg = AFFINE ? kg_t + it * (NTHREADS / JV) : idx / JV;
             const int jv = AFFINE ? jv_t : idx % JV;
-            char *dst = lds + kg * PLANE_B;
+            char *dst = lds + kg * SUBPLANE_B;
 #pragma unroll
             for (int c = 0; c < VJ; ++c) {
-                frag_t f;
+                lfrag_t f;
 #pragma unroll
-                for (int q = 0; q < KP; ++q) f.v[q] = st.r[it][q].v[c];
-                *reinterpret_cast<frag_t *>(dst + lds_slot(jv * VJ + c) * FRAG_BYTES) = f;
+                for (int q = 0; q < KPL; ++q) f.v[q] = st.r[it][q].v[c];
+                *reinterpret_cast<lfrag_t *>(dst + lds_slot(jv * VJ + c) * LFRAG_BYTES) = f;
             }
         }
     }
@@ -460,12 +494,12 @@ struct tile_stage {
     static constexpr int UNITS_B = kmajor_stage<BN, VEC_B>::ITERS;
 #else
     jmajor_stage b;
-    static constexpr int UNITS_B = jmajor_stage::ITERS * KP;
+    static constexpr int UNITS_B = jmajor_stage::ITERS * KPL;
 #endif
     static constexpr int UNITS_A = CONV_PATCH ? 0 : kmajor_stage<BM, VEC>::ITERS;
     static constexpr int UNITS = UNITS_A + UNITS_B; // global load instructions per thread and tile
     static constexpr int SUNITS_A = UNITS_A;
-    static constexpr int SUNITS = SUNITS_A + (B_KMAJOR ? UNITS_B : UNITS_B / KP); // store units (one per staged vector / block)
+    static constexpr int SUNITS = SUNITS_A + (B_KMAJOR ? UNITS_B : UNITS_B / KPL); // store units (one per staged vector / block)
 };
 
 // issue load units [u0, u1) of the tile of step k0
@@ -487,10 +521,10 @@ __device__ __forceinline__ void stage_load(tile_stage &st, const in_t *__restric
 __device__ __forceinline__ void stage_store(const tile_stage &st, char *__restrict__ lds, int tid, int u0 = 0, int u1 = tile_stage::SUNITS)
 {
 #if !CONV_PATCH
-    kmajor_store<BM, VEC, PLANE_A>(st.a, lds, tid, u0, u1);
+    kmajor_store<BM, VEC, SUBPLANE_A>(st.a, lds, tid, u0, u1);
 #endif
 #if B_KMAJOR
-    kmajor_store<BN, VEC_B, PLANE_B>(st.b, lds + A_STAGE_BYTES, tid, u0 - tile_stage::SUNITS_A, u1 - tile_stage::SUNITS_A);
+    kmajor_store<BN, VEC_B, SUBPLANE_B>(st.b, lds + A_STAGE_BYTES, tid, u0 - tile_stage::SUNITS_A, u1 - tile_stage::SUNITS_A);
 #else
     jmajor_store(st.b, lds + A_STAGE_BYTES, tid, u0 - tile_stage::SUNITS_A, u1 - tile_stage::SUNITS_A);
 #endif
@@ -514,8 +548,7 @@ __device__ __forceinline__ void read_frags(frag_t (&fa)[K3][TM], frag_t (&fb)[K3
 #pragma unroll
             for (int r3 = 0; r3 < I3; ++r3) {
                 const int trow = (r1 * I2 + wi) * I3 + r3;
-                fa[q][r1 * I3 + r3] =
-                    *reinterpret_cast<const frag_t *>(la + step * LANE_GROUPS * PLANE_A + lds_slot(trow * MI_M + lrow) * FRAG_BYTES);
+                fa[q][r1 * I3 + r3] = lds_frag<SUBPLANE_A>(la + step * LANE_GROUPS * PLANE_A + lds_slot(trow * MI_M + lrow) * LFRAG_BYTES);
             }
 #endif
 #pragma unroll
@@ -523,8 +556,7 @@ __device__ __forceinline__ void read_frags(frag_t (&fa)[K3][TM], frag_t (&fb)[K3
 #pragma unroll
             for (int c3 = 0; c3 < J3; ++c3) {
                 const int tcol = (c1 * J2 + wj) * J3 + c3;
-                fb[q][c1 * J3 + c3] =
-                    *reinterpret_cast<const frag_t *>(lb + step * LANE_GROUPS * PLANE_B + lds_slot(tcol * MI_N + lrow) * FRAG_BYTES);
+                fb[q][c1 * J3 + c3] = lds_frag<SUBPLANE_B>(lb + step * LANE_GROUPS * PLANE_B + lds_slot(tcol * MI_N + lrow) * LFRAG_BYTES);
             }
     }
 }
@@ -621,8 +653,7 @@ __device__ __forceinline__ void weights_to_regs(frag_t (&bw)[NSTEP][TN], const i
 #pragma unroll
                 for (int c3 = 0; c3 < J3; ++c3) {
                     const int tcol = (c1 * J2 + wj) * J3 + c3;
-                    bw[k0 * KSTEPS + q][c1 * J3 + c3] =
-                        *reinterpret_cast<const frag_t *>(lb + q * LANE_GROUPS * PLANE_B + lds_slot(tcol * MI_N + lrow) * FRAG_BYTES);
+                    bw[k0 * KSTEPS + q][c1 * J3 + c3] = lds_frag<SUBPLANE_B>(lb + q * LANE_GROUPS * PLANE_B + lds_slot(tcol * MI_N + lrow) * LFRAG_BYTES);
                 }
     }
 }

@@ -405,13 +405,6 @@ static void add_cat(ms_space *sp, int32_t id, const char *name, std::initializer
     }
 }
 
-static void mfma_dims(int64_t code, int *m, int *n, int *k)
-{
-    *m = int(code / 10000);
-    *n = int(code / 100 % 100);
-    *k = int(code % 100);
-}
-
 extern "C" int32_t ms_space_describe(const ms_op *op, uint32_t flags, ms_space *out)
 {
     if (!op || !out) return fail(MS_ERR_BAD_ARG, "ms_space_describe: NULL argument");
@@ -446,9 +439,9 @@ extern "C" int32_t ms_space_describe(const ms_op *op, uint32_t flags, ms_space *
         static const int64_t f16_list[] = {161616, 323208, 161632, 323216};
         static const int64_t i8_list[] = {161632, 323216, 161664, 323232};
         static const int64_t f32_list[] = {161604, 323202};
-        static const int64_t f8_list[] = {161632, 323216};
+        static const int64_t f8_list[] = {161632, 323216, 1616128, 323264};
         const int64_t *list = d.in_dtype == MS_I8 ? i8_list : (d.in_dtype == MS_F32 ? f32_list : (d.in_dtype == MS_F8E4M3 ? f8_list : f16_list));
-        for (int c = 0; c < (d.in_dtype == MS_F32 || d.in_dtype == MS_F8E4M3 ? 2 : 4); ++c) {
+        for (int c = 0; c < (d.in_dtype == MS_F32 ? 2 : 4); ++c) {
             int m, n, k;
             mfma_dims(list[c], &m, &n, &k);
             if (op->M % m || op->N % n || op->K % k) continue;

@@ -19,6 +19,20 @@ struct ms_op {
 namespace ms {
 
 int32_t fail(int32_t code, const char *fmt, ...) __attribute__((format(printf, 2, 3)));
+
+// (m, n, k) of an MS_MFMA_CODE
+inline void mfma_dims(int64_t code, int *m, int *n, int *k)
+{
+    if (code >= 1000000) {
+        *m = int(code / 100000);
+        *n = int(code / 1000 % 100);
+        *k = int(code % 1000);
+    } else {
+        *m = int(code / 10000);
+        *n = int(code / 100 % 100);
+        *k = int(code % 100);
+    }
+}
 void set_error(const char *fmt, ...) __attribute__((format(printf, 1, 2)));
 
 // 64-bit counter-based generator: integer only, platform independent.

@@ -166,9 +166,7 @@ extern "C" int32_t ms_trace_validate(const ms_op *op, const ms_space *space, con
             p.tile_unit[0] = p.tile_unit[1] = p.tile_unit[2] = 1;
         } else {
             p.mfma = (int32_t)cat_value(space, trace, MS_SLOT_TENSORIZE, 0);
-            p.tile_unit[0] = p.mfma / 10000;
-            p.tile_unit[1] = p.mfma / 100 % 100;
-            p.tile_unit[2] = p.mfma % 100;
+            mfma_dims(p.mfma, &p.tile_unit[0], &p.tile_unit[1], &p.tile_unit[2]);
             if (p.tile_unit[0] != p.tile_unit[1] || (p.tile_unit[0] != 16 && p.tile_unit[0] != 32))
                 return reject("tensorize: unknown intrinsic %d", p.mfma);
         }
@@ -208,7 +206,9 @@ extern "C" int32_t ms_trace_validate(const ms_op *op, const ms_space *space, con
         if (p.mfma) {
             int kp = p.tile_unit[2] / (L.wave_size / p.tile_unit[0]); // k elements one lane feeds per intrinsic
             int64_t padb = p.lds_pad ? 16 : 0;
-            int64_t rowsA = bm * kp * es + padb, rowsB = bn * kp * es + padb;
+            // fragments of more than 16 bytes lie in LDS as 16-byte halves, each in a (padded) plane of its own
+            const int split = kp * es > 16 ? kp * es / 16 : 1;
+            int64_t rowsA = split * (bm * (kp / split) * es + padb), rowsB = split * (bn * (kp / split) * es + padb);
             lds = (int64_t)(p.cache_read >= 2 ? 2 : 1) * (bk / kp) * (rowsA + rowsB);
             if (p.cache_read >= 5) {
                 // direct-to-LDS ring: dense tiles, no padding (the swizzle replaces it)

@@ -178,8 +178,8 @@ extern "C" int32_t ms_variant_features(const ms_op *op, const ms_variant_params 
     const int32_t *tl[4] = {p->ti, p->tj, p->tc, p->tk};
     for (int l = 0; l < 4; ++l)
         for (int k = 0; k < 4; ++k) f.push_back(lg((double)tl[l][k]));
-    f.push_back((double)(p->mfma / 10000));            // intrinsic rows (0 = vector ALU)
-    f.push_back((double)(p->mfma % 100));              // intrinsic k
+    f.push_back((double)(p->mfma ? p->tile_unit[0] : 0)); // intrinsic rows (0 = vector ALU)
+    f.push_back((double)(p->mfma ? p->tile_unit[2] : 0)); // intrinsic k
     f.push_back(lg((double)p->block_m));
     f.push_back(lg((double)p->block_n));
     f.push_back(lg((double)p->block_k));

@@ -311,14 +311,15 @@ extern "C" int32_t ms_calibrate_mfma(int32_t in_dtype, int32_t mfma_code, const 
     if (!scratch || !tflops) return fail(MS_ERR_BAD_ARG, "ms_calibrate_mfma: NULL argument");
     static const int f16_codes[] = {161616, 323208, 161632, 323216}, i8_codes[] = {161632, 323216, 161664, 323232},
                      f32_codes[] = {161604, 323202, 161604, 323202};
-    static const int f8_codes[] = {161632, 323216, 161632, 323216};
+    static const int f8_codes[] = {161632, 323216, 1616128, 323264}; // 1616128: the 16x16x128 intrinsic (three-digit k)
     const int *codes = in_dtype == MS_I8 ? i8_codes : (in_dtype == MS_F32 ? f32_codes : (in_dtype == MS_F8E4M3 ? f8_codes : f16_codes));
     if (in_dtype != MS_F16 && in_dtype != MS_BF16 && in_dtype != MS_I8 && in_dtype != MS_F32 && in_dtype != MS_F8E4M3)
         return fail(MS_ERR_BAD_ARG, "ms_calibrate_mfma: bad dtype");
     bool ok = false;
     for (int i = 0; i < 4; ++i) ok = ok || codes[i] == mfma_code;
     if (!ok) return fail(MS_ERR_BAD_ARG, "ms_calibrate_mfma: no intrinsic %d for %s", mfma_code, dtype_name(in_dtype));
-    int m = mfma_code / 10000, n = mfma_code / 100 % 100, k = mfma_code % 100;
+    int m, n, k;
+    mfma_dims(mfma_code, &m, &n, &k);
     std::vector<std::string> defs = {"-DMODE=0", "-DCAL_DT=" + std::to_string(in_dtype), "-DMI_M=" + std::to_string(m),
                                      "-DMI_N=" + std::to_string(n), "-DMI_K=" + std::to_string(k)};
     CalibKernel ck;

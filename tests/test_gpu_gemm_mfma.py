@@ -329,3 +329,47 @@ def test_fp8_gemm_exact_on_small_ints_then_random():
         if got is None:
             continue
         compare.assert_float_close(got, ref, compare.RTOL_F8, "fp8 NT trace %d" % n)
+
+
+F8_DEEP_INTRINS = [1616128, 323264]
+
+
+def test_fp8_deep_intrinsics_exact_then_random():
+    """The 128-deep (16x16) and 64-deep (32x32) 8-bit float intrinsics: a lane feeds 32 bytes per operand, which lie
+    in LDS as two 16-byte halves.  Small integers: bit-equal to the oracle (any mismatch between the k positions of
+    the two operands, or between the halves, would show); then normal values, NN and NT forms."""
+    M, N, K = 192, 160, 384
+    A, Bm = I.gemm_inputs(M, N, K, "f8", 5, "ints")
+    ref = O.gemm(A, Bm)
+    op = B.gemm_op(M, N, K, "f8", "f32")
+    space = op.space()
+    seen = set()
+    for n, t in enumerate(traces_covering_intrinsics(op, space, 15, 4, F8_DEEP_INTRINS)):
+        print("ints trace", n, t.decisions(), flush=True)
+        got = run_variant(op, space, t, [A, Bm], "f32", (M, N), instances=2)
+        seen.add(B.trace_validate(op, space, t).mfma)
+        if got is None:
+            continue
+        assert np.array_equal(got[0], ref) and np.array_equal(got[1], ref), "trace %d" % n
+    assert seen == set(F8_DEEP_INTRINS)
+    A, Bm = I.gemm_inputs(M, N, K, "f8", 6, "normal", 1.0)
+    ref = O.gemm(A, Bm)
+    for n, t in enumerate(traces_covering_intrinsics(op, space, 16, 2, F8_DEEP_INTRINS)):
+        print("normal trace", n, t.decisions(), flush=True)
+        got = run_variant(op, space, t, [A, Bm], "f32", (M, N))
+        if got is None:
+            continue
+        compare.assert_float_close(got, ref, compare.RTOL_F8, "fp8 deep trace %d" % n)
+    Bn, Mh, Nh, Kh = 3, 64, 96, 256
+    g = I.rng(43)
+    Q = I.normal(g, (Bn, Mh, Kh), 1.0, "f8")
+    Kt = I.normal(g, (Bn, Nh, Kh), 1.0, "f8")
+    ref = O.bmm(Q, Kt, trans_b=True)
+    op = B.bmm_op(Bn, Mh, Nh, Kh, True, "f8", "f32")
+    space = op.space()
+    for n, t in enumerate(traces_covering_intrinsics(op, space, 17, 2, F8_DEEP_INTRINS)):
+        print("NT trace", n, t.decisions(), flush=True)
+        got = run_variant(op, space, t, [Q, Kt], "f32", (Bn, Mh, Nh))
+        if got is None:
+            continue
+        compare.assert_float_close(got, ref, compare.RTOL_F8, "fp8 deep NT trace %d" % n)
