@@ -20,9 +20,18 @@
  *             Xpad[n][oh*s+kh-p][ow*s+kw-p][ci] * W[kh][kw][ci][co])
  *   depthwise conv2d NHWC (Appendix A.2: DEP)
  *       Y[n][oh][ow][c] = sum_{kh,kw} Xpad[n][oh*s+kh-p][ow*s+kw-p][c] * W[kh][kw][c]
+ *   softmax over the last axis (Appendix A.2: SFM, batch x m x n)
+ *       Y[r][j] = exp(X[r][j] - max_j X[r][j]) / sum_j exp(X[r][j] - max_j X[r][j])
+ *   norm (Appendix A.2: NRM, batch x m x n)
+ *       Y[b] = sqrt(sum_{i,j} X[b][i][j]^2)
  *
  * Readings where the paper is silent: cross-correlation (no kernel flip),
  * zero padding, output size floor((H + 2p - KH)/s) + 1, weights HWIO.
+ * The appendix gives only the shapes of SFM and NRM: softmax is taken over
+ * the last axis n of every (batch, m) row, in the shifted form above (equal
+ * to exp(x_j) / sum exp(x_j) in exact arithmetic); the norm is the 2-norm of
+ * all m*n elements of one batch entry (the Frobenius norm of the matrix), one
+ * number per batch entry.
  *
  * Floating point inputs (fp32, fp16, bf16 bit patterns) are widened exactly
  * to double and accumulated in double, in index order.  int8 inputs are
@@ -34,6 +43,7 @@
  * The outermost output loop carries an OpenMP pragma; it changes nothing in
  * the arithmetic of any output element.
  */
+#include <math.h>
 #include <stdint.h>
 #include <stddef.h>
 #include <string.h>
@@ -264,6 +274,45 @@ int ms_oracle_dwconv2d_nhwc(int dtype, int64_t N, int64_t H, int64_t W_, int64_t
                 Y[((n * OH + oh) * OW + ow) * C + c] = acc;
             }
         }
+    }
+    return 0;
+}
+
+/*
+ * Softmax over the last axis: X is dense [rows][n], Y [rows][n] in double.
+ * The maximum is subtracted before exponentiation (exp() of double from libm).
+ */
+int ms_oracle_softmax(int dtype, int64_t rows, int64_t n, const void *X, double *Y)
+{
+    if (dtype != ORA_F32 && dtype != ORA_F16 && dtype != ORA_BF16) return -1;
+    int64_t r;
+#pragma omp parallel for schedule(static)
+    for (r = 0; r < rows; ++r) {
+        double mx = load_elem(dtype, X, r * n);
+        for (int64_t j = 1; j < n; ++j) {
+            double x = load_elem(dtype, X, r * n + j);
+            if (x > mx) mx = x;
+        }
+        double sum = 0.0;
+        for (int64_t j = 0; j < n; ++j) sum += exp(load_elem(dtype, X, r * n + j) - mx);
+        for (int64_t j = 0; j < n; ++j) Y[r * n + j] = exp(load_elem(dtype, X, r * n + j) - mx) / sum;
+    }
+    return 0;
+}
+
+/* 2-norm of each batch entry: X dense [nb][len], Y [nb] in double. */
+int ms_oracle_norm(int dtype, int64_t nb, int64_t len, const void *X, double *Y)
+{
+    if (dtype != ORA_F32 && dtype != ORA_F16 && dtype != ORA_BF16) return -1;
+    int64_t b;
+#pragma omp parallel for schedule(static)
+    for (b = 0; b < nb; ++b) {
+        double acc = 0.0;
+        for (int64_t k = 0; k < len; ++k) {
+            double x = load_elem(dtype, X, b * len + k);
+            acc += x * x;
+        }
+        Y[b] = sqrt(acc);
     }
     return 0;
 }

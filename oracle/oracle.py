@@ -3,7 +3,7 @@
 Every function takes numpy arrays holding the exact bits the GPU path is
 given (fp16 as float16, bf16 as uint16 bit patterns, int8, fp32) and returns
 float64 (int32 for the int8 operator).  Definitions: Appendix A.2 workloads
-GMM, TBG, C2D/CBR, DEP of arXiv 2205.13603, written out in ms_oracle.c.
+GMM, TBG, C2D/CBR, DEP, SFM, NRM of arXiv 2205.13603, written out in ms_oracle.c.
 """
 import ctypes as C
 import os
@@ -36,6 +36,10 @@ def lib():
         L.ms_oracle_conv2d_nhwc.argtypes = [C.c_int] + [i64] * 10 + [vp, vp, vp, C.c_int, vp]
         L.ms_oracle_dwconv2d_nhwc.restype = C.c_int
         L.ms_oracle_dwconv2d_nhwc.argtypes = [C.c_int] + [i64] * 8 + [vp, vp, vp]
+        L.ms_oracle_softmax.restype = C.c_int
+        L.ms_oracle_softmax.argtypes = [C.c_int, i64, i64, vp, vp]
+        L.ms_oracle_norm.restype = C.c_int
+        L.ms_oracle_norm.argtypes = [C.c_int, i64, i64, vp, vp]
         L.ms_oracle_split_walk.restype = i64
         L.ms_oracle_split_walk.argtypes = [C.c_int, vp, vp, i64]
         L.ms_oracle_perfect_tiles.restype = i64
@@ -151,6 +155,27 @@ def dwconv2d_nhwc(X, Wt, stride=1, pad=0, bf16=False):
                                        _ptr(X), _ptr(Wt), _ptr(out))
     if rc != 0:
         raise RuntimeError("oracle dwconv2d failed")
+    return out
+
+
+def softmax(X, bf16=False):
+    """Softmax over the last axis of X (Appendix A.2: SFM); float64, same shape."""
+    X = np.ascontiguousarray(X)
+    n = X.shape[-1]
+    rows = X.size // n
+    out = np.empty(X.shape, np.float64)
+    if lib().ms_oracle_softmax(_dtype_code(X, bf16), rows, n, _ptr(X), _ptr(out)) != 0:
+        raise RuntimeError("oracle softmax failed")
+    return out
+
+
+def norm(X, bf16=False):
+    """2-norm over all but the first axis of X [B, ...] (Appendix A.2: NRM); float64 [B]."""
+    X = np.ascontiguousarray(X)
+    nb = X.shape[0]
+    out = np.empty((nb,), np.float64)
+    if lib().ms_oracle_norm(_dtype_code(X, bf16), nb, X.size // nb, _ptr(X), _ptr(out)) != 0:
+        raise RuntimeError("oracle norm failed")
     return out
 
 

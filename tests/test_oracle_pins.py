@@ -1,7 +1,7 @@
 """Pins of the CPU oracle against facts it does not compute itself:
 the paper's worked example, closed forms, invariants, brute force in pure
 Python, and independent library routines (numpy float64 matmul, torch CPU
-conv2d).  All CPU-only.
+conv2d, scipy's softmax, numpy's norm).  All CPU-only.
 """
 import itertools
 import math
@@ -413,3 +413,55 @@ def test_f8_gemm_against_decoded_float64_matmul():
                 acc += a[i, k] * b[k, j]
             brute[i, j] = acc
     assert np.array_equal(got, brute)
+
+
+# ---------------------------------------------------------------- softmax and norm (Appendix A.2: SFM, NRM)
+
+def test_softmax_closed_forms():
+    n = 7
+    y = O.softmax(np.full((3, n), 2.5, np.float32))
+    assert np.array_equal(y, np.full((3, n), 1.0 / n))                      # uniform row
+    a, b = 0.75, -1.5
+    y = O.softmax(np.array([[a, b]], np.float32))
+    assert abs(y[0, 0] - 1.0 / (1.0 + math.exp(b - a))) < 1e-16            # two elements: the logistic function
+    assert abs(y[0, 1] - 1.0 / (1.0 + math.exp(a - b))) < 1e-16
+    y = O.softmax(np.array([[1000.0, 999.0, -1000.0]], np.float32))         # no overflow, no NaN; the third term vanishes
+    assert abs(y[0, 0] - 1.0 / (1.0 + math.exp(-1.0))) < 1e-15 and y[0, 2] == 0.0
+
+
+def test_softmax_is_over_the_last_axis_and_rows_are_independent():
+    X = np.array([[[0.0, math.log(3.0)], [5.0, 5.0]], [[-2.0, -2.0], [math.log(3.0), 0.0]]], np.float64).astype(np.float32)
+    y = O.softmax(X)
+    assert y.shape == X.shape
+    np.testing.assert_allclose(y[0, 0], [0.25, 0.75], rtol=1e-7)
+    np.testing.assert_allclose(y[1, 1], [0.75, 0.25], rtol=1e-7)
+    assert np.array_equal(y[0, 1], [0.5, 0.5]) and np.array_equal(y[1, 0], [0.5, 0.5])
+
+
+def test_softmax_invariants_and_library():
+    from scipy.special import softmax as sp_softmax
+    g = np.random.default_rng(5)
+    X = g.integers(-8, 9, (6, 33)).astype(np.float32)
+    y = O.softmax(X)
+    assert np.all(y > 0) and np.max(np.abs(y.sum(-1) - 1.0)) < 1e-15
+    np.testing.assert_allclose(O.softmax(X + np.float32(3.0)), y, rtol=1e-15)        # shift invariance (integers: exact shift)
+    i, j = 4, 17
+    np.testing.assert_allclose(y[:, i] / y[:, j], np.exp(X[:, i].astype(np.float64) - X[:, j]), rtol=1e-14)
+    for dt in (np.float32, np.float16):
+        Xr = (g.standard_normal((5, 256)) * 3).astype(dt)
+        np.testing.assert_allclose(O.softmax(Xr), sp_softmax(Xr.astype(np.float64), axis=-1), rtol=1e-13, atol=0)
+    perm = g.permutation(33)
+    np.testing.assert_allclose(O.softmax(np.ascontiguousarray(X[:, perm])), y[:, perm], rtol=1e-14)
+
+
+def test_norm_closed_forms_and_library():
+    assert np.array_equal(O.norm(np.array([[3.0, 4.0, 0.0, 0.0], [5.0, 0.0, -12.0, 0.0]], np.float32)), [5.0, 13.0])
+    assert np.array_equal(O.norm(np.ones((2, 16, 16), np.float16)), [16.0, 16.0])    # sqrt(256 ones)
+    g = np.random.default_rng(6)
+    X = g.standard_normal((3, 40, 50)).astype(np.float32)
+    ref = np.sqrt((X.astype(np.float64) ** 2).reshape(3, -1).sum(-1))
+    np.testing.assert_allclose(O.norm(X), ref, rtol=1e-14)
+    np.testing.assert_allclose(O.norm(X), np.linalg.norm(X.astype(np.float64).reshape(3, -1), axis=1), rtol=1e-14)
+    assert np.array_equal(O.norm(X * np.float32(2.0)), 2.0 * O.norm(X))              # homogeneity (scaling by 2 is exact)
+    assert np.array_equal(O.norm(-X), O.norm(X))
+    assert np.array_equal(O.norm(X[::-1].copy()), O.norm(X)[::-1])                   # one number per batch entry
