@@ -70,7 +70,9 @@ typedef enum ms_op_kind {
     MS_OP_BMM_NT = 1,        /* C[b][i][j] = sum_k A[b][i][k] * B[b][j][k]  (TBG: Q.K^T) */
     MS_OP_BMM_NN = 2,        /* C[b][i][j] = sum_k A[b][i][k] * B[b][k][j] */
     MS_OP_CONV2D_NHWC = 3,   /* Y = act(bias + conv(X, W)), X NHWC, W HWIO  (C2D / CBR) */
-    MS_OP_DWCONV2D_NHWC = 4  /* depthwise, X NHWC, W [KH][KW][C]            (DEP) */
+    MS_OP_DWCONV2D_NHWC = 4, /* depthwise, X NHWC, W [KH][KW][C]            (DEP) */
+    MS_OP_SOFTMAX = 5,       /* Y[b][i][:] = softmax(X[b][i][:]), last axis  (SFM) */
+    MS_OP_NORM = 6           /* Y[b] = sqrt(sum_{i,j} X[b][i][j]^2)          (NRM) */
 } ms_op_kind;
 
 typedef enum ms_dtype { MS_F32 = 0, MS_F16 = 1, MS_BF16 = 2, MS_I8 = 3, MS_I32 = 4,
@@ -84,6 +86,8 @@ typedef enum ms_dtype { MS_F32 = 0, MS_F16 = 1, MS_BF16 = 2, MS_I8 = 3, MS_I32 =
  *   BMM_NT, BMM_NN  B, M, N, K
  *   CONV2D_NHWC     N, H, W, Cin, Cout, KH, KW
  *   DWCONV2D_NHWC   N, H, W, C, KH, KW
+ *   SOFTMAX, NORM   B, M, N   (X dense [B][M][N]; F32, F16 or BF16 in; softmax writes the input dtype or F32,
+ *                              the norm writes F32 [B]; all arithmetic in fp32: max, exp(x - max), sum, scale)
  * Convolutions: cross-correlation, zero padding `pad` on all four sides,
  * output size floor((H + 2*pad - KH)/stride) + 1.  bias is fp32 [Cout], added
  * to the accumulator before ReLU, before the single rounding to out_dtype.
@@ -92,7 +96,7 @@ typedef enum ms_dtype { MS_F32 = 0, MS_F16 = 1, MS_BF16 = 2, MS_I8 = 3, MS_I32 =
  * a_strides / b_strides (GEMM and BMM only; element units; all zero = the
  * dense default of the op kind): A element (b,i,k) at b*a[0] + i*a[1] + k*a[2];
  * B element (b,k,j) at b*b[0] + k*b[1] + j*b[2].
- * Inputs of a launch: GEMM/BMM {A, B}; CONV {X, W, bias or NULL}; DW {X, W}.
+ * Inputs of a launch: GEMM/BMM {A, B}; CONV {X, W, bias or NULL}; DW {X, W}; SOFTMAX/NORM {X}.
  */
 typedef struct ms_op_desc {
     int32_t kind;
@@ -237,7 +241,8 @@ typedef struct ms_slot {
 #define MS_SPACE_DEFAULT 0xffu       /* every module above except the opt-in one; masks with bit 31 set (the
                                          all-ones default of earlier tuning records) mean the same */
 
-typedef enum ms_family { MS_FAM_GEMM_ALU = 0, MS_FAM_GEMM_MFMA = 1, MS_FAM_DWCONV = 2 } ms_family;
+typedef enum ms_family { MS_FAM_GEMM_ALU = 0, MS_FAM_GEMM_MFMA = 1, MS_FAM_DWCONV = 2,
+                         MS_FAM_REDUCE = 3 /* softmax, norm: rows reduced by groups of lanes */ } ms_family;
 
 typedef struct ms_space {
     int32_t family;

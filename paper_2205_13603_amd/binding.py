@@ -12,7 +12,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(HERE, "libms.so")
 
 MS_OK, MS_ERR_BAD_ARG, MS_ERR_INVALID_TRACE, MS_ERR_UNSUPPORTED, MS_ERR_COMPILE, MS_ERR_HIP, MS_ERR_NOMEM = range(7)
-OP_GEMM, OP_BMM_NT, OP_BMM_NN, OP_CONV2D_NHWC, OP_DWCONV2D_NHWC = range(5)
+OP_GEMM, OP_BMM_NT, OP_BMM_NN, OP_CONV2D_NHWC, OP_DWCONV2D_NHWC, OP_SOFTMAX, OP_NORM = range(7)
 F32, F16, BF16, I8, I32 = range(5)
 SLOT_PERFECT_TILE, SLOT_CATEGORICAL = 0, 1
 (SLOT_TENSORIZE, SLOT_TILE_I, SLOT_TILE_J, SLOT_TILE_C, SLOT_TILE_K, SLOT_UNROLL, SLOT_CACHE_READ, SLOT_VECTORIZE,
@@ -21,7 +21,7 @@ SPACE_TENSORIZE, SPACE_CACHE_READ, SPACE_VECTORIZE, SPACE_UNROLL, SPACE_STORAGE_
 SPACE_COMPUTE_AT = 128
 SPACE_TENSORIZE_F32 = 0x100  # opt-in: fp32 operators on the fp32 matrix-core intrinsics
 SPACE_DEFAULT = 0xFF
-FAM_GEMM_ALU, FAM_GEMM_MFMA, FAM_DWCONV = range(3)
+FAM_GEMM_ALU, FAM_GEMM_MFMA, FAM_DWCONV, FAM_REDUCE = range(4)
 MAX_SLOTS, MAX_FACTORS, MAX_CANDS, MAX_LOOPS = 16, 4, 8, 8
 
 F8E4M3 = 5
@@ -275,6 +275,16 @@ def conv2d_op(N, H, W, Cin, Cout, KH, KW, stride=1, pad=0, has_bias=True, relu=T
 
 def dwconv2d_op(N, H, W, Cc, KH=3, KW=3, stride=1, pad=1):
     return Op(OP_DWCONV2D_NHWC, "f32", "f32", [N, H, W, Cc, KH, KW], stride=stride, pad=pad)
+
+
+def softmax_op(B, M, N, in_dtype="f32", out_dtype=None):
+    """Softmax over the last axis of X [B, M, N]."""
+    return Op(OP_SOFTMAX, in_dtype, out_dtype or in_dtype, [B, M, N])
+
+
+def norm_op(B, M, N, in_dtype="f32"):
+    """2-norm of each batch entry of X [B, M, N]; fp32 [B]."""
+    return Op(OP_NORM, in_dtype, "f32", [B, M, N])
 
 
 def space_log10_size(space):

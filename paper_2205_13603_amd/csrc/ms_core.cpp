@@ -99,6 +99,8 @@ const char *op_kind_name(int32_t kind)
     case MS_OP_BMM_NN: return "bmm_nn";
     case MS_OP_CONV2D_NHWC: return "conv2d_nhwc";
     case MS_OP_DWCONV2D_NHWC: return "dwconv2d_nhwc";
+    case MS_OP_SOFTMAX: return "softmax";
+    case MS_OP_NORM: return "norm";
     default: return "?";
     }
 }
@@ -182,6 +184,8 @@ extern "C" int32_t ms_op_create(const ms_op_desc *desc, ms_op **out)
     case MS_OP_BMM_NN: ndims = 4; break;
     case MS_OP_CONV2D_NHWC: ndims = 7; break;
     case MS_OP_DWCONV2D_NHWC: ndims = 6; break;
+    case MS_OP_SOFTMAX:
+    case MS_OP_NORM: ndims = 3; break;
     default: return fail(MS_ERR_BAD_ARG, "ms_op_create: unknown op kind %d", d.kind);
     }
     for (int i = 0; i < ndims; ++i)
@@ -191,8 +195,12 @@ extern "C" int32_t ms_op_create(const ms_op_desc *desc, ms_op **out)
         return fail(MS_ERR_BAD_ARG, "ms_op_create: bad in_dtype %d", d.in_dtype);
     if (d.in_dtype == MS_F8E4M3 && d.kind != MS_OP_GEMM && d.kind != MS_OP_BMM_NT && d.kind != MS_OP_BMM_NN)
         return fail(MS_ERR_UNSUPPORTED, "ms_op_create: 8-bit float inputs are for matrix products only");
+    const bool is_reduce = d.kind == MS_OP_SOFTMAX || d.kind == MS_OP_NORM;
     bool out_ok;
-    if (d.in_dtype == MS_I8)
+    if (is_reduce)
+        out_ok = (d.in_dtype == MS_F32 || d.in_dtype == MS_F16 || d.in_dtype == MS_BF16) &&
+                 (d.out_dtype == MS_F32 || (d.kind == MS_OP_SOFTMAX && d.out_dtype == d.in_dtype));
+    else if (d.in_dtype == MS_I8)
         out_ok = d.out_dtype == MS_I32;
     else if (d.in_dtype == MS_F8E4M3)
         out_ok = d.out_dtype == MS_F32 || d.out_dtype == MS_F16;
@@ -232,6 +240,17 @@ extern "C" int32_t ms_op_create(const ms_op_desc *desc, ms_op **out)
                 return fail(MS_ERR_BAD_ARG, "ms_op_create: negative stride");
         if (d.stride || d.pad || d.has_bias || d.relu || d.dilation)
             return fail(MS_ERR_BAD_ARG, "ms_op_create: stride/pad/bias/relu/dilation only apply to convolutions");
+    } else if (is_reduce) {
+        if (d.stride || d.pad || d.has_bias || d.relu || d.dilation)
+            return fail(MS_ERR_BAD_ARG, "ms_op_create: stride/pad/bias/relu/dilation only apply to convolutions");
+        for (int i = 0; i < 3; ++i)
+            if (d.a_strides[i] || d.b_strides[i]) return fail(MS_ERR_BAD_ARG, "ms_op_create: softmax and norm take dense inputs");
+        // rows that are reduced independently, and their length
+        op.M = d.kind == MS_OP_SOFTMAX ? d.dims[0] * d.dims[1] : d.dims[0];
+        op.K = d.kind == MS_OP_SOFTMAX ? d.dims[2] : d.dims[1] * d.dims[2];
+        op.N = 1;
+        if (op.M > (int64_t(1) << 30) || op.K > (int64_t(1) << 30) || op.M * op.K > (int64_t(1) << 40))
+            return fail(MS_ERR_BAD_ARG, "ms_op_create: tensor too large");
     } else {
         if (d.stride < 1 || d.pad < 0) return fail(MS_ERR_BAD_ARG, "ms_op_create: bad stride/pad");
         int64_t H = d.dims[1], W = d.dims[2];
@@ -306,6 +325,14 @@ extern "C" int32_t ms_op_loops(const ms_op *op, ms_loop *loops, int32_t *n_loops
         set_loop(&loops[n++], "kh", op->d.dims[4], 1);
         set_loop(&loops[n++], "kw", op->d.dims[5], 1);
         break;
+    case MS_OP_SOFTMAX:
+        set_loop(&loops[n++], "i", op->M, 0); // fuse(b, m)
+        set_loop(&loops[n++], "k", op->K, 1); // n: reduced for the maximum and the sum, then revisited for the output
+        break;
+    case MS_OP_NORM:
+        set_loop(&loops[n++], "i", op->M, 0); // b
+        set_loop(&loops[n++], "k", op->K, 1); // fuse(m, n)
+        break;
     }
     *n_loops = n;
     return MS_OK;
@@ -339,6 +366,13 @@ extern "C" int32_t ms_op_tensor_bytes(const ms_op *op, int32_t idx, int64_t *byt
         else if (idx == 0) e = d.dims[0] * d.dims[1] * d.dims[2] * d.dims[3];
         else if (idx == 1) e = d.dims[4] * d.dims[5] * d.dims[3];
         break;
+    case MS_OP_SOFTMAX:
+        if (idx < 0 || idx == 0) e = op->M * op->K;
+        break;
+    case MS_OP_NORM:
+        if (idx < 0) e = op->M;
+        else if (idx == 0) e = op->M * op->K;
+        break;
     }
     if (e < 0) return fail(MS_ERR_BAD_ARG, "ms_op_tensor_bytes: no tensor %d", idx);
     *bytes = e * sz;
@@ -369,6 +403,15 @@ extern "C" int32_t ms_op_work(const ms_op *op, double *flop, double *bytes)
             outs * op->out_size;
         break;
     }
+    case MS_OP_SOFTMAX:
+        // per element: compare, subtract, exponential, add, scale
+        f = 5.0 * op->M * op->K;
+        b = (double)op->M * op->K * (op->in_size + op->out_size);
+        break;
+    case MS_OP_NORM:
+        f = 2.0 * op->M * op->K;
+        b = (double)op->M * op->K * op->in_size + (double)op->M * op->out_size;
+        break;
     }
     *flop = f;
     *bytes = b;
@@ -418,6 +461,17 @@ extern "C" int32_t ms_space_describe(const ms_op *op, uint32_t flags, ms_space *
     if (d.kind == MS_OP_DWCONV2D_NHWC) flags &= ~(MS_SPACE_TENSORIZE | MS_SPACE_VECTORIZE | MS_SPACE_STORAGE_ALIGN | MS_SPACE_CACHE_WRITE);
     if (d.kind != MS_OP_CONV2D_NHWC) flags &= ~MS_SPACE_COMPUTE_AT;
     flags &= 0x1ffu;
+    if (d.kind == MS_OP_SOFTMAX || d.kind == MS_OP_NORM) {
+        // rows i: [workgroups, serial, thread groups, rows of one group at a time]; reduction k: [serial, loads in
+        // flight, lanes of a group (cross-thread reduction), vector]
+        flags &= d.kind == MS_OP_SOFTMAX ? MS_SPACE_CACHE_READ : 0u;
+        out->flags = flags;
+        out->family = MS_FAM_REDUCE;
+        add_tile(out, MS_SLOT_TILE_I, "i", op->M);
+        add_tile(out, MS_SLOT_TILE_K, "k", op->K);
+        if (flags & MS_SPACE_CACHE_READ) add_cat(out, MS_SLOT_CACHE_READ, "cache_read", {0, 1});
+        return MS_OK;
+    }
     out->flags = flags;
     if (d.kind == MS_OP_DWCONV2D_NHWC) {
         out->family = MS_FAM_DWCONV;
@@ -774,7 +828,15 @@ extern "C" int32_t ms_trace_to_text(const ms_op *op, const ms_space *space, cons
             appendf(s, "%s0, %s1, %s2, %s3 = split(loop=%s, factors=[%d, %d, %d, %d])\n", nm[l], nm[l], nm[l], nm[l], nm[l],
                     tl[l][0], tl[l][1], tl[l][2], tl[l][3]);
         }
-        if (p.family == MS_FAM_DWCONV) {
+        if (p.family == MS_FAM_REDUCE) {
+            s += "reorder(i0, i1, i2, i3, k0, k1, k2, k3)\nbind(i0, blockIdx.x)\n";
+            appendf(s, "bind(fuse(i2, k2), threadIdx.x)  # k2: cross-thread reduction over %d lanes (wavefront shuffles%s)\n", p.tk[2],
+                    p.tk[2] > 64 ? ", LDS across wavefronts" : "");
+            appendf(s, "vectorize(k3)\nunroll(k1)\n");
+            if (p.cache_read) appendf(s, "cache-read(buffer=X, scope=registers, compute-at=i3)  # one pass over global memory\n");
+            appendf(s, "# workgroup=%d threads, grid=%d, lds=%d B, values/lane=%d\n", p.threads, p.grid[0] * p.grid[1] * p.grid[2], p.lds_bytes,
+                    p.acc_per_thread);
+        } else if (p.family == MS_FAM_DWCONV) {
             s += "reorder(i0, j0, c0, i1, j1, c1, i2, j2, c2, i3, j3, c3, kh, kw)\n";
             s += "bind(fuse(i0, j0, c0), blockIdx.x)\nbind(fuse(i2, j2, c2), threadIdx.x)\nvectorize(c3)\n";
         } else {
@@ -783,6 +845,9 @@ extern "C" int32_t ms_trace_to_text(const ms_op *op, const ms_space *space, cons
             else appendf(s, "bind(fuse(%s), blockIdx.x)\n", p.reorder == 1 ? "j0, i0" : "i0, j0");
             appendf(s, "bind(fuse(i2, j2), %s)\n", p.mfma ? "wavefront" : "threadIdx.x");
         }
+        if (p.family == MS_FAM_REDUCE) {
+            // everything was said above
+        } else {
         if (p.cache_read) {
             if (p.cache_read >= 5)
                 appendf(s, "cache-read(buffers=[A, B], scope=lds, at=k0, stages=%d, prefetch_distance=%d, direct_to_lds=1)\n", p.cache_read - 3, p.cache_read - 4);
@@ -807,6 +872,7 @@ extern "C" int32_t ms_trace_to_text(const ms_op *op, const ms_space *space, cons
         appendf(s, "unroll(k1, factor=%d)\nunroll(k2, factor=%d)\n", p.unroll_k1, p.unroll_k2);
         appendf(s, "# workgroup=%d threads, grid=%d, lds=%d B, acc/lane=%d\n", p.threads, p.grid[0] * p.grid[1] * p.grid[2], p.lds_bytes,
                 p.acc_per_thread);
+        }
     } else {
         appendf(s, "# invalid: %s\n", ms_last_error());
     }

@@ -394,6 +394,43 @@ extern "C" int32_t ms_trace_validate(const ms_op *op, const ms_space *space, con
         p.tk[2] = (int32_t)d.dims[5];
         p.tk[3] = 1;
         p.unroll_k1 = p.unroll_k2 = p.unroll > 0 ? 0 : 1; // 0 = full unroll of the tap loops
+    } else if (space->family == MS_FAM_REDUCE) {
+        if (!get_tile(space, trace, MS_SLOT_TILE_I, p.ti) || !get_tile(space, trace, MS_SLOT_TILE_K, p.tk))
+            return fail(MS_ERR_BAD_ARG, "ms_trace_validate: the space lacks a tile slot");
+        p.cache_read = (int32_t)cat_value(space, trace, MS_SLOT_CACHE_READ, 0);
+        if (d.kind == MS_OP_NORM) p.cache_read = 0; // a single pass anyway
+        p.tile_unit[0] = p.tile_unit[1] = p.tile_unit[2] = 1;
+        const int es = op->in_size;
+        const int64_t k0 = p.tk[0], k1 = p.tk[1], k2 = p.tk[2], k3 = p.tk[3];
+        if (k3 * es > 16 || (k3 & (k3 - 1))) return reject("vector of %" PRId64 " elements: a load moves 1, 2, 4, ... elements and at most 16 bytes", k3);
+        if (op->out_size * k3 > 16) return reject("vector of %" PRId64 " output elements exceeds 16 bytes", k3);
+        if (k2 > L.max_threads || (k2 & (k2 - 1))) return reject("%" PRId64 " lanes per row: the cross-thread reduction needs a power of two up to %d", k2, L.max_threads);
+        if (d.kind == MS_OP_NORM && k2 < 64 && op->K > 4096)
+            return reject("%" PRId64 " lanes would each sum %" PRId64 " squares in one fp32 chain; at least one wavefront per row", k2, op->K / k2);
+        int64_t threads = (int64_t)p.ti[2] * k2;
+        if (threads > L.max_threads) return reject("%" PRId64 " threads per workgroup, the limit is %d", threads, L.max_threads);
+        if (threads % L.wave_size) return reject("%" PRId64 " threads per workgroup is not a whole number of wavefronts", threads);
+        p.threads = (int32_t)threads;
+        p.waves = p.threads / L.wave_size;
+        if (k1 > 64) return reject("%" PRId64 " loads in flight per lane", k1);
+        // values a lane holds at once: the rows of its group that are processed together, all of the lane's
+        // share of them when the row stays in registers between the passes
+        int64_t live = (int64_t)p.ti[3] * k1 * k3 * (p.cache_read ? k0 : 1);
+        const int budget = std::min(L.max_acc_per_thread, 128); // the loaded vectors and the exponentials are live together
+        if (live > budget) return reject("%" PRId64 " values per lane exceed the register budget %d", live, budget);
+        if (p.cache_read && k0 * k1 > 64) return reject("%" PRId64 " loads per lane and row in a fully unrolled pass", k0 * k1);
+        p.acc_per_thread = (int32_t)live;
+        p.block_m = (int32_t)std::min<int64_t>((int64_t)p.ti[1] * p.ti[2] * p.ti[3], 0x7fffffff);
+        p.block_n = 1;
+        p.block_k = (int32_t)std::min<int64_t>(op->K, 0x7fffffff);
+        p.vec = (int32_t)k3;
+        p.grid[0] = p.ti[0];
+        p.grid[1] = 1;
+        p.grid[2] = 1;
+        // partial results of the wavefronts of a group meet in LDS (maximum and sum use it in turn)
+        p.lds_bytes = k2 > L.wave_size ? (int32_t)(p.waves * p.ti[3] * 4) : 0;
+        p.unroll_k1 = (int32_t)k1;
+        p.unroll_k2 = 1;
     } else {
         return fail(MS_ERR_BAD_ARG, "ms_trace_validate: unknown family %d", space->family);
     }
@@ -500,6 +537,11 @@ int32_t make_kernel_spec(const ms_op *op, const ms_variant_params *p, KernelSpec
         } else {
             k.template_name = "gemm_alu.hip";
         }
+    } else if (p->family == MS_FAM_REDUCE) {
+        k.template_name = "reduce.hip";
+        D.push_back(def("RD_OP", d.kind == MS_OP_NORM ? 1 : 0));
+        D.push_back(def("RD_ROWS", op->M));
+        D.push_back(def("RD_LEN", op->K));
     } else {
         k.template_name = "dwconv.hip";
         D.push_back(def("CV_N", d.dims[0]));
@@ -561,6 +603,27 @@ extern "C" int32_t ms_variant_coverage(const ms_op *op, const ms_variant_params 
                                 }
                 }
             }
+    } else if (p->family == MS_FAM_REDUCE) {
+        const bool per_element = op->d.kind == MS_OP_SOFTMAX;
+        for (int64_t wg = 0; wg < p->grid[0]; ++wg)
+            for (int64_t r1 = 0; r1 < p->ti[1]; ++r1)
+                for (int64_t g = 0; g < p->ti[2]; ++g)
+                    for (int64_t r3 = 0; r3 < p->ti[3]; ++r3) {
+                        int64_t row = split_index(p->ti, wg, r1, g, r3);
+                        if (row >= op->M) return fail(MS_ERR_INVALID_TRACE, "coverage: index out of range");
+                        if (!per_element) {
+                            ++counts[row];
+                            continue;
+                        }
+                        for (int64_t q0 = 0; q0 < p->tk[0]; ++q0)
+                            for (int64_t q1 = 0; q1 < p->tk[1]; ++q1)
+                                for (int64_t t = 0; t < p->tk[2]; ++t)
+                                    for (int64_t q3 = 0; q3 < p->tk[3]; ++q3) {
+                                        int64_t k = split_index(p->tk, q0, q1, t, q3);
+                                        if (k >= op->K) return fail(MS_ERR_INVALID_TRACE, "coverage: index out of range");
+                                        ++counts[row * op->K + k];
+                                    }
+                    }
     } else {
         const ms_op_desc &d = op->d;
         int64_t C = d.dims[3];

@@ -123,13 +123,14 @@ extern "C" int32_t ms_variant_launch(ms_variant *v, const void *const *inputs, v
     (void)workspace;
     if (!v || !inputs || !outputs) return fail(MS_ERR_BAD_ARG, "ms_variant_launch: NULL argument");
     if (instances < 1) return fail(MS_ERR_BAD_ARG, "ms_variant_launch: instances = %d", instances);
-    if (!inputs[0] || !inputs[1] || !outputs[0]) return fail(MS_ERR_BAD_ARG, "ms_variant_launch: NULL tensor pointer");
+    const bool one_input = v->p.family == MS_FAM_REDUCE;
+    if (!inputs[0] || (!one_input && !inputs[1]) || !outputs[0]) return fail(MS_ERR_BAD_ARG, "ms_variant_launch: NULL tensor pointer");
     uint64_t gz = (uint64_t)v->spec.grid[2] * (uint64_t)instances;
     if (gz > 65535ull * 32768ull || (uint64_t)v->spec.grid[0] * gz > 0x7fffffffull)
         return fail(MS_ERR_BAD_ARG, "ms_variant_launch: %d instances overflow the grid", instances);
     int32_t rc = ensure_loaded(v);
     if (rc != MS_OK) return rc;
-    const void *in0 = inputs[0], *in1 = inputs[1];
+    const void *in0 = inputs[0], *in1 = one_input ? nullptr : inputs[1];
     const void *in2 = nullptr;
     if (v->op.d.kind == MS_OP_CONV2D_NHWC && v->op.d.has_bias) {
         in2 = inputs[2];

@@ -377,3 +377,68 @@ def test_interpreter_covers_every_output_once(mk):
         p = B.trace_validate(op, sp, t)
         cov = B.variant_coverage(op, p, elems)
         assert cov.min() == 1 and cov.max() == 1, t.decisions()
+
+
+# ---------------------------------------------------------------- softmax / norm (row reductions)
+
+def test_reduce_ops_descriptor_loops_and_work():
+    op = B.softmax_op(2, 48, 96, "f16")
+    assert op.loops() == [("i", 96, False), ("k", 96, True)]
+    assert op.tensor_bytes(0) == 2 * 48 * 96 * 2 and op.tensor_bytes(-1) == 2 * 48 * 96 * 2
+    assert op.work()[1] == 2 * 48 * 96 * 4
+    op = B.norm_op(3, 16, 20, "bf16")
+    assert op.loops() == [("i", 3, False), ("k", 320, True)]
+    assert op.tensor_bytes(0) == 3 * 320 * 2 and op.tensor_bytes(-1) == 3 * 4
+    assert op.work() == (2.0 * 3 * 320, 3 * 320 * 2 + 12.0)
+    with pytest.raises(B.MsError):
+        B.Op(B.OP_NORM, "f32", "f16", [1, 4, 4])       # the norm is written in fp32
+    with pytest.raises(B.MsError):
+        B.Op(B.OP_SOFTMAX, "i8", "i32", [1, 4, 4])
+    with pytest.raises(B.MsError):
+        B.Op(B.OP_SOFTMAX, "f32", "f32", [1, 4, 4], stride=1)
+
+
+def test_reduce_space_coverage_and_text_round_trip():
+    for op, elems in ((B.softmax_op(1, 256, 256), 65536), (B.softmax_op(3, 20, 96, "f16"), 5760), (B.norm_op(6, 32, 24), 6)):
+        sp = op.space()
+        assert sp.family == B.FAM_REDUCE
+        names = [sp.slots[i].name.decode() for i in range(sp.n_slots)]
+        assert names[:2] == ["i", "k"] and (names[2:] == ["cache_read"]) == (elems != 6)
+        for idx in range(20):
+            t = B.trace_sample_valid(op, sp, 33, idx)
+            p = B.trace_validate(op, sp, t)
+            assert p.threads == p.ti[2] * p.tk[2] and p.threads % 64 == 0 and p.grid[0] == p.ti[0]
+            cov = B.variant_coverage(op, p, elems)
+            assert cov.min() == 1 and cov.max() == 1, t.decisions()
+            text = B.trace_to_text(op, sp, t)
+            assert "cross-thread reduction over %d lanes" % p.tk[2] in text
+            assert B.trace_from_text(sp, text).decisions() == t.decisions()
+    # without the cache-read module the softmax space has only the two tile slots
+    assert B.softmax_op(1, 8, 64).space(0).n_slots == 2
+
+
+def test_reduce_validator_rejections():
+    op = B.softmax_op(1, 64, 256)
+    sp = op.space()
+
+    def why(vals):
+        with pytest.raises(B.MsError) as e:
+            B.trace_validate(op, sp, B.make_trace(sp, vals))
+        assert e.value.code == B.MS_ERR_INVALID_TRACE
+        return str(e.value)
+
+    assert "at most 16 bytes" in why([[1, 1, 64, 1], [1, 1, 32, 8], [0]])
+    assert "power of two" not in why([[1, 1, 64, 1], [1, 1, 32, 8], [0]])
+    assert "whole number of wavefronts" in why([[32, 1, 2, 1], [4, 4, 16, 1], [0]])
+    assert "threads per workgroup" in why([[1, 1, 64, 1], [2, 1, 32, 4], [0]])
+    assert "register budget" in why([[1, 1, 8, 8], [8, 4, 8, 1], [1]])
+    op3 = B.softmax_op(1, 64, 96)
+    sp3 = op3.space()
+    with pytest.raises(B.MsError) as e:
+        B.trace_validate(op3, sp3, B.make_trace(sp3, [[1, 1, 64, 1], [1, 8, 12, 1], [0]]))
+    assert "power of two" in str(e.value)
+    opn = B.norm_op(1, 256, 256)
+    spn = opn.space()
+    with pytest.raises(B.MsError) as e:
+        B.trace_validate(opn, spn, B.make_trace(spn, [[1, 1, 1, 1], [512, 2, 16, 4]]))
+    assert "one wavefront per row" in str(e.value)
