@@ -43,6 +43,8 @@ def workload_inputs(name, seed):
         "c4c_gemm_i8_512": lambda: list(I.c4c(seed)),
         "c5a_dw_f32_112x112x32": lambda: list(I.c5a(seed)),
         "c5b_dw_f32_56x56x144": lambda: list(I.c5b(seed)),
+        "x3_softmax_f32_256x256": lambda: list(I.sfm(seed)),
+        "x4_norm_f32_256x256": lambda: list(I.nrm(seed)),
     }[name]()
 
 
@@ -60,6 +62,10 @@ def oracle_run(name, ins):
         return O.dwconv2d_nhwc(ins[0], ins[1], stride=1, pad=1)
     if name == "c5b_dw_f32_56x56x144":
         return O.dwconv2d_nhwc(ins[0], ins[1], stride=2, pad=1)
+    if name == "x3_softmax_f32_256x256":
+        return O.softmax(ins[0])
+    if name == "x4_norm_f32_256x256":
+        return O.norm(ins[0])
     raise KeyError(name)
 
 
@@ -68,12 +74,14 @@ OUT_SHAPE = {
     "c3_conv_f16_56x56x64": ((1, 56, 56, 64), "f16"), "c4a_bmm_nt_f16": ((12, 128, 128), "f16"),
     "c4b_bmm_nn_f16": ((12, 128, 64), "f16"), "c4c_gemm_i8_512": ((512, 512), "i32"),
     "c5a_dw_f32_112x112x32": ((1, 112, 112, 32), "f32"), "c5b_dw_f32_56x56x144": ((1, 28, 28, 144), "f32"),
+    "x3_softmax_f32_256x256": ((1, 256, 256), "f32"), "x4_norm_f32_256x256": ((1,), "f32"),
 }
 BOUND = {  # which roofline bounds the workload (AI vs ridge), and the in-dtype
     "c1_gemm_f32_128": ("alu", "f32"), "c2_gemm_f16_1024": ("mfma", "f16"), "c3_conv_f16_56x56x64": ("mfma", "f16"),
     "c4a_bmm_nt_f16": ("hbm", "f16"), "c4b_bmm_nn_f16": ("hbm", "f16"), "c4c_gemm_i8_512": ("hbm", "i8"),
     "c5a_dw_f32_112x112x32": ("hbm", "f32"), "c5b_dw_f32_56x56x144": ("hbm", "f32"),
     "x2_gemm_f8_1024": ("mfma", "f8"),  # beyond the eight configs: config 2 with 8-bit float inputs
+    "x3_softmax_f32_256x256": ("hbm", "f32"), "x4_norm_f32_256x256": ("hbm", "f32"),  # row reductions
 }
 
 
@@ -241,7 +249,7 @@ def main():
             nb = 1 << 30
             src = torch.ones(nb, dtype=torch.uint8, device="cuda")
             dst = torch.empty(nb, dtype=torch.uint8, device="cuda")
-            attainable = B.calibrate_stream(1, src.data_ptr(), dst.data_ptr(), nb, stream=stream)
+            attainable = max(B.calibrate_stream(m, src.data_ptr(), dst.data_ptr(), nb, stream=stream) for m in (1, 4))
             del src, dst
     except B.MsError as e:
         print("calibration failed: %s" % str(e)[:200], file=sys.stderr)
@@ -276,7 +284,7 @@ def main():
                      "traffic": traffic, "kernel_us": kernel_us,
                      "attainable": attainable, "frac_of_attainable": (achieved / attainable) if attainable else None,
                      "attainable_kind": {"mfma": "register-resident loop of the variant's intrinsic on this workload's operand values",
-                                         "hbm": "1 GiB copy kernel, bytes read + written"}.get(bound) if attainable else None},
+                                         "hbm": "1 GiB copy kernel (the faster of two launch shapes), bytes read + written"}.get(bound) if attainable else None},
         "single_instance": {"single_launch_us": l1.median_us, "steady_state_us": l2.median_us,
                             "steady_state_" + ("gbs" if bound == "hbm" else "tflops"): per1 / (l2.median_us * 1e-6),
                             "rotating_sets": R},

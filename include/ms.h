@@ -521,7 +521,8 @@ int32_t ms_device_info_get(ms_device_info *out);
  * attainable rate depends on the operand values through power management).
  * scratch: device pointer to at least 4 KiB (never written in practice).
  * ms_calibrate_stream: mode 1 copies `bytes` from src to dst, mode 2 only
- * reads src, mode 3 only writes dst; bytes must be a multiple of 4096; device pointers, 16-byte
+ * reads src, mode 3 only writes dst, mode 4 copies like mode 1 but with one 64-lane workgroup per KiB (the launch
+ * shape of the bandwidth-bound operator kernels; the fastest copy found on this device); bytes must be a multiple of 4096; device pointers, 16-byte
  * aligned; *gbs = bytes moved (copy: read + written) per second / 1e9.
  * Both synchronise `stream`.
  */

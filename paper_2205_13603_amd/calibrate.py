@@ -28,7 +28,8 @@ def main():
     dst = torch.empty(n, dtype=torch.uint8, device="cuda")
     out["stream"] = {"bytes": n, "copy_gbs_read_plus_write": B.calibrate_stream(1, src.data_ptr(), dst.data_ptr(), n),
                      "read_gbs": B.calibrate_stream(2, src.data_ptr(), dst.data_ptr(), n),
-                     "write_gbs": B.calibrate_stream(3, src.data_ptr(), dst.data_ptr(), n)}
+                     "write_gbs": B.calibrate_stream(3, src.data_ptr(), dst.data_ptr(), n),
+                     "copy_small_chunks_gbs": B.calibrate_stream(4, src.data_ptr(), dst.data_ptr(), n)}
     if not args.quick:
         scratch = torch.zeros(1 << 16, dtype=torch.float32, device="cuda")
         bpc, gbs = B.calibrate_lds(scratch.data_ptr())

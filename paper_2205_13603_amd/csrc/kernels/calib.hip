@@ -4,6 +4,8 @@
 //   MODE 1: copy `n16` 16-byte words src -> dst, one contiguous range per workgroup
 //   MODE 2: read `n16` 16-byte words (sum folded into a value that is stored only if it hits a sentinel)
 //   MODE 6: write `n16` 16-byte words to dst
+//   MODE 7: copy `n16` 16-byte words, 1 KiB per workgroup of 64 lanes (the launch shape of the bandwidth-bound operator
+//           kernels: many small workgroups, all loads of a lane issued first)
 //   MODE 5: one wavefront waits until the constant-rate wall clock has advanced by `ticks` (a kernel of known
 //           duration: checks the event timing that every measurement here relies on)
 #define IN_DT CAL_DT
@@ -165,11 +167,29 @@ extern "C" __global__ void __launch_bounds__(256) ms_calib_kernel(const void *sr
 #pragma unroll
         for (int t = 0; t < 8; ++t) {
             w16_t x = s[i];
-            acc += x.v[0] + x.v[3];
+            acc += (x.v[0] + x.v[1]) + (x.v[2] + x.v[3]); // every word is used: a load whose middle words are dead gets split into narrower loads
             i = (i + 256 * 61) % WORDS;
         }
     }
     if (acc == -12345.678f) ((float *)dst)[threadIdx.x] = acc;
+}
+#elif MODE == 7
+// 1 KiB per workgroup of 64 lanes, two 8-byte words per lane, all loads before the stores: the fastest of the shapes
+// tried (workgroups of 64-1024 lanes, 1-64 KiB per workgroup, 8- and 16-byte words)
+typedef vec_t<float, 2> w8_t;
+extern "C" __global__ void __launch_bounds__(64) ms_calib_kernel(const void *src, const void *, const void *, void *dst, int n16_lo)
+{
+    const long n8 = (long)(unsigned)n16_lo * 512; // the host passes the number of 16-byte words / 256
+    const w8_t *s = (const w8_t *)src;
+    w8_t *d = (w8_t *)dst;
+    const long base = (long)blockIdx.x * 128 + threadIdx.x;
+    w8_t x[2];
+#pragma unroll
+    for (int u = 0; u < 2; ++u)
+        if (base + u * 64 < n8) x[u] = s[base + u * 64];
+#pragma unroll
+    for (int u = 0; u < 2; ++u)
+        if (base + u * 64 < n8) d[base + u * 64] = x[u];
 }
 #else
 typedef vec_t<float, 4> w16_t;

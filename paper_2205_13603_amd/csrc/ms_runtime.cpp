@@ -282,7 +282,7 @@ int32_t load_calib(const std::vector<std::string> &defs, uint64_t key, CalibKern
     return MS_OK;
 }
 
-int32_t time_launches(hipFunction_t fn, unsigned grid, void **args, hipStream_t s, int reps, double *best_ms)
+int32_t time_launches(hipFunction_t fn, unsigned grid, void **args, hipStream_t s, int reps, double *best_ms, unsigned block = 256)
 {
     hipEvent_t e0, e1;
     HIP_TRY(hipEventCreate(&e0));
@@ -291,7 +291,7 @@ int32_t time_launches(hipFunction_t fn, unsigned grid, void **args, hipStream_t 
     int32_t rc = MS_OK;
     for (int r = 0; r < reps + 1 && rc == MS_OK; ++r) { // first repeat is the warm-up
         hipError_t e = hipEventRecord(e0, s);
-        if (e == hipSuccess) e = hipModuleLaunchKernel(fn, grid, 1, 1, 256, 1, 1, 0, s, args, nullptr);
+        if (e == hipSuccess) e = hipModuleLaunchKernel(fn, grid, 1, 1, block, 1, 1, 0, s, args, nullptr);
         if (e == hipSuccess) e = hipEventRecord(e1, s);
         if (e == hipSuccess) e = hipEventSynchronize(e1);
         float ms_el = 0;
@@ -346,10 +346,10 @@ extern "C" int32_t ms_calibrate_mfma(int32_t in_dtype, int32_t mfma_code, const 
 extern "C" int32_t ms_calibrate_stream(int32_t mode, const void *src, void *dst, size_t bytes, void *stream, double *gbs)
 {
     if (!src || !dst || !gbs) return fail(MS_ERR_BAD_ARG, "ms_calibrate_stream: NULL argument");
-    if ((mode != 1 && mode != 2 && mode != 3) || bytes == 0 || bytes % 4096 || bytes / 4096 > 0x7fffffffull)
-        return fail(MS_ERR_BAD_ARG, "ms_calibrate_stream: mode must be 1, 2 or 3 and bytes a multiple of 4096");
-    // kernel modes: 1 copy, 2 read, 6 write (3, 4, 5 are the LDS, L2 and timer kernels)
-    std::vector<std::string> defs = {"-DMODE=" + std::to_string(mode == 3 ? 6 : mode), "-DCAL_DT=0"};
+    if (mode < 1 || mode > 4 || bytes == 0 || bytes % 4096 || bytes / 4096 > 0x7fffffffull)
+        return fail(MS_ERR_BAD_ARG, "ms_calibrate_stream: mode must be 1, 2, 3 or 4 and bytes a multiple of 4096");
+    // kernel modes: 1 copy, 2 read, 6 write, 7 copy in small chunks (3, 4, 5 are the LDS, L2 and timer kernels)
+    std::vector<std::string> defs = {"-DMODE=" + std::to_string(mode == 3 ? 6 : (mode == 4 ? 7 : mode)), "-DCAL_DT=0"};
     CalibKernel ck;
     int32_t rc = load_calib(defs, mix64(0xCA11B1ull ^ (uint64_t)mode), &ck);
     if (rc != MS_OK) return rc;
@@ -359,12 +359,13 @@ extern "C" int32_t ms_calibrate_stream(int32_t mode, const void *src, void *dst,
     HIP_TRY(hipGetDeviceProperties(&prop, dev));
     unsigned grid = (unsigned)prop.multiProcessorCount * 16;
     int n16_by_256 = (int)(bytes / 4096);
+    if (mode == 4) grid = (unsigned)(bytes / 1024); // one 64-lane workgroup per KiB
     void *args[] = {&src, &src, &src, &dst, &n16_by_256};
     double ms_best = 0;
-    rc = time_launches(ck.fn, grid, args, (hipStream_t)stream, 5, &ms_best);
+    rc = time_launches(ck.fn, grid, args, (hipStream_t)stream, 5, &ms_best, mode == 4 ? 64u : 256u);
     (void)hipModuleUnload(ck.mod);
     if (rc != MS_OK) return rc;
-    *gbs = (double)bytes * (mode == 1 ? 2.0 : 1.0) / (ms_best * 1e-3) / 1e9;
+    *gbs = (double)bytes * (mode == 1 || mode == 4 ? 2.0 : 1.0) / (ms_best * 1e-3) / 1e9;
     return MS_OK;
 }
 

@@ -128,3 +128,13 @@ def c5a(seed=0):
 
 def c5b(seed=0):
     return dw_inputs(1, 56, 56, 144, seed=seed)
+
+
+def sfm(seed=0, B=1, M=256, N=256, dtype="f32"):
+    """Softmax workload (batch 1, 256 x 256): logits with standard deviation 2."""
+    return (normal(rng(seed), (B, M, N), 2.0, dtype),)
+
+
+def nrm(seed=0, B=1, M=256, N=256, dtype="f32"):
+    """Norm workload (batch 1, 256 x 256): standard normal values."""
+    return (normal(rng(seed), (B, M, N), 1.0, dtype),)
