@@ -222,6 +222,12 @@ template <int ROWS, int V> struct kmajor_stage {
 };
 
 #if IS_CONV
+// A reduction extent KH*KW*Cin that is no multiple of the intrinsic's k is rounded up: the loaders of both operands
+// deliver zeros for k >= KH*KW*Cin (im2col staging only)
+constexpr int CV_KREAL = CV_KH * CV_KW * CV_CIN;
+constexpr bool K_PADDED = K0 * BK != CV_KREAL;
+static_assert(K0 * BK >= CV_KREAL && K0 * BK - CV_KREAL < MI_K, "the k split covers the reduction, padded by less than one intrinsic");
+static_assert(!K_PADDED || COMPUTE_AT == 0, "a padded reduction needs the im2col loader");
 // im2col on the fly: row = output pixel, k = (kh, kw, ci)
 template <int V> __device__ __forceinline__ vec_t<in_t, V> load_conv_a(const in_t *__restrict__ X, int row, int k)
 {
@@ -229,7 +235,7 @@ template <int V> __device__ __forceinline__ vec_t<in_t, V> load_conv_a(const in_
     const int ci = k % CV_CIN, kw = (k / CV_CIN) % CV_KW, kh = k / (CV_CIN * CV_KW);
     const int ih = oh * CV_STRIDE + kh * CV_DIL - CV_PAD, iw = ow * CV_STRIDE + kw * CV_DIL - CV_PAD;
     vec_t<in_t, V> x;
-    if (ih >= 0 && ih < CV_H && iw >= 0 && iw < CV_W) {
+    if (ih >= 0 && ih < CV_H && iw >= 0 && iw < CV_W && (!K_PADDED || k < CV_KREAL)) {
         x = *reinterpret_cast<const vec_t<in_t, V> *>(X + (((long)n * CV_H + ih) * CV_W + iw) * CV_CIN + ci);
     } else {
 #pragma unroll
@@ -326,6 +332,13 @@ __device__ __forceinline__ void jmajor_load(jmajor_stage &st, const in_t *__rest
             for (int q = 0; q < KPL; ++q) {
                 const int u = it * KPL + q;
                 if (u < u0 || u >= u1) continue;
+#if IS_CONV
+                if (K_PADDED && k0e + kg * KPL + q >= CV_KREAL) { // rows of the padding: zeros, nothing is read
+#pragma unroll
+                    for (int c = 0; c < VJ; ++c) st.r[it][q].v[c] = 0;
+                    continue;
+                }
+#endif
                 if (NTHREADS % JV == 0) {
                     const char *ub = (const char *)(src + (k0e + (it * (NTHREADS / JV)) * KPL + q) * k_stride + col0);
                     const unsigned voff = (unsigned)(((tid / JV) * KPL * k_stride + (tid % JV) * VJ) * ES);

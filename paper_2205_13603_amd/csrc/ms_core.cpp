@@ -498,7 +498,8 @@ extern "C" int32_t ms_space_describe(const ms_op *op, uint32_t flags, ms_space *
         for (int c = 0; c < (d.in_dtype == MS_F32 ? 2 : 4); ++c) {
             int m, n, k;
             mfma_dims(list[c], &m, &n, &k);
-            if (op->M % m || op->N % n || op->K % k) continue;
+            // conv2d: a reduction extent that k does not divide is rounded up (zero padded by the loaders)
+            if (op->M % m || op->N % n || (op->K % k && d.kind != MS_OP_CONV2D_NHWC)) continue;
             t->candidates[t->n_candidates] = list[c];
             t->weight[t->n_candidates] = 1;
             ++t->n_candidates;
@@ -516,7 +517,7 @@ extern "C" int32_t ms_space_describe(const ms_op *op, uint32_t flags, ms_space *
             for (int c = 0; c < t->n_candidates; ++c) {
                 int mnk[3];
                 mfma_dims(t->candidates[c], &mnk[0], &mnk[1], &mnk[2]);
-                s->extent_by_choice[c] = ext[l] / mnk[l];
+                s->extent_by_choice[c] = (ext[l] + mnk[l] - 1) / mnk[l];
             }
         }
         if (flags & MS_SPACE_UNROLL) add_cat(out, MS_SLOT_UNROLL, "unroll", {0, 16, 64});
@@ -545,6 +546,19 @@ extern "C" int32_t ms_space_describe(const ms_op *op, uint32_t flags, ms_space *
         }
         if (flags & MS_SPACE_CACHE_WRITE) add_cat(out, MS_SLOT_CACHE_WRITE, "cache_write", {0, 1});
         if (flags & MS_SPACE_COMPUTE_AT) add_cat(out, MS_SLOT_COMPUTE_AT, "compute_at", {0, 1, 2, 3, 4});
+        if (d.kind == MS_OP_CONV2D_NHWC) {
+            // candidates that no trace of this operator can use keep their position (stored decisions are indices)
+            // but get weight 0: vector widths that do not divide the channel counts, and the resident-patch modes
+            // when no intrinsic's k divides Cin
+            for (int i = 0; i < out->n_slots; ++i) {
+                ms_slot &sl = out->slots[i];
+                for (int c = 0; c < sl.n_candidates; ++c) {
+                    if (sl.slot_id == MS_SLOT_VECTORIZE && d.dims[3] % sl.candidates[c]) sl.weight[c] = 0;
+                    if (sl.slot_id == MS_SLOT_VECTORIZE_B && d.dims[4] % sl.candidates[c]) sl.weight[c] = 0;
+                    if (sl.slot_id == MS_SLOT_COMPUTE_AT && sl.candidates[c] > 0 && d.dims[3] % 8) sl.weight[c] = 0;
+                }
+            }
+        }
         return MS_OK;
     }
     flags &= ~(MS_SPACE_CACHE_WRITE | MS_SPACE_COMPUTE_AT);

@@ -230,6 +230,11 @@ extern "C" int32_t ms_trace_validate(const ms_op *op, const ms_space *space, con
                 int64_t btile = d.b_strides[2] == 1 ? ((bk * (bn / ce) + 63) / 64) * 1024 : bn * bk * es;
                 lds = (int64_t)(p.cache_read - 3) * (bm * bk * es + btile);
             }
+            if (d.kind == MS_OP_CONV2D_NHWC && op->K % p.tile_unit[2]) {
+                // the k split covers the reduction rounded up to the intrinsic's k; only the im2col loader pads with zeros
+                if (p.compute_at) return reject("KH*KW*Cin = %" PRId64 " is not a multiple of the intrinsic's k = %d: compute_at must be 0", op->K, p.tile_unit[2]);
+                if (p.cache_read >= 5) return reject("a padded reduction cannot be staged directly to LDS");
+            }
             if (p.compute_at) {
                 // conv2d with the activations' cache-read under the workgroup tile loop: the input rows of
                 // the tile (zero halo included) are resident, only the weights are staged per k step

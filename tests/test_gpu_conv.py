@@ -212,3 +212,56 @@ def test_conv_bf16_every_compute_location():
             for r in range(2):
                 compare.assert_float_close(got[r], ref, compare.RTOL_HALF, "bf16 conv, compute_at %d trace %d" % (compute_at, n))
     assert {0, 1, 2} <= ran
+
+
+@pytest.mark.parametrize("Cin,k,stride,pad,H,W_", [(3, 7, 2, 3, 32, 32), (5, 3, 1, 1, 16, 16), (12, 3, 1, 1, 8, 16), (3, 1, 1, 0, 16, 16)])
+def test_conv_reduction_extent_not_a_multiple_of_the_intrinsic(Cin, k, stride, pad, H, W_):
+    """KH*KW*Cin = 147, 45, 108 and 3: the k split covers the extent rounded up to the intrinsic's k and both loaders
+    deliver zeros beyond it (a first layer with 3 input channels is such an operator).  Integer-valued inputs: bit-equal
+    to the oracle for every intrinsic that the space offers."""
+    N, Cout = 1, 32
+    g = I.rng(61)
+    X = I.small_ints(g, (N, H, W_, Cin), -2, 2, "f16")
+    Wt = I.small_ints(g, (k, k, Cin, Cout), -2, 2, "f16")
+    bias = g.integers(-3, 4, size=Cout).astype(np.float32)
+    ref = O.conv2d_nhwc(X, Wt, bias=bias, relu=True, stride=stride, pad=pad)
+    OH, OW = ref.shape[1], ref.shape[2]
+    op = B.conv2d_op(N, H, W_, Cin, Cout, k, k, stride=stride, pad=pad, out_dtype="f32")
+    space = op.space()
+    cands = [space.slots[0].candidates[i] for i in range(space.slots[0].n_candidates)]
+    assert any((k * k * Cin) % (c % 100) for c in cands)
+    want = {c: 2 for c in cands}
+    idx = 0
+    while any(want.values()) and idx < 400:
+        t = B.trace_sample_valid(op, space, 62, idx)
+        idx += 1
+        p = B.trace_validate(op, space, t)
+        if want.get(p.mfma, 0) == 0:
+            continue
+        want[p.mfma] -= 1
+        assert p.compute_at == 0 or (k * k * Cin) % p.tile_unit[2] == 0
+        print("trace", idx, t.decisions(), flush=True)
+        got = run_variant(op, space, t, [X, Wt, bias], "f32", (N, OH, OW, Cout), instances=2)
+        if got is None:
+            continue
+        assert np.array_equal(got[0], ref) and np.array_equal(got[1], ref), "trace %d" % idx
+    assert not any(want.values()), want
+
+
+def test_cbr_first_layer_224x224x3_7x7_stride_2():
+    """The paper's CBR shape (Appendix A.2: 224 x 224 x 3 -> 64, 7 x 7, stride 2, padding 3), batch normalisation folded
+    into weights and bias: U[0,1] input, N(0, 0.05) weights, fp16 output within the half-precision tolerance."""
+    g = I.rng(63)
+    X = I.uniform(g, (1, 224, 224, 3), 0.0, 1.0, "f16")
+    Wt = I.normal(g, (7, 7, 3, 64), 0.05, "f16")
+    bias = I.normal(g, (64,), 0.05, "f32")
+    ref = O.conv2d_nhwc(X, Wt, bias=bias, relu=True, stride=2, pad=3)
+    op = B.conv2d_op(1, 224, 224, 3, 64, 7, 7, stride=2, pad=3)
+    space = op.space()
+    for n in range(6):
+        t = B.trace_sample_valid(op, space, 64, n)
+        print("trace", n, t.decisions(), flush=True)
+        got = run_variant(op, space, t, [X, Wt, bias], "f16", ref.shape)
+        if got is None:
+            continue
+        compare.assert_float_close(got, ref, compare.RTOL_HALF, "CBR trace %d" % n)

@@ -348,11 +348,15 @@ def test_validator_conv_compute_location_rules():
     assert 161616 in cands
     t = B.make_trace(sp3, [[161616], [9, 1, 1, 1], [1, 2, 1, 1], [9, 1, 1, 1], [0], [1], [8], [8], [0], [0], [0], [1]])
     assert B.trace_validate(op3, sp3, t).compute_at == 1
-    if 161632 in cands:
-        t = B.make_trace(sp3, [[161632], [9, 1, 1, 1], [1, 2, 1, 1], [9, 1, 1, 1], [0], [1], [8], [8], [0], [0], [0], [1]])
+    assert 161632 in cands
+    if True:
+        # K = 144 is rounded up to 160 for the 32-deep intrinsic (5 k steps, zero padded by the im2col loader only)
+        t = B.make_trace(sp3, [[161632], [9, 1, 1, 1], [1, 2, 1, 1], [5, 1, 1, 1], [0], [1], [8], [8], [0], [0], [0], [1]])
         with pytest.raises(B.MsError) as e:
             B.trace_validate(op3, sp3, t)
-        assert "Cin" in str(e.value)
+        assert "Cin" in str(e.value) and "compute_at must be 0" in str(e.value)
+        t = B.make_trace(sp3, [[161632], [9, 1, 1, 1], [1, 2, 1, 1], [5, 1, 1, 1], [0], [1], [8], [8], [0], [0], [0], [0]])
+        assert B.trace_validate(op3, sp3, t).block_k == 32
 
 
 CONFIG_OPS = [
