@@ -43,6 +43,8 @@ def workload_inputs(name, seed):
         "c4c_gemm_i8_512": lambda: list(I.c4c(seed)),
         "c5a_dw_f32_112x112x32": lambda: list(I.c5a(seed)),
         "c5b_dw_f32_56x56x144": lambda: list(I.c5b(seed)),
+        "x5_cbr_f16_224x224x3": lambda: list(I.cbr(seed)),
+        "x5b_cbr_f16_224x224x4": lambda: list(I.cbr4(seed)),
         "x3_softmax_f32_256x256": lambda: list(I.sfm(seed)),
         "x4_norm_f32_256x256": lambda: list(I.nrm(seed)),
     }[name]()
@@ -62,6 +64,8 @@ def oracle_run(name, ins):
         return O.dwconv2d_nhwc(ins[0], ins[1], stride=1, pad=1)
     if name == "c5b_dw_f32_56x56x144":
         return O.dwconv2d_nhwc(ins[0], ins[1], stride=2, pad=1)
+    if name in ("x5_cbr_f16_224x224x3", "x5b_cbr_f16_224x224x4"):
+        return O.conv2d_nhwc(ins[0], ins[1], bias=ins[2], relu=True, stride=2, pad=3)
     if name == "x3_softmax_f32_256x256":
         return O.softmax(ins[0])
     if name == "x4_norm_f32_256x256":
@@ -75,6 +79,7 @@ OUT_SHAPE = {
     "c4b_bmm_nn_f16": ((12, 128, 64), "f16"), "c4c_gemm_i8_512": ((512, 512), "i32"),
     "c5a_dw_f32_112x112x32": ((1, 112, 112, 32), "f32"), "c5b_dw_f32_56x56x144": ((1, 28, 28, 144), "f32"),
     "x3_softmax_f32_256x256": ((1, 256, 256), "f32"), "x4_norm_f32_256x256": ((1,), "f32"),
+    "x5_cbr_f16_224x224x3": ((1, 112, 112, 64), "f16"), "x5b_cbr_f16_224x224x4": ((1, 112, 112, 64), "f16"),
 }
 BOUND = {  # which roofline bounds the workload (AI vs ridge), and the in-dtype
     "c1_gemm_f32_128": ("alu", "f32"), "c2_gemm_f16_1024": ("mfma", "f16"), "c3_conv_f16_56x56x64": ("mfma", "f16"),
@@ -82,6 +87,7 @@ BOUND = {  # which roofline bounds the workload (AI vs ridge), and the in-dtype
     "c5a_dw_f32_112x112x32": ("hbm", "f32"), "c5b_dw_f32_56x56x144": ("hbm", "f32"),
     "x2_gemm_f8_1024": ("mfma", "f8"),  # beyond the eight configs: config 2 with 8-bit float inputs
     "x3_softmax_f32_256x256": ("hbm", "f32"), "x4_norm_f32_256x256": ("hbm", "f32"),  # row reductions
+    "x5_cbr_f16_224x224x3": ("hbm", "f16"), "x5b_cbr_f16_224x224x4": ("hbm", "f16"),  # 122 flop per byte: below the ridge of 312
 }
 
 

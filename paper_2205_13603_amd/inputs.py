@@ -138,3 +138,22 @@ def sfm(seed=0, B=1, M=256, N=256, dtype="f32"):
 def nrm(seed=0, B=1, M=256, N=256, dtype="f32"):
     """Norm workload (batch 1, 256 x 256): standard normal values."""
     return (normal(rng(seed), (B, M, N), 1.0, dtype),)
+
+
+def cbr(seed=0, dtype="f16"):
+    """First layer of a residual network (224 x 224 x 3 -> 64, 7 x 7, stride 2, padding 3), batch normalisation folded
+    into weights and bias: X ~ U[0, 1], W ~ N(0, 0.05), bias ~ N(0, 0.05) fp32."""
+    g = rng(seed)
+    return (uniform(g, (1, 224, 224, 3), 0.0, 1.0, dtype), normal(g, (7, 7, 3, 64), 0.05, dtype), normal(g, (64,), 0.05, "f32"))
+
+
+def cbr4(seed=0, dtype="f16"):
+    """The same layer with the input stored with 4 channels per pixel (the fourth is zero, and so are its weights):
+    one 8-byte load per pixel instead of three 2-byte loads."""
+    import numpy as np
+    X, W, b = cbr(seed, dtype)
+    X4 = np.zeros(X.shape[:3] + (4,), X.dtype)
+    X4[..., :3] = X
+    W4 = np.zeros(W.shape[:2] + (4,) + W.shape[3:], W.dtype)
+    W4[:, :, :3, :] = W
+    return (X4, W4, b)
