@@ -20,6 +20,9 @@
  *             Xpad[n][oh*s+kh-p][ow*s+kw-p][ci] * W[kh][kw][ci][co])
  *   depthwise conv2d NHWC (Appendix A.2: DEP)
  *       Y[n][oh][ow][c] = sum_{kh,kw} Xpad[n][oh*s+kh-p][ow*s+kw-p][c] * W[kh][kw][c]
+ *   transposed conv2d NHWC (Appendix A.2: T2D), the adjoint of the conv2d above in X:
+ *       Y[n][ih*s+kh-p][iw*s+kw-p][co] += X[n][ih][iw][ci] * W[kh][kw][ci][co]   (then bias, ReLU)
+ *       output size (H-1)*s - 2p + KH
  *   softmax over the last axis (Appendix A.2: SFM, batch x m x n)
  *       Y[r][j] = exp(X[r][j] - max_j X[r][j]) / sum_j exp(X[r][j] - max_j X[r][j])
  *   norm (Appendix A.2: NRM, batch x m x n)
@@ -241,6 +244,53 @@ int ms_oracle_conv2d_nhwc(int dtype, int64_t N, int64_t H, int64_t W_, int64_t C
                 Y[((n * OH + oh) * OW + ow) * Cout + co] = acc;
             }
         }
+    }
+    return 0;
+}
+
+/*
+ * Transposed conv2d, NHWC, in its scatter form: every input element adds its
+ * contribution X * W[kh][kw] to the output position (ih*s + kh - p, iw*s + kw - p)
+ * if that position exists.  W is [KH][KW][Cin][Cout].  Y is dense
+ * [N][OH][OW][Cout] in double with OH = (H-1)*s - 2p + KH; bias and ReLU are
+ * applied after all contributions have been added.  One thread per image, so
+ * that no two threads add to the same output.
+ */
+int ms_oracle_conv2d_transposed_nhwc(int dtype, int64_t N, int64_t H, int64_t W_, int64_t Cin, int64_t Cout,
+                                     int64_t KH, int64_t KW, int64_t stride, int64_t pad,
+                                     const void *X, const void *Wt, const float *bias, int relu,
+                                     double *Y)
+{
+    if (dtype != ORA_F32 && dtype != ORA_F16 && dtype != ORA_BF16) return -1;
+    int64_t OH = (H - 1) * stride - 2 * pad + KH, OW = (W_ - 1) * stride - 2 * pad + KW;
+    if (OH < 1 || OW < 1) return -1;
+    int64_t n;
+#pragma omp parallel for schedule(static)
+    for (n = 0; n < N; ++n) {
+        double *Yn = Y + n * OH * OW * Cout;
+        for (int64_t i = 0; i < OH * OW * Cout; ++i) Yn[i] = 0.0;
+        for (int64_t ih = 0; ih < H; ++ih)
+            for (int64_t iw = 0; iw < W_; ++iw)
+                for (int64_t kh = 0; kh < KH; ++kh) {
+                    int64_t oh = ih * stride + kh - pad;
+                    if (oh < 0 || oh >= OH) continue;
+                    for (int64_t kw = 0; kw < KW; ++kw) {
+                        int64_t ow = iw * stride + kw - pad;
+                        if (ow < 0 || ow >= OW) continue;
+                        for (int64_t ci = 0; ci < Cin; ++ci) {
+                            double x = load_elem(dtype, X, ((n * H + ih) * W_ + iw) * Cin + ci);
+                            for (int64_t co = 0; co < Cout; ++co)
+                                Yn[(oh * OW + ow) * Cout + co] += x * load_elem(dtype, Wt, ((kh * KW + kw) * Cin + ci) * Cout + co);
+                        }
+                    }
+                }
+        for (int64_t i = 0; i < OH * OW; ++i)
+            for (int64_t co = 0; co < Cout; ++co) {
+                double v = Yn[i * Cout + co];
+                if (bias) v += (double)bias[co];
+                if (relu && v < 0.0) v = 0.0;
+                Yn[i * Cout + co] = v;
+            }
     }
     return 0;
 }

@@ -34,6 +34,8 @@ def lib():
         L.ms_oracle_conv_out_size.argtypes = [i64, i64, i64, i64]
         L.ms_oracle_conv2d_nhwc.restype = C.c_int
         L.ms_oracle_conv2d_nhwc.argtypes = [C.c_int] + [i64] * 10 + [vp, vp, vp, C.c_int, vp]
+        L.ms_oracle_conv2d_transposed_nhwc.restype = C.c_int
+        L.ms_oracle_conv2d_transposed_nhwc.argtypes = [C.c_int] + [i64] * 9 + [vp, vp, vp, C.c_int, vp]
         L.ms_oracle_dwconv2d_nhwc.restype = C.c_int
         L.ms_oracle_dwconv2d_nhwc.argtypes = [C.c_int] + [i64] * 8 + [vp, vp, vp]
         L.ms_oracle_softmax.restype = C.c_int
@@ -139,6 +141,27 @@ def conv2d_nhwc(X, Wt, bias=None, relu=False, stride=1, pad=0, bf16=False, dilat
                                      _ptr(X), _ptr(Wt), bptr, int(bool(relu)), _ptr(out))
     if rc != 0:
         raise RuntimeError("oracle conv2d failed")
+    return out
+
+
+def conv2d_transposed_nhwc(X, Wt, bias=None, relu=False, stride=1, pad=0, bf16=False):
+    """X [N,H,W,Cin], Wt [KH,KW,Cin,Cout]; output [N, (H-1)*stride - 2*pad + KH, (W-1)*stride - 2*pad + KW, Cout]."""
+    X = np.ascontiguousarray(X)
+    Wt = np.ascontiguousarray(Wt)
+    N, H, W_, Cin = X.shape
+    KH, KW, Cin2, Cout = Wt.shape
+    assert Cin2 == Cin and X.dtype == Wt.dtype
+    OH, OW = (H - 1) * stride - 2 * pad + KH, (W_ - 1) * stride - 2 * pad + KW
+    out = np.empty((N, OH, OW, Cout), np.float64)
+    bptr = None
+    if bias is not None:
+        bias = np.ascontiguousarray(bias, dtype=np.float32)
+        assert bias.shape == (Cout,)
+        bptr = _ptr(bias)
+    rc = lib().ms_oracle_conv2d_transposed_nhwc(_dtype_code(X, bf16), N, H, W_, Cin, Cout, KH, KW, stride, pad,
+                                                _ptr(X), _ptr(Wt), bptr, int(bool(relu)), _ptr(out))
+    if rc != 0:
+        raise RuntimeError("oracle transposed conv2d failed")
     return out
 
 

@@ -465,3 +465,51 @@ def test_norm_closed_forms_and_library():
     assert np.array_equal(O.norm(X * np.float32(2.0)), 2.0 * O.norm(X))              # homogeneity (scaling by 2 is exact)
     assert np.array_equal(O.norm(-X), O.norm(X))
     assert np.array_equal(O.norm(X[::-1].copy()), O.norm(X)[::-1])                   # one number per batch entry
+
+
+# ---------------------------------------------------------------- transposed conv2d (Appendix A.2: T2D)
+
+@pytest.mark.parametrize("stride,pad,k", [(2, 1, 4), (1, 0, 3), (2, 0, 2), (3, 2, 5), (1, 1, 3)])
+def test_transposed_conv_vs_torch_cpu_and_adjoint_identity(stride, pad, k):
+    import torch
+    g = np.random.default_rng(70 + stride + k)
+    N, H, W_, Cin, Cout = 2, 5, 4, 3, 6
+    X = g.standard_normal((N, H, W_, Cin)).astype(np.float32)
+    Wt = g.standard_normal((k, k, Cin, Cout)).astype(np.float32)
+    bias = g.standard_normal(Cout).astype(np.float32)
+    got = O.conv2d_transposed_nhwc(X, Wt, bias=bias, relu=False, stride=stride, pad=pad)
+    # library routine: weight layout (Cin, Cout, KH, KW), activations NCHW
+    ref = torch.nn.functional.conv_transpose2d(torch.from_numpy(X).double().permute(0, 3, 1, 2),
+                                               torch.from_numpy(Wt).double().permute(2, 3, 0, 1),
+                                               torch.from_numpy(bias).double(), stride=stride, padding=pad)
+    np.testing.assert_allclose(got, ref.permute(0, 2, 3, 1).numpy(), rtol=1e-12, atol=1e-12)
+    assert got.shape == (N, (H - 1) * stride - 2 * pad + k, (W_ - 1) * stride - 2 * pad + k, Cout)
+    # adjoint of the (pinned) direct convolution: <conv(Z, W'), X> = <Z, convT(X, W)> with W'[kh][kw][co][ci] = W[kh][kw][ci][co]
+    Z = g.standard_normal(got.shape).astype(np.float32)
+    fwd = O.conv2d_nhwc(Z, np.ascontiguousarray(Wt.transpose(0, 1, 3, 2)), stride=stride, pad=pad)
+    assert fwd.shape == X.shape
+    lhs = float((fwd * X).sum())
+    rhs = float((Z.astype(np.float64) * O.conv2d_transposed_nhwc(X, Wt, stride=stride, pad=pad)).sum())
+    assert abs(lhs - rhs) <= 1e-10 * max(1.0, abs(lhs))
+
+
+def test_transposed_conv_closed_forms():
+    # one input pixel, stride 2, no padding: the output is the filter itself, placed at (2*ih, 2*iw)
+    Wt = np.arange(1, 10, dtype=np.float32).reshape(3, 3, 1, 1)
+    X = np.zeros((1, 2, 2, 1), np.float32)
+    X[0, 1, 0, 0] = 2.0
+    y = O.conv2d_transposed_nhwc(X, Wt, stride=2, pad=0)
+    assert y.shape == (1, 5, 5, 1)
+    want = np.zeros((5, 5))
+    want[2:5, 0:3] = 2.0 * Wt[:, :, 0, 0]
+    assert np.array_equal(y[0, :, :, 0], want)
+    # stride 1, 1x1 filter: a plain matrix product over channels; bias then ReLU
+    g = np.random.default_rng(9)
+    X = g.integers(-3, 4, (1, 3, 3, 4)).astype(np.float32)
+    W1 = g.integers(-3, 4, (1, 1, 4, 5)).astype(np.float32)
+    b = np.arange(-2, 3, dtype=np.float32)
+    y = O.conv2d_transposed_nhwc(X, W1, bias=b, relu=True, stride=1, pad=0)
+    assert np.array_equal(y, np.maximum(X.astype(np.float64) @ W1[0, 0].astype(np.float64) + b, 0.0))
+    # all ones, 2x2 filter, stride 1: every output counts the inputs that reach it (1, 2 or 4)
+    y = O.conv2d_transposed_nhwc(np.ones((1, 3, 3, 1), np.float16), np.ones((2, 2, 1, 1), np.float16), stride=1, pad=0)
+    assert np.array_equal(y[0, :, :, 0], [[1, 2, 2, 1], [2, 4, 4, 2], [2, 4, 4, 2], [1, 2, 2, 1]])
