@@ -72,7 +72,9 @@ typedef enum ms_op_kind {
     MS_OP_CONV2D_NHWC = 3,   /* Y = act(bias + conv(X, W)), X NHWC, W HWIO  (C2D / CBR) */
     MS_OP_DWCONV2D_NHWC = 4, /* depthwise, X NHWC, W [KH][KW][C]            (DEP) */
     MS_OP_SOFTMAX = 5,       /* Y[b][i][:] = softmax(X[b][i][:]), last axis  (SFM) */
-    MS_OP_NORM = 6           /* Y[b] = sqrt(sum_{i,j} X[b][i][j]^2)          (NRM) */
+    MS_OP_NORM = 6,          /* Y[b] = sqrt(sum_{i,j} X[b][i][j]^2)          (NRM) */
+    MS_OP_CONV2D_TRANSPOSED_NHWC = 7 /* Y = act(bias + convT(X, W)): the adjoint of CONV2D_NHWC in X; X NHWC,
+                                        W [KH][KW][Cin][Cout]                (T2D) */
 } ms_op_kind;
 
 typedef enum ms_dtype { MS_F32 = 0, MS_F16 = 1, MS_BF16 = 2, MS_I8 = 3, MS_I32 = 4,
@@ -86,6 +88,9 @@ typedef enum ms_dtype { MS_F32 = 0, MS_F16 = 1, MS_BF16 = 2, MS_I8 = 3, MS_I32 =
  *   BMM_NT, BMM_NN  B, M, N, K
  *   CONV2D_NHWC     N, H, W, Cin, Cout, KH, KW
  *   DWCONV2D_NHWC   N, H, W, C, KH, KW
+ *   CONV2D_TRANSPOSED_NHWC  N, H, W, Cin, Cout, KH, KW   (input element (ih, iw) contributes X * W[kh][kw] to output
+ *                           (ih*stride + kh - pad, iw*stride + kw - pad); output size (H-1)*stride - 2*pad + KH;
+ *                           dense filters only; same inputs, bias and ReLU as CONV2D_NHWC)
  *   SOFTMAX, NORM   B, M, N   (X dense [B][M][N]; F32, F16 or BF16 in; softmax writes the input dtype or F32,
  *                              the norm writes F32 [B]; all arithmetic in fp32: max, exp(x - max), sum, scale)
  * Convolutions: cross-correlation, zero padding `pad` on all four sides,

@@ -12,7 +12,8 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(HERE, "libms.so")
 
 MS_OK, MS_ERR_BAD_ARG, MS_ERR_INVALID_TRACE, MS_ERR_UNSUPPORTED, MS_ERR_COMPILE, MS_ERR_HIP, MS_ERR_NOMEM = range(7)
-OP_GEMM, OP_BMM_NT, OP_BMM_NN, OP_CONV2D_NHWC, OP_DWCONV2D_NHWC, OP_SOFTMAX, OP_NORM = range(7)
+(OP_GEMM, OP_BMM_NT, OP_BMM_NN, OP_CONV2D_NHWC, OP_DWCONV2D_NHWC, OP_SOFTMAX, OP_NORM,
+ OP_CONV2D_TRANSPOSED_NHWC) = range(8)
 F32, F16, BF16, I8, I32 = range(5)
 SLOT_PERFECT_TILE, SLOT_CATEGORICAL = 0, 1
 (SLOT_TENSORIZE, SLOT_TILE_I, SLOT_TILE_J, SLOT_TILE_C, SLOT_TILE_K, SLOT_UNROLL, SLOT_CACHE_READ, SLOT_VECTORIZE,
@@ -271,6 +272,12 @@ def bmm_op(B, M, N, K, trans_b, in_dtype="f16", out_dtype=None, **kw):
 def conv2d_op(N, H, W, Cin, Cout, KH, KW, stride=1, pad=0, has_bias=True, relu=True, in_dtype="f16", out_dtype=None, dilation=1):
     return Op(OP_CONV2D_NHWC, in_dtype, out_dtype or in_dtype, [N, H, W, Cin, Cout, KH, KW], stride=stride, pad=pad,
               has_bias=has_bias, relu=relu, dilation=dilation)
+
+
+def conv2d_transposed_op(N, H, W, Cin, Cout, KH, KW, stride=1, pad=0, has_bias=True, relu=True, in_dtype="f16", out_dtype=None):
+    """Transposed convolution: output [N, (H-1)*stride - 2*pad + KH, (W-1)*stride - 2*pad + KW, Cout]."""
+    return Op(OP_CONV2D_TRANSPOSED_NHWC, in_dtype, out_dtype or in_dtype, [N, H, W, Cin, Cout, KH, KW], stride=stride, pad=pad,
+              has_bias=has_bias, relu=relu, dilation=1)
 
 
 def dwconv2d_op(N, H, W, Cc, KH=3, KW=3, stride=1, pad=1):

@@ -63,6 +63,9 @@
 #ifndef HELPER_WAVES
 #define HELPER_WAVES 0
 #endif
+#ifndef CV_TRANSPOSED
+#define CV_TRANSPOSED 0
+#endif
 
 #define NWAVES (I2 * J2)
 #define LANE_GROUPS (64 / MI_M)
@@ -228,12 +231,21 @@ constexpr int CV_KREAL = CV_KH * CV_KW * CV_CIN;
 constexpr bool K_PADDED = K0 * BK != CV_KREAL;
 static_assert(K0 * BK >= CV_KREAL && K0 * BK - CV_KREAL < MI_K, "the k split covers the reduction, padded by less than one intrinsic");
 static_assert(!K_PADDED || COMPUTE_AT == 0, "a padded reduction needs the im2col loader");
+static_assert(!CV_TRANSPOSED || (COMPUTE_AT == 0 && CV_DIL == 1), "the transposed convolution exists in the im2col loader only");
 // im2col on the fly: row = output pixel, k = (kh, kw, ci)
 template <int V> __device__ __forceinline__ vec_t<in_t, V> load_conv_a(const in_t *__restrict__ X, int row, int k)
 {
     const int ow = row % CV_OW, oh = (row / CV_OW) % CV_OH, n = row / (CV_OW * CV_OH);
     const int ci = k % CV_CIN, kw = (k / CV_CIN) % CV_KW, kh = k / (CV_CIN * CV_KW);
+#if CV_TRANSPOSED
+    // transposed convolution: input element ih reaches outputs ih * stride + kh - pad, so output row oh takes tap kh
+    // from input row (oh + pad - kh) / stride when that is a whole number inside the image
+    const int ihn = oh + CV_PAD - kh, iwn = ow + CV_PAD - kw;
+    const bool on_grid = ihn >= 0 && iwn >= 0 && ihn % CV_STRIDE == 0 && iwn % CV_STRIDE == 0;
+    const int ih = on_grid ? ihn / CV_STRIDE : -1, iw = on_grid ? iwn / CV_STRIDE : -1;
+#else
     const int ih = oh * CV_STRIDE + kh * CV_DIL - CV_PAD, iw = ow * CV_STRIDE + kw * CV_DIL - CV_PAD;
+#endif
     vec_t<in_t, V> x;
     if (ih >= 0 && ih < CV_H && iw >= 0 && iw < CV_W && (!K_PADDED || k < CV_KREAL)) {
         x = *reinterpret_cast<const vec_t<in_t, V> *>(X + (((long)n * CV_H + ih) * CV_W + iw) * CV_CIN + ci);

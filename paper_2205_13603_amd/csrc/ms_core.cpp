@@ -98,6 +98,7 @@ const char *op_kind_name(int32_t kind)
     case MS_OP_BMM_NT: return "bmm_nt";
     case MS_OP_BMM_NN: return "bmm_nn";
     case MS_OP_CONV2D_NHWC: return "conv2d_nhwc";
+    case MS_OP_CONV2D_TRANSPOSED_NHWC: return "conv2d_transposed_nhwc";
     case MS_OP_DWCONV2D_NHWC: return "dwconv2d_nhwc";
     case MS_OP_SOFTMAX: return "softmax";
     case MS_OP_NORM: return "norm";
@@ -182,7 +183,8 @@ extern "C" int32_t ms_op_create(const ms_op_desc *desc, ms_op **out)
     case MS_OP_GEMM: ndims = 3; break;
     case MS_OP_BMM_NT:
     case MS_OP_BMM_NN: ndims = 4; break;
-    case MS_OP_CONV2D_NHWC: ndims = 7; break;
+    case MS_OP_CONV2D_NHWC:
+    case MS_OP_CONV2D_TRANSPOSED_NHWC: ndims = 7; break;
     case MS_OP_DWCONV2D_NHWC: ndims = 6; break;
     case MS_OP_SOFTMAX:
     case MS_OP_NORM: ndims = 3; break;
@@ -254,16 +256,22 @@ extern "C" int32_t ms_op_create(const ms_op_desc *desc, ms_op **out)
     } else {
         if (d.stride < 1 || d.pad < 0) return fail(MS_ERR_BAD_ARG, "ms_op_create: bad stride/pad");
         int64_t H = d.dims[1], W = d.dims[2];
-        int64_t KH = d.kind == MS_OP_CONV2D_NHWC ? d.dims[5] : d.dims[4];
-        int64_t KW = d.kind == MS_OP_CONV2D_NHWC ? d.dims[6] : d.dims[5];
+        int64_t KH = is_conv2d(d.kind) ? d.dims[5] : d.dims[4];
+        int64_t KW = is_conv2d(d.kind) ? d.dims[6] : d.dims[5];
         if (d.dilation < 0 || d.dilation > 64) return fail(MS_ERR_BAD_ARG, "ms_op_create: bad dilation");
         if (op.d.dilation == 0) op.d.dilation = 1;
-        if (op.d.dilation != 1 && d.kind != MS_OP_CONV2D_NHWC) return fail(MS_ERR_UNSUPPORTED, "ms_op_create: dilation is for conv2d only");
+        if (op.d.dilation != 1 && !is_conv2d(d.kind)) return fail(MS_ERR_UNSUPPORTED, "ms_op_create: dilation is for conv2d only");
         // a filter whose taps are `dilation` apart spans dilation * (K - 1) + 1 input elements
         op.OH = conv_out(H, op.d.dilation * (KH - 1) + 1, d.stride, d.pad);
         op.OW = conv_out(W, op.d.dilation * (KW - 1) + 1, d.stride, d.pad);
+        if (d.kind == MS_OP_CONV2D_TRANSPOSED_NHWC) {
+            // the adjoint of a stride-s convolution: input element ih reaches outputs ih*s + kh - pad
+            if (op.d.dilation != 1) return fail(MS_ERR_UNSUPPORTED, "ms_op_create: the transposed convolution has dense filters");
+            op.OH = (H - 1) * d.stride - 2 * (int64_t)d.pad + KH;
+            op.OW = (W - 1) * d.stride - 2 * (int64_t)d.pad + KW;
+        }
         if (op.OH < 1 || op.OW < 1) return fail(MS_ERR_BAD_ARG, "ms_op_create: empty convolution output");
-        if (d.kind == MS_OP_CONV2D_NHWC) {
+        if (is_conv2d(d.kind)) {
             if (d.in_dtype == MS_I8) return fail(MS_ERR_UNSUPPORTED, "ms_op_create: int8 conv2d is not supported");
             op.M = d.dims[0] * op.OH * op.OW;
             op.N = d.dims[4];
@@ -313,6 +321,7 @@ extern "C" int32_t ms_op_loops(const ms_op *op, ms_loop *loops, int32_t *n_loops
         set_loop(&loops[n++], "k", op->K, 1);
         break;
     case MS_OP_CONV2D_NHWC:
+    case MS_OP_CONV2D_TRANSPOSED_NHWC:
         set_loop(&loops[n++], "i", op->M, 0); // fuse(n, oh, ow)
         set_loop(&loops[n++], "j", op->N, 0); // co
         set_loop(&loops[n++], "k", op->K, 1); // fuse(kh, kw, ci)
@@ -356,6 +365,7 @@ extern "C" int32_t ms_op_tensor_bytes(const ms_op *op, int32_t idx, int64_t *byt
             e = (op->nb - 1) * d.b_strides[0] + (op->K - 1) * d.b_strides[1] + (op->N - 1) * d.b_strides[2] + 1;
         break;
     case MS_OP_CONV2D_NHWC:
+    case MS_OP_CONV2D_TRANSPOSED_NHWC:
         if (idx < 0) e = op->M * op->N;
         else if (idx == 0) e = d.dims[0] * d.dims[1] * d.dims[2] * d.dims[3];
         else if (idx == 1) e = d.dims[5] * d.dims[6] * d.dims[3] * d.dims[4];
@@ -390,6 +400,12 @@ extern "C" int32_t ms_op_work(const ms_op *op, double *flop, double *bytes)
     case MS_OP_BMM_NN:
         f = 2.0 * op->nb * op->M * op->N * op->K;
         b = (double)op->nb * (op->M * op->K + op->K * op->N) * op->in_size + (double)op->nb * op->M * op->N * op->out_size;
+        break;
+    case MS_OP_CONV2D_TRANSPOSED_NHWC:
+        // every input element meets every tap once (contributions that fall outside the output are not discounted)
+        f = 2.0 * d.dims[0] * d.dims[1] * d.dims[2] * op->K * op->N;
+        b = (double)(d.dims[0] * d.dims[1] * d.dims[2] * d.dims[3] + op->K * op->N) * op->in_size +
+            (d.has_bias ? 4.0 * op->N : 0.0) + (double)op->M * op->N * op->out_size;
         break;
     case MS_OP_CONV2D_NHWC:
         f = 2.0 * op->M * op->N * op->K;
@@ -454,12 +470,12 @@ extern "C" int32_t ms_space_describe(const ms_op *op, uint32_t flags, ms_space *
     memset(out, 0, sizeof *out);
     const ms_op_desc &d = op->d;
     if (flags & 0x80000000u) flags &= 0xffu; // all-ones masks of earlier records: the default set, opt-in modules off
-    if (d.in_dtype == MS_F32 && !((flags & MS_SPACE_TENSORIZE_F32) && d.kind != MS_OP_DWCONV2D_NHWC && d.kind != MS_OP_CONV2D_NHWC))
+    if (d.in_dtype == MS_F32 && !((flags & MS_SPACE_TENSORIZE_F32) && d.kind != MS_OP_DWCONV2D_NHWC && !is_conv2d(d.kind)))
         flags &= ~(MS_SPACE_TENSORIZE | MS_SPACE_TENSORIZE_F32);
     if (d.in_dtype != MS_F32) flags &= ~MS_SPACE_TENSORIZE_F32;
     if (flags & MS_SPACE_TENSORIZE_F32) flags |= MS_SPACE_TENSORIZE;
     if (d.kind == MS_OP_DWCONV2D_NHWC) flags &= ~(MS_SPACE_TENSORIZE | MS_SPACE_VECTORIZE | MS_SPACE_STORAGE_ALIGN | MS_SPACE_CACHE_WRITE);
-    if (d.kind != MS_OP_CONV2D_NHWC) flags &= ~MS_SPACE_COMPUTE_AT;
+    if (d.kind != MS_OP_CONV2D_NHWC) flags &= ~MS_SPACE_COMPUTE_AT; // the resident-patch modes assume the direct index map
     flags &= 0x1ffu;
     if (d.kind == MS_OP_SOFTMAX || d.kind == MS_OP_NORM) {
         // rows i: [workgroups, serial, thread groups, rows of one group at a time]; reduction k: [serial, loads in
@@ -485,9 +501,9 @@ extern "C" int32_t ms_space_describe(const ms_op *op, uint32_t flags, ms_space *
     }
     if (flags & MS_SPACE_TENSORIZE) {
         out->family = MS_FAM_GEMM_MFMA;
-        if (d.a_strides[2] != 1 && d.kind != MS_OP_CONV2D_NHWC)
+        if (d.a_strides[2] != 1 && !is_conv2d(d.kind))
             return fail(MS_ERR_UNSUPPORTED, "ms_space_describe: matrix-core kernels need A contiguous along k");
-        if (d.kind != MS_OP_CONV2D_NHWC && d.b_strides[1] != 1 && d.b_strides[2] != 1)
+        if (!is_conv2d(d.kind) && d.b_strides[1] != 1 && d.b_strides[2] != 1)
             return fail(MS_ERR_UNSUPPORTED, "ms_space_describe: matrix-core kernels need B contiguous along k or j");
         ms_slot *t = add_slot(out, MS_SLOT_TENSORIZE, MS_SLOT_CATEGORICAL, "tensorize");
         static const int64_t f16_list[] = {161616, 323208, 161632, 323216};
@@ -499,7 +515,7 @@ extern "C" int32_t ms_space_describe(const ms_op *op, uint32_t flags, ms_space *
             int m, n, k;
             mfma_dims(list[c], &m, &n, &k);
             // conv2d: a reduction extent that k does not divide is rounded up (zero padded by the loaders)
-            if (op->M % m || op->N % n || (op->K % k && d.kind != MS_OP_CONV2D_NHWC)) continue;
+            if (op->M % m || op->N % n || (op->K % k && !is_conv2d(d.kind))) continue;
             t->candidates[t->n_candidates] = list[c];
             t->weight[t->n_candidates] = 1;
             ++t->n_candidates;
@@ -523,7 +539,7 @@ extern "C" int32_t ms_space_describe(const ms_op *op, uint32_t flags, ms_space *
         if (flags & MS_SPACE_UNROLL) add_cat(out, MS_SLOT_UNROLL, "unroll", {0, 16, 64});
         if (flags & MS_SPACE_CACHE_READ) {
             // direct-to-LDS staging (5, 6, 7) exists for 2-byte and 1-byte inputs of plain matrix products
-            if (d.in_dtype != MS_F32 && d.in_dtype != MS_F8E4M3 && d.kind != MS_OP_CONV2D_NHWC)
+            if (d.in_dtype != MS_F32 && d.in_dtype != MS_F8E4M3 && !is_conv2d(d.kind))
                 add_cat(out, MS_SLOT_CACHE_READ, "cache_read", {1, 2, 3, 4, 5, 6, 7});
             else add_cat(out, MS_SLOT_CACHE_READ, "cache_read", {1, 2, 3, 4});
         }
@@ -541,12 +557,12 @@ extern "C" int32_t ms_space_describe(const ms_op *op, uint32_t flags, ms_space *
         }
         if (flags & MS_SPACE_STORAGE_ALIGN) add_cat(out, MS_SLOT_STORAGE_ALIGN, "storage_align", {0, 1, 2});
         if (flags & MS_SPACE_REORDER) {
-            if (d.in_dtype != MS_F32 && d.in_dtype != MS_F8E4M3 && d.kind != MS_OP_CONV2D_NHWC) add_cat(out, MS_SLOT_REORDER, "reorder", {0, 1, 2, 3});
+            if (d.in_dtype != MS_F32 && d.in_dtype != MS_F8E4M3 && !is_conv2d(d.kind)) add_cat(out, MS_SLOT_REORDER, "reorder", {0, 1, 2, 3});
             else add_cat(out, MS_SLOT_REORDER, "reorder", {0, 1, 2});
         }
         if (flags & MS_SPACE_CACHE_WRITE) add_cat(out, MS_SLOT_CACHE_WRITE, "cache_write", {0, 1});
         if (flags & MS_SPACE_COMPUTE_AT) add_cat(out, MS_SLOT_COMPUTE_AT, "compute_at", {0, 1, 2, 3, 4});
-        if (d.kind == MS_OP_CONV2D_NHWC) {
+        if (is_conv2d(d.kind)) {
             // candidates that no trace of this operator can use keep their position (stored decisions are indices)
             // but get weight 0: vector widths that do not divide the channel counts, and the resident-patch modes
             // when no intrinsic's k divides Cin
@@ -563,7 +579,7 @@ extern "C" int32_t ms_space_describe(const ms_op *op, uint32_t flags, ms_space *
     }
     flags &= ~(MS_SPACE_CACHE_WRITE | MS_SPACE_COMPUTE_AT);
     out->flags = flags;
-    if (d.kind == MS_OP_CONV2D_NHWC)
+    if (is_conv2d(d.kind))
         return fail(MS_ERR_UNSUPPORTED, "ms_space_describe: conv2d needs the tensorize module (fp16/bf16 inputs)");
     if (d.in_dtype == MS_F8E4M3)
         return fail(MS_ERR_UNSUPPORTED, "ms_space_describe: 8-bit float inputs need the tensorize module");

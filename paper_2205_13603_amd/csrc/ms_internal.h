@@ -20,6 +20,9 @@ namespace ms {
 
 int32_t fail(int32_t code, const char *fmt, ...) __attribute__((format(printf, 2, 3)));
 
+// the two operators that share the conv2d kernels (the transposed one differs in the im2col index map only)
+inline bool is_conv2d(int32_t kind) { return kind == MS_OP_CONV2D_NHWC || kind == MS_OP_CONV2D_TRANSPOSED_NHWC; }
+
 // (m, n, k) of an MS_MFMA_CODE
 inline void mfma_dims(int64_t code, int *m, int *n, int *k)
 {

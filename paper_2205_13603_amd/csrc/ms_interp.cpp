@@ -230,7 +230,7 @@ extern "C" int32_t ms_trace_validate(const ms_op *op, const ms_space *space, con
                 int64_t btile = d.b_strides[2] == 1 ? ((bk * (bn / ce) + 63) / 64) * 1024 : bn * bk * es;
                 lds = (int64_t)(p.cache_read - 3) * (bm * bk * es + btile);
             }
-            if (d.kind == MS_OP_CONV2D_NHWC && op->K % p.tile_unit[2]) {
+            if (is_conv2d(d.kind) && op->K % p.tile_unit[2]) {
                 // the k split covers the reduction rounded up to the intrinsic's k; only the im2col loader pads with zeros
                 if (p.compute_at) return reject("KH*KW*Cin = %" PRId64 " is not a multiple of the intrinsic's k = %d: compute_at must be 0", op->K, p.tile_unit[2]);
                 if (p.cache_read >= 5) return reject("a padded reduction cannot be staged directly to LDS");
@@ -238,7 +238,7 @@ extern "C" int32_t ms_trace_validate(const ms_op *op, const ms_space *space, con
             if (p.compute_at) {
                 // conv2d with the activations' cache-read under the workgroup tile loop: the input rows of
                 // the tile (zero halo included) are resident, only the weights are staged per k step
-                if (d.kind != MS_OP_CONV2D_NHWC) return reject("compute_location applies to conv2d only");
+                if (!is_conv2d(d.kind)) return reject("compute_location applies to conv2d only");
                 if (p.compute_at == 1 && p.cache_read > 3) return reject("with the input patch resident only the weights are staged per k step: cache_read 1, 2 or 3");
                 if (p.compute_at == 2 && p.cache_read > 2) return reject("with resident weights cache_read is 1 (patch loaded between tiles) or 2 (next patch prefetched)");
                 if (p.compute_at == 3 && (p.cache_read != 2 || !p.cache_write))
@@ -335,7 +335,7 @@ extern "C" int32_t ms_trace_validate(const ms_op *op, const ms_space *space, con
         if (p.vec > 1) {
             int v = p.vec;
             if (v * es > 16) return reject("vector of %d x %d bytes is wider than a 16-byte load", v, es);
-            if (d.kind == MS_OP_CONV2D_NHWC) {
+            if (is_conv2d(d.kind)) {
                 if (d.dims[3] % v) return reject("vector width %d does not divide Cin = %" PRId64, v, d.dims[3]);
                 if (bk % v) return reject("vector width %d does not divide the k tile %" PRId64, v, bk);
             } else {
@@ -347,7 +347,7 @@ extern "C" int32_t ms_trace_validate(const ms_op *op, const ms_space *space, con
         if (p.vec_b > 1) {
             int v = p.vec_b;
             if (v * es > 16) return reject("vector of %d x %d bytes is wider than a 16-byte load", v, es);
-            if (d.kind == MS_OP_CONV2D_NHWC) {
+            if (is_conv2d(d.kind)) {
                 if (d.dims[4] % v) return reject("vector width %d does not divide Cout = %" PRId64, v, d.dims[4]);
                 if (bn % v) return reject("vector width %d does not divide the j tile %" PRId64, v, bn);
             } else if (d.b_strides[2] == 1) { // vector along j
@@ -493,7 +493,7 @@ int32_t make_kernel_spec(const ms_op *op, const ms_variant_params *p, KernelSpec
         D.push_back(def("DIM_M", op->M));
         D.push_back(def("DIM_N", op->N));
         D.push_back(def("DIM_K", op->K));
-        bool conv = d.kind == MS_OP_CONV2D_NHWC;
+        bool conv = is_conv2d(d.kind);
         D.push_back(def("IS_CONV", conv ? 1 : 0));
         if (conv) {
             D.push_back(def("CV_N", d.dims[0]));
@@ -508,6 +508,7 @@ int32_t make_kernel_spec(const ms_op *op, const ms_variant_params *p, KernelSpec
             D.push_back(def("CV_STRIDE", d.stride));
             D.push_back(def("CV_PAD", d.pad));
             D.push_back(def("CV_DIL", d.dilation));
+            D.push_back(def("CV_TRANSPOSED", d.kind == MS_OP_CONV2D_TRANSPOSED_NHWC ? 1 : 0));
             D.push_back(def("HAS_BIAS", d.has_bias ? 1 : 0));
             D.push_back(def("RELU", d.relu ? 1 : 0));
             // implicit GEMM view: A rows are output pixels, B = W as [K][N]

@@ -132,7 +132,7 @@ extern "C" int32_t ms_variant_launch(ms_variant *v, const void *const *inputs, v
     if (rc != MS_OK) return rc;
     const void *in0 = inputs[0], *in1 = one_input ? nullptr : inputs[1];
     const void *in2 = nullptr;
-    if (v->op.d.kind == MS_OP_CONV2D_NHWC && v->op.d.has_bias) {
+    if (is_conv2d(v->op.d.kind) && v->op.d.has_bias) {
         in2 = inputs[2];
         if (!in2) return fail(MS_ERR_BAD_ARG, "ms_variant_launch: the op has a bias but inputs[2] is NULL");
     }

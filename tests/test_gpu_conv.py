@@ -265,3 +265,46 @@ def test_cbr_first_layer_224x224x3_7x7_stride_2():
         if got is None:
             continue
         compare.assert_float_close(got, ref, compare.RTOL_HALF, "CBR trace %d" % n)
+
+
+@pytest.mark.parametrize("stride,pad,k,H,W_", [(2, 1, 4, 8, 8), (1, 0, 3, 6, 6), (2, 0, 2, 8, 4), (3, 2, 5, 6, 6), (1, 1, 3, 8, 16)])
+def test_transposed_conv_exact(stride, pad, k, H, W_):
+    """Transposed convolution (Appendix A.2: T2D): the kernels gather (output pixel <- the input pixels whose scattered
+    filter reaches it), the oracle scatters.  Integer-valued inputs, batch 2, 2 instances: bit-equal fp32 outputs."""
+    N, Cin, Cout = 2, 16, 32
+    g = I.rng(71)
+    X = I.small_ints(g, (N, H, W_, Cin), -2, 2, "f16")
+    Wt = I.small_ints(g, (k, k, Cin, Cout), -2, 2, "f16")
+    bias = g.integers(-3, 4, size=Cout).astype(np.float32)
+    ref = O.conv2d_transposed_nhwc(X, Wt, bias=bias, relu=True, stride=stride, pad=pad)
+    OH, OW = ref.shape[1], ref.shape[2]
+    assert (OH, OW) == ((H - 1) * stride - 2 * pad + k, (W_ - 1) * stride - 2 * pad + k) and (N * OH * OW) % 16 == 0
+    op = B.conv2d_transposed_op(N, H, W_, Cin, Cout, k, k, stride=stride, pad=pad, out_dtype="f32")
+    space = op.space()
+    for n in range(6):
+        t = B.trace_sample_valid(op, space, 72, n)
+        print("trace", n, t.decisions(), flush=True)
+        got = run_variant(op, space, t, [X, Wt, bias], "f32", (N, OH, OW, Cout), instances=2)
+        if got is None:
+            continue
+        assert np.array_equal(got[0], ref) and np.array_equal(got[1], ref), "trace %d" % n
+
+
+@pytest.mark.parametrize("dtype", ["f16", "bf16"])
+def test_t2d_config_transposed_conv_4x4x512(dtype):
+    """The paper's T2D shape: 4 x 4 x 512 -> 8 x 8 x 256, 4 x 4 filter, stride 2, padding 1 (K = 8192)."""
+    g = I.rng(73)
+    X = I.normal(g, (1, 4, 4, 512), 1.0, dtype)
+    Wt = I.normal(g, (4, 4, 512, 256), 0.05, dtype)
+    bias = I.normal(g, (256,), 0.05, "f32")
+    ref = O.conv2d_transposed_nhwc(X, Wt, bias=bias, relu=True, stride=2, pad=1, bf16=dtype == "bf16")
+    assert ref.shape == (1, 8, 8, 256)
+    op = B.conv2d_transposed_op(1, 4, 4, 512, 256, 4, 4, stride=2, pad=1, in_dtype=dtype)
+    space = op.space()
+    for n in range(6):
+        t = B.trace_sample_valid(op, space, 74, n)
+        print("trace", n, t.decisions(), flush=True)
+        got = run_variant(op, space, t, [X, Wt, bias], dtype, ref.shape)
+        if got is None:
+            continue
+        compare.assert_float_close(got, ref, compare.RTOL_HALF, "T2D %s trace %d" % (dtype, n))

@@ -446,3 +446,23 @@ def test_reduce_validator_rejections():
     with pytest.raises(B.MsError) as e:
         B.trace_validate(opn, spn, B.make_trace(spn, [[1, 1, 1, 1], [512, 2, 16, 4]]))
     assert "one wavefront per row" in str(e.value)
+
+
+def test_transposed_conv_descriptor_and_space():
+    op = B.conv2d_transposed_op(1, 4, 4, 512, 256, 4, 4, stride=2, pad=1)
+    assert op.loops() == [("i", 64, False), ("j", 256, False), ("k", 8192, True)]      # 8 x 8 output pixels
+    assert op.tensor_bytes(-1) == 64 * 256 * 2 and op.tensor_bytes(0) == 16 * 512 * 2 and op.tensor_bytes(1) == 8192 * 256 * 2
+    assert op.work()[0] == 2.0 * 16 * 8192 * 256
+    sp = op.space()
+    assert sp.family == B.FAM_GEMM_MFMA
+    assert "compute_at" not in [sp.slots[i].name.decode() for i in range(sp.n_slots)]
+    t = B.trace_sample_valid(op, sp, 2, 0)
+    p = B.trace_validate(op, sp, t)
+    assert p.compute_at == 0
+    cov = B.variant_coverage(op, p, 64 * 256)
+    assert cov.min() == 1 and cov.max() == 1
+    assert "op=conv2d_transposed_nhwc" in B.trace_to_text(op, sp, t)
+    with pytest.raises(B.MsError):
+        B.Op(B.OP_CONV2D_TRANSPOSED_NHWC, "f16", "f16", [1, 4, 4, 8, 8, 3, 3], stride=1, pad=0, dilation=2)
+    with pytest.raises(B.MsError):
+        B.conv2d_transposed_op(1, 1, 1, 8, 8, 2, 2, stride=1, pad=1)   # empty output
