@@ -157,3 +157,10 @@ def cbr4(seed=0, dtype="f16"):
     W4 = np.zeros(W.shape[:2] + (4,) + W.shape[3:], W.dtype)
     W4[:, :, :3, :] = W
     return (X4, W4, b)
+
+
+def t2d(seed=0, dtype="f16"):
+    """Transposed convolution workload (4 x 4 x 512 -> 8 x 8 x 256, 4 x 4 filter, stride 2, padding 1):
+    X ~ N(0, 1), W ~ N(0, 0.05), bias ~ N(0, 0.05) fp32."""
+    g = rng(seed)
+    return (normal(g, (1, 4, 4, 512), 1.0, dtype), normal(g, (4, 4, 512, 256), 0.05, dtype), normal(g, (256,), 0.05, "f32"))

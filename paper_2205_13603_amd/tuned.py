@@ -22,6 +22,7 @@ WORKLOADS = {
     "c5b_dw_f32_56x56x144": (lambda: B.dwconv2d_op(1, 56, 56, 144, stride=2, pad=1), 512),
     "x5_cbr_f16_224x224x3": (lambda: B.conv2d_op(1, 224, 224, 3, 64, 7, 7, stride=2, pad=3), 256),
     "x5b_cbr_f16_224x224x4": (lambda: B.conv2d_op(1, 224, 224, 4, 64, 7, 7, stride=2, pad=3), 256),
+    "x6_t2d_f16_4x4x512": (lambda: B.conv2d_transposed_op(1, 4, 4, 512, 256, 4, 4, stride=2, pad=1), 128),
     "x3_softmax_f32_256x256": (lambda: B.softmax_op(1, 256, 256), 2048),
     "x4_norm_f32_256x256": (lambda: B.norm_op(1, 256, 256), 2048),
 }
