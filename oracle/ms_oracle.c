@@ -15,7 +15,8 @@
  *
  *   GEMM / batched matmul (Appendix A.2: GMM, TBG)
  *       C[b][i][j] = sum_k A[b][i][k] * B[b][k][j]
- *   conv2d NHWC with bias and ReLU (Appendix A.2: C2D, CBR)
+ *   conv2d NHWC with bias and ReLU (Appendix A.2: C2D, CBR; with groups: GRP - each group of Cout/groups
+ *   output channels sums over its own Cin/groups input channels only)
  *       Y[n][oh][ow][co] = act(bias[co] + sum_{kh,kw,ci}
  *             Xpad[n][oh*s+kh-p][ow*s+kw-p][ci] * W[kh][kw][ci][co])
  *   depthwise conv2d NHWC (Appendix A.2: DEP)
@@ -210,12 +211,16 @@ int64_t ms_oracle_conv_out_size(int64_t in, int64_t k, int64_t s, int64_t p)
  * ow*stride + kw*dilation - pad), zero outside the image.  Y is dense [N][OH][OW][Cout] in double.
  */
 int ms_oracle_conv2d_nhwc(int dtype, int64_t N, int64_t H, int64_t W_, int64_t Cin, int64_t Cout,
-                          int64_t KH, int64_t KW, int64_t stride, int64_t pad, int64_t dilation,
+                          int64_t KH, int64_t KW, int64_t stride, int64_t pad, int64_t dilation, int64_t groups,
                           const void *X, const void *Wt, const float *bias, int relu,
                           double *Y)
 {
     if (dtype != ORA_F32 && dtype != ORA_F16 && dtype != ORA_BF16) return -1;
     if (dilation < 1) return -1;
+    /* grouped convolution: output channel co belongs to group co / (Cout/groups) and sees only the Cin/groups
+       input channels of that group; W is [KH][KW][Cin/groups][Cout] */
+    if (groups < 1 || Cin % groups || Cout % groups) return -1;
+    int64_t Cg = Cin / groups, Ng = Cout / groups;
     /* a filter with taps `dilation` apart spans dilation*(K-1)+1 input elements */
     int64_t OH = conv_out_size(H, dilation * (KH - 1) + 1, stride, pad);
     int64_t OW = conv_out_size(W_, dilation * (KW - 1) + 1, stride, pad);
@@ -230,11 +235,11 @@ int ms_oracle_conv2d_nhwc(int dtype, int64_t N, int64_t H, int64_t W_, int64_t C
                     int64_t ih = oh * stride + kh * dilation - pad;
                     for (int64_t kw = 0; kw < KW; ++kw) {
                         int64_t iw = ow * stride + kw * dilation - pad;
-                        for (int64_t ci = 0; ci < Cin; ++ci) {
+                        for (int64_t ci = 0; ci < Cg; ++ci) {
                             double x = 0.0;
                             if (ih >= 0 && ih < H && iw >= 0 && iw < W_)
-                                x = load_elem(dtype, X, ((n * H + ih) * W_ + iw) * Cin + ci);
-                            double w = load_elem(dtype, Wt, ((kh * KW + kw) * Cin + ci) * Cout + co);
+                                x = load_elem(dtype, X, ((n * H + ih) * W_ + iw) * Cin + (co / Ng) * Cg + ci);
+                            double w = load_elem(dtype, Wt, ((kh * KW + kw) * Cg + ci) * Cout + co);
                             acc += x * w;
                         }
                     }

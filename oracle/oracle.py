@@ -33,7 +33,7 @@ def lib():
         L.ms_oracle_conv_out_size.restype = i64
         L.ms_oracle_conv_out_size.argtypes = [i64, i64, i64, i64]
         L.ms_oracle_conv2d_nhwc.restype = C.c_int
-        L.ms_oracle_conv2d_nhwc.argtypes = [C.c_int] + [i64] * 10 + [vp, vp, vp, C.c_int, vp]
+        L.ms_oracle_conv2d_nhwc.argtypes = [C.c_int] + [i64] * 11 + [vp, vp, vp, C.c_int, vp]
         L.ms_oracle_conv2d_transposed_nhwc.restype = C.c_int
         L.ms_oracle_conv2d_transposed_nhwc.argtypes = [C.c_int] + [i64] * 9 + [vp, vp, vp, C.c_int, vp]
         L.ms_oracle_dwconv2d_nhwc.restype = C.c_int
@@ -123,13 +123,13 @@ def conv_out_size(n, k, s, p):
     return int(lib().ms_oracle_conv_out_size(n, k, s, p))
 
 
-def conv2d_nhwc(X, Wt, bias=None, relu=False, stride=1, pad=0, bf16=False, dilation=1):
-    """X [N,H,W,Cin], Wt [KH,KW,Cin,Cout], bias fp32 [Cout] or None; taps `dilation` elements apart."""
+def conv2d_nhwc(X, Wt, bias=None, relu=False, stride=1, pad=0, bf16=False, dilation=1, groups=1):
+    """X [N,H,W,Cin], Wt [KH,KW,Cin/groups,Cout], bias fp32 [Cout] or None; taps `dilation` elements apart."""
     X = np.ascontiguousarray(X)
     Wt = np.ascontiguousarray(Wt)
     N, H, W_, Cin = X.shape
     KH, KW, Cin2, Cout = Wt.shape
-    assert Cin2 == Cin and X.dtype == Wt.dtype
+    assert Cin2 * groups == Cin and Cout % groups == 0 and X.dtype == Wt.dtype
     OH, OW = conv_out_size(H, dilation * (KH - 1) + 1, stride, pad), conv_out_size(W_, dilation * (KW - 1) + 1, stride, pad)
     out = np.empty((N, OH, OW, Cout), np.float64)
     bptr = None
@@ -137,7 +137,7 @@ def conv2d_nhwc(X, Wt, bias=None, relu=False, stride=1, pad=0, bf16=False, dilat
         bias = np.ascontiguousarray(bias, dtype=np.float32)
         assert bias.shape == (Cout,)
         bptr = _ptr(bias)
-    rc = lib().ms_oracle_conv2d_nhwc(_dtype_code(X, bf16), N, H, W_, Cin, Cout, KH, KW, stride, pad, dilation,
+    rc = lib().ms_oracle_conv2d_nhwc(_dtype_code(X, bf16), N, H, W_, Cin, Cout, KH, KW, stride, pad, dilation, groups,
                                      _ptr(X), _ptr(Wt), bptr, int(bool(relu)), _ptr(out))
     if rc != 0:
         raise RuntimeError("oracle conv2d failed")

@@ -513,3 +513,31 @@ def test_transposed_conv_closed_forms():
     # all ones, 2x2 filter, stride 1: every output counts the inputs that reach it (1, 2 or 4)
     y = O.conv2d_transposed_nhwc(np.ones((1, 3, 3, 1), np.float16), np.ones((2, 2, 1, 1), np.float16), stride=1, pad=0)
     assert np.array_equal(y[0, :, :, 0], [[1, 2, 2, 1], [2, 4, 4, 2], [2, 4, 4, 2], [1, 2, 2, 1]])
+
+
+# ---------------------------------------------------------------- grouped conv2d (Appendix A.2: GRP)
+
+@pytest.mark.parametrize("groups,stride,pad,k", [(4, 2, 1, 3), (2, 1, 0, 1), (3, 1, 1, 3)])
+def test_grouped_conv_vs_torch_cpu_and_vs_block_diagonal_weights(groups, stride, pad, k):
+    import torch
+    g = np.random.default_rng(80 + groups)
+    N, H, W_, Cin, Cout = 2, 7, 6, 12, 24
+    Cg, Ng = Cin // groups, Cout // groups
+    X = g.standard_normal((N, H, W_, Cin)).astype(np.float32)
+    Wt = g.standard_normal((k, k, Cg, Cout)).astype(np.float32)
+    bias = g.standard_normal(Cout).astype(np.float32)
+    got = O.conv2d_nhwc(X, Wt, bias=bias, relu=False, stride=stride, pad=pad, groups=groups)
+    # library routine: weight (Cout, Cin/groups, KH, KW)
+    ref = torch.nn.functional.conv2d(torch.from_numpy(X).double().permute(0, 3, 1, 2), torch.from_numpy(Wt).double().permute(3, 2, 0, 1),
+                                     torch.from_numpy(bias).double(), stride=stride, padding=pad, groups=groups)
+    np.testing.assert_allclose(got, ref.permute(0, 2, 3, 1).numpy(), rtol=1e-12, atol=1e-12)
+    # the same operator as a dense convolution whose weights are zero outside the diagonal blocks
+    Wd = np.zeros((k, k, Cin, Cout), np.float32)
+    for q in range(groups):
+        Wd[:, :, q * Cg:(q + 1) * Cg, q * Ng:(q + 1) * Ng] = Wt[:, :, :, q * Ng:(q + 1) * Ng]
+    np.testing.assert_allclose(got, O.conv2d_nhwc(X, Wd, bias=bias, stride=stride, pad=pad), rtol=1e-13, atol=1e-13)
+    # groups == channels with one output per group is the depthwise operator
+    Xd = g.standard_normal((1, 6, 6, 5)).astype(np.float32)
+    Wdw = g.standard_normal((3, 3, 5)).astype(np.float32)
+    np.testing.assert_allclose(O.conv2d_nhwc(Xd, Wdw.reshape(3, 3, 1, 5), stride=1, pad=1, groups=5),
+                               O.dwconv2d_nhwc(Xd, Wdw, stride=1, pad=1), rtol=1e-13, atol=1e-13)
