@@ -86,7 +86,8 @@ typedef enum ms_dtype { MS_F32 = 0, MS_F16 = 1, MS_BF16 = 2, MS_I8 = 3, MS_I32 =
  * dims:
  *   GEMM            M, N, K
  *   BMM_NT, BMM_NN  B, M, N, K
- *   CONV2D_NHWC     N, H, W, Cin, Cout, KH, KW
+ *   CONV2D_NHWC     N, H, W, Cin, Cout, KH, KW, groups   (groups 0 or 1: dense.  groups G > 1 (GRP): output channel co
+ *                   sums over the Cin/G input channels of group co / (Cout/G) only; W is [KH][KW][Cin/G][Cout])
  *   DWCONV2D_NHWC   N, H, W, C, KH, KW
  *   CONV2D_TRANSPOSED_NHWC  N, H, W, Cin, Cout, KH, KW   (input element (ih, iw) contributes X * W[kh][kw] to output
  *                           (ih*stride + kh - pad, iw*stride + kw - pad); output size (H-1)*stride - 2*pad + KH;

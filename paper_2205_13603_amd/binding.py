@@ -269,8 +269,10 @@ def bmm_op(B, M, N, K, trans_b, in_dtype="f16", out_dtype=None, **kw):
               [B, M, N, K], **kw)
 
 
-def conv2d_op(N, H, W, Cin, Cout, KH, KW, stride=1, pad=0, has_bias=True, relu=True, in_dtype="f16", out_dtype=None, dilation=1):
-    return Op(OP_CONV2D_NHWC, in_dtype, out_dtype or in_dtype, [N, H, W, Cin, Cout, KH, KW], stride=stride, pad=pad,
+def conv2d_op(N, H, W, Cin, Cout, KH, KW, stride=1, pad=0, has_bias=True, relu=True, in_dtype="f16", out_dtype=None, dilation=1,
+              groups=1):
+    """groups > 1: W is [KH][KW][Cin/groups][Cout] and an output channel sees the input channels of its own group."""
+    return Op(OP_CONV2D_NHWC, in_dtype, out_dtype or in_dtype, [N, H, W, Cin, Cout, KH, KW] + ([groups] if groups > 1 else []), stride=stride, pad=pad,
               has_bias=has_bias, relu=relu, dilation=dilation)
 
 

@@ -66,6 +66,19 @@
 #ifndef CV_TRANSPOSED
 #define CV_TRANSPOSED 0
 #endif
+// Grouped conv2d: the batch index of the launch is the group.  A group reads CV_CIN of the CV_XC channels of a pixel
+// (offset SA_B per group), DIM_N of the LDC output channels (weights, bias and output offset by DIM_N per group).
+#ifndef LDC
+#define LDC DIM_N                  // elements between two rows of the output = bias values per instance
+#endif
+#ifndef C_BATCH
+#define C_BATCH ((long)DIM_M * DIM_N) // output elements between two batch entries
+#endif
+#if IS_CONV
+#ifndef CV_XC
+#define CV_XC CV_CIN               // channels per pixel of X
+#endif
+#endif
 
 #define NWAVES (I2 * J2)
 #define LANE_GROUPS (64 / MI_M)
@@ -232,6 +245,7 @@ constexpr bool K_PADDED = K0 * BK != CV_KREAL;
 static_assert(K0 * BK >= CV_KREAL && K0 * BK - CV_KREAL < MI_K, "the k split covers the reduction, padded by less than one intrinsic");
 static_assert(!K_PADDED || COMPUTE_AT == 0, "a padded reduction needs the im2col loader");
 static_assert(!CV_TRANSPOSED || (COMPUTE_AT == 0 && CV_DIL == 1), "the transposed convolution exists in the im2col loader only");
+static_assert(DIM_B == 1 || COMPUTE_AT == 0, "grouped convolution exists in the im2col loader only");
 // im2col on the fly: row = output pixel, k = (kh, kw, ci)
 template <int V> __device__ __forceinline__ vec_t<in_t, V> load_conv_a(const in_t *__restrict__ X, int row, int k)
 {
@@ -248,7 +262,7 @@ template <int V> __device__ __forceinline__ vec_t<in_t, V> load_conv_a(const in_
 #endif
     vec_t<in_t, V> x;
     if (ih >= 0 && ih < CV_H && iw >= 0 && iw < CV_W && (!K_PADDED || k < CV_KREAL)) {
-        x = *reinterpret_cast<const vec_t<in_t, V> *>(X + (((long)n * CV_H + ih) * CV_W + iw) * CV_CIN + ci);
+        x = *reinterpret_cast<const vec_t<in_t, V> *>(X + (((long)n * CV_H + ih) * CV_W + iw) * CV_XC + ci);
     } else {
 #pragma unroll
         for (int q = 0; q < V; ++q) x.v[q] = 0;
@@ -878,7 +892,7 @@ __device__ __forceinline__ void flush_cstage(out_t *__restrict__ C, int i0, int 
     for (int idx = t; idx < TOTAL; idx += NT) {
         const int row = idx / CHUNKS_PER_ROW, ch = idx % CHUNKS_PER_ROW;
         const chunk_t v = *reinterpret_cast<const chunk_t *>(cstage + row * CROW + ch * 16);
-        char *dst = (char *)(C + ((long)i0 * BM + row) * DIM_N + (long)j0 * BN) + ch * 16;
+        char *dst = (char *)(C + ((long)i0 * BM + row) * LDC + (long)j0 * BN) + ch * 16;
         *reinterpret_cast<chunk_t *>(dst) = v;
     }
 }
@@ -910,7 +924,7 @@ __device__ __forceinline__ void write_tile(accv_t (&acc)[TM][TN], out_t *__restr
                         const long col = (long)j0 * BN + lc;
                         vec_t<out_t, 4> o;
 #if HAS_BIAS
-                        const vec_t<float, 4> bias = *reinterpret_cast<const vec_t<float, 4> *>((const float *)bias_ + (long)inst * DIM_N + col);
+                        const vec_t<float, 4> bias = *reinterpret_cast<const vec_t<float, 4> *>((const float *)bias_ + (long)inst * LDC + col);
 #endif
 #pragma unroll
                         for (int e = 0; e < 4; ++e) {
@@ -926,7 +940,7 @@ __device__ __forceinline__ void write_tile(accv_t (&acc)[TM][TN], out_t *__restr
 #if CACHE_WRITE
                         *reinterpret_cast<vec_t<out_t, 4> *>(cstage + lr * CROW + lc * (int)sizeof(out_t)) = o;
 #else
-                        *reinterpret_cast<vec_t<out_t, 4> *>(C + ((long)i0 * BM + lr) * DIM_N + col) = o;
+                        *reinterpret_cast<vec_t<out_t, 4> *>(C + ((long)i0 * BM + lr) * LDC + col) = o;
 #endif
                     }
                 }
@@ -1240,7 +1254,10 @@ ms_kernel(const void *__restrict__ a_, const void *__restrict__ b_, const void *
     if (inst >= instances) return;
     const in_t *__restrict__ A = (const in_t *)a_ + (long)inst * A_INST + (long)bb * SA_B;
     const in_t *__restrict__ B = (const in_t *)b_ + (long)inst * B_INST + (long)bb * SB_B;
-    out_t *__restrict__ C = (out_t *)c_ + ((long)inst * DIM_B + bb) * ((long)DIM_M * DIM_N);
+    out_t *__restrict__ C = (out_t *)c_ + (long)inst * ((long)DIM_B * DIM_M * DIM_N) + (long)bb * C_BATCH;
+#if IS_CONV && HAS_BIAS
+    bias_ = (const float *)bias_ + (long)bb * DIM_N; // the group's slice of the bias
+#endif
 
     const int tid = threadIdx.x;
     const int lane = tid % 64, wave = tid / 64;

@@ -273,9 +273,14 @@ extern "C" int32_t ms_op_create(const ms_op_desc *desc, ms_op **out)
         if (op.OH < 1 || op.OW < 1) return fail(MS_ERR_BAD_ARG, "ms_op_create: empty convolution output");
         if (is_conv2d(d.kind)) {
             if (d.in_dtype == MS_I8) return fail(MS_ERR_UNSUPPORTED, "ms_op_create: int8 conv2d is not supported");
+            // dims[7] = groups (0 or 1: a dense convolution); a group is a batch entry of the implicit GEMM
+            const int64_t G = d.dims[7] ? d.dims[7] : 1;
+            if (G < 1 || d.dims[3] % G || d.dims[4] % G) return fail(MS_ERR_BAD_ARG, "ms_op_create: %" PRId64 " groups do not divide the channel counts", G);
+            if (G > 1 && d.kind == MS_OP_CONV2D_TRANSPOSED_NHWC) return fail(MS_ERR_UNSUPPORTED, "ms_op_create: the transposed convolution has no groups");
+            op.nb = G;
             op.M = d.dims[0] * op.OH * op.OW;
-            op.N = d.dims[4];
-            op.K = KH * KW * d.dims[3];
+            op.N = d.dims[4] / G;
+            op.K = KH * KW * (d.dims[3] / G);
         } else {
             if (d.in_dtype != MS_F32) return fail(MS_ERR_UNSUPPORTED, "ms_op_create: depthwise conv is fp32 only");
             if (d.has_bias || d.relu) return fail(MS_ERR_UNSUPPORTED, "ms_op_create: depthwise has no epilogue");
@@ -322,6 +327,7 @@ extern "C" int32_t ms_op_loops(const ms_op *op, ms_loop *loops, int32_t *n_loops
         break;
     case MS_OP_CONV2D_NHWC:
     case MS_OP_CONV2D_TRANSPOSED_NHWC:
+        if (op->nb > 1) set_loop(&loops[n++], "g", op->nb, 0); // groups
         set_loop(&loops[n++], "i", op->M, 0); // fuse(n, oh, ow)
         set_loop(&loops[n++], "j", op->N, 0); // co
         set_loop(&loops[n++], "k", op->K, 1); // fuse(kh, kw, ci)
@@ -366,9 +372,9 @@ extern "C" int32_t ms_op_tensor_bytes(const ms_op *op, int32_t idx, int64_t *byt
         break;
     case MS_OP_CONV2D_NHWC:
     case MS_OP_CONV2D_TRANSPOSED_NHWC:
-        if (idx < 0) e = op->M * op->N;
+        if (idx < 0) e = op->M * op->N * op->nb;
         else if (idx == 0) e = d.dims[0] * d.dims[1] * d.dims[2] * d.dims[3];
-        else if (idx == 1) e = d.dims[5] * d.dims[6] * d.dims[3] * d.dims[4];
+        else if (idx == 1) e = op->K * op->N * op->nb; // [KH][KW][Cin / groups][Cout]
         else if (idx == 2 && d.has_bias) { e = d.dims[4]; sz = 4; }
         break;
     case MS_OP_DWCONV2D_NHWC:
@@ -408,9 +414,9 @@ extern "C" int32_t ms_op_work(const ms_op *op, double *flop, double *bytes)
             (d.has_bias ? 4.0 * op->N : 0.0) + (double)op->M * op->N * op->out_size;
         break;
     case MS_OP_CONV2D_NHWC:
-        f = 2.0 * op->M * op->N * op->K;
-        b = (double)(d.dims[0] * d.dims[1] * d.dims[2] * d.dims[3] + op->K * op->N) * op->in_size +
-            (d.has_bias ? 4.0 * op->N : 0.0) + (double)op->M * op->N * op->out_size;
+        f = 2.0 * op->M * op->N * op->K * op->nb;
+        b = (double)(d.dims[0] * d.dims[1] * d.dims[2] * d.dims[3] + op->K * op->N * op->nb) * op->in_size +
+            (d.has_bias ? 4.0 * op->N * op->nb : 0.0) + (double)op->M * op->N * op->nb * op->out_size;
         break;
     case MS_OP_DWCONV2D_NHWC: {
         double outs = (double)d.dims[0] * op->OH * op->OW * d.dims[3];
@@ -569,9 +575,9 @@ extern "C" int32_t ms_space_describe(const ms_op *op, uint32_t flags, ms_space *
             for (int i = 0; i < out->n_slots; ++i) {
                 ms_slot &sl = out->slots[i];
                 for (int c = 0; c < sl.n_candidates; ++c) {
-                    if (sl.slot_id == MS_SLOT_VECTORIZE && d.dims[3] % sl.candidates[c]) sl.weight[c] = 0;
-                    if (sl.slot_id == MS_SLOT_VECTORIZE_B && d.dims[4] % sl.candidates[c]) sl.weight[c] = 0;
-                    if (sl.slot_id == MS_SLOT_COMPUTE_AT && sl.candidates[c] > 0 && d.dims[3] % 8) sl.weight[c] = 0;
+                    if (sl.slot_id == MS_SLOT_VECTORIZE && (d.dims[3] / op->nb) % sl.candidates[c]) sl.weight[c] = 0;
+                    if (sl.slot_id == MS_SLOT_VECTORIZE_B && op->N % sl.candidates[c]) sl.weight[c] = 0;
+                    if (sl.slot_id == MS_SLOT_COMPUTE_AT && sl.candidates[c] > 0 && (d.dims[3] % 8 || op->nb > 1)) sl.weight[c] = 0;
                 }
             }
         }

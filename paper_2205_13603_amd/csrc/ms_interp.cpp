@@ -235,6 +235,7 @@ extern "C" int32_t ms_trace_validate(const ms_op *op, const ms_space *space, con
                 if (p.compute_at) return reject("KH*KW*Cin = %" PRId64 " is not a multiple of the intrinsic's k = %d: compute_at must be 0", op->K, p.tile_unit[2]);
                 if (p.cache_read >= 5) return reject("a padded reduction cannot be staged directly to LDS");
             }
+            if (is_conv2d(d.kind) && op->nb > 1 && p.compute_at) return reject("grouped convolution: compute_at must be 0");
             if (p.compute_at) {
                 // conv2d with the activations' cache-read under the workgroup tile loop: the input rows of
                 // the tile (zero halo included) are resident, only the weights are staged per k step
@@ -336,7 +337,7 @@ extern "C" int32_t ms_trace_validate(const ms_op *op, const ms_space *space, con
             int v = p.vec;
             if (v * es > 16) return reject("vector of %d x %d bytes is wider than a 16-byte load", v, es);
             if (is_conv2d(d.kind)) {
-                if (d.dims[3] % v) return reject("vector width %d does not divide Cin = %" PRId64, v, d.dims[3]);
+                if ((d.dims[3] / op->nb) % v) return reject("vector width %d does not divide Cin = %" PRId64 " (per group)", v, d.dims[3] / op->nb);
                 if (bk % v) return reject("vector width %d does not divide the k tile %" PRId64, v, bk);
             } else {
                 if (d.a_strides[2] != 1) return reject("vector loads of A need k contiguous");
@@ -348,7 +349,7 @@ extern "C" int32_t ms_trace_validate(const ms_op *op, const ms_space *space, con
             int v = p.vec_b;
             if (v * es > 16) return reject("vector of %d x %d bytes is wider than a 16-byte load", v, es);
             if (is_conv2d(d.kind)) {
-                if (d.dims[4] % v) return reject("vector width %d does not divide Cout = %" PRId64, v, d.dims[4]);
+                if (op->N % v) return reject("vector width %d does not divide Cout = %" PRId64 " (per group)", v, op->N);
                 if (bn % v) return reject("vector width %d does not divide the j tile %" PRId64, v, bn);
             } else if (d.b_strides[2] == 1) { // vector along j
                 if (bn % v || d.b_strides[1] % v || (op->nb > 1 && d.b_strides[0] % v))
@@ -499,8 +500,11 @@ int32_t make_kernel_spec(const ms_op *op, const ms_variant_params *p, KernelSpec
             D.push_back(def("CV_N", d.dims[0]));
             D.push_back(def("CV_H", d.dims[1]));
             D.push_back(def("CV_W", d.dims[2]));
-            D.push_back(def("CV_CIN", d.dims[3]));
+            D.push_back(def("CV_CIN", d.dims[3] / op->nb)); // channels a group reduces over
+            D.push_back(def("CV_XC", d.dims[3]));           // channels per pixel of X
             D.push_back(def("CV_COUT", d.dims[4]));
+            D.push_back(def("LDC", d.dims[4]));             // output channels per pixel of Y = bias values per instance
+            D.push_back(def("C_BATCH", op->N));             // a group's outputs start op->N channels after the previous group's
             D.push_back(def("CV_KH", d.dims[5]));
             D.push_back(def("CV_KW", d.dims[6]));
             D.push_back(def("CV_OH", op->OH));
@@ -512,14 +516,14 @@ int32_t make_kernel_spec(const ms_op *op, const ms_variant_params *p, KernelSpec
             D.push_back(def("HAS_BIAS", d.has_bias ? 1 : 0));
             D.push_back(def("RELU", d.relu ? 1 : 0));
             // implicit GEMM view: A rows are output pixels, B = W as [K][N]
-            D.push_back(def("SA_B", 0));
+            D.push_back(def("SA_B", d.dims[3] / op->nb)); // channel offset of a group
             D.push_back(def("SA_I", 0));
             D.push_back(def("SA_K", 1));
-            D.push_back(def("SB_B", 0));
+            D.push_back(def("SB_B", op->N));              // column offset of a group in W [K][Cout]
             D.push_back(def("SB_K", d.dims[4]));
             D.push_back(def("SB_J", 1));
             D.push_back(def("A_INST", d.dims[0] * d.dims[1] * d.dims[2] * d.dims[3]));
-            D.push_back(def("B_INST", op->K * op->N));
+            D.push_back(def("B_INST", op->K * op->N * op->nb));
         } else {
             D.push_back(def("HAS_BIAS", 0));
             D.push_back(def("RELU", 0));
@@ -604,7 +608,8 @@ extern "C" int32_t ms_variant_coverage(const ms_op *op, const ms_variant_params 
                                         for (int c = 0; c < un; ++c) {
                                             int64_t i = iu * um + a, j = ju * un + c;
                                             if (i >= op->M || j >= op->N) return fail(MS_ERR_INVALID_TRACE, "coverage: index out of range");
-                                            ++counts[(b * op->M + i) * op->N + j];
+                                            if (is_conv2d(op->d.kind)) ++counts[i * (op->N * op->nb) + b * op->N + j]; // groups interleave per pixel
+                                            else ++counts[(b * op->M + i) * op->N + j];
                                         }
                                 }
                 }

@@ -308,3 +308,45 @@ def test_t2d_config_transposed_conv_4x4x512(dtype):
         if got is None:
             continue
         compare.assert_float_close(got, ref, compare.RTOL_HALF, "T2D %s trace %d" % (dtype, n))
+
+
+@pytest.mark.parametrize("groups,Cin,Cout,k,stride,pad", [(4, 64, 128, 3, 2, 1), (2, 16, 64, 3, 1, 1), (8, 64, 128, 1, 1, 0), (3, 48, 96, 3, 1, 1)])
+def test_grouped_conv_exact(groups, Cin, Cout, k, stride, pad):
+    """Grouped convolution (Appendix A.2: GRP): a group is a batch entry of the implicit GEMM, reading its slice of the
+    channels of X, its columns of W and the bias, and writing its slice of the channels of Y.  Integer-valued inputs,
+    batch 2, 2 instances: bit-equal fp32 outputs."""
+    N, H, W_ = 2, 16, 8
+    g = I.rng(81)
+    X = I.small_ints(g, (N, H, W_, Cin), -2, 2, "f16")
+    Wt = I.small_ints(g, (k, k, Cin // groups, Cout), -2, 2, "f16")
+    bias = g.integers(-3, 4, size=Cout).astype(np.float32)
+    ref = O.conv2d_nhwc(X, Wt, bias=bias, relu=True, stride=stride, pad=pad, groups=groups)
+    OH, OW = ref.shape[1], ref.shape[2]
+    op = B.conv2d_op(N, H, W_, Cin, Cout, k, k, stride=stride, pad=pad, out_dtype="f32", groups=groups)
+    space = op.space()
+    for n in range(8):
+        t = B.trace_sample_valid(op, space, 82, n)
+        assert B.trace_validate(op, space, t).compute_at == 0
+        print("trace", n, t.decisions(), flush=True)
+        got = run_variant(op, space, t, [X, Wt, bias], "f32", (N, OH, OW, Cout), instances=2)
+        if got is None:
+            continue
+        assert np.array_equal(got[0], ref) and np.array_equal(got[1], ref), "trace %d" % n
+
+
+def test_grp_config_grouped_conv_56x56x64_to_128():
+    """The paper's GRP shape: 56 x 56 x 64 -> 28 x 28 x 128, 3 x 3, stride 2, padding 1, 4 groups; fp16."""
+    g = I.rng(83)
+    X = I.uniform(g, (1, 56, 56, 64), 0.0, 1.0, "f16")
+    Wt = I.normal(g, (3, 3, 16, 128), 0.05, "f16")
+    bias = I.normal(g, (128,), 0.05, "f32")
+    ref = O.conv2d_nhwc(X, Wt, bias=bias, relu=True, stride=2, pad=1, groups=4)
+    op = B.conv2d_op(1, 56, 56, 64, 128, 3, 3, stride=2, pad=1, groups=4)
+    space = op.space()
+    for n in range(8):
+        t = B.trace_sample_valid(op, space, 84, n)
+        print("trace", n, t.decisions(), flush=True)
+        got = run_variant(op, space, t, [X, Wt, bias], "f16", ref.shape)
+        if got is None:
+            continue
+        compare.assert_float_close(got, ref, compare.RTOL_HALF, "GRP trace %d" % n)

@@ -466,3 +466,28 @@ def test_transposed_conv_descriptor_and_space():
         B.Op(B.OP_CONV2D_TRANSPOSED_NHWC, "f16", "f16", [1, 4, 4, 8, 8, 3, 3], stride=1, pad=0, dilation=2)
     with pytest.raises(B.MsError):
         B.conv2d_transposed_op(1, 1, 1, 8, 8, 2, 2, stride=1, pad=1)   # empty output
+
+
+def test_grouped_conv_descriptor_space_and_coverage():
+    op = B.conv2d_op(1, 56, 56, 64, 128, 3, 3, stride=2, pad=1, groups=4)
+    assert op.loops() == [("g", 4, False), ("i", 784, False), ("j", 32, False), ("k", 144, True)]
+    assert op.tensor_bytes(1) == 3 * 3 * 16 * 128 * 2 and op.tensor_bytes(-1) == 784 * 128 * 2 and op.tensor_bytes(2) == 128 * 4
+    assert op.work()[0] == 2.0 * 784 * 128 * 144
+    sp = op.space()
+    ca = [sp.slots[i] for i in range(sp.n_slots) if sp.slots[i].name == b"compute_at"][0]
+    assert list(ca.weight)[:5] == [1, 0, 0, 0, 0]
+    for idx in range(10):
+        t = B.trace_sample_valid(op, sp, 7, idx)
+        p = B.trace_validate(op, sp, t)
+        assert p.grid[2] == 4 and p.compute_at == 0
+        cov = B.variant_coverage(op, p, 784 * 128)
+        assert cov.min() == 1 and cov.max() == 1
+    with pytest.raises(B.MsError):
+        B.conv2d_op(1, 8, 8, 30, 64, 3, 3, groups=4)          # 4 does not divide 30
+    with pytest.raises(B.MsError):
+        B.Op(B.OP_CONV2D_TRANSPOSED_NHWC, "f16", "f16", [1, 4, 4, 16, 16, 2, 2, 2], stride=1, pad=0)
+    # a dense convolution is unchanged by the new field: same kernel key with groups 0 and 1
+    d0, d1 = B.conv2d_op(1, 8, 8, 16, 32, 3, 3, pad=1), B.conv2d_op(1, 8, 8, 16, 32, 3, 3, pad=1, groups=1)
+    s0 = d0.space()
+    t = B.trace_sample_valid(d0, s0, 1, 0)
+    assert B.trace_validate(d0, s0, t).key == B.trace_validate(d1, d1.space(), t).key
