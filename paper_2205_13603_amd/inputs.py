@@ -164,3 +164,10 @@ def t2d(seed=0, dtype="f16"):
     X ~ N(0, 1), W ~ N(0, 0.05), bias ~ N(0, 0.05) fp32."""
     g = rng(seed)
     return (normal(g, (1, 4, 4, 512), 1.0, dtype), normal(g, (4, 4, 512, 256), 0.05, dtype), normal(g, (256,), 0.05, "f32"))
+
+
+def grp(seed=0, dtype="f16"):
+    """Grouped convolution workload (56 x 56 x 64 -> 28 x 28 x 128, 3 x 3, stride 2, padding 1, 4 groups):
+    X ~ U[0, 1], W ~ N(0, 0.05) as [3][3][16][128], bias ~ N(0, 0.05) fp32."""
+    g = rng(seed)
+    return (uniform(g, (1, 56, 56, 64), 0.0, 1.0, dtype), normal(g, (3, 3, 16, 128), 0.05, dtype), normal(g, (128,), 0.05, "f32"))
