@@ -171,3 +171,9 @@ def grp(seed=0, dtype="f16"):
     X ~ U[0, 1], W ~ N(0, 0.05) as [3][3][16][128], bias ~ N(0, 0.05) fp32."""
     g = rng(seed)
     return (uniform(g, (1, 56, 56, 64), 0.0, 1.0, dtype), normal(g, (3, 3, 16, 128), 0.05, dtype), normal(g, (128,), 0.05, "f32"))
+
+
+def c2nt(seed=0, dtype="f16"):
+    """Config 2 with the second operand stored transposed: A [1][1024][1024], B [1][N][K], 0.1 * N(0, 1)."""
+    g = rng(seed)
+    return (normal(g, (1, 1024, 1024), 0.1, dtype), normal(g, (1, 1024, 1024), 0.1, dtype))
