@@ -245,7 +245,7 @@ constexpr bool K_PADDED = K0 * BK != CV_KREAL;
 static_assert(K0 * BK >= CV_KREAL && K0 * BK - CV_KREAL < MI_K, "the k split covers the reduction, padded by less than one intrinsic");
 static_assert(!K_PADDED || COMPUTE_AT == 0, "a padded reduction needs the im2col loader");
 static_assert(!CV_TRANSPOSED || (COMPUTE_AT == 0 && CV_DIL == 1), "the transposed convolution exists in the im2col loader only");
-static_assert(DIM_B == 1 || COMPUTE_AT == 0, "grouped convolution exists in the im2col loader only");
+static_assert(DIM_B == 1 || COMPUTE_AT <= 1, "grouped convolution: im2col staging or the resident patch of one tile; the persistent modes have no group loop");
 // im2col on the fly: row = output pixel, k = (kh, kw, ci)
 template <int V> __device__ __forceinline__ vec_t<in_t, V> load_conv_a(const in_t *__restrict__ X, int row, int k)
 {
@@ -450,7 +450,7 @@ __device__ __forceinline__ void patch_map_init(patch_map &pm, int tid)
         const int q = P_NT >= P_CR ? tid % P_CR : s * P_NT + tid;
         const int pc = q / P_CPP, c = q % P_CPP;
         const int iw = pc - CV_PAD;
-        pm.goff[s] = iw * CV_CIN + c * VEC;
+        pm.goff[s] = iw * CV_XC + c * VEC;
         pm.loff[s] = pc * P_PS + c * (VEC * ES);
         pm.ok[s] = q < P_CR && pm.row_t < P_RPP && (unsigned)iw < (unsigned)CV_W;
     }
@@ -462,7 +462,7 @@ __device__ __forceinline__ void patch_fetch(patch_regs &pr, const patch_map &pm,
     const int m0 = i0 * BM;
     const int n = m0 / (CV_OH * CV_OW);
     const int ih_lo = ((m0 % (CV_OH * CV_OW)) / CV_OW) * CV_STRIDE - CV_PAD;
-    const in_t *img = X + (long)n * (CV_H * CV_W * CV_CIN);
+    const in_t *img = X + (long)n * (CV_H * CV_W * CV_XC);
 #pragma unroll
     for (int p = 0; p < P_PASSES; ++p)
 #pragma unroll
@@ -471,7 +471,7 @@ __device__ __forceinline__ void patch_fetch(patch_regs &pr, const patch_map &pm,
             const int ih = ih_lo + row;
             const bool ok = pm.ok[s] && (unsigned)ih < (unsigned)CV_H && (P_R % P_RPP == 0 || row < P_R);
             // elements outside the image read element 0 (always mapped) and become zero: no divergent loads
-            const int off = ok ? ih * (CV_W * CV_CIN) + pm.goff[s] : 0;
+            const int off = ok ? ih * (CV_W * CV_XC) + pm.goff[s] : 0;
             vec_t<in_t, VEC> x = *reinterpret_cast<const vec_t<in_t, VEC> *>(img + off);
             if (!ok) {
 #pragma unroll

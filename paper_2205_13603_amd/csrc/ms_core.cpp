@@ -577,7 +577,9 @@ extern "C" int32_t ms_space_describe(const ms_op *op, uint32_t flags, ms_space *
                 for (int c = 0; c < sl.n_candidates; ++c) {
                     if (sl.slot_id == MS_SLOT_VECTORIZE && (d.dims[3] / op->nb) % sl.candidates[c]) sl.weight[c] = 0;
                     if (sl.slot_id == MS_SLOT_VECTORIZE_B && op->N % sl.candidates[c]) sl.weight[c] = 0;
-                    if (sl.slot_id == MS_SLOT_COMPUTE_AT && sl.candidates[c] > 0 && (d.dims[3] % 8 || op->nb > 1)) sl.weight[c] = 0;
+                    if (sl.slot_id == MS_SLOT_COMPUTE_AT && sl.candidates[c] > 0 &&
+                        ((d.dims[3] / op->nb) % 8 || (op->nb > 1 && sl.candidates[c] > 1)))
+                        sl.weight[c] = 0;
                 }
             }
         }

@@ -235,7 +235,7 @@ extern "C" int32_t ms_trace_validate(const ms_op *op, const ms_space *space, con
                 if (p.compute_at) return reject("KH*KW*Cin = %" PRId64 " is not a multiple of the intrinsic's k = %d: compute_at must be 0", op->K, p.tile_unit[2]);
                 if (p.cache_read >= 5) return reject("a padded reduction cannot be staged directly to LDS");
             }
-            if (is_conv2d(d.kind) && op->nb > 1 && p.compute_at) return reject("grouped convolution: compute_at must be 0");
+            if (is_conv2d(d.kind) && op->nb > 1 && p.compute_at > 1) return reject("grouped convolution: compute_at must be 0 or 1 (the persistent modes have no group loop)");
             if (p.compute_at) {
                 // conv2d with the activations' cache-read under the workgroup tile loop: the input rows of
                 // the tile (zero halo included) are resident, only the weights are staged per k step
@@ -245,7 +245,7 @@ extern "C" int32_t ms_trace_validate(const ms_op *op, const ms_space *space, con
                 if (p.compute_at == 3 && (p.cache_read != 2 || !p.cache_write))
                     return reject("helper wavefronts prefetch the patch and write the staged tile: cache_read 2 and cache_write 1");
                 if (p.compute_at >= 2 && p.reorder != 0) return reject("persistent workgroups with resident weights walk the tile list in order: reorder must be 0");
-                int64_t cin = d.dims[3], ohw = op->OH * op->OW;
+                int64_t cin = d.dims[3] / op->nb, ohw = op->OH * op->OW; // channels of one group
                 if (cin % p.tile_unit[2]) return reject("resident input patch: Cin = %" PRId64 " is not a multiple of the intrinsic's k = %d", cin, p.tile_unit[2]);
                 if (ohw % bm) return reject("resident input patch: the %" PRId64 "-pixel tile straddles images of %" PRId64 " output pixels", bm, ohw);
                 int64_t rows = bm % op->OW == 0 ? bm / op->OW : (op->OW + bm - 2) / op->OW + 1;
@@ -260,7 +260,7 @@ extern "C" int32_t ms_trace_validate(const ms_op *op, const ms_space *space, con
                     if (p.cache_read > 2) return reject("with the weights in registers cache_read is 1 (patch loaded between tiles) or 2 (next patch prefetched)");
                 }
                 if ((cin * es) % 16 && p.lds_pad) return reject("resident input patch: padded pixels need Cin * element size to be a multiple of 16 bytes");
-                if (d.dims[0] * d.dims[1] * d.dims[2] * cin > 0x7fffffff / es) return reject("resident input patch: one instance of X exceeds 32-bit byte offsets");
+                if (d.dims[0] * d.dims[1] * d.dims[2] * d.dims[3] > 0x7fffffff / es) return reject("resident input patch: one instance of X exceeds 32-bit byte offsets");
             }
             if (p.reorder == 3 && p.cache_read < 5) return reject("persistent workgroups (reorder 3) are built on direct-to-LDS staging (cache_read 5, 6, 7)");
             if (p.cache_write) {

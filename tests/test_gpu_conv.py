@@ -324,9 +324,9 @@ def test_grouped_conv_exact(groups, Cin, Cout, k, stride, pad):
     OH, OW = ref.shape[1], ref.shape[2]
     op = B.conv2d_op(N, H, W_, Cin, Cout, k, k, stride=stride, pad=pad, out_dtype="f32", groups=groups)
     space = op.space()
-    for n in range(8):
+    for n in range(12):
         t = B.trace_sample_valid(op, space, 82, n)
-        assert B.trace_validate(op, space, t).compute_at == 0
+        assert B.trace_validate(op, space, t).compute_at <= 1
         print("trace", n, t.decisions(), flush=True)
         got = run_variant(op, space, t, [X, Wt, bias], "f32", (N, OH, OW, Cout), instances=2)
         if got is None:
