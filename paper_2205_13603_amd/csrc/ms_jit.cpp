@@ -143,7 +143,9 @@ int32_t jit_get_code(const KernelSpec &spec, uint64_t key, std::vector<char> **c
         if (r != HIPRTC_SUCCESS) return fail(MS_ERR_COMPILE, "hiprtcCreateProgram: %s", hiprtcGetErrorString(r));
         std::vector<std::string> opts = spec.defines;
         for (auto &x : extra) opts.push_back(x);
-        opts.push_back("--offload-arch=gfx950");
+        // developer knob: the full target id (e.g. gfx950:sramecc+:xnack-) instead of the generic one
+        const char *arch_env = getenv("MS_OFFLOAD_ARCH");
+        opts.push_back(std::string("--offload-arch=") + (arch_env && *arch_env ? arch_env : "gfx950"));
         opts.push_back("-O3");
         opts.push_back("-std=c++17");
         // no fast-math: results must not depend on reassociation
