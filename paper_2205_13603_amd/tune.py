@@ -1,6 +1,6 @@
 """Tune one workload on the GPU: run the evolutionary search over traces and store the best as a record.
 
-    python -m paper_2205_13603_amd.tune --workload c2_gemm_f16_1024 --trials 256 --out gpurun_out/tuned
+    python -m paper_2205_13603_amd.tune --workload c2_gemm_f16_1024 --trials 256 --out tuned_out
 
 Writes <out>/<workload>.jsonl (best record, appendable to tuned_records/) and <out>/<workload>.log.jsonl
 (every trial: index, status, latency, best so far, trace text) so that a search can be inspected or resumed.
@@ -19,7 +19,7 @@ def main():
     ap.add_argument("--seed", type=int, default=0)
     ap.add_argument("--instances", type=int, default=0)
     ap.add_argument("--flags", type=lambda s: int(s, 0), default=0xFF, help="search-space module mask (0xff = default, 0x1ff = with fp32 tensorize)")
-    ap.add_argument("--out", default="gpurun_out/tuned")
+    ap.add_argument("--out", default="tuned_out")
     ap.add_argument("--cost-model", action="store_true", help="let the learned cost model pick which proposals are measured")
     ap.add_argument("--model-candidates", type=int, default=8, help="proposals scored per measured candidate")
     ap.add_argument("--seed-records", action="store_true", help="measure stored records first (reported, not part of the search)")
