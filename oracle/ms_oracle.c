@@ -21,6 +21,8 @@
  *             Xpad[n][oh*s+kh-p][ow*s+kw-p][ci] * W[kh][kw][ci][co])
  *   depthwise conv2d NHWC (Appendix A.2: DEP)
  *       Y[n][oh][ow][c] = sum_{kh,kw} Xpad[n][oh*s+kh-p][ow*s+kw-p][c] * W[kh][kw][c]
+ *   conv1d NWC with bias and ReLU (Appendix A.2: C1D)
+ *       Y[n][ol][co] = act(bias[co] + sum_{k,ci} Xpad[n][ol*s + k*d - p][ci] * W[k][ci][co])
  *   transposed conv2d NHWC (Appendix A.2: T2D), the adjoint of the conv2d above in X:
  *       Y[n][ih*s+kh-p][iw*s+kw-p][co] += X[n][ih][iw][ci] * W[kh][kw][ci][co]   (then bias, ReLU)
  *       output size (H-1)*s - 2p + KH
@@ -248,6 +250,37 @@ int ms_oracle_conv2d_nhwc(int dtype, int64_t N, int64_t H, int64_t W_, int64_t C
                 if (relu && acc < 0.0) acc = 0.0;
                 Y[((n * OH + oh) * OW + ow) * Cout + co] = acc;
             }
+        }
+    }
+    return 0;
+}
+
+/*
+ * conv1d, NWC: X [N][L][Cin], W [K][Cin][Cout], Y dense [N][OL][Cout] in double,
+ * OL = floor((L + 2*pad - dilation*(K-1) - 1) / stride) + 1; zero padding at both ends.
+ */
+int ms_oracle_conv1d_nwc(int dtype, int64_t N, int64_t L, int64_t Cin, int64_t Cout, int64_t K,
+                         int64_t stride, int64_t pad, int64_t dilation,
+                         const void *X, const void *Wt, const float *bias, int relu, double *Y)
+{
+    if (dtype != ORA_F32 && dtype != ORA_F16 && dtype != ORA_BF16) return -1;
+    if (dilation < 1) return -1;
+    int64_t OL = conv_out_size(L, dilation * (K - 1) + 1, stride, pad);
+    int64_t row;
+#pragma omp parallel for schedule(static)
+    for (row = 0; row < N * OL; ++row) {
+        int64_t n = row / OL, ol = row % OL;
+        for (int64_t co = 0; co < Cout; ++co) {
+            double acc = 0.0;
+            for (int64_t k = 0; k < K; ++k) {
+                int64_t il = ol * stride + k * dilation - pad;
+                if (il < 0 || il >= L) continue;
+                for (int64_t ci = 0; ci < Cin; ++ci)
+                    acc += load_elem(dtype, X, (n * L + il) * Cin + ci) * load_elem(dtype, Wt, (k * Cin + ci) * Cout + co);
+            }
+            if (bias) acc += (double)bias[co];
+            if (relu && acc < 0.0) acc = 0.0;
+            Y[row * Cout + co] = acc;
         }
     }
     return 0;

@@ -34,6 +34,8 @@ def lib():
         L.ms_oracle_conv_out_size.argtypes = [i64, i64, i64, i64]
         L.ms_oracle_conv2d_nhwc.restype = C.c_int
         L.ms_oracle_conv2d_nhwc.argtypes = [C.c_int] + [i64] * 11 + [vp, vp, vp, C.c_int, vp]
+        L.ms_oracle_conv1d_nwc.restype = C.c_int
+        L.ms_oracle_conv1d_nwc.argtypes = [C.c_int] + [i64] * 8 + [vp, vp, vp, C.c_int, vp]
         L.ms_oracle_conv2d_transposed_nhwc.restype = C.c_int
         L.ms_oracle_conv2d_transposed_nhwc.argtypes = [C.c_int] + [i64] * 9 + [vp, vp, vp, C.c_int, vp]
         L.ms_oracle_dwconv2d_nhwc.restype = C.c_int
@@ -141,6 +143,27 @@ def conv2d_nhwc(X, Wt, bias=None, relu=False, stride=1, pad=0, bf16=False, dilat
                                      _ptr(X), _ptr(Wt), bptr, int(bool(relu)), _ptr(out))
     if rc != 0:
         raise RuntimeError("oracle conv2d failed")
+    return out
+
+
+def conv1d_nwc(X, Wt, bias=None, relu=False, stride=1, pad=0, bf16=False, dilation=1):
+    """X [N,L,Cin], Wt [K,Cin,Cout], bias fp32 [Cout] or None."""
+    X = np.ascontiguousarray(X)
+    Wt = np.ascontiguousarray(Wt)
+    N, L_, Cin = X.shape
+    K, Cin2, Cout = Wt.shape
+    assert Cin2 == Cin and X.dtype == Wt.dtype
+    OL = conv_out_size(L_, dilation * (K - 1) + 1, stride, pad)
+    out = np.empty((N, OL, Cout), np.float64)
+    bptr = None
+    if bias is not None:
+        bias = np.ascontiguousarray(bias, dtype=np.float32)
+        assert bias.shape == (Cout,)
+        bptr = _ptr(bias)
+    rc = lib().ms_oracle_conv1d_nwc(_dtype_code(X, bf16), N, L_, Cin, Cout, K, stride, pad, dilation, _ptr(X), _ptr(Wt), bptr,
+                                    int(bool(relu)), _ptr(out))
+    if rc != 0:
+        raise RuntimeError("oracle conv1d failed")
     return out
 
 

@@ -23,6 +23,8 @@ def main():
     ap.add_argument("--cost-model", action="store_true", help="let the learned cost model pick which proposals are measured")
     ap.add_argument("--model-candidates", type=int, default=8, help="proposals scored per measured candidate")
     ap.add_argument("--seed-records", action="store_true", help="measure stored records first (reported, not part of the search)")
+    ap.add_argument("--measure", default="1,3,3", help="warm-up launches, repeats, launches per repeat of every trial; a long "
+                    "warm-up (e.g. 150,3,20) times candidates at the clocks of a sustained run instead of just after an idle gap")
     args = ap.parse_args()
 
     import torch
@@ -60,7 +62,8 @@ def main():
     cfg = B.search_cfg_default()
     cfg.seed, cfg.trials = args.seed, args.trials
     cfg.cost_model, cfg.model_candidates = int(args.cost_model), args.model_candidates
-    cfg.measure = B.ms_measure_cfg(1, 3, 3, R)
+    wu, reps, lpr = (int(x) for x in args.measure.split(","))
+    cfg.measure = B.ms_measure_cfg(wu, reps, lpr, R)
     res = B.search(op, space, cfg, bufsets=sets, stream=devmem.current_stream(), on_trial=on_trial)
     flop, byts = op.work()
     rec = {"workload": args.workload, "trace": B.trace_to_text(op, space, res.best_trace), "us": res.best_us,

@@ -541,3 +541,31 @@ def test_grouped_conv_vs_torch_cpu_and_vs_block_diagonal_weights(groups, stride,
     Wdw = g.standard_normal((3, 3, 5)).astype(np.float32)
     np.testing.assert_allclose(O.conv2d_nhwc(Xd, Wdw.reshape(3, 3, 1, 5), stride=1, pad=1, groups=5),
                                O.dwconv2d_nhwc(Xd, Wdw, stride=1, pad=1), rtol=1e-13, atol=1e-13)
+
+
+# ---------------------------------------------------------------- conv1d (Appendix A.2: C1D)
+
+@pytest.mark.parametrize("stride,pad,k,dil", [(2, 1, 3, 1), (1, 0, 1, 1), (1, 2, 5, 1), (1, 2, 3, 2), (3, 0, 4, 1)])
+def test_conv1d_vs_torch_cpu_and_closed_forms(stride, pad, k, dil):
+    import torch
+    g = np.random.default_rng(90 + k)
+    N, L_, Cin, Cout = 2, 19, 5, 7
+    X = g.standard_normal((N, L_, Cin)).astype(np.float32)
+    Wt = g.standard_normal((k, Cin, Cout)).astype(np.float32)
+    bias = g.standard_normal(Cout).astype(np.float32)
+    got = O.conv1d_nwc(X, Wt, bias=bias, stride=stride, pad=pad, dilation=dil)
+    ref = torch.nn.functional.conv1d(torch.from_numpy(X).double().permute(0, 2, 1), torch.from_numpy(Wt).double().permute(2, 1, 0),
+                                     torch.from_numpy(bias).double(), stride=stride, padding=pad, dilation=dil)
+    np.testing.assert_allclose(got, ref.permute(0, 2, 1).numpy(), rtol=1e-12, atol=1e-12)
+    # all ones, no padding: every output = K * Cin; with padding the two ends see fewer taps
+    y = O.conv1d_nwc(np.ones((1, 8, 3), np.float32), np.ones((3, 3, 2), np.float32), stride=1, pad=1)
+    assert np.array_equal(y[0, :, 0], [6, 9, 9, 9, 9, 9, 9, 6])
+    # one-hot tap 0 with padding 1 shifts the signal right by one (pins the padding direction)
+    W0 = np.zeros((3, 1, 1), np.float32)
+    W0[0, 0, 0] = 1.0
+    sig = np.arange(1, 7, dtype=np.float32).reshape(1, 6, 1)
+    assert np.array_equal(O.conv1d_nwc(sig, W0, stride=1, pad=1)[0, :, 0], [0, 1, 2, 3, 4, 5])
+    # a 1 x K conv2d over an image of height 1 is the same operator when it is not padded
+    if pad == 0:
+        y2 = O.conv2d_nhwc(X[:, None], Wt[None], bias=bias, stride=stride, pad=0, dilation=dil)
+        np.testing.assert_allclose(got, y2[:, 0], rtol=1e-13, atol=1e-13)
