@@ -75,6 +75,9 @@
 #define C_BATCH ((long)DIM_M * DIM_N) // output elements between two batch entries
 #endif
 #if IS_CONV
+#ifndef CV_PAD_H
+#define CV_PAD_H CV_PAD            // zero rows above the image (CV_PAD: zero columns left of it)
+#endif
 #ifndef CV_XC
 #define CV_XC CV_CIN               // channels per pixel of X
 #endif
@@ -254,11 +257,11 @@ template <int V> __device__ __forceinline__ vec_t<in_t, V> load_conv_a(const in_
 #if CV_TRANSPOSED
     // transposed convolution: input element ih reaches outputs ih * stride + kh - pad, so output row oh takes tap kh
     // from input row (oh + pad - kh) / stride when that is a whole number inside the image
-    const int ihn = oh + CV_PAD - kh, iwn = ow + CV_PAD - kw;
+    const int ihn = oh + CV_PAD_H - kh, iwn = ow + CV_PAD - kw;
     const bool on_grid = ihn >= 0 && iwn >= 0 && ihn % CV_STRIDE == 0 && iwn % CV_STRIDE == 0;
     const int ih = on_grid ? ihn / CV_STRIDE : -1, iw = on_grid ? iwn / CV_STRIDE : -1;
 #else
-    const int ih = oh * CV_STRIDE + kh * CV_DIL - CV_PAD, iw = ow * CV_STRIDE + kw * CV_DIL - CV_PAD;
+    const int ih = oh * CV_STRIDE + kh * CV_DIL - CV_PAD_H, iw = ow * CV_STRIDE + kw * CV_DIL - CV_PAD;
 #endif
     vec_t<in_t, V> x;
     if (ih >= 0 && ih < CV_H && iw >= 0 && iw < CV_W && (!K_PADDED || k < CV_KREAL)) {
@@ -461,7 +464,7 @@ __device__ __forceinline__ void patch_fetch(patch_regs &pr, const patch_map &pm,
 {
     const int m0 = i0 * BM;
     const int n = m0 / (CV_OH * CV_OW);
-    const int ih_lo = ((m0 % (CV_OH * CV_OW)) / CV_OW) * CV_STRIDE - CV_PAD;
+    const int ih_lo = ((m0 % (CV_OH * CV_OW)) / CV_OW) * CV_STRIDE - CV_PAD_H;
     const in_t *img = X + (long)n * (CV_H * CV_W * CV_XC);
 #pragma unroll
     for (int p = 0; p < P_PASSES; ++p)

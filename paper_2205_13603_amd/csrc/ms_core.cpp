@@ -99,6 +99,7 @@ const char *op_kind_name(int32_t kind)
     case MS_OP_BMM_NN: return "bmm_nn";
     case MS_OP_CONV2D_NHWC: return "conv2d_nhwc";
     case MS_OP_CONV2D_TRANSPOSED_NHWC: return "conv2d_transposed_nhwc";
+    case MS_OP_CONV1D_NWC: return "conv1d_nwc";
     case MS_OP_DWCONV2D_NHWC: return "dwconv2d_nhwc";
     case MS_OP_SOFTMAX: return "softmax";
     case MS_OP_NORM: return "norm";
@@ -176,8 +177,18 @@ extern "C" int32_t ms_op_create(const ms_op_desc *desc, ms_op **out)
     *out = nullptr;
     ms_op op;
     memset(&op, 0, sizeof op);
-    op.d = *desc;
-    const ms_op_desc &d = *desc;
+    ms_op_desc conv = *desc;
+    const bool is_1d = desc->kind == MS_OP_CONV1D_NWC;
+    if (is_1d) {
+        // N, L, Cin, Cout, K, groups -> an image of height 1, a 1 x K filter, no vertical padding
+        for (int i = 0; i < 5; ++i)
+            if (desc->dims[i] < 1 || desc->dims[i] > (int64_t(1) << 30)) return fail(MS_ERR_BAD_ARG, "ms_op_create: dims[%d] = %" PRId64 " out of range", i, desc->dims[i]);
+        conv.kind = MS_OP_CONV2D_NHWC;
+        const int64_t v[8] = {desc->dims[0], 1, desc->dims[1], desc->dims[2], desc->dims[3], 1, desc->dims[4], desc->dims[5]};
+        for (int i = 0; i < 8; ++i) conv.dims[i] = v[i];
+    }
+    op.d = conv;
+    const ms_op_desc &d = conv;
     int ndims = 0;
     switch (d.kind) {
     case MS_OP_GEMM: ndims = 3; break;
@@ -262,7 +273,8 @@ extern "C" int32_t ms_op_create(const ms_op_desc *desc, ms_op **out)
         if (op.d.dilation == 0) op.d.dilation = 1;
         if (op.d.dilation != 1 && !is_conv2d(d.kind)) return fail(MS_ERR_UNSUPPORTED, "ms_op_create: dilation is for conv2d only");
         // a filter whose taps are `dilation` apart spans dilation * (K - 1) + 1 input elements
-        op.OH = conv_out(H, op.d.dilation * (KH - 1) + 1, d.stride, d.pad);
+        op.pad_h = is_1d ? 0 : d.pad;
+        op.OH = conv_out(H, op.d.dilation * (KH - 1) + 1, d.stride, op.pad_h);
         op.OW = conv_out(W, op.d.dilation * (KW - 1) + 1, d.stride, d.pad);
         if (d.kind == MS_OP_CONV2D_TRANSPOSED_NHWC) {
             // the adjoint of a stride-s convolution: input element ih reaches outputs ih*s + kh - pad
@@ -290,6 +302,8 @@ extern "C" int32_t ms_op_create(const ms_op_desc *desc, ms_op **out)
             op.K = KH * KW;
         }
     }
+    op.user = op.d;
+    if (is_1d) op.user = *desc;
     ms_op *p = new (std::nothrow) ms_op(op);
     if (!p) return fail(MS_ERR_NOMEM, "ms_op_create: out of memory");
     *out = p;
@@ -301,7 +315,7 @@ extern "C" void ms_op_destroy(ms_op *op) { delete op; }
 extern "C" int32_t ms_op_get_desc(const ms_op *op, ms_op_desc *out)
 {
     if (!op || !out) return fail(MS_ERR_BAD_ARG, "ms_op_get_desc: NULL argument");
-    *out = op->d;
+    *out = op->user;
     return MS_OK;
 }
 
@@ -835,7 +849,7 @@ extern "C" int32_t ms_trace_to_text(const ms_op *op, const ms_space *space, cons
     if (!op || !space_ok(space) || !trace) return fail(MS_ERR_BAD_ARG, "ms_trace_to_text: bad argument");
     if (trace->n != space->n_slots) return fail(MS_ERR_INVALID_TRACE, "ms_trace_to_text: trace/space length mismatch");
     std::string s;
-    appendf(s, "# op=%s in=%s out=%s M=%" PRId64 " N=%" PRId64 " K=%" PRId64 " batch=%" PRId64 "\n", op_kind_name(op->d.kind),
+    appendf(s, "# op=%s in=%s out=%s M=%" PRId64 " N=%" PRId64 " K=%" PRId64 " batch=%" PRId64 "\n", op_kind_name(op->user.kind),
             dtype_name(op->d.in_dtype), dtype_name(op->d.out_dtype), op->M, op->N, op->K, op->nb);
     // sampling instructions with their decisions
     for (int i = 0; i < space->n_slots; ++i) {

@@ -8,7 +8,9 @@
 #include <vector>
 
 struct ms_op {
-    ms_op_desc d;
+    ms_op_desc d;        // the operator in the form the kernels see (a 1-D convolution as a conv2d of height 1)
+    ms_op_desc user;     // the descriptor as given, default strides filled in
+    int32_t pad_h;       // convolutions: zero rows above and below the image (d.pad: columns left and right)
     // derived
     int64_t nb;          // batch (BMM) or 1
     int64_t M, N, K;     // implicit-GEMM view (conv: M = N*OH*OW, N = Cout, K = KH*KW*Cin)

@@ -56,6 +56,7 @@ uint64_t hash_params(const ms_op *op, const ms_variant_params *p)
     add((uint64_t)d.out_dtype);
     add((uint64_t)d.stride);
     add((uint64_t)d.pad);
+    if (op->pad_h != d.pad && (is_conv2d(d.kind))) add(0x1D00000000ull + (uint64_t)op->pad_h); // 1-D convolutions only
     add((uint64_t)d.dilation);
     add((uint64_t)d.has_bias);
     add((uint64_t)d.relu);
@@ -511,6 +512,7 @@ int32_t make_kernel_spec(const ms_op *op, const ms_variant_params *p, KernelSpec
             D.push_back(def("CV_OW", op->OW));
             D.push_back(def("CV_STRIDE", d.stride));
             D.push_back(def("CV_PAD", d.pad));
+            D.push_back(def("CV_PAD_H", op->pad_h));
             D.push_back(def("CV_DIL", d.dilation));
             D.push_back(def("CV_TRANSPOSED", d.kind == MS_OP_CONV2D_TRANSPOSED_NHWC ? 1 : 0));
             D.push_back(def("HAS_BIAS", d.has_bias ? 1 : 0));

@@ -350,3 +350,53 @@ def test_grp_config_grouped_conv_56x56x64_to_128():
         if got is None:
             continue
         compare.assert_float_close(got, ref, compare.RTOL_HALF, "GRP trace %d" % n)
+
+
+@pytest.mark.parametrize("stride,pad,k,dil,L_", [(2, 1, 3, 1, 64), (1, 0, 1, 1, 32), (1, 2, 5, 1, 48), (1, 2, 3, 2, 32), (1, 1, 3, 1, 16)])
+def test_conv1d_exact_for_every_compute_location(stride, pad, k, dil, L_):
+    """1-D convolution (Appendix A.2: C1D) on the conv2d kernels: an image of height 1, a 1 x K filter, padding at the
+    two ends of the row only.  Integer-valued inputs, batch 2, 2 instances: bit-equal fp32 outputs; every cache-read
+    location that the space offers is exercised."""
+    N, Cin, Cout = 2, 32, 32
+    g = I.rng(91)
+    X = I.small_ints(g, (N, L_, Cin), -2, 2, "f16")
+    Wt = I.small_ints(g, (k, Cin, Cout), -2, 2, "f16")
+    bias = g.integers(-3, 4, size=Cout).astype(np.float32)
+    ref = O.conv1d_nwc(X, Wt, bias=bias, relu=True, stride=stride, pad=pad, dilation=dil)
+    OL = ref.shape[1]
+    assert (N * OL) % 16 == 0
+    op = B.conv1d_op(N, L_, Cin, Cout, k, stride=stride, pad=pad, out_dtype="f32", dilation=dil)
+    space = op.space()
+    want = {0: 2, 1: 2, 2: 1, 3: 1, 4: 1}
+    idx = 0
+    while any(want.values()) and idx < 600:
+        t = B.trace_sample_valid(op, space, 92, idx)
+        idx += 1
+        ca = B.trace_validate(op, space, t).compute_at
+        if want[ca] == 0:
+            continue
+        want[ca] -= 1
+        print("trace", idx, "compute_at", ca, t.decisions(), flush=True)
+        got = run_variant(op, space, t, [X, Wt, bias], "f32", (N, OL, Cout), instances=2)
+        if got is None:
+            continue
+        assert np.array_equal(got[0], ref) and np.array_equal(got[1], ref), "trace %d" % idx
+    assert want[0] == 0 and want[1] == 0, want
+
+
+def test_c1d_config_conv1d_256x64_to_128():
+    """The paper's C1D shape: length 256, 64 -> 128 channels, kernel 3, stride 2, padding 1; fp16."""
+    g = I.rng(93)
+    X = I.uniform(g, (1, 256, 64), 0.0, 1.0, "f16")
+    Wt = I.normal(g, (3, 64, 128), 0.05, "f16")
+    bias = I.normal(g, (128,), 0.05, "f32")
+    ref = O.conv1d_nwc(X, Wt, bias=bias, relu=True, stride=2, pad=1)
+    op = B.conv1d_op(1, 256, 64, 128, 3, stride=2, pad=1)
+    space = op.space()
+    for n in range(8):
+        t = B.trace_sample_valid(op, space, 94, n)
+        print("trace", n, t.decisions(), flush=True)
+        got = run_variant(op, space, t, [X, Wt, bias], "f16", ref.shape)
+        if got is None:
+            continue
+        compare.assert_float_close(got, ref, compare.RTOL_HALF, "C1D trace %d" % n)

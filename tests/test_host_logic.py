@@ -491,3 +491,21 @@ def test_grouped_conv_descriptor_space_and_coverage():
     s0 = d0.space()
     t = B.trace_sample_valid(d0, s0, 1, 0)
     assert B.trace_validate(d0, s0, t).key == B.trace_validate(d1, d1.space(), t).key
+
+
+def test_conv1d_descriptor_runs_on_the_conv2d_space():
+    op = B.conv1d_op(1, 256, 64, 128, 3, stride=2, pad=1)
+    assert op.loops() == [("i", 128, False), ("j", 128, False), ("k", 192, True)]        # OL = 128
+    d = op.desc()
+    assert d.kind == B.OP_CONV1D_NWC and list(d.dims)[:5] == [1, 256, 64, 128, 3]        # the descriptor as given
+    assert op.tensor_bytes(0) == 256 * 64 * 2 and op.tensor_bytes(1) == 3 * 64 * 128 * 2 and op.tensor_bytes(-1) == 128 * 128 * 2
+    sp = op.space()
+    assert sp.family == B.FAM_GEMM_MFMA and [sp.slots[i].name for i in range(sp.n_slots)][-1] == b"compute_at"
+    t = B.trace_sample_valid(op, sp, 3, 0)
+    p = B.trace_validate(op, sp, t)
+    assert "op=conv1d_nwc" in B.trace_to_text(op, sp, t)
+    # not the same kernel as the 1 x 3 conv2d over an image of height 1, which is also padded vertically (3 output rows)
+    op2 = B.conv2d_op(1, 1, 256, 64, 128, 1, 3, stride=2, pad=1)
+    assert op2.loops()[0] == ("i", 2 * 128, False)
+    with pytest.raises(B.MsError):
+        B.conv1d_op(1, 2, 8, 16, 5, stride=1, pad=0)                                      # empty output
