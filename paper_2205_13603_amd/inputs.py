@@ -177,3 +177,10 @@ def c2nt(seed=0, dtype="f16"):
     """Config 2 with the second operand stored transposed: A [1][1024][1024], B [1][N][K], 0.1 * N(0, 1)."""
     g = rng(seed)
     return (normal(g, (1, 1024, 1024), 0.1, dtype), normal(g, (1, 1024, 1024), 0.1, dtype))
+
+
+def c1d(seed=0, dtype="f16"):
+    """1-D convolution workload (length 256, 64 -> 128 channels, kernel 3, stride 2, padding 1): X ~ U[0, 1],
+    W ~ N(0, 0.05) as [3][64][128], bias ~ N(0, 0.05) fp32."""
+    g = rng(seed)
+    return (uniform(g, (1, 256, 64), 0.0, 1.0, dtype), normal(g, (3, 64, 128), 0.05, dtype), normal(g, (128,), 0.05, "f32"))

@@ -25,6 +25,7 @@ WORKLOADS = {
     "x6_t2d_f16_4x4x512": (lambda: B.conv2d_transposed_op(1, 4, 4, 512, 256, 4, 4, stride=2, pad=1), 128),
     "x7_grp_f16_56x56x64_g4": (lambda: B.conv2d_op(1, 56, 56, 64, 128, 3, 3, stride=2, pad=1, groups=4), 512),
     "x8_gemm_nt_f16_1024": (lambda: B.bmm_op(1, 1024, 1024, 1024, True, "f16"), 64),
+    "x9_c1d_f16_256x64": (lambda: B.conv1d_op(1, 256, 64, 128, 3, stride=2, pad=1), 4096),
     "x3_softmax_f32_256x256": (lambda: B.softmax_op(1, 256, 256), 2048),
     "x4_norm_f32_256x256": (lambda: B.norm_op(1, 256, 256), 2048),
 }
