@@ -21,6 +21,9 @@
  *             Xpad[n][oh*s+kh-p][ow*s+kw-p][ci] * W[kh][kw][ci][co])
  *   depthwise conv2d NHWC (Appendix A.2: DEP)
  *       Y[n][oh][ow][c] = sum_{kh,kw} Xpad[n][oh*s+kh-p][ow*s+kw-p][c] * W[kh][kw][c]
+ *   conv3d NDHWC with bias and ReLU (Appendix A.2: C3D), the same stride, padding and dilation on the three axes
+ *       Y[n][od][oh][ow][co] = act(bias[co] + sum_{kd,kh,kw,ci}
+ *             Xpad[n][od*s+kd*d-p][oh*s+kh*d-p][ow*s+kw*d-p][ci] * W[kd][kh][kw][ci][co])
  *   conv1d NWC with bias and ReLU (Appendix A.2: C1D)
  *       Y[n][ol][co] = act(bias[co] + sum_{k,ci} Xpad[n][ol*s + k*d - p][ci] * W[k][ci][co])
  *   transposed conv2d NHWC (Appendix A.2: T2D), the adjoint of the conv2d above in X:
@@ -251,6 +254,49 @@ int ms_oracle_conv2d_nhwc(int dtype, int64_t N, int64_t H, int64_t W_, int64_t C
                 Y[((n * OH + oh) * OW + ow) * Cout + co] = acc;
             }
         }
+    }
+    return 0;
+}
+
+/*
+ * conv3d, NDHWC: X [N][D][H][W][Cin], W [KD][KH][KW][Cin][Cout], Y dense [N][OD][OH][OW][Cout] in double;
+ * one stride, zero padding and dilation for the three axes, output size as for conv2d on each axis.
+ */
+int ms_oracle_conv3d_ndhwc(int dtype, int64_t N, int64_t D, int64_t H, int64_t W_, int64_t Cin, int64_t Cout,
+                           int64_t KD, int64_t KH, int64_t KW, int64_t stride, int64_t pad, int64_t dilation,
+                           const void *X, const void *Wt, const float *bias, int relu, double *Y)
+{
+    if (dtype != ORA_F32 && dtype != ORA_F16 && dtype != ORA_BF16) return -1;
+    if (dilation < 1) return -1;
+    int64_t OD = conv_out_size(D, dilation * (KD - 1) + 1, stride, pad);
+    int64_t OH = conv_out_size(H, dilation * (KH - 1) + 1, stride, pad);
+    int64_t OW = conv_out_size(W_, dilation * (KW - 1) + 1, stride, pad);
+    int64_t row;
+#pragma omp parallel for schedule(static)
+    for (row = 0; row < N * OD * OH; ++row) {
+        int64_t n = row / (OD * OH), od = (row / OH) % OD, oh = row % OH;
+        for (int64_t ow = 0; ow < OW; ++ow)
+            for (int64_t co = 0; co < Cout; ++co) {
+                double acc = 0.0;
+                for (int64_t kd = 0; kd < KD; ++kd) {
+                    int64_t id = od * stride + kd * dilation - pad;
+                    if (id < 0 || id >= D) continue;
+                    for (int64_t kh = 0; kh < KH; ++kh) {
+                        int64_t ih = oh * stride + kh * dilation - pad;
+                        if (ih < 0 || ih >= H) continue;
+                        for (int64_t kw = 0; kw < KW; ++kw) {
+                            int64_t iw = ow * stride + kw * dilation - pad;
+                            if (iw < 0 || iw >= W_) continue;
+                            for (int64_t ci = 0; ci < Cin; ++ci)
+                                acc += load_elem(dtype, X, (((n * D + id) * H + ih) * W_ + iw) * Cin + ci) *
+                                       load_elem(dtype, Wt, (((kd * KH + kh) * KW + kw) * Cin + ci) * Cout + co);
+                        }
+                    }
+                }
+                if (bias) acc += (double)bias[co];
+                if (relu && acc < 0.0) acc = 0.0;
+                Y[(row * OW + ow) * Cout + co] = acc;
+            }
     }
     return 0;
 }

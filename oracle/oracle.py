@@ -34,6 +34,8 @@ def lib():
         L.ms_oracle_conv_out_size.argtypes = [i64, i64, i64, i64]
         L.ms_oracle_conv2d_nhwc.restype = C.c_int
         L.ms_oracle_conv2d_nhwc.argtypes = [C.c_int] + [i64] * 11 + [vp, vp, vp, C.c_int, vp]
+        L.ms_oracle_conv3d_ndhwc.restype = C.c_int
+        L.ms_oracle_conv3d_ndhwc.argtypes = [C.c_int] + [i64] * 12 + [vp, vp, vp, C.c_int, vp]
         L.ms_oracle_conv1d_nwc.restype = C.c_int
         L.ms_oracle_conv1d_nwc.argtypes = [C.c_int] + [i64] * 8 + [vp, vp, vp, C.c_int, vp]
         L.ms_oracle_conv2d_transposed_nhwc.restype = C.c_int
@@ -143,6 +145,27 @@ def conv2d_nhwc(X, Wt, bias=None, relu=False, stride=1, pad=0, bf16=False, dilat
                                      _ptr(X), _ptr(Wt), bptr, int(bool(relu)), _ptr(out))
     if rc != 0:
         raise RuntimeError("oracle conv2d failed")
+    return out
+
+
+def conv3d_ndhwc(X, Wt, bias=None, relu=False, stride=1, pad=0, bf16=False, dilation=1):
+    """X [N,D,H,W,Cin], Wt [KD,KH,KW,Cin,Cout], bias fp32 [Cout] or None."""
+    X = np.ascontiguousarray(X)
+    Wt = np.ascontiguousarray(Wt)
+    N, D, H, W_, Cin = X.shape
+    KD, KH, KW, Cin2, Cout = Wt.shape
+    assert Cin2 == Cin and X.dtype == Wt.dtype
+    OD, OH, OW = (conv_out_size(e, dilation * (k - 1) + 1, stride, pad) for e, k in ((D, KD), (H, KH), (W_, KW)))
+    out = np.empty((N, OD, OH, OW, Cout), np.float64)
+    bptr = None
+    if bias is not None:
+        bias = np.ascontiguousarray(bias, dtype=np.float32)
+        assert bias.shape == (Cout,)
+        bptr = _ptr(bias)
+    rc = lib().ms_oracle_conv3d_ndhwc(_dtype_code(X, bf16), N, D, H, W_, Cin, Cout, KD, KH, KW, stride, pad, dilation,
+                                      _ptr(X), _ptr(Wt), bptr, int(bool(relu)), _ptr(out))
+    if rc != 0:
+        raise RuntimeError("oracle conv3d failed")
     return out
 
 

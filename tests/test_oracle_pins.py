@@ -569,3 +569,42 @@ def test_conv1d_vs_torch_cpu_and_closed_forms(stride, pad, k, dil):
     if pad == 0:
         y2 = O.conv2d_nhwc(X[:, None], Wt[None], bias=bias, stride=stride, pad=0, dilation=dil)
         np.testing.assert_allclose(got, y2[:, 0], rtol=1e-13, atol=1e-13)
+
+
+# ---------------------------------------------------------------- conv3d (Appendix A.2: C3D)
+
+@pytest.mark.parametrize("stride,pad,k,dil", [(2, 3, 7, 1), (1, 0, 1, 1), (1, 1, 3, 1), (2, 1, 3, 1), (1, 2, 3, 2)])
+def test_conv3d_vs_torch_cpu_and_reductions_to_conv2d(stride, pad, k, dil):
+    import torch
+    g = np.random.default_rng(95 + k + stride)
+    N, D, H, W_, Cin, Cout = 2, 6, 7, 5, 3, 4
+    X = g.standard_normal((N, D, H, W_, Cin)).astype(np.float32)
+    Wt = g.standard_normal((k, k, k, Cin, Cout)).astype(np.float32)
+    bias = g.standard_normal(Cout).astype(np.float32)
+    got = O.conv3d_ndhwc(X, Wt, bias=bias, stride=stride, pad=pad, dilation=dil)
+    ref = torch.nn.functional.conv3d(torch.from_numpy(X).double().permute(0, 4, 1, 2, 3), torch.from_numpy(Wt).double().permute(4, 3, 0, 1, 2),
+                                     torch.from_numpy(bias).double(), stride=stride, padding=pad, dilation=dil)
+    np.testing.assert_allclose(got, ref.permute(0, 2, 3, 4, 1).numpy(), rtol=1e-12, atol=1e-12)
+    # depth 1 and a filter of depth 1, unpadded: the (pinned) conv2d
+    if pad == 0:
+        X2 = X[:, :1]
+        W2 = g.standard_normal((1, k, k, Cin, Cout)).astype(np.float32)
+        np.testing.assert_allclose(O.conv3d_ndhwc(X2, W2, bias=bias, stride=stride, pad=0, dilation=dil)[:, 0],
+                                   O.conv2d_nhwc(X2[:, 0], W2[0], bias=bias, stride=stride, pad=0, dilation=dil), rtol=1e-13, atol=1e-13)
+
+
+def test_conv3d_closed_forms():
+    # all ones, 3x3x3, padding 1: an output counts the taps inside the volume: 27 inside, 18 on a face, 12 on an edge, 8 at a corner
+    y = O.conv3d_ndhwc(np.ones((1, 4, 4, 4, 1), np.float32), np.ones((3, 3, 3, 1, 1), np.float32), stride=1, pad=1)[0, :, :, :, 0]
+    assert y[1, 1, 1] == 27 and y[0, 1, 1] == 18 and y[0, 0, 1] == 12 and y[0, 0, 0] == 8 and y[3, 3, 3] == 8
+    # one-hot tap (0, 0, 0) with padding 1 shifts the volume by (+1, +1, +1)
+    W0 = np.zeros((3, 3, 3, 1, 1), np.float32)
+    W0[0, 0, 0, 0, 0] = 1.0
+    vol = np.arange(1, 28, dtype=np.float32).reshape(1, 3, 3, 3, 1)
+    y = O.conv3d_ndhwc(vol, W0, stride=1, pad=1)[0, :, :, :, 0]
+    assert np.array_equal(y[1:, 1:, 1:], vol[0, :2, :2, :2, 0]) and not y[0].any() and not y[:, 0].any() and not y[:, :, 0].any()
+    # the three axes are distinguished: a filter that is 1 only at kd = 2 (kh = kw = 1) shifts along depth only
+    W1 = np.zeros((3, 3, 3, 1, 1), np.float32)
+    W1[2, 1, 1, 0, 0] = 1.0
+    y = O.conv3d_ndhwc(vol, W1, stride=1, pad=1)[0, :, :, :, 0]
+    assert np.array_equal(y[:2], vol[0, 1:, :, :, 0]) and not y[2].any()
