@@ -75,7 +75,8 @@ typedef enum ms_op_kind {
     MS_OP_NORM = 6,          /* Y[b] = sqrt(sum_{i,j} X[b][i][j]^2)          (NRM) */
     MS_OP_CONV2D_TRANSPOSED_NHWC = 7, /* Y = act(bias + convT(X, W)): the adjoint of CONV2D_NHWC in X; X NHWC,
                                         W [KH][KW][Cin][Cout]                (T2D) */
-    MS_OP_CONV1D_NWC = 8     /* Y = act(bias + conv(X, W)), X [N][L][Cin], W [K][Cin][Cout]  (C1D) */
+    MS_OP_CONV1D_NWC = 8,    /* Y = act(bias + conv(X, W)), X [N][L][Cin], W [K][Cin][Cout]  (C1D) */
+    MS_OP_CONV3D_NDHWC = 9   /* Y = act(bias + conv(X, W)), X [N][D][H][W][Cin], W [K][K][K][Cin][Cout]  (C3D) */
 } ms_op_kind;
 
 typedef enum ms_dtype { MS_F32 = 0, MS_F16 = 1, MS_BF16 = 2, MS_I8 = 3, MS_I32 = 4,
@@ -90,6 +91,8 @@ typedef enum ms_dtype { MS_F32 = 0, MS_F16 = 1, MS_BF16 = 2, MS_I8 = 3, MS_I32 =
  *   CONV2D_NHWC     N, H, W, Cin, Cout, KH, KW, groups   (groups 0 or 1: dense.  groups G > 1 (GRP): output channel co
  *                   sums over the Cin/G input channels of group co / (Cout/G) only; W is [KH][KW][Cin/G][Cout])
  *   DWCONV2D_NHWC   N, H, W, C, KH, KW
+ *   CONV3D_NDHWC    N, D, H, W, Cin, Cout, K    (a K x K x K filter; one stride, padding and dilation for the three
+ *                   axes; runs on the conv2d kernels with im2col staging, the depth folded into rows and reduction)
  *   CONV1D_NWC      N, L, Cin, Cout, K, groups   (zero padding `pad` at both ends of L only; runs on the conv2d
  *                   kernels as an image of height 1 with a 1 x K filter that is not padded vertically)
  *   CONV2D_TRANSPOSED_NHWC  N, H, W, Cin, Cout, KH, KW   (input element (ih, iw) contributes X * W[kh][kw] to output

@@ -13,7 +13,7 @@ LIB_PATH = os.path.join(HERE, "libms.so")
 
 MS_OK, MS_ERR_BAD_ARG, MS_ERR_INVALID_TRACE, MS_ERR_UNSUPPORTED, MS_ERR_COMPILE, MS_ERR_HIP, MS_ERR_NOMEM = range(7)
 (OP_GEMM, OP_BMM_NT, OP_BMM_NN, OP_CONV2D_NHWC, OP_DWCONV2D_NHWC, OP_SOFTMAX, OP_NORM,
- OP_CONV2D_TRANSPOSED_NHWC, OP_CONV1D_NWC) = range(9)
+ OP_CONV2D_TRANSPOSED_NHWC, OP_CONV1D_NWC, OP_CONV3D_NDHWC) = range(10)
 F32, F16, BF16, I8, I32 = range(5)
 SLOT_PERFECT_TILE, SLOT_CATEGORICAL = 0, 1
 (SLOT_TENSORIZE, SLOT_TILE_I, SLOT_TILE_J, SLOT_TILE_C, SLOT_TILE_K, SLOT_UNROLL, SLOT_CACHE_READ, SLOT_VECTORIZE,
@@ -273,6 +273,12 @@ def conv2d_op(N, H, W, Cin, Cout, KH, KW, stride=1, pad=0, has_bias=True, relu=T
               groups=1):
     """groups > 1: W is [KH][KW][Cin/groups][Cout] and an output channel sees the input channels of its own group."""
     return Op(OP_CONV2D_NHWC, in_dtype, out_dtype or in_dtype, [N, H, W, Cin, Cout, KH, KW] + ([groups] if groups > 1 else []), stride=stride, pad=pad,
+              has_bias=has_bias, relu=relu, dilation=dilation)
+
+
+def conv3d_op(N, D, H, W, Cin, Cout, K, stride=1, pad=0, has_bias=True, relu=True, in_dtype="f16", out_dtype=None, dilation=1):
+    """3-D convolution with a K x K x K filter: X [N, D, H, W, Cin], W [K, K, K, Cin, Cout], Y [N, OD, OH, OW, Cout]."""
+    return Op(OP_CONV3D_NDHWC, in_dtype, out_dtype or in_dtype, [N, D, H, W, Cin, Cout, K], stride=stride, pad=pad,
               has_bias=has_bias, relu=relu, dilation=dilation)
 
 

@@ -81,6 +81,11 @@
 #ifndef CV_XC
 #define CV_XC CV_CIN               // channels per pixel of X
 #endif
+#ifndef CV_D
+#define CV_D 1                     // 3-D convolution: input depth, filter depth, output depth (padded like the columns)
+#define CV_KD 1
+#define CV_OD 1
+#endif
 #endif
 
 #define NWAVES (I2 * J2)
@@ -243,17 +248,20 @@ template <int ROWS, int V> struct kmajor_stage {
 #if IS_CONV
 // A reduction extent KH*KW*Cin that is no multiple of the intrinsic's k is rounded up: the loaders of both operands
 // deliver zeros for k >= KH*KW*Cin (im2col staging only)
-constexpr int CV_KREAL = CV_KH * CV_KW * CV_CIN;
+constexpr int CV_KREAL = CV_KD * CV_KH * CV_KW * CV_CIN;
 constexpr bool K_PADDED = K0 * BK != CV_KREAL;
 static_assert(K0 * BK >= CV_KREAL && K0 * BK - CV_KREAL < MI_K, "the k split covers the reduction, padded by less than one intrinsic");
 static_assert(!K_PADDED || COMPUTE_AT == 0, "a padded reduction needs the im2col loader");
 static_assert(!CV_TRANSPOSED || (COMPUTE_AT == 0 && CV_DIL == 1), "the transposed convolution exists in the im2col loader only");
+static_assert((CV_D == 1 && CV_KD == 1) || (COMPUTE_AT == 0 && !CV_TRANSPOSED), "3-D convolution exists in the im2col loader only");
 static_assert(DIM_B == 1 || COMPUTE_AT <= 1, "grouped convolution: im2col staging or the resident patch of one tile; the persistent modes have no group loop");
 // im2col on the fly: row = output pixel, k = (kh, kw, ci)
 template <int V> __device__ __forceinline__ vec_t<in_t, V> load_conv_a(const in_t *__restrict__ X, int row, int k)
 {
-    const int ow = row % CV_OW, oh = (row / CV_OW) % CV_OH, n = row / (CV_OW * CV_OH);
-    const int ci = k % CV_CIN, kw = (k / CV_CIN) % CV_KW, kh = k / (CV_CIN * CV_KW);
+    // row = (n, od, oh, ow), k = (kd, kh, kw, ci); od = kd = 0 for a 2-D convolution (CV_OD = CV_KD = 1)
+    const int ow = row % CV_OW, oh = (row / CV_OW) % CV_OH, od = (row / (CV_OW * CV_OH)) % CV_OD, n = row / (CV_OW * CV_OH * CV_OD);
+    const int ci = k % CV_CIN, kw = (k / CV_CIN) % CV_KW, kh = (k / (CV_CIN * CV_KW)) % CV_KH, kd = k / (CV_CIN * CV_KW * CV_KH);
+    const int id = CV_D > 1 || CV_KD > 1 ? od * CV_STRIDE + kd * CV_DIL - CV_PAD : 0;
 #if CV_TRANSPOSED
     // transposed convolution: input element ih reaches outputs ih * stride + kh - pad, so output row oh takes tap kh
     // from input row (oh + pad - kh) / stride when that is a whole number inside the image
@@ -264,8 +272,8 @@ template <int V> __device__ __forceinline__ vec_t<in_t, V> load_conv_a(const in_
     const int ih = oh * CV_STRIDE + kh * CV_DIL - CV_PAD_H, iw = ow * CV_STRIDE + kw * CV_DIL - CV_PAD;
 #endif
     vec_t<in_t, V> x;
-    if (ih >= 0 && ih < CV_H && iw >= 0 && iw < CV_W && (!K_PADDED || k < CV_KREAL)) {
-        x = *reinterpret_cast<const vec_t<in_t, V> *>(X + (((long)n * CV_H + ih) * CV_W + iw) * CV_XC + ci);
+    if (ih >= 0 && ih < CV_H && iw >= 0 && iw < CV_W && id >= 0 && id < CV_D && (!K_PADDED || k < CV_KREAL)) {
+        x = *reinterpret_cast<const vec_t<in_t, V> *>(X + ((((long)n * CV_D + id) * CV_H + ih) * CV_W + iw) * CV_XC + ci);
     } else {
 #pragma unroll
         for (int q = 0; q < V; ++q) x.v[q] = 0;

@@ -100,6 +100,7 @@ const char *op_kind_name(int32_t kind)
     case MS_OP_CONV2D_NHWC: return "conv2d_nhwc";
     case MS_OP_CONV2D_TRANSPOSED_NHWC: return "conv2d_transposed_nhwc";
     case MS_OP_CONV1D_NWC: return "conv1d_nwc";
+    case MS_OP_CONV3D_NDHWC: return "conv3d_ndhwc";
     case MS_OP_DWCONV2D_NHWC: return "dwconv2d_nhwc";
     case MS_OP_SOFTMAX: return "softmax";
     case MS_OP_NORM: return "norm";
@@ -186,6 +187,18 @@ extern "C" int32_t ms_op_create(const ms_op_desc *desc, ms_op **out)
         conv.kind = MS_OP_CONV2D_NHWC;
         const int64_t v[8] = {desc->dims[0], 1, desc->dims[1], desc->dims[2], desc->dims[3], 1, desc->dims[4], desc->dims[5]};
         for (int i = 0; i < 8; ++i) conv.dims[i] = v[i];
+    }
+    op.depth = op.kd = op.OD = 1;
+    const bool is_3d_op = desc->kind == MS_OP_CONV3D_NDHWC;
+    if (is_3d_op) {
+        // N, D, H, W, Cin, Cout, K -> the conv2d form plus the depth of the input and of the filter
+        for (int i = 0; i < 7; ++i)
+            if (desc->dims[i] < 1 || desc->dims[i] > (int64_t(1) << 30)) return fail(MS_ERR_BAD_ARG, "ms_op_create: dims[%d] = %" PRId64 " out of range", i, desc->dims[i]);
+        conv.kind = MS_OP_CONV2D_NHWC;
+        const int64_t v[8] = {desc->dims[0], desc->dims[2], desc->dims[3], desc->dims[4], desc->dims[5], desc->dims[6], desc->dims[6], 0};
+        for (int i = 0; i < 8; ++i) conv.dims[i] = v[i];
+        op.depth = desc->dims[1];
+        op.kd = desc->dims[6];
     }
     op.d = conv;
     const ms_op_desc &d = conv;
@@ -282,7 +295,8 @@ extern "C" int32_t ms_op_create(const ms_op_desc *desc, ms_op **out)
             op.OH = (H - 1) * d.stride - 2 * (int64_t)d.pad + KH;
             op.OW = (W - 1) * d.stride - 2 * (int64_t)d.pad + KW;
         }
-        if (op.OH < 1 || op.OW < 1) return fail(MS_ERR_BAD_ARG, "ms_op_create: empty convolution output");
+        if (is_3d_op) op.OD = conv_out(op.depth, op.d.dilation * (op.kd - 1) + 1, d.stride, d.pad);
+        if (op.OH < 1 || op.OW < 1 || op.OD < 1) return fail(MS_ERR_BAD_ARG, "ms_op_create: empty convolution output");
         if (is_conv2d(d.kind)) {
             if (d.in_dtype == MS_I8) return fail(MS_ERR_UNSUPPORTED, "ms_op_create: int8 conv2d is not supported");
             // dims[7] = groups (0 or 1: a dense convolution); a group is a batch entry of the implicit GEMM
@@ -290,9 +304,10 @@ extern "C" int32_t ms_op_create(const ms_op_desc *desc, ms_op **out)
             if (G < 1 || d.dims[3] % G || d.dims[4] % G) return fail(MS_ERR_BAD_ARG, "ms_op_create: %" PRId64 " groups do not divide the channel counts", G);
             if (G > 1 && d.kind == MS_OP_CONV2D_TRANSPOSED_NHWC) return fail(MS_ERR_UNSUPPORTED, "ms_op_create: the transposed convolution has no groups");
             op.nb = G;
-            op.M = d.dims[0] * op.OH * op.OW;
+            op.M = d.dims[0] * op.OD * op.OH * op.OW;
             op.N = d.dims[4] / G;
-            op.K = KH * KW * (d.dims[3] / G);
+            op.K = op.kd * KH * KW * (d.dims[3] / G);
+            if (op.M > (int64_t(1) << 30) || op.K > (int64_t(1) << 30)) return fail(MS_ERR_BAD_ARG, "ms_op_create: convolution too large");
         } else {
             if (d.in_dtype != MS_F32) return fail(MS_ERR_UNSUPPORTED, "ms_op_create: depthwise conv is fp32 only");
             if (d.has_bias || d.relu) return fail(MS_ERR_UNSUPPORTED, "ms_op_create: depthwise has no epilogue");
@@ -303,7 +318,7 @@ extern "C" int32_t ms_op_create(const ms_op_desc *desc, ms_op **out)
         }
     }
     op.user = op.d;
-    if (is_1d) op.user = *desc;
+    if (is_1d || is_3d_op) op.user = *desc;
     ms_op *p = new (std::nothrow) ms_op(op);
     if (!p) return fail(MS_ERR_NOMEM, "ms_op_create: out of memory");
     *out = p;
@@ -387,8 +402,8 @@ extern "C" int32_t ms_op_tensor_bytes(const ms_op *op, int32_t idx, int64_t *byt
     case MS_OP_CONV2D_NHWC:
     case MS_OP_CONV2D_TRANSPOSED_NHWC:
         if (idx < 0) e = op->M * op->N * op->nb;
-        else if (idx == 0) e = d.dims[0] * d.dims[1] * d.dims[2] * d.dims[3];
-        else if (idx == 1) e = op->K * op->N * op->nb; // [KH][KW][Cin / groups][Cout]
+        else if (idx == 0) e = d.dims[0] * op->depth * d.dims[1] * d.dims[2] * d.dims[3];
+        else if (idx == 1) e = op->K * op->N * op->nb; // [KD][KH][KW][Cin / groups][Cout]
         else if (idx == 2 && d.has_bias) { e = d.dims[4]; sz = 4; }
         break;
     case MS_OP_DWCONV2D_NHWC:
@@ -429,7 +444,7 @@ extern "C" int32_t ms_op_work(const ms_op *op, double *flop, double *bytes)
         break;
     case MS_OP_CONV2D_NHWC:
         f = 2.0 * op->M * op->N * op->K * op->nb;
-        b = (double)(d.dims[0] * d.dims[1] * d.dims[2] * d.dims[3] + op->K * op->N * op->nb) * op->in_size +
+        b = (double)(d.dims[0] * op->depth * d.dims[1] * d.dims[2] * d.dims[3] + op->K * op->N * op->nb) * op->in_size +
             (d.has_bias ? 4.0 * op->N * op->nb : 0.0) + (double)op->M * op->N * op->nb * op->out_size;
         break;
     case MS_OP_DWCONV2D_NHWC: {
@@ -592,7 +607,7 @@ extern "C" int32_t ms_space_describe(const ms_op *op, uint32_t flags, ms_space *
                     if (sl.slot_id == MS_SLOT_VECTORIZE && (d.dims[3] / op->nb) % sl.candidates[c]) sl.weight[c] = 0;
                     if (sl.slot_id == MS_SLOT_VECTORIZE_B && op->N % sl.candidates[c]) sl.weight[c] = 0;
                     if (sl.slot_id == MS_SLOT_COMPUTE_AT && sl.candidates[c] > 0 &&
-                        ((d.dims[3] / op->nb) % 8 || (op->nb > 1 && sl.candidates[c] > 1)))
+                        ((d.dims[3] / op->nb) % 8 || (op->nb > 1 && sl.candidates[c] > 1) || is_3d(op)))
                         sl.weight[c] = 0;
                 }
             }

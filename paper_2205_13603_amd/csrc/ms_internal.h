@@ -11,6 +11,7 @@ struct ms_op {
     ms_op_desc d;        // the operator in the form the kernels see (a 1-D convolution as a conv2d of height 1)
     ms_op_desc user;     // the descriptor as given, default strides filled in
     int32_t pad_h;       // convolutions: zero rows above and below the image (d.pad: columns left and right)
+    int64_t depth, kd, OD; // 3-D convolution: input depth, filter depth, output depth (1 otherwise); padded by d.pad
     // derived
     int64_t nb;          // batch (BMM) or 1
     int64_t M, N, K;     // implicit-GEMM view (conv: M = N*OH*OW, N = Cout, K = KH*KW*Cin)
@@ -24,6 +25,7 @@ int32_t fail(int32_t code, const char *fmt, ...) __attribute__((format(printf, 2
 
 // the two operators that share the conv2d kernels (the transposed one differs in the im2col index map only)
 inline bool is_conv2d(int32_t kind) { return kind == MS_OP_CONV2D_NHWC || kind == MS_OP_CONV2D_TRANSPOSED_NHWC; }
+inline bool is_3d(const ms_op *op) { return op->depth > 1 || op->kd > 1; }
 
 // (m, n, k) of an MS_MFMA_CODE
 inline void mfma_dims(int64_t code, int *m, int *n, int *k)

@@ -57,6 +57,10 @@ uint64_t hash_params(const ms_op *op, const ms_variant_params *p)
     add((uint64_t)d.stride);
     add((uint64_t)d.pad);
     if (op->pad_h != d.pad && (is_conv2d(d.kind))) add(0x1D00000000ull + (uint64_t)op->pad_h); // 1-D convolutions only
+    if (is_3d(op)) {
+        add(0x3D00000000ull + (uint64_t)op->depth);
+        add((uint64_t)op->kd);
+    }
     add((uint64_t)d.dilation);
     add((uint64_t)d.has_bias);
     add((uint64_t)d.relu);
@@ -236,6 +240,7 @@ extern "C" int32_t ms_trace_validate(const ms_op *op, const ms_space *space, con
                 if (p.compute_at) return reject("KH*KW*Cin = %" PRId64 " is not a multiple of the intrinsic's k = %d: compute_at must be 0", op->K, p.tile_unit[2]);
                 if (p.cache_read >= 5) return reject("a padded reduction cannot be staged directly to LDS");
             }
+            if (is_3d(op) && p.compute_at) return reject("3-D convolution: compute_at must be 0 (the resident patch is a set of image rows)");
             if (is_conv2d(d.kind) && op->nb > 1 && p.compute_at > 1) return reject("grouped convolution: compute_at must be 0 or 1 (the persistent modes have no group loop)");
             if (p.compute_at) {
                 // conv2d with the activations' cache-read under the workgroup tile loop: the input rows of
@@ -513,6 +518,9 @@ int32_t make_kernel_spec(const ms_op *op, const ms_variant_params *p, KernelSpec
             D.push_back(def("CV_STRIDE", d.stride));
             D.push_back(def("CV_PAD", d.pad));
             D.push_back(def("CV_PAD_H", op->pad_h));
+            D.push_back(def("CV_D", op->depth));
+            D.push_back(def("CV_KD", op->kd));
+            D.push_back(def("CV_OD", op->OD));
             D.push_back(def("CV_DIL", d.dilation));
             D.push_back(def("CV_TRANSPOSED", d.kind == MS_OP_CONV2D_TRANSPOSED_NHWC ? 1 : 0));
             D.push_back(def("HAS_BIAS", d.has_bias ? 1 : 0));
@@ -524,7 +532,7 @@ int32_t make_kernel_spec(const ms_op *op, const ms_variant_params *p, KernelSpec
             D.push_back(def("SB_B", op->N));              // column offset of a group in W [K][Cout]
             D.push_back(def("SB_K", d.dims[4]));
             D.push_back(def("SB_J", 1));
-            D.push_back(def("A_INST", d.dims[0] * d.dims[1] * d.dims[2] * d.dims[3]));
+            D.push_back(def("A_INST", d.dims[0] * op->depth * d.dims[1] * d.dims[2] * d.dims[3]));
             D.push_back(def("B_INST", op->K * op->N * op->nb));
         } else {
             D.push_back(def("HAS_BIAS", 0));

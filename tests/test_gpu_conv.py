@@ -400,3 +400,47 @@ def test_c1d_config_conv1d_256x64_to_128():
         if got is None:
             continue
         compare.assert_float_close(got, ref, compare.RTOL_HALF, "C1D trace %d" % n)
+
+
+@pytest.mark.parametrize("Cin,k,stride,pad,dil,D,H,W_", [(16, 3, 1, 1, 1, 4, 8, 8), (16, 3, 2, 1, 1, 6, 8, 16), (3, 7, 2, 3, 1, 6, 16, 16),
+                                                         (32, 1, 1, 0, 1, 2, 8, 8), (16, 3, 1, 2, 2, 4, 8, 8), (8, 2, 2, 0, 1, 4, 8, 8)])
+def test_conv3d_exact(Cin, k, stride, pad, dil, D, H, W_):
+    """3-D convolution (Appendix A.2: C3D): the depth is folded into the rows (n, od, oh, ow) and the reduction
+    (kd, kh, kw, ci) of the implicit GEMM by the im2col loader.  Integer-valued inputs, batch 2, 2 instances: bit-equal
+    fp32 outputs, also where KD*KH*KW*Cin is padded to the intrinsic's k."""
+    N, Cout = 2, 32
+    g = I.rng(96)
+    X = I.small_ints(g, (N, D, H, W_, Cin), -2, 2, "f16")
+    Wt = I.small_ints(g, (k, k, k, Cin, Cout), -2, 2, "f16")
+    bias = g.integers(-3, 4, size=Cout).astype(np.float32)
+    ref = O.conv3d_ndhwc(X, Wt, bias=bias, relu=True, stride=stride, pad=pad, dilation=dil)
+    assert ref[0].size // Cout * N % 16 == 0
+    op = B.conv3d_op(N, D, H, W_, Cin, Cout, k, stride=stride, pad=pad, out_dtype="f32", dilation=dil)
+    space = op.space()
+    for n in range(6):
+        t = B.trace_sample_valid(op, space, 97, n)
+        assert B.trace_validate(op, space, t).compute_at == 0
+        print("trace", n, t.decisions(), flush=True)
+        got = run_variant(op, space, t, [X, Wt, bias], "f32", ref.shape, instances=2)
+        if got is None:
+            continue
+        assert np.array_equal(got[0], ref) and np.array_equal(got[1], ref), "trace %d" % n
+
+
+def test_c3d_config_conv3d_16x224x224x3():
+    """The paper's C3D shape: 16 x 224 x 224 x 3 -> 8 x 112 x 112 x 64, 7 x 7 x 7, stride 2, padding 3; fp16 (K = 1029)."""
+    g = I.rng(98)
+    X = I.uniform(g, (1, 16, 224, 224, 3), 0.0, 1.0, "f16")
+    Wt = I.normal(g, (7, 7, 7, 3, 64), 0.02, "f16")
+    bias = I.normal(g, (64,), 0.05, "f32")
+    ref = O.conv3d_ndhwc(X, Wt, bias=bias, relu=True, stride=2, pad=3)
+    assert ref.shape == (1, 8, 112, 112, 64)
+    op = B.conv3d_op(1, 16, 224, 224, 3, 64, 7, stride=2, pad=3)
+    space = op.space()
+    for n in range(3):
+        t = B.trace_sample_valid(op, space, 99, n)
+        print("trace", n, t.decisions(), flush=True)
+        got = run_variant(op, space, t, [X, Wt, bias], "f16", ref.shape)
+        if got is None:
+            continue
+        compare.assert_float_close(got, ref, compare.RTOL_HALF, "C3D trace %d" % n)

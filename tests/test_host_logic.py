@@ -509,3 +509,22 @@ def test_conv1d_descriptor_runs_on_the_conv2d_space():
     assert op2.loops()[0] == ("i", 2 * 128, False)
     with pytest.raises(B.MsError):
         B.conv1d_op(1, 2, 8, 16, 5, stride=1, pad=0)                                      # empty output
+
+
+def test_conv3d_descriptor_and_space():
+    op = B.conv3d_op(1, 16, 224, 224, 3, 64, 7, stride=2, pad=3)
+    assert op.loops() == [("i", 8 * 112 * 112, False), ("j", 64, False), ("k", 343 * 3, True)]
+    assert op.desc().kind == B.OP_CONV3D_NDHWC and list(op.desc().dims)[:7] == [1, 16, 224, 224, 3, 64, 7]
+    assert op.tensor_bytes(0) == 16 * 224 * 224 * 3 * 2 and op.tensor_bytes(1) == 1029 * 64 * 2
+    sp = op.space()
+    ca = [sp.slots[i] for i in range(sp.n_slots) if sp.slots[i].name == b"compute_at"][0]
+    assert list(ca.weight)[:5] == [1, 0, 0, 0, 0]
+    op2 = B.conv3d_op(2, 6, 8, 8, 16, 32, 3, stride=1, pad=1)
+    sp2 = op2.space()
+    t = B.trace_sample_valid(op2, sp2, 5, 0)
+    p = B.trace_validate(op2, sp2, t)
+    cov = B.variant_coverage(op2, p, 2 * 6 * 8 * 8 * 32)
+    assert cov.min() == 1 and cov.max() == 1 and "op=conv3d_ndhwc" in B.trace_to_text(op2, sp2, t)
+    # another depth is another kernel
+    op3 = B.conv3d_op(2, 5, 8, 8, 16, 32, 3, stride=1, pad=1)
+    assert B.trace_validate(op3, op3.space(), B.trace_sample_valid(op3, op3.space(), 5, 0)).key != p.key
