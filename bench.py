@@ -46,6 +46,7 @@ def workload_inputs(name, seed):
         "x8_gemm_nt_f16_1024": lambda: list(I.c2nt(seed)),
         "x6_t2d_f16_4x4x512": lambda: list(I.t2d(seed)),
         "x9_c1d_f16_256x64": lambda: list(I.c1d(seed)),
+        "x10_c3d_f16_16x224x224x3": lambda: list(I.c3d(seed)),
         "x7_grp_f16_56x56x64_g4": lambda: list(I.grp(seed)),
         "x5_cbr_f16_224x224x3": lambda: list(I.cbr(seed)),
         "x5b_cbr_f16_224x224x4": lambda: list(I.cbr4(seed)),
@@ -72,6 +73,8 @@ def oracle_run(name, ins):
         return O.conv2d_nhwc(ins[0], ins[1], bias=ins[2], relu=True, stride=2, pad=1, groups=4)
     if name == "x8_gemm_nt_f16_1024":
         return O.bmm(ins[0], ins[1], trans_b=True)
+    if name == "x10_c3d_f16_16x224x224x3":
+        return O.conv3d_ndhwc(ins[0], ins[1], bias=ins[2], relu=True, stride=2, pad=3)
     if name == "x9_c1d_f16_256x64":
         return O.conv1d_nwc(ins[0], ins[1], bias=ins[2], relu=True, stride=2, pad=1)
     if name == "x6_t2d_f16_4x4x512":
@@ -93,6 +96,7 @@ OUT_SHAPE = {
     "x3_softmax_f32_256x256": ((1, 256, 256), "f32"), "x4_norm_f32_256x256": ((1,), "f32"),
     "x5_cbr_f16_224x224x3": ((1, 112, 112, 64), "f16"), "x5b_cbr_f16_224x224x4": ((1, 112, 112, 64), "f16"),
     "x8_gemm_nt_f16_1024": ((1, 1024, 1024), "f16"), "x9_c1d_f16_256x64": ((1, 128, 128), "f16"),
+    "x10_c3d_f16_16x224x224x3": ((1, 8, 112, 112, 64), "f16"),
     "x6_t2d_f16_4x4x512": ((1, 8, 8, 256), "f16"), "x7_grp_f16_56x56x64_g4": ((1, 28, 28, 128), "f16"),
 }
 BOUND = {  # which roofline bounds the workload (AI vs ridge), and the in-dtype
@@ -105,6 +109,7 @@ BOUND = {  # which roofline bounds the workload (AI vs ridge), and the in-dtype
     "x7_grp_f16_56x56x64_g4": ("hbm", "f16"),  # 45 flop per byte
     "x8_gemm_nt_f16_1024": ("mfma", "f16"),  # config 2 with B stored [N][K] (both operands contiguous along k)
     "x9_c1d_f16_256x64": ("hbm", "f16"),  # 55 flop per byte
+    "x10_c3d_f16_16x224x224x3": ("mfma", "f16"),  # 743 flop per byte
     "x6_t2d_f16_4x4x512": ("hbm", "f16"),  # 16 flop per byte: the 4 MiB of weights are read once per instance
 }
 

@@ -184,3 +184,10 @@ def c1d(seed=0, dtype="f16"):
     W ~ N(0, 0.05) as [3][64][128], bias ~ N(0, 0.05) fp32."""
     g = rng(seed)
     return (uniform(g, (1, 256, 64), 0.0, 1.0, dtype), normal(g, (3, 64, 128), 0.05, dtype), normal(g, (128,), 0.05, "f32"))
+
+
+def c3d(seed=0, dtype="f16"):
+    """3-D convolution workload (16 x 224 x 224 x 3 -> 8 x 112 x 112 x 64, 7 x 7 x 7, stride 2, padding 3):
+    X ~ U[0, 1], W ~ N(0, 0.02), bias ~ N(0, 0.05) fp32."""
+    g = rng(seed)
+    return (uniform(g, (1, 16, 224, 224, 3), 0.0, 1.0, dtype), normal(g, (7, 7, 7, 3, 64), 0.02, dtype), normal(g, (64,), 0.05, "f32"))

@@ -26,6 +26,7 @@ WORKLOADS = {
     "x7_grp_f16_56x56x64_g4": (lambda: B.conv2d_op(1, 56, 56, 64, 128, 3, 3, stride=2, pad=1, groups=4), 512),
     "x8_gemm_nt_f16_1024": (lambda: B.bmm_op(1, 1024, 1024, 1024, True, "f16"), 64),
     "x9_c1d_f16_256x64": (lambda: B.conv1d_op(1, 256, 64, 128, 3, stride=2, pad=1), 4096),
+    "x10_c3d_f16_16x224x224x3": (lambda: B.conv3d_op(1, 16, 224, 224, 3, 64, 7, stride=2, pad=3), 8),
     "x3_softmax_f32_256x256": (lambda: B.softmax_op(1, 256, 256), 2048),
     "x4_norm_f32_256x256": (lambda: B.norm_op(1, 256, 256), 2048),
 }
