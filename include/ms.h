@@ -250,6 +250,11 @@ typedef struct ms_slot {
 #define MS_SPACE_TENSORIZE_F32 0x100u /* opt-in, not part of the default: fp32 operators on the fp32 matrix-core
                                          intrinsics (16x16x4, 32x32x2) instead of the vector ALUs; the products are
                                          summed in another order than in the vector kernels, within the fp32 tolerance */
+#define MS_SPACE_TAP_ROWS 0x200u      /* opt-in, conv2d with dense filters and one group: the reduction is laid out as KH
+                                         runs of KW*Cin contiguous elements (one filter row across all its taps), each
+                                         rounded up to the intrinsic's k.  With few input channels (first layers) a
+                                         matrix-core k step then reads consecutive pixels of an input row instead of
+                                         the channels of one pixel; compute_at 0 and 1 only */
 #define MS_SPACE_DEFAULT 0xffu       /* every module above except the opt-in one; masks with bit 31 set (the
                                          all-ones default of earlier tuning records) mean the same */
 
@@ -332,7 +337,8 @@ typedef struct ms_variant_params {
     int32_t vec_b;          /* elements per global load of B */
     int32_t cache_write;    /* 0, 1 as in MS_SLOT_CACHE_WRITE */
     int32_t compute_at;     /* 0, 1 as in MS_SLOT_COMPUTE_AT */
-    int32_t reserved[5];
+    int32_t tap_rows;       /* 1: the reduction of the MS_SPACE_TAP_ROWS layout (tile_unit[2] * the k split = KH * run) */
+    int32_t reserved[4];
     uint64_t key;           /* hash of everything that selects the kernel */
 } ms_variant_params;
 

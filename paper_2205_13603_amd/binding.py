@@ -21,6 +21,7 @@ SLOT_PERFECT_TILE, SLOT_CATEGORICAL = 0, 1
 SPACE_TENSORIZE, SPACE_CACHE_READ, SPACE_VECTORIZE, SPACE_UNROLL, SPACE_STORAGE_ALIGN, SPACE_REORDER, SPACE_CACHE_WRITE = 1, 2, 4, 8, 16, 32, 64
 SPACE_COMPUTE_AT = 128
 SPACE_TENSORIZE_F32 = 0x100  # opt-in: fp32 operators on the fp32 matrix-core intrinsics
+SPACE_TAP_ROWS = 0x200  # opt-in: conv2d reduction laid out as filter rows (first layers with few input channels)
 SPACE_DEFAULT = 0xFF
 FAM_GEMM_ALU, FAM_GEMM_MFMA, FAM_DWCONV, FAM_REDUCE = range(4)
 MAX_SLOTS, MAX_FACTORS, MAX_CANDS, MAX_LOOPS = 16, 4, 8, 8
@@ -80,7 +81,7 @@ class ms_variant_params(C.Structure):
                 ("block_n", C.c_int32), ("block_k", C.c_int32), ("grid", C.c_int32 * 3), ("threads", C.c_int32),
                 ("waves", C.c_int32), ("acc_per_thread", C.c_int32), ("lds_bytes", C.c_int32),
                 ("cache_read", C.c_int32), ("vec", C.c_int32), ("unroll", C.c_int32), ("unroll_k1", C.c_int32),
-                ("unroll_k2", C.c_int32), ("lds_pad", C.c_int32), ("reorder", C.c_int32), ("vec_b", C.c_int32), ("cache_write", C.c_int32), ("compute_at", C.c_int32), ("reserved", C.c_int32 * 5),
+                ("unroll_k2", C.c_int32), ("lds_pad", C.c_int32), ("reorder", C.c_int32), ("vec_b", C.c_int32), ("cache_write", C.c_int32), ("compute_at", C.c_int32), ("tap_rows", C.c_int32), ("reserved", C.c_int32 * 4),
                 ("key", C.c_uint64)]
 
     def as_dict(self):

@@ -81,6 +81,14 @@
 #ifndef CV_XC
 #define CV_XC CV_CIN               // channels per pixel of X
 #endif
+// Filter-row layout of the reduction (CV_TAPROWS 1): k = (kh, q) with q running over the KW * Cin contiguous elements of
+// one filter row across all its taps, rounded up to CV_KR (a multiple of the intrinsic's k); q >= KW * Cin is padding.
+// In the input, the elements of one run are contiguous too (consecutive pixels of a row), so a matrix-core k step reads
+// a piece of an image row: what a first layer with 3 or 4 channels per pixel needs.
+#ifndef CV_TAPROWS
+#define CV_TAPROWS 0
+#define CV_KR 0
+#endif
 #ifndef CV_D
 #define CV_D 1                     // 3-D convolution: input depth, filter depth, output depth (padded like the columns)
 #define CV_KD 1
@@ -248,9 +256,12 @@ template <int ROWS, int V> struct kmajor_stage {
 #if IS_CONV
 // A reduction extent KH*KW*Cin that is no multiple of the intrinsic's k is rounded up: the loaders of both operands
 // deliver zeros for k >= KH*KW*Cin (im2col staging only)
-constexpr int CV_KREAL = CV_KD * CV_KH * CV_KW * CV_CIN;
+constexpr int CV_KREAL = CV_TAPROWS ? CV_KH * CV_KR : CV_KD * CV_KH * CV_KW * CV_CIN;
+constexpr int CV_RUN = CV_KW * CV_CIN; // real elements of a filter row
 constexpr bool K_PADDED = K0 * BK != CV_KREAL;
 static_assert(K0 * BK >= CV_KREAL && K0 * BK - CV_KREAL < MI_K, "the k split covers the reduction, padded by less than one intrinsic");
+static_assert(!CV_TAPROWS || (CV_KR % MI_K == 0 && CV_KR >= CV_RUN && !K_PADDED && CV_DIL == 1 && COMPUTE_AT <= 1 && !CV_TRANSPOSED && CV_D == 1 &&
+                              CV_KD == 1 && DIM_B == 1), "filter-row layout: plain conv2d, im2col staging or the resident patch of one tile");
 static_assert(!K_PADDED || COMPUTE_AT == 0, "a padded reduction needs the im2col loader");
 static_assert(!CV_TRANSPOSED || (COMPUTE_AT == 0 && CV_DIL == 1), "the transposed convolution exists in the im2col loader only");
 static_assert((CV_D == 1 && CV_KD == 1) || (COMPUTE_AT == 0 && !CV_TRANSPOSED), "3-D convolution exists in the im2col loader only");
@@ -260,7 +271,18 @@ template <int V> __device__ __forceinline__ vec_t<in_t, V> load_conv_a(const in_
 {
     // row = (n, od, oh, ow), k = (kd, kh, kw, ci); od = kd = 0 for a 2-D convolution (CV_OD = CV_KD = 1)
     const int ow = row % CV_OW, oh = (row / CV_OW) % CV_OH, od = (row / (CV_OW * CV_OH)) % CV_OD, n = row / (CV_OW * CV_OH * CV_OD);
+#if CV_TAPROWS
+    const int q = k % CV_KR, kh = k / CV_KR, kd = 0;
+    const int ci = q % CV_CIN, kw = q / CV_CIN; // kw >= CV_KW: padding of the run
+    if (q >= CV_RUN) {
+        vec_t<in_t, V> z;
+#pragma unroll
+        for (int e = 0; e < V; ++e) z.v[e] = 0;
+        return z;
+    }
+#else
     const int ci = k % CV_CIN, kw = (k / CV_CIN) % CV_KW, kh = (k / (CV_CIN * CV_KW)) % CV_KH, kd = k / (CV_CIN * CV_KW * CV_KH);
+#endif
     const int id = CV_D > 1 || CV_KD > 1 ? od * CV_STRIDE + kd * CV_DIL - CV_PAD : 0;
 #if CV_TRANSPOSED
     // transposed convolution: input element ih reaches outputs ih * stride + kh - pad, so output row oh takes tap kh
@@ -375,6 +397,19 @@ __device__ __forceinline__ void jmajor_load(jmajor_stage &st, const in_t *__rest
                     for (int c = 0; c < VJ; ++c) st.r[it][q].v[c] = 0;
                     continue;
                 }
+#if CV_TAPROWS
+                {
+                    // row (kh, qq) of the filter-row layout is row kh * KW * Cin + qq of W, or padding
+                    const int kk = (int)k0e + kg * KPL + q, qq = kk % CV_KR;
+                    if (qq >= CV_RUN) {
+#pragma unroll
+                        for (int c = 0; c < VJ; ++c) st.r[it][q].v[c] = 0;
+                    } else {
+                        st.r[it][q] = *reinterpret_cast<const vec_t<in_t, VJ> *>(src + (long)((kk / CV_KR) * CV_RUN + qq) * k_stride + col0 + jv * VJ);
+                    }
+                    continue;
+                }
+#endif
 #endif
                 if (NTHREADS % JV == 0) {
                     const char *ub = (const char *)(src + (k0e + (it * (NTHREADS / JV)) * KPL + q) * k_stride + col0);
@@ -418,11 +453,15 @@ __device__ __forceinline__ void jmajor_store(const jmajor_stage &st, char *__res
 // ---- resident input patch (COMPUTE_AT 1)
 constexpr int P_ROWS_OUT = BM % CV_OW == 0 ? BM / CV_OW : (CV_OW + BM - 2) / CV_OW + 1; // output rows a tile can touch
 constexpr int P_R = (P_ROWS_OUT - 1) * CV_STRIDE + CV_DIL * (CV_KH - 1) + 1; // patch rows (taps CV_DIL apart)
-constexpr int P_W = (CV_OW - 1) * CV_STRIDE + CV_DIL * (CV_KW - 1) + 1;      // patch columns (column pc = input column pc - pad)
-constexpr int P_PS = CV_CIN * ES + (LDS_PAD ? 16 : 0);      // bytes per patch pixel; the pad staggers neighbouring pixels over the banks
+// filter-row layout: dense pixels (a run crosses pixel boundaries), plus the pixels that the padding of a run reaches
+// behind the last tap (zeros or the next pixels: finite values that meet zero weights), rows at multiples of 4 bytes
+constexpr int P_W0 = (CV_OW - 1) * CV_STRIDE + CV_DIL * (CV_KW - 1) + 1 + (CV_TAPROWS ? (CV_KR - CV_RUN + CV_CIN - 1) / CV_CIN : 0);
+constexpr int P_PS = CV_CIN * ES + (LDS_PAD && !CV_TAPROWS ? 16 : 0); // bytes per patch pixel; the pad staggers neighbouring pixels over the banks
+constexpr int P_W = P_W0 + (CV_TAPROWS && (P_W0 * P_PS) % 4 ? 1 : 0);  // patch columns (column pc = input column pc - pad)
 constexpr int P_RS = P_W * P_PS;                            // bytes per patch row
 constexpr int PATCH_BYTES = ((P_R * P_RS + 15) / 16) * 16;
-static_assert(CV_CIN % MI_K == 0, "resident input patch: an MFMA k step must stay inside one filter tap");
+static_assert(CV_TAPROWS || CV_CIN % MI_K == 0, "resident input patch: an MFMA k step must stay inside one filter tap");
+static_assert(!CV_TAPROWS || ((CV_STRIDE * CV_CIN * ES) % 4 == 0 && P_RS % 4 == 0 && FRAG_BYTES % 4 == 0), "filter-row layout: fragments start at multiples of 4 bytes");
 static_assert((CV_OH * CV_OW) % BM == 0, "resident input patch: tiles must not straddle images");
 
 struct conv_ctx {
@@ -522,10 +561,28 @@ __device__ __forceinline__ void conv_ctx_init(conv_ctx &cx, const char *patch, i
         }
 }
 
+// a lane's A fragment from the patch; in the filter-row layout it starts at a multiple of 4 bytes only
+__device__ __forceinline__ frag_t patch_frag(const char *__restrict__ p)
+{
+#if CV_TAPROWS
+    frag_t f;
+    const unsigned *w = reinterpret_cast<const unsigned *>(__builtin_assume_aligned(p, 4));
+    unsigned *o = reinterpret_cast<unsigned *>(&f);
+#pragma unroll
+    for (int i = 0; i < FRAG_BYTES / 4; ++i) o[i] = w[i];
+    return f;
+#else
+    return *reinterpret_cast<const frag_t *>(p);
+#endif
+}
+
 // byte offset inside the patch of MFMA k step `step` of tile k0, relative to a pixel's (tap 0, 0, channel 0)
 __device__ __forceinline__ int conv_koff(int k0, int step)
 {
     const int kg = k0 * BK + step * MI_K; // wave-uniform
+#if CV_TAPROWS
+    return (kg / CV_KR) * P_RS + (kg % CV_KR) * ES; // filter row kh, then the position inside the run
+#endif
     const int tap = kg / CV_CIN, ci = kg % CV_CIN;
     const int kh = tap / CV_KW, kw = tap % CV_KW;
     return kh * CV_DIL * P_RS + kw * CV_DIL * P_PS + ci * ES;
@@ -591,7 +648,7 @@ __device__ __forceinline__ void read_frags(frag_t (&fa)[K3][TM], frag_t (&fb)[K3
 #if CONV_PATCH
         const int koff = conv_koff(kcur, step);
 #pragma unroll
-        for (int tm = 0; tm < TM; ++tm) fa[q][tm] = *reinterpret_cast<const frag_t *>(cx.patch + (cx.pix[tm] + koff));
+        for (int tm = 0; tm < TM; ++tm) fa[q][tm] = patch_frag(cx.patch + (cx.pix[tm] + koff));
 #else
 #pragma unroll
         for (int r1 = 0; r1 < I1; ++r1)

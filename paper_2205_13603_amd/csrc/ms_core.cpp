@@ -511,7 +511,9 @@ extern "C" int32_t ms_space_describe(const ms_op *op, uint32_t flags, ms_space *
     if (flags & MS_SPACE_TENSORIZE_F32) flags |= MS_SPACE_TENSORIZE;
     if (d.kind == MS_OP_DWCONV2D_NHWC) flags &= ~(MS_SPACE_TENSORIZE | MS_SPACE_VECTORIZE | MS_SPACE_STORAGE_ALIGN | MS_SPACE_CACHE_WRITE);
     if (d.kind != MS_OP_CONV2D_NHWC) flags &= ~MS_SPACE_COMPUTE_AT; // the resident-patch modes assume the direct index map
-    flags &= 0x1ffu;
+    // the filter-row layout of the reduction: plain conv2d only (dense filter, one group, two dimensions)
+    if (!(d.kind == MS_OP_CONV2D_NHWC && op->nb == 1 && !is_3d(op) && d.dilation == 1)) flags &= ~MS_SPACE_TAP_ROWS;
+    flags &= 0x3ffu;
     if (d.kind == MS_OP_SOFTMAX || d.kind == MS_OP_NORM) {
         // rows i: [workgroups, serial, thread groups, rows of one group at a time]; reduction k: [serial, loads in
         // flight, lanes of a group (cross-thread reduction), vector]
@@ -569,6 +571,11 @@ extern "C" int32_t ms_space_describe(const ms_op *op, uint32_t flags, ms_space *
                 int mnk[3];
                 mfma_dims(t->candidates[c], &mnk[0], &mnk[1], &mnk[2]);
                 s->extent_by_choice[c] = (ext[l] + mnk[l] - 1) / mnk[l];
+                if (l == 2 && (flags & MS_SPACE_TAP_ROWS)) {
+                    // KH runs of KW * Cin elements, each rounded up to the intrinsic's k
+                    const int64_t run = d.dims[6] * d.dims[3];
+                    s->extent_by_choice[c] = d.dims[5] * ((run + mnk[2] - 1) / mnk[2]);
+                }
             }
         }
         if (flags & MS_SPACE_UNROLL) add_cat(out, MS_SLOT_UNROLL, "unroll", {0, 16, 64});
@@ -609,6 +616,8 @@ extern "C" int32_t ms_space_describe(const ms_op *op, uint32_t flags, ms_space *
                     if (sl.slot_id == MS_SLOT_COMPUTE_AT && sl.candidates[c] > 0 &&
                         ((d.dims[3] / op->nb) % 8 || (op->nb > 1 && sl.candidates[c] > 1) || is_3d(op)))
                         sl.weight[c] = 0;
+                    if (sl.slot_id == MS_SLOT_COMPUTE_AT && (flags & MS_SPACE_TAP_ROWS))
+                        sl.weight[c] = sl.candidates[c] == 0 || (sl.candidates[c] == 1 && (d.stride * d.dims[3] * op->in_size) % 4 == 0) ? 1 : 0;
                 }
             }
         }

@@ -87,6 +87,7 @@ uint64_t hash_params(const ms_op *op, const ms_variant_params *p)
     add((uint64_t)p->lds_pad);
     add((uint64_t)p->reorder);
     add((uint64_t)p->compute_at);
+    if (p->tap_rows) add(0x7A9ull);
     return h;
 }
 
@@ -157,6 +158,7 @@ extern "C" int32_t ms_trace_validate(const ms_op *op, const ms_space *space, con
     p.vec_b = (int32_t)cat_value(space, trace, MS_SLOT_VECTORIZE_B, 1);
     p.cache_write = (int32_t)cat_value(space, trace, MS_SLOT_CACHE_WRITE, 0);
     p.lds_pad = (int32_t)cat_value(space, trace, MS_SLOT_STORAGE_ALIGN, 0);
+    p.tap_rows = (space->flags & MS_SPACE_TAP_ROWS) && d.kind == MS_OP_CONV2D_NHWC && op->nb == 1 && !is_3d(op) && d.dilation == 1 ? 1 : 0;
     p.reorder = (int32_t)cat_value(space, trace, MS_SLOT_REORDER, 0);
     p.compute_at = (int32_t)cat_value(space, trace, MS_SLOT_COMPUTE_AT, 0);
 
@@ -235,13 +237,19 @@ extern "C" int32_t ms_trace_validate(const ms_op *op, const ms_space *space, con
                 int64_t btile = d.b_strides[2] == 1 ? ((bk * (bn / ce) + 63) / 64) * 1024 : bn * bk * es;
                 lds = (int64_t)(p.cache_read - 3) * (bm * bk * es + btile);
             }
-            if (is_conv2d(d.kind) && op->K % p.tile_unit[2]) {
+            if (is_conv2d(d.kind) && op->K % p.tile_unit[2] && !p.tap_rows) {
                 // the k split covers the reduction rounded up to the intrinsic's k; only the im2col loader pads with zeros
                 if (p.compute_at) return reject("KH*KW*Cin = %" PRId64 " is not a multiple of the intrinsic's k = %d: compute_at must be 0", op->K, p.tile_unit[2]);
                 if (p.cache_read >= 5) return reject("a padded reduction cannot be staged directly to LDS");
             }
             if (is_3d(op) && p.compute_at) return reject("3-D convolution: compute_at must be 0 (the resident patch is a set of image rows)");
             if (is_conv2d(d.kind) && op->nb > 1 && p.compute_at > 1) return reject("grouped convolution: compute_at must be 0 or 1 (the persistent modes have no group loop)");
+            if (p.tap_rows) {
+                // the reduction as KH runs of KW * Cin contiguous elements, each rounded up to the intrinsic's k
+                if (p.compute_at > 1) return reject("filter-row layout: compute_at must be 0 or 1");
+                if (p.cache_read >= 5) return reject("filter-row layout: no direct-to-LDS staging");
+                if (p.compute_at == 1 && (d.stride * d.dims[3] * es) % 4) return reject("filter-row layout with a resident patch: pixels of an output row must start at multiples of 4 bytes");
+            }
             if (p.compute_at) {
                 // conv2d with the activations' cache-read under the workgroup tile loop: the input rows of
                 // the tile (zero halo included) are resident, only the weights are staged per k step
@@ -252,11 +260,18 @@ extern "C" int32_t ms_trace_validate(const ms_op *op, const ms_space *space, con
                     return reject("helper wavefronts prefetch the patch and write the staged tile: cache_read 2 and cache_write 1");
                 if (p.compute_at >= 2 && p.reorder != 0) return reject("persistent workgroups with resident weights walk the tile list in order: reorder must be 0");
                 int64_t cin = d.dims[3] / op->nb, ohw = op->OH * op->OW; // channels of one group
-                if (cin % p.tile_unit[2]) return reject("resident input patch: Cin = %" PRId64 " is not a multiple of the intrinsic's k = %d", cin, p.tile_unit[2]);
+                if (cin % p.tile_unit[2] && !p.tap_rows) return reject("resident input patch: Cin = %" PRId64 " is not a multiple of the intrinsic's k = %d", cin, p.tile_unit[2]);
                 if (ohw % bm) return reject("resident input patch: the %" PRId64 "-pixel tile straddles images of %" PRId64 " output pixels", bm, ohw);
                 int64_t rows = bm % op->OW == 0 ? bm / op->OW : (op->OW + bm - 2) / op->OW + 1;
                 int64_t pr = (rows - 1) * d.stride + d.dilation * (d.dims[5] - 1) + 1, pw = (op->OW - 1) * d.stride + d.dilation * (d.dims[6] - 1) + 1;
                 int64_t ps = cin * es + (p.lds_pad ? 16 : 0);
+                if (p.tap_rows) {
+                    // dense pixels (a run crosses pixel boundaries), and the pixels that the padding of the last run reads
+                    const int64_t run = d.dims[6] * cin, kr = (run + p.tile_unit[2] - 1) / p.tile_unit[2] * p.tile_unit[2];
+                    ps = cin * es;
+                    pw += (kr - run + cin - 1) / cin;
+                    if ((pw * ps) % 4) pw += 1; // rows start at multiples of 4 bytes (2-byte elements, odd Cin)
+                }
                 int64_t patch = pr * pw * ps;
                 lds = (int64_t)(p.cache_read >= 2 ? 2 : 1) * (bk / kp) * rowsB + patch;
                 if (p.compute_at >= 2) lds = (int64_t)p.tk[0] * (bk / kp) * rowsB + patch; // all k steps of the weights
@@ -265,7 +280,7 @@ extern "C" int32_t ms_trace_validate(const ms_op *op, const ms_space *space, con
                     lds = (bk / kp) * rowsB + patch;
                     if (p.cache_read > 2) return reject("with the weights in registers cache_read is 1 (patch loaded between tiles) or 2 (next patch prefetched)");
                 }
-                if ((cin * es) % 16 && p.lds_pad) return reject("resident input patch: padded pixels need Cin * element size to be a multiple of 16 bytes");
+                if ((cin * es) % 16 && p.lds_pad && !p.tap_rows) return reject("resident input patch: padded pixels need Cin * element size to be a multiple of 16 bytes");
                 if (d.dims[0] * d.dims[1] * d.dims[2] * d.dims[3] > 0x7fffffff / es) return reject("resident input patch: one instance of X exceeds 32-bit byte offsets");
             }
             if (p.reorder == 3 && p.cache_read < 5) return reject("persistent workgroups (reorder 3) are built on direct-to-LDS staging (cache_read 5, 6, 7)");
@@ -523,6 +538,8 @@ int32_t make_kernel_spec(const ms_op *op, const ms_variant_params *p, KernelSpec
             D.push_back(def("CV_OD", op->OD));
             D.push_back(def("CV_DIL", d.dilation));
             D.push_back(def("CV_TRANSPOSED", d.kind == MS_OP_CONV2D_TRANSPOSED_NHWC ? 1 : 0));
+            D.push_back(def("CV_TAPROWS", p->tap_rows));
+            D.push_back(def("CV_KR", (d.dims[6] * d.dims[3] + p->tile_unit[2] - 1) / p->tile_unit[2] * p->tile_unit[2]));
             D.push_back(def("HAS_BIAS", d.has_bias ? 1 : 0));
             D.push_back(def("RELU", d.relu ? 1 : 0));
             // implicit GEMM view: A rows are output pixels, B = W as [K][N]

@@ -444,3 +444,64 @@ def test_c3d_config_conv3d_16x224x224x3():
         if got is None:
             continue
         compare.assert_float_close(got, ref, compare.RTOL_HALF, "C3D trace %d" % n)
+
+
+@pytest.mark.parametrize("Cin,k,stride,pad,H,W_", [(3, 7, 2, 3, 32, 32), (4, 3, 1, 1, 16, 16), (3, 3, 1, 1, 16, 16), (2, 5, 2, 2, 16, 32), (8, 3, 1, 1, 8, 16),
+                                                   (4, 7, 2, 3, 32, 16)])
+def test_conv_filter_row_layout_exact(Cin, k, stride, pad, H, W_):
+    """The opt-in filter-row layout of the reduction (k = filter row, then the KW * Cin contiguous elements of that row,
+    rounded up to the intrinsic's k): im2col staging and, where pixels start at multiples of 4 bytes, the resident patch,
+    whose fragments are pieces of image rows.  Integer-valued inputs, batch 2, 2 instances: bit-equal fp32 outputs."""
+    N, Cout = 2, 32
+    g = I.rng(101)
+    X = I.small_ints(g, (N, H, W_, Cin), -2, 2, "f16")
+    Wt = I.small_ints(g, (k, k, Cin, Cout), -2, 2, "f16")
+    bias = g.integers(-3, 4, size=Cout).astype(np.float32)
+    ref = O.conv2d_nhwc(X, Wt, bias=bias, relu=True, stride=stride, pad=pad)
+    OH, OW = ref.shape[1], ref.shape[2]
+    op = B.conv2d_op(N, H, W_, Cin, Cout, k, k, stride=stride, pad=pad, out_dtype="f32")
+    space = op.space(B.SPACE_DEFAULT | B.SPACE_TAP_ROWS)
+    assert space.flags & B.SPACE_TAP_ROWS
+    patch_ok = (stride * Cin * 2) % 4 == 0
+    want = {0: 4, 1: 5 if patch_ok else 0}
+    idx = 0
+    while any(want.values()) and idx < 800:
+        t = B.trace_sample_valid(op, space, 102, idx)
+        idx += 1
+        p = B.trace_validate(op, space, t)
+        assert p.tap_rows == 1 and p.compute_at <= 1 and (patch_ok or p.compute_at == 0)
+        if want[p.compute_at] == 0:
+            continue
+        want[p.compute_at] -= 1
+        print("trace", idx, "compute_at", p.compute_at, t.decisions(), flush=True)
+        got = run_variant(op, space, t, [X, Wt, bias], "f32", (N, OH, OW, Cout), instances=2)
+        if got is None:
+            continue
+        assert np.array_equal(got[0], ref) and np.array_equal(got[1], ref), "trace %d" % idx
+    assert not any(want.values()), want
+
+
+def test_cbr_first_layer_filter_row_layout():
+    """The paper's CBR shape in the filter-row layout (K = 7 rows of 21 -> 32 elements), fp16, both cache-read locations."""
+    g = I.rng(63)
+    X = I.uniform(g, (1, 224, 224, 3), 0.0, 1.0, "f16")
+    Wt = I.normal(g, (7, 7, 3, 64), 0.05, "f16")
+    bias = I.normal(g, (64,), 0.05, "f32")
+    ref = O.conv2d_nhwc(X, Wt, bias=bias, relu=True, stride=2, pad=3)
+    op = B.conv2d_op(1, 224, 224, 3, 64, 7, 7, stride=2, pad=3)
+    space = op.space(B.SPACE_DEFAULT | B.SPACE_TAP_ROWS)
+    want = {0: 2, 1: 4}
+    idx = 0
+    while any(want.values()) and idx < 400:
+        t = B.trace_sample_valid(op, space, 104, idx)
+        idx += 1
+        ca = B.trace_validate(op, space, t).compute_at
+        if want[ca] == 0:
+            continue
+        want[ca] -= 1
+        print("trace", idx, "compute_at", ca, t.decisions(), flush=True)
+        got = run_variant(op, space, t, [X, Wt, bias], "f16", ref.shape)
+        if got is None:
+            continue
+        compare.assert_float_close(got, ref, compare.RTOL_HALF, "CBR filter rows trace %d" % idx)
+    assert not any(want.values()), want
