@@ -528,3 +528,34 @@ def test_conv3d_descriptor_and_space():
     # another depth is another kernel
     op3 = B.conv3d_op(2, 5, 8, 8, 16, 32, 3, stride=1, pad=1)
     assert B.trace_validate(op3, op3.space(), B.trace_sample_valid(op3, op3.space(), 5, 0)).key != p.key
+
+
+def test_filter_row_layout_space_and_rules():
+    op = B.conv2d_op(1, 224, 224, 3, 64, 7, 7, stride=2, pad=3)
+    sp = op.space(B.SPACE_DEFAULT | B.SPACE_TAP_ROWS)
+    assert sp.flags & B.SPACE_TAP_ROWS
+    ks = [sp.slots[i] for i in range(sp.n_slots) if sp.slots[i].name == b"k"][0]
+    tz = sp.slots[0]
+    # 7 runs of 21 elements, each rounded up to the intrinsic's k: 7*32/16, 7*24/8, 7*32/32, 7*32/16
+    assert {tz.candidates[c]: ks.extent_by_choice[c] for c in range(tz.n_candidates)} == {161616: 14, 323208: 21, 161632: 7, 323216: 14}
+    ca = [sp.slots[i] for i in range(sp.n_slots) if sp.slots[i].name == b"compute_at"][0]
+    assert list(ca.weight)[:5] == [1, 1, 0, 0, 0]
+    seen = set()
+    for idx in range(40):
+        t = B.trace_sample_valid(op, sp, 11, idx)
+        p = B.trace_validate(op, sp, t)
+        assert p.tap_rows == 1 and p.compute_at <= 1 and p.tile_unit[2] * p.tk[0] * p.tk[1] * p.tk[2] * p.tk[3] in (224, 168)
+        seen.add(p.compute_at)
+        assert "op=conv2d_nhwc" in B.trace_to_text(op, sp, t)
+    assert seen == {0, 1}
+    # the same trace in the default space is another kernel (or invalid): the layout is part of the key
+    assert not (op.space().flags & B.SPACE_TAP_ROWS)
+    # pixels that start at odd multiples of 2 bytes: im2col staging only
+    op2 = B.conv2d_op(1, 16, 16, 3, 32, 3, 3, stride=1, pad=1)
+    sp2 = op2.space(B.SPACE_DEFAULT | B.SPACE_TAP_ROWS)
+    ca2 = [sp2.slots[i] for i in range(sp2.n_slots) if sp2.slots[i].name == b"compute_at"][0]
+    assert list(ca2.weight)[:5] == [1, 0, 0, 0, 0]
+    # the flag is dropped where the layout does not apply: dilated, grouped, transposed, other operators
+    assert not (B.conv2d_op(1, 16, 16, 4, 32, 3, 3, pad=2, dilation=2).space(0x2ff).flags & B.SPACE_TAP_ROWS)
+    assert not (B.conv2d_op(1, 16, 16, 8, 32, 3, 3, pad=1, groups=2).space(0x2ff).flags & B.SPACE_TAP_ROWS)
+    assert not (B.gemm_op(128, 128, 128, "f16").space(0x2ff).flags & B.SPACE_TAP_ROWS)
