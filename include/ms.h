@@ -254,7 +254,8 @@ typedef struct ms_slot {
                                          runs of KW*Cin contiguous elements (one filter row across all its taps), each
                                          rounded up to the intrinsic's k.  With few input channels (first layers) a
                                          matrix-core k step then reads consecutive pixels of an input row instead of
-                                         the channels of one pixel; compute_at 0 and 1 only */
+                                         the channels of one pixel (the resident-patch modes then need pixels of an output
+                                         row to start at multiples of 4 bytes) */
 #define MS_SPACE_DEFAULT 0xffu       /* every module above except the opt-in one; masks with bit 31 set (the
                                          all-ones default of earlier tuning records) mean the same */
 

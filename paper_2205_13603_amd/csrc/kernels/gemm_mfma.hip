@@ -260,8 +260,8 @@ constexpr int CV_KREAL = CV_TAPROWS ? CV_KH * CV_KR : CV_KD * CV_KH * CV_KW * CV
 constexpr int CV_RUN = CV_KW * CV_CIN; // real elements of a filter row
 constexpr bool K_PADDED = K0 * BK != CV_KREAL;
 static_assert(K0 * BK >= CV_KREAL && K0 * BK - CV_KREAL < MI_K, "the k split covers the reduction, padded by less than one intrinsic");
-static_assert(!CV_TAPROWS || (CV_KR % MI_K == 0 && CV_KR >= CV_RUN && !K_PADDED && CV_DIL == 1 && COMPUTE_AT <= 1 && !CV_TRANSPOSED && CV_D == 1 &&
-                              CV_KD == 1 && DIM_B == 1), "filter-row layout: plain conv2d, im2col staging or the resident patch of one tile");
+static_assert(!CV_TAPROWS || (CV_KR % MI_K == 0 && CV_KR >= CV_RUN && !K_PADDED && CV_DIL == 1 && !CV_TRANSPOSED && CV_D == 1 &&
+                              CV_KD == 1 && DIM_B == 1), "filter-row layout: plain conv2d");
 static_assert(!K_PADDED || COMPUTE_AT == 0, "a padded reduction needs the im2col loader");
 static_assert(!CV_TRANSPOSED || (COMPUTE_AT == 0 && CV_DIL == 1), "the transposed convolution exists in the im2col loader only");
 static_assert((CV_D == 1 && CV_KD == 1) || (COMPUTE_AT == 0 && !CV_TRANSPOSED), "3-D convolution exists in the im2col loader only");
@@ -770,13 +770,13 @@ __device__ __forceinline__ void multiply_all_k(accv_t (&acc)[TM][TN], const frag
 {
     frag_t fa[2][TM];
 #pragma unroll
-    for (int tm = 0; tm < TM; ++tm) fa[0][tm] = *reinterpret_cast<const frag_t *>(cx.patch + (cx.pix[tm] + conv_koff(0, 0)));
+    for (int tm = 0; tm < TM; ++tm) fa[0][tm] = patch_frag(cx.patch + (cx.pix[tm] + conv_koff(0, 0)));
 #pragma unroll
     for (int s = 0; s < NSTEP; ++s) {
         if (s + 1 < NSTEP) {
 #pragma unroll
             for (int tm = 0; tm < TM; ++tm)
-                fa[(s + 1) & 1][tm] = *reinterpret_cast<const frag_t *>(cx.patch + (cx.pix[tm] + conv_koff(0, s + 1)));
+                fa[(s + 1) & 1][tm] = patch_frag(cx.patch + (cx.pix[tm] + conv_koff(0, s + 1)));
         }
 #pragma unroll
         for (int tm = 0; tm < TM; ++tm)

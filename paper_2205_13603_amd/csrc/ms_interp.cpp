@@ -246,9 +246,8 @@ extern "C" int32_t ms_trace_validate(const ms_op *op, const ms_space *space, con
             if (is_conv2d(d.kind) && op->nb > 1 && p.compute_at > 1) return reject("grouped convolution: compute_at must be 0 or 1 (the persistent modes have no group loop)");
             if (p.tap_rows) {
                 // the reduction as KH runs of KW * Cin contiguous elements, each rounded up to the intrinsic's k
-                if (p.compute_at > 1) return reject("filter-row layout: compute_at must be 0 or 1");
                 if (p.cache_read >= 5) return reject("filter-row layout: no direct-to-LDS staging");
-                if (p.compute_at == 1 && (d.stride * d.dims[3] * es) % 4) return reject("filter-row layout with a resident patch: pixels of an output row must start at multiples of 4 bytes");
+                if (p.compute_at >= 1 && (d.stride * d.dims[3] * es) % 4) return reject("filter-row layout with a resident patch: pixels of an output row must start at multiples of 4 bytes");
             }
             if (p.compute_at) {
                 // conv2d with the activations' cache-read under the workgroup tile loop: the input rows of
@@ -313,7 +312,7 @@ extern "C" int32_t ms_trace_validate(const ms_op *op, const ms_space *space, con
             if (p.compute_at == 4) {
                 // weight fragments of the wavefront's columns for every k step, A fragments of two steps
                 int64_t fr = kp * es / 4 > 0 ? kp * es / 4 : 1;
-                int64_t breg = (int64_t)p.tj[1] * p.tj[3] * (op->K / p.tile_unit[2]) * fr;
+                int64_t breg = (int64_t)p.tj[1] * p.tj[3] * ((int64_t)p.tk[0] * p.tk[1] * p.tk[2] * p.tk[3]) * fr; // every MFMA k step of the reduction
                 int64_t areg = 2 * (int64_t)p.ti[1] * p.ti[3] * fr;
                 int64_t pre = 0;
                 if (p.cache_read == 2) {

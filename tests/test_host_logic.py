@@ -539,15 +539,15 @@ def test_filter_row_layout_space_and_rules():
     # 7 runs of 21 elements, each rounded up to the intrinsic's k: 7*32/16, 7*24/8, 7*32/32, 7*32/16
     assert {tz.candidates[c]: ks.extent_by_choice[c] for c in range(tz.n_candidates)} == {161616: 14, 323208: 21, 161632: 7, 323216: 14}
     ca = [sp.slots[i] for i in range(sp.n_slots) if sp.slots[i].name == b"compute_at"][0]
-    assert list(ca.weight)[:5] == [1, 1, 0, 0, 0]
+    assert list(ca.weight)[:5] == [1, 1, 1, 1, 1]
     seen = set()
     for idx in range(40):
         t = B.trace_sample_valid(op, sp, 11, idx)
         p = B.trace_validate(op, sp, t)
-        assert p.tap_rows == 1 and p.compute_at <= 1 and p.tile_unit[2] * p.tk[0] * p.tk[1] * p.tk[2] * p.tk[3] in (224, 168)
+        assert p.tap_rows == 1 and p.tile_unit[2] * p.tk[0] * p.tk[1] * p.tk[2] * p.tk[3] in (224, 168)
         seen.add(p.compute_at)
         assert "op=conv2d_nhwc" in B.trace_to_text(op, sp, t)
-    assert seen == {0, 1}
+    assert {0, 1, 2} <= seen
     # the same trace in the default space is another kernel (or invalid): the layout is part of the key
     assert not (op.space().flags & B.SPACE_TAP_ROWS)
     # pixels that start at odd multiples of 2 bytes: im2col staging only
