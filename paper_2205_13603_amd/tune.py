@@ -50,7 +50,11 @@ def main():
     log = open(os.path.join(args.out, args.workload + ".log.jsonl"), "w")
     t0 = time.time()
 
+    curve = []  # (trial index, best latency so far)
+
     def on_trial(t):
+        if t.status == 0:
+            curve.append((t.index, t.best_us))
         rec = {"trial": t.index, "status": t.status, "us": t.us, "best_us": t.best_us, "key": "%016x" % t.key,
                "decisions": t.trace.decisions(), "t": round(time.time() - t0, 2)}
         log.write(json.dumps(rec) + "\n")
@@ -69,7 +73,9 @@ def main():
     rec = {"workload": args.workload, "trace": B.trace_to_text(op, space, res.best_trace), "us": res.best_us,
            "mode": "device-filling, %d instances" % R, "tflops": flop * R / res.best_us / 1e6, "gbs": byts * R / res.best_us / 1e3,
            "trials": res.n_measured, "trials_to_best": res.best_trial, "invalid": res.n_invalid, "failed": res.n_failed,
-           "duplicate": res.n_duplicate, "search_seconds": round(res.wall_seconds, 1), "seed": args.seed, "flags": args.flags}
+           "duplicate": res.n_duplicate, "search_seconds": round(res.wall_seconds, 1), "seed": args.seed, "flags": args.flags,
+           # first measured trial whose best-so-far latency is within 1 % of the final best
+           "trials_to_within_1pct": next((i for i, b in curve if b <= 1.01 * res.best_us), res.best_trial)}
     with open(os.path.join(args.out, args.workload + ".jsonl"), "a") as f:
         f.write(json.dumps(rec, sort_keys=True) + "\n")
     print(json.dumps({k: v for k, v in rec.items() if k != "trace"}))
