@@ -84,3 +84,33 @@ def test_search_bad_config():
     cfg = B.search_cfg_default()
     with pytest.raises(B.MsError):  # measuring needs buffers
         B.search(op, sp, cfg)
+
+
+@pytest.mark.parametrize("which", ["softmax", "norm", "grouped", "conv1d", "conv3d", "first_layer_rows"])
+def test_search_runs_on_every_operator_family_added_later(which):
+    """The search only sees slots, traces and the validator: it must work unchanged on the row reductions and on the
+    convolution variants (their spaces have zero-weight candidates, padded reductions and an extra layout flag)."""
+    op, flags = {
+        "softmax": (lambda: B.softmax_op(1, 256, 256), B.SPACE_DEFAULT),
+        "norm": (lambda: B.norm_op(1, 256, 256), B.SPACE_DEFAULT),
+        "grouped": (lambda: B.conv2d_op(1, 56, 56, 64, 128, 3, 3, stride=2, pad=1, groups=4), B.SPACE_DEFAULT),
+        "conv1d": (lambda: B.conv1d_op(1, 256, 64, 128, 3, stride=2, pad=1), B.SPACE_DEFAULT),
+        "conv3d": (lambda: B.conv3d_op(1, 8, 32, 32, 3, 64, 3, stride=1, pad=1), B.SPACE_DEFAULT),
+        "first_layer_rows": (lambda: B.conv2d_op(1, 224, 224, 3, 64, 7, 7, stride=2, pad=3), B.SPACE_DEFAULT | B.SPACE_TAP_ROWS),
+    }[which]
+    op = op()
+    sp = op.space(flags)
+    cfg = B.search_cfg_default()
+    cfg.seed, cfg.trials = 3, 48
+
+    def latency(p):  # fewer, larger workgroups are "faster": a known direction for the search to follow
+        return 1.0 + 64.0 / p.threads + 0.001 * p.grid[0]
+
+    seen = []
+    res = B.search(op, sp, cfg, fake_latency=latency, on_trial=lambda t: seen.append(t.us) and 0)
+    assert res.n_measured == 48 and len(seen) >= 48
+    assert res.best_us == min(u for u in seen if u > 0)
+    p = B.trace_validate(op, sp, res.best_trace)          # the best trace is a valid trace of this space
+    assert abs(latency(p) - res.best_us) < 1e-12
+    res2 = B.search(op, sp, cfg, fake_latency=latency)
+    assert bytes(res2.best_trace) == bytes(res.best_trace)  # same seed, same result
