@@ -195,7 +195,10 @@ typedef enum ms_slot_id {
                                  4 = as 2 (cache_read 1 or 2), but the weights end in registers: each wavefront keeps
                                  the fragments of its own output columns for all k steps, the k loop is fully
                                  unrolled whatever the unroll budget (the k split only sets the size of the staging
-                                 steps) and reads only activations from LDS */
+                                 steps) and reads only activations from LDS.
+                                 Candidates that an operator cannot use are listed with weight 0: 1..4 need Cin (per
+                                 group) to be a multiple of 8 unless the space has MS_SPACE_TAP_ROWS, grouped
+                                 convolutions stop at 1, 3-D and transposed convolutions at 0 */
 } ms_slot_id;
 
 /* Tensorize candidates: (m, n, k) of one matrix-core instruction.  The code
