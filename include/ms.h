@@ -197,8 +197,10 @@ typedef enum ms_slot_id {
                                  unrolled whatever the unroll budget (the k split only sets the size of the staging
                                  steps) and reads only activations from LDS.
                                  Candidates that an operator cannot use are listed with weight 0: 1..4 need Cin (per
-                                 group) to be a multiple of 8 unless the space has MS_SPACE_TAP_ROWS, grouped
-                                 convolutions stop at 1, 3-D and transposed convolutions at 0 */
+                                 group) to be a multiple of 8 unless the space has MS_SPACE_TAP_ROWS (for a grouped
+                                 convolution the tile list of 2..4 runs over instance x group, "the weights of the
+                                 current instance" being those of the current group), 3-D and transposed
+                                 convolutions stop at 0 */
 } ms_slot_id;
 
 /* Tensorize candidates: (m, n, k) of one matrix-core instruction.  The code

@@ -265,7 +265,6 @@ static_assert(!CV_TAPROWS || (CV_KR % MI_K == 0 && CV_KR >= CV_RUN && !K_PADDED 
 static_assert(!K_PADDED || COMPUTE_AT == 0, "a padded reduction needs the im2col loader");
 static_assert(!CV_TRANSPOSED || (COMPUTE_AT == 0 && CV_DIL == 1), "the transposed convolution exists in the im2col loader only");
 static_assert((CV_D == 1 && CV_KD == 1) || (COMPUTE_AT == 0 && !CV_TRANSPOSED), "3-D convolution exists in the im2col loader only");
-static_assert(DIM_B == 1 || COMPUTE_AT <= 1, "grouped convolution: im2col staging or the resident patch of one tile; the persistent modes have no group loop");
 // im2col on the fly: row = output pixel, k = (kh, kw, ci)
 template <int V> __device__ __forceinline__ vec_t<in_t, V> load_conv_a(const in_t *__restrict__ X, int row, int k)
 {
@@ -1146,7 +1145,7 @@ ms_kernel(const void *__restrict__ a_, const void *__restrict__ b_, const void *
 #elif CONV_RESIDENT
 // --------------------------------------------------------------------------------------
 // conv2d, COMPUTE_AT 2: persistent workgroups, resident weights, input patch per tile.
-// Tile list of the launch: index f = (inst * J0 + j0) * I0 + i0; workgroup w owns the run
+// Tile list of the launch: index f = ((inst * DIM_B + group) * J0 + j0) * I0 + i0; workgroup w owns the run
 // [w * run, (w + 1) * run): consecutive tiles share their weights and neighbouring patches.
 extern "C" __global__ void __launch_bounds__(NTHREADS)
 ms_kernel(const void *__restrict__ a_, const void *__restrict__ b_, const void *__restrict__ bias_, void *__restrict__ c_, int instances)
@@ -1163,7 +1162,16 @@ ms_kernel(const void *__restrict__ a_, const void *__restrict__ b_, const void *
     char *const patch = lds + W_BYTES;
     char *const cstage = lds + W_BYTES + PATCH_BYTES;
 
-    const long total = (long)I0 * J0 * instances;
+    const long total = (long)I0 * J0 * DIM_B * instances;
+    // z = f / (I0 * J0) = instance * DIM_B + group: where that entry's image, weights, bias slice and output start
+    auto x_of = [&](long z) { return (const in_t *)a_ + (z / DIM_B) * A_INST + (z % DIM_B) * SA_B; };
+    auto w_of = [&](long z) { return (const in_t *)b_ + (z / DIM_B) * B_INST + (z % DIM_B) * SB_B; };
+    auto c_of = [&](long z) { return (out_t *)c_ + (z / DIM_B) * ((long)DIM_B * DIM_M * DIM_N) + (z % DIM_B) * C_BATCH; };
+#if HAS_BIAS
+    auto bias_of = [&](long z) { return (const void *)((const float *)bias_ + (z % DIM_B) * DIM_N); };
+#else
+    auto bias_of = [&](long) { return bias_; };
+#endif
     const long run = (total + gridDim.x - 1) / gridDim.x;
     const long first = (long)blockIdx.x * run;
     const long last = first + run < total ? first + run : total;
@@ -1178,18 +1186,18 @@ ms_kernel(const void *__restrict__ a_, const void *__restrict__ b_, const void *
     patch_regs pr;
     if (helper) {
         patch_map_init(pm, htid);
-        const int inst = (int)(first / (I0 * J0)), i0 = (int)(first % I0);
-        patch_fetch(pr, pm, (const in_t *)a_ + (long)inst * A_INST, i0);
+        patch_fetch(pr, pm, x_of(first / (I0 * J0)), (int)(first % I0));
         patch_commit(pr, pm, patch, htid);
     }
     long have_w = -1;
 #pragma unroll 1
     for (long f = first; f < last; ++f) {
-        const int i0 = (int)(f % I0), j0 = (int)((f / I0) % J0), inst = (int)(f / (I0 * J0));
+        const int i0 = (int)(f % I0), j0 = (int)((f / I0) % J0);
+        const long z = f / (I0 * J0);
         if (f / I0 != have_w) {
             // all wavefronts load the weights; the previous tile's k loop ended with barrier B
             have_w = f / I0;
-            const in_t *Wt = (const in_t *)b_ + (long)inst * B_INST;
+            const in_t *Wt = w_of(z);
             tile_stage st;
 #pragma unroll 1
             for (int k0 = 0; k0 < K0; ++k0) {
@@ -1202,11 +1210,11 @@ ms_kernel(const void *__restrict__ a_, const void *__restrict__ b_, const void *
             // loads before stores: the wait for the patch then does not include the younger stores
             if (f + 1 < last) {
                 const long g = f + 1;
-                patch_fetch(pr, pm, (const in_t *)a_ + (g / (I0 * J0)) * A_INST, (int)(g % I0));
+                patch_fetch(pr, pm, x_of(g / (I0 * J0)), (int)(g % I0));
             }
             if (f > first) {
                 const long g = f - 1;
-                out_t *Cp = (out_t *)c_ + (g / (I0 * J0)) * ((long)DIM_M * DIM_N);
+                out_t *Cp = c_of(g / (I0 * J0));
                 flush_cstage<P_NT>(Cp, (int)(g % I0), (int)((g / I0) % J0), cstage, htid);
             }
             __syncthreads(); // barrier B: the matrix-core wavefronts are done with patch f, the helpers with the staging area
@@ -1230,13 +1238,13 @@ ms_kernel(const void *__restrict__ a_, const void *__restrict__ b_, const void *
 #endif
             }
             __syncthreads(); // barrier B
-            write_tile(acc, nullptr, bias_, inst, i0, j0, cstage, tid, wi, wj, lrow, lgrp); // accumulators -> staging area only
+            write_tile(acc, nullptr, bias_of(z), (int)(z / DIM_B), i0, j0, cstage, tid, wi, wj, lrow, lgrp); // accumulators -> staging area only
         }
     }
     __syncthreads();
     if (helper) {
         const long g = last - 1;
-        out_t *Cp = (out_t *)c_ + (g / (I0 * J0)) * ((long)DIM_M * DIM_N);
+        out_t *Cp = c_of(g / (I0 * J0));
         flush_cstage<P_NT>(Cp, (int)(g % I0), (int)((g / I0) % J0), cstage, htid);
     }
 }
@@ -1245,8 +1253,7 @@ ms_kernel(const void *__restrict__ a_, const void *__restrict__ b_, const void *
     patch_regs pr;
     patch_map_init(pm, tid);
     {
-        const int inst = (int)(first / (I0 * J0)), i0 = (int)(first % I0);
-        patch_fetch(pr, pm, (const in_t *)a_ + (long)inst * A_INST, i0);
+        patch_fetch(pr, pm, x_of(first / (I0 * J0)), (int)(first % I0));
         patch_commit(pr, pm, patch, tid);
     }
     long have_w = -1; // (inst, j0) of the weights in LDS (or registers)
@@ -1255,11 +1262,12 @@ ms_kernel(const void *__restrict__ a_, const void *__restrict__ b_, const void *
 #endif
 #pragma unroll 1
     for (long f = first; f < last; ++f) {
-        const int i0 = (int)(f % I0), j0 = (int)((f / I0) % J0), inst = (int)(f / (I0 * J0));
+        const int i0 = (int)(f % I0), j0 = (int)((f / I0) % J0);
+        const long z = f / (I0 * J0);
         if (f / I0 != have_w) {
             // every wavefront has passed the barrier that ended the previous tile's k loop: the old weights are dead
             have_w = f / I0;
-            const in_t *Wt = (const in_t *)b_ + (long)inst * B_INST;
+            const in_t *Wt = w_of(z);
 #if CONV_BREG
             weights_to_regs(bw, Wt, j0, lds, tid, lgrp, wj, lrow);
 #else
@@ -1275,7 +1283,7 @@ ms_kernel(const void *__restrict__ a_, const void *__restrict__ b_, const void *
 #if CACHE_READ >= 2
         if (f + 1 < last) {
             const long g = f + 1;
-            patch_fetch(pr, pm, (const in_t *)a_ + (g / (I0 * J0)) * A_INST, (int)(g % I0));
+            patch_fetch(pr, pm, x_of(g / (I0 * J0)), (int)(g % I0));
         }
 #endif
         conv_ctx cx;
@@ -1303,12 +1311,11 @@ ms_kernel(const void *__restrict__ a_, const void *__restrict__ b_, const void *
         if (f + 1 < last) {
 #if CACHE_READ < 2
             const long g = f + 1;
-            patch_fetch(pr, pm, (const in_t *)a_ + (g / (I0 * J0)) * A_INST, (int)(g % I0));
+            patch_fetch(pr, pm, x_of(g / (I0 * J0)), (int)(g % I0));
 #endif
             patch_commit(pr, pm, patch, tid);
         }
-        out_t *C = (out_t *)c_ + (long)inst * ((long)DIM_M * DIM_N);
-        write_tile(acc, C, bias_, inst, i0, j0, cstage, tid, wi, wj, lrow, lgrp);
+        write_tile(acc, c_of(z), bias_of(z), (int)(z / DIM_B), i0, j0, cstage, tid, wi, wj, lrow, lgrp);
     }
 }
 #endif // CONV_HELPERS

@@ -614,7 +614,7 @@ extern "C" int32_t ms_space_describe(const ms_op *op, uint32_t flags, ms_space *
                     if (sl.slot_id == MS_SLOT_VECTORIZE && (d.dims[3] / op->nb) % sl.candidates[c]) sl.weight[c] = 0;
                     if (sl.slot_id == MS_SLOT_VECTORIZE_B && op->N % sl.candidates[c]) sl.weight[c] = 0;
                     if (sl.slot_id == MS_SLOT_COMPUTE_AT && sl.candidates[c] > 0 &&
-                        ((d.dims[3] / op->nb) % 8 || (op->nb > 1 && sl.candidates[c] > 1) || is_3d(op)))
+                        ((d.dims[3] / op->nb) % 8 || is_3d(op)))
                         sl.weight[c] = 0;
                     if (sl.slot_id == MS_SLOT_COMPUTE_AT && (flags & MS_SPACE_TAP_ROWS))
                         sl.weight[c] = sl.candidates[c] == 0 || (d.stride * d.dims[3] * op->in_size) % 4 == 0 ? 1 : 0;

@@ -243,7 +243,6 @@ extern "C" int32_t ms_trace_validate(const ms_op *op, const ms_space *space, con
                 if (p.cache_read >= 5) return reject("a padded reduction cannot be staged directly to LDS");
             }
             if (is_3d(op) && p.compute_at) return reject("3-D convolution: compute_at must be 0 (the resident patch is a set of image rows)");
-            if (is_conv2d(d.kind) && op->nb > 1 && p.compute_at > 1) return reject("grouped convolution: compute_at must be 0 or 1 (the persistent modes have no group loop)");
             if (p.tap_rows) {
                 // the reduction as KH runs of KW * Cin contiguous elements, each rounded up to the intrinsic's k
                 if (p.cache_read >= 5) return reject("filter-row layout: no direct-to-LDS staging");

@@ -324,14 +324,47 @@ def test_grouped_conv_exact(groups, Cin, Cout, k, stride, pad):
     OH, OW = ref.shape[1], ref.shape[2]
     op = B.conv2d_op(N, H, W_, Cin, Cout, k, k, stride=stride, pad=pad, out_dtype="f32", groups=groups)
     space = op.space()
-    for n in range(12):
+    seen = set()
+    for n in range(16):
         t = B.trace_sample_valid(op, space, 82, n)
-        assert B.trace_validate(op, space, t).compute_at <= 1
+        seen.add(B.trace_validate(op, space, t).compute_at)
         print("trace", n, t.decisions(), flush=True)
         got = run_variant(op, space, t, [X, Wt, bias], "f32", (N, OH, OW, Cout), instances=2)
         if got is None:
             continue
         assert np.array_equal(got[0], ref) and np.array_equal(got[1], ref), "trace %d" % n
+
+
+def test_grouped_conv_persistent_runs_cross_groups_and_instances():
+    """Grouped convolution under the persistent compute locations: the tile list runs over instance x group, so a
+    workgroup's run of tiles crosses group and instance boundaries (weights and bias slice change, the patch of the
+    next group is prefetched).  200 instances of 5 distinct data sets in rotation, integer-valued inputs, fp32
+    output: exact equality."""
+    N, H, W_, Cin, Cout, G, R = 2, 16, 8, 64, 128, 4, 200
+    g = I.rng(85)
+    sets, refs = [], []
+    for r in range(5):
+        X = I.small_ints(g, (N, H, W_, Cin), -2, 2, "f16")
+        Wt = I.small_ints(g, (3, 3, Cin // G, Cout), -2, 2, "f16")
+        bias = g.integers(-3, 4, size=Cout).astype(np.float32)
+        sets.append([X, Wt, bias])
+        refs.append(O.conv2d_nhwc(X, Wt, bias=bias, relu=True, stride=1, pad=1, groups=G))
+    ins = [sets[r % 5] for r in range(R)]
+    op = B.conv2d_op(N, H, W_, Cin, Cout, 3, 3, stride=1, pad=1, out_dtype="f32", groups=G)
+    space = op.space()
+    for compute_at in (2, 3, 4):
+        traces = _traces_with_resident_patch(op, space, 86, 2, compute_at)
+        assert traces, "no valid trace with compute_at %d" % compute_at
+        for n, t in enumerate(traces):
+            p = B.trace_validate(op, space, t)
+            tiles = p.grid[0] * p.grid[2] * R
+            print("compute_at", compute_at, "trace", n, t.decisions(), "tiles", tiles, flush=True)
+            assert p.grid[2] == G and tiles > 1024, "the launch must have more tiles than workgroups"
+            got = run_variant_distinct(op, space, t, ins, "f32", (N, H, W_, Cout))
+            if got is None:
+                continue
+            for r in range(R):
+                assert np.array_equal(got[r], refs[r % 5]), "instance %d trace %d" % (r, n)
 
 
 def test_grp_config_grouped_conv_56x56x64_to_128():
