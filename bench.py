@@ -50,6 +50,8 @@ def workload_inputs(name, seed):
         "x7_grp_f16_56x56x64_g4": lambda: list(I.grp(seed)),
         "x5_cbr_f16_224x224x3": lambda: list(I.cbr(seed)),
         "x5b_cbr_f16_224x224x4": lambda: list(I.cbr4(seed)),
+        "x11_gemm_bf16_1024": lambda: list(I.c2(seed, dtype="bf16")),
+        "x12_conv_bf16_56x56x64": lambda: list(I.c3(seed, dtype="bf16")),
         "x3_softmax_f32_256x256": lambda: list(I.sfm(seed)),
         "x4_norm_f32_256x256": lambda: list(I.nrm(seed)),
     }[name]()
@@ -59,6 +61,10 @@ def oracle_run(name, ins):
     from oracle import oracle as O
     if name in ("c1_gemm_f32_128", "c2_gemm_f16_1024", "c4c_gemm_i8_512", "x2_gemm_f8_1024"):
         return O.gemm(ins[0], ins[1])
+    if name == "x11_gemm_bf16_1024":
+        return O.gemm(ins[0], ins[1], bf16=True)
+    if name == "x12_conv_bf16_56x56x64":
+        return O.conv2d_nhwc(ins[0], ins[1], bias=ins[2], relu=True, stride=1, pad=1, bf16=True)
     if name == "c4a_bmm_nt_f16":
         return O.bmm(ins[0], ins[1], trans_b=True)
     if name == "c4b_bmm_nn_f16":
@@ -97,6 +103,7 @@ OUT_SHAPE = {
     "x5_cbr_f16_224x224x3": ((1, 112, 112, 64), "f16"), "x5b_cbr_f16_224x224x4": ((1, 112, 112, 64), "f16"),
     "x8_gemm_nt_f16_1024": ((1, 1024, 1024), "f16"), "x9_c1d_f16_256x64": ((1, 128, 128), "f16"),
     "x10_c3d_f16_16x224x224x3": ((1, 8, 112, 112, 64), "f16"),
+    "x11_gemm_bf16_1024": ((1024, 1024), "bf16"), "x12_conv_bf16_56x56x64": ((1, 56, 56, 64), "bf16"),
     "x6_t2d_f16_4x4x512": ((1, 8, 8, 256), "f16"), "x7_grp_f16_56x56x64_g4": ((1, 28, 28, 128), "f16"),
 }
 BOUND = {  # which roofline bounds the workload (AI vs ridge), and the in-dtype
@@ -110,6 +117,7 @@ BOUND = {  # which roofline bounds the workload (AI vs ridge), and the in-dtype
     "x8_gemm_nt_f16_1024": ("mfma", "f16"),  # config 2 with B stored [N][K] (both operands contiguous along k)
     "x9_c1d_f16_256x64": ("hbm", "f16"),  # 55 flop per byte
     "x10_c3d_f16_16x224x224x3": ("mfma", "f16"),  # 743 flop per byte
+    "x11_gemm_bf16_1024": ("mfma", "bf16"), "x12_conv_bf16_56x56x64": ("mfma", "bf16"),  # configs 2 and 3 in bfloat16
     "x6_t2d_f16_4x4x512": ("hbm", "f16"),  # 16 flop per byte: the 4 MiB of weights are read once per instance
 }
 

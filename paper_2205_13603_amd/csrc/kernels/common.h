@@ -35,14 +35,10 @@ template <typename T, int N> struct __attribute__((aligned(sizeof(T) * N))) vec_
 
 __device__ __forceinline__ float bf16_to_float(unsigned short b) { return __uint_as_float((unsigned)b << 16); }
 
-// round to nearest even; NaN stays NaN
-__device__ __forceinline__ unsigned short float_to_bf16(float f)
-{
-    unsigned u = __float_as_uint(f);
-    if ((u & 0x7fffffffu) > 0x7f800000u) return (unsigned short)((u >> 16) | 0x40u);
-    u += 0x7fffu + ((u >> 16) & 1u);
-    return (unsigned short)(u >> 16);
-}
+// round to nearest even; NaN stays NaN.  The conversion is the hardware's (one instruction per pair of values):
+// spelled out in integer arithmetic with its NaN test it costs a branch per element, and an epilogue of 128
+// values per lane then shows in the run time of a tile
+__device__ __forceinline__ unsigned short float_to_bf16(float f) { return __builtin_bit_cast(unsigned short, (__bf16)f); }
 
 __device__ __forceinline__ acc_t to_acc(in_t x)
 {

@@ -27,6 +27,8 @@ WORKLOADS = {
     "x8_gemm_nt_f16_1024": (lambda: B.bmm_op(1, 1024, 1024, 1024, True, "f16"), 64),
     "x9_c1d_f16_256x64": (lambda: B.conv1d_op(1, 256, 64, 128, 3, stride=2, pad=1), 4096),
     "x10_c3d_f16_16x224x224x3": (lambda: B.conv3d_op(1, 16, 224, 224, 3, 64, 7, stride=2, pad=3), 8),
+    "x11_gemm_bf16_1024": (lambda: B.gemm_op(1024, 1024, 1024, "bf16"), 64),
+    "x12_conv_bf16_56x56x64": (lambda: B.conv2d_op(1, 56, 56, 64, 64, 3, 3, stride=1, pad=1, in_dtype="bf16"), 512),
     "x3_softmax_f32_256x256": (lambda: B.softmax_op(1, 256, 256), 2048),
     "x4_norm_f32_256x256": (lambda: B.norm_op(1, 256, 256), 2048),
 }
