@@ -129,7 +129,8 @@ PROFILE_NAME = {"c1_gemm_f32_128": "gemm_mfma_c1_gemm_f32_128", "c2_gemm_f16_102
                 "x3_softmax_f32_256x256": "reduce_x3_softmax_f32_256x256", "x4_norm_f32_256x256": "reduce_x4_norm_f32_256x256",
                 "x5_cbr_f16_224x224x3": "gemm_mfma_x5_cbr_f16_224x224x3", "x6_t2d_f16_4x4x512": "gemm_mfma_x6_t2d_f16_4x4x512",
                 "x7_grp_f16_56x56x64_g4": "gemm_mfma_x7_grp_f16_56x56x64_g4", "x8_gemm_nt_f16_1024": "gemm_mfma_x8_gemm_nt_f16_1024",
-                "x9_c1d_f16_256x64": "gemm_mfma_x9_c1d_f16_256x64"}
+                "x9_c1d_f16_256x64": "gemm_mfma_x9_c1d_f16_256x64", "x11_gemm_bf16_1024": "gemm_mfma_x11_gemm_bf16_1024",
+                "x12_conv_bf16_56x56x64": "gemm_mfma_x12_conv_bf16_56x56x64"}
 
 
 def main():
