@@ -146,6 +146,8 @@ def main():
     ap.add_argument("--trials", type=int, default=16, help="measured candidates of the fresh search")
     ap.add_argument("--seed", type=int, default=0)
     ap.add_argument("--no-records", action="store_true", help="ignore stored tuning records")
+    ap.add_argument("--record-index", type=int, default=-1,
+                    help="consider only this stored record (0 = the best stored latency): fixes the variant, e.g. for counter runs")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--trace-file", default="", help="time exactly this trace (text form) instead of searching")
     args = ap.parse_args()
@@ -221,8 +223,9 @@ def main():
         consider(B.trace_from_text(space, open(args.trace_file).read()), "file")
     else:
         if not args.no_records:
-            for rec, sp, t in tuned.records_with_traces(name, op):
-                consider(t, "record", rec, sp)
+            for idx, (rec, sp, t) in enumerate(tuned.records_with_traces(name, op)):
+                if args.record_index < 0 or idx == args.record_index:
+                    consider(t, "record", rec, sp)
         if args.trials > 0:
             cfg = B.search_cfg_default()
             cfg.seed, cfg.trials = args.seed, args.trials
