@@ -193,6 +193,12 @@ def lib():
     if _lib is None:
         if not os.path.exists(LIB_PATH):
             raise OSError("%s is missing: run `python -m paper_2205_13603_amd.build_lib` (there is no fallback path)" % LIB_PATH)
+        # PyTorch brings its own copy of the HIP runtime.  Loaded after libms.so's, it found no device on the MI355X
+        # boxes ("no ROCm-capable device is detected" from the first HIP call of libms.so); loaded first, both work.
+        try:
+            import torch  # noqa: F401
+        except ImportError:
+            pass
         L = C.CDLL(LIB_PATH)
         for name, (res, args) in SYMBOLS.items():
             fn = getattr(L, name)
