@@ -367,6 +367,40 @@ def test_grouped_conv_persistent_runs_cross_groups_and_instances():
                 assert np.array_equal(got[r], refs[r % 5]), "instance %d trace %d" % (r, n)
 
 
+@pytest.mark.parametrize("stride,pad,k,L_", [(1, 1, 3, 32), (2, 2, 5, 64)])
+def test_grouped_conv1d_exact(stride, pad, k, L_):
+    """Grouped 1-D convolution: the group count of the conv1d descriptor on the conv2d kernels, every compute location
+    the space offers.  Reference: the oracle's grouped conv2d on an image of height 1 with a 1 x K filter, whose output
+    row that reads the image row (row pad / stride) is the 1-D result.  Integer-valued inputs, batch 2, 2 instances:
+    bit-equal fp32 outputs."""
+    N, Cin, Cout, G = 2, 64, 64, 4
+    g = I.rng(93)
+    X = I.small_ints(g, (N, L_, Cin), -2, 2, "f16")
+    Wt = I.small_ints(g, (k, Cin // G, Cout), -2, 2, "f16")
+    bias = g.integers(-3, 4, size=Cout).astype(np.float32)
+    assert pad % stride == 0
+    ref = O.conv2d_nhwc(X[:, None], Wt[None], bias=bias, relu=True, stride=stride, pad=pad, groups=G)[:, pad // stride]
+    OL = ref.shape[1]
+    op = B.conv1d_op(N, L_, Cin, Cout, k, stride=stride, pad=pad, out_dtype="f32", groups=G)
+    assert op.loops()[0] == ("g", G, False)
+    space = op.space()
+    want = {0: 2, 1: 2, 2: 1, 3: 1, 4: 1}
+    idx = 0
+    while any(want.values()) and idx < 800:
+        t = B.trace_sample_valid(op, space, 94, idx)
+        idx += 1
+        ca = B.trace_validate(op, space, t).compute_at
+        if want[ca] == 0:
+            continue
+        want[ca] -= 1
+        print("trace", idx, "compute_at", ca, t.decisions(), flush=True)
+        got = run_variant(op, space, t, [X, Wt, bias], "f32", (N, OL, Cout), instances=2)
+        if got is None:
+            continue
+        assert np.array_equal(got[0], ref) and np.array_equal(got[1], ref), "trace %d" % idx
+    assert want[0] == 0 and want[1] == 0, want
+
+
 def test_grp_config_grouped_conv_56x56x64_to_128():
     """The paper's GRP shape: 56 x 56 x 64 -> 28 x 28 x 128, 3 x 3, stride 2, padding 1, 4 groups; fp16."""
     g = I.rng(83)
