@@ -201,6 +201,15 @@ typedef enum ms_slot_id {
                                  convolution the tile list of 2..4 runs over instance x group, "the weights of the
                                  current instance" being those of the current group), 3-D and transposed
                                  convolutions stop at 0 */
+    ,
+    MS_SLOT_RFACTOR = 13      /* categorical (matrix-core kernels; Table 2, rfactor: "factorize a reduction across a
+                                 loop"): the k0 loop is cut into S = 1, 2, 4 or 8 consecutive runs and the runs of one
+                                 output tile go to S workgroups.  Each writes the fp32 (int32) partial sums of its run
+                                 to the workspace; a second kernel of the same launch adds the S partial results of
+                                 every output element in run order, applies bias and ReLU and rounds once.  The result
+                                 does not depend on how the workgroups are scheduled.  S must divide k0; persistent
+                                 workgroups (reorder 3, compute_at 2..4) and cache_write 1 own the whole reduction
+                                 and the epilogue and need S = 1 */
 } ms_slot_id;
 
 /* Tensorize candidates: (m, n, k) of one matrix-core instruction.  The code
@@ -261,6 +270,9 @@ typedef struct ms_slot {
                                          matrix-core k step then reads consecutive pixels of an input row instead of
                                          the channels of one pixel (the resident-patch modes then need pixels of an output
                                          row to start at multiples of 4 bytes) */
+#define MS_SPACE_RFACTOR 0x400u       /* opt-in, matrix-core kernels: sample the rfactor decision (splits the reduction
+                                         across workgroups through a caller-provided workspace): for launches that
+                                         would otherwise leave most compute units idle; off = 1 */
 #define MS_SPACE_DEFAULT 0xffu       /* every module above except the opt-in one; masks with bit 31 set (the
                                          all-ones default of earlier tuning records) mean the same */
 
@@ -342,9 +354,10 @@ typedef struct ms_variant_params {
     int32_t reorder;
     int32_t vec_b;          /* elements per global load of B */
     int32_t cache_write;    /* 0, 1 as in MS_SLOT_CACHE_WRITE */
-    int32_t compute_at;     /* 0, 1 as in MS_SLOT_COMPUTE_AT */
+    int32_t compute_at;     /* 0 .. 4 as in MS_SLOT_COMPUTE_AT */
     int32_t tap_rows;       /* 1: the reduction of the MS_SPACE_TAP_ROWS layout (tile_unit[2] * the k split = KH * run) */
-    int32_t reserved[4];
+    int32_t rfactor;        /* workgroups that share the reduction of one output tile (1 = no workspace) */
+    int32_t reserved[3];
     uint64_t key;           /* hash of everything that selects the kernel */
 } ms_variant_params;
 
@@ -362,7 +375,7 @@ int32_t ms_trace_validate(const ms_op *op, const ms_space *space, const ms_trace
  * MI355X; ms_set_limits replaces them (tests use it to force rejections). */
 typedef struct ms_limits {
     int32_t max_threads;      /* 1024 */
-    int32_t max_lds_bytes;    /* 65536 (static LDS per workgroup) */
+    int32_t max_lds_bytes;    /* 163840: the 160 KiB of a compute unit, which one workgroup may take whole */
     int32_t max_acc_per_thread; /* 256 */
     int32_t wave_size;        /* 64 */
     int32_t max_waves;        /* 16 */
@@ -379,19 +392,34 @@ typedef struct ms_variant ms_variant;
  * Errors: INVALID_TRACE, COMPILE (compiler log in ms_last_error). */
 int32_t ms_variant_build(const ms_op *op, const ms_space *space, const ms_trace *trace, ms_variant **out);
 void ms_variant_destroy(ms_variant *v);
+/* params and workspace_bytes may be NULL.  *workspace_bytes = bytes of workspace ONE instance needs (0 unless
+ * rfactor > 1: rfactor x batch x M x N accumulator values); a launch over R instances needs R times as much. */
 int32_t ms_variant_info(const ms_variant *v, ms_variant_params *params, size_t *workspace_bytes);
+/* What materialising a variant compiles (Section 4, building a candidate): the kernel template's file name, then the
+ * -D options that specialise it, one per line.  Two parameter sets that give the same text are the same kernel and
+ * have the same params.key.  Writes at most cap bytes including the NUL; *needed (may be NULL) = size needed. */
+int32_t ms_variant_kernel_text(const ms_op *op, const ms_variant_params *params, char *buf, size_t cap, size_t *needed);
 /* Compile the kernels of n traces ahead of use on `threads` host threads
  * (invalid traces are skipped).  *n_built = kernels now in the cache. */
 int32_t ms_prebuild(const ms_op *op, const ms_space *space, const ms_trace *traces, int32_t n,
                     int32_t threads, int32_t *n_built);
 /* Directory of the on-disk kernel cache (NULL or "" = in-memory only). */
 int32_t ms_set_cache_dir(const char *path);
+/* Where this process got its kernels from so far (Section 4: building a candidate is part of the cost of measuring
+ * it): kernels compiled now, code objects read from the on-disk cache, requests served from memory; and the
+ * version of the run-time compiler the process is bound to.  The version is part of every cache key, so a code
+ * object is only reused by the compiler that made it: a stored latency and a later launch then refer to the same
+ * machine code.  Any pointer may be NULL. */
+int32_t ms_jit_stats(int64_t *compiled, int64_t *from_disk, int64_t *from_memory, int32_t *compiler_major, int32_t *compiler_minor);
 
 /* Enqueue one execution over `instances` instances on `stream`.  inputs /
  * outputs: host arrays of device pointers (see ms_op_desc for the order; one
- * output).  workspace: device pointer of at least workspace_bytes, or NULL
- * if that is 0.  Asynchronous; returns launch errors only.  BAD_ARG if
- * instances < 1 or the grid would exceed 2^31-1 workgroups. */
+ * output).  workspace: device pointer, 16-byte aligned, of at least instances x
+ * workspace_bytes (ms_variant_info), owned by the caller and not shared with a
+ * launch that may run at the same time; NULL if that is 0.  Its contents need no
+ * initialisation and are undefined afterwards.  Asynchronous (a variant with
+ * rfactor > 1 enqueues two kernels); returns launch errors only.  BAD_ARG if
+ * instances < 1, the grid would exceed 2^31-1 workgroups, or a needed workspace is NULL. */
 int32_t ms_variant_launch(ms_variant *v, const void *const *inputs, void *const *outputs,
                           void *workspace, int32_t instances, void *stream);
 
@@ -403,6 +431,15 @@ int32_t ms_variant_launch(ms_variant *v, const void *const *inputs, void *const 
  * once.  This executes index arithmetic only, never the operator.
  */
 int32_t ms_variant_coverage(const ms_op *op, const ms_variant_params *params, int32_t *counts, int64_t out_elems);
+/*
+ * The same for the reduction: walks the rfactor / k0 / k1 / k2 / k3 / intrinsic-k loops (depthwise: the filter taps)
+ * that produce ONE output element and counts how often each position of the reduction is visited.  counts: host
+ * pointer to k_elems int32; *k_elems_needed (may be NULL) receives the length of the interpreted reduction (the
+ * operator's K, rounded up where a convolution pads it to the intrinsic's k).  A correct split visits every position
+ * exactly once, whatever the decisions.  Index arithmetic only.
+ */
+int32_t ms_variant_reduction_coverage(const ms_op *op, const ms_variant_params *params, int32_t *counts, int64_t k_elems,
+                                      int64_t *k_elems_needed);
 
 /* ------------------------------------------------------------------ f(e) */
 

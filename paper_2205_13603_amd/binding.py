@@ -17,11 +17,12 @@ MS_OK, MS_ERR_BAD_ARG, MS_ERR_INVALID_TRACE, MS_ERR_UNSUPPORTED, MS_ERR_COMPILE,
 F32, F16, BF16, I8, I32 = range(5)
 SLOT_PERFECT_TILE, SLOT_CATEGORICAL = 0, 1
 (SLOT_TENSORIZE, SLOT_TILE_I, SLOT_TILE_J, SLOT_TILE_C, SLOT_TILE_K, SLOT_UNROLL, SLOT_CACHE_READ, SLOT_VECTORIZE,
- SLOT_STORAGE_ALIGN, SLOT_REORDER, SLOT_VECTORIZE_B, SLOT_CACHE_WRITE, SLOT_COMPUTE_AT) = range(13)
+ SLOT_STORAGE_ALIGN, SLOT_REORDER, SLOT_VECTORIZE_B, SLOT_CACHE_WRITE, SLOT_COMPUTE_AT, SLOT_RFACTOR) = range(14)
 SPACE_TENSORIZE, SPACE_CACHE_READ, SPACE_VECTORIZE, SPACE_UNROLL, SPACE_STORAGE_ALIGN, SPACE_REORDER, SPACE_CACHE_WRITE = 1, 2, 4, 8, 16, 32, 64
 SPACE_COMPUTE_AT = 128
 SPACE_TENSORIZE_F32 = 0x100  # opt-in: fp32 operators on the fp32 matrix-core intrinsics
 SPACE_TAP_ROWS = 0x200  # opt-in: conv2d reduction laid out as filter rows (first layers with few input channels)
+SPACE_RFACTOR = 0x400  # opt-in: sample the split of the reduction across workgroups (needs a workspace)
 SPACE_DEFAULT = 0xFF
 FAM_GEMM_ALU, FAM_GEMM_MFMA, FAM_DWCONV, FAM_REDUCE = range(4)
 MAX_SLOTS, MAX_FACTORS, MAX_CANDS, MAX_LOOPS = 16, 4, 8, 8
@@ -81,7 +82,7 @@ class ms_variant_params(C.Structure):
                 ("block_n", C.c_int32), ("block_k", C.c_int32), ("grid", C.c_int32 * 3), ("threads", C.c_int32),
                 ("waves", C.c_int32), ("acc_per_thread", C.c_int32), ("lds_bytes", C.c_int32),
                 ("cache_read", C.c_int32), ("vec", C.c_int32), ("unroll", C.c_int32), ("unroll_k1", C.c_int32),
-                ("unroll_k2", C.c_int32), ("lds_pad", C.c_int32), ("reorder", C.c_int32), ("vec_b", C.c_int32), ("cache_write", C.c_int32), ("compute_at", C.c_int32), ("tap_rows", C.c_int32), ("reserved", C.c_int32 * 4),
+                ("unroll_k2", C.c_int32), ("lds_pad", C.c_int32), ("reorder", C.c_int32), ("vec_b", C.c_int32), ("cache_write", C.c_int32), ("compute_at", C.c_int32), ("tap_rows", C.c_int32), ("rfactor", C.c_int32), ("reserved", C.c_int32 * 3),
                 ("key", C.c_uint64)]
 
     def as_dict(self):
@@ -161,10 +162,13 @@ SYMBOLS = {
     "ms_variant_build": (C.c_int32, [C.c_void_p, _P(ms_space), _P(ms_trace), _P(C.c_void_p)]),
     "ms_variant_destroy": (None, [C.c_void_p]),
     "ms_variant_info": (C.c_int32, [C.c_void_p, _P(ms_variant_params), _P(C.c_size_t)]),
+    "ms_variant_kernel_text": (C.c_int32, [C.c_void_p, _P(ms_variant_params), C.c_char_p, C.c_size_t, _P(C.c_size_t)]),
     "ms_prebuild": (C.c_int32, [C.c_void_p, _P(ms_space), _P(ms_trace), C.c_int32, C.c_int32, _P(C.c_int32)]),
     "ms_set_cache_dir": (C.c_int32, [C.c_char_p]),
+    "ms_jit_stats": (C.c_int32, [_P(C.c_int64), _P(C.c_int64), _P(C.c_int64), _P(C.c_int32), _P(C.c_int32)]),
     "ms_variant_launch": (C.c_int32, [C.c_void_p, _P(C.c_void_p), _P(C.c_void_p), C.c_void_p, C.c_int32, C.c_void_p]),
     "ms_variant_coverage": (C.c_int32, [C.c_void_p, _P(ms_variant_params), C.c_void_p, C.c_int64]),
+    "ms_variant_reduction_coverage": (C.c_int32, [C.c_void_p, _P(ms_variant_params), C.c_void_p, C.c_int64, _P(C.c_int64)]),
     "ms_measure": (C.c_int32, [C.c_void_p, _P(ms_bufset), C.c_int32, _P(ms_measure_cfg), C.c_void_p, _P(ms_measure_result)]),
     "ms_search_cfg_default": (None, [_P(ms_search_cfg)]),
     "ms_search": (C.c_int32, [C.c_void_p, _P(ms_space), _P(ms_search_cfg), _P(ms_bufset), C.c_int32, C.c_void_p,
@@ -396,6 +400,23 @@ def variant_coverage(op, params, out_elems):
     return counts
 
 
+def variant_reduction_coverage(op, params):
+    import numpy as np
+    need = C.c_int64()
+    _check(lib().ms_variant_reduction_coverage(op.handle, C.byref(params), None, 0, C.byref(need)))
+    counts = np.zeros(need.value, np.int32)
+    _check(lib().ms_variant_reduction_coverage(op.handle, C.byref(params), counts.ctypes.data_as(C.c_void_p), need.value, None))
+    return counts
+
+
+def variant_kernel_text(op, params):
+    need = C.c_size_t()
+    _check(lib().ms_variant_kernel_text(op.handle, C.byref(params), None, 0, C.byref(need)))
+    buf = C.create_string_buffer(need.value)
+    _check(lib().ms_variant_kernel_text(op.handle, C.byref(params), buf, need.value, None))
+    return buf.value.decode()
+
+
 def prebuild(op, space, traces, threads=8):
     arr = (ms_trace * len(traces))(*traces)
     n = C.c_int32()
@@ -405,6 +426,24 @@ def prebuild(op, space, traces, threads=8):
 
 def set_cache_dir(path):
     _check(lib().ms_set_cache_dir(path.encode() if path else None))
+
+
+def _bufsets(bufsets):
+    """[(inputs, output[, workspace])] of device pointers -> array of ms_bufset (at least one element)."""
+    arr = (ms_bufset * max(1, len(bufsets)))()
+    for i, bs in enumerate(bufsets):
+        for k, p in enumerate(bs[0]):
+            arr[i].inputs[k] = p
+        arr[i].output = bs[1]
+        arr[i].workspace = bs[2] if len(bs) > 2 else None
+    return arr
+
+
+def jit_stats():
+    """{compiled, from_disk, from_memory, compiler: (major, minor)} of this process."""
+    a, b, c, mj, mn = C.c_int64(), C.c_int64(), C.c_int64(), C.c_int32(), C.c_int32()
+    _check(lib().ms_jit_stats(C.byref(a), C.byref(b), C.byref(c), C.byref(mj), C.byref(mn)))
+    return {"compiled": a.value, "from_disk": b.value, "from_memory": c.value, "compiler": (mj.value, mn.value)}
 
 
 class Variant:
@@ -424,19 +463,22 @@ class Variant:
         _check(lib().ms_variant_info(self.handle, C.byref(p), C.byref(ws)))
         return p
 
+    def workspace_bytes(self):
+        """Bytes of workspace one instance needs (0 unless the reduction is split across workgroups);
+        a launch over R instances takes R times as much."""
+        ws = C.c_size_t()
+        _check(lib().ms_variant_info(self.handle, None, C.byref(ws)))
+        return ws.value
+
     def launch(self, inputs, output, instances=1, stream=None, workspace=None):
-        """inputs / output: device pointers (ints)."""
+        """inputs / output / workspace: device pointers (ints)."""
         ins = (C.c_void_p * 4)(*[C.c_void_p(p) for p in inputs])
         outs = (C.c_void_p * 1)(C.c_void_p(output))
         _check(lib().ms_variant_launch(self.handle, ins, outs, workspace, instances, stream))
 
     def measure(self, bufsets, warmup=2, repeats=5, launches_per_repeat=20, instances=1, stream=None):
-        """bufsets: list of (inputs, output) device pointer tuples."""
-        arr = (ms_bufset * len(bufsets))()
-        for i, (ins, out) in enumerate(bufsets):
-            for k, p in enumerate(ins):
-                arr[i].inputs[k] = p
-            arr[i].output = out
+        """bufsets: list of (inputs, output) or (inputs, output, workspace) device pointer tuples."""
+        arr = _bufsets(bufsets)
         cfg = ms_measure_cfg(warmup, repeats, launches_per_repeat, instances)
         res = ms_measure_result()
         _check(lib().ms_measure(self.handle, arr, len(bufsets), C.byref(cfg), stream, C.byref(res)))
@@ -525,11 +567,7 @@ def search_cfg_default():
 
 
 def search(op, space, cfg, bufsets=(), stream=None, fake_latency=None, on_trial=None):
-    arr = (ms_bufset * max(1, len(bufsets)))()
-    for i, (ins, out) in enumerate(bufsets):
-        for k, p in enumerate(ins):
-            arr[i].inputs[k] = p
-        arr[i].output = out
+    arr = _bufsets(bufsets)
     res = ms_search_result()
     lat = LATENCY_FN(lambda p, u: float(fake_latency(p.contents))) if fake_latency else C.cast(None, LATENCY_FN)
     cb = TRIAL_CB(lambda t, u: int(on_trial(t.contents) or 0)) if on_trial else C.cast(None, TRIAL_CB)

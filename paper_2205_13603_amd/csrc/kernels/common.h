@@ -65,9 +65,14 @@ __device__ __forceinline__ out_t from_acc(acc_t x)
 // (x fastest, then y, z) to XCD f mod 8, so id (f mod 8) * (total / 8) + f / 8 makes the workgroups
 // one XCD receives consecutive in (z, i0, j0) order; tiles that share operand panels, and whole
 // instances, then sit behind one L2.
-__device__ __forceinline__ void block_to_tile(int &z, int &i0, int &j0)
+// RFACTOR > 1 (matrix-core kernels): RFACTOR consecutive workgroups share one output tile, workgroup ks
+// of them reduces over the ks-th run of k0 steps.
+#ifndef RFACTOR
+#define RFACTOR 1
+#endif
+__device__ __forceinline__ void block_to_tile(int &z, int &i0, int &j0, int &ks)
 {
-    constexpr int G = I0 * J0;
+    constexpr int G = I0 * J0 * RFACTOR;
     int wg = blockIdx.x;
     z = blockIdx.z * gridDim.y + blockIdx.y;
 #if REORDER >= 2
@@ -80,6 +85,8 @@ __device__ __forceinline__ void block_to_tile(int &z, int &i0, int &j0)
         z = (int)(g / G);
     }
 #endif
+    ks = wg % RFACTOR;
+    wg /= RFACTOR;
 #if REORDER == 1
     j0 = wg / I0;
     i0 = wg % I0;

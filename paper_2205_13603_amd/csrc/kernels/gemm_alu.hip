@@ -72,7 +72,8 @@ ms_kernel(const void *__restrict__ a_, const void *__restrict__ b_, const void *
 {
     (void)unused_;
     int z, i0, j0;
-    block_to_tile(z, i0, j0);
+    int ks; // always 0: the vector kernels keep the reduction inside one workgroup
+    block_to_tile(z, i0, j0, ks);
     const int inst = z / DIM_B, bb = z % DIM_B;
     if (inst >= instances) return;
     const in_t *__restrict__ A = (const in_t *)a_ + (long)inst * A_INST + (long)bb * SA_B;

@@ -18,6 +18,10 @@
 //   storage-align: LDS_PAD 1, 2: each LDS plane padded by 16 bytes; 2: slots of a plane XOR-swizzled
 //   vectorize: global loads of VEC (A) and VEC_B (B) elements
 //   cache-write (CACHE_WRITE 1): the output tile is assembled in LDS and stored as whole rows
+//   rfactor (RFACTOR S > 1): the k0 loop is cut into S runs of K0 / S steps, S consecutive workgroups share an
+//           output tile and each writes the accumulators of its run to the workspace [S][instance x batch][M][N];
+//           ms_rfactor_reduce (second kernel of the launch) adds the S partial results in run order and applies
+//           the epilogue.  Nothing is added atomically: the result does not depend on scheduling
 //   unroll  k1 by UNROLL_K1, k2 by UNROLL_K2; k3 and the wave's tile loops fully.  When the
 //           budget unrolls k1 and k2 completely the k step becomes a software pipeline: each of
 //           its K1*K2 slots issues the next slot's LDS reads and a share of the next tile's global
@@ -1320,13 +1324,88 @@ ms_kernel(const void *__restrict__ a_, const void *__restrict__ b_, const void *
 }
 #endif // CONV_HELPERS
 #else // REORDER != 3
-extern "C" __global__ void __launch_bounds__(NTHREADS)
-ms_kernel(const void *__restrict__ a_, const void *__restrict__ b_, const void *__restrict__ bias_, void *__restrict__ c_, int instances)
+constexpr int K0L = K0 / RFACTOR; // k0 steps of one workgroup
+static_assert(K0 % RFACTOR == 0, "rfactor divides the k0 loop");
+static_assert(RFACTOR == 1 || (!CACHE_WRITE && !CONV_RESIDENT), "rfactor: partial sums leave straight from the accumulators");
+
+#if RFACTOR > 1
+// partial sums of run ks: accumulator values, no epilogue, to ws[ks][z][row][col]
+__device__ __forceinline__ void write_partial(accv_t (&acc)[TM][TN], acc_t *__restrict__ W, int i0, int j0, int wi, int wj, int lrow, int lgrp)
 {
-    int z, i0, j0;
-    block_to_tile(z, i0, j0);
+#pragma unroll
+    for (int r1 = 0; r1 < I1; ++r1)
+#pragma unroll
+        for (int r3 = 0; r3 < I3; ++r3)
+#pragma unroll
+            for (int c1 = 0; c1 < J1; ++c1)
+#pragma unroll
+                for (int c3 = 0; c3 < J3; ++c3) {
+                    const int trow = (r1 * I2 + wi) * I3 + r3, tcol = (c1 * J2 + wj) * J3 + c3;
+                    const long row = (long)i0 * BM + trow * MI_M + lrow;
+#pragma unroll
+                    for (int g = 0; g < ACC_N / 4; ++g) {
+                        const long col = (long)j0 * BN + tcol * MI_N + (MI_M == 16 ? 4 * lgrp : 8 * g + 4 * lgrp);
+                        vec_t<acc_t, 4> o;
+#pragma unroll
+                        for (int e = 0; e < 4; ++e) o.v[e] = acc[r1 * I3 + r3][c1 * J3 + c3][4 * g + e];
+                        *reinterpret_cast<vec_t<acc_t, 4> *>(W + row * DIM_N + col) = o;
+                    }
+                }
+}
+
+// Second kernel of an rfactor launch: one thread per 4 consecutive output columns adds the RFACTOR partial
+// results in run order (a fixed order: the result is reproducible), then bias, ReLU and the single rounding.
+extern "C" __global__ void __launch_bounds__(256)
+ms_rfactor_reduce(const void *__restrict__ ws_, const void *__restrict__ bias_, void *__restrict__ c_, int instances)
+{
+    const long nz = (long)instances * DIM_B;
+    const long quads = nz * DIM_M * (DIM_N / 4);
+    const long q = (long)blockIdx.x * 256 + threadIdx.x;
+    if (q >= quads) return;
+    const int col = (int)(q % (DIM_N / 4)) * 4;
+    const long zr = q / (DIM_N / 4);
+    const int row = (int)(zr % DIM_M);
+    const long z = zr / DIM_M;
+    const int inst = (int)(z / DIM_B), bb = (int)(z % DIM_B);
+    const acc_t *W = (const acc_t *)ws_ + (z * DIM_M + row) * DIM_N + col;
+    vec_t<acc_t, 4> sum = *reinterpret_cast<const vec_t<acc_t, 4> *>(W);
+#pragma unroll
+    for (int ks = 1; ks < RFACTOR; ++ks) {
+        const vec_t<acc_t, 4> part = *reinterpret_cast<const vec_t<acc_t, 4> *>(W + (long)ks * nz * DIM_M * DIM_N);
+#pragma unroll
+        for (int e = 0; e < 4; ++e) sum.v[e] += part.v[e];
+    }
+#if HAS_BIAS
+    const vec_t<float, 4> bias = *reinterpret_cast<const vec_t<float, 4> *>((const float *)bias_ + (long)inst * LDC + (long)bb * DIM_N + col);
+#endif
+    vec_t<out_t, 4> o;
+#pragma unroll
+    for (int e = 0; e < 4; ++e) {
+        acc_t x = sum.v[e];
+#if HAS_BIAS
+        x += bias.v[e];
+#endif
+#if RELU
+        x = x > 0 ? x : 0;
+#endif
+        o.v[e] = from_acc(x);
+    }
+    out_t *C = (out_t *)c_ + (long)inst * ((long)DIM_B * DIM_M * DIM_N) + (long)bb * C_BATCH;
+    *reinterpret_cast<vec_t<out_t, 4> *>(C + (long)row * LDC + col) = o;
+    (void)bias_;
+}
+#endif
+
+extern "C" __global__ void __launch_bounds__(NTHREADS)
+ms_kernel(const void *__restrict__ a_, const void *__restrict__ b_, const void *__restrict__ bias_, void *__restrict__ c_, int instances,
+          void *__restrict__ ws_)
+{
+    int z, i0, j0, ks;
+    block_to_tile(z, i0, j0, ks);
     const int inst = z / DIM_B, bb = z % DIM_B;
     if (inst >= instances) return;
+    const int KB = ks * K0L, KE = KB + K0L; // this workgroup's run of k0 steps
+    (void)ws_;
     const in_t *__restrict__ A = (const in_t *)a_ + (long)inst * A_INST + (long)bb * SA_B;
     const in_t *__restrict__ B = (const in_t *)b_ + (long)inst * B_INST + (long)bb * SB_B;
     out_t *__restrict__ C = (out_t *)c_ + (long)inst * ((long)DIM_B * DIM_M * DIM_N) + (long)bb * C_BATCH;
@@ -1378,16 +1457,16 @@ ms_kernel(const void *__restrict__ a_, const void *__restrict__ b_, const void *
         const int wave_u = __builtin_amdgcn_readfirstlane(wave); // scalar register: load addresses and LDS targets become wave-uniform
         // prologue: DL_STAGES - 1 tiles in flight
 #pragma unroll
-        for (int t = 0; t < DL_STAGES - 1; ++t) dl_issue(A, B, lds + t * DL_STAGE_BYTES, i0, j0, t < K0 ? t : K0 - 1, wave_u, lane);
+        for (int t = 0; t < DL_STAGES - 1; ++t) dl_issue(A, B, lds + t * DL_STAGE_BYTES, i0, j0, KB + t < KE ? KB + t : KE - 1, wave_u, lane);
         int rd = 0, wr = DL_STAGES - 1; // stage multiplied in this step / stage refilled in this step
 #pragma unroll 1
-        for (int k0 = 0; k0 < K0; ++k0) {
+        for (int k0 = KB; k0 < KE; ++k0) {
             // this wavefront's loads of tile k0 have landed once at most the loads of the DL_STAGES - 2
             // younger tiles are outstanding; the barrier then covers every wavefront's share, and also
             // tells that all of them are done reading the stage that is refilled next
             DL_WAIT_VM((DL_STAGES - 2) * DL_LPW_MIN);
             __builtin_amdgcn_s_barrier();
-            dl_issue(A, B, lds + wr * DL_STAGE_BYTES, i0, j0, k0 + DL_STAGES - 1 < K0 ? k0 + DL_STAGES - 1 : K0 - 1, wave_u, lane);
+            dl_issue(A, B, lds + wr * DL_STAGE_BYTES, i0, j0, k0 + DL_STAGES - 1 < KE ? k0 + DL_STAGES - 1 : KE - 1, wave_u, lane);
             const char *stage = lds + rd * DL_STAGE_BYTES;
 #if UNROLL_K1 == K1 && UNROLL_K2 == K2 && K1 * K2 > 1
             {
@@ -1425,26 +1504,26 @@ ms_kernel(const void *__restrict__ a_, const void *__restrict__ b_, const void *
     // last are clamped (a harmless re-load) instead of branching.
     {
         tile_stage st0, st1;
-        stage_load(st0, A, B, i0, j0, 0, tid);
-        stage_load(st1, A, B, i0, j0, K0 > 1 ? 1 : 0, tid);
+        stage_load(st0, A, B, i0, j0, KB, tid);
+        stage_load(st1, A, B, i0, j0, K0L > 1 ? KB + 1 : KB, tid);
         stage_store(st0, lds, tid);
         __syncthreads();
 #pragma unroll 1
-        for (int k0 = 0; k0 < K0; k0 += 2) {
+        for (int k0 = KB; k0 < KE; k0 += 2) {
 #if UNROLL_K1 == K1 && UNROLL_K2 == K2
-            pipelined_step(acc, lds, lds + STAGE_BYTES, st1, st0, A, B, i0, j0, k0 + 2 < K0 ? k0 + 2 : K0 - 1, tid, lgrp, wi, wj, lrow, cx, k0);
+            pipelined_step(acc, lds, lds + STAGE_BYTES, st1, st0, A, B, i0, j0, k0 + 2 < KE ? k0 + 2 : KE - 1, tid, lgrp, wi, wj, lrow, cx, k0);
             __syncthreads();
-            if (k0 + 1 < K0) {
-                pipelined_step(acc, lds + STAGE_BYTES, lds, st0, st1, A, B, i0, j0, k0 + 3 < K0 ? k0 + 3 : K0 - 1, tid, lgrp, wi, wj, lrow, cx, k0 + 1);
+            if (k0 + 1 < KE) {
+                pipelined_step(acc, lds + STAGE_BYTES, lds, st0, st1, A, B, i0, j0, k0 + 3 < KE ? k0 + 3 : KE - 1, tid, lgrp, wi, wj, lrow, cx, k0 + 1);
                 __syncthreads();
             }
 #else
-            stage_load(st0, A, B, i0, j0, k0 + 2 < K0 ? k0 + 2 : K0 - 1, tid);
+            stage_load(st0, A, B, i0, j0, k0 + 2 < KE ? k0 + 2 : KE - 1, tid);
             multiply_tile(acc, lds, lgrp, wi, wj, lrow, cx, k0);
             stage_store(st1, lds + STAGE_BYTES, tid);
             __syncthreads();
-            if (k0 + 1 < K0) {
-                stage_load(st1, A, B, i0, j0, k0 + 3 < K0 ? k0 + 3 : K0 - 1, tid);
+            if (k0 + 1 < KE) {
+                stage_load(st1, A, B, i0, j0, k0 + 3 < KE ? k0 + 3 : KE - 1, tid);
                 multiply_tile(acc, lds + STAGE_BYTES, lgrp, wi, wj, lrow, cx, k0 + 1);
                 stage_store(st0, lds, tid);
                 __syncthreads();
@@ -1462,19 +1541,19 @@ ms_kernel(const void *__restrict__ a_, const void *__restrict__ b_, const void *
     {
         tile_stage st;
         const bool late = wave >= NWAVES / 2;
-        stage_load(st, A, B, i0, j0, 0, tid);
+        stage_load(st, A, B, i0, j0, KB, tid);
         stage_store(st, lds, tid);
-        stage_load(st, A, B, i0, j0, K0 > 1 ? 1 : 0, tid);
+        stage_load(st, A, B, i0, j0, K0L > 1 ? KB + 1 : KB, tid);
         __syncthreads();
         if (late) __builtin_amdgcn_s_barrier();
         int stage = 0;
 #pragma unroll 1
-        for (int k0 = 0; k0 < K0; ++k0) {
+        for (int k0 = KB; k0 < KE; ++k0) {
             frag_t fa[K3][TM], fb[K3][TN];
             const char *base = lds + stage * STAGE_BYTES;
             read_frags(fa, fb, base + lgrp * PLANE_A, base + A_STAGE_BYTES + lgrp * PLANE_B, 0, wi, wj, lrow, cx, k0);
             stage_store(st, lds + (stage ^ 1) * STAGE_BYTES, tid);
-            stage_load(st, A, B, i0, j0, k0 + 2 < K0 ? k0 + 2 : K0 - 1, tid);
+            stage_load(st, A, B, i0, j0, k0 + 2 < KE ? k0 + 2 : KE - 1, tid);
             __syncthreads();
             __builtin_amdgcn_s_setprio(1);
             mfma_slot(acc, fa, fb);
@@ -1488,13 +1567,13 @@ ms_kernel(const void *__restrict__ a_, const void *__restrict__ b_, const void *
     tile_stage st;
     int stage = 0;
 #if CACHE_READ == 2
-    stage_load(st, A, B, i0, j0, 0, tid);
+    stage_load(st, A, B, i0, j0, KB, tid);
     stage_store(st, lds, tid);
     __syncthreads();
 #endif
 
 #pragma unroll 1
-    for (int k0 = 0; k0 < K0; ++k0) {
+    for (int k0 = KB; k0 < KE; ++k0) {
 #if CACHE_READ == 1
         stage_load(st, A, B, i0, j0, k0, tid);
         stage_store(st, lds, tid);
@@ -1514,7 +1593,7 @@ ms_kernel(const void *__restrict__ a_, const void *__restrict__ b_, const void *
                 if (s + 1 < NS) read_frags(fa[(s + 1) & 1], fb[(s + 1) & 1], la, lb, s + 1, wi, wj, lrow, cx, k0);
 #if CACHE_READ == 2
                 // the last step fetches its own tile again instead of branching: the loop body stays one block
-                stage_load(st, A, B, i0, j0, k0 + 1 < K0 ? k0 + 1 : k0, tid, s * tile_stage::UNITS / NS, (s + 1) * tile_stage::UNITS / NS);
+                stage_load(st, A, B, i0, j0, k0 + 1 < KE ? k0 + 1 : k0, tid, s * tile_stage::UNITS / NS, (s + 1) * tile_stage::UNITS / NS);
 #endif
                 mfma_slot(acc, fa[s & 1], fb[s & 1]);
                 __builtin_amdgcn_sched_barrier(0);
@@ -1522,7 +1601,7 @@ ms_kernel(const void *__restrict__ a_, const void *__restrict__ b_, const void *
         }
 #else
 #if CACHE_READ == 2
-        if (k0 + 1 < K0) stage_load(st, A, B, i0, j0, k0 + 1, tid);
+        if (k0 + 1 < KE) stage_load(st, A, B, i0, j0, k0 + 1, tid);
 #endif
 #pragma unroll UNROLL_K1
         for (int k1 = 0; k1 < K1; ++k1) {
@@ -1542,7 +1621,7 @@ ms_kernel(const void *__restrict__ a_, const void *__restrict__ b_, const void *
         // would let the compiler sink the prefetch loads down here, behind the MFMAs
         stage_store(st, lds + (stage ^ 1) * STAGE_BYTES, tid);
 #else
-        if (k0 + 1 < K0) stage_store(st, lds + (stage ^ 1) * STAGE_BYTES, tid);
+        if (k0 + 1 < KE) stage_store(st, lds + (stage ^ 1) * STAGE_BYTES, tid);
 #endif
         __syncthreads();
         stage ^= 1;
@@ -1551,6 +1630,12 @@ ms_kernel(const void *__restrict__ a_, const void *__restrict__ b_, const void *
 
 #endif // CACHE_READ != 3
 
+#if RFACTOR > 1
+    write_partial(acc, (acc_t *)ws_ + (((long)ks * instances * DIM_B + z) * DIM_M) * DIM_N, i0, j0, wi, wj, lrow, lgrp);
+    (void)C;
+    (void)tid;
+#else
     write_tile(acc, C, bias_, inst, i0, j0, lds, tid, wi, wj, lrow, lgrp);
+#endif
 }
 #endif // REORDER != 3

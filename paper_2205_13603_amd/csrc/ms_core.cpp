@@ -16,11 +16,20 @@ namespace ms {
 
 static thread_local char g_err[4096] = "";
 
+// The message is formatted into a buffer of its own first: callers may pass ms_last_error() (= g_err) as an
+// argument, and vsnprintf must not read from the buffer it writes.
+static void format_error(const char *fmt, va_list ap)
+{
+    char tmp[sizeof g_err];
+    vsnprintf(tmp, sizeof tmp, fmt, ap);
+    memcpy(g_err, tmp, sizeof g_err);
+}
+
 void set_error(const char *fmt, ...)
 {
     va_list ap;
     va_start(ap, fmt);
-    vsnprintf(g_err, sizeof g_err, fmt, ap);
+    format_error(fmt, ap);
     va_end(ap);
 }
 
@@ -28,7 +37,7 @@ int32_t fail(int32_t code, const char *fmt, ...)
 {
     va_list ap;
     va_start(ap, fmt);
-    vsnprintf(g_err, sizeof g_err, fmt, ap);
+    format_error(fmt, ap);
     va_end(ap);
     return code;
 }
@@ -510,10 +519,11 @@ extern "C" int32_t ms_space_describe(const ms_op *op, uint32_t flags, ms_space *
     if (d.in_dtype != MS_F32) flags &= ~MS_SPACE_TENSORIZE_F32;
     if (flags & MS_SPACE_TENSORIZE_F32) flags |= MS_SPACE_TENSORIZE;
     if (d.kind == MS_OP_DWCONV2D_NHWC) flags &= ~(MS_SPACE_TENSORIZE | MS_SPACE_VECTORIZE | MS_SPACE_STORAGE_ALIGN | MS_SPACE_CACHE_WRITE);
+    if (!(flags & MS_SPACE_TENSORIZE)) flags &= ~MS_SPACE_RFACTOR; // the matrix-core kernels implement it
     if (d.kind != MS_OP_CONV2D_NHWC) flags &= ~MS_SPACE_COMPUTE_AT; // the resident-patch modes assume the direct index map
     // the filter-row layout of the reduction: plain conv2d only (dense filter, one group, two dimensions)
     if (!(d.kind == MS_OP_CONV2D_NHWC && op->nb == 1 && !is_3d(op) && d.dilation == 1)) flags &= ~MS_SPACE_TAP_ROWS;
-    flags &= 0x3ffu;
+    flags &= 0x7ffu;
     if (d.kind == MS_OP_SOFTMAX || d.kind == MS_OP_NORM) {
         // rows i: [workgroups, serial, thread groups, rows of one group at a time]; reduction k: [serial, loads in
         // flight, lanes of a group (cross-thread reduction), vector]
@@ -604,6 +614,7 @@ extern "C" int32_t ms_space_describe(const ms_op *op, uint32_t flags, ms_space *
         }
         if (flags & MS_SPACE_CACHE_WRITE) add_cat(out, MS_SLOT_CACHE_WRITE, "cache_write", {0, 1});
         if (flags & MS_SPACE_COMPUTE_AT) add_cat(out, MS_SLOT_COMPUTE_AT, "compute_at", {0, 1, 2, 3, 4});
+        if (flags & MS_SPACE_RFACTOR) add_cat(out, MS_SLOT_RFACTOR, "rfactor", {1, 2, 4, 8});
         if (is_conv2d(d.kind)) {
             // candidates that no trace of this operator can use keep their position (stored decisions are indices)
             // but get weight 0: vector widths that do not divide the channel counts, and the resident-patch modes
@@ -943,6 +954,7 @@ extern "C" int32_t ms_trace_to_text(const ms_op *op, const ms_space *space, cons
             appendf(s, "storage-align(scope=lds, pad_bytes=%d, swizzle=%d)\n", p.lds_pad ? 16 : 0, p.lds_pad == 2);
         }
         if (p.cache_write) appendf(s, "cache-write(buffer=C, scope=lds)\n");
+        if (p.rfactor > 1) appendf(s, "rfactor(loop=k0, factor=%d)  # partial sums in the workspace, second kernel adds them in order\n", p.rfactor);
         if (p.vec > 1) appendf(s, "vectorize(global loads of A, width=%d)\n", p.vec);
         if (p.vec_b > 1) appendf(s, "vectorize(global loads of B, width=%d)\n", p.vec_b);
         appendf(s, "unroll(k1, factor=%d)\nunroll(k2, factor=%d)\n", p.unroll_k1, p.unroll_k2);

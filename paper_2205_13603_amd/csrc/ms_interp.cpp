@@ -81,13 +81,13 @@ uint64_t hash_params(const ms_op *op, const ms_variant_params *p)
     add((uint64_t)p->vec);
     add((uint64_t)p->vec_b);
     add((uint64_t)p->cache_write);
-    add((uint64_t)p->unroll_k1);
-    add((uint64_t)p->unroll_k2);
-    add((uint64_t)p->unroll);
+    add((uint64_t)p->unroll_k1); // the unroll budget itself is not part of the key: the two factors it
+    add((uint64_t)p->unroll_k2); // resolves to select the code, and budgets that resolve alike give one kernel
     add((uint64_t)p->lds_pad);
     add((uint64_t)p->reorder);
     add((uint64_t)p->compute_at);
     if (p->tap_rows) add(0x7A9ull);
+    if (p->rfactor > 1) add(0x4F0000ull + (uint64_t)p->rfactor);
     return h;
 }
 
@@ -161,6 +161,7 @@ extern "C" int32_t ms_trace_validate(const ms_op *op, const ms_space *space, con
     p.tap_rows = (space->flags & MS_SPACE_TAP_ROWS) && d.kind == MS_OP_CONV2D_NHWC && op->nb == 1 && !is_3d(op) && d.dilation == 1 ? 1 : 0;
     p.reorder = (int32_t)cat_value(space, trace, MS_SLOT_REORDER, 0);
     p.compute_at = (int32_t)cat_value(space, trace, MS_SLOT_COMPUTE_AT, 0);
+    p.rfactor = (int32_t)cat_value(space, trace, MS_SLOT_RFACTOR, 1);
 
     if (space->family == MS_FAM_GEMM_ALU || space->family == MS_FAM_GEMM_MFMA) {
         if (!get_tile(space, trace, MS_SLOT_TILE_I, p.ti) || !get_tile(space, trace, MS_SLOT_TILE_J, p.tj) ||
@@ -282,6 +283,14 @@ extern "C" int32_t ms_trace_validate(const ms_op *op, const ms_space *space, con
                 if (d.dims[0] * d.dims[1] * d.dims[2] * d.dims[3] > 0x7fffffff / es) return reject("resident input patch: one instance of X exceeds 32-bit byte offsets");
             }
             if (p.reorder == 3 && p.cache_read < 5) return reject("persistent workgroups (reorder 3) are built on direct-to-LDS staging (cache_read 5, 6, 7)");
+            if (p.rfactor > 1) {
+                // the reduction of one output tile shared by rfactor workgroups: whole runs of k0 steps each
+                if (p.tk[0] % p.rfactor) return reject("rfactor %d does not divide the %d steps of the k0 loop", p.rfactor, p.tk[0]);
+                if (p.reorder == 3 || p.compute_at >= 2) return reject("persistent workgroups own the whole reduction of their tiles: rfactor must be 1");
+                if (p.cache_write) return reject("rfactor writes partial sums straight from the accumulators: cache_write must be 0");
+                if (g * p.rfactor > 0x7fffffff / std::max<int64_t>(1, op->nb)) return reject("grid of %" PRId64 " workgroups overflows", g * p.rfactor);
+                p.grid[0] = (int32_t)(g * p.rfactor);
+            }
             if (p.cache_write) {
                 // the output tile reuses the operand buffers: rows of bn outputs padded by 16 bytes
                 int64_t ctile = bm * (bn * op->out_size + 16);
@@ -508,6 +517,7 @@ int32_t make_kernel_spec(const ms_op *op, const ms_variant_params *p, KernelSpec
     D.push_back(def("REORDER", p->reorder));
     D.push_back(def("COMPUTE_AT", p->compute_at));
     D.push_back(def("HELPER_WAVES", p->compute_at == 3 ? 4 : 0));
+    D.push_back(def("RFACTOR", p->rfactor > 1 ? p->rfactor : 1));
     if (p->family == MS_FAM_GEMM_ALU || p->family == MS_FAM_GEMM_MFMA) {
         D.push_back(def("DIM_B", op->nb));
         D.push_back(def("DIM_M", op->M));
@@ -596,6 +606,23 @@ int32_t make_kernel_spec(const ms_op *op, const ms_variant_params *p, KernelSpec
 
 } // namespace ms
 
+extern "C" int32_t ms_variant_kernel_text(const ms_op *op, const ms_variant_params *p, char *buf, size_t cap, size_t *needed)
+{
+    if (!op || !p) return fail(MS_ERR_BAD_ARG, "ms_variant_kernel_text: NULL argument");
+    KernelSpec k;
+    int32_t rc = make_kernel_spec(op, p, &k);
+    if (rc != MS_OK) return rc;
+    std::string s = k.template_name + "\n";
+    for (auto &d : k.defines) s += d + "\n";
+    if (needed) *needed = s.size() + 1;
+    if (buf && cap) {
+        size_t n = std::min(cap - 1, s.size());
+        memcpy(buf, s.data(), n);
+        buf[n] = 0;
+    }
+    return MS_OK;
+}
+
 // Index of the four-level split: ((x0*f1 + x1)*f2 + x2)*f3 + x3.
 static inline int64_t split_index(const int32_t *f, int64_t x0, int64_t x1, int64_t x2, int64_t x3)
 {
@@ -612,7 +639,7 @@ extern "C" int32_t ms_variant_coverage(const ms_op *op, const ms_variant_params 
     if (p->family == MS_FAM_GEMM_ALU || p->family == MS_FAM_GEMM_MFMA) {
         int um = p->tile_unit[0], un = p->tile_unit[1];
         for (int64_t b = 0; b < op->nb; ++b)
-            for (int64_t wg = 0; wg < p->grid[0]; ++wg) {
+            for (int64_t wg = 0; wg < p->grid[0] / std::max(1, p->rfactor); ++wg) { // output tiles (rfactor workgroups share one)
                 int64_t i0, j0;
                 if (p->reorder == 1) {
                     j0 = wg / p->ti[0];
@@ -683,5 +710,43 @@ extern "C" int32_t ms_variant_coverage(const ms_op *op, const ms_variant_params 
                 }
             }
     }
+    return MS_OK;
+}
+
+extern "C" int32_t ms_variant_reduction_coverage(const ms_op *op, const ms_variant_params *p, int32_t *counts, int64_t k_elems, int64_t *needed)
+{
+    if (!op || !p) return fail(MS_ERR_BAD_ARG, "ms_variant_reduction_coverage: NULL argument");
+    const bool dw = p->family == MS_FAM_DWCONV;
+    const int unit = dw ? 1 : std::max(1, p->tile_unit[2]);
+    const int64_t len = dw ? (int64_t)op->d.dims[4] * op->d.dims[5] : (int64_t)p->tk[0] * p->tk[1] * p->tk[2] * p->tk[3] * unit;
+    if (needed) *needed = len;
+    if (!counts) return needed ? MS_OK : fail(MS_ERR_BAD_ARG, "ms_variant_reduction_coverage: NULL argument");
+    if (k_elems != len) return fail(MS_ERR_BAD_ARG, "ms_variant_reduction_coverage: k_elems %" PRId64 " != %" PRId64, k_elems, len);
+    // the interpreted reduction covers the operator's K, padded by less than one intrinsic where a convolution rounds it up
+    if (!dw && !p->tap_rows && (len < op->K || len - op->K >= unit))
+        return fail(MS_ERR_INVALID_TRACE, "reduction coverage: the split covers %" PRId64 " positions, the operator reduces over %" PRId64, len, op->K);
+    memset(counts, 0, sizeof(int32_t) * (size_t)len);
+    if (dw) {
+        for (int64_t kh = 0; kh < p->tk[1]; ++kh)
+            for (int64_t kw = 0; kw < p->tk[2]; ++kw) {
+                int64_t k = kh * op->d.dims[5] + kw;
+                if (k >= len) return fail(MS_ERR_INVALID_TRACE, "reduction coverage: index out of range");
+                ++counts[k];
+            }
+        return MS_OK;
+    }
+    const int rf = std::max(1, p->rfactor);
+    if (p->tk[0] % rf) return fail(MS_ERR_INVALID_TRACE, "reduction coverage: rfactor does not divide k0");
+    const int64_t run = p->tk[0] / rf; // k0 steps of one workgroup
+    for (int64_t s = 0; s < rf; ++s)
+        for (int64_t q0 = s * run; q0 < (s + 1) * run; ++q0)
+            for (int64_t q1 = 0; q1 < p->tk[1]; ++q1)
+                for (int64_t q2 = 0; q2 < p->tk[2]; ++q2)
+                    for (int64_t q3 = 0; q3 < p->tk[3]; ++q3)
+                        for (int u = 0; u < unit; ++u) {
+                            int64_t k = split_index(p->tk, q0, q1, q2, q3) * unit + u;
+                            if (k < 0 || k >= len) return fail(MS_ERR_INVALID_TRACE, "reduction coverage: index out of range");
+                            ++counts[k];
+                        }
     return MS_OK;
 }

@@ -22,6 +22,17 @@ static std::map<uint64_t, std::unique_ptr<std::vector<char>>> g_codes;
 static std::map<std::string, std::string> g_sources;
 static std::string g_cache_dir;
 static bool g_cache_dir_set = false;
+static int64_t g_n_compiled = 0, g_n_disk = 0, g_n_mem = 0;
+
+// Version of the run-time compiler this process is bound to.  A process that loaded PyTorch first runs PyTorch's
+// copy of the compiler library, one that did not runs the system's; the two generate different code for the same
+// source, so the version is part of every cache key: a code object is only ever reused by the compiler that made it.
+static uint64_t compiler_id()
+{
+    int major = 0, minor = 0;
+    if (hiprtcVersion(&major, &minor) != HIPRTC_SUCCESS) return 0;
+    return ((uint64_t)(uint32_t)major << 32) | (uint32_t)minor;
+}
 
 std::string kernels_dir()
 {
@@ -120,11 +131,12 @@ int32_t jit_get_code(const KernelSpec &spec, uint64_t key, std::vector<char> **c
         }
         for (auto &x : extra) opts_joined += x + " ";
     }
-    uint64_t k = mix64(key ^ hash_bytes(src) ^ mix64(hash_bytes(opts_joined)));
+    uint64_t k = mix64(key ^ hash_bytes(src) ^ mix64(hash_bytes(opts_joined)) ^ mix64(0xC0DE000000000000ull ^ compiler_id()));
     {
         std::lock_guard<std::mutex> lk(g_mu);
         auto it = g_codes.find(k);
         if (it != g_codes.end()) {
+            ++g_n_mem;
             *code_out = it->second.get();
             return MS_OK;
         }
@@ -135,7 +147,11 @@ int32_t jit_get_code(const KernelSpec &spec, uint64_t key, std::vector<char> **c
     std::unique_ptr<std::vector<char>> code(new std::vector<char>());
     if (!dir.empty()) {
         std::string blob;
-        if (read_file(dir + fname, &blob) && blob.size() > 64) code->assign(blob.begin(), blob.end());
+        if (read_file(dir + fname, &blob) && blob.size() > 64) {
+            code->assign(blob.begin(), blob.end());
+            std::lock_guard<std::mutex> lk(g_mu);
+            ++g_n_disk;
+        }
     }
     if (code->empty()) {
         hiprtcProgram prog;
@@ -172,6 +188,10 @@ int32_t jit_get_code(const KernelSpec &spec, uint64_t key, std::vector<char> **c
         code->resize(cs);
         hiprtcGetCode(prog, code->data());
         hiprtcDestroyProgram(&prog);
+        {
+            std::lock_guard<std::mutex> lk(g_mu);
+            ++g_n_compiled;
+        }
         if (!dir.empty()) {
             mkdir(dir.c_str(), 0777);
             char tmpn[96];
@@ -194,6 +214,18 @@ int32_t jit_get_code(const KernelSpec &spec, uint64_t key, std::vector<char> **c
 }
 
 } // namespace ms
+
+extern "C" int32_t ms_jit_stats(int64_t *compiled, int64_t *from_disk, int64_t *from_memory, int32_t *compiler_major, int32_t *compiler_minor)
+{
+    std::lock_guard<std::mutex> lk(ms::g_mu);
+    if (compiled) *compiled = ms::g_n_compiled;
+    if (from_disk) *from_disk = ms::g_n_disk;
+    if (from_memory) *from_memory = ms::g_n_mem;
+    const uint64_t id = ms::compiler_id();
+    if (compiler_major) *compiler_major = (int32_t)(id >> 32);
+    if (compiler_minor) *compiler_minor = (int32_t)(id & 0xffffffffu);
+    return MS_OK;
+}
 
 extern "C" int32_t ms_set_cache_dir(const char *path)
 {

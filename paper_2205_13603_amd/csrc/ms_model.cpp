@@ -198,6 +198,7 @@ extern "C" int32_t ms_variant_features(const ms_op *op, const ms_variant_params 
     f.push_back((double)p->reorder);
     f.push_back((double)p->cache_write);
     f.push_back((double)p->compute_at);
+    f.push_back(lg((double)std::max(1, p->rfactor)));
     // derived: register tile of one thread / wavefront, operand traffic per multiply-accumulate of a workgroup tile
     const double rm = (double)std::max(1, p->ti[1]) * std::max(1, p->ti[3]) * std::max(1, p->tile_unit[0]);
     const double rn = (double)std::max(1, p->tj[1]) * std::max(1, p->tj[3]) * std::max(1, p->tile_unit[1]);

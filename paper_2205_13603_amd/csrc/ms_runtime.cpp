@@ -20,6 +20,7 @@ struct ms_variant {
     std::vector<char> *code; // owned by the cache
     hipModule_t mod;
     hipFunction_t fn;
+    hipFunction_t fn_reduce; // second kernel of an rfactor launch, else null
     int device;              // device the module is loaded on, -1 = not loaded
     int compute_units;       // of that device
 };
@@ -43,6 +44,7 @@ extern "C" int32_t ms_variant_build(const ms_op *op, const ms_space *space, cons
     v->p = p;
     v->mod = nullptr;
     v->fn = nullptr;
+    v->fn_reduce = nullptr;
     v->device = -1;
     rc = make_kernel_spec(op, &p, &v->spec);
     if (rc == MS_OK) rc = jit_get_code(v->spec, p.key, &v->code);
@@ -61,11 +63,18 @@ extern "C" void ms_variant_destroy(ms_variant *v)
     delete v;
 }
 
+// rfactor partial results of one instance: [rfactor][batch][M][N] accumulator values (fp32 or int32)
+static size_t workspace_per_instance(const ms_variant *v)
+{
+    if (v->p.rfactor <= 1) return 0;
+    return (size_t)v->p.rfactor * (size_t)v->op.nb * (size_t)v->op.M * (size_t)v->op.N * 4u;
+}
+
 extern "C" int32_t ms_variant_info(const ms_variant *v, ms_variant_params *params, size_t *workspace_bytes)
 {
     if (!v) return fail(MS_ERR_BAD_ARG, "ms_variant_info: NULL variant");
     if (params) *params = v->p;
-    if (workspace_bytes) *workspace_bytes = 0;
+    if (workspace_bytes) *workspace_bytes = workspace_per_instance(v);
     return MS_OK;
 }
 
@@ -112,6 +121,8 @@ static int32_t ensure_loaded(ms_variant *v)
         return fail(MS_ERR_HIP, "variant needs %d bytes of LDS, the device offers %zu per workgroup", v->p.lds_bytes, (size_t)prop.sharedMemPerBlock);
     HIP_TRY(hipModuleLoadData(&v->mod, v->code->data()));
     HIP_TRY(hipModuleGetFunction(&v->fn, v->mod, v->spec.entry.c_str()));
+    v->fn_reduce = nullptr;
+    if (v->p.rfactor > 1) HIP_TRY(hipModuleGetFunction(&v->fn_reduce, v->mod, "ms_rfactor_reduce"));
     v->device = dev;
     v->compute_units = prop.multiProcessorCount;
     return MS_OK;
@@ -120,9 +131,12 @@ static int32_t ensure_loaded(ms_variant *v)
 extern "C" int32_t ms_variant_launch(ms_variant *v, const void *const *inputs, void *const *outputs, void *workspace,
                                      int32_t instances, void *stream)
 {
-    (void)workspace;
     if (!v || !inputs || !outputs) return fail(MS_ERR_BAD_ARG, "ms_variant_launch: NULL argument");
     if (instances < 1) return fail(MS_ERR_BAD_ARG, "ms_variant_launch: instances = %d", instances);
+    if (v->p.rfactor > 1 && !workspace)
+        return fail(MS_ERR_BAD_ARG, "ms_variant_launch: the variant splits its reduction over %d workgroups and needs a workspace of %zu bytes per instance",
+                    v->p.rfactor, workspace_per_instance(v));
+    if (v->p.rfactor > 1 && ((uintptr_t)workspace & 15u)) return fail(MS_ERR_BAD_ARG, "ms_variant_launch: the workspace must be 16-byte aligned");
     const bool one_input = v->p.family == MS_FAM_REDUCE;
     if (!inputs[0] || (!one_input && !inputs[1]) || !outputs[0]) return fail(MS_ERR_BAD_ARG, "ms_variant_launch: NULL tensor pointer");
     uint64_t gz = (uint64_t)v->spec.grid[2] * (uint64_t)instances;
@@ -138,7 +152,8 @@ extern "C" int32_t ms_variant_launch(ms_variant *v, const void *const *inputs, v
     }
     void *o = outputs[0];
     int32_t inst = instances;
-    void *args[] = {&in0, &in1, &in2, &o, &inst};
+    void *ws = workspace;
+    void *args[] = {&in0, &in1, &in2, &o, &inst, &ws}; // kernels without a workspace declare the first five only
     // grid z carries batch x instances; fold overflow beyond 65535 into y
     unsigned gy = 1, gzz = (unsigned)gz;
     if (gz > 65535) {
@@ -165,6 +180,15 @@ extern "C" int32_t ms_variant_launch(ms_variant *v, const void *const *inputs, v
         gzz = 1;
     }
     HIP_TRY(hipModuleLaunchKernel(v->fn, gx, gy, gzz, v->spec.block[0], 1, 1, v->spec.lds_dynamic, (hipStream_t)stream, args, nullptr));
+    if (v->p.rfactor > 1) {
+        // stream order makes the partial sums visible to the kernel that adds them: 4 outputs per thread
+        const uint64_t quads = (uint64_t)instances * (uint64_t)v->op.nb * (uint64_t)v->op.M * (uint64_t)(v->op.N / 4);
+        const uint64_t blocks = (quads + 255) / 256;
+        if (blocks > 0x7fffffffull) return fail(MS_ERR_BAD_ARG, "ms_variant_launch: %d instances overflow the grid of the reduction", instances);
+        const void *wsc = workspace;
+        void *rargs[] = {&wsc, &in2, &o, &inst};
+        HIP_TRY(hipModuleLaunchKernel(v->fn_reduce, (unsigned)blocks, 1, 1, 256, 1, 1, 0, (hipStream_t)stream, rargs, nullptr));
+    }
     return MS_OK;
 }
 

@@ -29,8 +29,7 @@ def main():
 
     import torch
     from . import binding as B, devmem, tuned
-    sys.path.insert(0, os.path.dirname(os.path.dirname(os.path.abspath(__file__))))
-    from bench import workload_inputs, OUT_SHAPE
+    from .workloads import workload_inputs, OUT_SHAPE
 
     devmem.require_gpu()
     mk, default_r = tuned.WORKLOADS[args.workload]

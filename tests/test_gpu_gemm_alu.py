@@ -9,14 +9,8 @@ pytestmark = pytest.mark.gpu
 
 
 def run_gemm(op, space, trace, A, Bm, out_dtype, shape, instances=1):
-    from paper_2205_13603_amd import devmem
-    v = B.Variant(op, space, trace)
-    if not devmem.gpu_available():
-        return None  # precompile run: the kernel is now in the cache
-    dA, dB = devmem.to_device(A, instances), devmem.to_device(Bm, instances)
-    dC = devmem.empty_output(shape, out_dtype, instances, poison=True)
-    v.launch([dA.data_ptr(), dB.data_ptr()], dC.data_ptr(), instances=instances, stream=devmem.current_stream())
-    return devmem.to_host(dC, out_dtype)
+    from gpu_util import run_variant
+    return run_variant(op, space, trace, [A, Bm], out_dtype, shape, instances)
 
 
 def test_c1_sixteen_traces():
@@ -112,7 +106,7 @@ def test_event_timing_recovers_a_known_duration(target_us):
     that ms_measure uses: every repeat must report the target plus at most the launch overhead."""
     from paper_2205_13603_amd import devmem
     if not devmem.gpu_available():
-        return
+        pytest.skip("no GPU in this process")
     import torch
     scratch = torch.zeros(1024, dtype=torch.uint8, device="cuda")
     res = B.calibrate_timer(target_us, scratch.data_ptr(), warmup=2, repeats=7, launches_per_repeat=1, stream=devmem.current_stream())

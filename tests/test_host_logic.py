@@ -561,3 +561,85 @@ def test_filter_row_layout_space_and_rules():
     assert not (B.conv2d_op(1, 16, 16, 4, 32, 3, 3, pad=2, dilation=2).space(0x2ff).flags & B.SPACE_TAP_ROWS)
     assert not (B.conv2d_op(1, 16, 16, 8, 32, 3, 3, pad=1, groups=2).space(0x2ff).flags & B.SPACE_TAP_ROWS)
     assert not (B.gemm_op(128, 128, 128, "f16").space(0x2ff).flags & B.SPACE_TAP_ROWS)
+
+
+# ---------------------------------------------------------------- kernel identity
+
+@pytest.mark.parametrize("mk", CONFIG_OPS + [lambda: B.softmax_op(1, 64, 256)])
+def test_equal_kernel_text_means_equal_key(mk):
+    """The key names the kernel: traces whose decisions resolve to the same template options (e.g. unroll budgets
+    that are clamped alike) share one key, so a search never compiles or measures one kernel twice; different
+    options give different keys."""
+    op = mk()
+    sp = op.space()
+    by_text, by_key = {}, {}
+    for idx in range(300):
+        p = B.trace_validate(op, sp, B.trace_sample_valid(op, sp, 33, idx))
+        text = B.variant_kernel_text(op, p)
+        assert by_text.setdefault(text, p.key) == p.key, "one kernel, two keys:\n" + text
+        assert by_key.setdefault(p.key, text) == text, "one key, two kernels"
+    assert len(by_text) > 20
+
+
+def test_unroll_budgets_that_resolve_alike_share_a_key():
+    op = B.dwconv2d_op(1, 28, 28, 12)
+    sp = op.space()
+    t = B.trace_sample_valid(op, sp, 1, 0)
+    pos = [i for i in range(sp.n_slots) if sp.slots[i].slot_id == B.SLOT_UNROLL][0]
+    keys = []
+    for choice in range(3):  # budgets 0, 16, 64
+        t.d[pos].v[0] = choice
+        keys.append(B.trace_validate(op, sp, t).key)
+    assert keys[1] == keys[2] and keys[0] != keys[1]  # 16 and 64 both unroll the 9 taps fully
+
+
+# ---------------------------------------------------------------- rfactor (reduction split across workgroups)
+
+def test_rfactor_is_an_opt_in_module_with_rules():
+    op = B.gemm_op(256, 256, 512, "f16")
+    assert B.SLOT_RFACTOR not in [op.space().slots[i].slot_id for i in range(op.space().n_slots)]
+    sp = op.space(B.SPACE_DEFAULT | B.SPACE_RFACTOR)
+    s = sp.slots[sp.n_slots - 1]
+    assert s.slot_id == B.SLOT_RFACTOR and [s.candidates[c] for c in range(s.n_candidates)] == [1, 2, 4, 8]
+    # the vector-ALU family has no such decision
+    sp_alu = B.gemm_op(128, 128, 128, "f32").space(B.SPACE_DEFAULT | B.SPACE_RFACTOR)
+    assert B.SLOT_RFACTOR not in [sp_alu.slots[i].slot_id for i in range(sp_alu.n_slots)]
+
+    def mk(k, cache=2, pad=0, reorder=0, cw=0, rf=1):
+        return B.make_trace(sp, [[161632], [4, 2, 2, 1], [4, 2, 2, 1], k, [0], [cache], [8], [8], [pad], [reorder], [cw], [rf]])
+
+    base = B.trace_validate(op, sp, mk([8, 1, 1, 2]))
+    assert base.rfactor == 1 and base.grid[0] == 16
+    p = B.trace_validate(op, sp, mk([8, 1, 1, 2], rf=4))
+    assert p.rfactor == 4 and p.grid[0] == 64 and p.key != base.key
+    assert "-DRFACTOR=4" in B.variant_kernel_text(op, p)
+    assert "rfactor(loop=k0, factor=4)" in B.trace_to_text(op, sp, mk([8, 1, 1, 2], rf=4))
+    for bad, why in [(mk([4, 2, 1, 2], rf=8), "does not divide"), (mk([8, 1, 1, 2], rf=2, cw=1), "cache_write"),
+                     (mk([8, 1, 1, 2], cache=5, reorder=3, rf=2), "persistent")]:
+        with pytest.raises(B.MsError, match=why):
+            B.trace_validate(op, sp, bad)
+    # launching without the workspace is refused before anything touches a device
+    v = B.Variant(op, sp, mk([8, 1, 1, 2], rf=4))
+    assert v.workspace_bytes() == 4 * 256 * 256 * 4
+    with pytest.raises(B.MsError, match="workspace"):
+        v.launch([8, 8], 8)
+    with pytest.raises(B.MsError, match="aligned"):
+        v.launch([8, 8], 8, workspace=4)
+
+
+@pytest.mark.parametrize("mk", CONFIG_OPS + [lambda: B.softmax_op(1, 64, 256), lambda: B.norm_op(2, 32, 48),
+                                             lambda: B.conv2d_op(1, 32, 32, 3, 32, 7, 7, stride=2, pad=3)])
+def test_interpreter_visits_every_reduction_position_once(mk):
+    """The k split (rfactor run, k0, k1, k2, k3, intrinsic k) of any valid trace visits each position of the
+    reduction exactly once: nothing is dropped or counted twice, whatever the decisions."""
+    op = mk()
+    flags = B.SPACE_DEFAULT | B.SPACE_RFACTOR
+    sp = op.space(flags)
+    K = [e for n, e, red in op.loops() if red]
+    for idx in range(40):
+        t = B.trace_sample_valid(op, sp, 22, idx)
+        p = B.trace_validate(op, sp, t)
+        cov = B.variant_reduction_coverage(op, p)
+        assert cov.min() == 1 and cov.max() == 1, t.decisions()
+        total = int(np.prod(K))
+        assert total <= len(cov) < total + max(1, p.tile_unit[2])  # a convolution may pad K up to the intrinsic's k
