@@ -51,7 +51,7 @@
 extern "C" {
 #endif
 
-#define MS_ABI_VERSION 1
+#define MS_ABI_VERSION 2
 
 typedef enum ms_status {
     MS_OK = 0,
@@ -154,7 +154,7 @@ int32_t ms_op_tensor_bytes(const ms_op *op, int32_t idx /* -1 = output */, int64
 
 #define MS_MAX_SLOTS 16
 #define MS_MAX_FACTORS 4
-#define MS_MAX_CANDS 8
+#define MS_MAX_CANDS 12
 
 typedef enum ms_slot_kind { MS_SLOT_PERFECT_TILE = 0, MS_SLOT_CATEGORICAL = 1 } ms_slot_kind;
 
@@ -170,8 +170,13 @@ typedef enum ms_slot_id {
                               1 = staged in LDS, 2 = staged in LDS, double buffered,
                               3 (matrix-core kernels) = double buffered, prefetch two tiles ahead,
                               4 (matrix-core kernels) = double buffered, two wavefront groups half a step apart,
-                              5, 6, 7 (matrix-core kernels, 2-byte inputs) = global memory -> LDS directly,
-                              a ring of 2, 3, 4 buffers */
+                              5, 6, 7 (matrix-core kernels, 2-byte and 1-byte inputs) = global memory -> LDS directly,
+                              a ring of 2, 3, 4 buffers,
+                              8, 9, 10 = that ring of 2, 3, 4 buffers under persistent workgroups (reorder 3) whose
+                              wavefronts form two groups one phase apart: while one group multiplies a slot of
+                              k3 intrinsic steps from registers, the other reads its next slot from LDS; a k0 step
+                              is k2 such slots (k1 = 1); with cache_write 1 every wavefront stages its results in an
+                              LDS area of its own */
     MS_SLOT_VECTORIZE = 7, /* categorical: elements per global load instruction of operand A (conv: X) */
     MS_SLOT_STORAGE_ALIGN = 8, /* categorical: LDS layout: 0 = dense, 1 = each row / plane padded by 16 bytes,
                               2 (matrix-core kernels) = padded, and the 16-byte slots of a plane XOR-swizzled */
@@ -346,7 +351,7 @@ typedef struct ms_variant_params {
     int32_t waves;
     int32_t acc_per_thread; /* accumulator registers per lane */
     int32_t lds_bytes;
-    int32_t cache_read;     /* 0 .. 7 as in MS_SLOT_CACHE_READ */
+    int32_t cache_read;     /* 0 .. 10 as in MS_SLOT_CACHE_READ */
     int32_t vec;            /* elements per global load of A (depthwise: channels per access) */
     int32_t unroll;         /* budget */
     int32_t unroll_k1, unroll_k2; /* unroll factors of the two rolled reduction loops */

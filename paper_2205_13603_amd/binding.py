@@ -25,7 +25,7 @@ SPACE_TAP_ROWS = 0x200  # opt-in: conv2d reduction laid out as filter rows (firs
 SPACE_RFACTOR = 0x400  # opt-in: sample the split of the reduction across workgroups (needs a workspace)
 SPACE_DEFAULT = 0xFF
 FAM_GEMM_ALU, FAM_GEMM_MFMA, FAM_DWCONV, FAM_REDUCE = range(4)
-MAX_SLOTS, MAX_FACTORS, MAX_CANDS, MAX_LOOPS = 16, 4, 8, 8
+MAX_SLOTS, MAX_FACTORS, MAX_CANDS, MAX_LOOPS = 16, 4, 12, 8
 
 F8E4M3 = 5
 DTYPE_NAMES = {"f32": F32, "f16": F16, "bf16": BF16, "i8": I8, "i32": I32, "f8": F8E4M3}

@@ -14,7 +14,10 @@
 //           writes of the next tile are spread between the MFMAs as well; 4: two buffers, the wavefronts split
 //           into two groups half a step apart so that one group's memory phase
 //           runs under the other's MFMA phase; 5, 6, 7: tiles loaded from global memory
-//           straight into a ring of 2, 3, 4 LDS buffers (see "Direct-to-LDS path" below))
+//           straight into a ring of 2, 3, 4 LDS buffers (see "Direct-to-LDS path" below); 8, 9: the same ring
+//           of 2, 3 buffers under persistent workgroups whose wavefronts form two groups one phase apart:
+//           while one group multiplies a k step from registers, the other reads the next step's fragments
+//           from LDS (see "Ping-pong on the ring" below))
 //   storage-align: LDS_PAD 1, 2: each LDS plane padded by 16 bytes; 2: slots of a plane XOR-swizzled
 //   vectorize: global loads of VEC (A) and VEC_B (B) elements
 //   cache-write (CACHE_WRITE 1): the output tile is assembled in LDS and stored as whole rows
@@ -814,7 +817,7 @@ constexpr int NS = K1 * K2;
 // 16-byte fragments only: 2-byte inputs with 16x16x32 / 32x32x16, 1-byte inputs with 16x16x64 / 32x32x32 (their B of NN
 // is read with the 8-bit transpose load, 8 k-rows x 16 columns per group of 16 lanes).
 #if CACHE_READ >= 5
-constexpr int DL_STAGES = CACHE_READ - 3;
+constexpr int DL_STAGES = CACHE_READ >= 8 ? CACHE_READ - 6 : CACHE_READ - 3; // 5, 6, 7 and 8, 9, 10: rings of 2, 3, 4 stages
 constexpr int CE = 16 / ES;                               // elements per 16-byte chunk
 constexpr int CPR = BK / CE;                              // 16-byte chunks per k-contiguous row
 constexpr int ROW_BYTES = BK * ES;
@@ -885,6 +888,36 @@ __device__ __forceinline__ void dl_issue(const in_t *__restrict__ A, const in_t 
 #endif
             __builtin_amdgcn_global_load_lds(AS1(ub + voff), AS3(stage + DL_A_BYTES + ib * 1024), 16, 0, 0);
         }
+    }
+}
+
+// load instruction number n (wave-uniform, at run time; n counts as in dl_issue) of this wavefront's share
+__device__ __forceinline__ void dl_issue_one(const in_t *__restrict__ A, const in_t *__restrict__ B, char *stage, int i0, int j0, int k0, int wave,
+                                             int lane, int n)
+{
+    const long k0e = (long)k0 * BK;
+    const int inst = n * NWAVES + wave; // wave-uniform
+    if (inst < DL_IA) {
+        const int row = inst * RPI + lane / CPR;
+        const int c = (lane % CPR) ^ dl_swz(row);
+        const char *ub = (const char *)(A + ((long)i0 * BM + inst * RPI) * SA_I + k0e);
+        const unsigned voff = (unsigned)(((lane / CPR) * SA_I + c * CE) * ES);
+        __builtin_amdgcn_global_load_lds(AS1(ub + voff), AS3(stage + inst * 1024), 16, 0, 0);
+    } else if (DL_INSTR % NWAVES == 0 || inst < DL_INSTR) {
+        const int ib = inst - DL_IA;
+#if B_KMAJOR
+        const int row = ib * RPI + lane / CPR;
+        const int c = (lane % CPR) ^ dl_swz(row);
+        const char *ub = (const char *)(B + ((long)j0 * BN + ib * RPI) * SB_J + k0e);
+        const unsigned voff = (unsigned)(((lane / CPR) * SB_J + c * CE) * ES);
+#else
+        const int idx = ib * 64 + lane;
+        const int k = (BK * CB) % 64 == 0 ? idx / CB : (idx / CB < BK ? idx / CB : BK - 1);
+        const int c = (idx % CB) ^ dl_swz_b(k);
+        const char *ub = (const char *)(B + k0e * SB_K + (long)j0 * BN);
+        const unsigned voff = (unsigned)((k * SB_K + c * CE) * ES);
+#endif
+        __builtin_amdgcn_global_load_lds(AS1(ub + voff), AS3(stage + DL_A_BYTES + ib * 1024), 16, 0, 0);
     }
 }
 
@@ -1041,14 +1074,238 @@ __device__ __forceinline__ tile_id decode_tile(long f, long total)
     constexpr int G = I0 * J0;
     if (total % 8 == 0) f = (f % 8) * (total / 8) + f / 8;
     const int wg = (int)(f % G), z = (int)(f / G);
-    tile_id t;
-    t.inst = z / DIM_B;
-    t.bb = z % DIM_B;
-    t.i0 = wg / J0;
-    t.j0 = wg % J0;
+    tile_id t; // wave-uniform, and in scalar registers: the addresses derived from it are scalar arithmetic
+    t.inst = __builtin_amdgcn_readfirstlane(z / DIM_B);
+    t.bb = __builtin_amdgcn_readfirstlane(z % DIM_B);
+    t.i0 = __builtin_amdgcn_readfirstlane(wg / J0);
+    t.j0 = __builtin_amdgcn_readfirstlane(wg % J0);
     return t;
 }
 
+#if CACHE_READ >= 8
+// --------------------------------------------------------------------------------------
+// Ping-pong on the ring (CACHE_READ 8, 9 = 2, 3 stages; persistent workgroups, K1 = K2 = 1).
+//
+// The wavefronts form two groups (wavefront w and w + NWAVES/2 share a SIMD).  A k0 step (one ring stage) is
+// K2 slots of K3 MFMA k steps; a slot of a group is two phases: R = read the slot's fragments from LDS into
+// registers, M = the slot's MFMAs from registers.
+// Group 1 runs one phase behind group 0 and every phase ends with a workgroup barrier, so in every phase one
+// wavefront of each SIMD multiplies while the other moves data: matrix cores and the LDS port work at the
+// same time by construction, not by the luck of the scheduler.  The loads of step n + STAGES - 1 are issued
+// from the phase on in which group 0 reads the first slot of step n (the stage they refill was last read one
+// phase earlier, by group 1), by the group that is multiplying.  A tile ends with one more phase per group in which the group writes its results:
+// through a staging area of its own per wavefront (CACHE_WRITE 1: whole 128-byte lines, no workgroup
+// barrier) or straight from the registers.
+#define WAIT_LGKM0() __builtin_amdgcn_s_waitcnt((15 | (3 << 14) | (7 << 4) | (0 << 8)))
+#define PHASE_END()                          \
+    do {                                     \
+        __builtin_amdgcn_sched_barrier(0);   \
+        __builtin_amdgcn_s_barrier();        \
+        __builtin_amdgcn_sched_barrier(0);   \
+    } while (0)
+
+static_assert(K1 == 1, "ping-pong on the ring: a step is K2 slots of K3 MFMA k steps, each slot one read phase and one multiply phase");
+static_assert(NWAVES % 2 == 0, "ping-pong on the ring: two groups of wavefronts");
+
+// staging area of one wavefront: MI_M rows of its J3 adjacent tiles, 16-byte chunks XOR-swizzled by the row
+constexpr int WS_COLS = J3 * MI_N;
+constexpr int WS_ROW = WS_COLS * (int)sizeof(out_t);
+constexpr int WS_CH = WS_ROW / 16;
+constexpr int WS_SWZ = (WS_CH & (WS_CH - 1)) == 0 ? (WS_CH > 8 ? 7 : WS_CH - 1) : 0;
+constexpr int WS_BYTES = CACHE_WRITE ? MI_M * WS_ROW : 0;
+static_assert(!CACHE_WRITE || WS_ROW % 16 == 0, "staged output rows are whole 16-byte chunks");
+
+__device__ __forceinline__ void write_tile_wave(accv_t (&acc)[TM][TN], out_t *__restrict__ C, int i0, int j0, char *__restrict__ wstage, int lane,
+                                                int wi, int wj, int lrow, int lgrp)
+{
+#pragma unroll
+    for (int r1 = 0; r1 < I1; ++r1)
+#pragma unroll
+        for (int r3 = 0; r3 < I3; ++r3)
+#pragma unroll
+            for (int c1 = 0; c1 < J1; ++c1) {
+                const int trow = (r1 * I2 + wi) * I3 + r3;
+                const int tcol0 = (c1 * J2 + wj) * J3; // first of the J3 adjacent tiles
+#pragma unroll
+                for (int c3 = 0; c3 < J3; ++c3)
+#pragma unroll
+                    for (int g = 0; g < ACC_N / 4; ++g) {
+                        const int lc = c3 * MI_N + (MI_M == 16 ? 4 * lgrp : 8 * g + 4 * lgrp); // column inside the staged rows
+                        vec_t<out_t, 4> o;
+#pragma unroll
+                        for (int e = 0; e < 4; ++e) o.v[e] = from_acc(acc[r1 * I3 + r3][c1 * J3 + c3][4 * g + e]);
+#if CACHE_WRITE
+                        const int byte = lc * (int)sizeof(out_t);
+                        *reinterpret_cast<vec_t<out_t, 4> *>(wstage + lrow * WS_ROW + (((byte / 16) ^ (lrow & WS_SWZ)) * 16) + byte % 16) = o;
+#else
+                        *reinterpret_cast<vec_t<out_t, 4> *>(C + ((long)i0 * BM + trow * MI_M + lrow) * LDC + (long)j0 * BN + tcol0 * MI_N + lc) = o;
+#endif
+                    }
+#if CACHE_WRITE
+                // the same wavefront reads what it wrote (LDS operations of one wavefront execute in order)
+                typedef vec_t<unsigned, 4> chunk_t;
+#pragma unroll
+                for (int idx = lane; idx < MI_M * WS_CH; idx += 64) {
+                    const int row = idx / WS_CH, ch = idx % WS_CH;
+                    const chunk_t v = *reinterpret_cast<const chunk_t *>(wstage + row * WS_ROW + ((ch ^ (row & WS_SWZ)) * 16));
+                    char *dst = (char *)(C + ((long)i0 * BM + trow * MI_M + row) * LDC + (long)j0 * BN + tcol0 * MI_N) + ch * 16;
+                    *reinterpret_cast<chunk_t *>(dst) = v;
+                }
+#endif
+            }
+}
+
+// The loads of a step are cut into PP_PARTS parts, one per M phase that may carry them, and inside an M phase they
+// are spread evenly between the MFMAs.  A load instruction holds the wavefront that issues it until the memory
+// pipeline accepts it (about 30 cycles of the compute unit's time per KiB when the unit streams its tiles): issued
+// in a row they lengthen the phase by that much, spread out they find the pipeline free and the matrix cores keep
+// working on the MFMAs already issued.  With two stages the last slot of a step carries no loads: they would have to
+// land within that same phase.
+constexpr int PP_NI = (DL_INSTR + NWAVES - 1) / NWAVES;                          // load instructions per wavefront and step
+constexpr int PP_PARTS = DL_STAGES == 2 ? (K2 > 1 ? K2 - 1 : 1) : K2;
+constexpr int PP_LOADS = (PP_NI + PP_PARTS - 1) / PP_PARTS;                     // load instructions of one part
+constexpr int PP_NM = K3 * TM * TN;                                              // MFMAs of one M phase
+
+extern "C" __global__ void __launch_bounds__(NTHREADS)
+ms_kernel(const void *__restrict__ a_, const void *__restrict__ b_, const void *__restrict__ bias_, void *__restrict__ c_, int instances)
+{
+    (void)bias_;
+    const int tid = threadIdx.x;
+    const int lane = tid % 64, wave = tid / 64;
+    const int wi = wave / J2, wj = wave % J2;
+    const int lrow = lane % MI_M, lgrp = lane / MI_M;
+    const int wave_u = __builtin_amdgcn_readfirstlane(wave);
+    const bool late = wave_u >= NWAVES / 2; // group 1: one phase behind
+
+    constexpr int OPND_BYTES = DL_STAGES * DL_STAGE_BYTES;
+    constexpr int LDS_BYTES = OPND_BYTES + NWAVES * WS_BYTES;
+    __shared__ __attribute__((aligned(16))) char lds[LDS_BYTES];
+    char *const wstage = lds + OPND_BYTES + wave_u * WS_BYTES;
+
+    const long total = (long)I0 * J0 * DIM_B * instances;
+    const long first = blockIdx.x, stride = gridDim.x;
+    if (first >= total) return;
+    const long my_tiles = (total - first + stride - 1) / stride;
+    const long my_steps = my_tiles * K0;
+
+    // load cursor: the step whose loads are being requested = k step lk of tile lt, into stage wr; past the end the
+    // last step is requested again (never read), so that every wavefront keeps issuing the same number of loads
+    long ls = 0;
+    int lk = 0;
+    tile_id lt = decode_tile(first, total);
+    long lf = first;
+    int wr = 0;
+    const in_t *cA = (const in_t *)a_ + (long)lt.inst * A_INST + (long)lt.bb * SA_B;
+    const in_t *cB = (const in_t *)b_ + (long)lt.inst * B_INST + (long)lt.bb * SB_B;
+    auto advance = [&]() {
+        wr = wr + 1 == DL_STAGES ? 0 : wr + 1;
+        if (ls + 1 < my_steps) {
+            ++ls;
+            if (++lk == K0) {
+                lk = 0;
+                lf += stride;
+                lt = decode_tile(lf, total);
+                cA = (const in_t *)a_ + (long)lt.inst * A_INST + (long)lt.bb * SA_B;
+                cB = (const in_t *)b_ + (long)lt.inst * B_INST + (long)lt.bb * SB_B;
+            }
+        }
+    };
+#pragma unroll
+    for (int t = 0; t < DL_STAGES - 1; ++t) {
+        dl_issue(cA, cB, lds + wr * DL_STAGE_BYTES, lt.i0, lt.j0, lk, wave_u, lane);
+        advance();
+    }
+
+    accv_t acc[TM][TN];
+    frag_t fa[K3][TM], fb[K3][TN];
+    auto zero_acc = [&]() {
+#pragma unroll
+        for (int tm = 0; tm < TM; ++tm)
+#pragma unroll
+            for (int tn = 0; tn < TN; ++tn)
+#pragma unroll
+                for (int e = 0; e < ACC_N; ++e) acc[tm][tn][e] = 0;
+    };
+    zero_acc();
+    int rd = 0;
+    bool drain = false; // stores of an epilogue are outstanding: the next wait counts them too, so it waits for everything
+
+    // step 0 has landed for everybody
+    DL_WAIT_VM((DL_STAGES - 2) * DL_LPW_MIN);
+    PHASE_END();
+    if (late) {
+        // the phase in which group 0 reads slot 0 of step 0: group 1 only requests part 0 of the step at the cursor
+#pragma unroll
+        for (int n = 0; n < PP_LOADS; ++n)
+            if (n < PP_NI) dl_issue_one(cA, cB, lds + wr * DL_STAGE_BYTES, lt.i0, lt.j0, lk, wave_u, lane, n);
+        if (PP_PARTS == 1) advance();
+        PHASE_END();
+    }
+#pragma unroll 1
+    for (long ti = 0; ti < my_tiles; ++ti) {
+        const tile_id ct = decode_tile(first + ti * stride, total);
+#pragma unroll 1
+        for (int k0 = 0; k0 < K0; ++k0) {
+#pragma unroll
+            for (int h = 0; h < K2; ++h) { // the K2 slots of a step: K3 MFMA k steps each, one R and one M phase
+                // ---- phase R: fragments of this slot -> registers
+                dl_read_frags(fa, fb, lds + rd * DL_STAGE_BYTES, h, wi, wj, lane);
+                WAIT_LGKM0(); // after its last slot the stage may be refilled from the next phase on
+                if (late && h == K2 - 1) {
+                    // group 1: its loads of the next step (requested one or more phases ago) have landed
+                    if (drain) DL_WAIT_VM(0);
+                    else DL_WAIT_VM((DL_STAGES - 2) * DL_LPW_MIN);
+                    drain = false;
+                }
+                PHASE_END();
+                // ---- phase M: request this phase's part of the step at the cursor, multiply from registers
+                // (group 0 in slot h: part h; group 1 runs one phase behind, its slot h coincides with group 0's
+                // reading of slot h + 1: part h + 1, or part 0 of the following step after the last slot)
+                const int part = late ? (h + 1) % K2 : h; // wave-uniform
+                const bool loading = part < PP_PARTS;
+                const int n0 = part * PP_LOADS;
+                char *const wstg = lds + wr * DL_STAGE_BYTES;
+                __builtin_amdgcn_s_setprio(1);
+                {
+                    int m = 0; // a constant after unrolling
+#pragma unroll
+                    for (int q = 0; q < K3; ++q)
+#pragma unroll
+                        for (int tm = 0; tm < TM; ++tm)
+#pragma unroll
+                            for (int tn = 0; tn < TN; ++tn) {
+                                acc[tm][tn] = mfma(fb[q][tn], fa[q][tm], acc[tm][tn]);
+                                ++m;
+                                // after m of the NM MFMAs, floor(m * (LOADS + 1) / NM) of the phase's loads are out (all of
+                                // them before the last MFMA): evenly spread, several per gap when there are more loads than MFMAs
+                                const int due = (m * (PP_LOADS + 1)) / PP_NM, was = ((m - 1) * (PP_LOADS + 1)) / PP_NM;
+#pragma unroll
+                                for (int l = was; l < due; ++l)
+                                    if (l < PP_LOADS && loading && n0 + l < PP_NI) dl_issue_one(cA, cB, wstg, lt.i0, lt.j0, lk, wave_u, lane, n0 + l);
+                            }
+                }
+                if (loading && part == PP_PARTS - 1) advance();
+                __builtin_amdgcn_s_setprio(0);
+                if (!late && h == K2 - 1) {
+                    if (drain) DL_WAIT_VM(0);
+                    else DL_WAIT_VM((DL_STAGES - 2) * DL_LPW_MIN);
+                    drain = false;
+                }
+                PHASE_END();
+            }
+            rd = rd + 1 == DL_STAGES ? 0 : rd + 1;
+        }
+        // ---- phase E: results of the tile (the other group multiplies its last slot, or reads its first)
+        out_t *C = (out_t *)c_ + ((long)ct.inst * DIM_B + ct.bb) * ((long)DIM_M * DIM_N);
+        write_tile_wave(acc, C, ct.i0, ct.j0, wstage, lane, wi, wj, lrow, lgrp);
+        zero_acc();
+        drain = true;
+        PHASE_END();
+    }
+    if (!late) PHASE_END(); // group 1's last phase
+    DL_WAIT_VM(0);          // the re-loads past the end must land before the workgroup's LDS is released
+}
+#else
 extern "C" __global__ void __launch_bounds__(NTHREADS)
 ms_kernel(const void *__restrict__ a_, const void *__restrict__ b_, const void *__restrict__ bias_, void *__restrict__ c_, int instances)
 {
@@ -1146,6 +1403,7 @@ ms_kernel(const void *__restrict__ a_, const void *__restrict__ b_, const void *
     }
     DL_WAIT_VM(0); // the re-loads past the end must land before the workgroup's LDS is released
 }
+#endif // CACHE_READ >= 8
 #elif CONV_RESIDENT
 // --------------------------------------------------------------------------------------
 // conv2d, COMPUTE_AT 2: persistent workgroups, resident weights, input patch per tile.

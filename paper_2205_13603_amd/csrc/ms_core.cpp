@@ -592,7 +592,7 @@ extern "C" int32_t ms_space_describe(const ms_op *op, uint32_t flags, ms_space *
         if (flags & MS_SPACE_CACHE_READ) {
             // direct-to-LDS staging (5, 6, 7) exists for 2-byte and 1-byte inputs of plain matrix products
             if (d.in_dtype != MS_F32 && d.in_dtype != MS_F8E4M3 && !is_conv2d(d.kind))
-                add_cat(out, MS_SLOT_CACHE_READ, "cache_read", {1, 2, 3, 4, 5, 6, 7});
+                add_cat(out, MS_SLOT_CACHE_READ, "cache_read", {1, 2, 3, 4, 5, 6, 7, 8, 9, 10});
             else add_cat(out, MS_SLOT_CACHE_READ, "cache_read", {1, 2, 3, 4});
         }
         if (flags & MS_SPACE_VECTORIZE) {
@@ -936,7 +936,11 @@ extern "C" int32_t ms_trace_to_text(const ms_op *op, const ms_space *space, cons
             // everything was said above
         } else {
         if (p.cache_read) {
-            if (p.cache_read >= 5)
+            if (p.cache_read >= 8)
+                appendf(s, "cache-read(buffers=[A, B], scope=lds, at=k0, stages=%d, prefetch_distance=%d, direct_to_lds=1)\n"
+                           "annotate(block=C, key=wave_groups, value=ping_pong_on_the_ring)  # slots of k3 steps: one group reads, the other multiplies\n",
+                        p.cache_read - 6, p.cache_read - 7);
+            else if (p.cache_read >= 5)
                 appendf(s, "cache-read(buffers=[A, B], scope=lds, at=k0, stages=%d, prefetch_distance=%d, direct_to_lds=1)\n", p.cache_read - 3, p.cache_read - 4);
             else if (p.compute_at >= 2)
                 appendf(s, "%sbind(fuse(i0, j0), persistent workgroup loop over runs of consecutive tiles)\n"
@@ -953,7 +957,7 @@ extern "C" int32_t ms_trace_to_text(const ms_op *op, const ms_space *space, cons
             if (p.cache_read == 4) appendf(s, "annotate(block=C, key=wave_groups, value=ping_pong)\n");
             appendf(s, "storage-align(scope=lds, pad_bytes=%d, swizzle=%d)\n", p.lds_pad ? 16 : 0, p.lds_pad == 2);
         }
-        if (p.cache_write) appendf(s, "cache-write(buffer=C, scope=lds)\n");
+        if (p.cache_write) appendf(s, "cache-write(buffer=C, scope=lds%s)\n", p.cache_read >= 8 ? ", per wavefront" : "");
         if (p.rfactor > 1) appendf(s, "rfactor(loop=k0, factor=%d)  # partial sums in the workspace, second kernel adds them in order\n", p.rfactor);
         if (p.vec > 1) appendf(s, "vectorize(global loads of A, width=%d)\n", p.vec);
         if (p.vec_b > 1) appendf(s, "vectorize(global loads of B, width=%d)\n", p.vec_b);

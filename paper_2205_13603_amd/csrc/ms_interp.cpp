@@ -236,7 +236,26 @@ extern "C" int32_t ms_trace_validate(const ms_op *op, const ms_space *space, con
                 if (p.lds_pad) return reject("direct-to-LDS staging has its own swizzle: storage_align must be 0");
                 // the j-contiguous B tile is rounded up to whole 1 KiB load instructions
                 int64_t btile = d.b_strides[2] == 1 ? ((bk * (bn / ce) + 63) / 64) * 1024 : bn * bk * es;
-                lds = (int64_t)(p.cache_read - 3) * (bm * bk * es + btile);
+                const int stages = p.cache_read >= 8 ? p.cache_read - 6 : p.cache_read - 3;
+                lds = (int64_t)stages * (bm * bk * es + btile);
+                if (p.cache_read >= 8) {
+                    // ping-pong on the ring: two groups of wavefronts one phase apart under persistent workgroups
+                    if (p.reorder != 3) return reject("ping-pong on the ring (cache_read 8, 9, 10) runs under persistent workgroups: reorder must be 3");
+                    if (p.waves % 2) return reject("ping-pong on the ring needs an even number of wavefronts, not %d", p.waves);
+                    if (p.tk[1] != 1) return reject("ping-pong on the ring: a k0 step is k2 slots of k3 intrinsic steps, k1 must be 1");
+                    // a slot's fragments and the accumulators are all live; 64 more registers hold the LDS addresses of the
+                    // fragments, the load offsets and the epilogue's temporaries (what the compiler needed for a
+                    // 128 x 64 wave tile: 247 registers with 128 accumulators and 48 fragment registers)
+                    const int64_t fr = kp * es / 4 > 0 ? kp * es / 4 : 1;
+                    const int64_t fragr = ((int64_t)p.ti[1] * p.ti[3] + (int64_t)p.tj[1] * p.tj[3]) * p.tk[3] * fr;
+                    const int64_t have = 512 / ((p.waves + 3) / 4);
+                    if (fragr + acc + 64 > have)
+                        return reject("ping-pong on the ring: %" PRId64 " fragment + %" PRId64 " accumulator + 64 other registers per lane exceed the %" PRId64
+                                      " a wavefront can have", fragr, acc, have);
+                    // the k2 slots are always unrolled, whatever the budget: one kernel, one key
+                    p.unroll_k1 = 1;
+                    p.unroll_k2 = p.tk[2];
+                }
             }
             if (is_conv2d(d.kind) && op->K % p.tile_unit[2] && !p.tap_rows) {
                 // the k split covers the reduction rounded up to the intrinsic's k; only the im2col loader pads with zeros
@@ -294,7 +313,12 @@ extern "C" int32_t ms_trace_validate(const ms_op *op, const ms_space *space, con
             if (p.cache_write) {
                 // the output tile reuses the operand buffers: rows of bn outputs padded by 16 bytes
                 int64_t ctile = bm * (bn * op->out_size + 16);
-                if (p.reorder == 3 || p.compute_at >= 2) lds += ctile; // persistent workgroups keep their operands alive during the epilogue
+                if (p.cache_read >= 8) {
+                    // one staging area per wavefront: the rows of one intrinsic tile across the wavefront's j3 adjacent tiles
+                    const int64_t wrow = (int64_t)p.tj[3] * p.tile_unit[1] * op->out_size;
+                    if (wrow % 16) return reject("cache_write on the ring: a wavefront's staged rows of %" PRId64 " bytes are not whole 16-byte chunks", wrow);
+                    lds += (int64_t)p.waves * p.tile_unit[0] * wrow;
+                } else if (p.reorder == 3 || p.compute_at >= 2) lds += ctile; // persistent workgroups keep their operands alive during the epilogue
                 else if (ctile > lds) lds = ctile;
                 if ((op->N * op->out_size) % 16) return reject("cache_write needs output rows that are multiples of 16 bytes");
             }

@@ -373,3 +373,79 @@ def test_fp8_deep_intrinsics_exact_then_random():
         if got is None:
             continue
         compare.assert_float_close(got, ref, compare.RTOL_F8, "fp8 deep NT trace %d" % n)
+
+
+def test_ping_pong_on_the_ring_exact():
+    """cache_read 8, 9, 10: persistent workgroups on the direct-to-LDS ring whose wavefronts form two groups one
+    phase apart.  Integer-valued inputs (every sum exact): fp16 NN and NT, int8, both 16-byte-fragment intrinsics,
+    1 to 4 slots per k0 step, 2 / 3 / 4 stages, results staged per wavefront or stored from registers, odd tile counts,
+    fewer tiles than compute units (3 instances) and runs of several tiles per workgroup (40 instances)."""
+    M, N, K = 192, 320, 512
+    g = I.rng(77)
+
+    def run(op, space, traces, ins_of, refs_of, odt, what):
+        for R in (3, 40):
+            ins = [ins_of(r) for r in range(R)]
+            refs = [refs_of(x) for x in ins[:3]] + [None] * (R - 3)
+            for n, t in enumerate(traces):
+                try:
+                    p = B.trace_validate(op, space, t)
+                except B.MsError as e:
+                    raise AssertionError("%s trace %d rejected: %s" % (what, n, e))
+                print(what, "R", R, "trace", n, t.decisions(), "lds", p.lds_bytes, flush=True)
+                got = run_variant_distinct(op, space, t, ins, odt, (M, N))
+                if got is None:
+                    continue
+                for r in (0, 1, 2, R - 1):
+                    ref = refs[r] if refs[r] is not None else refs_of(ins[r])
+                    assert np.array_equal(got[r], ref), "%s R %d trace %d instance %d" % (what, R, n, r)
+
+    # fp16, B stored [K][N] (read with the LDS transpose load)
+    op = B.gemm_op(M, N, K, "f16", "f32")
+    sp = op.space()
+
+    def mk(sp, mfma, i, j, k, cache=8, cw=0, vec=8):
+        return B.make_trace(sp, [[mfma], i, j, k, [0], [cache], [vec], [vec], [0], [3], [cw]])
+
+    pool = [(I.small_ints(g, (M, K), -2, 2, "f16"), I.small_ints(g, (K, N), -2, 2, "f16")) for _ in range(5)]
+    traces = [mk(sp, 323216, [3, 1, 2, 1], [5, 1, 1, 2], [8, 1, 2, 2], cache=8, cw=1),     # BK = 64, two slots, staged per wavefront
+              mk(sp, 323216, [3, 2, 1, 1], [5, 1, 2, 1], [16, 1, 1, 2], cache=10, cw=0),   # BK = 32, 4 stages
+              mk(sp, 161632, [3, 2, 2, 1], [5, 2, 1, 2], [4, 1, 4, 1], cache=9, cw=1),     # BK = 128, four slots of one step
+              mk(sp, 161632, [6, 1, 2, 1], [10, 1, 2, 1], [16, 1, 1, 1], cache=9, cw=1),   # one intrinsic step per slot
+              mk(sp, 161632, [3, 1, 4, 1], [5, 2, 2, 1], [8, 1, 1, 2], cache=8, cw=0)]     # 8 wavefronts, 4 x 2
+    run(op, sp, traces, lambda r: list(pool[r % 5]), lambda x: O.gemm(x[0], x[1]), "f32", "f16 NN")
+    # fp16, B stored [N][K] (both operands contiguous along k), fp16 output
+    opt = B.bmm_op(1, M, N, K, True, "f16")
+    spt = opt.space()
+    poolt = [(I.small_ints(g, (1, M, K), -1, 1, "f16"), I.small_ints(g, (1, N, K), -1, 1, "f16")) for _ in range(5)]
+    tr_t = [mk(spt, 323216, [3, 1, 2, 1], [5, 1, 1, 2], [8, 1, 2, 2], cache=8, cw=1),
+            mk(spt, 161632, [3, 2, 2, 1], [10, 1, 2, 1], [8, 1, 2, 1], cache=10, cw=0)]
+    run(opt, spt, tr_t, lambda r: list(poolt[r % 5]), lambda x: O.bmm(x[0], x[1], trans_b=True)[0], "f16", "f16 NT")
+    # int8 -> int32 (8-bit transpose load for B)
+    op8 = B.gemm_op(M, N, K, "i8")
+    sp8 = op8.space()
+    pool8 = [(I.int8_uniform(g, (M, K)), I.int8_uniform(g, (K, N))) for _ in range(5)]
+    tr_8 = [mk(sp8, 323232, [3, 1, 2, 1], [5, 1, 1, 2], [4, 1, 2, 2], cache=8, cw=1, vec=16),
+            mk(sp8, 161664, [3, 2, 2, 1], [5, 2, 1, 2], [4, 1, 1, 2], cache=9, cw=0, vec=16)]
+    run(op8, sp8, tr_8, lambda r: list(pool8[r % 5]), lambda x: O.gemm(x[0], x[1]), "i32", "int8")
+
+
+def test_ping_pong_on_the_ring_c2_shape():
+    """Config 2's shape in the launch configuration bench.py times (64 instances): sampled instances against the oracle."""
+    op = B.gemm_op(1024, 1024, 1024, "f16")
+    sp = op.space()
+    ins = [I.c2(seed=50 + r) for r in range(4)]
+    R = 64
+    per_instance = [list(ins[r % 4]) for r in range(R)]
+    refs = None
+    for n, (i, j, k, cache, cw) in enumerate([([4, 4, 2, 1], [4, 1, 4, 2], [16, 1, 2, 2], 8, 1), ([4, 4, 2, 1], [4, 1, 4, 2], [32, 1, 1, 2], 10, 1),
+                                              ([4, 2, 2, 2], [4, 1, 4, 2], [32, 1, 1, 2], 9, 0)]):
+        t = B.make_trace(sp, [[323216], i, j, k, [0], [cache], [8], [8], [0], [3], [cw]])
+        print("c2 ping-pong trace", n, t.decisions(), flush=True)
+        got = run_variant_distinct(op, sp, t, per_instance, "f16", (1024, 1024))
+        if got is None:
+            continue
+        if refs is None:
+            refs = [O.gemm(a, b) for a, b in ins]
+        for r in (0, 1, 2, 3, 31, 63):
+            compare.assert_float_close(got[r], refs[r % 4], compare.RTOL_HALF, "C2 ping-pong trace %d instance %d" % (n, r))

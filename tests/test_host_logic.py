@@ -25,7 +25,7 @@ def test_library_exports_every_declared_symbol():
     for name in sorted(declared):
         assert hasattr(L, name), "libms.so does not export %s" % name
     assert declared == set(B.SYMBOLS), (declared ^ set(B.SYMBOLS))
-    assert L.ms_version() == 1
+    assert L.ms_version() == 2
 
 
 def test_struct_sizes_match_header():
