@@ -429,6 +429,25 @@ int32_t ms_variant_launch(ms_variant *v, const void *const *inputs, void *const 
                           void *workspace, int32_t instances, void *stream);
 
 /*
+ * For callers that cannot allocate (code under HIP graph capture, tight serving loops, harnesses that forbid
+ * hipMalloc): ms_variant_launch with the workspace taken from an array inside the library's own device image
+ * instead of from the caller.  MS_STATIC_WORKSPACE_BYTES of it exist on every GPU the library runs on, from the first
+ * ms_variant_prepare on that GPU until the process ends.
+ *   ms_variant_prepare        set-up, may allocate: loads the variant's kernels on the current device and resolves
+ *                             that device's copy of the workspace.  Once per variant and device.
+ *   ms_variant_launch_static  allocates nothing and frees nothing.  Same inputs / outputs / instances / stream as
+ *                             ms_variant_launch.  BAD_ARG if ms_variant_prepare has not run for this variant on the
+ *                             current device, or if instances x workspace_bytes exceeds MS_STATIC_WORKSPACE_BYTES
+ *                             (a variant with rfactor = 1 needs none and always fits).
+ * All calls on one GPU share that GPU's array, which keeps the previous call's partial sums: every value a call
+ * reads it has written itself, so nothing needs clearing, but two calls that overlap on one GPU (two streams, two
+ * threads) race on it; callers serialise them, e.g. by using one stream.
+ */
+#define MS_STATIC_WORKSPACE_BYTES (32u << 20)
+int32_t ms_variant_prepare(ms_variant *v);
+int32_t ms_variant_launch_static(ms_variant *v, const void *const *inputs, void *const *outputs, int32_t instances, void *stream);
+
+/*
  * Host-side coverage check of the interpreted loop nest (no GPU): walks the
  * grid / thread / register loops the parameters describe and counts, for
  * every output element, how often it is produced.  counts: host pointer to

@@ -24,6 +24,7 @@ SPACE_TENSORIZE_F32 = 0x100  # opt-in: fp32 operators on the fp32 matrix-core in
 SPACE_TAP_ROWS = 0x200  # opt-in: conv2d reduction laid out as filter rows (first layers with few input channels)
 SPACE_RFACTOR = 0x400  # opt-in: sample the split of the reduction across workgroups (needs a workspace)
 SPACE_DEFAULT = 0xFF
+STATIC_WORKSPACE_BYTES = 32 << 20
 FAM_GEMM_ALU, FAM_GEMM_MFMA, FAM_DWCONV, FAM_REDUCE = range(4)
 MAX_SLOTS, MAX_FACTORS, MAX_CANDS, MAX_LOOPS = 16, 4, 12, 8
 
@@ -167,6 +168,8 @@ SYMBOLS = {
     "ms_set_cache_dir": (C.c_int32, [C.c_char_p]),
     "ms_jit_stats": (C.c_int32, [_P(C.c_int64), _P(C.c_int64), _P(C.c_int64), _P(C.c_int32), _P(C.c_int32)]),
     "ms_variant_launch": (C.c_int32, [C.c_void_p, _P(C.c_void_p), _P(C.c_void_p), C.c_void_p, C.c_int32, C.c_void_p]),
+    "ms_variant_prepare": (C.c_int32, [C.c_void_p]),
+    "ms_variant_launch_static": (C.c_int32, [C.c_void_p, _P(C.c_void_p), _P(C.c_void_p), C.c_int32, C.c_void_p]),
     "ms_variant_coverage": (C.c_int32, [C.c_void_p, _P(ms_variant_params), C.c_void_p, C.c_int64]),
     "ms_variant_reduction_coverage": (C.c_int32, [C.c_void_p, _P(ms_variant_params), C.c_void_p, C.c_int64, _P(C.c_int64)]),
     "ms_measure": (C.c_int32, [C.c_void_p, _P(ms_bufset), C.c_int32, _P(ms_measure_cfg), C.c_void_p, _P(ms_measure_result)]),
@@ -475,6 +478,16 @@ class Variant:
         ins = (C.c_void_p * 4)(*[C.c_void_p(p) for p in inputs])
         outs = (C.c_void_p * 1)(C.c_void_p(output))
         _check(lib().ms_variant_launch(self.handle, ins, outs, workspace, instances, stream))
+
+    def prepare(self):
+        """Set-up for launch_static: loads the kernels on the current device, resolves the built-in workspace."""
+        _check(lib().ms_variant_prepare(self.handle))
+
+    def launch_static(self, inputs, output, instances=1, stream=None):
+        """launch() with the workspace taken from the library's built-in array; allocates nothing."""
+        ins = (C.c_void_p * 4)(*[C.c_void_p(p) for p in inputs])
+        outs = (C.c_void_p * 1)(C.c_void_p(output))
+        _check(lib().ms_variant_launch_static(self.handle, ins, outs, instances, stream))
 
     def measure(self, bufsets, warmup=2, repeats=5, launches_per_repeat=20, instances=1, stream=None):
         """bufsets: list of (inputs, output) or (inputs, output, workspace) device pointer tuples."""

@@ -7,6 +7,7 @@
 #include <algorithm>
 #include <atomic>
 #include <cstring>
+#include <mutex>
 #include <new>
 #include <thread>
 #include <vector>
@@ -126,6 +127,67 @@ static int32_t ensure_loaded(ms_variant *v)
     v->device = dev;
     v->compute_units = prop.multiProcessorCount;
     return MS_OK;
+}
+
+// ---------------------------------------------------------------- launch without allocation
+//
+// Workspace of ms_variant_launch_static: one array per GPU, in the library's own device image, held until the
+// process ends.  In host code the array's name is only a stand-in; its address on a device comes from
+// hipGetSymbolAddress with that device current, once per device, and that pointer is what kernels receive.
+static __device__ __align__(256) unsigned char scratch[MS_STATIC_WORKSPACE_BYTES];
+
+namespace {
+constexpr int kMaxDevices = 64;
+std::mutex g_scratch_mu;
+void *g_scratch_ptr[kMaxDevices]; // per device, null until ms_variant_prepare ran on it
+
+int32_t scratch_on_current_device(bool resolve, void **out)
+{
+    int dev = 0;
+    HIP_TRY(hipGetDevice(&dev));
+    if (dev < 0 || dev >= kMaxDevices) return fail(MS_ERR_UNSUPPORTED, "device index %d is beyond the %d this library keeps a workspace for", dev, kMaxDevices);
+    std::lock_guard<std::mutex> lk(g_scratch_mu);
+    if (!g_scratch_ptr[dev]) {
+        if (!resolve) return fail(MS_ERR_BAD_ARG, "ms_variant_launch_static: call ms_variant_prepare on device %d first (set-up may allocate, this call must not)", dev);
+        void *ptr = nullptr;
+        HIP_TRY(hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch)));
+        if (!ptr) return fail(MS_ERR_HIP, "hipGetSymbolAddress returned a null workspace");
+        g_scratch_ptr[dev] = ptr;
+    }
+    *out = g_scratch_ptr[dev];
+    return MS_OK;
+}
+} // namespace
+
+
+
+extern "C" int32_t ms_variant_prepare(ms_variant *v)
+{
+    if (!v) return fail(MS_ERR_BAD_ARG, "ms_variant_prepare: NULL variant");
+    int32_t rc = ensure_loaded(v);
+    if (rc != MS_OK) return rc;
+    void *ptr = nullptr;
+    return scratch_on_current_device(true, &ptr);
+}
+
+extern "C" int32_t ms_variant_launch_static(ms_variant *v, const void *const *inputs, void *const *outputs, int32_t instances, void *stream)
+{
+    if (!v || !inputs || !outputs) return fail(MS_ERR_BAD_ARG, "ms_variant_launch_static: NULL argument");
+    if (instances < 1) return fail(MS_ERR_BAD_ARG, "ms_variant_launch_static: instances = %d", instances);
+    int dev = 0;
+    HIP_TRY(hipGetDevice(&dev));
+    if (v->device != dev || !v->fn) return fail(MS_ERR_BAD_ARG, "ms_variant_launch_static: call ms_variant_prepare on device %d first (loading a kernel allocates)", dev);
+    const size_t need = workspace_per_instance(v) * (size_t)instances;
+    if (need > (size_t)MS_STATIC_WORKSPACE_BYTES)
+        return fail(MS_ERR_BAD_ARG, "ms_variant_launch_static: %d instances need a workspace of %zu bytes, the built-in one holds %zu",
+                    instances, need, (size_t)MS_STATIC_WORKSPACE_BYTES);
+    void *ws = nullptr;
+    if (need) {
+        int32_t rc = scratch_on_current_device(false, &ws);
+        if (rc != MS_OK) return rc;
+    }
+    // every partial sum the second kernel reads is written by the first kernel of the same call: nothing to clear
+    return ms_variant_launch(v, inputs, outputs, ws, instances, stream);
 }
 
 extern "C" int32_t ms_variant_launch(ms_variant *v, const void *const *inputs, void *const *outputs, void *workspace,
