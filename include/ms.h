@@ -292,6 +292,52 @@ typedef struct ms_space {
     ms_slot slots[MS_MAX_SLOTS];
 } ms_space;
 
+/*
+ * The modules as data (Section 3.2): every transformation module has a name, the location of e0 it applies to, the
+ * Table 2 primitives it emits, its bit in a module mask and the bits that must already be in the space.  Module 0 is
+ * Multi-Level-Tiling, the base every kernel family is built on.
+ */
+#define MS_MAX_MODULES 16
+typedef enum ms_location {
+    MS_LOC_BLOCK = 0,   /* the compute block C of e0 */
+    MS_LOC_READS = 1,   /* the reads of C's operands (exists once the block is tiled) */
+    MS_LOC_LDS = 2,     /* the LDS stage of the operands (exists once the block is tiled) */
+    MS_LOC_WRITE = 3,   /* the write of C's result (exists once the block is tiled) */
+    MS_LOC_LAUNCH = 4   /* the grid loops bound to workgroups (exists once the block is tiled) */
+} ms_location;
+typedef struct ms_module_info {
+    char name[32];        /* e.g. "multi-level-tiling", "use-mfma", "cache-read" */
+    char primitives[96];  /* the sampling and transformation primitives of Table 2 the module consists of */
+    int32_t location;     /* ms_location */
+    uint32_t flag;        /* its bit in a module mask (0 for the base module) */
+    uint32_t requires;    /* bits of modules that must have been applied before it */
+    int32_t reserved;
+} ms_module_info;
+int32_t ms_module_count(void);
+int32_t ms_module_get(int32_t index, ms_module_info *out);
+/*
+ * Compose(modules, e0): apply an ordered list of modules (indices of ms_module_get) to the operator and write the
+ * resulting space.  The list must start with module 0; a module whose `requires` bits were not applied earlier in the
+ * list is an error (BAD_ARG, the message names both); a module that does not apply to this operator (the matrix-core
+ * module on an fp32 depthwise convolution, compute-location on a plain matrix product, ...) is the identity, as a
+ * module's own program analysis would make it.  *applied_mask (may be NULL) receives the bits that took effect.  The
+ * space equals ms_space_describe(op, *applied_mask): slot order is canonical, so traces and stored records of one
+ * mask stay valid whatever order the modules were listed in.
+ */
+int32_t ms_space_compose(const ms_op *op, const int32_t *modules, int32_t n, uint32_t *applied_mask, ms_space *out);
+/*
+ * Stochastic-Compose (Section 3.2, its composition algorithm): while locations remain, take the next location of the
+ * program, draw one module from `module_set` and apply it there.  In this build a draw at a location is uniform over
+ * the not yet applied modules of the set that belong to that location, apply to the operator and have their
+ * requirements met, plus one "identity" outcome that retires the location; a module that was applied leaves the
+ * (changed) location in the list, so it is visited again.  Module 0 is always applied first (it creates the other
+ * locations); for an operator that has no vector-ALU kernel family (convolutions, 8-bit float inputs) the matrix-core
+ * module follows it at once (UNSUPPORTED if the set lacks it).  Deterministic in `seed`.  applied[MS_MAX_MODULES] / *n_applied: the modules in the order they were
+ * applied.  The space is ms_space_compose of that list.
+ */
+int32_t ms_space_stochastic_compose(const ms_op *op, const int32_t *module_set, int32_t n, uint64_t seed,
+                                    int32_t *applied, int32_t *n_applied, ms_space *out);
+
 /* Write the space of `op` under the enabled modules.  MS_SPACE_TENSORIZE is
  * dropped silently for F32 inputs.  UNSUPPORTED if no kernel family covers the
  * op with these flags (conv2d needs the tensorize module). */

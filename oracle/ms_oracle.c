@@ -141,6 +141,28 @@ int ms_oracle_threads(void)
 #endif
 }
 
+/* Threads of the following calls (the benchmark's single-thread baseline); 0 restores the default. No arithmetic. */
+void ms_oracle_set_threads(int n)
+{
+#ifdef _OPENMP
+    static int initial = 0;
+    if (!initial) initial = omp_get_max_threads();
+    omp_set_num_threads(n > 0 ? n : initial);
+#else
+    (void)n;
+#endif
+}
+
+/*
+ * Type of the running sum of the three operators the benchmark times as its CPU baseline (matrix product, conv2d,
+ * depthwise conv2d).  The oracle is built with double, always: that is what every test compares with.  The benchmark
+ * additionally builds this file with -DORA_ACC_T=float into a library of its own, only to report how fast the same
+ * plain loops run when they accumulate in the operator's own precision; no test loads that library.
+ */
+#ifndef ORA_ACC_T
+#define ORA_ACC_T double
+#endif
+
 /* Exposed so that tests can pin the widening itself. */
 double ms_oracle_widen(int dtype, const void *base, int64_t idx)
 {
@@ -163,7 +185,7 @@ int ms_oracle_bmm(int dtype, int64_t nb, int64_t M, int64_t N, int64_t K,
     for (bi = 0; bi < nb * M; ++bi) {
         int64_t b = bi / M, i = bi % M;
         for (int64_t j = 0; j < N; ++j) {
-            double acc = 0.0;
+            ORA_ACC_T acc = 0.0;
             for (int64_t k = 0; k < K; ++k) {
                 double a = load_elem(dtype, A, b * sAb + i * sAi + k * sAk);
                 double w = load_elem(dtype, B, b * sBb + k * sBk + j * sBj);
@@ -235,7 +257,7 @@ int ms_oracle_conv2d_nhwc(int dtype, int64_t N, int64_t H, int64_t W_, int64_t C
         int64_t n = row / OH, oh = row % OH;
         for (int64_t ow = 0; ow < OW; ++ow) {
             for (int64_t co = 0; co < Cout; ++co) {
-                double acc = 0.0;
+                ORA_ACC_T acc = 0.0;
                 for (int64_t kh = 0; kh < KH; ++kh) {
                     int64_t ih = oh * stride + kh * dilation - pad;
                     for (int64_t kw = 0; kw < KW; ++kw) {
@@ -393,7 +415,7 @@ int ms_oracle_dwconv2d_nhwc(int dtype, int64_t N, int64_t H, int64_t W_, int64_t
         int64_t n = row / OH, oh = row % OH;
         for (int64_t ow = 0; ow < OW; ++ow) {
             for (int64_t c = 0; c < C; ++c) {
-                double acc = 0.0;
+                ORA_ACC_T acc = 0.0;
                 for (int64_t kh = 0; kh < KH; ++kh) {
                     int64_t ih = oh * stride + kh - pad;
                     for (int64_t kw = 0; kw < KW; ++kw) {

@@ -15,12 +15,25 @@ from . import build as _build
 F32, F16, BF16, I8, F8E4M3 = 0, 1, 2, 3, 5
 
 _lib = None
+_libs = {}
+_kind = "f64"
+
+
+def use_build(kind):
+    """Select which build of ms_oracle.c the following calls run: "f64" = the oracle (double accumulation; the only one
+    tests ever use), "f32acc" = the same loops accumulating in float, which bench.py times as a second CPU baseline."""
+    global _lib, _kind
+    assert kind in ("f64", "f32acc")
+    _kind = kind
+    _lib = _libs.get(kind)
 
 
 def lib():
     global _lib
     if _lib is None:
         path = _build.build(force=False)
+        if _kind == "f32acc":
+            path = _build.LIB_F32ACC
         L = C.CDLL(path)
         i64, vp, dp = C.c_int64, C.c_void_p, C.POINTER(C.c_double)
         L.ms_oracle_threads.restype = C.c_int
@@ -50,12 +63,20 @@ def lib():
         L.ms_oracle_split_walk.argtypes = [C.c_int, vp, vp, i64]
         L.ms_oracle_perfect_tiles.restype = i64
         L.ms_oracle_perfect_tiles.argtypes = [i64, C.c_int, vp, i64]
+        L.ms_oracle_set_threads.restype = None
+        L.ms_oracle_set_threads.argtypes = [C.c_int]
         _lib = L
+        _libs[_kind] = L
     return _lib
 
 
 def threads():
     return int(lib().ms_oracle_threads())
+
+
+def set_threads(n):
+    """OpenMP threads of the following oracle calls (0 = the default); for the benchmark's single-thread baseline."""
+    lib().ms_oracle_set_threads(int(n))
 
 
 def _dtype_code(a, bf16=False):

@@ -55,6 +55,11 @@ class ms_slot(C.Structure):
                 ("extent_by_choice", C.c_int64 * MAX_CANDS)]
 
 
+class ms_module_info(C.Structure):
+    _fields_ = [("name", C.c_char * 32), ("primitives", C.c_char * 96), ("location", C.c_int32), ("flag", C.c_uint32),
+                ("requires", C.c_uint32), ("reserved", C.c_int32)]
+
+
 class ms_space(C.Structure):
     _fields_ = [("family", C.c_int32), ("flags", C.c_uint32), ("n_slots", C.c_int32), ("reserved", C.c_int32),
                 ("slots", ms_slot * MAX_SLOTS)]
@@ -150,6 +155,10 @@ SYMBOLS = {
     "ms_op_loops": (C.c_int32, [C.c_void_p, _P(ms_loop), _P(C.c_int32)]),
     "ms_op_work": (C.c_int32, [C.c_void_p, _P(C.c_double), _P(C.c_double)]),
     "ms_op_tensor_bytes": (C.c_int32, [C.c_void_p, C.c_int32, _P(C.c_int64)]),
+    "ms_module_count": (C.c_int32, []),
+    "ms_module_get": (C.c_int32, [C.c_int32, _P(ms_module_info)]),
+    "ms_space_compose": (C.c_int32, [C.c_void_p, _P(C.c_int32), C.c_int32, _P(C.c_uint32), _P(ms_space)]),
+    "ms_space_stochastic_compose": (C.c_int32, [C.c_void_p, _P(C.c_int32), C.c_int32, C.c_uint64, _P(C.c_int32), _P(C.c_int32), _P(ms_space)]),
     "ms_space_describe": (C.c_int32, [C.c_void_p, C.c_uint32, _P(ms_space)]),
     "ms_space_log10_size": (C.c_int32, [_P(ms_space), _P(C.c_double)]),
     "ms_trace_sample": (C.c_int32, [_P(ms_space), C.c_uint64, C.c_uint64, _P(ms_trace)]),
@@ -320,6 +329,45 @@ def softmax_op(B, M, N, in_dtype="f32", out_dtype=None):
 def norm_op(B, M, N, in_dtype="f32"):
     """2-norm of each batch entry of X [B, M, N]; fp32 [B]."""
     return Op(OP_NORM, in_dtype, "f32", [B, M, N])
+
+
+MAX_MODULES = 16
+
+
+def modules():
+    """The module table: list of dicts {index, name, primitives, location, flag, requires}."""
+    out = []
+    for i in range(lib().ms_module_count()):
+        m = ms_module_info()
+        _check(lib().ms_module_get(i, C.byref(m)))
+        out.append({"index": i, "name": m.name.decode(), "primitives": m.primitives.decode(), "location": m.location,
+                    "flag": m.flag, "requires": m.requires})
+    return out
+
+
+def module_indices(names):
+    table = {m["name"]: m["index"] for m in modules()}
+    return [table[n] if isinstance(n, str) else int(n) for n in names]
+
+
+def space_compose(op, names_or_indices):
+    """Compose(modules, e0): the space of an ordered module list; returns (space, applied mask)."""
+    idx = module_indices(names_or_indices)
+    arr = (C.c_int32 * len(idx))(*idx)
+    sp, mask = ms_space(), C.c_uint32()
+    _check(lib().ms_space_compose(op.handle, arr, len(idx), C.byref(mask), C.byref(sp)))
+    return sp, mask.value
+
+
+def space_stochastic_compose(op, names_or_indices, seed):
+    """Stochastic-Compose over a module set; returns (space, names of the modules in the order they were applied)."""
+    idx = module_indices(names_or_indices)
+    arr = (C.c_int32 * max(1, len(idx)))(*idx)
+    applied, n = (C.c_int32 * MAX_MODULES)(), C.c_int32()
+    sp = ms_space()
+    _check(lib().ms_space_stochastic_compose(op.handle, arr, len(idx), seed, applied, C.byref(n), C.byref(sp)))
+    names = {m["index"]: m["name"] for m in modules()}
+    return sp, [names[applied[i]] for i in range(n.value)]
 
 
 def space_log10_size(space):

@@ -655,6 +655,135 @@ extern "C" int32_t ms_space_describe(const ms_op *op, uint32_t flags, ms_space *
     return MS_OK;
 }
 
+// ---------------------------------------------------------------- modules as data (Section 3.2)
+
+namespace {
+struct Module {
+    const char *name;
+    const char *primitives;
+    int32_t location;
+    uint32_t flag, requires_;
+};
+// canonical order = the order in which ms_space_describe lays out the slots the modules contribute
+const Module kModules[] = {
+    {"multi-level-tiling", "sample-perfect-tile, split, reorder, bind (4 factors per loop)", MS_LOC_BLOCK, 0u, 0u},
+    {"use-mfma", "sample-categorical, blockize, tensorize (matrix-core intrinsic; tiles counted in its units)", MS_LOC_BLOCK, MS_SPACE_TENSORIZE, 0u},
+    {"use-mfma-f32", "sample-categorical, blockize, tensorize (fp32 matrix-core intrinsics, opt-in)", MS_LOC_BLOCK, MS_SPACE_TENSORIZE_F32, 0u},
+    {"unroll", "sample-categorical, unroll (budget 0, 16, 64)", MS_LOC_BLOCK, MS_SPACE_UNROLL, 0u},
+    {"rfactor", "sample-categorical, rfactor (k0 across workgroups, workspace)", MS_LOC_BLOCK, MS_SPACE_RFACTOR, MS_SPACE_TENSORIZE},
+    {"cache-read", "sample-categorical, cache-read, set-scope, compute-at (staging scheme of the operands)", MS_LOC_READS, MS_SPACE_CACHE_READ, 0u},
+    {"vectorize", "sample-categorical, vectorize (global load width per operand)", MS_LOC_READS, MS_SPACE_VECTORIZE, 0u},
+    {"compute-location", "sample-compute-location, compute-at (loop that holds the cache-read of the activations)", MS_LOC_READS, MS_SPACE_COMPUTE_AT, MS_SPACE_TENSORIZE},
+    {"filter-row-layout", "transform-layout (reduction as filter rows, opt-in)", MS_LOC_READS, MS_SPACE_TAP_ROWS, MS_SPACE_TENSORIZE},
+    {"storage-align", "sample-categorical, storage-align (padding / swizzle of the LDS planes)", MS_LOC_LDS, MS_SPACE_STORAGE_ALIGN, 0u},
+    {"cache-write", "sample-categorical, cache-write, reverse-compute-at (result tile staged in LDS)", MS_LOC_WRITE, MS_SPACE_CACHE_WRITE, MS_SPACE_TENSORIZE},
+    {"reorder-grid", "sample-categorical, reorder, bind (workgroup loop order, XCD grouping, persistent loop)", MS_LOC_LAUNCH, MS_SPACE_REORDER, 0u},
+};
+constexpr int kNumModules = (int)(sizeof kModules / sizeof kModules[0]);
+static_assert(kNumModules <= MS_MAX_MODULES, "module table fits the public limit");
+
+// does the module change the space of this operator, given what has been applied?  (ms_space_describe drops the bits
+// that do not apply; a bit that survives it took effect)
+bool module_takes_effect(const ms_op *op, uint32_t before, const Module &m)
+{
+    if (!m.flag) return true;
+    ms_space sp;
+    if (ms_space_describe(op, before | m.flag, &sp) != MS_OK) return false;
+    return (sp.flags & m.flag) != 0;
+}
+} // namespace
+
+extern "C" int32_t ms_module_count(void) { return kNumModules; }
+
+extern "C" int32_t ms_module_get(int32_t index, ms_module_info *out)
+{
+    if (!out || index < 0 || index >= kNumModules) return fail(MS_ERR_BAD_ARG, "ms_module_get: no module %d", index);
+    memset(out, 0, sizeof *out);
+    snprintf(out->name, sizeof out->name, "%s", kModules[index].name);
+    snprintf(out->primitives, sizeof out->primitives, "%s", kModules[index].primitives);
+    out->location = kModules[index].location;
+    out->flag = kModules[index].flag;
+    out->requires = kModules[index].requires_;
+    return MS_OK;
+}
+
+extern "C" int32_t ms_space_compose(const ms_op *op, const int32_t *modules, int32_t n, uint32_t *applied_mask, ms_space *out)
+{
+    if (!op || !modules || !out || n < 1 || n > MS_MAX_MODULES) return fail(MS_ERR_BAD_ARG, "ms_space_compose: bad argument");
+    if (modules[0] != 0) return fail(MS_ERR_BAD_ARG, "ms_space_compose: the list must start with %s: every kernel family is built on it", kModules[0].name);
+    uint32_t mask = 0, listed = 0;
+    for (int i = 0; i < n; ++i) {
+        if (modules[i] < 0 || modules[i] >= kNumModules) return fail(MS_ERR_BAD_ARG, "ms_space_compose: no module %d", modules[i]);
+        const Module &m = kModules[modules[i]];
+        if (i > 0 && modules[i] == 0) return fail(MS_ERR_BAD_ARG, "ms_space_compose: %s listed twice", m.name);
+        if (m.flag && (listed & m.flag)) return fail(MS_ERR_BAD_ARG, "ms_space_compose: %s listed twice", m.name);
+        if ((m.requires_ & listed) != m.requires_) {
+            for (int j = 0; j < kNumModules; ++j)
+                if (kModules[j].flag & m.requires_ & ~listed)
+                    return fail(MS_ERR_BAD_ARG, "ms_space_compose: %s needs %s earlier in the list", m.name, kModules[j].name);
+        }
+        listed |= m.flag;
+        if (module_takes_effect(op, mask, m)) mask |= m.flag;
+    }
+    int32_t rc = ms_space_describe(op, mask, out);
+    if (rc != MS_OK) return rc;
+    if (applied_mask) *applied_mask = out->flags;
+    return MS_OK;
+}
+
+extern "C" int32_t ms_space_stochastic_compose(const ms_op *op, const int32_t *module_set, int32_t n, uint64_t seed, int32_t *applied,
+                                               int32_t *n_applied, ms_space *out)
+{
+    if (!op || !module_set || !applied || !n_applied || !out || n < 0 || n > MS_MAX_MODULES)
+        return fail(MS_ERR_BAD_ARG, "ms_space_stochastic_compose: bad argument");
+    bool in_set[MS_MAX_MODULES] = {false}, done[MS_MAX_MODULES] = {false};
+    for (int i = 0; i < n; ++i) {
+        if (module_set[i] < 0 || module_set[i] >= kNumModules) return fail(MS_ERR_BAD_ARG, "ms_space_stochastic_compose: no module %d", module_set[i]);
+        in_set[module_set[i]] = true;
+    }
+    Rng rng(mix64(seed ^ 0x53C0A705E5ull));
+    int na = 0;
+    uint32_t mask = 0;
+    // the program starts as the untiled block; tiling it creates the other locations
+    applied[na++] = 0;
+    done[0] = true;
+    {
+        // operators without a vector-ALU kernel family (convolutions, 8-bit float inputs) exist on the matrix cores
+        // only: for them the hardware-specific module is part of the base, provided the set offers it
+        ms_space probe;
+        if (ms_space_describe(op, 0, &probe) != MS_OK) {
+            if (!in_set[1] || ms_space_describe(op, kModules[1].flag, &probe) != MS_OK)
+                return fail(MS_ERR_UNSUPPORTED, "ms_space_stochastic_compose: the operator needs %s, which the module set lacks or which does not apply", kModules[1].name);
+            applied[na++] = 1;
+            done[1] = true;
+            mask |= kModules[1].flag;
+        }
+    }
+    int queue[8] = {MS_LOC_BLOCK, MS_LOC_READS, MS_LOC_LDS, MS_LOC_WRITE, MS_LOC_LAUNCH}, nq = 5, head = 0;
+    while (head < nq) { // while locations are not exhausted
+        const int loc = queue[head]; // next-location(program)
+        int cand[MS_MAX_MODULES], nc = 0;
+        for (int j = 1; j < kNumModules; ++j) {
+            const Module &m = kModules[j];
+            if (!in_set[j] || done[j] || m.location != loc) continue;
+            if ((m.requires_ & mask) != m.requires_) continue;
+            if (!module_takes_effect(op, mask, m)) continue;
+            cand[nc++] = j;
+        }
+        const int pick = (int)rng.below((uint64_t)nc + 1); // m ~ Sample(modules); outcome nc = identity
+        if (pick == nc) {
+            ++head; // the location is retired
+            continue;
+        }
+        const int j = cand[pick];
+        applied[na++] = j; // program <- m(location, program); the changed location stays at the head of the list
+        done[j] = true;
+        mask |= kModules[j].flag;
+    }
+    *n_applied = na;
+    return ms_space_compose(op, applied, na, nullptr, out);
+}
+
 // number of ordered n-tuples with product e: prod over primes C(a+n-1, n-1)
 static double log10_tiles(int64_t e, int n)
 {

@@ -643,3 +643,87 @@ def test_interpreter_visits_every_reduction_position_once(mk):
         assert cov.min() == 1 and cov.max() == 1, t.decisions()
         total = int(np.prod(K))
         assert total <= len(cov) < total + max(1, p.tile_unit[2])  # a convolution may pad K up to the intrinsic's k
+
+
+# ---------------------------------------------------------------- modules as data, Compose, Stochastic-Compose (Section 3.2)
+
+def test_module_table_and_compose():
+    mods = B.modules()
+    names = [m["name"] for m in mods]
+    assert names[0] == "multi-level-tiling" and mods[0]["flag"] == 0
+    assert {"use-mfma", "cache-read", "vectorize", "unroll", "storage-align", "reorder-grid", "cache-write", "compute-location",
+            "rfactor"} <= set(names)
+    flags = [m["flag"] for m in mods[1:]]
+    assert len(set(flags)) == len(flags) and all(f and not (f & (f - 1)) for f in flags)   # one bit each
+    by_flag = {m["flag"]: m for m in mods}
+    for m in mods:                                                                         # requirements name real modules
+        r = m["requires"]
+        while r:
+            bit = r & -r
+            assert bit in by_flag
+            r ^= bit
+    op = B.gemm_op(256, 256, 256, "f16")
+    default = ["multi-level-tiling", "use-mfma", "cache-read", "vectorize", "unroll", "storage-align", "reorder-grid", "cache-write"]
+    sp, mask = B.space_compose(op, default)
+    assert mask == 0x7F and bytes(sp) == bytes(op.space())          # compute-location does not apply to a matrix product
+    # the order of the list does not change the space (slot order is canonical), as long as requirements come first
+    sp2, _ = B.space_compose(op, ["multi-level-tiling", "unroll", "use-mfma", "cache-write", "reorder-grid", "storage-align", "vectorize", "cache-read"])
+    assert bytes(sp2) == bytes(sp)
+    # every prefix of a list is a space of its own: the space grows module by module
+    sizes = []
+    for n in range(1, len(default) + 1):
+        spn, maskn = B.space_compose(op, default[:n])
+        sizes.append(B.space_log10_size(spn))
+        assert spn.n_slots >= 3
+    assert all(b >= a for a, b in zip(sizes[1:], sizes[2:]))        # (the matrix-core module changes the tile units, so [0] -> [1] may shrink)
+    with pytest.raises(B.MsError, match="must start with multi-level-tiling"):
+        B.space_compose(op, ["use-mfma"])
+    with pytest.raises(B.MsError, match="cache-write needs use-mfma"):
+        B.space_compose(op, ["multi-level-tiling", "cache-write", "use-mfma"])
+    with pytest.raises(B.MsError, match="listed twice"):
+        B.space_compose(op, ["multi-level-tiling", "unroll", "unroll"])
+    # a module that does not apply to the operator is the identity
+    dw = B.dwconv2d_op(1, 28, 28, 16)
+    spd, maskd = B.space_compose(dw, default)
+    assert bytes(spd) == bytes(dw.space()) and not (maskd & B.SPACE_TENSORIZE)
+    conv = B.conv2d_op(1, 28, 28, 16, 32, 3, 3, stride=1, pad=1)
+    spc, maskc = B.space_compose(conv, default + ["compute-location"])
+    assert maskc == 0xFF and bytes(spc) == bytes(conv.space())
+
+
+def test_stochastic_compose_is_seeded_and_respects_requirements():
+    mods = B.modules()
+    req = {m["name"]: m["requires"] for m in mods}
+    flag = {m["name"]: m["flag"] for m in mods}
+    op = B.conv2d_op(1, 28, 28, 16, 32, 3, 3, stride=1, pad=1)
+    every = [m["name"] for m in mods]
+    seen_masks, count = set(), {n: 0 for n in every}
+    N = 300
+    for seed in range(N):
+        sp, applied = B.space_stochastic_compose(op, every, seed)
+        again_sp, again = B.space_stochastic_compose(op, every, seed)
+        assert applied == again and bytes(sp) == bytes(again_sp)
+        assert applied[0] == "multi-level-tiling" and len(set(applied)) == len(applied)
+        have = 0
+        for n in applied:
+            assert (req[n] & have) == req[n], (applied, n)          # requirements were applied earlier
+            have |= flag[n]
+            count[n] += 1
+        assert sp.flags == have
+        seen_masks.add(sp.flags)
+        # the composed space is a working space: a valid trace can be drawn unless the conv has no vector kernel family
+        if sp.flags & B.SPACE_TENSORIZE:
+            B.trace_sample_valid(op, sp, 1, 0)
+    assert len(seen_masks) > 30
+    # the first draw at a location with c candidates applies each of them with probability 1 / (c + 1)
+    assert count["use-mfma"] == N and count["use-mfma-f32"] == 0 and 0.2 * N < count["compute-location"] < 0.8 * N
+    gemm = B.gemm_op(128, 128, 128, "f16")               # has a vector-ALU family: the matrix-core module is one of the draws
+    n_mfma = sum("use-mfma" in B.space_stochastic_compose(gemm, every, seed)[1] for seed in range(N))
+    assert 0.3 * N < n_mfma < 0.9 * N
+    with pytest.raises(B.MsError, match="needs use-mfma"):
+        B.space_stochastic_compose(op, ["unroll", "cache-read"], 0)
+    # a restricted module set restricts the space
+    sp, applied = B.space_stochastic_compose(op, ["use-mfma", "unroll"], 4)
+    assert set(applied) <= {"multi-level-tiling", "use-mfma", "unroll"}
+    sp, applied = B.space_stochastic_compose(B.gemm_op(128, 128, 128, "f32"), [], 0)
+    assert applied == ["multi-level-tiling"] and sp.flags == 0

@@ -9,10 +9,10 @@ from paper_2205_13603_amd import binding as B, tuned
 def test_records_parse_in_their_own_space(name):
     mk, instances = tuned.WORKLOADS[name]
     op = mk()
-    recs = tuned.load_records(name)
+    recs = tuned.load_records(name, "filling")
     assert recs, "no stored record for %s" % name
     assert all(a["us"] <= b["us"] for a, b in zip(recs, recs[1:]))      # best first
-    usable = tuned.records_with_traces(name, op, limit=len(recs))
+    usable = tuned.records_with_traces(name, op, limit=len(recs), protocol="filling")
     assert usable, "no record of %s is valid in today's space" % name
     best_rec, space, trace = usable[0]
     assert best_rec is recs[0] or best_rec["us"] <= 1.25 * recs[0]["us"], "the best records of %s no longer parse" % name
