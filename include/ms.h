@@ -450,6 +450,17 @@ int32_t ms_variant_info(const ms_variant *v, ms_variant_params *params, size_t *
  * -D options that specialise it, one per line.  Two parameter sets that give the same text are the same kernel and
  * have the same params.key.  Writes at most cap bytes including the NUL; *needed (may be NULL) = size needed. */
 int32_t ms_variant_kernel_text(const ms_op *op, const ms_variant_params *params, char *buf, size_t cap, size_t *needed);
+/* What the compiled kernel occupies, read from the metadata of its code object (no GPU needed): vector registers per
+ * lane (architectural and accumulation registers: a wavefront is granted their sum), scalar registers, bytes of
+ * scratch memory per lane (non-zero = the compiler spilled registers), vector registers spilled, bytes of LDS. */
+typedef struct ms_variant_resources {
+    int32_t vgprs, agprs, sgprs;
+    int32_t scratch_bytes;
+    int32_t spilled_vgprs;
+    int32_t lds_bytes;
+    int32_t reserved[2];
+} ms_variant_resources;
+int32_t ms_variant_resources_get(const ms_variant *v, ms_variant_resources *out);
 /* Compile the kernels of n traces ahead of use on `threads` host threads
  * (invalid traces are skipped).  *n_built = kernels now in the cache. */
 int32_t ms_prebuild(const ms_op *op, const ms_space *space, const ms_trace *traces, int32_t n,

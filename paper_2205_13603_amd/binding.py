@@ -99,6 +99,11 @@ class ms_variant_params(C.Structure):
         return out
 
 
+class ms_variant_resources(C.Structure):
+    _fields_ = [("vgprs", C.c_int32), ("agprs", C.c_int32), ("sgprs", C.c_int32), ("scratch_bytes", C.c_int32),
+                ("spilled_vgprs", C.c_int32), ("lds_bytes", C.c_int32), ("reserved", C.c_int32 * 2)]
+
+
 class ms_limits(C.Structure):
     _fields_ = [("max_threads", C.c_int32), ("max_lds_bytes", C.c_int32), ("max_acc_per_thread", C.c_int32),
                 ("wave_size", C.c_int32), ("max_waves", C.c_int32), ("reserved", C.c_int32 * 3)]
@@ -173,6 +178,7 @@ SYMBOLS = {
     "ms_variant_destroy": (None, [C.c_void_p]),
     "ms_variant_info": (C.c_int32, [C.c_void_p, _P(ms_variant_params), _P(C.c_size_t)]),
     "ms_variant_kernel_text": (C.c_int32, [C.c_void_p, _P(ms_variant_params), C.c_char_p, C.c_size_t, _P(C.c_size_t)]),
+    "ms_variant_resources_get": (C.c_int32, [C.c_void_p, _P(ms_variant_resources)]),
     "ms_prebuild": (C.c_int32, [C.c_void_p, _P(ms_space), _P(ms_trace), C.c_int32, C.c_int32, _P(C.c_int32)]),
     "ms_set_cache_dir": (C.c_int32, [C.c_char_p]),
     "ms_jit_stats": (C.c_int32, [_P(C.c_int64), _P(C.c_int64), _P(C.c_int64), _P(C.c_int32), _P(C.c_int32)]),
@@ -513,6 +519,12 @@ class Variant:
         ws = C.c_size_t()
         _check(lib().ms_variant_info(self.handle, C.byref(p), C.byref(ws)))
         return p
+
+    def resources(self):
+        """Registers, scratch and LDS of the compiled kernel, from its code object's metadata."""
+        r = ms_variant_resources()
+        _check(lib().ms_variant_resources_get(self.handle, C.byref(r)))
+        return r
 
     def workspace_bytes(self):
         """Bytes of workspace one instance needs (0 unless the reduction is split across workgroups);

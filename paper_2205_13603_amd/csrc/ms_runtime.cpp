@@ -9,6 +9,7 @@
 #include <cstring>
 #include <mutex>
 #include <new>
+#include <string>
 #include <thread>
 #include <vector>
 
@@ -76,6 +77,58 @@ extern "C" int32_t ms_variant_info(const ms_variant *v, ms_variant_params *param
     if (!v) return fail(MS_ERR_BAD_ARG, "ms_variant_info: NULL variant");
     if (params) *params = v->p;
     if (workspace_bytes) *workspace_bytes = workspace_per_instance(v);
+    return MS_OK;
+}
+
+// The code object's metadata is a MessagePack map in an ELF note; each kernel entry holds ".vgpr_count", ".agpr_count",
+// ... as a short string key followed by an unsigned integer.  Reads the value behind the first occurrence of `key`
+// that lies after `from` (the position of the kernel's ".name" entry), -1 if absent.
+static long meta_uint(const std::vector<char> &blob, const char *key, size_t from)
+{
+    const size_t kl = strlen(key);
+    for (size_t i = from; i + kl + 1 < blob.size(); ++i) {
+        if (memcmp(&blob[i], key, kl) != 0) continue;
+        if (i == 0 || (unsigned char)blob[i - 1] != (0xa0u | kl)) continue; // a fixstr of exactly this length
+        const unsigned char *p = (const unsigned char *)&blob[i + kl];
+        const size_t left = blob.size() - (i + kl);
+        if (p[0] <= 0x7f) return p[0];
+        if (p[0] == 0xcc && left >= 2) return p[1];
+        if (p[0] == 0xcd && left >= 3) return (p[1] << 8) | p[2];
+        if (p[0] == 0xce && left >= 5) return ((long)p[1] << 24) | (p[2] << 16) | (p[3] << 8) | p[4];
+        return -1;
+    }
+    return -1;
+}
+
+extern "C" int32_t ms_variant_resources_get(const ms_variant *v, ms_variant_resources *out)
+{
+    if (!v || !out) return fail(MS_ERR_BAD_ARG, "ms_variant_resources_get: NULL argument");
+    memset(out, 0, sizeof *out);
+    const std::vector<char> &blob = *v->code;
+    // the entry of the main kernel: its symbol is "<entry>.kd"
+    const std::string sym = v->spec.entry + ".kd";
+    size_t at = std::string::npos;
+    for (size_t i = 0; i + sym.size() <= blob.size(); ++i)
+        if (memcmp(&blob[i], sym.data(), sym.size()) == 0 && i > 0 && (unsigned char)blob[i - 1] == (0xa0u | sym.size())) {
+            at = i;
+            break;
+        }
+    if (at == std::string::npos) return fail(MS_ERR_UNSUPPORTED, "ms_variant_resources_get: no metadata entry for %s", sym.c_str());
+    // the keys of one kernel's map are sorted, so those before ".symbol" precede it in the blob: scan from the start of
+    // this kernel's map, which begins at the last ".agpr_count" (its first key) before the symbol
+    size_t start = 0;
+    for (size_t i = 0; i + 11 < at; ++i)
+        if (memcmp(&blob[i], ".agpr_count", 11) == 0) start = i > 0 ? i - 1 : 0;
+    const long vg = meta_uint(blob, ".vgpr_count", start), ag = meta_uint(blob, ".agpr_count", start), sg = meta_uint(blob, ".sgpr_count", start);
+    const long sc = meta_uint(blob, ".private_segment_fixed_size", start), sp = meta_uint(blob, ".vgpr_spill_count", start);
+    const long ld = meta_uint(blob, ".group_segment_fixed_size", start);
+    if (vg < 0 || sg < 0) return fail(MS_ERR_UNSUPPORTED, "ms_variant_resources_get: register counts not found in the code object");
+    out->vgprs = (int32_t)vg;
+    out->agprs = (int32_t)(ag < 0 ? 0 : ag);
+    out->sgprs = (int32_t)sg;
+    out->scratch_bytes = (int32_t)(sc < 0 ? 0 : sc);
+    out->spilled_vgprs = (int32_t)(sp < 0 ? 0 : sp);
+    out->lds_bytes = (int32_t)(ld < 0 ? 0 : ld);
     return MS_OK;
 }
 

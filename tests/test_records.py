@@ -22,3 +22,20 @@ def test_records_parse_in_their_own_space(name):
     again = B.trace_from_text(space, B.trace_to_text(op, space, trace))
     assert bytes(again) == bytes(trace)
     assert instances >= 1
+
+
+@pytest.mark.parametrize("name", ["c1_gemm_f32_128", "c2_gemm_f16_1024", "c3_conv_f16_56x56x64", "c4a_bmm_nt_f16", "c4b_bmm_nn_f16",
+                                  "c4c_gemm_i8_512", "c5a_dw_f32_112x112x32", "c5b_dw_f32_56x56x144"])
+def test_best_records_compile_without_spills_and_with_the_lds_the_validator_counted(name):
+    """What the compiler made of the record the benchmark times (from the code object's metadata, no GPU): no scratch
+    memory, registers within what the workgroup's wavefronts can share, and exactly the LDS bytes the validator
+    charged the trace with."""
+    mk, _ = tuned.WORKLOADS[name]
+    op = mk()
+    rec, space, trace = tuned.records_with_traces(name, op, limit=1, protocol="filling")[0]
+    v = B.Variant(op, space, trace)
+    p, r = v.params(), v.resources()
+    assert r.scratch_bytes == 0 and r.spilled_vgprs == 0, "the best record of %s spills %d registers" % (name, r.spilled_vgprs)
+    assert r.lds_bytes == p.lds_bytes
+    waves_per_simd = (p.waves + 3) // 4
+    assert 0 < r.vgprs + r.agprs <= 512 // waves_per_simd
