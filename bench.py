@@ -35,7 +35,7 @@ PEAK_HBM_GBS = 8000.0
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=200)
+    ap.add_argument("--steps", type=int, default=1000)
     ap.add_argument("--warmup", type=int, default=20)
     ap.add_argument("--settle-ms", type=float, default=100.0,
                     help="untimed launches of the chosen variant for this long before the warm-up steps: after the host-side "
@@ -48,6 +48,7 @@ def main():
     ap.add_argument("--record-index", type=int, default=-1,
                     help="consider only this stored record (0 = the best stored latency): fixes the variant, e.g. for counter runs")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-steady", action="store_true", help="skip the steady-state block (profiling runs: only the timed variant's launches remain)")
     ap.add_argument("--trace-file", default="", help="time exactly this trace (text form) instead of searching")
     args = ap.parse_args()
     if args.gpus != 1:
@@ -83,6 +84,28 @@ def main():
     full_set = [(in_ptrs, dev_out.data_ptr())]
     # one buffer set per instance, for the single-instance protocols (rotating over > last-level-cache bytes)
     inst_sets = [([t[r].data_ptr() for t in dev_in], dev_out[r].data_ptr()) for r in range(R)]
+
+    # ---- the oracle's result for the distinct inputs (and, from the same calls, the CPU baseline)
+    t_or = time.time()
+    refs = [oracle_run(name, b) for b in base]
+    oracle_runs = len(base)
+    if not args.no_cpu_baseline:
+        # the CPU baseline is the oracle as it stands: keep timing whole instances until about 10 s of CPU work are
+        # sampled (at most 64 more runs; cheap operators finish far earlier and are then timed on all of those runs)
+        while time.time() - t_or < 10.0 and oracle_runs < len(base) + 64:
+            oracle_run(name, base[oracle_runs % len(base)])
+            oracle_runs += 1
+    oracle_seconds = (time.time() - t_or) / oracle_runs
+    rtol = compare.RTOL_F32 if odt == "f32" and BOUND[name][1] == "f32" else compare.RTOL_HALF
+
+    def check(got, rows, what):
+        """got[r] against the oracle for the instances `rows` (instance r holds input set r mod len(base))"""
+        for r in rows:
+            ref = np.asarray(refs[r % len(base)]).reshape(shape)
+            if odt == "i32":
+                compare.assert_int_equal(got[r], ref, "%s instance %d" % (what, r))
+            else:
+                compare.assert_float_close(got[r], ref, rtol, "%s instance %d" % (what, r))
 
     # ---- candidates: stored records + fresh search, all measured now in the timed configuration
     t_search0 = time.time()
@@ -136,9 +159,31 @@ def main():
             cfg.seed, cfg.trials = args.seed, args.trials
             cfg.init_population = min(cfg.init_population, max(1, args.trials // 2))
             cfg.measure = B.ms_measure_cfg(**mcfg)
-            res = B.search(op, space, cfg, bufsets=full_set, stream=stream)
+            # a search ranks on latency alone: every candidate it measures is also run on the first instances and compared
+            # with the oracle (the kernel is in the library's cache by then), and a mismatch ends the benchmark
+            n_chk = min(R, len(base))
+            chk = devmem.empty_output(shape, odt, n_chk, poison=True)
+            wrong = []
+
+            def on_trial(t):
+                if t.status != 0:
+                    return 0
+                try:
+                    vt = B.Variant(op, space, t.trace.copy())
+                    chk.fill_({"bf16": 0x7FC0, "i32": -123456789}.get(odt, float("nan")))
+                    vt.launch(in_ptrs, chk.data_ptr(), instances=n_chk, stream=stream)
+                    check(devmem.to_host(chk, odt).reshape((n_chk,) + tuple(shape)), range(n_chk), "search trial %d" % t.index)
+                except Exception as e:  # must not unwind through the C callback
+                    wrong.append(repr(e)[:500])
+                    return 1
+                return 0
+
+            res = B.search(op, space, cfg, bufsets=full_set, stream=stream, on_trial=on_trial)
+            if wrong:
+                print("bench.py: a candidate of the search does not match the oracle: %s" % wrong[0], file=sys.stderr)
+                return 1
             search_info = {"trials": res.n_measured, "trials_to_best": res.best_trial, "invalid": res.n_invalid,
-                           "failed": res.n_failed, "duplicate": res.n_duplicate}
+                           "failed": res.n_failed, "duplicate": res.n_duplicate, "checked_against_oracle": res.n_measured}
             if res.best_us < best[1]:
                 best = (res.best_trace, res.best_us, "search", space)
     if best[0] is None:
@@ -153,23 +198,7 @@ def main():
     dev_out.fill_({"bf16": 0x7FC0, "i32": -123456789}.get(odt, float("nan")))
     v.launch(in_ptrs, dev_out.data_ptr(), instances=R, stream=stream)
     got = devmem.to_host(dev_out, odt)
-    t_or = time.time()
-    refs = [oracle_run(name, b) for b in base]
-    oracle_runs = len(base)
-    if not args.no_cpu_baseline:
-        # the CPU baseline is the oracle as it stands: keep timing whole instances until about 10 s of CPU work are
-        # sampled (at most 64 more runs; cheap operators finish far earlier and are then timed on all of those runs)
-        while time.time() - t_or < 10.0 and oracle_runs < len(base) + 64:
-            oracle_run(name, base[oracle_runs % len(base)])
-            oracle_runs += 1
-    oracle_seconds = (time.time() - t_or) / oracle_runs
-    for r in sorted({0, 1 % R, R // 2, R - 1}):
-        ref = refs[r % len(base)]
-        if odt == "i32":
-            compare.assert_int_equal(got[r], ref, "instance %d" % r)
-        else:
-            compare.assert_float_close(got[r], ref, compare.RTOL_F32 if odt == "f32" and BOUND[name][1] == "f32" else compare.RTOL_HALF,
-                                       "instance %d" % r)
+    check(got, sorted({0, 1 % R, R // 2, R - 1}), "timed variant")
 
     # ---- timed region: clock settling, W warm-up steps, then exactly K steps between synchronisations
     settle_launches = settle(v, args.settle_ms)
@@ -216,11 +245,11 @@ def main():
     # partial sums go to a workspace) and the device-filling variant; all measured now, the fastest is reported
     ws = torch.empty(8 * dev_out[0].numel() * 4, dtype=torch.uint8, device="cuda")
     steady_sets = [(ins, out, ws.data_ptr()) for ins, out in inst_sets]
-    lpr = max(200, R)
-    steady = {"us": v.measure(steady_sets, warmup=20, repeats=5, launches_per_repeat=lpr, instances=1, stream=stream).median_us,
+    lpr = max(200, R) if not args.no_steady else 2
+    steady = {"us": v.measure(steady_sets, warmup=20 if not args.no_steady else 0, repeats=5 if not args.no_steady else 1, launches_per_repeat=lpr, instances=1, stream=stream).median_us,
               "variant_from": "the device-filling variant", "rfactor": 1, "record_search": None}
     filling_variant_steady_us = steady["us"]
-    if not args.no_records and not args.trace_file:
+    if not args.no_records and not args.trace_file and not args.no_steady:
         for rec, sp, t in tuned.records_with_traces(name, op, limit=4, protocol="steady"):
             try:
                 vs = B.Variant(op, sp, t)
@@ -279,6 +308,9 @@ def main():
                      "attainable": attainable, "frac_of_attainable": (achieved / attainable) if attainable else None,
                      "attainable_kind": {"mfma": "register-resident loop of the variant's intrinsic on this workload's operand values",
                                          "hbm": "1 GiB copy kernel (the faster of two launch shapes), bytes read + written"}.get(bound) if attainable else None},
+        # vector-ALU kernels here issue one fp32 FMA per lane and clock (the packed two-FMA forms are compiled out):
+        # 256 CUs x 64 lanes x 2 flop x 2.4 GHz = 78.6 TFLOP/s is what such code can reach; the published 157.3 counts the packed form
+        "alu_unpacked": ({"peak": PEAK_FP32_VECTOR / 2, "frac": achieved / (PEAK_FP32_VECTOR / 2)} if bound == "alu" else None),
         "steady_state": {"protocol": "back-to-back launches of ONE instance, %d per repeat, rotating over %d buffer sets (%.0f MB, beyond the last-level cache)"
                                      % (lpr, R, bytes1 * R / 1e6),
                          "us_per_launch": steady["us"], "value": per1 / (steady["us"] * 1e-6), "unit": unit,
