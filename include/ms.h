@@ -51,7 +51,7 @@
 extern "C" {
 #endif
 
-#define MS_ABI_VERSION 2
+#define MS_ABI_VERSION 3
 
 typedef enum ms_status {
     MS_OK = 0,
@@ -179,7 +179,11 @@ typedef enum ms_slot_id {
                               LDS area of its own */
     MS_SLOT_VECTORIZE = 7, /* categorical: elements per global load instruction of operand A (conv: X) */
     MS_SLOT_STORAGE_ALIGN = 8, /* categorical: LDS layout: 0 = dense, 1 = each row / plane padded by 16 bytes,
-                              2 (matrix-core kernels) = padded, and the 16-byte slots of a plane XOR-swizzled */
+                              2 (matrix-core kernels) = padded, and the 16-byte slots of a plane XOR-swizzled,
+                              3 (matrix-core GEMMs whose B is contiguous along j, 1- and 2-byte inputs, register staging,
+                              B loaded in 16-byte vectors) = A as with 2, B kept in LDS as in global memory (row-major
+                              k-rows, 16-column granules XOR-swizzled with the row) and read with the transposing LDS
+                              loads instead of being transposed in registers (Table 2, transform-layout) */
     MS_SLOT_REORDER = 9,   /* categorical: order of the grid loops, 0 = i outer, 1 = j outer,
                               2 = i outer with workgroups grouped per XCD, 3 (with cache_read 5..7) = as 2 with
                               persistent workgroups that loop over tiles */
@@ -574,7 +578,20 @@ typedef struct ms_search_cfg {
     ms_measure_cfg measure;
     int32_t cost_model;       /* 0 = every proposal is measured; 1 = a learned cost model picks which proposals to measure */
     int32_t model_candidates; /* with the cost model: proposals scored per measured candidate (e.g. 8) */
-    int32_t model_min_trials; /* measurements needed before the model is used (earlier generations run as without it) */
+    int32_t model_min_trials; /* measurements needed before the model is used (earlier generations run as without it);
+                               * pre-training rows count as measurements */
+    int32_t pretrain_n;       /* rows of pretrain_X / pretrain_y, 0 = none */
+    /* Pre-training of the cost model (Section 4, "End-to-end search": the model is updated during the search and
+     * may be pre-trained): host arrays, read during the call only, of feature vectors (row-major, pretrain_n x
+     * pretrain_d, as ms_variant_features writes them for this operator) and targets (log2 of the latency in
+     * microseconds) of earlier measurements of the same operator under the same measurement protocol, e.g. the log
+     * of an earlier search.  Every fit sees these rows followed by this search's own measurements.  With enough
+     * rows (>= model_min_trials) the model also picks the initial population: model_candidates x init_population
+     * valid samples are drawn, half of the slots go to the best predicted ones and half to samples in the order
+     * drawn.  Ignored without cost_model. */
+    const double *pretrain_X;
+    const double *pretrain_y;
+    int32_t pretrain_d;
     int32_t reserved;
 } ms_search_cfg;
 void ms_search_cfg_default(ms_search_cfg *cfg);

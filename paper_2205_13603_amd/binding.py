@@ -127,7 +127,9 @@ class ms_search_cfg(C.Structure):
     _fields_ = [("seed", C.c_uint64), ("trials", C.c_int32), ("init_population", C.c_int32), ("population", C.c_int32),
                 ("children", C.c_int32), ("eps_permille", C.c_int32), ("compile_threads", C.c_int32),
                 ("temperature0", C.c_double), ("temperature1", C.c_double), ("measure", ms_measure_cfg),
-                ("cost_model", C.c_int32), ("model_candidates", C.c_int32), ("model_min_trials", C.c_int32), ("reserved", C.c_int32)]
+                ("cost_model", C.c_int32), ("model_candidates", C.c_int32), ("model_min_trials", C.c_int32), ("pretrain_n", C.c_int32),
+                ("pretrain_X", C.POINTER(C.c_double)), ("pretrain_y", C.POINTER(C.c_double)), ("pretrain_d", C.c_int32),
+                ("reserved", C.c_int32)]
 
 
 class ms_trial(C.Structure):
@@ -440,6 +442,22 @@ def make_trace(space, values):
     return t
 
 
+def trace_from_decisions(space, decisions):
+    """Inverse of ms_trace.decisions(): [(slot_id, [raw values])] in the space's slot order -> trace."""
+    if len(decisions) != space.n_slots:
+        raise ValueError("%d decisions for a space of %d slots" % (len(decisions), space.n_slots))
+    t = ms_trace()
+    t.n = space.n_slots
+    for i, (slot_id, vals) in enumerate(decisions):
+        s = space.slots[i]
+        if s.slot_id != slot_id:
+            raise ValueError("decision %d is for slot %d, the space has slot %d there" % (i, slot_id, s.slot_id))
+        t.d[i].slot_id, t.d[i].kind, t.d[i].n = s.slot_id, s.kind, len(vals)
+        for k, v in enumerate(vals):
+            t.d[i].v[k] = v
+    return t
+
+
 def get_limits():
     lim = ms_limits()
     _check(lib().ms_get_limits(C.byref(lim)))
@@ -639,11 +657,26 @@ def search_cfg_default():
     return cfg
 
 
-def search(op, space, cfg, bufsets=(), stream=None, fake_latency=None, on_trial=None):
+def search(op, space, cfg, bufsets=(), stream=None, fake_latency=None, on_trial=None, pretrain=None):
+    """pretrain = (X, y): rows for cfg.pretrain_X / pretrain_y (features as variant_features gives them, log2 microseconds)."""
     arr = _bufsets(bufsets)
+    if pretrain is not None:
+        import numpy as np
+        X = np.ascontiguousarray(pretrain[0], dtype=np.float64)
+        y = np.ascontiguousarray(pretrain[1], dtype=np.float64)
+        if X.ndim != 2 or y.shape != (X.shape[0],):
+            raise ValueError("pretrain: X must be n x d and y of length n")
+        cfg.pretrain_n, cfg.pretrain_d = X.shape
+        cfg.pretrain_X = X.ctypes.data_as(C.POINTER(C.c_double))
+        cfg.pretrain_y = y.ctypes.data_as(C.POINTER(C.c_double))
     res = ms_search_result()
     lat = LATENCY_FN(lambda p, u: float(fake_latency(p.contents))) if fake_latency else C.cast(None, LATENCY_FN)
     cb = TRIAL_CB(lambda t, u: int(on_trial(t.contents) or 0)) if on_trial else C.cast(None, TRIAL_CB)
-    _check(lib().ms_search(op.handle, C.byref(space), C.byref(cfg), arr, len(bufsets), stream, lat, None, cb, None,
-                           C.byref(res)))
+    try:
+        _check(lib().ms_search(op.handle, C.byref(space), C.byref(cfg), arr, len(bufsets), stream, lat, None, cb, None,
+                               C.byref(res)))
+    finally:
+        if pretrain is not None:  # the arrays live only as long as this call
+            cfg.pretrain_n = cfg.pretrain_d = 0
+            cfg.pretrain_X = cfg.pretrain_y = None
     return res

@@ -103,6 +103,10 @@
 #endif
 #endif
 
+#define B_KMAJOR (!IS_CONV && SB_K == 1 && SB_J != 1)
+// LDS_PAD 3 (j-contiguous B of a GEMM, register staging): B lies in LDS as in global memory, row-major k-rows of BN
+// elements, and the fragments come out of the transposing LDS loads; A as with LDS_PAD 2
+#define B_ROWMAJOR (!IS_CONV && !B_KMAJOR && LDS_PAD == 3 && CACHE_READ <= 4)
 #define NWAVES (I2 * J2)
 #define LANE_GROUPS (64 / MI_M)
 #define KP (MI_K / LANE_GROUPS)
@@ -132,14 +136,16 @@ constexpr int PLANE_B = LSPLIT * SUBPLANE_B;
 // consecutive rows still touch 8 distinct slots of one aligned group.
 __device__ __forceinline__ int lds_slot(int n)
 {
-#if LDS_PAD == 2
+#if LDS_PAD >= 2
     return n ^ ((n >> 3) & 7);
 #else
     return n;
 #endif
 }
 constexpr int A_STAGE_BYTES = CONV_PATCH ? 0 : KG * PLANE_A; // the per-k-step stage holds A unless X is resident as a patch
-constexpr int STAGE_BYTES = A_STAGE_BYTES + KG * PLANE_B;
+constexpr int B_STAGE_BYTES = B_ROWMAJOR ? BK * BN * ES : KG * PLANE_B;
+constexpr int B_LGRP = B_ROWMAJOR ? 0 : PLANE_B;  // offset of a lane group's fragments inside the B stage
+constexpr int STAGE_BYTES = A_STAGE_BYTES + B_STAGE_BYTES;
 constexpr int STAGES = CACHE_READ >= 2 ? 2 : 1;
 constexpr int KSTEPS = K1 * K2 * K3;              // MFMA k steps per tile
 
@@ -453,8 +459,6 @@ __device__ __forceinline__ void jmajor_store(const jmajor_stage &st, char *__res
     }
 }
 
-#define B_KMAJOR (!IS_CONV && SB_K == 1 && SB_J != 1)
-
 #if CONV_PATCH
 // ---- resident input patch (COMPUTE_AT 1)
 constexpr int P_ROWS_OUT = BM % CV_OW == 0 ? BM / CV_OW : (CV_OW + BM - 2) / CV_OW + 1; // output rows a tile can touch
@@ -598,6 +602,96 @@ struct conv_ctx {
 };
 #endif
 
+// ---- j-contiguous B kept row-major in LDS (direct-to-LDS rings and LDS_PAD 3): k-rows of BN elements, the
+// 16-column granules (what one transposing LDS load covers: 32 bytes of 2-byte, 16 bytes of 1-byte elements) of a row
+// XOR-swizzled with the row number; needs a power-of-two granule count
+constexpr int CE = 16 / ES;                               // elements per 16-byte chunk
+#if !B_KMAJOR
+constexpr int CB = BN / CE;                               // 16-byte chunks per k-row of the j-contiguous B tile
+constexpr int BROW_BYTES = BN * ES;
+constexpr int NGRAN = BN / 16;
+constexpr int GRAN_MASK = (NGRAN & (NGRAN - 1)) ? 0 : (NGRAN > 16 ? 15 : NGRAN - 1);
+// chunk-index XOR for k-row `k`: moves whole 16-column granules (ES chunks each)
+__device__ __forceinline__ int dl_swz_b(int k) { return (k & GRAN_MASK) * ES; }
+#endif
+typedef short tr4_t __attribute__((ext_vector_type(4)));
+typedef int tr2_t __attribute__((ext_vector_type(2)));
+
+#if B_ROWMAJOR
+static_assert((ES == 2 && KP == 8) || (ES == 1 && KP == 16), "row-major B in LDS: 16-byte fragments of 2-byte or 1-byte inputs");
+static_assert(VEC_B == CE, "row-major B in LDS moves 16-byte vectors");
+// a thread moves 16-byte chunks; chunk idx -> (k-row, chunk of the row), chunks of a row on consecutive lanes
+struct rowmajor_stage {
+    static constexpr int TOTAL = BK * CB;
+    static constexpr int ITERS = (TOTAL + NTHREADS - 1) / NTHREADS;
+    vec_t<in_t, CE> r[ITERS];
+};
+
+__device__ __forceinline__ void rowmajor_load(rowmajor_stage &st, const in_t *__restrict__ src, long col0, long k0e, long k_stride, int tid, int u0,
+                                              int u1)
+{
+    typedef rowmajor_stage S;
+#pragma unroll
+    for (int it = 0; it < S::ITERS; ++it) {
+        if (it < u0 || it >= u1) continue;
+        const int idx = it * NTHREADS + tid;
+        if (S::TOTAL % NTHREADS == 0 || idx < S::TOTAL) {
+            if (NTHREADS % CB == 0) {
+                // wave-uniform base + 32-bit per-lane offset
+                const char *ub = (const char *)(src + (k0e + it * (NTHREADS / CB)) * k_stride + col0);
+                const unsigned voff = (unsigned)(((tid / CB) * k_stride + (tid % CB) * CE) * ES);
+                st.r[it] = *reinterpret_cast<const vec_t<in_t, CE> *>(ub + voff);
+            } else {
+                st.r[it] = *reinterpret_cast<const vec_t<in_t, CE> *>(src + (k0e + idx / CB) * k_stride + col0 + (idx % CB) * CE);
+            }
+        }
+    }
+}
+
+__device__ __forceinline__ void rowmajor_store(const rowmajor_stage &st, char *__restrict__ lds, int tid, int u0, int u1)
+{
+    typedef rowmajor_stage S;
+#pragma unroll
+    for (int it = 0; it < S::ITERS; ++it) {
+        if (it < u0 || it >= u1) continue;
+        const int idx = it * NTHREADS + tid;
+        if (S::TOTAL % NTHREADS == 0 || idx < S::TOTAL) {
+            const int k = idx / CB, c = idx % CB;
+            *reinterpret_cast<vec_t<in_t, CE> *>(lds + k * BROW_BYTES + ((c ^ dl_swz_b(k)) * 16)) = st.r[it];
+        }
+    }
+}
+
+// the B fragment of MFMA k step `step` for the 16 x 16 or 32 x 32 tile at tile column `tcol`, from the stage's B
+// region at `b`.  2-byte elements (ds_read_b64_tr_b16): 16 lanes hand in 4 k-rows x 16 columns (lane: k-row li/4,
+// 4 columns from li%4) and every lane receives 4 consecutive k of its own column; two loads = 8 k.  1-byte elements
+// (ds_read_b64_tr_b8): 8 k-rows x 16 columns per 16 lanes (lane: k-row li/2, 8 columns from li%2); two loads = 16 k.
+__device__ __forceinline__ frag_t rowmajor_frag(const char *__restrict__ b, int step, int tcol, int lane)
+{
+    const int lrow = lane % MI_M, lgrp = lane / MI_M, li = lane % 16;
+    const int pn = (tcol * MI_N + lrow) / 16; // 16-column granule of this lane's column
+    frag_t f;
+#if IN_DT != DT_I8 && IN_DT != DT_F8E4M3
+    const int krow = step * MI_K + lgrp * 8 + li / 4;
+    const char *b0 = b + krow * BROW_BYTES + (((pn << 1) ^ dl_swz_b(krow)) * 16) + (li % 4) * 8;
+    const char *b1 = b + (krow + 4) * BROW_BYTES + (((pn << 1) ^ dl_swz_b(krow + 4)) * 16) + (li % 4) * 8;
+    const tr4_t lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) tr4_t *)(b0));
+    const tr4_t hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) tr4_t *)(b1));
+    *reinterpret_cast<tr4_t *>(&f.v[0]) = lo;
+    *reinterpret_cast<tr4_t *>(&f.v[4]) = hi;
+#else
+    const int krow = step * MI_K + lgrp * 16 + li / 2;
+    const char *b0 = b + krow * BROW_BYTES + ((pn ^ dl_swz_b(krow)) * 16) + (li % 2) * 8;
+    const char *b1 = b + (krow + 8) * BROW_BYTES + ((pn ^ dl_swz_b(krow + 8)) * 16) + (li % 2) * 8;
+    const tr2_t lo = __builtin_amdgcn_ds_read_tr8_b64_v2i32((__attribute__((address_space(3))) tr2_t *)(b0));
+    const tr2_t hi = __builtin_amdgcn_ds_read_tr8_b64_v2i32((__attribute__((address_space(3))) tr2_t *)(b1));
+    *reinterpret_cast<tr2_t *>(&f.v[0]) = lo;
+    *reinterpret_cast<tr2_t *>(&f.v[8]) = hi;
+#endif
+    return f;
+}
+#endif
+
 struct tile_stage {
 #if !CONV_PATCH
     kmajor_stage<BM, VEC> a;
@@ -605,6 +699,9 @@ struct tile_stage {
 #if B_KMAJOR
     kmajor_stage<BN, VEC_B> b;
     static constexpr int UNITS_B = kmajor_stage<BN, VEC_B>::ITERS;
+#elif B_ROWMAJOR
+    rowmajor_stage b;
+    static constexpr int UNITS_B = rowmajor_stage::ITERS;
 #else
     jmajor_stage b;
     static constexpr int UNITS_B = jmajor_stage::ITERS * KPL;
@@ -612,7 +709,7 @@ struct tile_stage {
     static constexpr int UNITS_A = CONV_PATCH ? 0 : kmajor_stage<BM, VEC>::ITERS;
     static constexpr int UNITS = UNITS_A + UNITS_B; // global load instructions per thread and tile
     static constexpr int SUNITS_A = UNITS_A;
-    static constexpr int SUNITS = SUNITS_A + (B_KMAJOR ? UNITS_B : UNITS_B / KPL); // store units (one per staged vector / block)
+    static constexpr int SUNITS = SUNITS_A + (B_KMAJOR || B_ROWMAJOR ? UNITS_B : UNITS_B / KPL); // store units (one per staged vector / block)
 };
 
 // issue load units [u0, u1) of the tile of step k0
@@ -625,6 +722,8 @@ __device__ __forceinline__ void stage_load(tile_stage &st, const in_t *__restric
 #endif
 #if B_KMAJOR
     kmajor_load<BN, VEC_B, false>(st.b, B, (long)j0 * BN, k0e, SB_J, tid, u0 - tile_stage::UNITS_A, u1 - tile_stage::UNITS_A);
+#elif B_ROWMAJOR
+    rowmajor_load(st.b, B, (long)j0 * BN, k0e, SB_K, tid, u0 - tile_stage::UNITS_A, u1 - tile_stage::UNITS_A);
 #else
     jmajor_load(st.b, B, (long)j0 * BN, k0e, SB_K, tid, u0 - tile_stage::UNITS_A, u1 - tile_stage::UNITS_A);
 #endif
@@ -638,6 +737,8 @@ __device__ __forceinline__ void stage_store(const tile_stage &st, char *__restri
 #endif
 #if B_KMAJOR
     kmajor_store<BN, VEC_B, SUBPLANE_B>(st.b, lds + A_STAGE_BYTES, tid, u0 - tile_stage::SUNITS_A, u1 - tile_stage::SUNITS_A);
+#elif B_ROWMAJOR
+    rowmajor_store(st.b, lds + A_STAGE_BYTES, tid, u0 - tile_stage::SUNITS_A, u1 - tile_stage::SUNITS_A);
 #else
     jmajor_store(st.b, lds + A_STAGE_BYTES, tid, u0 - tile_stage::SUNITS_A, u1 - tile_stage::SUNITS_A);
 #endif
@@ -669,7 +770,11 @@ __device__ __forceinline__ void read_frags(frag_t (&fa)[K3][TM], frag_t (&fb)[K3
 #pragma unroll
             for (int c3 = 0; c3 < J3; ++c3) {
                 const int tcol = (c1 * J2 + wj) * J3 + c3;
+#if B_ROWMAJOR
+                fb[q][c1 * J3 + c3] = rowmajor_frag(lb, step, tcol, (int)(threadIdx.x % 64));
+#else
                 fb[q][c1 * J3 + c3] = lds_frag<SUBPLANE_B>(lb + step * LANE_GROUPS * PLANE_B + lds_slot(tcol * MI_N + lrow) * LFRAG_BYTES);
+#endif
             }
     }
 }
@@ -698,7 +803,7 @@ __device__ __forceinline__ void pipelined_step(accv_t (&acc)[TM][TN], const char
                                                const conv_ctx &cx, int kcur)
 {
     const char *la = cur + lgrp * PLANE_A;
-    const char *lb = cur + A_STAGE_BYTES + lgrp * PLANE_B;
+    const char *lb = cur + A_STAGE_BYTES + lgrp * B_LGRP;
     frag_t fa[2][K3][TM], fb[2][K3][TN];
     read_frags(fa[0], fb[0], la, lb, 0, wi, wj, lrow, cx, kcur);
 #pragma unroll
@@ -716,7 +821,7 @@ __device__ __forceinline__ void multiply_tile(accv_t (&acc)[TM][TN], const char 
                                               const conv_ctx &cx, int kcur)
 {
     const char *la = stage_base + lgrp * PLANE_A;
-    const char *lb = stage_base + A_STAGE_BYTES + lgrp * PLANE_B;
+    const char *lb = stage_base + A_STAGE_BYTES + lgrp * B_LGRP;
 #pragma unroll UNROLL_K1
     for (int k1 = 0; k1 < K1; ++k1) {
 #pragma unroll UNROLL_K2
@@ -733,7 +838,7 @@ __device__ __forceinline__ void multiply_tile_unrolled(accv_t (&acc)[TM][TN], co
                                                        int lrow, const conv_ctx &cx, int kcur)
 {
     const char *la = stage_base + lgrp * PLANE_A;
-    const char *lb = stage_base + A_STAGE_BYTES + lgrp * PLANE_B;
+    const char *lb = stage_base + A_STAGE_BYTES + lgrp * B_LGRP;
     frag_t fa[2][K3][TM], fb[2][K3][TN];
     read_frags(fa[0], fb[0], la, lb, 0, wi, wj, lrow, cx, kcur);
 #pragma unroll
@@ -818,7 +923,6 @@ constexpr int NS = K1 * K2;
 // is read with the 8-bit transpose load, 8 k-rows x 16 columns per group of 16 lanes).
 #if CACHE_READ >= 5
 constexpr int DL_STAGES = CACHE_READ >= 8 ? CACHE_READ - 6 : CACHE_READ - 3; // 5, 6, 7 and 8, 9, 10: rings of 2, 3, 4 stages
-constexpr int CE = 16 / ES;                               // elements per 16-byte chunk
 constexpr int CPR = BK / CE;                              // 16-byte chunks per k-contiguous row
 constexpr int ROW_BYTES = BK * ES;
 constexpr int SWZ_DIV = CPR >= 8 ? 1 : 8 / CPR;           // rows that share one 128-byte line
@@ -834,13 +938,7 @@ constexpr int DL_IA = BM / RPI;                           // load instructions p
 #if B_KMAJOR
 constexpr int DL_IB = BN / RPI;
 #else
-constexpr int CB = BN / CE;                               // 16-byte chunks per k-row of the j-contiguous B tile
-constexpr int BROW_BYTES = BN * ES;
 constexpr int DL_IB = (BK * CB + 63) / 64;
-// swizzle of the 16-column granules (what one transpose load covers: 32 bytes of 2-byte, 16 bytes of 1-byte
-// elements) of a row with the row number; needs a power-of-two granule count
-constexpr int NGRAN = BN / 16;
-constexpr int GRAN_MASK = (NGRAN & (NGRAN - 1)) ? 0 : (NGRAN > 16 ? 15 : NGRAN - 1);
 #endif
 constexpr int DL_INSTR = DL_IA + DL_IB;
 constexpr int DL_LPW_MIN = DL_INSTR / NWAVES;             // loads every wavefront issues per tile, at least
@@ -851,10 +949,6 @@ static_assert(CPR == 4 || CPR == 8 || CPR == 16, "direct-to-LDS path: k tile of 
 #define AS3(p) ((__attribute__((address_space(3))) void *)(p))
 
 __device__ __forceinline__ int dl_swz(int row) { return (row / SWZ_DIV) % CPR; }
-#if !B_KMAJOR
-// chunk-index XOR for k-row `k` of the j-contiguous operand: moves whole 16-column granules (ES chunks each)
-__device__ __forceinline__ int dl_swz_b(int k) { return (k & GRAN_MASK) * ES; }
-#endif
 
 // issue this wavefront's share of the loads of tile `k0` into the stage at `stage`
 __device__ __forceinline__ void dl_issue(const in_t *__restrict__ A, const in_t *__restrict__ B, char *stage, int i0, int j0, int k0, int wave,
@@ -920,9 +1014,6 @@ __device__ __forceinline__ void dl_issue_one(const in_t *__restrict__ A, const i
         __builtin_amdgcn_global_load_lds(AS1(ub + voff), AS3(stage + DL_A_BYTES + ib * 1024), 16, 0, 0);
     }
 }
-
-typedef short tr4_t __attribute__((ext_vector_type(4)));
-typedef int tr2_t __attribute__((ext_vector_type(2)));
 
 __device__ __forceinline__ void dl_read_frags(frag_t (&fa)[K3][TM], frag_t (&fb)[K3][TN], const char *__restrict__ stage, int slot, int wi, int wj,
                                               int lane)
@@ -1809,7 +1900,7 @@ ms_kernel(const void *__restrict__ a_, const void *__restrict__ b_, const void *
         for (int k0 = KB; k0 < KE; ++k0) {
             frag_t fa[K3][TM], fb[K3][TN];
             const char *base = lds + stage * STAGE_BYTES;
-            read_frags(fa, fb, base + lgrp * PLANE_A, base + A_STAGE_BYTES + lgrp * PLANE_B, 0, wi, wj, lrow, cx, k0);
+            read_frags(fa, fb, base + lgrp * PLANE_A, base + A_STAGE_BYTES + lgrp * B_LGRP, 0, wi, wj, lrow, cx, k0);
             stage_store(st, lds + (stage ^ 1) * STAGE_BYTES, tid);
             stage_load(st, A, B, i0, j0, k0 + 2 < KE ? k0 + 2 : KE - 1, tid);
             __syncthreads();
@@ -1838,7 +1929,7 @@ ms_kernel(const void *__restrict__ a_, const void *__restrict__ b_, const void *
         __syncthreads();
 #endif
         const char *la = lds + stage * STAGE_BYTES + lgrp * PLANE_A;
-        const char *lb = lds + stage * STAGE_BYTES + A_STAGE_BYTES + lgrp * PLANE_B;
+        const char *lb = lds + stage * STAGE_BYTES + A_STAGE_BYTES + lgrp * B_LGRP;
 #if PIPELINED
         // k1, k2 fully unrolled: software pipeline over the NS = K1*K2 slots of this tile.  Slot s
         // first issues the LDS reads of slot s+1 and its share of the next tile's global loads, then

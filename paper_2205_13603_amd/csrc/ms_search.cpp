@@ -116,7 +116,7 @@ struct Search {
         if (cfg->cost_model) {
             double fv[128];
             int32_t nf = 0;
-            if (ms_variant_features(op, &p, fv, 128, &nf) == MS_OK) {
+            if (ms_variant_features(op, &p, fv, 128, &nf) == MS_OK && (n_feat == 0 || nf == n_feat)) {
                 n_feat = nf;
                 feat.insert(feat.end(), fv, fv + nf);
                 target.push_back(log2(us));
@@ -149,6 +149,9 @@ extern "C" int32_t ms_search(const ms_op *op, const ms_space *space, const ms_se
         return fail(MS_ERR_BAD_ARG, "ms_search: bad configuration");
     if (cfg->cost_model && (cfg->model_candidates < 1 || cfg->model_candidates > 1024 || cfg->model_min_trials < 4))
         return fail(MS_ERR_BAD_ARG, "ms_search: bad cost-model configuration");
+    const bool pretrained = cfg->cost_model && cfg->pretrain_n > 0;
+    if (pretrained && (!cfg->pretrain_X || !cfg->pretrain_y || cfg->pretrain_d < 1 || cfg->pretrain_d > 128))
+        return fail(MS_ERR_BAD_ARG, "ms_search: pre-training rows without arrays or with a bad width");
     ms_cost_model *model = nullptr;
     if (cfg->cost_model) {
         int32_t rc = ms_cost_model_create(60, 4, 0.3, 2, &model);
@@ -172,6 +175,15 @@ extern "C" int32_t ms_search(const ms_op *op, const ms_space *space, const ms_se
     S.cb = cb;
     S.cb_user = cb_user;
     S.res = out;
+    if (pretrained) {
+        for (int64_t i = 0; i < (int64_t)cfg->pretrain_n * cfg->pretrain_d; ++i)
+            if (!std::isfinite(cfg->pretrain_X[i])) return fail(MS_ERR_BAD_ARG, "ms_search: pre-training feature %lld is not finite", (long long)i);
+        for (int32_t i = 0; i < cfg->pretrain_n; ++i)
+            if (!std::isfinite(cfg->pretrain_y[i])) return fail(MS_ERR_BAD_ARG, "ms_search: pre-training target %d is not finite", i);
+        S.n_feat = cfg->pretrain_d;
+        S.feat.assign(cfg->pretrain_X, cfg->pretrain_X + (size_t)cfg->pretrain_n * cfg->pretrain_d);
+        S.target.assign(cfg->pretrain_y, cfg->pretrain_y + cfg->pretrain_n);
+    }
     Rng rng(mix64(cfg->seed ^ 0x5851F42D4C957F2Dull));
     std::vector<Member> pop;
     uint64_t sample_index = 0;
@@ -188,10 +200,61 @@ extern "C" int32_t ms_search(const ms_op *op, const ms_space *space, const ms_se
         if ((int)pop.size() > cfg->population) pop.resize((size_t)cfg->population);
     };
 
-    // initial population: draws from the prior P(tau)
+    // initial population: draws from the prior P(tau); a pre-trained model picks half of them from a larger draw
+    const int want_init = std::min(cfg->init_population, cfg->trials);
+    if (pretrained && cfg->pretrain_n >= cfg->model_min_trials) {
+        if (ms_cost_model_fit(model, S.feat.data(), S.target.data(), (int32_t)S.target.size(), S.n_feat) != MS_OK) return MS_ERR_BAD_ARG;
+        struct Drawn {
+            ms_trace t;
+            double pred;
+        };
+        std::vector<Drawn> drawn;
+        std::map<uint64_t, bool> have;
+        const int pool = want_init * cfg->model_candidates;
+        for (int tries = 0; (int)drawn.size() < pool && tries < pool * 1000; ++tries) {
+            Drawn d;
+            int32_t rc = ms_trace_sample(space, cfg->seed, sample_index++, &d.t);
+            if (rc != MS_OK) return rc;
+            ++proposals;
+            ms_variant_params p;
+            if (ms_trace_validate(op, space, &d.t, &p) != MS_OK) {
+                ++out->n_invalid;
+                continue;
+            }
+            if (have.count(p.key)) {
+                ++out->n_duplicate;
+                continue;
+            }
+            double fv[128];
+            int32_t nf = 0;
+            if (ms_variant_features(op, &p, fv, 128, &nf) != MS_OK) continue;
+            if (nf != S.n_feat) return fail(MS_ERR_BAD_ARG, "ms_search: pre-training rows have %d features, this operator's variants %d", S.n_feat, nf);
+            if (ms_cost_model_predict(model, fv, 1, nf, &d.pred) != MS_OK) continue;
+            have[p.key] = true;
+            drawn.push_back(d);
+        }
+        std::vector<size_t> by_pred(drawn.size());
+        for (size_t i = 0; i < drawn.size(); ++i) by_pred[i] = i;
+        std::stable_sort(by_pred.begin(), by_pred.end(), [&](size_t a, size_t b) { return drawn[a].pred < drawn[b].pred; });
+        std::vector<bool> taken(drawn.size(), false);
+        std::vector<ms_trace> batch;
+        for (size_t r = 0; r < by_pred.size() && (int)batch.size() < (want_init + 1) / 2; ++r) {
+            taken[by_pred[r]] = true;
+            batch.push_back(drawn[by_pred[r]].t);
+        }
+        for (size_t i = 0; i < drawn.size() && (int)batch.size() < want_init; ++i)
+            if (!taken[i]) batch.push_back(drawn[i].t);
+        if (!fake_latency && !batch.empty()) ms_prebuild(op, space, batch.data(), (int32_t)batch.size(), cfg->compile_threads, nullptr);
+        for (auto &t : batch) {
+            if (S.stop || out->n_measured >= want_init) break;
+            uint64_t key = 0;
+            double us = S.evaluate(t, &key);
+            if (us > 0) insert_member(t, us, key);
+        }
+    }
     {
         std::vector<ms_trace> batch;
-        int want = std::min(cfg->init_population, cfg->trials);
+        int want = want_init;
         while (out->n_measured < want && !S.stop && proposals < max_proposals) {
             batch.clear();
             int need = want - out->n_measured;

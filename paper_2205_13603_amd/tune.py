@@ -32,6 +32,9 @@ def main():
     ap.add_argument("--out", default="tuned_out")
     ap.add_argument("--cost-model", action="store_true", help="let the learned cost model pick which proposals are measured")
     ap.add_argument("--model-candidates", type=int, default=8, help="proposals scored per measured candidate")
+    ap.add_argument("--pretrain", default="", help="with --cost-model: pre-train the model on trial logs of earlier searches of this "
+                    "workload and protocol; a comma-separated list of *.log.jsonl files, or 'stored' for the logs kept with the "
+                    "records (the one of this very seed left out)")
     ap.add_argument("--measure", default="", help="warm-up launches, repeats, launches per repeat of every trial (default 1,3,3 for "
                     "filling; 8,3,<sets> for steady); a long warm-up (e.g. 150,3,20) times candidates at the clocks of a sustained run")
     ap.add_argument("--compile-threads", type=int, default=16)
@@ -103,14 +106,25 @@ def main():
     cfg.compile_threads = args.compile_threads
     cfg.cost_model, cfg.model_candidates = int(args.cost_model), args.model_candidates
     cfg.measure = B.ms_measure_cfg(wu, reps, lpr, inst)
-    res = B.search(op, space, cfg, bufsets=sets, stream=devmem.current_stream(), on_trial=on_trial)
+    pretrain, pretrain_logs = None, []
+    if args.pretrain:
+        if not args.cost_model:
+            raise SystemExit("--pretrain needs --cost-model")
+        pretrain_logs = (tuned.pretraining_logs(args.workload, args.protocol, exclude_seed=args.seed) if args.pretrain == "stored"
+                         else [p for p in args.pretrain.split(",") if p])
+        pretrain = tuned.pretraining_rows(op, space, pretrain_logs)
+        print("cost model pre-trained on %d trials of %d logs" % (len(pretrain[1]), len(pretrain_logs)), flush=True)
+        if len(pretrain[1]) == 0:
+            raise SystemExit("--pretrain: no usable trial in %s" % pretrain_logs)
+    res = B.search(op, space, cfg, bufsets=sets, stream=devmem.current_stream(), on_trial=on_trial, pretrain=pretrain)
     flop, byts = op.work()
     mode = "device-filling, %d instances" % R if args.protocol == "filling" else "steady state, 1 instance, %d rotating buffer sets" % R
     rec = {"workload": args.workload, "trace": B.trace_to_text(op, space, res.best_trace), "us": res.best_us, "protocol": args.protocol,
            "mode": mode, "tflops": flop * inst / res.best_us / 1e6, "gbs": byts * inst / res.best_us / 1e3,
            "trials": res.n_measured, "trials_to_best": res.best_trial, "invalid": res.n_invalid, "failed": res.n_failed,
            "duplicate": res.n_duplicate, "search_seconds": round(res.wall_seconds, 1), "seed": args.seed, "flags": args.flags,
-           "cost_model": int(args.cost_model), "modules": composed, "compiler": list(B.jit_stats()["compiler"]),
+           "cost_model": int(args.cost_model), "pretrain_trials": int(len(pretrain[1])) if pretrain else 0,
+           "pretrain_logs": [os.path.basename(p) for p in pretrain_logs], "modules": composed, "compiler": list(B.jit_stats()["compiler"]),
            # first measured trial whose best-so-far latency is within 1 % of the final best
            "trials_to_within_1pct": next((i for i, b in curve if b <= 1.01 * res.best_us), res.best_trial)}
     with open(os.path.join(args.out, args.workload + ".jsonl"), "a") as f:

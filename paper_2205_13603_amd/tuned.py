@@ -37,6 +37,46 @@ def load_searches(name, trials=256):
     return [r for r in rows if r.get("workload") == name and r.get("trials") == trials]
 
 
+def pretraining_rows(op, space, log_paths):
+    """(X, y) for the search's cost model from the trial logs the tuning command writes: the feature vector of
+    every measured trial whose trace still validates in `space`, and log2 of its latency in microseconds.  The
+    logs must be of the same workload and measurement protocol as the search that uses the rows."""
+    import math
+    import numpy as np
+    X, y = [], []
+    for path in log_paths:
+        for line in open(path):
+            if not line.strip():
+                continue
+            r = json.loads(line)
+            if r.get("status") != 0 or not r.get("us", 0) > 0:
+                continue
+            try:
+                p = B.trace_validate(op, space, B.trace_from_decisions(space, r["decisions"]))
+            except (B.MsError, ValueError):
+                continue
+            X.append(B.variant_features(op, p))
+            y.append(math.log2(r["us"]))
+    return np.array(X, dtype=np.float64).reshape(len(y), -1), np.array(y, dtype=np.float64)
+
+
+PRETRAIN_DIR = os.path.join(RECORD_DIR, "logs")
+
+
+def pretraining_logs(name, protocol, exclude_seed=None):
+    """Stored trial logs of a workload under a protocol (written by the tuning command, kept next to the records)."""
+    if not os.path.isdir(PRETRAIN_DIR):
+        return []
+    pre = "%s.%s.s" % (name, protocol)
+    out = []
+    for f in sorted(os.listdir(PRETRAIN_DIR)):
+        if f.startswith(pre) and f.endswith(".log.jsonl"):
+            if exclude_seed is not None and f == "%s%d.log.jsonl" % (pre, exclude_seed):
+                continue
+            out.append(os.path.join(PRETRAIN_DIR, f))
+    return out
+
+
 def append_record(name, rec):
     os.makedirs(RECORD_DIR, exist_ok=True)
     with open(record_path(name), "a") as f:

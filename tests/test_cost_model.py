@@ -152,6 +152,71 @@ def test_model_guided_search_on_the_synthetic_latency():
     assert med_guided < 0.9 * med_plain
 
 
+def _pretraining_rows(n=400, seed=777):
+    op = B.gemm_op(128, 128, 128, "f32")
+    sp = op.space()
+    X, y = [], []
+    for i in range(n):
+        p = B.trace_validate(op, sp, B.trace_sample_valid(op, sp, seed, i))
+        X.append(B.variant_features(op, p))
+        y.append(np.log2(synthetic_latency(p)))
+    return np.array(X), np.array(y)
+
+
+def test_pretrained_model_cuts_the_trials_to_the_optimum():
+    """The model fitted beforehand on 400 random variants of the same operator (another seed's draws, their
+    latencies from the same function) picks half of the initial population and is in use from the first generation:
+    on every one of eight seeds the search then reaches the optimum, and in fewer measurements in total than the
+    plain search needs (which misses it on two of the seeds within the budget)."""
+    op = B.gemm_op(128, 128, 128, "f32")
+    sp = op.space()
+    rows = _pretraining_rows()
+    first_plain, first_pre = [], []
+    for seed in range(8):
+        for pre, out in ((None, first_plain), (rows, first_pre)):
+            cfg = B.search_cfg_default()
+            cfg.seed, cfg.trials, cfg.cost_model = seed, 192, int(pre is not None)
+            curve = []
+            res = B.search(op, sp, cfg, fake_latency=synthetic_latency, on_trial=lambda t: curve.append(t.best_us) and 0, pretrain=pre)
+            assert res.n_measured == 192 and cfg.pretrain_n == 0          # the binding drops the arrays after the call
+            out.append(next((i + 1 for i, b in enumerate(curve) if b <= 1.0 + 1e-9), 193))
+    print("plain", first_plain, "pre-trained", first_pre)
+    assert max(first_pre) <= 192
+    assert sum(first_pre) < 0.75 * sum(first_plain)
+    assert sum(a <= b for a, b in zip(first_pre, first_plain)) >= 7
+
+
+def test_pretraining_rows_are_checked():
+    op = B.gemm_op(128, 128, 128, "f32")
+    sp = op.space()
+    X, y = _pretraining_rows(60)
+    cfg = B.search_cfg_default()
+    cfg.trials, cfg.cost_model = 40, 1
+    with pytest.raises(B.MsError):                       # other feature count than this operator's variants
+        B.search(op, sp, cfg, fake_latency=synthetic_latency, pretrain=(X[:, :-1], y))
+    bad = y.copy()
+    bad[3] = np.nan
+    with pytest.raises(B.MsError):
+        B.search(op, sp, cfg, fake_latency=synthetic_latency, pretrain=(X, bad))
+    with pytest.raises(ValueError):
+        B.search(op, sp, cfg, fake_latency=synthetic_latency, pretrain=(X, y[:-1]))
+    # without cost_model the rows are ignored: the run equals the plain one
+    cfg.cost_model = 0
+    a = B.search(op, sp, cfg, fake_latency=synthetic_latency, pretrain=(X, y))
+    b = B.search(op, sp, cfg, fake_latency=synthetic_latency)
+    assert bytes(a.best_trace) == bytes(b.best_trace) and a.best_us == b.best_us
+
+
+def test_trace_from_decisions_round_trip():
+    op = B.conv2d_op(1, 56, 56, 64, 64, 3, 3, stride=1, pad=1)
+    sp = op.space()
+    for i in range(20):
+        t = B.trace_sample(sp, 4, i)
+        assert bytes(B.trace_from_decisions(sp, t.decisions())) == bytes(t)
+    with pytest.raises(ValueError):
+        B.trace_from_decisions(sp, B.trace_sample(sp, 4, 0).decisions()[:-1])
+
+
 def test_model_guided_search_is_deterministic_and_identical_before_the_model_starts():
     r1, l1 = _run(3, 96, 1)
     r2, l2 = _run(3, 96, 1)

@@ -449,3 +449,105 @@ def test_ping_pong_on_the_ring_c2_shape():
             refs = [O.gemm(a, b) for a, b in ins]
         for r in (0, 1, 2, 3, 31, 63):
             compare.assert_float_close(got[r], refs[r % 4], compare.RTOL_HALF, "C2 ping-pong trace %d instance %d" % (n, r))
+
+
+def test_row_major_b_in_lds_exact():
+    """storage_align 3: the j-contiguous B goes global memory -> registers -> LDS in 16-byte vectors without a register
+    transposition and the fragments come out of the transposing LDS loads.  int8 (both 16-k-per-lane intrinsics) and
+    integer-valued fp16 / bf16 (both 8-k-per-lane intrinsics) with fp32 output must equal the oracle bit for bit; every
+    register-staging mode (single stage, double buffer, prefetch distance 2, software-pipelined k loop, ping-pong wave
+    groups), odd tile counts, column counts whose granule count is not a power of two (no swizzle), 3 instances with
+    distinct inputs."""
+    M, N, K = 192, 160, 384
+    g = I.rng(47)
+    ins = [[I.int8_uniform(g, (M, K)), I.int8_uniform(g, (K, N))] for _ in range(3)]
+    refs = [O.gemm(a, b) for a, b in ins]
+    op = B.gemm_op(M, N, K, "i8")
+    space = op.space()
+
+    def mk(sp, mfma, i, j, k, vecs, unroll=0, cache=1, reorder=0, cw=0):
+        return B.make_trace(sp, [[mfma], i, j, k, [unroll], [cache], [vecs[0]], [vecs[1]], [3], [reorder], [cw]])
+
+    traces = [mk(space, 161664, [12, 1, 1, 1], [10, 1, 1, 1], [6, 1, 1, 1], (16, 16)),                      # one wave, 16 columns
+              mk(space, 161664, [3, 2, 2, 1], [5, 1, 2, 1], [3, 1, 2, 1], (16, 16), unroll=64, cache=2, cw=1),  # pipelined, BN = 32
+              mk(space, 323232, [3, 1, 2, 1], [1, 1, 5, 1], [6, 1, 1, 2], (4, 16), cache=3, reorder=2),        # BN = 160: 10 granules
+              mk(space, 323232, [2, 1, 3, 1], [5, 1, 1, 1], [3, 2, 2, 1], (8, 16), unroll=16, reorder=1, cw=1),
+              mk(space, 161664, [6, 1, 2, 1], [5, 2, 1, 1], [6, 1, 1, 1], (16, 16), cache=4, reorder=2),       # ping-pong wave groups
+              mk(space, 161664, [3, 2, 2, 1], [5, 1, 1, 2], [3, 2, 1, 1], (16, 16), unroll=64, cache=2)]
+    ran = 0
+    for n, t in enumerate(traces):
+        p = B.trace_validate(op, space, t)
+        assert p.lds_pad == 3
+        print("int8 trace", n, t.decisions(), flush=True)
+        ran += 1
+        got = run_variant_distinct(op, space, t, ins, "i32", (M, N))
+        if got is None:
+            continue
+        for r in range(3):
+            compare.assert_int_equal(got[r], refs[r], "row-major B, int8, instance %d trace %d" % (r, n))
+    assert ran == 6
+    for dtype in ("f16", "bf16"):
+        M2, N2, K2 = 192, 160, 224
+        A, Bm = I.gemm_inputs(M2, N2, K2, dtype, 2, "ints")
+        ref = O.gemm(A, Bm, bf16=(dtype == "bf16"))
+        op2 = B.gemm_op(M2, N2, K2, dtype, "f32")
+        sp2 = op2.space()
+        traces = [mk(sp2, 161632, [12, 1, 1, 1], [10, 1, 1, 1], [7, 1, 1, 1], (8, 8)),
+                  mk(sp2, 323216, [3, 1, 2, 1], [5, 1, 1, 1], [7, 1, 1, 2], (8, 8), cache=2, reorder=2, cw=1),
+                  mk(sp2, 161632, [3, 2, 2, 1], [1, 1, 5, 2], [7, 1, 1, 1], (4, 8), cache=3, reorder=1),
+                  mk(sp2, 323216, [1, 3, 2, 1], [5, 1, 1, 1], [7, 1, 2, 1], (8, 8), unroll=64, cache=2),
+                  mk(sp2, 161632, [6, 1, 2, 1], [5, 1, 2, 1], [7, 1, 1, 1], (8, 8), cache=4)]
+        for n, t in enumerate(traces):
+            B.trace_validate(op2, sp2, t)
+            print(dtype, "trace", n, t.decisions(), flush=True)
+            got = run_variant(op2, sp2, t, [A, Bm], "f32", (M2, N2), instances=2)
+            if got is None:
+                continue
+            assert np.array_equal(got[0], ref) and np.array_equal(got[1], ref), "row-major B, %s trace %d" % (dtype, n)
+    # batched NN form (the attention product P x V of config C4b's kind)
+    Bn, Mh, Nh, Kh = 3, 64, 96, 128
+    P = I.gemm_inputs(Bn * Mh, 8, Kh, "f16", 1, "ints")[0].reshape(Bn, Mh, Kh)
+    V = I.gemm_inputs(Bn * Kh, 8, Nh, "f16", 1, "ints")[0].reshape(Bn, Kh, Nh)
+    ref = O.bmm(P, V, trans_b=False)
+    op3 = B.bmm_op(Bn, Mh, Nh, Kh, False, "f16", "f32")
+    sp3 = op3.space()
+    for n, t in enumerate([mk(sp3, 161632, [2, 1, 2, 1], [3, 1, 2, 1], [2, 1, 2, 1], (8, 8), cache=2, reorder=2),
+                           mk(sp3, 323216, [1, 1, 2, 1], [3, 1, 1, 1], [4, 1, 1, 2], (8, 8), cw=1)]):
+        B.trace_validate(op3, sp3, t)
+        print("bmm NN trace", n, t.decisions(), flush=True)
+        got = run_variant(op3, sp3, t, [P, V], "f32", (Bn, Mh, Nh))
+        if got is None:
+            continue
+        assert np.array_equal(got, ref), "row-major B, BMM-NN trace %d" % n
+
+
+def test_row_major_b_in_lds_c4c_and_c2_shapes():
+    """The same layout at the full shapes of config C4c (bit exact) and config C2 (tolerance of the fp16 configs)."""
+    A, Bm = I.c4c(seed=2)
+    ref = O.gemm(A, Bm)
+    op = B.gemm_op(512, 512, 512, "i8")
+    space = op.space()
+    for n, vals in enumerate([[[161664], [4, 8, 1, 1], [4, 2, 4, 1], [4, 1, 2, 1], [0], [1], [16], [16], [3], [2], [0]],
+                              [[323232], [4, 2, 2, 1], [4, 1, 2, 2], [4, 1, 4, 1], [0], [1], [16], [16], [3], [2], [0]],
+                              [[161664], [2, 4, 4, 1], [4, 8, 1, 1], [4, 1, 2, 1], [64], [2], [16], [16], [3], [2], [1]]]):
+        t = B.make_trace(space, vals)
+        B.trace_validate(op, space, t)
+        print("C4c trace", n, t.decisions(), flush=True)
+        got = run_variant(op, space, t, [A, Bm], "i32", (512, 512))
+        if got is None:
+            continue
+        compare.assert_int_equal(got, ref, "row-major B, C4c trace %d" % n)
+    A, Bm = I.c2(seed=1)
+    ref = O.gemm(A, Bm)
+    op = B.gemm_op(1024, 1024, 1024, "f16")
+    space = op.space()
+    for n, vals in enumerate([[[323216], [4, 2, 2, 2], [4, 2, 2, 2], [16, 1, 4, 1], [64], [2], [8], [8], [3], [2], [0]],
+                              [[323216], [4, 1, 4, 2], [4, 2, 2, 2], [16, 1, 1, 4], [0], [4], [8], [8], [3], [2], [1]],
+                              [[161632], [8, 2, 2, 2], [8, 1, 2, 4], [32, 1, 1, 1], [0], [3], [8], [8], [3], [0], [0]]]):
+        t = B.make_trace(space, vals)
+        B.trace_validate(op, space, t)
+        print("C2 trace", n, t.decisions(), flush=True)
+        got = run_variant(op, space, t, [A, Bm], "f16", (1024, 1024))
+        if got is None:
+            continue
+        compare.assert_float_close(got, ref, compare.RTOL_HALF, "row-major B, C2 trace %d" % n)

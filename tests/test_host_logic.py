@@ -25,7 +25,7 @@ def test_library_exports_every_declared_symbol():
     for name in sorted(declared):
         assert hasattr(L, name), "libms.so does not export %s" % name
     assert declared == set(B.SYMBOLS), (declared ^ set(B.SYMBOLS))
-    assert L.ms_version() == 2
+    assert L.ms_version() == 3
 
 
 def test_struct_sizes_match_header():
@@ -727,3 +727,40 @@ def test_stochastic_compose_is_seeded_and_respects_requirements():
     assert set(applied) <= {"multi-level-tiling", "use-mfma", "unroll"}
     sp, applied = B.space_stochastic_compose(B.gemm_op(128, 128, 128, "f32"), [], 0)
     assert applied == ["multi-level-tiling"] and sp.flags == 0
+
+
+def test_row_major_b_layout_is_offered_and_validated():
+    """storage_align 3 (B row-major in LDS, transposing LDS loads): offered for matrix-core GEMMs whose B is contiguous
+    along j; the validator wants 16-byte fragments, 16-byte loads of B and register staging, and counts a dense B tile."""
+    def align_candidates(op):
+        sp = op.space()
+        for i in range(sp.n_slots):
+            if sp.slots[i].slot_id == B.SLOT_STORAGE_ALIGN:
+                return [sp.slots[i].candidates[c] for c in range(sp.slots[i].n_candidates)]
+        return None
+
+    assert align_candidates(B.gemm_op(512, 512, 512, "i8")) == [0, 1, 2, 3]
+    assert align_candidates(B.gemm_op(1024, 1024, 1024, "f16")) == [0, 1, 2, 3]
+    assert align_candidates(B.bmm_op(4, 64, 64, 64, False, "f16")) == [0, 1, 2, 3]
+    assert align_candidates(B.bmm_op(4, 64, 64, 64, True, "f16")) == [0, 1, 2]           # B contiguous along k
+    assert align_candidates(B.conv2d_op(1, 56, 56, 64, 64, 3, 3, stride=1, pad=1)) == [0, 1, 2]
+    assert align_candidates(B.gemm_op(256, 256, 256, "f8", "f16")) == [0, 1, 2]
+    op = B.gemm_op(512, 512, 512, "i8")
+    sp = op.space()
+
+    def mk(mfma=161664, k=(4, 1, 2, 1), cache=1, vec_b=16):
+        return B.make_trace(sp, [[mfma], [4, 8, 1, 1], [4, 2, 4, 1], list(k), [0], [cache], [16], [vec_b], [3], [2], [0]])
+
+    p = B.trace_validate(op, sp, mk())
+    assert p.lds_pad == 3
+    # A: 8 planes of 128 fragments of 16 bytes + 16 bytes of padding each; B: 128 k-rows of 128 bytes, dense
+    assert p.lds_bytes == 8 * (128 * 16 + 16) + 128 * 128
+    assert "transform-layout(buffer=B.lds" in B.trace_to_text(op, sp, mk())
+    assert B.trace_validate(op, sp, mk(cache=2)).lds_bytes == 2 * p.lds_bytes
+    for bad, why in ((mk(vec_b=4), "vectorize_b"), (mk(mfma=161632, k=(4, 1, 2, 2)), "16-byte fragments"), (mk(cache=5), "")):
+        with pytest.raises(B.MsError) as e:
+            B.trace_validate(op, sp, bad)
+        assert why in str(e.value)
+    # a different layout is a different kernel
+    q = B.trace_validate(op, sp, B.make_trace(sp, [[161664], [4, 8, 1, 1], [4, 2, 4, 1], [4, 1, 2, 1], [0], [1], [16], [16], [2], [2], [0]]))
+    assert q.key != p.key and B.variant_kernel_text(op, q) != B.variant_kernel_text(op, p)
