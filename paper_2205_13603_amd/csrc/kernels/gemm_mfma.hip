@@ -618,7 +618,8 @@ typedef short tr4_t __attribute__((ext_vector_type(4)));
 typedef int tr2_t __attribute__((ext_vector_type(2)));
 
 #if B_ROWMAJOR
-static_assert((ES == 2 && KP == 8) || (ES == 1 && KP == 16), "row-major B in LDS: 16-byte fragments of 2-byte or 1-byte inputs");
+static_assert((ES == 2 && (KP == 4 || KP == 8)) || (ES == 1 && (KP == 8 || KP == 16 || KP == 32)),
+              "row-major B in LDS: fragments of whole transposing loads (4 k of 2-byte, 8 k of 1-byte elements)");
 static_assert(VEC_B == CE, "row-major B in LDS moves 16-byte vectors");
 // a thread moves 16-byte chunks; chunk idx -> (k-row, chunk of the row), chunks of a row on consecutive lanes
 struct rowmajor_stage {
@@ -663,30 +664,29 @@ __device__ __forceinline__ void rowmajor_store(const rowmajor_stage &st, char *_
 }
 
 // the B fragment of MFMA k step `step` for the 16 x 16 or 32 x 32 tile at tile column `tcol`, from the stage's B
-// region at `b`.  2-byte elements (ds_read_b64_tr_b16): 16 lanes hand in 4 k-rows x 16 columns (lane: k-row li/4,
-// 4 columns from li%4) and every lane receives 4 consecutive k of its own column; two loads = 8 k.  1-byte elements
-// (ds_read_b64_tr_b8): 8 k-rows x 16 columns per 16 lanes (lane: k-row li/2, 8 columns from li%2); two loads = 16 k.
+// region at `b`.  A lane's KP k values come from KP/4 (2-byte elements) or KP/8 (1-byte elements) transposing loads.
+// 2-byte (ds_read_b64_tr_b16): 16 lanes hand in 4 k-rows x 16 columns (lane: k-row li/4, 4 columns from li%4) and every
+// lane receives 4 consecutive k of its own column.  1-byte (ds_read_b64_tr_b8): 8 k-rows x 16 columns per 16 lanes
+// (lane: k-row li/2, 8 columns from li%2), every lane receives 8 consecutive k of its own column.
 __device__ __forceinline__ frag_t rowmajor_frag(const char *__restrict__ b, int step, int tcol, int lane)
 {
     const int lrow = lane % MI_M, lgrp = lane / MI_M, li = lane % 16;
     const int pn = (tcol * MI_N + lrow) / 16; // 16-column granule of this lane's column
     frag_t f;
 #if IN_DT != DT_I8 && IN_DT != DT_F8E4M3
-    const int krow = step * MI_K + lgrp * 8 + li / 4;
-    const char *b0 = b + krow * BROW_BYTES + (((pn << 1) ^ dl_swz_b(krow)) * 16) + (li % 4) * 8;
-    const char *b1 = b + (krow + 4) * BROW_BYTES + (((pn << 1) ^ dl_swz_b(krow + 4)) * 16) + (li % 4) * 8;
-    const tr4_t lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) tr4_t *)(b0));
-    const tr4_t hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) tr4_t *)(b1));
-    *reinterpret_cast<tr4_t *>(&f.v[0]) = lo;
-    *reinterpret_cast<tr4_t *>(&f.v[4]) = hi;
+#pragma unroll
+    for (int h = 0; h < KP / 4; ++h) {
+        const int krow = step * MI_K + lgrp * KP + h * 4 + li / 4;
+        const char *src = b + krow * BROW_BYTES + (((pn << 1) ^ dl_swz_b(krow)) * 16) + (li % 4) * 8;
+        *reinterpret_cast<tr4_t *>(&f.v[4 * h]) = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) tr4_t *)(src));
+    }
 #else
-    const int krow = step * MI_K + lgrp * 16 + li / 2;
-    const char *b0 = b + krow * BROW_BYTES + ((pn ^ dl_swz_b(krow)) * 16) + (li % 2) * 8;
-    const char *b1 = b + (krow + 8) * BROW_BYTES + ((pn ^ dl_swz_b(krow + 8)) * 16) + (li % 2) * 8;
-    const tr2_t lo = __builtin_amdgcn_ds_read_tr8_b64_v2i32((__attribute__((address_space(3))) tr2_t *)(b0));
-    const tr2_t hi = __builtin_amdgcn_ds_read_tr8_b64_v2i32((__attribute__((address_space(3))) tr2_t *)(b1));
-    *reinterpret_cast<tr2_t *>(&f.v[0]) = lo;
-    *reinterpret_cast<tr2_t *>(&f.v[8]) = hi;
+#pragma unroll
+    for (int h = 0; h < KP / 8; ++h) {
+        const int krow = step * MI_K + lgrp * KP + h * 8 + li / 2;
+        const char *src = b + krow * BROW_BYTES + ((pn ^ dl_swz_b(krow)) * 16) + (li % 2) * 8;
+        *reinterpret_cast<tr2_t *>(&f.v[8 * h]) = __builtin_amdgcn_ds_read_tr8_b64_v2i32((__attribute__((address_space(3))) tr2_t *)(src));
+    }
 #endif
     return f;
 }

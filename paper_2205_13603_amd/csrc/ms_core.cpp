@@ -610,7 +610,7 @@ extern "C" int32_t ms_space_describe(const ms_op *op, uint32_t flags, ms_space *
         if (flags & MS_SPACE_STORAGE_ALIGN) {
             // 3 (B row-major in LDS, read with the transposing loads): GEMMs whose B is contiguous along j, 1- and 2-byte inputs
             const bool b_rows = !is_conv2d(d.kind) && d.b_strides[2] == 1 && d.b_strides[1] != 1 &&
-                                (d.in_dtype == MS_F16 || d.in_dtype == MS_BF16 || d.in_dtype == MS_I8);
+                                (d.in_dtype == MS_F16 || d.in_dtype == MS_BF16 || d.in_dtype == MS_I8 || d.in_dtype == MS_F8E4M3);
             if (b_rows) add_cat(out, MS_SLOT_STORAGE_ALIGN, "storage_align", {0, 1, 2, 3});
             else add_cat(out, MS_SLOT_STORAGE_ALIGN, "storage_align", {0, 1, 2});
         }

@@ -551,3 +551,34 @@ def test_row_major_b_in_lds_c4c_and_c2_shapes():
         if got is None:
             continue
         compare.assert_float_close(got, ref, compare.RTOL_HALF, "row-major B, C2 trace %d" % n)
+
+
+def test_row_major_b_in_lds_every_fragment_size():
+    """storage_align 3 with the other fragment sizes: 4 k per lane of 2-byte inputs (one transposing load), 8 k per
+    lane of 1-byte inputs (one load: the shallow int8 and 8-bit float intrinsics) and 32 k per lane (four loads: the
+    128-deep and 64-deep 8-bit float intrinsics).  Integer-valued inputs, fp32 / int32 outputs: bit-equal to the oracle."""
+    def mk(sp, mfma, i, j, k, vec_b, unroll=0, cache=1, reorder=0, cw=0, vec=0):
+        return B.make_trace(sp, [[mfma], i, j, k, [unroll], [cache], [vec or vec_b], [vec_b], [3], [reorder], [cw]])
+
+    M, N, K = 192, 160, 256
+    cases = [("f16", "f32", 8, [(161616, [12, 1, 1, 1], [5, 2, 1, 1], [8, 1, 2, 1], 1), (323208, [3, 1, 2, 1], [5, 1, 1, 1], [8, 2, 1, 2], 2),
+                                (161616, [3, 2, 2, 1], [1, 1, 5, 2], [4, 1, 4, 1], 3)]),
+             ("i8", "i32", 16, [(161632, [12, 1, 1, 1], [5, 2, 1, 1], [4, 1, 2, 1], 1), (323216, [3, 1, 2, 1], [5, 1, 1, 1], [4, 2, 1, 2], 2),
+                                (161632, [3, 2, 2, 1], [1, 1, 5, 2], [8, 1, 1, 1], 4)]),
+             ("f8", "f32", 16, [(161632, [12, 1, 1, 1], [5, 2, 1, 1], [4, 1, 2, 1], 1), (323216, [3, 1, 2, 1], [5, 1, 1, 1], [4, 2, 1, 2], 2),
+                                (1616128, [6, 1, 2, 1], [5, 1, 2, 1], [2, 1, 1, 1], 1), (323264, [3, 1, 2, 1], [5, 1, 1, 1], [2, 1, 2, 1], 2),
+                                (1616128, [3, 2, 2, 1], [1, 1, 5, 2], [1, 1, 2, 1], 3), (323264, [1, 3, 2, 1], [5, 1, 1, 1], [4, 1, 1, 1], 1)])]
+    for dtype, odt, vb, traces in cases:
+        A, Bm = I.gemm_inputs(M, N, K, dtype, 7, "ints") if dtype != "i8" else (I.int8_uniform(I.rng(9), (M, K)), I.int8_uniform(I.rng(10), (K, N)))
+        ref = O.gemm(A, Bm)
+        op = B.gemm_op(M, N, K, dtype, odt)
+        sp = op.space()
+        for n, (mfma, i, j, k, cache) in enumerate(traces):
+            t = mk(sp, mfma, i, j, k, vb, cache=cache, reorder=2 * (n % 2), cw=n % 2)
+            p = B.trace_validate(op, sp, t)
+            assert p.lds_pad == 3 and p.mfma == mfma
+            print(dtype, "trace", n, t.decisions(), flush=True)
+            got = run_variant(op, sp, t, [A, Bm], odt, (M, N), instances=2)
+            if got is None:
+                continue
+            assert np.array_equal(got[0], ref) and np.array_equal(got[1], ref), "row-major B, %s trace %d" % (dtype, n)

@@ -744,7 +744,8 @@ def test_row_major_b_layout_is_offered_and_validated():
     assert align_candidates(B.bmm_op(4, 64, 64, 64, False, "f16")) == [0, 1, 2, 3]
     assert align_candidates(B.bmm_op(4, 64, 64, 64, True, "f16")) == [0, 1, 2]           # B contiguous along k
     assert align_candidates(B.conv2d_op(1, 56, 56, 64, 64, 3, 3, stride=1, pad=1)) == [0, 1, 2]
-    assert align_candidates(B.gemm_op(256, 256, 256, "f8", "f16")) == [0, 1, 2]
+    assert align_candidates(B.gemm_op(256, 256, 256, "f8", "f16")) == [0, 1, 2, 3]
+    assert align_candidates(B.gemm_op(128, 128, 128, "f32")) == [0, 1]                   # vector-ALU space
     op = B.gemm_op(512, 512, 512, "i8")
     sp = op.space()
 
@@ -757,7 +758,8 @@ def test_row_major_b_layout_is_offered_and_validated():
     assert p.lds_bytes == 8 * (128 * 16 + 16) + 128 * 128
     assert "transform-layout(buffer=B.lds" in B.trace_to_text(op, sp, mk())
     assert B.trace_validate(op, sp, mk(cache=2)).lds_bytes == 2 * p.lds_bytes
-    for bad, why in ((mk(vec_b=4), "vectorize_b"), (mk(mfma=161632, k=(4, 1, 2, 2)), "16-byte fragments"), (mk(cache=5), "")):
+    assert B.trace_validate(op, sp, mk(mfma=161632, k=(4, 1, 2, 2))).lds_bytes == 16 * (128 * 8 + 16) + 128 * 128   # 8-byte fragments
+    for bad, why in ((mk(vec_b=4), "vectorize_b"), (mk(cache=5), "")):
         with pytest.raises(B.MsError) as e:
             B.trace_validate(op, sp, bad)
         assert why in str(e.value)
