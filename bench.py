@@ -319,7 +319,7 @@ def main():
                          "floor_us": max(gap_us, ideal_us), "launch_gap_us": gap_us, "ideal_us_at_published_peak": ideal_us,
                          "single_launch_us": l1.median_us},
     }
-    out["config"]["search_256"] = [{k: r.get(k) for k in ("protocol", "seed", "us", "trials_to_best", "trials_to_within_1pct", "cost_model", "flags")}
+    out["config"]["search_256"] = [{k: r.get(k) for k in ("protocol", "seed", "us", "trials_to_best", "trials_to_within_1pct", "best_us_at", "cost_model", "pretrain_trials", "flags")}
                                    for r in tuned.load_searches(name, 256)]
     out["config"]["headline_variant_from"] = ("stored record of a %s-trial search (seed %s)" % (record_search.get("trials"), record_search.get("seed"))
                                               if best[2] == "record" and record_search else best[2])

@@ -581,9 +581,9 @@ typedef struct ms_search_cfg {
     int32_t model_min_trials; /* measurements needed before the model is used (earlier generations run as without it);
                                * pre-training rows count as measurements */
     int32_t pretrain_n;       /* rows of pretrain_X / pretrain_y, 0 = none */
-    /* Pre-training of the cost model (Section 4, "End-to-end search": the model is updated during the search and
-     * may be pre-trained): host arrays, read during the call only, of feature vectors (row-major, pretrain_n x
-     * pretrain_d, as ms_variant_features writes them for this operator) and targets (log2 of the latency in
+    /* Rows the cost model is fitted on before the search starts (Section 4, "End-to-end search", allows a model
+     * trained beforehand besides the refits during the search): host arrays, read during the call only, of feature
+     * vectors (row-major, pretrain_n x pretrain_d, as ms_variant_features writes them for this operator) and targets (log2 of the latency in
      * microseconds) of earlier measurements of the same operator under the same measurement protocol, e.g. the log
      * of an earlier search.  Every fit sees these rows followed by this search's own measurements.  With enough
      * rows (>= model_min_trials) the model also picks the initial population: model_candidates x init_population

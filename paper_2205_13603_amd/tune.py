@@ -7,8 +7,10 @@ Two measurement protocols (what a trial's latency is):
   filling  one launch over R instances of the workload (the device-filling batch): kernel quality against the roofline
   steady   back-to-back launches of ONE instance, rotating over R distinct buffer sets whose footprint exceeds the
            last-level cache: the workload at its own shape, dispatch gaps included
-Writes <out>/<workload>.jsonl (best record, appendable to tuned_records/), <out>/<workload>.log.jsonl (every trial:
-index, status, latency, best so far, decisions) and one summary line per run to <out>/searches.jsonl.
+Writes <out>/<workload>.jsonl (best record, appendable to tuned_records/), <out>/<workload>.<protocol>.s<seed>.log.jsonl
+(every trial: index, status, latency, best so far, decisions) and one summary line per run to <out>/searches.jsonl.
+Such trial logs are what `--cost-model --pretrain` fits the cost model on before a later search of the same workload
+and protocol starts (Section 4 allows a model trained before the search); `--pretrain stored` takes the logs under tuned_records/logs.
 """
 import argparse
 import json

@@ -7,7 +7,7 @@ import pytest
 
 from oracle import compare
 from oracle.workloads import oracle_run
-from paper_2205_13603_amd import binding as B, devmem
+from paper_2205_13603_amd import binding as B, devmem, tuned
 from paper_2205_13603_amd.workloads import WORKLOADS, OUT_SHAPE, BOUND, workload_inputs
 
 pytestmark = pytest.mark.gpu
@@ -15,7 +15,7 @@ pytestmark = pytest.mark.gpu
 TRIALS = 32
 
 
-def _search(name, seed, trials, init_population, cost_model=0, check=True):
+def _search(name, seed, trials, init_population, cost_model=0, check=True, pretrain=None):
     import torch
     mk, _ = WORKLOADS[name]
     op = mk()
@@ -60,7 +60,10 @@ def _search(name, seed, trials, init_population, cost_model=0, check=True):
     cfg.compile_threads = 16
     cfg.cost_model, cfg.model_min_trials = cost_model, 12
     cfg.measure = B.ms_measure_cfg(1, 3, 3, R)
-    res = B.search(op, space, cfg, bufsets=sets, stream=stream, on_trial=on_trial)
+    rows = tuned.pretraining_rows(op, space, tuned.pretraining_logs(name, "filling")) if pretrain else None
+    if pretrain:
+        assert len(rows[1]) >= 256, "stored trial logs of %s" % name
+    res = B.search(op, space, cfg, bufsets=sets, stream=stream, on_trial=on_trial, pretrain=rows)
     torch.cuda.synchronize()
     return res, trials_seen, errors
 
@@ -101,3 +104,21 @@ def test_model_guided_search_measures_correct_kernels():
     res, seen, errors = _search("c5b_dw_f32_56x56x144", seed=3, trials=40, init_population=12, cost_model=1)
     assert not errors, errors[0]
     assert res.n_measured == 40 and res.n_failed == 0
+
+
+def test_pretrained_model_picks_a_better_initial_population():
+    """The model fitted beforehand on the stored trial logs of the workload (Section 4 allows a model trained before the search)
+    chooses half of the initial population from 8x as many draws: the better half of the 12 kernels it measures first
+    is faster than the better half of the 12 random draws the plain search starts with (same seed), and every kernel is
+    checked against the oracle."""
+    if not devmem.gpu_available():
+        pytest.skip("the search measures on the device")
+    name = "c5a_dw_f32_112x112x32"
+    res, seen, errors = _search(name, seed=6, trials=24, init_population=12, cost_model=1, pretrain=True)
+    assert not errors, errors[0]
+    assert res.n_measured == 24 and res.n_failed == 0
+    plain = _search(name, seed=6, trials=12, init_population=12, check=False)[1]
+    first = sorted(s[2] for s in seen[:12] if s[1] == 0)[:6]
+    base = sorted(s[2] for s in plain if s[1] == 0)[:6]
+    print("pre-trained", first, "plain", base, flush=True)
+    assert sum(first) < sum(base)
