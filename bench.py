@@ -178,12 +178,21 @@ def main():
                     return 1
                 return 0
 
-            res = B.search(op, space, cfg, bufsets=full_set, stream=stream, on_trial=on_trial)
+            # with stored trial logs of the workload the search's cost model is fitted on them before the first
+            # trial (Section 4 allows a model trained beforehand), so even a short search starts from good candidates
+            logs = tuned.pretraining_logs(name, "filling")
+            rows = tuned.pretraining_rows(op, space, logs) if logs else None
+            if rows is not None and len(rows[1]) >= cfg.model_min_trials:
+                cfg.cost_model = 1
+            else:
+                rows = None
+            res = B.search(op, space, cfg, bufsets=full_set, stream=stream, on_trial=on_trial, pretrain=rows)
             if wrong:
                 print("bench.py: a candidate of the search does not match the oracle: %s" % wrong[0], file=sys.stderr)
                 return 1
             search_info = {"trials": res.n_measured, "trials_to_best": res.best_trial, "invalid": res.n_invalid,
-                           "failed": res.n_failed, "duplicate": res.n_duplicate, "checked_against_oracle": res.n_measured}
+                           "failed": res.n_failed, "duplicate": res.n_duplicate, "checked_against_oracle": res.n_measured,
+                           "best_us": res.best_us, "cost_model": "pre-trained on %d stored trials" % len(rows[1]) if rows is not None else "off"}
             if res.best_us < best[1]:
                 best = (res.best_trace, res.best_us, "search", space)
     if best[0] is None:

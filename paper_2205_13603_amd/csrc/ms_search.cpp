@@ -200,6 +200,20 @@ extern "C" int32_t ms_search(const ms_op *op, const ms_space *space, const ms_se
         if ((int)pop.size() > cfg->population) pop.resize((size_t)cfg->population);
     };
 
+    if (pretrained) {
+        // the rows must be as wide as this operator's feature vectors (looked up on the first valid draw; the draws
+        // themselves are made again below)
+        for (uint64_t probe = 0; probe < 4096; ++probe) {
+            ms_trace t;
+            ms_variant_params p;
+            if (ms_trace_sample(space, cfg->seed, probe, &t) != MS_OK) break;
+            if (ms_trace_validate(op, space, &t, &p) != MS_OK) continue;
+            int32_t nf = 0;
+            if (ms_variant_features(op, &p, nullptr, 0, &nf) == MS_OK && nf != S.n_feat)
+                return fail(MS_ERR_BAD_ARG, "ms_search: pre-training rows have %d features, this operator's variants %d", S.n_feat, nf);
+            break;
+        }
+    }
     // initial population: draws from the prior P(tau); a pre-trained model picks half of them from a larger draw
     const int want_init = std::min(cfg->init_population, cfg->trials);
     if (pretrained && cfg->pretrain_n >= cfg->model_min_trials) {
