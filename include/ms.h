@@ -183,7 +183,9 @@ typedef enum ms_slot_id {
                               3 (matrix-core GEMMs whose B is contiguous along j, 1- and 2-byte inputs, register staging,
                               B loaded in 16-byte vectors) = A as with 2, B kept in LDS as in global memory (row-major
                               k-rows, 16-column granules XOR-swizzled with the row) and read with the transposing LDS
-                              loads instead of being transposed in registers (Table 2, transform-layout) */
+                              loads instead of being transposed in registers (Table 2, transform-layout),
+                              4 = as 3 without any swizzle: the k-rows of B padded by 32 bytes, the planes of A by 16, so
+                              that every fragment address is a per-lane base plus a constant */
     MS_SLOT_REORDER = 9,   /* categorical: order of the grid loops, 0 = i outer, 1 = j outer,
                               2 = i outer with workgroups grouped per XCD, 3 (with cache_read 5..7) = as 2 with
                               persistent workgroups that loop over tiles */

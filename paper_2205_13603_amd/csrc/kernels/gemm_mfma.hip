@@ -18,7 +18,8 @@
 //           of 2, 3 buffers under persistent workgroups whose wavefronts form two groups one phase apart:
 //           while one group multiplies a k step from registers, the other reads the next step's fragments
 //           from LDS (see "Ping-pong on the ring" below))
-//   storage-align: LDS_PAD 1, 2: each LDS plane padded by 16 bytes; 2: slots of a plane XOR-swizzled
+//   storage-align: LDS_PAD 1, 2: each LDS plane padded by 16 bytes; 2: slots of a plane XOR-swizzled; 3, 4: B row-major
+//           in LDS (see B_ROWMAJOR)
 //   vectorize: global loads of VEC (A) and VEC_B (B) elements
 //   cache-write (CACHE_WRITE 1): the output tile is assembled in LDS and stored as whole rows
 //   rfactor (RFACTOR S > 1): the k0 loop is cut into S runs of K0 / S steps, S consecutive workgroups share an
@@ -105,8 +106,11 @@
 
 #define B_KMAJOR (!IS_CONV && SB_K == 1 && SB_J != 1)
 // LDS_PAD 3 (j-contiguous B of a GEMM, register staging): B lies in LDS as in global memory, row-major k-rows of BN
-// elements, and the fragments come out of the transposing LDS loads; A as with LDS_PAD 2
-#define B_ROWMAJOR (!IS_CONV && !B_KMAJOR && LDS_PAD == 3 && CACHE_READ <= 4)
+// elements, and the fragments come out of the transposing LDS loads; A as with LDS_PAD 2.  LDS_PAD 4: the same without
+// any XOR swizzle - the rows of B are padded by 32 bytes and the planes of A by 16 instead - so that every fragment
+// address is one per-lane base plus a compile-time constant (the immediate offset of the LDS instruction): unrolled
+// k loops then need two address registers instead of one per fragment
+#define B_ROWMAJOR (!IS_CONV && !B_KMAJOR && (LDS_PAD == 3 || LDS_PAD == 4) && CACHE_READ <= 4)
 #define NWAVES (I2 * J2)
 #define LANE_GROUPS (64 / MI_M)
 #define KP (MI_K / LANE_GROUPS)
@@ -136,14 +140,15 @@ constexpr int PLANE_B = LSPLIT * SUBPLANE_B;
 // consecutive rows still touch 8 distinct slots of one aligned group.
 __device__ __forceinline__ int lds_slot(int n)
 {
-#if LDS_PAD >= 2
+#if LDS_PAD == 2 || LDS_PAD == 3
     return n ^ ((n >> 3) & 7);
 #else
     return n;
 #endif
 }
 constexpr int A_STAGE_BYTES = CONV_PATCH ? 0 : KG * PLANE_A; // the per-k-step stage holds A unless X is resident as a patch
-constexpr int B_STAGE_BYTES = B_ROWMAJOR ? BK * BN * ES : KG * PLANE_B;
+constexpr int RM_ROW = BN * ES + (LDS_PAD == 4 ? 32 : 0); // bytes of one k-row of the row-major B stage
+constexpr int B_STAGE_BYTES = B_ROWMAJOR ? BK * RM_ROW : KG * PLANE_B;
 constexpr int B_LGRP = B_ROWMAJOR ? 0 : PLANE_B;  // offset of a lane group's fragments inside the B stage
 constexpr int STAGE_BYTES = A_STAGE_BYTES + B_STAGE_BYTES;
 constexpr int STAGES = CACHE_READ >= 2 ? 2 : 1;
@@ -618,6 +623,8 @@ typedef short tr4_t __attribute__((ext_vector_type(4)));
 typedef int tr2_t __attribute__((ext_vector_type(2)));
 
 #if B_ROWMAJOR
+// chunk-index XOR of k-row `k` in the register-staged row-major stage (none with padded rows)
+__device__ __forceinline__ int rm_swz(int k) { return LDS_PAD == 4 ? 0 : dl_swz_b(k); }
 static_assert((ES == 2 && (KP == 4 || KP == 8)) || (ES == 1 && (KP == 8 || KP == 16 || KP == 32)),
               "row-major B in LDS: fragments of whole transposing loads (4 k of 2-byte, 8 k of 1-byte elements)");
 static_assert(VEC_B == CE, "row-major B in LDS moves 16-byte vectors");
@@ -658,7 +665,7 @@ __device__ __forceinline__ void rowmajor_store(const rowmajor_stage &st, char *_
         const int idx = it * NTHREADS + tid;
         if (S::TOTAL % NTHREADS == 0 || idx < S::TOTAL) {
             const int k = idx / CB, c = idx % CB;
-            *reinterpret_cast<vec_t<in_t, CE> *>(lds + k * BROW_BYTES + ((c ^ dl_swz_b(k)) * 16)) = st.r[it];
+            *reinterpret_cast<vec_t<in_t, CE> *>(lds + k * RM_ROW + ((c ^ rm_swz(k)) * 16)) = st.r[it];
         }
     }
 }
@@ -677,14 +684,14 @@ __device__ __forceinline__ frag_t rowmajor_frag(const char *__restrict__ b, int 
 #pragma unroll
     for (int h = 0; h < KP / 4; ++h) {
         const int krow = step * MI_K + lgrp * KP + h * 4 + li / 4;
-        const char *src = b + krow * BROW_BYTES + (((pn << 1) ^ dl_swz_b(krow)) * 16) + (li % 4) * 8;
+        const char *src = b + krow * RM_ROW + (((pn << 1) ^ rm_swz(krow)) * 16) + (li % 4) * 8;
         *reinterpret_cast<tr4_t *>(&f.v[4 * h]) = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) tr4_t *)(src));
     }
 #else
 #pragma unroll
     for (int h = 0; h < KP / 8; ++h) {
         const int krow = step * MI_K + lgrp * KP + h * 8 + li / 2;
-        const char *src = b + krow * BROW_BYTES + ((pn ^ dl_swz_b(krow)) * 16) + (li % 2) * 8;
+        const char *src = b + krow * RM_ROW + ((pn ^ rm_swz(krow)) * 16) + (li % 2) * 8;
         *reinterpret_cast<tr2_t *>(&f.v[8 * h]) = __builtin_amdgcn_ds_read_tr8_b64_v2i32((__attribute__((address_space(3))) tr2_t *)(src));
     }
 #endif

@@ -611,7 +611,7 @@ extern "C" int32_t ms_space_describe(const ms_op *op, uint32_t flags, ms_space *
             // 3 (B row-major in LDS, read with the transposing loads): GEMMs whose B is contiguous along j, 1- and 2-byte inputs
             const bool b_rows = !is_conv2d(d.kind) && d.b_strides[2] == 1 && d.b_strides[1] != 1 &&
                                 (d.in_dtype == MS_F16 || d.in_dtype == MS_BF16 || d.in_dtype == MS_I8 || d.in_dtype == MS_F8E4M3);
-            if (b_rows) add_cat(out, MS_SLOT_STORAGE_ALIGN, "storage_align", {0, 1, 2, 3});
+            if (b_rows) add_cat(out, MS_SLOT_STORAGE_ALIGN, "storage_align", {0, 1, 2, 3, 4});
             else add_cat(out, MS_SLOT_STORAGE_ALIGN, "storage_align", {0, 1, 2});
         }
         if (flags & MS_SPACE_REORDER) {
@@ -1090,8 +1090,9 @@ extern "C" int32_t ms_trace_to_text(const ms_op *op, const ms_space *space, cons
             else
                 appendf(s, "cache-read(buffers=[A, B], scope=lds, compute-at=k0, stages=%d, prefetch_distance=%d)\n", p.cache_read >= 2 ? 2 : 1, p.cache_read == 3 ? 2 : (p.cache_read >= 2 ? 1 : 0));
             if (p.cache_read == 4) appendf(s, "annotate(block=C, key=wave_groups, value=ping_pong)\n");
-            appendf(s, "storage-align(scope=lds, pad_bytes=%d, swizzle=%d)\n", p.lds_pad ? 16 : 0, p.lds_pad >= 2);
+            appendf(s, "storage-align(scope=lds, pad_bytes=%d, swizzle=%d)\n", p.lds_pad ? 16 : 0, p.lds_pad == 2 || p.lds_pad == 3);
             if (p.lds_pad == 3) appendf(s, "transform-layout(buffer=B.lds, row-major k-rows, fragments through transposing LDS loads)\n");
+            if (p.lds_pad == 4) appendf(s, "transform-layout(buffer=B.lds, row-major k-rows padded by 32 bytes, fragments through transposing LDS loads)\n");
         }
         if (p.cache_write) appendf(s, "cache-write(buffer=C, scope=lds%s)\n", p.cache_read >= 8 ? ", per wavefront" : "");
         if (p.rfactor > 1) appendf(s, "rfactor(loop=k0, factor=%d)  # partial sums in the workspace, second kernel adds them in order\n", p.rfactor);

@@ -218,15 +218,16 @@ extern "C" int32_t ms_trace_validate(const ms_op *op, const ms_space *space, con
             const int split = kp * es > 16 ? kp * es / 16 : 1;
             int64_t rowsA = split * (bm * (kp / split) * es + padb), rowsB = split * (bn * (kp / split) * es + padb);
             lds = (int64_t)(p.cache_read >= 2 ? 2 : 1) * (bk / kp) * (rowsA + rowsB);
-            if (p.lds_pad == 3) {
+            if (p.lds_pad == 3 || p.lds_pad == 4) {
                 // B row-major in LDS (dense k-rows of bn elements, granules swizzled), fragments through the transposing loads
-                if (is_conv2d(d.kind) || !(d.b_strides[2] == 1 && d.b_strides[1] != 1)) return reject("storage_align 3 (row-major B in LDS) is for GEMMs whose B is contiguous along j");
+                if (is_conv2d(d.kind) || !(d.b_strides[2] == 1 && d.b_strides[1] != 1)) return reject("storage_align 3, 4 (row-major B in LDS) is for GEMMs whose B is contiguous along j");
                 if (!((es == 2 && (kp == 4 || kp == 8)) || (es == 1 && (kp == 8 || kp == 16 || kp == 32))))
-                    return reject("storage_align 3 needs fragments of whole transposing loads: 4 or 8 k per lane of 2-byte, 8, 16 or 32 k per lane of 1-byte inputs");
-                if (p.cache_read < 1 || p.cache_read > 4) return reject("storage_align 3 applies to register staging (cache_read 1..4)");
-                if (p.vec_b * es != 16) return reject("storage_align 3 moves B in 16-byte vectors: vectorize_b must be %d", 16 / es);
-                if (d.b_strides[1] % (16 / es) || d.b_strides[0] % (16 / es)) return reject("storage_align 3 needs 16-byte aligned rows of B");
-                lds = (int64_t)(p.cache_read >= 2 ? 2 : 1) * ((bk / kp) * rowsA + bk * bn * es);
+                    return reject("storage_align 3, 4 needs fragments of whole transposing loads: 4 or 8 k per lane of 2-byte, 8, 16 or 32 k per lane of 1-byte inputs");
+                if (p.cache_read < 1 || p.cache_read > 4) return reject("storage_align 3, 4 applies to register staging (cache_read 1..4)");
+                if (p.vec_b * es != 16) return reject("storage_align 3, 4 moves B in 16-byte vectors: vectorize_b must be %d", 16 / es);
+                if (d.b_strides[1] % (16 / es) || d.b_strides[0] % (16 / es)) return reject("storage_align 3, 4 needs 16-byte aligned rows of B");
+                // 4: rows of B padded by 32 bytes instead of swizzled
+                lds = (int64_t)(p.cache_read >= 2 ? 2 : 1) * ((bk / kp) * rowsA + bk * (bn * es + (p.lds_pad == 4 ? 32 : 0)));
             }
             if (p.cache_read >= 5) {
                 // direct-to-LDS ring: dense tiles, no padding (the swizzle replaces it)

@@ -451,8 +451,9 @@ def test_ping_pong_on_the_ring_c2_shape():
             compare.assert_float_close(got[r], refs[r % 4], compare.RTOL_HALF, "C2 ping-pong trace %d instance %d" % (n, r))
 
 
-def test_row_major_b_in_lds_exact():
-    """storage_align 3: the j-contiguous B goes global memory -> registers -> LDS in 16-byte vectors without a register
+@pytest.mark.parametrize("layout", [3, 4])
+def test_row_major_b_in_lds_exact(layout):
+    """storage_align 3 (XOR-swizzled granules) and 4 (rows padded by 32 bytes, no swizzle anywhere): the j-contiguous B goes global memory -> registers -> LDS in 16-byte vectors without a register
     transposition and the fragments come out of the transposing LDS loads.  int8 (both 16-k-per-lane intrinsics) and
     integer-valued fp16 / bf16 (both 8-k-per-lane intrinsics) with fp32 output must equal the oracle bit for bit; every
     register-staging mode (single stage, double buffer, prefetch distance 2, software-pipelined k loop, ping-pong wave
@@ -466,7 +467,7 @@ def test_row_major_b_in_lds_exact():
     space = op.space()
 
     def mk(sp, mfma, i, j, k, vecs, unroll=0, cache=1, reorder=0, cw=0):
-        return B.make_trace(sp, [[mfma], i, j, k, [unroll], [cache], [vecs[0]], [vecs[1]], [3], [reorder], [cw]])
+        return B.make_trace(sp, [[mfma], i, j, k, [unroll], [cache], [vecs[0]], [vecs[1]], [layout], [reorder], [cw]])
 
     traces = [mk(space, 161664, [12, 1, 1, 1], [10, 1, 1, 1], [6, 1, 1, 1], (16, 16)),                      # one wave, 16 columns
               mk(space, 161664, [3, 2, 2, 1], [5, 1, 2, 1], [3, 1, 2, 1], (16, 16), unroll=64, cache=2, cw=1),  # pipelined, BN = 32
@@ -477,7 +478,7 @@ def test_row_major_b_in_lds_exact():
     ran = 0
     for n, t in enumerate(traces):
         p = B.trace_validate(op, space, t)
-        assert p.lds_pad == 3
+        assert p.lds_pad == layout
         print("int8 trace", n, t.decisions(), flush=True)
         ran += 1
         got = run_variant_distinct(op, space, t, ins, "i32", (M, N))
@@ -529,7 +530,9 @@ def test_row_major_b_in_lds_c4c_and_c2_shapes():
     space = op.space()
     for n, vals in enumerate([[[161664], [4, 8, 1, 1], [4, 2, 4, 1], [4, 1, 2, 1], [0], [1], [16], [16], [3], [2], [0]],
                               [[323232], [4, 2, 2, 1], [4, 1, 2, 2], [4, 1, 4, 1], [0], [1], [16], [16], [3], [2], [0]],
-                              [[161664], [2, 4, 4, 1], [4, 8, 1, 1], [4, 1, 2, 1], [64], [2], [16], [16], [3], [2], [1]]]):
+                              [[161664], [2, 4, 4, 1], [4, 8, 1, 1], [4, 1, 2, 1], [64], [2], [16], [16], [3], [2], [1]],
+                              [[161664], [4, 8, 1, 1], [4, 2, 4, 1], [4, 1, 2, 1], [0], [1], [16], [16], [4], [2], [0]],
+                              [[323232], [4, 2, 2, 1], [4, 1, 2, 2], [4, 1, 4, 1], [64], [2], [16], [16], [4], [2], [1]]]):
         t = B.make_trace(space, vals)
         B.trace_validate(op, space, t)
         print("C4c trace", n, t.decisions(), flush=True)
@@ -543,7 +546,9 @@ def test_row_major_b_in_lds_c4c_and_c2_shapes():
     space = op.space()
     for n, vals in enumerate([[[323216], [4, 2, 2, 2], [4, 2, 2, 2], [16, 1, 4, 1], [64], [2], [8], [8], [3], [2], [0]],
                               [[323216], [4, 1, 4, 2], [4, 2, 2, 2], [16, 1, 1, 4], [0], [4], [8], [8], [3], [2], [1]],
-                              [[161632], [8, 2, 2, 2], [8, 1, 2, 4], [32, 1, 1, 1], [0], [3], [8], [8], [3], [0], [0]]]):
+                              [[161632], [8, 2, 2, 2], [8, 1, 2, 4], [32, 1, 1, 1], [0], [3], [8], [8], [3], [0], [0]],
+                              [[323216], [4, 4, 2, 1], [4, 4, 2, 1], [16, 1, 2, 2], [0], [1], [8], [8], [4], [2], [1]],   # 128 x 128 wave tiles
+                              [[323216], [4, 2, 2, 2], [4, 2, 2, 2], [16, 1, 4, 1], [64], [2], [8], [8], [4], [2], [0]]]):
         t = B.make_trace(space, vals)
         B.trace_validate(op, space, t)
         print("C2 trace", n, t.decisions(), flush=True)
@@ -553,12 +558,13 @@ def test_row_major_b_in_lds_c4c_and_c2_shapes():
         compare.assert_float_close(got, ref, compare.RTOL_HALF, "row-major B, C2 trace %d" % n)
 
 
-def test_row_major_b_in_lds_every_fragment_size():
-    """storage_align 3 with the other fragment sizes: 4 k per lane of 2-byte inputs (one transposing load), 8 k per
+@pytest.mark.parametrize("layout", [3, 4])
+def test_row_major_b_in_lds_every_fragment_size(layout):
+    """storage_align 3 and 4 with the other fragment sizes: 4 k per lane of 2-byte inputs (one transposing load), 8 k per
     lane of 1-byte inputs (one load: the shallow int8 and 8-bit float intrinsics) and 32 k per lane (four loads: the
     128-deep and 64-deep 8-bit float intrinsics).  Integer-valued inputs, fp32 / int32 outputs: bit-equal to the oracle."""
     def mk(sp, mfma, i, j, k, vec_b, unroll=0, cache=1, reorder=0, cw=0, vec=0):
-        return B.make_trace(sp, [[mfma], i, j, k, [unroll], [cache], [vec or vec_b], [vec_b], [3], [reorder], [cw]])
+        return B.make_trace(sp, [[mfma], i, j, k, [unroll], [cache], [vec or vec_b], [vec_b], [layout], [reorder], [cw]])
 
     M, N, K = 192, 160, 256
     cases = [("f16", "f32", 8, [(161616, [12, 1, 1, 1], [5, 2, 1, 1], [8, 1, 2, 1], 1), (323208, [3, 1, 2, 1], [5, 1, 1, 1], [8, 2, 1, 2], 2),
@@ -576,7 +582,7 @@ def test_row_major_b_in_lds_every_fragment_size():
         for n, (mfma, i, j, k, cache) in enumerate(traces):
             t = mk(sp, mfma, i, j, k, vb, cache=cache, reorder=2 * (n % 2), cw=n % 2)
             p = B.trace_validate(op, sp, t)
-            assert p.lds_pad == 3 and p.mfma == mfma
+            assert p.lds_pad == layout and p.mfma == mfma
             print(dtype, "trace", n, t.decisions(), flush=True)
             got = run_variant(op, sp, t, [A, Bm], odt, (M, N), instances=2)
             if got is None:

@@ -739,12 +739,12 @@ def test_row_major_b_layout_is_offered_and_validated():
                 return [sp.slots[i].candidates[c] for c in range(sp.slots[i].n_candidates)]
         return None
 
-    assert align_candidates(B.gemm_op(512, 512, 512, "i8")) == [0, 1, 2, 3]
-    assert align_candidates(B.gemm_op(1024, 1024, 1024, "f16")) == [0, 1, 2, 3]
-    assert align_candidates(B.bmm_op(4, 64, 64, 64, False, "f16")) == [0, 1, 2, 3]
+    assert align_candidates(B.gemm_op(512, 512, 512, "i8")) == [0, 1, 2, 3, 4]
+    assert align_candidates(B.gemm_op(1024, 1024, 1024, "f16")) == [0, 1, 2, 3, 4]
+    assert align_candidates(B.bmm_op(4, 64, 64, 64, False, "f16")) == [0, 1, 2, 3, 4]
     assert align_candidates(B.bmm_op(4, 64, 64, 64, True, "f16")) == [0, 1, 2]           # B contiguous along k
     assert align_candidates(B.conv2d_op(1, 56, 56, 64, 64, 3, 3, stride=1, pad=1)) == [0, 1, 2]
-    assert align_candidates(B.gemm_op(256, 256, 256, "f8", "f16")) == [0, 1, 2, 3]
+    assert align_candidates(B.gemm_op(256, 256, 256, "f8", "f16")) == [0, 1, 2, 3, 4]
     assert align_candidates(B.gemm_op(128, 128, 128, "f32")) == [0, 1]                   # vector-ALU space
     op = B.gemm_op(512, 512, 512, "i8")
     sp = op.space()
@@ -757,6 +757,11 @@ def test_row_major_b_layout_is_offered_and_validated():
     # A: 8 planes of 128 fragments of 16 bytes + 16 bytes of padding each; B: 128 k-rows of 128 bytes, dense
     assert p.lds_bytes == 8 * (128 * 16 + 16) + 128 * 128
     assert "transform-layout(buffer=B.lds" in B.trace_to_text(op, sp, mk())
+    # 4: no swizzle, every k-row of B padded by 32 bytes
+    t4 = B.make_trace(sp, [[161664], [4, 8, 1, 1], [4, 2, 4, 1], [4, 1, 2, 1], [0], [1], [16], [16], [4], [2], [0]])
+    p4 = B.trace_validate(op, sp, t4)
+    assert p4.lds_pad == 4 and p4.lds_bytes == 8 * (128 * 16 + 16) + 128 * (128 + 32) and p4.key != p.key
+    assert "padded by 32 bytes" in B.trace_to_text(op, sp, t4)
     assert B.trace_validate(op, sp, mk(cache=2)).lds_bytes == 2 * p.lds_bytes
     assert B.trace_validate(op, sp, mk(mfma=161632, k=(4, 1, 2, 2))).lds_bytes == 16 * (128 * 8 + 16) + 128 * 128   # 8-byte fragments
     for bad, why in ((mk(vec_b=4), "vectorize_b"), (mk(cache=5), "")):
