@@ -257,6 +257,21 @@ __device__ __forceinline__ accv_t mfma(const frag_t &a, const frag_t &b, accv_t 
 #endif
 }
 
+// One-wavefront-per-SIMD tiles (256 accumulators per lane) load their operands through buffer instructions: the
+// address of a load is a resource descriptor and a byte offset in scalar registers plus one 32-bit per-lane offset
+// shared by all loads of the operand, where flat 64-bit addresses take two vector registers per load once the k loop
+// is unrolled.  The descriptor covers 2 GiB from the operand's base and checks nothing: the offsets are those of the
+// pointer form.
+#define BUFFER_LOADS (!IS_CONV && CACHE_READ <= 4 && (I1) * (I3) * (J1) * (J3) * (MI_M == 16 ? 4 : 16) >= 256)
+#if BUFFER_LOADS
+typedef int bl4_t __attribute__((ext_vector_type(4)));
+__device__ __forceinline__ bl4_t buffer_load16(const void *base, unsigned voff, long uniform_bytes)
+{
+    const __amdgpu_buffer_rsrc_t rs = __builtin_amdgcn_make_buffer_rsrc(const_cast<void *>(base), 0, 0x7FFFFFF0, 0x00020000);
+    return __builtin_amdgcn_raw_buffer_load_b128(rs, (int)voff, __builtin_amdgcn_readfirstlane((int)uniform_bytes), 0);
+}
+#endif
+
 // ---- global -> registers -> LDS staging of one operand tile
 //
 // K-contiguous operand (A; B of the NT form; conv activations): a thread
@@ -343,8 +358,15 @@ __device__ __forceinline__ void kmajor_load(kmajor_stage<ROWS, V> &st, const in_
 #endif
             if (NTHREADS % KV == 0) {
                 // address = uniform base (scalar registers) + one 32-bit per-lane offset shared by all iterations
-                const char *ub = (const char *)(src + (row0 + it * (NTHREADS / KV)) * row_stride + k0e);
                 const unsigned voff = (unsigned)(((tid / KV) * row_stride + (tid % KV) * V) * ES);
+#if BUFFER_LOADS
+                if constexpr (V * ES == 16) {
+                    const bl4_t x = buffer_load16(src, voff, ((row0 + it * (NTHREADS / KV)) * row_stride + k0e) * ES);
+                    st.r[it] = *reinterpret_cast<const vec_t<in_t, V> *>(&x);
+                    continue;
+                }
+#endif
+                const char *ub = (const char *)(src + (row0 + it * (NTHREADS / KV)) * row_stride + k0e);
                 st.r[it] = *reinterpret_cast<const vec_t<in_t, V> *>(ub + voff);
             } else {
                 st.r[it] = *reinterpret_cast<const vec_t<in_t, V> *>(src + (row0 + row) * row_stride + k0e + kv * V);
@@ -646,8 +668,15 @@ __device__ __forceinline__ void rowmajor_load(rowmajor_stage &st, const in_t *__
         if (S::TOTAL % NTHREADS == 0 || idx < S::TOTAL) {
             if (NTHREADS % CB == 0) {
                 // wave-uniform base + 32-bit per-lane offset
-                const char *ub = (const char *)(src + (k0e + it * (NTHREADS / CB)) * k_stride + col0);
                 const unsigned voff = (unsigned)(((tid / CB) * k_stride + (tid % CB) * CE) * ES);
+#if BUFFER_LOADS
+                {
+                    const bl4_t x = buffer_load16(src, voff, ((k0e + it * (NTHREADS / CB)) * k_stride + col0) * ES);
+                    st.r[it] = *reinterpret_cast<const vec_t<in_t, CE> *>(&x);
+                    continue;
+                }
+#endif
+                const char *ub = (const char *)(src + (k0e + it * (NTHREADS / CB)) * k_stride + col0);
                 st.r[it] = *reinterpret_cast<const vec_t<in_t, CE> *>(ub + voff);
             } else {
                 st.r[it] = *reinterpret_cast<const vec_t<in_t, CE> *>(src + (k0e + idx / CB) * k_stride + col0 + (idx % CB) * CE);
