@@ -588,3 +588,47 @@ def test_row_major_b_in_lds_every_fragment_size(layout):
             if got is None:
                 continue
             assert np.array_equal(got[0], ref) and np.array_equal(got[1], ref), "row-major B, %s trace %d" % (dtype, n)
+
+
+def test_one_wavefront_per_simd_tiles_exact():
+    """Workgroups of 4 wavefronts with 128 x 128 wave tiles (256 accumulators per lane, one wavefront per SIMD): these
+    kernels fetch their operands through buffer loads (descriptor and tile offset in scalar registers, one lane offset
+    per operand).  Integer-valued fp16 with fp32 output and int8: bit-equal to the oracle in every register-staged mode,
+    rolled and software-pipelined k loops, all B layouts, two tiles per instance in each direction, 2 instances (the
+    staged epilogue of such tiles is covered at the config-2 shape, where the fp16 output fits LDS)."""
+    M, N, K = 512, 512, 192
+    A, Bm = I.gemm_inputs(M, N, K, "f16", 11, "ints")
+    ref = O.gemm(A, Bm)
+    op = B.gemm_op(M, N, K, "f16", "f32")
+    sp = op.space()
+
+    def mk(space, mfma, k, unroll, cache, vec_b, layout, reorder=2, cw=0, ij=([2, 4, 2, 1], [2, 4, 2, 1]), vec=8):
+        return B.make_trace(space, [[mfma], ij[0], ij[1], k, [unroll], [cache], [vec], [vec_b], [layout], [reorder], [cw]])
+
+    traces = [mk(sp, 323216, [6, 1, 2, 1], 0, 3, 8, 4), mk(sp, 323216, [3, 1, 4, 1], 64, 2, 8, 4),
+              mk(sp, 323216, [3, 1, 2, 2], 0, 1, 8, 3, reorder=0), mk(sp, 323216, [3, 1, 4, 1], 0, 2, 4, 2),
+              mk(sp, 323216, [6, 1, 2, 1], 64, 2, 2, 1, reorder=1, ij=([2, 1, 2, 4], [2, 1, 2, 4])),
+              mk(sp, 161632, [6, 1, 1, 1], 0, 1, 8, 4, ij=([2, 8, 2, 1], [2, 8, 2, 1]))]
+    for n, t in enumerate(traces):
+        p = B.trace_validate(op, sp, t)
+        assert p.waves == 4 and p.acc_per_thread == 256
+        print("f16 trace", n, t.decisions(), flush=True)
+        got = run_variant(op, sp, t, [A, Bm], "f32", (M, N), instances=2)
+        if got is None:
+            continue
+        assert np.array_equal(got[0], ref) and np.array_equal(got[1], ref), "128 x 128 wave tiles, f16 trace %d" % n
+    g = I.rng(53)
+    A8, B8 = I.int8_uniform(g, (M, 256)), I.int8_uniform(g, (256, N))
+    ref8 = O.gemm(A8, B8)
+    op8 = B.gemm_op(M, N, 256, "i8")
+    sp8 = op8.space()
+    for n, t in enumerate([mk(sp8, 323232, [4, 1, 2, 1], 0, 2, 16, 4, vec=16), mk(sp8, 323232, [2, 1, 4, 1], 64, 2, 16, 3, vec=16),
+                           mk(sp8, 323232, [4, 1, 1, 2], 0, 1, 4, 2, vec=16)]):
+        p = B.trace_validate(op8, sp8, t)
+        assert p.waves == 4 and p.acc_per_thread == 256
+        print("int8 trace", n, t.decisions(), flush=True)
+        got = run_variant(op8, sp8, t, [A8, B8], "i32", (M, N), instances=2)
+        if got is None:
+            continue
+        compare.assert_int_equal(got[0], ref8, "128 x 128 wave tiles, int8 trace %d" % n)
+        compare.assert_int_equal(got[1], ref8, "128 x 128 wave tiles, int8 trace %d, instance 1" % n)
