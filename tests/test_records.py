@@ -39,3 +39,25 @@ def test_best_records_compile_without_spills_and_with_the_lds_the_validator_coun
     assert r.lds_bytes == p.lds_bytes
     waves_per_simd = (p.waves + 3) // 4
     assert 0 < r.vgprs + r.agprs <= 512 // waves_per_simd
+
+
+def test_stored_trial_logs_give_pretraining_rows():
+    """The trial logs kept next to the records (plain 256-trial searches, seeds 1-3, of the eight configurations) are the
+    cost model's pre-training data: every logged trial still validates in today's space of its workload, its feature
+    vector has the width the search expects, and leaving out the log of the seed being run leaves the other two."""
+    import numpy as np
+    from paper_2205_13603_amd.workloads import WORKLOADS
+    names = [n for n in WORKLOADS if n.startswith("c")]
+    assert len(names) == 8
+    for name in names:
+        logs = tuned.pretraining_logs(name, "filling")
+        assert len(logs) == 3, (name, logs)
+        assert len(tuned.pretraining_logs(name, "filling", exclude_seed=2)) == 2
+        op = WORKLOADS[name][0]()
+        sp = op.space(0xFF)
+        X, y = tuned.pretraining_rows(op, sp, logs)
+        assert X.shape[0] == y.shape[0] >= 700, (name, X.shape)       # 3 x 256 trials, all still valid
+        p = B.trace_validate(op, sp, B.trace_sample_valid(op, sp, 1, 0))
+        assert X.shape[1] == len(B.variant_features(op, p))
+        assert np.all(np.isfinite(X)) and np.all(np.isfinite(y)) and y.min() > 0   # log2 of microseconds above 1
+    assert tuned.pretraining_logs("x3_softmax_f32_256x256", "filling") == []
