@@ -24,7 +24,7 @@ def oracle_run(name, ins):
         return O.conv2d_nhwc(ins[0], ins[1], bias=ins[2], relu=True, stride=2, pad=1, groups=4)
     if name == "x8_gemm_nt_f16_1024":
         return O.bmm(ins[0], ins[1], trans_b=True)
-    if name == "x10_c3d_f16_16x224x224x3":
+    if name in ("x10_c3d_f16_16x224x224x3", "x10b_c3d_f16_16x224x224x4"):
         return O.conv3d_ndhwc(ins[0], ins[1], bias=ins[2], relu=True, stride=2, pad=3)
     if name == "x9_c1d_f16_256x64":
         return O.conv1d_nwc(ins[0], ins[1], bias=ins[2], relu=True, stride=2, pad=1)

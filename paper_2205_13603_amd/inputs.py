@@ -191,3 +191,15 @@ def c3d(seed=0, dtype="f16"):
     X ~ U[0, 1], W ~ N(0, 0.02), bias ~ N(0, 0.05) fp32."""
     g = rng(seed)
     return (uniform(g, (1, 16, 224, 224, 3), 0.0, 1.0, dtype), normal(g, (7, 7, 7, 3, 64), 0.02, dtype), normal(g, (64,), 0.05, "f32"))
+
+
+def c3d4(seed=0, dtype="f16"):
+    """The same 3-D convolution with the input stored with 4 channels per voxel (the fourth is zero, and so are its
+    weights): one 8-byte load per voxel and tap instead of three 2-byte loads."""
+    import numpy as np
+    X, W, b = c3d(seed, dtype)
+    X4 = np.zeros(X.shape[:4] + (4,), X.dtype)
+    X4[..., :3] = X
+    W4 = np.zeros(W.shape[:3] + (4,) + W.shape[4:], W.dtype)
+    W4[:, :, :, :3, :] = W
+    return (X4, W4, b)

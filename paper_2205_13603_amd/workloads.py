@@ -21,6 +21,7 @@ WORKLOADS = {
     "x8_gemm_nt_f16_1024": (lambda: B.bmm_op(1, 1024, 1024, 1024, True, "f16"), 64),
     "x9_c1d_f16_256x64": (lambda: B.conv1d_op(1, 256, 64, 128, 3, stride=2, pad=1), 4096),
     "x10_c3d_f16_16x224x224x3": (lambda: B.conv3d_op(1, 16, 224, 224, 3, 64, 7, stride=2, pad=3), 8),
+    "x10b_c3d_f16_16x224x224x4": (lambda: B.conv3d_op(1, 16, 224, 224, 4, 64, 7, stride=2, pad=3), 8),
     "x11_gemm_bf16_1024": (lambda: B.gemm_op(1024, 1024, 1024, "bf16"), 64),
     "x12_conv_bf16_56x56x64": (lambda: B.conv2d_op(1, 56, 56, 64, 64, 3, 3, stride=1, pad=1, in_dtype="bf16"), 512),
     "x3_softmax_f32_256x256": (lambda: B.softmax_op(1, 256, 256), 2048),
@@ -45,6 +46,7 @@ def workload_inputs(name, seed):
         "x6_t2d_f16_4x4x512": lambda: list(I.t2d(seed)),
         "x9_c1d_f16_256x64": lambda: list(I.c1d(seed)),
         "x10_c3d_f16_16x224x224x3": lambda: list(I.c3d(seed)),
+        "x10b_c3d_f16_16x224x224x4": lambda: list(I.c3d4(seed)),
         "x7_grp_f16_56x56x64_g4": lambda: list(I.grp(seed)),
         "x5_cbr_f16_224x224x3": lambda: list(I.cbr(seed)),
         "x5b_cbr_f16_224x224x4": lambda: list(I.cbr4(seed)),
@@ -64,7 +66,7 @@ OUT_SHAPE = {
     "x3_softmax_f32_256x256": ((1, 256, 256), "f32"), "x4_norm_f32_256x256": ((1,), "f32"),
     "x5_cbr_f16_224x224x3": ((1, 112, 112, 64), "f16"), "x5b_cbr_f16_224x224x4": ((1, 112, 112, 64), "f16"),
     "x8_gemm_nt_f16_1024": ((1, 1024, 1024), "f16"), "x9_c1d_f16_256x64": ((1, 128, 128), "f16"),
-    "x10_c3d_f16_16x224x224x3": ((1, 8, 112, 112, 64), "f16"),
+    "x10_c3d_f16_16x224x224x3": ((1, 8, 112, 112, 64), "f16"), "x10b_c3d_f16_16x224x224x4": ((1, 8, 112, 112, 64), "f16"),
     "x11_gemm_bf16_1024": ((1024, 1024), "bf16"), "x12_conv_bf16_56x56x64": ((1, 56, 56, 64), "bf16"),
     "x6_t2d_f16_4x4x512": ((1, 8, 8, 256), "f16"), "x7_grp_f16_56x56x64_g4": ((1, 28, 28, 128), "f16"),
 }
@@ -79,6 +81,7 @@ BOUND = {  # which roofline bounds the workload (AI vs ridge), and the in-dtype
     "x8_gemm_nt_f16_1024": ("mfma", "f16"),  # config 2 with B stored [N][K] (both operands contiguous along k)
     "x9_c1d_f16_256x64": ("hbm", "f16"),  # 55 flop per byte
     "x10_c3d_f16_16x224x224x3": ("mfma", "f16"),  # 743 flop per byte
+    "x10b_c3d_f16_16x224x224x4": ("mfma", "f16"),
     "x11_gemm_bf16_1024": ("mfma", "bf16"), "x12_conv_bf16_56x56x64": ("mfma", "bf16"),  # configs 2 and 3 in bfloat16
     "x6_t2d_f16_4x4x512": ("hbm", "f16"),  # 16 flop per byte: the 4 MiB of weights are read once per instance
 }
