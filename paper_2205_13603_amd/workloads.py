@@ -92,7 +92,8 @@ PROFILE_NAME = {"c1_gemm_f32_128": "gemm_alu_c1_gemm_f32_128", "c2_gemm_f16_1024
                 "c5b_dw_f32_56x56x144": "dwconv_c5b_dw_f32_56x56x144", "c4a_bmm_nt_f16": "gemm_mfma_c4a_bmm_nt_f16", "c4b_bmm_nn_f16": "gemm_mfma_c4b_bmm_nn_f16",
                 "c4c_gemm_i8_512": "gemm_mfma_c4c_gemm_i8_512", "x2_gemm_f8_1024": "gemm_mfma_x2_gemm_f8_1024",
                 "x3_softmax_f32_256x256": "reduce_x3_softmax_f32_256x256", "x4_norm_f32_256x256": "reduce_x4_norm_f32_256x256",
-                "x5_cbr_f16_224x224x3": "gemm_mfma_x5_cbr_f16_224x224x3", "x6_t2d_f16_4x4x512": "gemm_mfma_x6_t2d_f16_4x4x512",
+                "x5_cbr_f16_224x224x3": "gemm_mfma_x5_cbr_f16_224x224x3", "x5b_cbr_f16_224x224x4": "gemm_mfma_x5b_cbr_f16_224x224x4",
+                "x10_c3d_f16_16x224x224x3": "gemm_mfma_x10_c3d_f16_16x224x224x3", "x10b_c3d_f16_16x224x224x4": "gemm_mfma_x10b_c3d_f16_16x224x224x4", "x6_t2d_f16_4x4x512": "gemm_mfma_x6_t2d_f16_4x4x512",
                 "x7_grp_f16_56x56x64_g4": "gemm_mfma_x7_grp_f16_56x56x64_g4", "x8_gemm_nt_f16_1024": "gemm_mfma_x8_gemm_nt_f16_1024",
                 "x9_c1d_f16_256x64": "gemm_mfma_x9_c1d_f16_256x64", "x11_gemm_bf16_1024": "gemm_mfma_x11_gemm_bf16_1024",
                 "x12_conv_bf16_56x56x64": "gemm_mfma_x12_conv_bf16_56x56x64"}
