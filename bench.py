@@ -291,12 +291,17 @@ def main():
 
     # HBM bytes per launch from the committed rocprofv3 counter summary, if it is of this very variant
     traffic, traffic_source = None, None
-    prof = os.path.join(ROOT, "profiles", "ms_kernel_%s.txt" % PROFILE_NAME.get(name, name))
-    if R == default_r and os.path.exists(prof):
+    # (one summary per profiled record of the workload: ms_kernel_<family>_<workload>.txt and ..._record<i>.txt)
+    import glob
+    stem = os.path.join(ROOT, "profiles", "ms_kernel_%s" % PROFILE_NAME.get(name, name))
+    for prof in [stem + ".txt"] + sorted(glob.glob(stem + "_record*.txt")):
+        if R != default_r or not os.path.exists(prof):
+            continue
         fields = dict(line.split(":", 1) for line in open(prof) if line.startswith(("traffic_bytes_per_launch:", "variant_key:")))
         if fields.get("variant_key", "").strip() == "%016x" % params.key and "traffic_bytes_per_launch" in fields:
             traffic = float(fields["traffic_bytes_per_launch"])
             traffic_source = "profiles/%s: rocprofv3 FETCH_SIZE + WRITE_SIZE of this very variant (matched by key), not measured in this run" % os.path.basename(prof)
+            break
 
     out = {
         "metric": METRIC, "value": value, "unit": unit,
